@@ -1,0 +1,229 @@
+"""Pins for the discrete part of the oracle: the LRU expert cache and the speculative-prefetch
+bookkeeping (Sec. 3.1-3.3).  The simulator is compared with a brute-force replay that keeps no
+slots and no stamps: after any access sequence an LRU cache of k entries holds the k distinct
+most recently accessed keys, found by scanning the history backwards."""
+import itertools
+
+import numpy as np
+
+from oracle import moe_oracle as O
+
+
+def most_recent_distinct(history, k):
+    seen = []
+    for e in reversed(history):
+        if e not in seen:
+            seen.append(e)
+            if len(seen) == k:
+                break
+    return seen  # most recent first
+
+
+class BruteCache:
+    """History-replay model of one layer; access order inside a step: resident experts first,
+    then absent ones, each in ascending id (the order the engine touches the cache in)."""
+
+    def __init__(self, k):
+        self.k, self.history = k, []
+
+    def step(self, needed):
+        before = most_recent_distinct(self.history, self.k)
+        needed = sorted(set(needed))
+        order = [e for e in needed if e in before] + [e for e in needed if e not in before]
+        out = []
+        for e in order:
+            cur = most_recent_distinct(self.history, self.k)
+            hit = e in cur
+            victim = -1
+            if not hit and len(cur) == self.k:
+                victim = cur[-1]          # least recently used of the k
+            out.append((e, hit, victim))
+            self.history.append(e)
+        return out
+
+    def contents(self):
+        return sorted(most_recent_distinct(self.history, self.k))
+
+
+def test_lru_exhaustive_single_access_traces():
+    for E in (2, 3, 4):
+        for k in (1, 2, 3):
+            for length in range(1, 7):
+                for trace in itertools.product(range(E), repeat=length):
+                    sim = O.ExpertCacheSim(1, E, k, b=0)
+                    brute = BruteCache(k)
+                    for e in trace:
+                        acc, _ = sim.step(0, [[e]])
+                        want = brute.step([e])
+                        assert [(a.expert, a.status == O.HIT, a.victim) for a in acc] == want
+                        assert sim.contents(0) == brute.contents()
+
+
+def test_lru_random_top2_and_batched_steps():
+    rng = np.random.default_rng(0)
+    for E, k, B in [(8, 2, 1), (8, 4, 1), (8, 3, 1), (8, 4, 4), (8, 4, 16), (6, 2, 3)]:
+        sim = O.ExpertCacheSim(1, E, k, b=0)
+        brute = BruteCache(k)
+        for _ in range(300):
+            sel = [list(rng.choice(E, size=2, replace=False)) for _ in range(B)]
+            acc, _ = sim.step(0, sel)
+            want = brute.step([e for t in sel for e in t])
+            assert [(a.expert, a.status == O.HIT, a.victim) for a in acc] == want
+            assert sim.contents(0) == brute.contents()
+            # slot bookkeeping is consistent: each access names the slot that now holds it (unless
+            # a later access of the same step reused that slot)
+            for a in acc:
+                assert 0 <= a.slot < k
+            for s, e in enumerate(sim.slot_expert[0]):
+                if e >= 0:
+                    assert [a.slot for a in acc if a.expert == e] in ([], [s])
+        st = sim.stats[0]
+        assert st.hits + st.misses == st.needed and st.prefetch_hits == 0
+
+
+def test_lru_empty_slots_fill_in_index_order_before_any_eviction():
+    sim = O.ExpertCacheSim(1, 8, 4, b=0)
+    acc, _ = sim.step(0, [[5, 2]])
+    assert [(a.expert, a.slot, a.victim) for a in acc] == [(2, 0, -1), (5, 1, -1)]
+    acc, _ = sim.step(0, [[7, 5]])
+    assert [(a.expert, a.status, a.slot, a.victim) for a in acc] == [(5, O.HIT, 1, -1), (7, O.MISS, 2, -1)]
+    acc, _ = sim.step(0, [[0, 1]])
+    assert [(a.expert, a.slot, a.victim) for a in acc] == [(0, 3, -1), (1, 0, 2)]
+    assert sim.stats[0].evictions == 1
+
+
+def test_lru_closed_form_k2_top2():
+    """k = K = 2, batch 1: after every step the cache holds exactly that step's two experts, so an
+    access hits iff the expert was selected at the previous token; hits = sum |S_t & S_{t-1}|."""
+    rng = np.random.default_rng(1)
+    E = 8
+    sim = O.ExpertCacheSim(1, E, 2, b=0)
+    prev, hits = set(), 0
+    for _ in range(2000):
+        S = set(int(e) for e in rng.choice(E, size=2, replace=False))
+        acc, _ = sim.step(0, [sorted(S)])
+        assert {a.expert for a in acc if a.status == O.HIT} == (S & prev)
+        assert set(sim.contents(0)) == S
+        hits += len(S & prev)
+        prev = S
+    st = sim.stats[0]
+    assert st.hits == hits and st.needed == 4000
+    # uniform i.i.d. routing: P(hit) = K/E = 0.25 (binomial std over 4000 draws ~ 0.007)
+    assert abs(st.recall - 0.25) < 0.03
+
+
+def test_cache_as_large_as_the_expert_set_only_misses_on_first_touch():
+    rng = np.random.default_rng(2)
+    sim = O.ExpertCacheSim(1, 8, 8, b=0)
+    seen = set()
+    for _ in range(200):
+        S = [int(e) for e in rng.choice(8, size=2, replace=False)]
+        acc, _ = sim.step(0, [S])
+        for a in acc:
+            assert (a.status == O.MISS) == (a.expert not in seen)
+            seen.add(a.expert)
+    assert sim.stats[0].misses == len(seen) == 8 and sim.stats[0].evictions == 0
+
+
+def test_warm_start_holds_experts_zero_to_k_minus_one():
+    sim = O.ExpertCacheSim(2, 8, 3, b=4, warm=True)
+    assert sim.contents(0) == [0, 1, 2] and sim.contents(1) == [0, 1, 2]
+    acc, _ = sim.step(0, [[1, 6]])
+    assert [(a.expert, a.status, a.victim) for a in acc] == [(1, O.HIT, -1), (6, O.MISS, 0)]
+
+
+# ------------------------------------------------------------------ speculative prefetch
+
+def test_prefetch_guess_equals_selection_when_gates_coincide():
+    rng = np.random.default_rng(3)
+    E, H = 8, 64
+    wg = rng.normal(size=(E, H)).astype(np.float32)
+    for _ in range(100):
+        h = rng.normal(size=H).astype(np.float16)
+        idx, _, _ = O.route(wg, h, 2)
+        assert O.prefetch_guess(O.prefetch_scores(wg, h), 2) == idx
+    # batch: the score is the summed softmax mass, so a single token reduces to its own gate
+    hb = rng.normal(size=(5, H)).astype(np.float16)
+    s = O.prefetch_scores(wg, hb)
+    assert np.allclose(s, sum(O.softmax(O.gate_logits(wg, hb[t])) for t in range(5)), atol=1e-14)
+    assert abs(s.sum() - 5.0) < 1e-12
+
+
+def test_prefetch_never_touches_the_cache_until_used():
+    sim = O.ExpertCacheSim(3, 8, 2, b=4)
+    sim.step(1, [[0, 1]])
+    before = (list(sim.slot_expert[1]), list(sim.slot_stamp[1]))
+    # guess {1 (resident: skipped), 5 (staged)} for layer 1 while running layer 0
+    acc, dec = sim.step(0, [[2, 3]], guess=[1, 5])
+    assert dec == [(1, False), (5, True)]
+    assert (list(sim.slot_expert[1]), list(sim.slot_stamp[1])) == before
+    assert sim.staged[1] == [5] and sim.stats[1].spec_issued == 1
+    # layer 1 now needs 5 (a prefetch hit, which evicts the LRU entry 0) and 1 (a plain hit)
+    acc, _ = sim.step(1, [[5, 1]])
+    assert [(a.expert, a.status, a.victim) for a in acc] == [(1, O.HIT, -1), (5, O.PREFETCH_HIT, 0)]
+    assert sim.staged[1] == [] and sim.stats[1].spec_wasted == 0 and sim.stats[1].prefetch_hits == 1
+
+
+def test_unused_guesses_are_dropped_and_counted():
+    sim = O.ExpertCacheSim(2, 8, 2, b=4)
+    sim.step(0, [[0, 1]], guess=[6, 7])
+    assert sim.staged[1] == [6, 7]
+    acc, _ = sim.step(1, [[6, 2]])
+    assert [(a.expert, a.status) for a in acc] == [(2, O.MISS), (6, O.PREFETCH_HIT)]
+    assert sim.stats[1].spec_wasted == 1 and sim.staged_total() == 0
+    # the last layer has no successor: its guess is ignored
+    _, dec = sim.step(1, [[6, 2]], guess=[3, 4])
+    assert dec == [] and sim.staged_total() == 0
+
+
+def test_staging_buffers_are_a_shared_bounded_pool():
+    sim = O.ExpertCacheSim(4, 8, 2, b=3)
+    _, d0 = sim.step(0, [[0, 1]], guess=[4, 5])
+    _, d2 = sim.step(2, [[0, 1]], guess=[6, 7])      # layer 1 has not run: its guesses still hold 2 buffers
+    assert d0 == [(4, True), (5, True)] and d2 == [(6, True), (7, False)]
+    assert sim.staged_total() == 3
+    _, d0 = sim.step(0, [[0, 1]], guess=[4, 2])      # 4 already staged; pool full for 2
+    assert d0 == [(4, False), (2, False)]
+
+
+def test_prefetch_changes_labels_but_not_cache_contents_or_evictions():
+    """Sec. 3.2: speculative loading does not change what the model computes; in cache terms the
+    contents, slots, victims and order after every step are identical with and without it."""
+    rng = np.random.default_rng(4)
+    L, E, k = 4, 8, 2
+    on = O.ExpertCacheSim(L, E, k, b=4)
+    off = O.ExpertCacheSim(L, E, k, b=4)
+    for _ in range(300):
+        for l in range(L):
+            sel = [[int(e) for e in rng.choice(E, size=2, replace=False)]]
+            guess = [int(e) for e in rng.choice(E, size=2, replace=False)]
+            a_on, _ = on.step(l, sel, guess)
+            a_off, _ = off.step(l, sel, None)
+            assert [(a.expert, a.slot, a.victim) for a in a_on] == [(a.expert, a.slot, a.victim) for a in a_off]
+            assert [(a.status == O.HIT) for a in a_on] == [(a.status == O.HIT) for a in a_off]
+            assert on.slot_expert[l] == off.slot_expert[l] and on.slot_stamp[l] == off.slot_stamp[l]
+    for l in range(L):
+        s_on, s_off = on.stats[l], off.stats[l]
+        assert s_on.hits == s_off.hits and s_on.evictions == s_off.evictions
+        assert s_on.misses + s_on.prefetch_hits == s_off.misses and s_off.prefetch_hits == 0
+        assert s_on.spec_issued == s_on.prefetch_hits + s_on.spec_wasted + len(on.staged[l])
+    assert sum(s.prefetch_hits for s in on.stats) > 0
+
+
+def test_zero_experts_make_the_speculative_guess_exact():
+    """If the experts output 0 the residual stream is unchanged, so the next layer's gate sees the
+    same x; with equal norm gains its true selection equals the guess: speculative recall 1."""
+    rng = np.random.default_rng(5)
+    E, H, F, g = 8, 64, 64, 16
+    zero_expert = [(np.zeros(s, np.uint8), np.ones((s[0], s[1] // g), np.float16), np.zeros((s[0], s[1] // g), np.float16))
+                   for s in ((F, H), (F, H), (H, F))]
+    gam = np.ones(H, np.float16)
+    wg0 = rng.normal(size=(E, H)).astype(np.float32)
+    wg1 = rng.normal(size=(E, H)).astype(np.float32)
+    for _ in range(50):
+        x = rng.normal(size=H).astype(np.float16)
+        r0 = O.moe_block(x, wg0, [zero_expert] * E, g, 2, gam, 1e-5)
+        assert (r0.x_out == x).all()
+        guess = O.prefetch_guess(O.prefetch_scores(wg1, r0.h), 2)
+        r1 = O.moe_block(r0.x_out, wg1, [zero_expert] * E, g, 2, gam, 1e-5)
+        assert guess == r1.idx
