@@ -1,0 +1,229 @@
+/*
+ * moe_offload.h -- C ABI of the MI355X (gfx950) MoE-offloading decode engine.
+ *
+ * The library implements the per-token decode step of a sparse Mixture-of-Experts
+ * block with expert offloading, after "Fast Inference of Mixture-of-Experts
+ * Language Models with Offloading" (arXiv 2312.17238):
+ *
+ *   - linear token-level gate and top-k expert selection            (Sec. 2.1)
+ *   - an LRU cache of k experts per layer in device memory          (Sec. 3.1)
+ *   - speculative loading: the next layer's gate applied to the
+ *     hidden state the current layer's gate saw                     (Sec. 3.2)
+ *   - one contiguous buffer per expert in pinned host memory, moved
+ *     by a single asynchronous host-to-device copy, and b shared
+ *     on-device staging buffers for speculative loads               (Sec. 3.3)
+ *   - expert weights stored group-wise quantized (2/3/4 bit codes,
+ *     a scale and a zero point per group), dequantized on the fly   (Sec. 4.2)
+ *
+ * Conventions
+ *   - Every function returns MOE_OK (0) or a negative moe_status; nothing throws or
+ *     aborts across this boundary.  moe_last_error() gives a thread-local message.
+ *   - "dev" pointers are device (HBM) memory, "host" pointers are host memory.
+ *     The library never frees caller memory; arenas passed to *_create must stay
+ *     alive until the matching *_destroy.
+ *   - Streams are hipStream_t handles passed as void*; the caller owns them.
+ *     Kernels run on the compute stream, expert copies on the copy stream; the
+ *     library orders the two with HIP events.  Both must have default priority.
+ *   - One host thread drives a context; calls are not re-entrant.
+ *   - fp16 values cross the boundary as IEEE binary16 bit patterns in uint16_t.
+ */
+#ifndef MOE_OFFLOAD_H
+#define MOE_OFFLOAD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MOE_MAX_EXPERTS 16   /* experts per layer                    */
+#define MOE_MAX_TOPK     4   /* active experts per token             */
+#define MOE_MAX_BATCH   64   /* tokens per decode step               */
+#define MOE_MAX_GUESS    4   /* speculatively loaded experts per step */
+
+typedef enum {
+    MOE_OK      =  0,
+    MOE_EINVAL  = -1,  /* bad argument (null pointer, unsupported shape or format, batch > max_batch) */
+    MOE_ESTATE  = -2,  /* call not valid in this state (e.g. step before every expert was loaded)    */
+    MOE_ENOMEM  = -3,  /* a caller-provided arena is too small, or a small internal allocation failed */
+    MOE_EHIP    = -4   /* a HIP runtime call failed; moe_last_hip_error() has its code               */
+} moe_status;
+
+/* How a needed expert was found by the cache (Sec. 3.1, 3.3). */
+typedef enum {
+    MOE_HIT          = 0,  /* resident in one of the layer's k slots: no transfer                    */
+    MOE_PREFETCH_HIT = 1,  /* speculatively loaded earlier: installed by a buffer swap, no transfer   */
+    MOE_MISS         = 2   /* one demand copy of the expert's blob over the host link                */
+} moe_access_status;
+
+typedef struct moe_ctx   moe_ctx_t;    /* owns the b staging buffers, scratch, events (shared by all layers, Sec. 3.3) */
+typedef struct moe_layer moe_layer_t;  /* owns the layer's k device slots, its host blobs and its LRU state (Sec. 3.1) */
+
+enum {
+    MOE_CTX_HOST_ONLY = 1   /* no GPU: only the bookkeeping entry points work (used by CPU tests) */
+};
+
+typedef struct {
+    int32_t n_staging;        /* b: shared on-device buffers for speculative loads (paper: 4)    */
+    int32_t max_batch;        /* 1..MOE_MAX_BATCH                                                */
+    int32_t max_hidden;       /* largest hidden size of any layer                                */
+    int32_t max_ffn;          /* largest expert FFN width of any layer                           */
+    int32_t max_top_k;        /* 1..MOE_MAX_TOPK                                                 */
+    int32_t flags;            /* MOE_CTX_*                                                       */
+    uint64_t max_expert_bytes;/* size of the largest expert blob (moe_expert_blob_bytes)         */
+} moe_ctx_config_t;
+
+enum {
+    MOE_LAYER_NO_CACHE = 1    /* ablation "without LRU cache": residency is forgotten before every step,
+                                 so every needed expert is a demand copy (or a prefetch hit)       */
+};
+
+typedef struct {
+    int32_t hidden;           /* H: model width (multiple of 64)                                 */
+    int32_t ffn;              /* F: expert FFN width (multiple of 64)                            */
+    int32_t n_experts;        /* E <= MOE_MAX_EXPERTS                                            */
+    int32_t top_k;            /* K <= MOE_MAX_TOPK (Mixtral: 2)                                  */
+    int32_t bits;             /* 4, 3 or 2                                                       */
+    int32_t group;            /* codes per (scale, zero) pair along the input dimension:
+                                 4-bit: 32, 64 or 128; 3-bit: 64; 2-bit: 16                      */
+    int32_t cache_slots;      /* k: device-resident experts of this layer; top_k <= k <= E       */
+    int32_t prefetch_m;       /* m: experts guessed for this layer by its predecessor, 0..MOE_MAX_GUESS */
+    float   rms_eps;          /* > 0: RMSNorm with this eps in front of the gate; 0: gate sees x */
+    int32_t init_policy;      /* 0: cache starts empty; 1: experts 0..k-1 resident after loading */
+    int32_t flags;            /* MOE_LAYER_*                                                     */
+} moe_layer_config_t;
+
+typedef struct {
+    int32_t expert;           /* needed expert                                                   */
+    int32_t status;           /* moe_access_status                                               */
+    int32_t slot;             /* cache slot it occupies after this access                        */
+    int32_t victim;           /* expert evicted from that slot, -1 if the slot was empty or on a hit */
+} moe_access_t;
+
+/* What one decode step decided.  Filled synchronously by moe_layer_step / moe_layer_resolve. */
+typedef struct {
+    int32_t batch, top_k, n_experts;
+    int32_t expert_idx[MOE_MAX_BATCH * MOE_MAX_TOPK];   /* [b*top_k + j], best first              */
+    float   expert_w  [MOE_MAX_BATCH * MOE_MAX_TOPK];   /* combine weights, sum to 1 per token    */
+    double  logits    [MOE_MAX_BATCH * MOE_MAX_EXPERTS];/* [b*n_experts + e] gate logits (fp64)   */
+    int32_t n_access;                                   /* distinct needed experts                */
+    moe_access_t access[MOE_MAX_EXPERTS];               /* in the order they touched the cache    */
+    int32_t n_guess;                                    /* speculative guesses for the next layer */
+    int32_t guess_expert[MOE_MAX_GUESS];                /* most likely first                      */
+    int32_t guess_issued[MOE_MAX_GUESS];                /* 1 if a copy into a staging buffer was issued */
+    double  guess_score[MOE_MAX_EXPERTS];               /* summed next-layer gate probabilities   */
+} moe_step_trace_t;
+
+typedef struct {
+    uint64_t steps;           /* decode steps of this layer                                      */
+    uint64_t needed;          /* distinct needed experts, summed over steps                      */
+    uint64_t hits, prefetch_hits, misses;
+    uint64_t evictions;
+    uint64_t spec_issued;     /* speculative copies issued for this layer                        */
+    uint64_t spec_wasted;     /* ... of which this layer did not use                             */
+    uint64_t bytes_h2d_demand;
+    uint64_t bytes_h2d_spec;
+} moe_stats_t;                /* "expert recall" (Sec. 4.1) = (hits + prefetch_hits) / needed    */
+
+/* ---- sizes ---------------------------------------------------------------------------------- */
+
+/* Bytes of one expert's contiguous blob (w1, w3, w2 codes and their fp16 scale/zero pairs) in the
+ * library's private layout; 0 if the shape or format is unsupported.  Sec. 3.3: one buffer per expert. */
+uint64_t moe_expert_blob_bytes(int32_t hidden, int32_t ffn, int32_t bits, int32_t group);
+/* Device arena bytes moe_ctx_create needs: b staging buffers plus activation scratch.  0 on bad config. */
+uint64_t moe_ctx_dev_bytes(const moe_ctx_config_t *cfg);
+/* Device bytes moe_layer_create needs: k buffers of the context's buffer size, the gate matrix, the gain. */
+uint64_t moe_layer_dev_bytes(const moe_ctx_t *ctx, const moe_layer_config_t *cfg);
+/* Pinned host bytes moe_layer_create needs: E blobs. */
+uint64_t moe_layer_host_bytes(const moe_layer_config_t *cfg);
+
+/* ---- life cycle ----------------------------------------------------------------------------- */
+
+/* Create a context.  dev_arena: device memory of at least moe_ctx_dev_bytes(cfg), 256-byte aligned
+ * (ignored with MOE_CTX_HOST_ONLY).  compute_stream / copy_stream: hipStream_t handles, distinct.
+ * All cache slots and staging buffers of this context have one size (Sec. 3.3: equal-size buffers),
+ * so a speculatively loaded expert is installed into a cache by swapping buffers, not by copying. */
+int32_t moe_ctx_create(const moe_ctx_config_t *cfg, void *dev_arena, uint64_t dev_arena_bytes,
+                       void *compute_stream, void *copy_stream, moe_ctx_t **out);
+int32_t moe_ctx_destroy(moe_ctx_t *ctx);
+
+/* Create one MoE layer.  gate_w_host: [E][H] fp32, copied.  rms_gamma_host: [H] fp16 bits or NULL
+ * (NULL with rms_eps > 0 means gain 1).  dev_mem: moe_layer_dev_bytes, 256-byte aligned.
+ * pinned_host_mem: moe_layer_host_bytes of page-locked host memory (Sec. 3.3), 64-byte aligned; in a
+ * host-only context ordinary memory will do.  The expert's blob size must not exceed the context's
+ * max_expert_bytes, hidden/ffn/top_k its maxima. */
+int32_t moe_layer_create(moe_ctx_t *ctx, const moe_layer_config_t *cfg, const float *gate_w_host,
+                         const uint16_t *rms_gamma_host, void *dev_mem, void *pinned_host_mem,
+                         moe_layer_t **out);
+int32_t moe_layer_destroy(moe_layer_t *layer);
+
+/* Hand one matrix of one expert to the layer.  matrix: 0 = w1 [F][H], 1 = w3 [F][H], 2 = w2 [H][F],
+ * row-major [out][in].  codes: one byte per weight, values < 2^bits.  scale/zero: fp16 bits,
+ * [out][in/group], groups along `in`; the stored weight is (code - zero) * scale (Sec. 4.2).
+ * All host memory, read during the call only.  The library repacks into the expert's blob in the
+ * pinned arena; with init_policy 1, experts 0..k-1 are also copied to their slots once complete. */
+int32_t moe_layer_load_expert(moe_layer_t *layer, int32_t expert, int32_t matrix, const uint8_t *codes,
+                              const uint16_t *scale_f16, const uint16_t *zero_f16);
+/* Read one weight back out of the packed host blob (checks the private layout without a GPU). */
+int32_t moe_layer_peek_weight(const moe_layer_t *layer, int32_t expert, int32_t matrix, int32_t row,
+                              int32_t col, uint8_t *code, uint16_t *scale_f16, uint16_t *zero_f16);
+
+/* ---- the decode step ------------------------------------------------------------------------ */
+
+/* One decode step of one layer for `batch` tokens (Sec. 3: token-by-token, layer-by-layer).
+ *   x_in_dev  [batch][H] fp16, device: the block's input (residual stream).
+ *   x_out_dev [batch][H] fp16, device: x_in + sum_j w_j expert_j(h); may alias x_in_dev.
+ *   h_out_dev nullable, [batch][H] fp16: receives the gate input h (x, or RMSNorm(x)).
+ *   next      nullable: the following layer.  If given and next->prefetch_m > 0 the step also applies
+ *             next's gate to h and stages its guesses (Sec. 3.2), right after this layer's own loads
+ *             were issued (Sec. 3.3).
+ *   trace     nullable, host: what was decided.
+ * The gate runs on the compute stream and the call waits for its result (the cache table lives on the
+ * host); copies and the expert kernels are then enqueued and the call returns without waiting for
+ * them: x_out is valid once the compute stream reaches this point. */
+int32_t moe_layer_step(moe_layer_t *layer, moe_layer_t *next, const uint16_t *x_in_dev, int32_t batch,
+                       uint16_t *x_out_dev, uint16_t *h_out_dev, moe_step_trace_t *trace);
+
+/* Stand-alone speculative loading (Sec. 3.2): apply `layer`'s own gate to h_dev [batch][H] fp16 (the
+ * previous layer's gate input) and stage up to prefetch_m guesses for `layer`.  Makes exactly the
+ * decisions moe_layer_step(prev, next=layer) makes.  trace (nullable) gets n_guess, guess_*. */
+int32_t moe_layer_prefetch(moe_layer_t *layer, const uint16_t *h_dev, int32_t batch, moe_step_trace_t *trace);
+
+/* Run `n_layers` layers back to back on one batch: x_in_dev -> x_out_dev through layers[0..n-1], each
+ * prefetching for its successor.  traces: nullable array of n_layers traces. */
+int32_t moe_stack_step(moe_layer_t *const *layers, int32_t n_layers, const uint16_t *x_in_dev, int32_t batch,
+                       uint16_t *x_out_dev, moe_step_trace_t *traces);
+
+/* The cache/prefetch bookkeeping of one step on its own, for given routing (host arrays):
+ * expert_idx [batch][top_k]; guess_score nullable [next->n_experts] (summed next-layer probabilities).
+ * In a GPU context it also issues the copies it decides on; in a host-only context it moves no data.
+ * moe_layer_step calls exactly this after its gate kernel. */
+int32_t moe_layer_resolve(moe_layer_t *layer, moe_layer_t *next, const int32_t *expert_idx, int32_t batch,
+                          const double *guess_score, moe_step_trace_t *trace);
+
+/* ---- state ---------------------------------------------------------------------------------- */
+
+int32_t moe_layer_stats(const moe_layer_t *layer, moe_stats_t *out);
+/* Cache contents: slot_expert[k] (expert id or -1), slot_stamp[k] (recency, larger = more recent),
+ * staged[MOE_MAX_EXPERTS] (n_staged ids speculatively loaded for this layer).  Any pointer may be NULL. */
+int32_t moe_layer_cache_state(const moe_layer_t *layer, int32_t *slot_expert, uint64_t *slot_stamp,
+                              int32_t *staged, int32_t *n_staged);
+/* Forget residency, staged guesses and statistics (cold cache, or warm per init_policy). Waits for both streams. */
+int32_t moe_layer_reset(moe_layer_t *layer);
+/* Change m, the number of experts its predecessor guesses for this layer (ablation "without pre-loading"). */
+int32_t moe_layer_set_prefetch(moe_layer_t *layer, int32_t prefetch_m);
+/* Set or clear MOE_LAYER_* flags. */
+int32_t moe_layer_set_flags(moe_layer_t *layer, int32_t flags);
+
+/* Diagnostic: copy the fp32 block output y [batch][hidden] of the most recent step (the weighted expert
+ * sum before the residual add) to host memory.  Waits for the compute stream. */
+int32_t moe_ctx_read_y(moe_ctx_t *ctx, int32_t batch, int32_t hidden, float *y_host);
+
+const char *moe_last_error(void);
+int32_t moe_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE_OFFLOAD_H */

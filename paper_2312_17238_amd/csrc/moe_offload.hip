@@ -1,0 +1,775 @@
+// C ABI of the MoE-offloading decode engine (see include/moe_offload.h for the contract).
+//
+// One decode step of one layer, as the paper orders it (Sec. 3.2, 3.3):
+//   gate kernel (compute stream)  ->  host reads the routing from host-mapped memory
+//   -> host resolves the LRU cache -> demand copies (copy stream) -> speculative copies for the next
+//   layer (copy stream, right after the demand copies) -> compute stream waits on the events of the
+//   buffers it is about to read -> fused dequant-GEMV kernels -> residual add.
+// The call returns as soon as everything is enqueued.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <atomic>
+#include <chrono>
+#include <cstdarg>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <thread>
+#include <vector>
+
+#include "../../include/moe_offload.h"
+#include "cache.h"
+#include "kernels.h"
+#include "layout.h"
+
+using namespace moe;
+
+// ---------------------------------------------------------------------------------------------
+// errors
+// ---------------------------------------------------------------------------------------------
+
+static thread_local char g_err[512] = "";
+static thread_local int32_t g_hip_err = 0;
+
+static int32_t fail(int32_t code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+#define HIPCHK(expr)                                                                                   \
+    do {                                                                                               \
+        hipError_t e_ = (expr);                                                                        \
+        if (e_ != hipSuccess) {                                                                        \
+            g_hip_err = (int32_t)e_;                                                                   \
+            return fail(MOE_EHIP, "%s failed: %s (%s:%d)", #expr, hipGetErrorString(e_), __FILE__, __LINE__); \
+        }                                                                                              \
+    } while (0)
+
+extern "C" const char *moe_last_error(void) { return g_err; }
+extern "C" int32_t moe_last_hip_error(void) { return g_hip_err; }
+
+// ---------------------------------------------------------------------------------------------
+// objects
+// ---------------------------------------------------------------------------------------------
+
+struct PoolBuf {
+    uint8_t *ptr = nullptr;
+    hipEvent_t ready = nullptr;   // recorded on the copy stream after the last copy into this buffer
+    bool pending = false;         // a copy was recorded that the compute stream has not yet waited on
+};
+
+struct moe_ctx {
+    moe_ctx_config_t cfg{};
+    bool host_only = false;
+    hipStream_t compute = nullptr, copy = nullptr;
+    uint64_t buf_bytes = 0;
+    std::vector<PoolBuf> bufs;          // [0, n_staging): staging; layers append their slots
+    BufferPool pool;
+    uint16_t *h_buf = nullptr, *a_buf = nullptr, *xbuf[2] = {nullptr, nullptr};
+    float *yacc = nullptr;
+    GateHostOut *gate_out = nullptr;    // host pointer
+    GateHostOut *gate_out_dev = nullptr;// the same memory as the device sees it
+    hipEvent_t ev_gate = nullptr, ev_compute = nullptr;
+    int32_t n_layers = 0;
+    int32_t w13_blocks = 512, w2_rows = 16;
+    bool sync_wait = false;
+};
+
+struct moe_layer {
+    moe_ctx *ctx = nullptr;
+    moe_layer_config_t cfg{};
+    BlobLayout lay;
+    LayerCache cache;
+    Counters st;
+    float *gate_w_dev = nullptr;
+    uint16_t *gamma_dev = nullptr;
+    uint8_t *host_blobs = nullptr;
+    std::vector<uint32_t> loaded;       // bit m set: matrix m of the expert was loaded
+    std::vector<int32_t> own_bufs;      // the k pool buffers created for this layer
+};
+
+static uint64_t align_u64(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
+
+static bool ctx_cfg_ok(const moe_ctx_config_t *c)
+{
+    return c && c->n_staging >= 0 && c->n_staging <= 64 && c->max_batch >= 1 && c->max_batch <= MOE_MAX_BATCH &&
+           c->max_hidden >= 64 && c->max_hidden % 64 == 0 && c->max_hidden <= 8192 && c->max_ffn >= 64 &&
+           c->max_ffn % 64 == 0 && c->max_ffn <= 32768 && c->max_top_k >= 1 && c->max_top_k <= MOE_MAX_TOPK &&
+           c->max_expert_bytes > 0;
+}
+
+static bool layer_cfg_ok(const moe_layer_config_t *c)
+{
+    return c && c->n_experts >= 1 && c->n_experts <= MOE_MAX_EXPERTS && c->top_k >= 1 && c->top_k <= MOE_MAX_TOPK &&
+           c->top_k <= c->n_experts && c->cache_slots >= c->top_k && c->cache_slots <= c->n_experts &&
+           c->prefetch_m >= 0 && c->prefetch_m <= MOE_MAX_GUESS && c->rms_eps >= 0.f &&
+           (c->init_policy == 0 || c->init_policy == 1) && blob_layout(c->hidden, c->ffn, c->bits, c->group).ok;
+}
+
+struct ScratchPlan { uint64_t staging, h, a, yacc, x0, x1, total; };
+
+static ScratchPlan plan_scratch(const moe_ctx_config_t *c)
+{
+    ScratchPlan p{};
+    const uint64_t buf = align_u64(c->max_expert_bytes, 4096);
+    uint64_t off = 0;
+    p.staging = off; off += buf * (uint64_t)c->n_staging;
+    p.h = off;    off += align_u64((uint64_t)c->max_batch * c->max_hidden * 2, 256);
+    p.a = off;    off += align_u64((uint64_t)c->max_batch * c->max_top_k * c->max_ffn * 2, 256);
+    p.yacc = off; off += align_u64((uint64_t)c->max_batch * c->max_hidden * 4, 256);
+    p.x0 = off;   off += align_u64((uint64_t)c->max_batch * c->max_hidden * 2, 256);
+    p.x1 = off;   off += align_u64((uint64_t)c->max_batch * c->max_hidden * 2, 256);
+    p.total = off;
+    return p;
+}
+
+// ---------------------------------------------------------------------------------------------
+// sizes
+// ---------------------------------------------------------------------------------------------
+
+extern "C" uint64_t moe_expert_blob_bytes(int32_t hidden, int32_t ffn, int32_t bits, int32_t group)
+{
+    BlobLayout b = blob_layout(hidden, ffn, bits, group);
+    return b.ok ? b.total : 0;
+}
+
+extern "C" uint64_t moe_ctx_dev_bytes(const moe_ctx_config_t *cfg)
+{
+    if (!ctx_cfg_ok(cfg)) return 0;
+    return plan_scratch(cfg).total;
+}
+
+extern "C" uint64_t moe_layer_dev_bytes(const moe_ctx_t *ctx, const moe_layer_config_t *cfg)
+{
+    if (!ctx || !layer_cfg_ok(cfg)) return 0;
+    return ctx->buf_bytes * (uint64_t)cfg->cache_slots + align_u64((uint64_t)cfg->n_experts * cfg->hidden * 4, 256) +
+           align_u64((uint64_t)cfg->hidden * 2, 256);
+}
+
+extern "C" uint64_t moe_layer_host_bytes(const moe_layer_config_t *cfg)
+{
+    if (!layer_cfg_ok(cfg)) return 0;
+    return blob_layout(cfg->hidden, cfg->ffn, cfg->bits, cfg->group).total * (uint64_t)cfg->n_experts;
+}
+
+// ---------------------------------------------------------------------------------------------
+// context
+// ---------------------------------------------------------------------------------------------
+
+static int env_int(const char *name, int dflt)
+{
+    const char *v = getenv(name);
+    return (v && *v) ? atoi(v) : dflt;
+}
+
+extern "C" int32_t moe_ctx_create(const moe_ctx_config_t *cfg, void *dev_arena, uint64_t dev_arena_bytes,
+                                  void *compute_stream, void *copy_stream, moe_ctx_t **out)
+{
+    if (!out) return fail(MOE_EINVAL, "moe_ctx_create: out is null");
+    *out = nullptr;
+    if (!ctx_cfg_ok(cfg)) return fail(MOE_EINVAL, "moe_ctx_create: bad configuration");
+    moe_ctx *c = new (std::nothrow) moe_ctx();
+    if (!c) return fail(MOE_ENOMEM, "moe_ctx_create: out of host memory");
+    c->cfg = *cfg;
+    c->host_only = (cfg->flags & MOE_CTX_HOST_ONLY) != 0;
+    c->buf_bytes = align_u64(cfg->max_expert_bytes, 4096);
+    c->bufs.resize(cfg->n_staging);
+    for (int i = 0; i < cfg->n_staging; ++i) c->pool.free_staging.push_back(i);
+    c->w13_blocks = std::max(1, env_int("MOE_W13_BLOCKS", 512));
+    c->w2_rows = std::max(8, env_int("MOE_W2_ROWS", 16) / 8 * 8);
+    c->sync_wait = env_int("MOE_SYNC_WAIT", 0) != 0;
+    if (c->host_only) {
+        c->gate_out = static_cast<GateHostOut *>(calloc(1, sizeof(GateHostOut)));
+        if (!c->gate_out) { delete c; return fail(MOE_ENOMEM, "moe_ctx_create: out of host memory"); }
+        *out = c;
+        return MOE_OK;
+    }
+    const ScratchPlan p = plan_scratch(cfg);
+    if (!dev_arena || ((uintptr_t)dev_arena & 255)) { delete c; return fail(MOE_EINVAL, "moe_ctx_create: device arena null or not 256-byte aligned"); }
+    if (dev_arena_bytes < p.total) { delete c; return fail(MOE_ENOMEM, "moe_ctx_create: device arena has %llu bytes, %llu needed", (unsigned long long)dev_arena_bytes, (unsigned long long)p.total); }
+    if (compute_stream == copy_stream) { delete c; return fail(MOE_EINVAL, "moe_ctx_create: compute and copy stream must differ"); }
+    c->compute = static_cast<hipStream_t>(compute_stream);
+    c->copy = static_cast<hipStream_t>(copy_stream);
+    uint8_t *base = static_cast<uint8_t *>(dev_arena);
+    for (int i = 0; i < cfg->n_staging; ++i) c->bufs[i].ptr = base + p.staging + c->buf_bytes * i;
+    c->h_buf = reinterpret_cast<uint16_t *>(base + p.h);
+    c->a_buf = reinterpret_cast<uint16_t *>(base + p.a);
+    c->yacc = reinterpret_cast<float *>(base + p.yacc);
+    c->xbuf[0] = reinterpret_cast<uint16_t *>(base + p.x0);
+    c->xbuf[1] = reinterpret_cast<uint16_t *>(base + p.x1);
+    hipError_t e = hipHostMalloc(reinterpret_cast<void **>(&c->gate_out), sizeof(GateHostOut), hipHostMallocMapped);
+    if (e == hipSuccess) e = hipHostGetDevicePointer(reinterpret_cast<void **>(&c->gate_out_dev), c->gate_out, 0);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_gate, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_compute, hipEventDisableTiming);
+    for (int i = 0; i < cfg->n_staging && e == hipSuccess; ++i)
+        e = hipEventCreateWithFlags(&c->bufs[i].ready, hipEventDisableTiming);
+    if (e != hipSuccess) {
+        g_hip_err = (int32_t)e;
+        moe_ctx_destroy(c);
+        return fail(MOE_EHIP, "moe_ctx_create: HIP set-up failed: %s", hipGetErrorString(e));
+    }
+    memset(c->gate_out, 0, sizeof(GateHostOut));
+    *out = c;
+    return MOE_OK;
+}
+
+extern "C" int32_t moe_ctx_destroy(moe_ctx_t *c)
+{
+    if (!c) return MOE_OK;
+    if (c->host_only) {
+        free(c->gate_out);
+    } else {
+        if (c->compute) (void)hipStreamSynchronize(c->compute);
+        if (c->copy) (void)hipStreamSynchronize(c->copy);
+        for (PoolBuf &b : c->bufs)
+            if (b.ready) (void)hipEventDestroy(b.ready);
+        if (c->ev_gate) (void)hipEventDestroy(c->ev_gate);
+        if (c->ev_compute) (void)hipEventDestroy(c->ev_compute);
+        if (c->gate_out) (void)hipHostFree(c->gate_out);
+    }
+    delete c;
+    return MOE_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// layer
+// ---------------------------------------------------------------------------------------------
+
+static void cache_init(moe_layer *l)
+{
+    LayerCache &c = l->cache;
+    c.k = l->cfg.cache_slots;
+    c.n_experts = l->cfg.n_experts;
+    c.slot_expert.assign(c.k, -1);
+    c.slot_stamp.assign(c.k, 0);
+    c.slot_buf = l->own_bufs;
+    c.staged.clear();
+    l->st = Counters();
+}
+
+extern "C" int32_t moe_layer_create(moe_ctx_t *ctx, const moe_layer_config_t *cfg, const float *gate_w_host,
+                                    const uint16_t *rms_gamma_host, void *dev_mem, void *pinned_host_mem,
+                                    moe_layer_t **out)
+{
+    if (!out) return fail(MOE_EINVAL, "moe_layer_create: out is null");
+    *out = nullptr;
+    if (!ctx) return fail(MOE_EINVAL, "moe_layer_create: ctx is null");
+    if (!layer_cfg_ok(cfg)) return fail(MOE_EINVAL, "moe_layer_create: bad or unsupported configuration");
+    if (cfg->bits != 4) return fail(MOE_EINVAL, "moe_layer_create: only 4-bit experts have kernels so far");
+    if (!gate_w_host || !pinned_host_mem) return fail(MOE_EINVAL, "moe_layer_create: null gate or host arena");
+    BlobLayout lay = blob_layout(cfg->hidden, cfg->ffn, cfg->bits, cfg->group);
+    if (lay.total > ctx->buf_bytes) return fail(MOE_EINVAL, "moe_layer_create: expert blob (%llu B) exceeds the context's buffer size (%llu B)", (unsigned long long)lay.total, (unsigned long long)ctx->buf_bytes);
+    if (cfg->hidden > ctx->cfg.max_hidden || cfg->ffn > ctx->cfg.max_ffn || cfg->top_k > ctx->cfg.max_top_k)
+        return fail(MOE_EINVAL, "moe_layer_create: layer exceeds the context's maxima");
+    if ((uintptr_t)pinned_host_mem & 63) return fail(MOE_EINVAL, "moe_layer_create: host arena not 64-byte aligned");
+    moe_layer *l = new (std::nothrow) moe_layer();
+    if (!l) return fail(MOE_ENOMEM, "moe_layer_create: out of host memory");
+    l->ctx = ctx;
+    l->cfg = *cfg;
+    l->lay = lay;
+    l->host_blobs = static_cast<uint8_t *>(pinned_host_mem);
+    l->loaded.assign(cfg->n_experts, 0);
+    const int first = (int)ctx->bufs.size();
+    if (!ctx->host_only) {
+        if (!dev_mem || ((uintptr_t)dev_mem & 255)) { delete l; return fail(MOE_EINVAL, "moe_layer_create: device memory null or not 256-byte aligned"); }
+        uint8_t *base = static_cast<uint8_t *>(dev_mem);
+        const uint64_t gate_bytes = (uint64_t)cfg->n_experts * cfg->hidden * 4;
+        l->gate_w_dev = reinterpret_cast<float *>(base + ctx->buf_bytes * cfg->cache_slots);
+        l->gamma_dev = reinterpret_cast<uint16_t *>(reinterpret_cast<uint8_t *>(l->gate_w_dev) + align_u64(gate_bytes, 256));
+        hipError_t e = hipMemcpy(l->gate_w_dev, gate_w_host, gate_bytes, hipMemcpyHostToDevice);
+        std::vector<uint16_t> ones;
+        if (e == hipSuccess) {
+            const uint16_t *g = rms_gamma_host;
+            if (!g) { ones.assign(cfg->hidden, 0x3c00); g = ones.data(); }
+            e = hipMemcpy(l->gamma_dev, g, (size_t)cfg->hidden * 2, hipMemcpyHostToDevice);
+        }
+        std::vector<PoolBuf> fresh(cfg->cache_slots);
+        for (int s = 0; s < cfg->cache_slots && e == hipSuccess; ++s) {
+            fresh[s].ptr = base + ctx->buf_bytes * s;
+            e = hipEventCreateWithFlags(&fresh[s].ready, hipEventDisableTiming);
+        }
+        if (e != hipSuccess) {
+            for (PoolBuf &b : fresh) if (b.ready) (void)hipEventDestroy(b.ready);
+            g_hip_err = (int32_t)e;
+            delete l;
+            return fail(MOE_EHIP, "moe_layer_create: HIP set-up failed: %s", hipGetErrorString(e));
+        }
+        for (PoolBuf &b : fresh) ctx->bufs.push_back(b);
+    } else {
+        ctx->bufs.resize(first + cfg->cache_slots);
+    }
+    for (int s = 0; s < cfg->cache_slots; ++s) l->own_bufs.push_back(first + s);
+    cache_init(l);
+    ctx->n_layers++;
+    *out = l;
+    return MOE_OK;
+}
+
+extern "C" int32_t moe_layer_destroy(moe_layer_t *l)
+{
+    if (!l) return MOE_OK;
+    if (!l->ctx->host_only) {
+        (void)hipStreamSynchronize(l->ctx->compute);
+        (void)hipStreamSynchronize(l->ctx->copy);
+    }
+    l->ctx->n_layers--;
+    delete l;   // pool buffers and their events stay with the context until it is destroyed
+    return MOE_OK;
+}
+
+static bool all_loaded(const moe_layer *l)
+{
+    for (uint32_t m : l->loaded)
+        if (m != 7u) return false;
+    return true;
+}
+
+static int32_t warm_fill(moe_layer *l, int32_t e)
+{
+    // init_policy 1: expert e < k sits in slot e from the start
+    LayerCache &c = l->cache;
+    c.slot_expert[e] = e;
+    c.slot_stamp[e] = ++l->ctx->pool.clock;
+    if (!l->ctx->host_only) {
+        PoolBuf &b = l->ctx->bufs[c.slot_buf[e]];
+        HIPCHK(hipMemcpy(b.ptr, l->host_blobs + (uint64_t)e * l->lay.total, l->lay.total, hipMemcpyHostToDevice));
+    }
+    return MOE_OK;
+}
+
+extern "C" int32_t moe_layer_load_expert(moe_layer_t *l, int32_t expert, int32_t matrix, const uint8_t *codes,
+                                         const uint16_t *scale, const uint16_t *zero)
+{
+    if (!l || !codes || !scale || !zero) return fail(MOE_EINVAL, "moe_layer_load_expert: null argument");
+    if (expert < 0 || expert >= l->cfg.n_experts || matrix < 0 || matrix > 2)
+        return fail(MOE_EINVAL, "moe_layer_load_expert: expert %d / matrix %d out of range", expert, matrix);
+    const BlobLayout &b = l->lay;
+    const MatLayout &m = mat_of(b, matrix);
+    uint8_t *blob = l->host_blobs + (uint64_t)expert * b.total;
+    const uint32_t groups = m.cols / b.group;
+    const uint32_t qmax = (1u << b.bits) - 1;
+    const unsigned hw = std::max(1u, std::min(16u, std::thread::hardware_concurrency()));
+    const unsigned nthreads = (uint64_t)m.rows * m.cols < (1u << 20) ? 1 : hw;
+    std::atomic<int> bad{0};
+    auto work = [&](uint32_t r0, uint32_t r1) {
+        for (uint32_t r = r0; r < r1; ++r) {
+            const uint8_t *cr = codes + (uint64_t)r * m.cols;
+            uint32_t mx = 0;
+            for (uint32_t i = 0; i < m.cols; ++i) mx |= cr[i];
+            if (mx > qmax) { bad.store(1); return; }
+            pack_row(b, m, cr, scale + (uint64_t)r * groups, zero + (uint64_t)r * groups, blob + row_offset(b, matrix, r));
+        }
+    };
+    if (nthreads == 1) {
+        work(0, m.rows);
+    } else {
+        std::vector<std::thread> th;
+        const uint32_t per = (m.rows + nthreads - 1) / nthreads;
+        for (unsigned t = 0; t < nthreads; ++t) {
+            uint32_t r0 = t * per, r1 = std::min(m.rows, r0 + per);
+            if (r0 < r1) th.emplace_back(work, r0, r1);
+        }
+        for (std::thread &t : th) t.join();
+    }
+    if (bad.load()) return fail(MOE_EINVAL, "moe_layer_load_expert: a code exceeds %u", qmax);
+    l->loaded[expert] |= 1u << matrix;
+    if (l->loaded[expert] == 7u && l->cfg.init_policy == 1 && expert < l->cfg.cache_slots) return warm_fill(l, expert);
+    return MOE_OK;
+}
+
+extern "C" int32_t moe_layer_peek_weight(const moe_layer_t *l, int32_t expert, int32_t matrix, int32_t row, int32_t col,
+                                         uint8_t *code, uint16_t *scale, uint16_t *zero)
+{
+    if (!l || !code || !scale || !zero) return fail(MOE_EINVAL, "moe_layer_peek_weight: null argument");
+    if (expert < 0 || expert >= l->cfg.n_experts || matrix < 0 || matrix > 2)
+        return fail(MOE_EINVAL, "moe_layer_peek_weight: expert or matrix out of range");
+    const MatLayout &m = mat_of(l->lay, matrix);
+    if (row < 0 || (uint32_t)row >= m.rows || col < 0 || (uint32_t)col >= m.cols)
+        return fail(MOE_EINVAL, "moe_layer_peek_weight: row or column out of range");
+    if (!(l->loaded[expert] & (1u << matrix))) return fail(MOE_ESTATE, "moe_layer_peek_weight: matrix not loaded");
+    peek_row(l->lay, m, l->host_blobs + (uint64_t)expert * l->lay.total + row_offset(l->lay, matrix, row), col, code, scale, zero);
+    return MOE_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// bookkeeping of one step (host only)
+// ---------------------------------------------------------------------------------------------
+
+struct StepPlan {
+    std::vector<AccessRec> access;
+    std::vector<CopyOp> demand;     // in access order
+    std::vector<CopyOp> spec;       // for the next layer
+    bool victim_needed = false;     // an expert needed in this step was evicted during it
+};
+
+static int32_t plan_step(moe_layer *l, moe_layer *next, const int32_t *idx, int32_t batch, const double *guess_score,
+                         moe_step_trace_t *tr, StepPlan &plan)
+{
+    const moe_layer_config_t &cf = l->cfg;
+    std::vector<int32_t> needed;
+    for (int i = 0; i < batch * cf.top_k; ++i) {
+        if (idx[i] < 0 || idx[i] >= cf.n_experts) return fail(MOE_EINVAL, "routing index %d out of range", idx[i]);
+        needed.push_back(idx[i]);
+    }
+    std::sort(needed.begin(), needed.end());
+    needed.erase(std::unique(needed.begin(), needed.end()), needed.end());
+    resolve_accesses(l->cache, l->ctx->pool, l->st, needed, (cf.flags & MOE_LAYER_NO_CACHE) != 0, plan.access, plan.demand);
+    for (const AccessRec &a : plan.access)
+        if (a.victim >= 0 && std::binary_search(needed.begin(), needed.end(), a.victim)) plan.victim_needed = true;
+    l->st.bytes_demand += (uint64_t)plan.demand.size() * l->lay.total;
+    std::vector<int32_t> guess, issued;
+    if (next && guess_score && next->cfg.prefetch_m > 0) {
+        guess = top_m(guess_score, next->cfg.n_experts, next->cfg.prefetch_m);
+        stage_guesses(next->cache, l->ctx->pool, next->st, guess, issued, plan.spec);
+        next->st.bytes_spec += (uint64_t)plan.spec.size() * next->lay.total;
+    }
+    if (tr) {
+        tr->batch = batch; tr->top_k = cf.top_k; tr->n_experts = cf.n_experts;
+        for (int i = 0; i < batch * cf.top_k; ++i) tr->expert_idx[i] = idx[i];
+        tr->n_access = (int32_t)plan.access.size();
+        for (size_t i = 0; i < plan.access.size(); ++i)
+            tr->access[i] = {plan.access[i].expert, plan.access[i].status, plan.access[i].slot, plan.access[i].victim};
+        tr->n_guess = (int32_t)guess.size();
+        for (size_t i = 0; i < guess.size(); ++i) { tr->guess_expert[i] = guess[i]; tr->guess_issued[i] = issued[i]; }
+        if (next && guess_score)
+            for (int e = 0; e < next->cfg.n_experts; ++e) tr->guess_score[e] = guess_score[e];
+    }
+    return MOE_OK;
+}
+
+static int32_t issue_copy(moe_ctx *c, const moe_layer *owner, const CopyOp &op)
+{
+    PoolBuf &b = c->bufs[op.buf];
+    HIPCHK(hipMemcpyAsync(b.ptr, owner->host_blobs + (uint64_t)op.expert * owner->lay.total, owner->lay.total,
+                          hipMemcpyHostToDevice, c->copy));
+    HIPCHK(hipEventRecord(b.ready, c->copy));
+    b.pending = true;
+    return MOE_OK;
+}
+
+static int32_t check_step_args(const moe_layer *l, const moe_layer *next, int32_t batch)
+{
+    if (!l) return fail(MOE_EINVAL, "layer is null");
+    if (batch < 1 || batch > l->ctx->cfg.max_batch) return fail(MOE_EINVAL, "batch %d outside 1..%d", batch, l->ctx->cfg.max_batch);
+    if (next && next->ctx != l->ctx) return fail(MOE_EINVAL, "next layer belongs to another context");
+    if (next && next->cfg.hidden != l->cfg.hidden) return fail(MOE_EINVAL, "next layer has another hidden size");
+    return MOE_OK;
+}
+
+extern "C" int32_t moe_layer_resolve(moe_layer_t *l, moe_layer_t *next, const int32_t *expert_idx, int32_t batch,
+                                     const double *guess_score, moe_step_trace_t *trace)
+{
+    int32_t rc = check_step_args(l, next, batch);
+    if (rc) return rc;
+    if (!expert_idx) return fail(MOE_EINVAL, "moe_layer_resolve: expert_idx is null");
+    if (!l->ctx->host_only && !all_loaded(l)) return fail(MOE_ESTATE, "moe_layer_resolve: not every expert of the layer is loaded");
+    StepPlan plan;
+    rc = plan_step(l, next, expert_idx, batch, guess_score, trace, plan);
+    if (rc) return rc;
+    if (!l->ctx->host_only) {
+        for (const CopyOp &op : plan.demand) { rc = issue_copy(l->ctx, l, op); if (rc) return rc; }
+        for (const CopyOp &op : plan.spec) { rc = issue_copy(l->ctx, next, op); if (rc) return rc; }
+    }
+    return MOE_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// the GPU step
+// ---------------------------------------------------------------------------------------------
+
+static int32_t wait_gate(moe_ctx *c, uint32_t expect)
+{
+    if (c->sync_wait) {
+        HIPCHK(hipStreamSynchronize(c->compute));
+    } else {
+        volatile uint32_t *flag = &c->gate_out->done;
+        for (uint64_t spin = 0;; ++spin) {
+            if (*flag == expect) break;
+            if (spin > 4096 && (spin & 255) == 0) {
+                hipError_t q = hipEventQuery(c->ev_gate);
+                if (q == hipSuccess) break;            // kernel over: the flag is re-read below
+                if (q != hipErrorNotReady) { g_hip_err = (int32_t)q; return fail(MOE_EHIP, "gate kernel failed: %s", hipGetErrorString(q)); }
+            }
+            __builtin_ia32_pause();
+        }
+    }
+    std::atomic_thread_fence(std::memory_order_acquire);
+    if (c->gate_out->done != expect) return fail(MOE_ESTATE, "gate kernel finished but published %u of %u results", c->gate_out->done, expect);
+    return MOE_OK;
+}
+
+static int32_t launch_gate(moe_ctx *c, const GateArgs &ga, int32_t batch)
+{
+    c->gate_out->done = 0;
+    std::atomic_thread_fence(std::memory_order_release);
+    hipLaunchKernelGGL(k_gate, dim3(batch), dim3(GATE_THREADS), (size_t)ga.H * 2, c->compute, ga);
+    HIPCHK(hipGetLastError());
+    if (!c->sync_wait) HIPCHK(hipEventRecord(c->ev_gate, c->compute));
+    return wait_gate(c, (uint32_t)batch);
+}
+
+template <int KCH>
+static void launch_w13(int nt, dim3 grid, hipStream_t s, const FfnArgs &A)
+{
+    const dim3 block(W13_WAVES * WAVE);
+    if (nt == 1) hipLaunchKernelGGL((k_w13_q4<KCH, 1>), grid, block, 0, s, A);
+    else if (nt == 2) hipLaunchKernelGGL((k_w13_q4<KCH, 2>), grid, block, 0, s, A);
+    else hipLaunchKernelGGL((k_w13_q4<KCH, 4>), grid, block, 0, s, A);
+}
+
+static int32_t launch_ffn(moe_layer *l, const std::vector<FfnEntry> &entries, int nt)
+{
+    moe_ctx *c = l->ctx;
+    const BlobLayout &b = l->lay;
+    const int kch = (b.hidden / 32 + 63) / 64;         // chunks per lane per w1/w3 row
+    const int cs = (b.ffn / 32 + 63) / 64;             // waves per block for w2
+    if (kch > 4 || cs > 16) return fail(MOE_EINVAL, "shape too large for the GEMV kernels");
+    if (kch == 4 && nt > 2) nt = 2;                    // register budget
+    for (size_t first = 0; first < entries.size(); first += MAX_ENTRIES) {
+        const int n = (int)std::min<size_t>(MAX_ENTRIES, entries.size() - first);
+        FfnArgs A{};
+        for (int i = 0; i < n; ++i) A.e[i] = entries[first + i];
+        A.h = c->h_buf; A.a = c->a_buf; A.yacc = c->yacc;
+        A.H = b.hidden; A.F = b.ffn; A.group = b.group;
+        A.stride13 = b.m13.row_stride; A.meta13 = b.m13.meta_off;
+        A.stride2 = b.m2.row_stride; A.meta2 = b.m2.meta_off;
+        A.off_w2 = b.off_w2;
+        A.rows_per_block = c->w2_rows;
+        int bx = std::max(1, std::min((b.ffn + W13_WAVES - 1) / W13_WAVES, c->w13_blocks / n));
+        const dim3 g13(bx, n);
+        if (kch == 1) launch_w13<1>(nt, g13, c->compute, A);
+        else if (kch == 2) launch_w13<2>(nt, g13, c->compute, A);
+        else launch_w13<4>(nt, g13, c->compute, A);
+        HIPCHK(hipGetLastError());
+        const dim3 g2((b.hidden + A.rows_per_block - 1) / A.rows_per_block, n), blk(cs * WAVE);
+        const size_t shm = (size_t)A.rows_per_block * nt * cs * sizeof(float);
+        if (nt == 1) hipLaunchKernelGGL((k_w2_q4<1>), g2, blk, shm, c->compute, A);
+        else if (nt == 2) hipLaunchKernelGGL((k_w2_q4<2>), g2, blk, shm, c->compute, A);
+        else hipLaunchKernelGGL((k_w2_q4<4>), g2, blk, shm, c->compute, A);
+        HIPCHK(hipGetLastError());
+    }
+    return MOE_OK;
+}
+
+extern "C" int32_t moe_layer_step(moe_layer_t *l, moe_layer_t *next, const uint16_t *x_in, int32_t batch,
+                                  uint16_t *x_out, uint16_t *h_out, moe_step_trace_t *trace)
+{
+    int32_t rc = check_step_args(l, next, batch);
+    if (rc) return rc;
+    moe_ctx *c = l->ctx;
+    if (c->host_only) return fail(MOE_ESTATE, "moe_layer_step: host-only context");
+    if (!x_in || !x_out) return fail(MOE_EINVAL, "moe_layer_step: null activation pointer");
+    if (!all_loaded(l)) return fail(MOE_ESTATE, "moe_layer_step: not every expert of the layer is loaded");
+    const moe_layer_config_t &cf = l->cfg;
+    const bool spec = next && next->cfg.prefetch_m > 0 && c->cfg.n_staging > 0;
+    if (spec && !all_loaded(next)) return fail(MOE_ESTATE, "moe_layer_step: next layer not fully loaded");
+
+    GateArgs ga{};
+    ga.x = x_in; ga.wg = l->gate_w_dev; ga.wg2 = spec ? next->gate_w_dev : nullptr;
+    ga.gamma = l->gamma_dev; ga.h_out = c->h_buf; ga.h_out2 = h_out; ga.yacc = c->yacc; ga.out = c->gate_out_dev;
+    ga.eps = (double)cf.rms_eps; ga.H = cf.hidden; ga.E = cf.n_experts; ga.E2 = spec ? next->cfg.n_experts : 0; ga.K = cf.top_k;
+    rc = launch_gate(c, ga, batch);
+    if (rc) return rc;
+
+    const GateHostOut *go = c->gate_out;
+    int32_t idx[MOE_MAX_BATCH * MOE_MAX_TOPK];
+    float w[MOE_MAX_BATCH * MOE_MAX_TOPK];
+    for (int i = 0; i < batch * cf.top_k; ++i) { idx[i] = go->idx[i]; w[i] = go->w[i]; }
+    double score[MOE_MAX_EXPERTS] = {0};
+    if (spec)
+        for (int b = 0; b < batch; ++b)
+            for (int e = 0; e < ga.E2; ++e) score[e] += go->spec_p[b * ga.E2 + e];
+
+    StepPlan plan;
+    rc = plan_step(l, next, idx, batch, spec ? score : nullptr, trace, plan);
+    if (rc) return rc;
+    if (trace) {
+        for (int i = 0; i < batch * cf.top_k; ++i) trace->expert_w[i] = w[i];
+        for (int i = 0; i < batch * cf.n_experts; ++i) trace->logits[i] = go->logits[i];
+    }
+
+    // Split the accesses into passes in which no pool buffer is used twice (only possible when more
+    // experts are needed than the layer has slots).  A later pass's copies wait for the earlier pass's kernels.
+    std::vector<std::vector<int>> passes(1);
+    {
+        std::vector<int32_t> used;
+        for (int i = 0; i < (int)plan.access.size(); ++i) {
+            const int32_t buf = plan.access[i].buf;
+            if (std::find(used.begin(), used.end(), buf) != used.end()) { passes.emplace_back(); used.clear(); }
+            used.push_back(buf);
+            passes.back().push_back(i);
+        }
+    }
+    // largest number of tokens routed to one expert decides the kernel variant
+    int max_tok = 1;
+    for (const AccessRec &a : plan.access) {
+        int n = 0;
+        for (int i = 0; i < batch * cf.top_k; ++i) n += (idx[i] == a.expert);
+        max_tok = std::max(max_tok, n);
+    }
+    const int nt = max_tok == 1 ? 1 : (max_tok == 2 ? 2 : 4);
+
+    size_t next_demand = 0;
+    for (size_t p = 0; p < passes.size(); ++p) {
+        if (p > 0) {
+            HIPCHK(hipEventRecord(c->ev_compute, c->compute));
+            HIPCHK(hipStreamWaitEvent(c->copy, c->ev_compute, 0));
+        }
+        for (int i : passes[p])
+            if (plan.access[i].status == MOE_MISS) { rc = issue_copy(c, l, plan.demand[next_demand++]); if (rc) return rc; }
+        if (p + 1 == passes.size() && !plan.victim_needed && passes.size() == 1)
+            for (const CopyOp &op : plan.spec) { rc = issue_copy(c, next, op); if (rc) return rc; }
+        std::vector<FfnEntry> entries;
+        for (int i : passes[p]) {
+            const AccessRec &a = plan.access[i];
+            PoolBuf &pb = c->bufs[a.buf];
+            if (pb.pending) { HIPCHK(hipStreamWaitEvent(c->compute, pb.ready, 0)); pb.pending = false; }
+            FfnEntry en{};
+            en.blob = pb.ptr;
+            for (int q = 0; q < batch * cf.top_k; ++q) {
+                if (idx[q] != a.expert) continue;
+                en.tok[en.n_tok] = q / cf.top_k; en.pair[en.n_tok] = q; en.w[en.n_tok] = w[q];
+                if (++en.n_tok == nt) { entries.push_back(en); en.n_tok = 0; }
+            }
+            if (en.n_tok) entries.push_back(en);
+        }
+        rc = launch_ffn(l, entries, nt);
+        if (rc) return rc;
+    }
+    if (plan.victim_needed || passes.size() > 1) {
+        // a buffer freed during this step may still be read by its kernels: speculative copies wait for them
+        HIPCHK(hipEventRecord(c->ev_compute, c->compute));
+        HIPCHK(hipStreamWaitEvent(c->copy, c->ev_compute, 0));
+        for (const CopyOp &op : plan.spec) { rc = issue_copy(c, next, op); if (rc) return rc; }
+    }
+    const int n = batch * cf.hidden;
+    hipLaunchKernelGGL(k_residual, dim3((n + 255) / 256), dim3(256), 0, c->compute, x_in, c->yacc, x_out, n);
+    HIPCHK(hipGetLastError());
+    return MOE_OK;
+}
+
+extern "C" int32_t moe_layer_prefetch(moe_layer_t *l, const uint16_t *h_dev, int32_t batch, moe_step_trace_t *trace)
+{
+    int32_t rc = check_step_args(l, nullptr, batch);
+    if (rc) return rc;
+    moe_ctx *c = l->ctx;
+    if (c->host_only) return fail(MOE_ESTATE, "moe_layer_prefetch: host-only context");
+    if (!h_dev) return fail(MOE_EINVAL, "moe_layer_prefetch: h_dev is null");
+    if (!all_loaded(l)) return fail(MOE_ESTATE, "moe_layer_prefetch: not every expert of the layer is loaded");
+    if (trace) trace->n_guess = 0;
+    if (l->cfg.prefetch_m <= 0 || c->cfg.n_staging <= 0) return MOE_OK;
+    GateArgs ga{};
+    ga.x = h_dev; ga.wg2 = l->gate_w_dev; ga.out = c->gate_out_dev; ga.eps = 0.0; ga.H = l->cfg.hidden;
+    ga.E2 = l->cfg.n_experts; ga.K = l->cfg.top_k;
+    rc = launch_gate(c, ga, batch);
+    if (rc) return rc;
+    double score[MOE_MAX_EXPERTS] = {0};
+    for (int b = 0; b < batch; ++b)
+        for (int e = 0; e < ga.E2; ++e) score[e] += c->gate_out->spec_p[b * ga.E2 + e];
+    std::vector<int32_t> guess = top_m(score, l->cfg.n_experts, l->cfg.prefetch_m), issued;
+    std::vector<CopyOp> copies;
+    stage_guesses(l->cache, c->pool, l->st, guess, issued, copies);
+    l->st.bytes_spec += (uint64_t)copies.size() * l->lay.total;
+    for (const CopyOp &op : copies) { rc = issue_copy(c, l, op); if (rc) return rc; }
+    if (trace) {
+        trace->n_guess = (int32_t)guess.size();
+        for (size_t i = 0; i < guess.size(); ++i) { trace->guess_expert[i] = guess[i]; trace->guess_issued[i] = issued[i]; }
+        for (int e = 0; e < l->cfg.n_experts; ++e) trace->guess_score[e] = score[e];
+    }
+    return MOE_OK;
+}
+
+extern "C" int32_t moe_stack_step(moe_layer_t *const *layers, int32_t n_layers, const uint16_t *x_in, int32_t batch,
+                                  uint16_t *x_out, moe_step_trace_t *traces)
+{
+    if (!layers || n_layers < 1) return fail(MOE_EINVAL, "moe_stack_step: no layers");
+    for (int i = 0; i < n_layers; ++i)
+        if (!layers[i] || layers[i]->ctx != layers[0]->ctx || layers[i]->cfg.hidden != layers[0]->cfg.hidden)
+            return fail(MOE_EINVAL, "moe_stack_step: layer %d is null, of another context or another width", i);
+    moe_ctx *c = layers[0]->ctx;
+    const uint16_t *cur = x_in;
+    for (int i = 0; i < n_layers; ++i) {
+        uint16_t *dst = (i + 1 == n_layers) ? x_out : c->xbuf[i & 1];
+        int32_t rc = moe_layer_step(layers[i], i + 1 < n_layers ? layers[i + 1] : nullptr, cur, batch, dst, nullptr,
+                                    traces ? traces + i : nullptr);
+        if (rc) return rc;
+        cur = dst;
+    }
+    return MOE_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// state
+// ---------------------------------------------------------------------------------------------
+
+extern "C" int32_t moe_layer_stats(const moe_layer_t *l, moe_stats_t *o)
+{
+    if (!l || !o) return fail(MOE_EINVAL, "moe_layer_stats: null argument");
+    const Counters &s = l->st;
+    *o = {s.steps, s.needed, s.hits, s.prefetch_hits, s.misses, s.evictions, s.spec_issued, s.spec_wasted, s.bytes_demand, s.bytes_spec};
+    return MOE_OK;
+}
+
+extern "C" int32_t moe_layer_cache_state(const moe_layer_t *l, int32_t *slot_expert, uint64_t *slot_stamp, int32_t *staged,
+                                         int32_t *n_staged)
+{
+    if (!l) return fail(MOE_EINVAL, "moe_layer_cache_state: layer is null");
+    for (int s = 0; s < l->cache.k; ++s) {
+        if (slot_expert) slot_expert[s] = l->cache.slot_expert[s];
+        if (slot_stamp) slot_stamp[s] = l->cache.slot_stamp[s];
+    }
+    if (staged)
+        for (size_t i = 0; i < l->cache.staged.size() && i < MOE_MAX_EXPERTS; ++i) staged[i] = l->cache.staged[i].expert;
+    if (n_staged) *n_staged = (int32_t)l->cache.staged.size();
+    return MOE_OK;
+}
+
+extern "C" int32_t moe_layer_reset(moe_layer_t *l)
+{
+    if (!l) return fail(MOE_EINVAL, "moe_layer_reset: layer is null");
+    moe_ctx *c = l->ctx;
+    if (!c->host_only) {
+        HIPCHK(hipStreamSynchronize(c->compute));
+        HIPCHK(hipStreamSynchronize(c->copy));
+    }
+    // return staged buffers to the pool and take back the layer's current slot buffers as its own
+    for (const StagedGuess &g : l->cache.staged) c->pool.free_staging.push_back(g.buf);
+    l->own_bufs = l->cache.slot_buf;
+    for (int32_t b : l->own_bufs) c->bufs[b].pending = false;
+    cache_init(l);
+    if (l->cfg.init_policy == 1)
+        for (int e = 0; e < l->cfg.cache_slots; ++e)
+            if (l->loaded[e] == 7u) { int32_t rc = warm_fill(l, e); if (rc) return rc; }
+    return MOE_OK;
+}
+
+extern "C" int32_t moe_ctx_read_y(moe_ctx_t *c, int32_t batch, int32_t hidden, float *y_host)
+{
+    if (!c || !y_host) return fail(MOE_EINVAL, "moe_ctx_read_y: null argument");
+    if (c->host_only) return fail(MOE_ESTATE, "moe_ctx_read_y: host-only context");
+    if (batch < 1 || batch > c->cfg.max_batch || hidden < 1 || hidden > c->cfg.max_hidden)
+        return fail(MOE_EINVAL, "moe_ctx_read_y: batch or hidden out of range");
+    HIPCHK(hipStreamSynchronize(c->compute));
+    HIPCHK(hipMemcpy(y_host, c->yacc, (size_t)batch * hidden * sizeof(float), hipMemcpyDeviceToHost));
+    return MOE_OK;
+}
+
+extern "C" int32_t moe_layer_set_prefetch(moe_layer_t *l, int32_t m)
+{
+    if (!l || m < 0 || m > MOE_MAX_GUESS) return fail(MOE_EINVAL, "moe_layer_set_prefetch: bad argument");
+    l->cfg.prefetch_m = m;
+    return MOE_OK;
+}
+
+extern "C" int32_t moe_layer_set_flags(moe_layer_t *l, int32_t flags)
+{
+    if (!l || (flags & ~MOE_LAYER_NO_CACHE)) return fail(MOE_EINVAL, "moe_layer_set_flags: bad argument");
+    l->cfg.flags = flags;
+    return MOE_OK;
+}

@@ -1,0 +1,213 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded
+inputs.  Bit-exact: gate input h, routing indices, cache hit/miss/eviction traces, prefetch
+decisions.  Within 2e-2 max-abs / 1e-3 relative RMS: the block output y (fp32, before the residual
+add) and x_out.  The comparison is teacher-forced per (token, layer): the oracle recomputes
+everything from the fp16 x the engine actually consumed."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import workload as W
+from oracle import c_ffn
+from oracle import moe_oracle as O
+from paper_2312_17238_amd import binding as B
+from paper_2312_17238_amd.engine import make_traces
+
+from harness import Model, check_x_out, check_y, oracle_routing, oracle_y
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def run_teacher_forced(model: Model, xs: torch.Tensor, ffn, check_ffn=lambda t, l: True, prefetch=True, b=4,
+                       sim=None):
+    """xs: [T][B][H] fp16 (CPU).  Runs layer by layer, checks every decision, returns (final x per token, sim, errs)."""
+    L, E, K = model.L, model.E, model.K
+    T, Bn, H = xs.shape
+    sim = sim or O.ExpertCacheSim(L, E, model.k, b)
+    dev = model.stack.device
+    xb = [torch.empty(Bn, H, dtype=torch.float16, device=dev) for _ in range(L + 1)]
+    hb = torch.empty(Bn, H, dtype=torch.float16, device=dev)
+    outs, errs = [], []
+    for t in range(T):
+        xb[0].copy_(xs[t])
+        torch.cuda.synchronize()
+        for l in range(L):
+            tr = B.StepTrace()
+            model.stack.step_layer(l, xb[l], xb[l + 1], hb, tr, prefetch=prefetch)
+            model.stack.synchronize()
+            x_np = xb[l].cpu().numpy()
+            routes = oracle_routing(model, l, x_np)
+            h_ref = np.stack([r[0] for r in routes])
+            assert (hb.cpu().numpy().view(np.uint16) == h_ref.view(np.uint16)).all(), f"gate input differs t={t} l={l}"
+            sel = [r[1] for r in routes]
+            assert tr.routing() == sel, f"routing differs t={t} l={l}: {tr.routing()} vs {sel}"
+            w_ref = np.array([r[2] for r in routes])
+            assert np.abs(np.array(tr.weights()) - w_ref).max() < 1e-6
+            z_ref = np.array([r[3] for r in routes])
+            z_gpu = np.array(tr.logits[: Bn * E]).reshape(Bn, E)
+            assert np.abs(z_gpu - z_ref).max() <= 1e-12 * max(1.0, np.abs(z_ref).max())
+            guess = None
+            if prefetch and l + 1 < L and model.m > 0:
+                guess = O.prefetch_guess(O.prefetch_scores(model.gate_np(l + 1), h_ref), model.m)
+            acc, dec = sim.step(l, sel, guess)
+            assert tr.accesses() == [(a.expert, a.status, a.slot, a.victim) for a in acc], f"cache trace differs t={t} l={l}"
+            assert tr.guesses() == [(e, i) for e, i in dec], f"prefetch decisions differ t={t} l={l}"
+            if check_ffn(t, l):
+                y_gpu = model.stack.read_y(Bn, H)
+                x_out = xb[l + 1].cpu().numpy()
+                for bb in range(Bn):
+                    h, idx, w, _ = routes[bb]
+                    y_ref = oracle_y(model, l, h, idx, w, ffn)
+                    errs.append(check_y(y_gpu[bb], y_ref, f"y t={t} l={l} b={bb}"))
+                    check_x_out(x_out[bb], x_np[bb], y_ref, f"x_out t={t} l={l} b={bb}")
+        outs.append(xb[L].cpu().numpy().copy())
+    return outs, sim, errs
+
+
+def test_tiny_layer_every_token():
+    """H=256, F=512, 8 experts top-2, 4-bit g64, LRU k=2, 64 i.i.d. tokens, every token checked."""
+    c = W.CONFIGS["tiny"]
+    say("tiny: build")
+    model = Model(1, c.hidden, c.ffn, c.n_experts, c.top_k, None, c.cache_slots, 0, 0.0, seed=c.seed)
+    xs = W.hidden_iid(c.seed, c.tokens, 1, c.hidden)
+    say("tiny: run")
+    _, sim, errs = run_teacher_forced(model, xs, O.expert_ffn)
+    st = model.stack.stats()[0]
+    assert st["hits"] == sim.stats[0].hits and st["misses"] == sim.stats[0].misses == st["bytes_h2d_demand"] // model.stack.blob_bytes[0]
+    assert st["needed"] == 2 * c.tokens
+    say(f"tiny: max abs {max(e[0] for e in errs):.2e} max rel-rms {max(e[1] for e in errs):.2e} hits {st['hits']}")
+    model.close()
+
+
+def test_tiny_layer_all_resident_control():
+    """Same layer with k = E: after the 8 compulsory misses nothing is ever copied again."""
+    c = W.CONFIGS["tiny"]
+    model = Model(1, c.hidden, c.ffn, c.n_experts, c.top_k, None, c.n_experts, 0, 0.0, seed=c.seed)
+    xs = W.hidden_iid(c.seed, c.tokens, 1, c.hidden)
+    run_teacher_forced(model, xs, O.expert_ffn)
+    st = model.stack.stats()[0]
+    assert st["misses"] == 8 and st["evictions"] == 0 and st["hits"] == 2 * c.tokens - 8
+    model.close()
+
+
+@pytest.mark.parametrize("k,m,Bn,T", [(2, 2, 1, 40), (4, 1, 1, 24), (4, 2, 4, 12), (4, 2, 16, 8), (2, 2, 3, 10)])
+def test_small_stack_with_prefetch(k, m, Bn, T):
+    """4 layers, RMSNorm, residual, LRU k, speculative prefetch of m, batch Bn (Bn=16 with k=4 needs
+    more experts than slots, so a step runs in several passes)."""
+    L, H, F = 4, 256, 512
+    say(f"small stack k={k} m={m} B={Bn}: build")
+    model = Model(L, H, F, 8, 2, None, k, m, 1e-5, max_batch=Bn, seed=3)
+    xs = W.hidden_ar1(3, T, Bn, H)
+    say("run")
+    outs, sim, errs = run_teacher_forced(model, xs, O.expert_ffn)
+    tot = model.stack.total_stats()
+    assert tot["prefetch_hits"] == sum(s.prefetch_hits for s in sim.stats)
+    assert tot["spec_issued"] == sum(s.spec_issued for s in sim.stats) > 0
+    assert tot["spec_wasted"] == sum(s.spec_wasted for s in sim.stats)
+    say(f"  recall {(tot['hits'] + tot['prefetch_hits']) / tot['needed']:.3f} prefetch hits {tot['prefetch_hits']} "
+        f"max rel-rms {max(e[1] for e in errs):.2e}")
+    # the same tokens through the asynchronous whole-stack entry point, after a reset: same traces,
+    # bit-identical outputs (Sec. 3.2: prefetching changes no prediction; here also no race changes one)
+    model.stack.reset()
+    dev = model.stack.device
+    x_in = torch.empty(Bn, H, dtype=torch.float16, device=dev)
+    x_out = torch.empty(Bn, H, dtype=torch.float16, device=dev)
+    sim2 = O.ExpertCacheSim(L, 8, k, 4)
+    for t in range(T):
+        x_in.copy_(xs[t])
+        torch.cuda.synchronize()
+        traces = make_traces(L)
+        model.stack.step(x_in, x_out, traces)
+        model.stack.synchronize()
+        assert (x_out.cpu().numpy().view(np.uint16) == outs[t].view(np.uint16)).all(), f"async stack differs at token {t}"
+    # and with prefetching off: identical outputs, identical cache contents, only labels and bytes differ
+    model.stack.reset()
+    model.stack.set_prefetch(0)
+    for t in range(T):
+        x_in.copy_(xs[t])
+        torch.cuda.synchronize()
+        model.stack.step(x_in, x_out, None)
+        model.stack.synchronize()
+        assert (x_out.cpu().numpy().view(np.uint16) == outs[t].view(np.uint16)).all(), f"prefetch-off differs at token {t}"
+    off = model.stack.total_stats()
+    assert off["prefetch_hits"] == 0 and off["spec_issued"] == 0
+    assert off["hits"] == tot["hits"] and off["misses"] == tot["misses"] + tot["prefetch_hits"]
+    model.close()
+
+
+def test_standalone_prefetch_matches_fused_prefetch():
+    """moe_layer_prefetch(layer l+1, h_l) takes the decisions step(l, next=l+1) takes."""
+    L, H, F = 2, 256, 512
+    a = Model(L, H, F, 8, 2, None, 2, 2, 1e-5, seed=5)
+    b = Model(L, H, F, 8, 2, None, 2, 2, 1e-5, seed=5)
+    xs = W.hidden_ar1(5, 12, 1, H)
+    dev = a.stack.device
+    x0 = torch.empty(1, H, dtype=torch.float16, device=dev)
+    x1 = torch.empty_like(x0); x2 = torch.empty_like(x0); h = torch.empty_like(x0)
+    for t in range(xs.shape[0]):
+        x0.copy_(xs[t]); torch.cuda.synchronize()
+        ta, tb, tp = B.StepTrace(), B.StepTrace(), B.StepTrace()
+        a.stack.step_layer(0, x0, x1, None, ta, prefetch=True)
+        b.stack.step_layer(0, x0, x1, h, tb, prefetch=False)
+        B.moe_layer_prefetch(b.stack.layers[1], h.data_ptr(), 1, tp)
+        assert ta.guesses() == tp.guesses() and tb.n_guess == 0
+        t1a, t1b = B.StepTrace(), B.StepTrace()
+        a.stack.step_layer(1, x1, x2, None, t1a)
+        a.stack.synchronize(); ya = x2.cpu().numpy().copy()
+        b.stack.step_layer(1, x1, x2, None, t1b)
+        b.stack.synchronize()
+        assert t1a.accesses() == t1b.accesses() and (ya.view(np.uint16) == x2.cpu().numpy().view(np.uint16)).all()
+    assert a.stack.total_stats() == b.stack.total_stats()
+    a.close(); b.close()
+
+
+def test_gate_special_values_and_ties():
+    """Equal logits everywhere (zero gate): experts 0 and 1 with weights 1/2; zero input: y = 0."""
+    H, F = 256, 512
+    from paper_2312_17238_amd.engine import Stack, layer_config
+    st = Stack([layer_config(H, F, 8, 2, 4, 64, 2, 0, 1e-5)], [torch.zeros(8, H)], None)
+    for e in range(8):
+        for mtx, (q, s, z) in enumerate(W.quantized_expert(7, 0, e, H, F, 4, 64)):
+            st.load_expert(0, e, mtx, q, s, z)
+    dev = st.device
+    x = torch.zeros(1, H, dtype=torch.float16, device=dev)
+    out = torch.empty_like(x)
+    tr = B.StepTrace()
+    st.step_layer(0, x, out, None, tr)
+    st.synchronize()
+    assert tr.routing() == [[0, 1]] and tr.weights() == [[0.5, 0.5]]
+    assert (out.cpu().numpy() == 0).all() and (st.read_y(1, H) == 0).all()
+    st.close()
+
+
+def test_mixtral_layer_all_resident():
+    """One Mixtral-shaped layer (H=4096, F=14336, 8 experts, 4-bit g64), all experts resident, AR(1) tokens."""
+    c = W.CONFIGS["mixtral_layer"]
+    say("mixtral layer: build (8 experts of 176M weights)")
+    model = Model(1, c.hidden, c.ffn, c.n_experts, c.top_k, None, c.cache_slots, 0, 0.0, seed=c.seed)
+    xs = W.hidden_ar1(c.seed, 6, 1, c.hidden)
+    say("mixtral layer: run + C oracle")
+    _, sim, errs = run_teacher_forced(model, xs, c_ffn.expert_ffn)
+    say(f"mixtral layer: max abs {max(e[0] for e in errs):.2e} max rel-rms {max(e[1] for e in errs):.2e}")
+    st = model.stack.stats()[0]
+    assert st["evictions"] == 0 and st["misses"] <= 8
+    model.close()
+
+
+def test_mixtral_layer_small_cache_batch4():
+    """The same shape with k=2 (99 MB demand copies in flight while kernels wait on their events) and batch 4."""
+    c = W.CONFIGS["mixtral_layer"]
+    say("mixtral layer k=2 B=4: build")
+    model = Model(1, c.hidden, c.ffn, c.n_experts, c.top_k, None, 4, 0, 0.0, max_batch=4, seed=c.seed)
+    xs = W.hidden_ar1(c.seed, 3, 4, c.hidden)
+    say("run")
+    _, sim, errs = run_teacher_forced(model, xs, c_ffn.expert_ffn, check_ffn=lambda t, l: True)
+    say(f"mixtral layer k=4 B=4: max rel-rms {max(e[1] for e in errs):.2e}")
+    model.close()

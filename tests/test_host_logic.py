@@ -1,0 +1,175 @@
+"""CPU-only checks of the library's host side: the shared object loads without a GPU and exports
+every symbol the header declares; the cache/prefetch bookkeeping (in a host-only context) equals
+the oracle's simulator decision for decision; the packed blob reads back every code; every
+documented error is reported as a status code, not a crash."""
+import os
+import re
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import moe_oracle as O
+from paper_2312_17238_amd import binding as B
+from paper_2312_17238_amd.engine import Stack, layer_config
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    with open(os.path.join(ROOT, "include", "moe_offload.h")) as f:
+        src = re.sub(r"/\*.*?\*/", "", f.read(), flags=re.S)
+    declared = set(re.findall(r"\b(moe_[a-z0-9_]+)\s*\(", src))
+    assert declared, "no declarations found"
+    lib = B.lib()
+    for name in sorted(declared):
+        assert hasattr(lib, name), f"{name} declared in the header but not exported"
+    assert declared == set(B.EXPORTS)
+
+
+def test_blob_sizes_match_the_format_arithmetic():
+    # 4-bit g64: H*F*3 codes at 4 bits + one fp16 (scale, zero) pair per 64 codes
+    P = 3 * 4096 * 14336
+    assert B.moe_expert_blob_bytes(4096, 14336, 4, 64) == P // 2 + P // 64 * 4 == 99_090_432
+    assert B.moe_expert_blob_bytes(256, 512, 4, 64) == 221_184
+    assert B.moe_expert_blob_bytes(4096, 14336, 5, 64) == 0
+    assert B.moe_expert_blob_bytes(100, 512, 4, 64) == 0
+
+
+def make_stack(L, E, k, m, b, H=64, F=64, flags=0, init_policy=0, max_batch=1):
+    cfgs = [layer_config(H, F, E, 2, 4, 64, k, m, 0.0, init_policy, flags) for _ in range(L)]
+    return Stack(cfgs, [torch.zeros(E, H) for _ in range(L)], n_staging=b, max_batch=max_batch, host_only=True)
+
+
+@pytest.mark.parametrize("L,E,k,m,b,B_", [(4, 8, 2, 2, 4, 1), (3, 8, 4, 2, 4, 1), (5, 8, 2, 1, 2, 1), (2, 6, 3, 2, 1, 1),
+                                          (3, 8, 4, 2, 4, 16), (3, 8, 4, 2, 4, 4), (2, 8, 8, 2, 4, 1)])
+def test_bookkeeping_equals_oracle_simulator(L, E, k, m, b, B_):
+    rng = np.random.default_rng(L * 100 + k * 10 + B_)
+    st = make_stack(L, E, k, m, b, max_batch=B_)
+    sim = O.ExpertCacheSim(L, E, k, b)
+    tr = B.StepTrace()
+    for _ in range(120):
+        for l in range(L):
+            sel = [[int(e) for e in rng.choice(E, size=2, replace=False)] for _ in range(B_)]
+            score = rng.dirichlet(np.ones(E)) * B_
+            if rng.random() < 0.2:                       # exact ties in the guess scores
+                score[rng.integers(E)] = score[rng.integers(E)]
+            nxt = st.layers[l + 1] if l + 1 < L else None
+            B.moe_layer_resolve(st.layers[l], nxt, [e for t in sel for e in t], B_, list(score) if nxt else None, tr)
+            guess = O.prefetch_guess(score, m) if nxt else None
+            acc, dec = sim.step(l, sel, guess)
+            assert tr.accesses() == [(a.expert, a.status, a.slot, a.victim) for a in acc]
+            assert tr.guesses() == [(e, i) for e, i in dec]
+            assert tr.routing() == sel
+            for ll in range(L):
+                se, ss, staged = B.moe_layer_cache_state(st.layers[ll], k)
+                assert se == sim.slot_expert[ll] and ss == sim.slot_stamp[ll] and staged == sim.staged[ll]
+    for l in range(L):
+        s, o = B.moe_layer_stats(st.layers[l]).as_dict(), sim.stats[l]
+        for name in ("steps", "needed", "hits", "prefetch_hits", "misses", "evictions", "spec_issued", "spec_wasted"):
+            assert s[name] == getattr(o, name), name
+        blob = B.moe_expert_blob_bytes(64, 64, 4, 64)
+        assert s["bytes_h2d_demand"] == o.misses * blob and s["bytes_h2d_spec"] == o.spec_issued * blob
+    st.close()
+
+
+def test_warm_start_reset_and_ablation_flags():
+    st = make_stack(2, 8, 3, 2, 4, init_policy=1)
+    lay = st.layers[0]
+    ones = np.zeros((64, 64), np.uint8), np.ones((64, 1), np.float16), np.zeros((64, 1), np.float16)
+    for e in range(8):
+        for mtx in range(3):
+            B.moe_layer_load_expert(lay, e, mtx, *[a.ctypes.data for a in ones])
+    assert B.moe_layer_cache_state(lay, 3)[0] == [0, 1, 2]
+    tr = B.StepTrace()
+    B.moe_layer_resolve(lay, None, [1, 6], 1, None, tr)
+    assert tr.accesses() == [(1, B.MOE_HIT, 1, -1), (6, B.MOE_MISS, 0, 0)]
+    B.moe_layer_reset(lay)
+    assert B.moe_layer_cache_state(lay, 3)[0] == [0, 1, 2] and B.moe_layer_stats(lay).steps == 0
+    # "without LRU cache": nothing is remembered between steps
+    B.moe_layer_set_flags(lay, B.MOE_LAYER_NO_CACHE)
+    for _ in range(3):
+        B.moe_layer_resolve(lay, None, [1, 6], 1, None, tr)
+        assert [a[1] for a in tr.accesses()] == [B.MOE_MISS, B.MOE_MISS]
+    # "without pre-loading": m = 0 stages nothing
+    B.moe_layer_set_flags(lay, 0)
+    B.moe_layer_set_prefetch(st.layers[1], 0)
+    B.moe_layer_resolve(lay, st.layers[1], [1, 6], 1, [0.5, 0.5, 0, 0, 0, 0, 0, 0], tr)
+    assert tr.n_guess == 0 and B.moe_layer_stats(st.layers[1]).spec_issued == 0
+    st.close()
+
+
+@pytest.mark.parametrize("group", [32, 64, 128])
+def test_packed_blob_reads_back_every_code(group):
+    rng = np.random.default_rng(group)
+    H, F, E = 128, 256, 2
+    st = Stack([layer_config(H, F, E, 2, 4, group, 2)], [torch.zeros(E, H)], host_only=True)
+    lay = st.layers[0]
+    mats = {}
+    for e in range(E):
+        for mtx, (r, c) in enumerate(((F, H), (F, H), (H, F))):
+            q = rng.integers(0, 16, size=(r, c)).astype(np.uint8)
+            if e == 0 and mtx == 0:                       # exhaustive code patterns in the first row
+                q[0, :] = np.arange(c) % 16
+                q[1, :] = (np.arange(c) // 16) % 16
+            s = rng.integers(0, 1 << 16, size=(r, c // group)).astype(np.uint16)
+            z = rng.integers(0, 1 << 16, size=(r, c // group)).astype(np.uint16)
+            mats[(e, mtx)] = (q, s, z)
+            B.moe_layer_load_expert(lay, e, mtx, q.ctypes.data, s.ctypes.data, z.ctypes.data)
+    for (e, mtx), (q, s, z) in mats.items():
+        rows = [0, 1, q.shape[0] - 1] + [int(x) for x in rng.integers(0, q.shape[0], 4)]
+        for r in rows:
+            for c in range(q.shape[1]):
+                assert B.moe_layer_peek_weight(lay, e, mtx, r, c) == (q[r, c], s[r, c // group], z[r, c // group])
+    # total bytes: every expert's blob is filled completely and the blobs do not overlap
+    assert B.moe_layer_host_bytes(st.cfgs[0]) == E * B.moe_expert_blob_bytes(H, F, 4, group)
+    st.close()
+
+
+def expect(code, fn, *args):
+    with pytest.raises(B.MoeError) as ei:
+        fn(*args)
+    assert ei.value.code == code, ei.value
+
+
+def test_error_codes():
+    cc = B.CtxConfig(4, 1, 64, 64, 2, B.MOE_CTX_HOST_ONLY, 1 << 16)
+    expect(B.MOE_EINVAL, B.moe_ctx_create, B.CtxConfig(4, 0, 64, 64, 2, 1, 1 << 16), None, 0, None, None)
+    expect(B.MOE_EINVAL, B.moe_ctx_create, B.CtxConfig(4, 1, 64, 64, 9, 1, 1 << 16), None, 0, None, None)
+    # a GPU context without an arena is rejected before any HIP call
+    expect(B.MOE_EINVAL, B.moe_ctx_create, B.CtxConfig(4, 1, 64, 64, 2, 0, 1 << 16), None, 0, None, None)
+    ctx = B.moe_ctx_create(cc, None, 0, None, None)
+    gw = np.zeros((8, 64), np.float32)
+    raw = np.zeros((1 << 20) + 64, np.uint8)
+    host = raw[(-raw.ctypes.data) % 64:][: 1 << 20]      # 64-byte aligned view
+    mk =lambda **kw: layer_config(**{**dict(hidden=64, ffn=64, n_experts=8, top_k=2, bits=4, group=64,
+                                             cache_slots=2), **kw})
+    for bad in (mk(cache_slots=1), mk(cache_slots=9), mk(top_k=5), mk(n_experts=17), mk(bits=5), mk(group=48),
+                mk(hidden=96), mk(prefetch_m=5), mk(rms_eps=-1.0), mk(init_policy=2), mk(hidden=128),
+                mk(bits=3), mk(bits=2, group=16)):
+        expect(B.MOE_EINVAL, B.moe_layer_create, ctx, bad, gw.ctypes.data, None, None, host.ctypes.data)
+    expect(B.MOE_EINVAL, B.moe_layer_create, ctx, mk(), None, None, None, host.ctypes.data)
+    expect(B.MOE_EINVAL, B.moe_layer_create, ctx, mk(), gw.ctypes.data, None, None, None)
+    big = B.moe_ctx_create(B.CtxConfig(4, 2, 64, 64, 2, 1, 1 << 10), None, 0, None, None)
+    expect(B.MOE_EINVAL, B.moe_layer_create, big, mk(), gw.ctypes.data, None, None, host.ctypes.data)  # blob > buffer
+    lay = B.moe_layer_create(ctx, mk(), gw.ctypes.data, None, None, host.ctypes.data)
+    q = np.zeros((64, 64), np.uint8); s = np.ones((64, 1), np.float16); z = np.zeros((64, 1), np.float16)
+    expect(B.MOE_EINVAL, B.moe_layer_load_expert, lay, 8, 0, q.ctypes.data, s.ctypes.data, z.ctypes.data)
+    expect(B.MOE_EINVAL, B.moe_layer_load_expert, lay, 0, 3, q.ctypes.data, s.ctypes.data, z.ctypes.data)
+    expect(B.MOE_EINVAL, B.moe_layer_load_expert, lay, 0, 0, None, s.ctypes.data, z.ctypes.data)
+    q[3, 3] = 16
+    expect(B.MOE_EINVAL, B.moe_layer_load_expert, lay, 0, 0, q.ctypes.data, s.ctypes.data, z.ctypes.data)
+    expect(B.MOE_ESTATE, B.moe_layer_peek_weight, lay, 0, 0, 0, 0)
+    expect(B.MOE_EINVAL, B.moe_layer_peek_weight, lay, 0, 0, 64, 0)
+    # stepping needs a GPU context; batch limits and routing indices are validated
+    expect(B.MOE_ESTATE, B.moe_layer_step, lay, None, 1, 1, 1)
+    expect(B.MOE_EINVAL, B.moe_layer_step, lay, None, 1, 2, 1)
+    expect(B.MOE_ESTATE, B.moe_layer_prefetch, lay, 1, 1)
+    expect(B.MOE_EINVAL, B.moe_layer_resolve, lay, None, [0, 8], 1)
+    expect(B.MOE_EINVAL, B.moe_layer_resolve, lay, None, [0, 1], 0)
+    expect(B.MOE_EINVAL, B.moe_layer_set_prefetch, lay, 9)
+    expect(B.MOE_EINVAL, B.moe_layer_set_flags, lay, 8)
+    assert "flags" in B.lib().moe_last_error().decode() or B.lib().moe_last_error()
+    B.moe_layer_destroy(lay)
+    B.moe_ctx_destroy(ctx)
+    B.moe_ctx_destroy(big)
