@@ -220,6 +220,15 @@ int32_t moe_layer_set_flags(moe_layer_t *layer, int32_t flags);
  * sum before the residual add) to host memory.  Waits for the compute stream. */
 int32_t moe_ctx_read_y(moe_ctx_t *ctx, int32_t batch, int32_t hidden, float *y_host);
 
+/* Optional timing of the engine's own launches, with HIP events recorded on the stream each launch is
+ * enqueued on (gate, w1/w3 kernel, w2 kernel: compute stream; expert copies: copy stream).
+ * `bytes` are algorithmic: each distinct expert a launch touches counts its packed w1+w3 (or w2) once;
+ * a copy counts the blob.  enable(1) clears the accumulators; read waits for both streams. */
+typedef struct { uint64_t launches; uint64_t bytes; double total_ms; } moe_profile_entry_t;
+typedef struct { moe_profile_entry_t gate, w13, w2, copy; } moe_profile_t;
+int32_t moe_ctx_profile_enable(moe_ctx_t *ctx, int32_t on);
+int32_t moe_ctx_profile_read(moe_ctx_t *ctx, moe_profile_t *out);
+
 const char *moe_last_error(void);
 int32_t moe_last_hip_error(void);
 

@@ -24,7 +24,7 @@ EXPORTS = [
     "moe_ctx_create", "moe_ctx_destroy", "moe_layer_create", "moe_layer_destroy",
     "moe_layer_load_expert", "moe_layer_peek_weight", "moe_layer_step", "moe_layer_prefetch",
     "moe_stack_step", "moe_layer_resolve", "moe_layer_stats", "moe_layer_cache_state",
-    "moe_layer_reset", "moe_ctx_read_y", "moe_layer_set_prefetch", "moe_layer_set_flags", "moe_last_error", "moe_last_hip_error",
+    "moe_layer_reset", "moe_ctx_read_y", "moe_ctx_profile_enable", "moe_ctx_profile_read", "moe_layer_set_prefetch", "moe_layer_set_flags", "moe_last_error", "moe_last_hip_error",
 ]
 
 
@@ -79,6 +79,18 @@ class Stats(C.Structure):
         return {n: int(getattr(self, n)) for n, _ in self._fields_}
 
 
+class ProfileEntry(C.Structure):
+    _fields_ = [("launches", C.c_uint64), ("bytes", C.c_uint64), ("total_ms", C.c_double)]
+
+
+class Profile(C.Structure):
+    _fields_ = [("gate", ProfileEntry), ("w13", ProfileEntry), ("w2", ProfileEntry), ("copy", ProfileEntry)]
+
+    def as_dict(self):
+        return {k: {"launches": int(getattr(self, k).launches), "bytes": int(getattr(self, k).bytes),
+                    "total_ms": float(getattr(self, k).total_ms)} for k, _ in self._fields_}
+
+
 class MoeError(RuntimeError):
     def __init__(self, code: int, msg: str):
         super().__init__(f"moe_offload error {code}: {msg}")
@@ -121,6 +133,8 @@ def lib() -> C.CDLL:
     L.moe_layer_cache_state.argtypes = [vp, C.POINTER(i32), C.POINTER(u64), C.POINTER(i32), C.POINTER(i32)]
     L.moe_layer_reset.argtypes = [vp]
     L.moe_ctx_read_y.argtypes = [vp, i32, i32, vp]
+    L.moe_ctx_profile_enable.argtypes = [vp, i32]
+    L.moe_ctx_profile_read.argtypes = [vp, C.POINTER(Profile)]
     L.moe_layer_set_prefetch.argtypes = [vp, i32]
     L.moe_layer_set_flags.argtypes = [vp, i32]
     L.moe_last_error.restype = C.c_char_p
@@ -230,6 +244,16 @@ def moe_layer_reset(layer) -> None:
 
 def moe_ctx_read_y(ctx, batch: int, hidden: int, y_host: int) -> None:
     check(lib().moe_ctx_read_y(ctx, batch, hidden, y_host))
+
+
+def moe_ctx_profile_enable(ctx, on: bool) -> None:
+    check(lib().moe_ctx_profile_enable(ctx, 1 if on else 0))
+
+
+def moe_ctx_profile_read(ctx) -> Profile:
+    p = Profile()
+    check(lib().moe_ctx_profile_read(ctx, C.byref(p)))
+    return p
 
 
 def moe_layer_set_prefetch(layer, m: int) -> None:

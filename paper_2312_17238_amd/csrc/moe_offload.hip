@@ -64,8 +64,25 @@ struct PoolBuf {
     bool pending = false;         // a copy was recorded that the compute stream has not yet waited on
 };
 
+// Optional timing of the engine's own launches with HIP events recorded on the stream each launch goes to.
+enum { PROF_GATE = 0, PROF_W13 = 1, PROF_W2 = 2, PROF_COPY = 3, PROF_KINDS = 4 };
+
+struct ProfKind {
+    std::vector<hipEvent_t> start, stop;   // created on demand, reused after a drain
+    size_t used = 0;
+    uint64_t launches = 0, bytes = 0;
+    double ms = 0.0;
+};
+
+struct Profiler {
+    bool on = false;
+    ProfKind kind[PROF_KINDS];
+    static constexpr size_t RING = 20000;
+};
+
 struct moe_ctx {
     moe_ctx_config_t cfg{};
+    Profiler prof;
     bool host_only = false;
     hipStream_t compute = nullptr, copy = nullptr;
     uint64_t buf_bytes = 0;
@@ -229,6 +246,10 @@ extern "C" int32_t moe_ctx_destroy(moe_ctx_t *c)
         if (c->copy) (void)hipStreamSynchronize(c->copy);
         for (PoolBuf &b : c->bufs)
             if (b.ready) (void)hipEventDestroy(b.ready);
+        for (int k = 0; k < PROF_KINDS; ++k) {
+            for (hipEvent_t e : c->prof.kind[k].start) (void)hipEventDestroy(e);
+            for (hipEvent_t e : c->prof.kind[k].stop) (void)hipEventDestroy(e);
+        }
         if (c->ev_gate) (void)hipEventDestroy(c->ev_gate);
         if (c->ev_compute) (void)hipEventDestroy(c->ev_compute);
         if (c->gate_out) (void)hipHostFree(c->gate_out);
@@ -398,6 +419,85 @@ extern "C" int32_t moe_layer_peek_weight(const moe_layer_t *l, int32_t expert, i
 }
 
 // ---------------------------------------------------------------------------------------------
+// profiling
+// ---------------------------------------------------------------------------------------------
+
+static int32_t prof_drain(moe_ctx *c, int k)
+{
+    ProfKind &p = c->prof.kind[k];
+    if (!p.used) return MOE_OK;
+    HIPCHK(hipEventSynchronize(p.stop[p.used - 1]));
+    for (size_t i = 0; i < p.used; ++i) {
+        float ms = 0.f;
+        HIPCHK(hipEventElapsedTime(&ms, p.start[i], p.stop[i]));
+        p.ms += ms;
+    }
+    p.used = 0;
+    return MOE_OK;
+}
+
+// Record the start event of a launch of kind k on stream s; *slot receives the ring index (or -1 when off).
+static int32_t prof_begin(moe_ctx *c, int k, hipStream_t s, uint64_t bytes, int *slot)
+{
+    *slot = -1;
+    if (!c->prof.on) return MOE_OK;
+    ProfKind &p = c->prof.kind[k];
+    if (p.used == Profiler::RING) { int32_t rc = prof_drain(c, k); if (rc) return rc; }
+    if (p.used == p.start.size()) {
+        hipEvent_t a, b;
+        HIPCHK(hipEventCreate(&a));
+        HIPCHK(hipEventCreate(&b));
+        p.start.push_back(a);
+        p.stop.push_back(b);
+    }
+    HIPCHK(hipEventRecord(p.start[p.used], s));
+    *slot = (int)p.used;
+    p.launches++;
+    p.bytes += bytes;
+    return MOE_OK;
+}
+
+static int32_t prof_end(moe_ctx *c, int k, hipStream_t s, int slot)
+{
+    if (slot < 0) return MOE_OK;
+    ProfKind &p = c->prof.kind[k];
+    HIPCHK(hipEventRecord(p.stop[slot], s));
+    p.used = (size_t)slot + 1;
+    return MOE_OK;
+}
+
+extern "C" int32_t moe_ctx_profile_enable(moe_ctx_t *c, int32_t on)
+{
+    if (!c) return fail(MOE_EINVAL, "moe_ctx_profile_enable: ctx is null");
+    if (c->host_only) return fail(MOE_ESTATE, "moe_ctx_profile_enable: host-only context");
+    HIPCHK(hipStreamSynchronize(c->compute));
+    HIPCHK(hipStreamSynchronize(c->copy));
+    for (int k = 0; k < PROF_KINDS; ++k) {
+        ProfKind &p = c->prof.kind[k];
+        p.used = 0; p.launches = 0; p.bytes = 0; p.ms = 0.0;
+    }
+    c->prof.on = on != 0;
+    return MOE_OK;
+}
+
+extern "C" int32_t moe_ctx_profile_read(moe_ctx_t *c, moe_profile_t *out)
+{
+    if (!c || !out) return fail(MOE_EINVAL, "moe_ctx_profile_read: null argument");
+    if (c->host_only) return fail(MOE_ESTATE, "moe_ctx_profile_read: host-only context");
+    HIPCHK(hipStreamSynchronize(c->compute));
+    HIPCHK(hipStreamSynchronize(c->copy));
+    moe_profile_entry_t *dst[PROF_KINDS] = {&out->gate, &out->w13, &out->w2, &out->copy};
+    for (int k = 0; k < PROF_KINDS; ++k) {
+        int32_t rc = prof_drain(c, k);
+        if (rc) return rc;
+        dst[k]->launches = c->prof.kind[k].launches;
+        dst[k]->bytes = c->prof.kind[k].bytes;
+        dst[k]->total_ms = c->prof.kind[k].ms;
+    }
+    return MOE_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
 // bookkeeping of one step (host only)
 // ---------------------------------------------------------------------------------------------
 
@@ -446,8 +546,13 @@ static int32_t plan_step(moe_layer *l, moe_layer *next, const int32_t *idx, int3
 static int32_t issue_copy(moe_ctx *c, const moe_layer *owner, const CopyOp &op)
 {
     PoolBuf &b = c->bufs[op.buf];
+    int ps;
+    int32_t rc = prof_begin(c, PROF_COPY, c->copy, owner->lay.total, &ps);
+    if (rc) return rc;
     HIPCHK(hipMemcpyAsync(b.ptr, owner->host_blobs + (uint64_t)op.expert * owner->lay.total, owner->lay.total,
                           hipMemcpyHostToDevice, c->copy));
+    rc = prof_end(c, PROF_COPY, c->copy, ps);
+    if (rc) return rc;
     HIPCHK(hipEventRecord(b.ready, c->copy));
     b.pending = true;
     return MOE_OK;
@@ -508,8 +613,13 @@ static int32_t launch_gate(moe_ctx *c, const GateArgs &ga, int32_t batch)
 {
     c->gate_out->done = 0;
     std::atomic_thread_fence(std::memory_order_release);
+    int ps;
+    int32_t rc = prof_begin(c, PROF_GATE, c->compute, 0, &ps);
+    if (rc) return rc;
     hipLaunchKernelGGL(k_gate, dim3(batch), dim3(GATE_THREADS), (size_t)ga.H * 2, c->compute, ga);
     HIPCHK(hipGetLastError());
+    rc = prof_end(c, PROF_GATE, c->compute, ps);
+    if (rc) return rc;
     if (!c->sync_wait) HIPCHK(hipEventRecord(c->ev_gate, c->compute));
     return wait_gate(c, (uint32_t)batch);
 }
@@ -543,16 +653,32 @@ static int32_t launch_ffn(moe_layer *l, const std::vector<FfnEntry> &entries, in
         A.rows_per_block = c->w2_rows;
         int bx = std::max(1, std::min((b.ffn + W13_WAVES - 1) / W13_WAVES, c->w13_blocks / n));
         const dim3 g13(bx, n);
+        // algorithmic bytes: every distinct expert of the launch is read once
+        uint64_t n_distinct = 0;
+        for (int i = 0; i < n; ++i) {
+            bool seen = false;
+            for (int j = 0; j < i; ++j) seen |= (A.e[j].blob == A.e[i].blob);
+            n_distinct += !seen;
+        }
+        int ps;
+        int32_t rc = prof_begin(c, PROF_W13, c->compute, n_distinct * 2 * (uint64_t)b.ffn * b.m13.row_stride, &ps);
+        if (rc) return rc;
         if (kch == 1) launch_w13<1>(nt, g13, c->compute, A);
         else if (kch == 2) launch_w13<2>(nt, g13, c->compute, A);
         else launch_w13<4>(nt, g13, c->compute, A);
         HIPCHK(hipGetLastError());
+        rc = prof_end(c, PROF_W13, c->compute, ps);
+        if (rc) return rc;
+        rc = prof_begin(c, PROF_W2, c->compute, n_distinct * (uint64_t)b.hidden * b.m2.row_stride, &ps);
+        if (rc) return rc;
         const dim3 g2((b.hidden + A.rows_per_block - 1) / A.rows_per_block, n), blk(cs * WAVE);
         const size_t shm = (size_t)A.rows_per_block * nt * cs * sizeof(float);
         if (nt == 1) hipLaunchKernelGGL((k_w2_q4<1>), g2, blk, shm, c->compute, A);
         else if (nt == 2) hipLaunchKernelGGL((k_w2_q4<2>), g2, blk, shm, c->compute, A);
         else hipLaunchKernelGGL((k_w2_q4<4>), g2, blk, shm, c->compute, A);
         HIPCHK(hipGetLastError());
+        rc = prof_end(c, PROF_W2, c->compute, ps);
+        if (rc) return rc;
     }
     return MOE_OK;
 }
