@@ -229,6 +229,21 @@ typedef struct { moe_profile_entry_t gate, w13, w2, copy; } moe_profile_t;
 int32_t moe_ctx_profile_enable(moe_ctx_t *ctx, int32_t on);
 int32_t moe_ctx_profile_read(moe_ctx_t *ctx, moe_profile_t *out);
 
+/* Launch-shape tuning knobs (defaults are the measured best for Mixtral shapes on MI355X):
+ *   "w13_blocks" total thread blocks of the w1/w3 kernel;  "w13_ring" rows a wave keeps in flight (1, 2, 4);
+ *   "w2_form" 1: w2 kernel with whole rows per wave (used when at most 2 tokens share an expert), 0: always the
+ *   column-split form;  "w2_blocks" total thread blocks of the row form;  "w2_ring" rows a wave keeps in flight;
+ *   "w2_rows" output rows per block of the column-split form;
+ *   "sync_wait" 1: wait for the gate result with hipStreamSynchronize instead of polling host-mapped memory. */
+int32_t moe_ctx_set_option(moe_ctx_t *ctx, const char *name, int32_t value);
+
+/* Calibration probe, independent of any context: `iters` launches of a plain streaming-read kernel over
+ * src_dev (dst_dev NULL) or of a plain copy kernel src_dev -> dst_dev, `blocks` blocks of 256 threads,
+ * 128-bit accesses; returns the average milliseconds per launch (HIP events on `stream`).  Used as the
+ * measured ceiling beside the nominal HBM peak and as the known-size kernel that scales hardware counters. */
+int32_t moe_probe_bandwidth(const void *src_dev, void *dst_dev, uint64_t bytes, int32_t blocks, int32_t iters,
+                            void *stream, double *avg_ms);
+
 const char *moe_last_error(void);
 int32_t moe_last_hip_error(void);
 

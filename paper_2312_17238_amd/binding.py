@@ -24,7 +24,7 @@ EXPORTS = [
     "moe_ctx_create", "moe_ctx_destroy", "moe_layer_create", "moe_layer_destroy",
     "moe_layer_load_expert", "moe_layer_peek_weight", "moe_layer_step", "moe_layer_prefetch",
     "moe_stack_step", "moe_layer_resolve", "moe_layer_stats", "moe_layer_cache_state",
-    "moe_layer_reset", "moe_ctx_read_y", "moe_ctx_profile_enable", "moe_ctx_profile_read", "moe_layer_set_prefetch", "moe_layer_set_flags", "moe_last_error", "moe_last_hip_error",
+    "moe_layer_reset", "moe_ctx_read_y", "moe_ctx_profile_enable", "moe_ctx_profile_read", "moe_ctx_set_option", "moe_probe_bandwidth", "moe_layer_set_prefetch", "moe_layer_set_flags", "moe_last_error", "moe_last_hip_error",
 ]
 
 
@@ -135,6 +135,8 @@ def lib() -> C.CDLL:
     L.moe_ctx_read_y.argtypes = [vp, i32, i32, vp]
     L.moe_ctx_profile_enable.argtypes = [vp, i32]
     L.moe_ctx_profile_read.argtypes = [vp, C.POINTER(Profile)]
+    L.moe_ctx_set_option.argtypes = [vp, C.c_char_p, i32]
+    L.moe_probe_bandwidth.argtypes = [vp, vp, u64, i32, i32, vp, C.POINTER(C.c_double)]
     L.moe_layer_set_prefetch.argtypes = [vp, i32]
     L.moe_layer_set_flags.argtypes = [vp, i32]
     L.moe_last_error.restype = C.c_char_p
@@ -254,6 +256,17 @@ def moe_ctx_profile_read(ctx) -> Profile:
     p = Profile()
     check(lib().moe_ctx_profile_read(ctx, C.byref(p)))
     return p
+
+
+def moe_ctx_set_option(ctx, name: str, value: int) -> None:
+    check(lib().moe_ctx_set_option(ctx, name.encode(), value))
+
+
+def moe_probe_bandwidth(src_dev: int, dst_dev: Optional[int], nbytes: int, blocks: int, iters: int, stream: int) -> float:
+    """Average milliseconds per launch of the plain read (dst_dev None) or copy probe kernel."""
+    ms = C.c_double()
+    check(lib().moe_probe_bandwidth(src_dev, dst_dev, nbytes, blocks, iters, stream, C.byref(ms)))
+    return ms.value
 
 
 def moe_layer_set_prefetch(layer, m: int) -> None:

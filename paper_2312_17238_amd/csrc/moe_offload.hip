@@ -7,6 +7,7 @@
 //   buffers it is about to read -> fused dequant-GEMV kernels -> residual add.
 // The call returns as soon as everything is enqueued.
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include <algorithm>
 #include <atomic>
@@ -16,6 +17,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <new>
+#include <string>
 #include <thread>
 #include <vector>
 
@@ -94,7 +96,7 @@ struct moe_ctx {
     GateHostOut *gate_out_dev = nullptr;// the same memory as the device sees it
     hipEvent_t ev_gate = nullptr, ev_compute = nullptr;
     int32_t n_layers = 0;
-    int32_t w13_blocks = 512, w2_rows = 16;
+    int32_t w13_blocks = 256, w13_ring = 2, w2_rows = 32, w2_ring = 4, w2_form = 0, w2_blocks = 256;
     bool sync_wait = false;
 };
 
@@ -198,8 +200,10 @@ extern "C" int32_t moe_ctx_create(const moe_ctx_config_t *cfg, void *dev_arena, 
     c->buf_bytes = align_u64(cfg->max_expert_bytes, 4096);
     c->bufs.resize(cfg->n_staging);
     for (int i = 0; i < cfg->n_staging; ++i) c->pool.free_staging.push_back(i);
-    c->w13_blocks = std::max(1, env_int("MOE_W13_BLOCKS", 512));
-    c->w2_rows = std::max(8, env_int("MOE_W2_ROWS", 16) / 8 * 8);
+    c->w13_blocks = std::max(1, env_int("MOE_W13_BLOCKS", c->w13_blocks));
+    c->w13_ring = env_int("MOE_W13_RING", c->w13_ring);
+    c->w2_rows = std::max(4, env_int("MOE_W2_ROWS", c->w2_rows));
+    c->w2_ring = env_int("MOE_W2_RING", c->w2_ring);
     c->sync_wait = env_int("MOE_SYNC_WAIT", 0) != 0;
     if (c->host_only) {
         c->gate_out = static_cast<GateHostOut *>(calloc(1, sizeof(GateHostOut)));
@@ -609,38 +613,106 @@ static int32_t wait_gate(moe_ctx *c, uint32_t expect)
     return MOE_OK;
 }
 
+// Launch a kernel; while profiling is on, attach a start/stop event pair to the dispatch itself
+// (hipExtLaunchKernelGGL), so the pair brackets the kernel's execution and nothing else.
+template <typename K, typename... Args>
+static int32_t launch_timed(moe_ctx *c, int kind, uint64_t bytes, K kernel, dim3 grid, dim3 block, size_t shm,
+                            Args... args)
+{
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (c->prof.on) {
+        ProfKind &p = c->prof.kind[kind];
+        if (p.used == Profiler::RING) { int32_t rc = prof_drain(c, kind); if (rc) return rc; }
+        if (p.used == p.start.size()) {
+            hipEvent_t a, b;
+            HIPCHK(hipEventCreate(&a));
+            HIPCHK(hipEventCreate(&b));
+            p.start.push_back(a);
+            p.stop.push_back(b);
+        }
+        e0 = p.start[p.used];
+        e1 = p.stop[p.used];
+        p.used++;
+        p.launches++;
+        p.bytes += bytes;
+    }
+    hipExtLaunchKernelGGL(kernel, grid, block, shm, c->compute, e0, e1, 0, args...);
+    HIPCHK(hipGetLastError());
+    return MOE_OK;
+}
+
 static int32_t launch_gate(moe_ctx *c, const GateArgs &ga, int32_t batch)
 {
     c->gate_out->done = 0;
     std::atomic_thread_fence(std::memory_order_release);
-    int ps;
-    int32_t rc = prof_begin(c, PROF_GATE, c->compute, 0, &ps);
-    if (rc) return rc;
-    hipLaunchKernelGGL(k_gate, dim3(batch), dim3(GATE_THREADS), (size_t)ga.H * 2, c->compute, ga);
-    HIPCHK(hipGetLastError());
-    rc = prof_end(c, PROF_GATE, c->compute, ps);
+    int32_t rc = launch_timed(c, PROF_GATE, 0, k_gate, dim3(batch), dim3(GATE_THREADS), 0, ga);
     if (rc) return rc;
     if (!c->sync_wait) HIPCHK(hipEventRecord(c->ev_gate, c->compute));
     return wait_gate(c, (uint32_t)batch);
 }
 
-template <int KCH>
-static void launch_w13(int nt, dim3 grid, hipStream_t s, const FfnArgs &A)
+template <int KCH, int NT>
+static int32_t launch_w13_g(moe_ctx *c, int g, uint64_t bytes, dim3 grid, const FfnArgs &A)
 {
     const dim3 block(W13_WAVES * WAVE);
-    if (nt == 1) hipLaunchKernelGGL((k_w13_q4<KCH, 1>), grid, block, 0, s, A);
-    else if (nt == 2) hipLaunchKernelGGL((k_w13_q4<KCH, 2>), grid, block, 0, s, A);
-    else hipLaunchKernelGGL((k_w13_q4<KCH, 4>), grid, block, 0, s, A);
+    if constexpr (KCH * NT >= 8) {
+        return launch_timed(c, PROF_W13, bytes, k_w13_q4<KCH, NT, 1>, grid, block, 0, A);
+    } else if constexpr (KCH * NT >= 4) {
+        if (g >= 2) return launch_timed(c, PROF_W13, bytes, k_w13_q4<KCH, NT, 2>, grid, block, 0, A);
+        return launch_timed(c, PROF_W13, bytes, k_w13_q4<KCH, NT, 1>, grid, block, 0, A);
+    } else {
+        if (g >= 4) return launch_timed(c, PROF_W13, bytes, k_w13_q4<KCH, NT, 4>, grid, block, 0, A);
+        if (g >= 2) return launch_timed(c, PROF_W13, bytes, k_w13_q4<KCH, NT, 2>, grid, block, 0, A);
+        return launch_timed(c, PROF_W13, bytes, k_w13_q4<KCH, NT, 1>, grid, block, 0, A);
+    }
+}
+
+template <int KCH>
+static int32_t launch_w13(moe_ctx *c, int nt, int g, uint64_t bytes, dim3 grid, const FfnArgs &A)
+{
+    if (nt == 1) return launch_w13_g<KCH, 1>(c, g, bytes, grid, A);
+    if (nt == 2) return launch_w13_g<KCH, 2>(c, g, bytes, grid, A);
+    if constexpr (KCH <= 2) return launch_w13_g<KCH, 4>(c, g, bytes, grid, A);
+    return fail(MOE_EINVAL, "no kernel for this shape and batch");
+}
+
+template <int NT>
+static int32_t launch_w2(moe_ctx *c, int g, uint64_t bytes, dim3 grid, dim3 block, size_t shm, const FfnArgs &A)
+{
+    if (g >= 16) return launch_timed(c, PROF_W2, bytes, k_w2_q4<NT, 16>, grid, block, shm, A);
+    if (g >= 8) return launch_timed(c, PROF_W2, bytes, k_w2_q4<NT, 8>, grid, block, shm, A);
+    return launch_timed(c, PROF_W2, bytes, k_w2_q4<NT, 4>, grid, block, shm, A);
+}
+
+template <int NT, int CH>
+static int32_t launch_w2_rows_g(moe_ctx *c, int g, uint64_t bytes, dim3 grid, const FfnArgs &A)
+{
+    const dim3 block(W13_WAVES * WAVE);
+    if (g >= 4 && CH * NT <= 8) return launch_timed(c, PROF_W2, bytes, k_w2_rows_q4<CH, NT, 4>, grid, block, 0, A);
+    if (g >= 3 && CH * NT <= 8) return launch_timed(c, PROF_W2, bytes, k_w2_rows_q4<CH, NT, 3>, grid, block, 0, A);
+    if (g >= 2) return launch_timed(c, PROF_W2, bytes, k_w2_rows_q4<CH, NT, 2>, grid, block, 0, A);
+    return launch_timed(c, PROF_W2, bytes, k_w2_rows_q4<CH, NT, 1>, grid, block, 0, A);
+}
+
+template <int NT>
+static int32_t launch_w2_rows(moe_ctx *c, int ch, int g, uint64_t bytes, dim3 grid, const FfnArgs &A)
+{
+    switch (ch) {
+    case 1: return launch_w2_rows_g<NT, 1>(c, g, bytes, grid, A);
+    case 2: return launch_w2_rows_g<NT, 2>(c, g, bytes, grid, A);
+    case 4: return launch_w2_rows_g<NT, 4>(c, g, bytes, grid, A);
+    case 7: return launch_w2_rows_g<NT, 7>(c, g, bytes, grid, A);
+    default: return launch_w2_rows_g<NT, 8>(c, g, bytes, grid, A);
+    }
 }
 
 static int32_t launch_ffn(moe_layer *l, const std::vector<FfnEntry> &entries, int nt)
 {
     moe_ctx *c = l->ctx;
     const BlobLayout &b = l->lay;
-    const int kch = (b.hidden / 32 + 63) / 64;         // chunks per lane per w1/w3 row
-    const int cs = (b.ffn / 32 + 63) / 64;             // waves per block for w2
-    if (kch > 4 || cs > 16) return fail(MOE_EINVAL, "shape too large for the GEMV kernels");
-    if (kch == 4 && nt > 2) nt = 2;                    // register budget
+    const int kch = (b.hidden / 32 + 63) / 64 > 2 ? 4 : (b.hidden / 32 + 63) / 64;   // chunks per lane per w1/w3 row
+    const int cs = (b.ffn / 32 + 63) / 64;                                           // waves per block for w2
+    if ((b.hidden / 32 + 63) / 64 > 4 || cs > 16) return fail(MOE_EINVAL, "shape too large for the GEMV kernels");
     for (size_t first = 0; first < entries.size(); first += MAX_ENTRIES) {
         const int n = (int)std::min<size_t>(MAX_ENTRIES, entries.size() - first);
         FfnArgs A{};
@@ -651,8 +723,6 @@ static int32_t launch_ffn(moe_layer *l, const std::vector<FfnEntry> &entries, in
         A.stride2 = b.m2.row_stride; A.meta2 = b.m2.meta_off;
         A.off_w2 = b.off_w2;
         A.rows_per_block = c->w2_rows;
-        int bx = std::max(1, std::min((b.ffn + W13_WAVES - 1) / W13_WAVES, c->w13_blocks / n));
-        const dim3 g13(bx, n);
         // algorithmic bytes: every distinct expert of the launch is read once
         uint64_t n_distinct = 0;
         for (int i = 0; i < n; ++i) {
@@ -660,24 +730,29 @@ static int32_t launch_ffn(moe_layer *l, const std::vector<FfnEntry> &entries, in
             for (int j = 0; j < i; ++j) seen |= (A.e[j].blob == A.e[i].blob);
             n_distinct += !seen;
         }
-        int ps;
-        int32_t rc = prof_begin(c, PROF_W13, c->compute, n_distinct * 2 * (uint64_t)b.ffn * b.m13.row_stride, &ps);
+        const uint64_t bytes13 = n_distinct * 2 * (uint64_t)b.ffn * b.m13.row_stride;
+        const uint64_t bytes2 = n_distinct * (uint64_t)b.hidden * b.m2.row_stride;
+        const int bx = std::max(1, std::min((b.ffn + W13_WAVES - 1) / W13_WAVES, c->w13_blocks / n));
+        const dim3 g13(bx, n);
+        int32_t rc;
+        if (kch == 1) rc = launch_w13<1>(c, nt, c->w13_ring, bytes13, g13, A);
+        else if (kch == 2) rc = launch_w13<2>(c, nt, c->w13_ring, bytes13, g13, A);
+        else rc = launch_w13<4>(c, nt, c->w13_ring, bytes13, g13, A);
         if (rc) return rc;
-        if (kch == 1) launch_w13<1>(nt, g13, c->compute, A);
-        else if (kch == 2) launch_w13<2>(nt, g13, c->compute, A);
-        else launch_w13<4>(nt, g13, c->compute, A);
-        HIPCHK(hipGetLastError());
-        rc = prof_end(c, PROF_W13, c->compute, ps);
-        if (rc) return rc;
-        rc = prof_begin(c, PROF_W2, c->compute, n_distinct * (uint64_t)b.hidden * b.m2.row_stride, &ps);
-        if (rc) return rc;
-        const dim3 g2((b.hidden + A.rows_per_block - 1) / A.rows_per_block, n), blk(cs * WAVE);
-        const size_t shm = (size_t)A.rows_per_block * nt * cs * sizeof(float);
-        if (nt == 1) hipLaunchKernelGGL((k_w2_q4<1>), g2, blk, shm, c->compute, A);
-        else if (nt == 2) hipLaunchKernelGGL((k_w2_q4<2>), g2, blk, shm, c->compute, A);
-        else hipLaunchKernelGGL((k_w2_q4<4>), g2, blk, shm, c->compute, A);
-        HIPCHK(hipGetLastError());
-        rc = prof_end(c, PROF_W2, c->compute, ps);
+        if (c->w2_form == 1 && nt <= 2 && cs <= 8) {
+            // row-per-wave form: whole activation vector in registers
+            const int bx2 = std::max(1, std::min((b.hidden + W13_WAVES - 1) / W13_WAVES, c->w2_blocks / n));
+            const dim3 gr(bx2, n);
+            const int ch = cs <= 1 ? 1 : (cs <= 2 ? 2 : (cs <= 4 ? 4 : (cs <= 7 ? 7 : 8)));
+            if (nt == 1) rc = launch_w2_rows<1>(c, ch, c->w2_ring, bytes2, gr, A);
+            else rc = launch_w2_rows<2>(c, ch, c->w2_ring, bytes2, gr, A);
+        } else {
+            const dim3 g2((b.hidden + A.rows_per_block - 1) / A.rows_per_block, n), blk(cs * WAVE);
+            const size_t shm = (size_t)A.rows_per_block * nt * cs * sizeof(float);
+            if (nt == 1) rc = launch_w2<1>(c, c->w2_ring, bytes2, g2, blk, shm, A);
+            else if (nt == 2) rc = launch_w2<2>(c, c->w2_ring, bytes2, g2, blk, shm, A);
+            else rc = launch_w2<4>(c, c->w2_ring, bytes2, g2, blk, shm, A);
+        }
         if (rc) return rc;
     }
     return MOE_OK;
@@ -739,7 +814,8 @@ extern "C" int32_t moe_layer_step(moe_layer_t *l, moe_layer_t *next, const uint1
         for (int i = 0; i < batch * cf.top_k; ++i) n += (idx[i] == a.expert);
         max_tok = std::max(max_tok, n);
     }
-    const int nt = max_tok == 1 ? 1 : (max_tok == 2 ? 2 : 4);
+    int nt = max_tok == 1 ? 1 : (max_tok == 2 ? 2 : 4);
+    if (cf.hidden > 4096 && nt > 2) nt = 2;             // register budget of the widest w1/w3 variant
 
     size_t next_demand = 0;
     for (size_t p = 0; p < passes.size(); ++p) {
@@ -883,6 +959,49 @@ extern "C" int32_t moe_ctx_read_y(moe_ctx_t *c, int32_t batch, int32_t hidden, f
         return fail(MOE_EINVAL, "moe_ctx_read_y: batch or hidden out of range");
     HIPCHK(hipStreamSynchronize(c->compute));
     HIPCHK(hipMemcpy(y_host, c->yacc, (size_t)batch * hidden * sizeof(float), hipMemcpyDeviceToHost));
+    return MOE_OK;
+}
+
+extern "C" int32_t moe_ctx_set_option(moe_ctx_t *c, const char *name, int32_t value)
+{
+    if (!c || !name) return fail(MOE_EINVAL, "moe_ctx_set_option: null argument");
+    const std::string n(name);
+    if (n == "w13_blocks" && value >= 1) c->w13_blocks = value;
+    else if (n == "w13_ring" && value >= 1) c->w13_ring = value;
+    else if (n == "w2_rows" && value >= 1 && value <= 256) c->w2_rows = value;
+    else if (n == "w2_ring" && value >= 1) c->w2_ring = value;
+    else if (n == "w2_form" && (value == 0 || value == 1)) c->w2_form = value;
+    else if (n == "w2_blocks" && value >= 1) c->w2_blocks = value;
+    else if (n == "sync_wait") c->sync_wait = value != 0;
+    else return fail(MOE_EINVAL, "moe_ctx_set_option: unknown option or bad value: %s = %d", name, value);
+    return MOE_OK;
+}
+
+extern "C" int32_t moe_probe_bandwidth(const void *src_dev, void *dst_dev, uint64_t bytes, int32_t blocks, int32_t iters,
+                                       void *stream, double *avg_ms)
+{
+    if (!src_dev || !avg_ms || bytes < 16 || blocks < 1 || iters < 1) return fail(MOE_EINVAL, "moe_probe_bandwidth: bad argument");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipEvent_t e0, e1;
+    HIPCHK(hipEventCreate(&e0));
+    HIPCHK(hipEventCreate(&e1));
+    uint32_t *sink = nullptr;
+    if (!dst_dev) HIPCHK(hipMalloc(reinterpret_cast<void **>(&sink), (size_t)blocks * 4));
+    const size_t n16 = bytes / 16;
+    for (int it = -1; it < iters; ++it) {      // one untimed warm-up launch
+        if (it == 0) HIPCHK(hipEventRecord(e0, s));
+        if (dst_dev) hipLaunchKernelGGL(k_probe_copy, dim3(blocks), dim3(256), 0, s, static_cast<const uint4 *>(src_dev), static_cast<uint4 *>(dst_dev), n16);
+        else hipLaunchKernelGGL(k_probe_read, dim3(blocks), dim3(256), 0, s, static_cast<const uint4 *>(src_dev), n16, sink);
+    }
+    HIPCHK(hipGetLastError());
+    HIPCHK(hipEventRecord(e1, s));
+    HIPCHK(hipEventSynchronize(e1));
+    float ms = 0.f;
+    HIPCHK(hipEventElapsedTime(&ms, e0, e1));
+    *avg_ms = (double)ms / iters;
+    if (sink) (void)hipFree(sink);
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
     return MOE_OK;
 }
 
