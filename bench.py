@@ -23,6 +23,10 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+# HBM bytes per launch (read + written) of the dominant kernel from hardware counters, valid for the default
+# workload and launch shape only (4-bit g64 Mixtral experts, batch 1): FETCH_SIZE and WRITE_SIZE of two
+# rocprofv3 --pmc runs, scaled by the copy probe; see profiles/hbm_traffic_gemv_kernels_4bit.md
+PMC_TRAFFIC_W13_4BIT_B1 = 132_593_967
 LINK_PEAK_GBS = 64.0           # PCIe Gen5 x16, one direction, nominal
 
 
@@ -99,6 +103,7 @@ def main() -> int:
     ap.add_argument("--no-cache", action="store_true", help="ablation without LRU cache (and usually --prefetch 0)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true", help="do not record HIP events around the engine's launches")
+    ap.add_argument("--no-probe", action="store_true", help="skip the plain streaming-read / copy calibration kernels")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (one process, no collectives); "
@@ -135,6 +140,21 @@ def main() -> int:
     x_dev = xs.to(device)                                   # inputs resident in HBM before the timed region
     x_out = torch.empty(batch, shape.hidden, dtype=torch.float16, device=device)
     torch.cuda.synchronize()
+
+    probe = None
+    if not args.no_probe:
+        # calibration: a plain streaming read (the practical HBM ceiling on this machine) and a plain copy of
+        # known size (the kernel hardware-counter readings are scaled by)
+        src = torch.empty(4 << 30, dtype=torch.uint8, device=device).zero_()
+        dst = torch.empty(1 << 30, dtype=torch.uint8, device=device)
+        s0 = torch.cuda.current_stream().cuda_stream
+        ms_r = B.moe_probe_bandwidth(src.data_ptr(), None, 4 << 30, 16384, 5, s0)
+        ms_c = B.moe_probe_bandwidth(src.data_ptr(), dst.data_ptr(), 1 << 30, 8192, 3, s0)
+        probe = {"read_gbs": (4 << 30) / ms_r / 1e6, "read_bytes": 4 << 30,
+                 "copy_gbs_each_way": (1 << 30) / ms_c / 1e6, "copy_bytes": 1 << 30}
+        del src, dst
+        torch.cuda.empty_cache()
+        log(f"probe: streaming read {probe['read_gbs']:.0f} GB/s, copy {probe['copy_gbs_each_way']:.0f} GB/s each way")
 
     for t in range(args.warmup):
         stack.step(x_dev[t], x_out)
@@ -178,9 +198,12 @@ def main() -> int:
         ach = w13["bytes"] / max(w13["total_ms"], 1e-9) / 1e6      # GB/s
         result["roofline"] = {"bound": "hbm", "kernel": "k_w13_q4 (fused dequant-GEMV w1,w3 -> SiLU*mul)",
                               "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
-                              "traffic": None, "launches": w13["launches"],
+                              "traffic": PMC_TRAFFIC_W13_4BIT_B1 if (batch == 1 and set(formats) == {(4, 64)}
+                                                                     and shape.hidden == 4096 and shape.ffn == 14336) else None,
+                              "launches": w13["launches"],
                               "bytes_per_launch": w13["bytes"] / max(1, w13["launches"]),
-                              "avg_us": 1e3 * w13["total_ms"] / max(1, w13["launches"])}
+                              "avg_us": 1e3 * w13["total_ms"] / max(1, w13["launches"]),
+                              "measured_read_probe_gbs": probe["read_gbs"] if probe else None}
         a2 = w2["bytes"] / max(w2["total_ms"], 1e-9) / 1e6
         result["roofline_w2"] = {"bound": "hbm", "kernel": "k_w2_q4 (fused dequant-GEMV w2 -> weighted accumulate)",
                                  "achieved": a2, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": a2 / HBM_PEAK_GBS,
@@ -194,6 +217,8 @@ def main() -> int:
                               "busy_frac_of_wall": cp["total_ms"] / (1e3 * dt),
                               "wall_gbs": link_bytes / dt / 1e9}
         result["gate_avg_us"] = 1e3 * gt["total_ms"] / max(1, gt["launches"])
+    if probe:
+        result["probe"] = probe
     if not args.no_cpu_baseline:
         log("timing the CPU oracle on a bounded sample")
         result["cpu_baseline"] = cpu_baseline(shape, formats, gates, gamma, kept, xs)
