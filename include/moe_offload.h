@@ -230,11 +230,9 @@ int32_t moe_ctx_profile_enable(moe_ctx_t *ctx, int32_t on);
 int32_t moe_ctx_profile_read(moe_ctx_t *ctx, moe_profile_t *out);
 
 /* Launch-shape tuning knobs (defaults are the measured best for Mixtral shapes on MI355X):
- *   "w13_blocks" total thread blocks of the w1/w3 kernel;  "w13_ring" rows a wave keeps in flight (1, 2, 4);
- *   "w2_form" 1: w2 kernel with whole rows per wave (used when at most 2 tokens share an expert), 0: always the
- *   column-split form;  "w2_blocks" total thread blocks of the row form;  "w2_ring" rows a wave keeps in flight;
- *   "w2_rows" output rows per block of the column-split form;
- *   "sync_wait" 1: wait for the gate result with hipStreamSynchronize instead of polling host-mapped memory. */
+ *   "w13_blocks" total thread blocks of the w1/w3 kernel (default 256: one per compute unit);
+ *   "w2_rows"    output rows per block of the w2 kernel (default 32);
+ *   "sync_wait"  1: wait for the gate result with hipStreamSynchronize instead of polling host-mapped memory. */
 int32_t moe_ctx_set_option(moe_ctx_t *ctx, const char *name, int32_t value);
 
 /* Calibration probe, independent of any context: `iters` launches of a plain streaming-read kernel over

@@ -1,630 +1,5 @@
-// gfx950 device code of the decode step: gate (RMSNorm + linear gate + top-k + speculative gate),
-// fused dequantize+GEMV for w1/w3 -> SiLU*mul and for w2 -> weighted accumulate, and the residual add.
-//
-// Wavefronts are 64 wide.  The GEMV kernels are bound by HBM bandwidth: every weight byte is read
-// exactly once per step with 128-bit loads, a lane owns a fixed 32-code column chunk of every row its
-// wave visits, the activations it needs for that chunk stay in registers for the whole kernel, and the
-// only cross-lane traffic is one DPP reduction per output row.  Each wave keeps a ring of G rows in
-// flight: as soon as a row's registers are consumed the load of the row G positions ahead is issued
-// into them, so the memory pipe never drains between rows.
-//
-// Dequantization is never materialised.  With W^ = (q - z) s per group (Sec. 4.2),
-//     sum_i W^_i h_i = s * (sum_i q_i h_i - z * sum_i h_i),
-// and sum_i q_i h_i comes from fp16 bit tricks: OR-ing a 4-bit code into the mantissa of 1024.0
-// (bits 0..3) or 64.0 (bits 4..7) gives the fp16 numbers 1024+q and 64+q exactly; two of them are
-// multiplied with two activations and accumulated in fp32 by one v_dot2_f32_f16.  The biases are
-// removed by starting the accumulator at -sum_i bias_i h_i, a per-lane constant.
+// gfx950 device code of the decode step.
 #pragma once
-#include <hip/hip_runtime.h>
-#include <stdint.h>
-
-namespace moe {
-
-typedef _Float16 h2_t __attribute__((ext_vector_type(2)));
-
-constexpr int WAVE = 64;
-constexpr int MAX_ENTRIES = 16;   // (expert, token-chunk) work entries per launch
-constexpr int MAX_NT = 4;         // tokens per entry
-
-// ---------------------------------------------------------------------------------------------
-// small helpers
-// ---------------------------------------------------------------------------------------------
-
-__device__ __forceinline__ h2_t as_h2(uint32_t v) { return __builtin_bit_cast(h2_t, v); }
-__device__ __forceinline__ float lo_half(uint32_t v) { return (float)__builtin_bit_cast(_Float16, (uint16_t)(v & 0xffff)); }
-__device__ __forceinline__ float hi_half(uint32_t v) { return (float)__builtin_bit_cast(_Float16, (uint16_t)(v >> 16)); }
-__device__ __forceinline__ double half_bits_to_f64(uint16_t v) { return (double)__builtin_bit_cast(_Float16, v); }
-
-template <int CTRL>
-__device__ __forceinline__ float dpp_f(float v)
-{
-    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
-}
-
-template <int CTRL, int ROW_MASK>
-__device__ __forceinline__ float dpp_masked_f(float v)
-{
-    // lanes of rows outside ROW_MASK receive 0
-    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, ROW_MASK, 0xf, false));
-}
-
-// Sum over the 64 lanes; the total is valid in lane 63 only.  Fixed order, so deterministic.
-__device__ __forceinline__ float wave_sum_l63(float v)
-{
-    v += dpp_f<0xB1>(v);    // quad_perm [1,0,3,2]
-    v += dpp_f<0x4E>(v);    // quad_perm [2,3,0,1]
-    v += dpp_f<0x141>(v);   // row_half_mirror
-    v += dpp_f<0x140>(v);   // row_mirror: every lane of a 16-lane row now holds the row's sum
-    v += dpp_masked_f<0x142, 0xA>(v);   // row_bcast:15 into rows 1 and 3
-    v += dpp_masked_f<0x143, 0xC>(v);   // row_bcast:31 into rows 2 and 3
-    return v;
-}
-
-template <int CTRL>
-__device__ __forceinline__ double dpp_d(double v)
-{
-    const long long b = __double_as_longlong(v);
-    const int lo = __builtin_amdgcn_update_dpp(0, (int)(b & 0xffffffffll), CTRL, 0xf, 0xf, true);
-    const int hi = __builtin_amdgcn_update_dpp(0, (int)(b >> 32), CTRL, 0xf, 0xf, true);
-    return __longlong_as_double(((long long)hi << 32) | (unsigned int)lo);
-}
-
-__device__ __forceinline__ double readlane_d(double v, int lane)
-{
-    const long long b = __double_as_longlong(v);
-    const int lo = __builtin_amdgcn_readlane((int)(b & 0xffffffffll), lane);
-    const int hi = __builtin_amdgcn_readlane((int)(b >> 32), lane);
-    return __longlong_as_double(((long long)hi << 32) | (unsigned int)lo);
-}
-
-// fp64 sum over the 64 lanes, total in every lane
-__device__ __forceinline__ double wave_sum_f64(double v)
-{
-    v += dpp_d<0xB1>(v);
-    v += dpp_d<0x4E>(v);
-    v += dpp_d<0x141>(v);
-    v += dpp_d<0x140>(v);
-    return (readlane_d(v, 0) + readlane_d(v, 16)) + (readlane_d(v, 32) + readlane_d(v, 48));
-}
-
-// Round-to-nearest-even conversion of a double straight to binary16 (no intermediate fp32 rounding,
-// which could double-round).  NaN maps to a quiet NaN.
-__device__ __forceinline__ uint16_t f64_to_f16_rne(double d)
-{
-    const uint64_t b = (uint64_t)__double_as_longlong(d);
-    const uint16_t sign = (uint16_t)((b >> 48) & 0x8000u);
-    const int ex = (int)((b >> 52) & 0x7ff);
-    const uint64_t man = b & 0xFFFFFFFFFFFFFull;
-    if (ex == 0x7ff) return sign | (man ? 0x7e00u : 0x7c00u);
-    if (ex == 0) return sign;                        // zero or a double subnormal: far below half range
-    const int e = ex - 1023;
-    if (e > 15) return sign | 0x7c00u;
-    const uint64_t m = man | (1ull << 52);
-    int shift = 42;
-    uint32_t base = (uint32_t)(e + 15) << 10;
-    if (e < -14) {                                   // half subnormal
-        shift = 42 + (-14 - e);
-        base = 0;
-        if (shift > 63) return sign;
-    }
-    uint64_t q = m >> shift;
-    const uint64_t rem = m & ((1ull << shift) - 1), halfway = 1ull << (shift - 1);
-    if (rem > halfway || (rem == halfway && (q & 1))) ++q;
-    // normal: q is in [1024, 2048]; adding q-1024 to the exponent field carries correctly on 2048.
-    // subnormal: q is in [0, 1024]; 1024 carries into the smallest normal.
-    const uint32_t r = (e < -14) ? (uint32_t)q : base + (uint32_t)(q - 1024);
-    return sign | (uint16_t)(r > 0x7c00u ? 0x7c00u : r);
-}
-
-// ---------------------------------------------------------------------------------------------
-// K1: RMSNorm + gate + top-k (+ next layer's gate for speculative loading)
-// ---------------------------------------------------------------------------------------------
-
-struct GateHostOut {                // lives in host-mapped pinned memory; written by the kernel
-    int32_t idx[64 * 4];            // [b*K + j]
-    float w[64 * 4];
-    double logits[64 * 16];         // [b*E + e]
-    double spec_p[64 * 16];         // [b*E2 + e] next-layer gate probabilities per token
-    uint32_t done;                  // incremented once per block, system scope, after its results
-};
-
-struct GateArgs {
-    const uint16_t *x;              // [B][H] fp16
-    const float *wg;                // [E][H] fp32 or null (speculative gate only)
-    const float *wg2;               // [E2][H] fp32 or null
-    const uint16_t *gamma;          // [H] fp16 or null (gain 1)
-    uint16_t *h_out;                // [B][H] fp16 or null
-    uint16_t *h_out2;               // optional second copy
-    float *yacc;                    // [B][H] fp32 to clear, or null
-    GateHostOut *out;
-    double eps;                     // 0: no norm
-    int32_t H, E, E2, K;
-};
-
-constexpr int GATE_THREADS = 1024;
-constexpr int GATE_WAVES = GATE_THREADS / WAVE;
-
-// One block per token, 4 consecutive elements per thread and pass.  All decisions are taken in fp64:
-// the products fp32 x fp16 are exact in fp64 and the sums differ from any other fp64 summation order
-// only at the 1e-16 level, so routing equals an fp64 reference except on ties closer than that.
-__global__ __launch_bounds__(GATE_THREADS) void k_gate(GateArgs a)
-{
-    __shared__ double red[GATE_WAVES][32];
-    __shared__ double tot[33];
-    const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    const uint16_t *x = a.x + (size_t)b * a.H;
-    const int n1 = a.wg ? a.E : 0, n2 = a.wg2 ? a.E2 : 0;
-
-    double scale = 1.0;
-    if (a.eps > 0.0) {
-        double ss = 0.0;
-        for (int i = tid * 4; i < a.H; i += GATE_THREADS * 4) {
-            const uint2 p = *reinterpret_cast<const uint2 *>(x + i);
-            const double v0 = half_bits_to_f64(p.x & 0xffff), v1 = half_bits_to_f64(p.x >> 16);
-            const double v2 = half_bits_to_f64(p.y & 0xffff), v3 = half_bits_to_f64(p.y >> 16);
-            ss += v0 * v0; ss += v1 * v1; ss += v2 * v2; ss += v3 * v3;
-        }
-        ss = wave_sum_f64(ss);
-        if (lane == 0) red[wv][0] = ss;
-        __syncthreads();
-        if (tid == 0) {
-            double t = 0.0;
-            for (int w = 0; w < GATE_WAVES; ++w) t += red[w][0];
-            tot[32] = 1.0 / sqrt(t / (double)a.H + a.eps);
-        }
-        __syncthreads();
-        scale = tot[32];
-    }
-
-    double acc[32];
-#pragma unroll
-    for (int e = 0; e < 32; ++e) acc[e] = 0.0;
-    for (int i = tid * 4; i < a.H; i += GATE_THREADS * 4) {
-        const uint2 p = *reinterpret_cast<const uint2 *>(x + i);
-        uint16_t hv[4] = {(uint16_t)(p.x & 0xffff), (uint16_t)(p.x >> 16), (uint16_t)(p.y & 0xffff), (uint16_t)(p.y >> 16)};
-        if (a.eps > 0.0) {
-            uint2 g = make_uint2(0x3c003c00u, 0x3c003c00u);
-            if (a.gamma) g = *reinterpret_cast<const uint2 *>(a.gamma + i);
-            const uint16_t gv[4] = {(uint16_t)(g.x & 0xffff), (uint16_t)(g.x >> 16), (uint16_t)(g.y & 0xffff), (uint16_t)(g.y >> 16)};
-#pragma unroll
-            for (int j = 0; j < 4; ++j) hv[j] = f64_to_f16_rne(half_bits_to_f64(hv[j]) * scale * half_bits_to_f64(gv[j]));
-        }
-        const uint2 ho = make_uint2((uint32_t)hv[0] | (uint32_t)hv[1] << 16, (uint32_t)hv[2] | (uint32_t)hv[3] << 16);
-        if (a.h_out) *reinterpret_cast<uint2 *>(a.h_out + (size_t)b * a.H + i) = ho;
-        if (a.h_out2) *reinterpret_cast<uint2 *>(a.h_out2 + (size_t)b * a.H + i) = ho;
-        if (a.yacc) *reinterpret_cast<float4 *>(a.yacc + (size_t)b * a.H + i) = make_float4(0.f, 0.f, 0.f, 0.f);
-        const double h0 = half_bits_to_f64(hv[0]), h1 = half_bits_to_f64(hv[1]), h2 = half_bits_to_f64(hv[2]),
-                     h3 = half_bits_to_f64(hv[3]);
-#pragma unroll
-        for (int e = 0; e < 16; ++e)
-            if (e < n1) {
-                const float4 w = *reinterpret_cast<const float4 *>(a.wg + (size_t)e * a.H + i);
-                acc[e] += (double)w.x * h0; acc[e] += (double)w.y * h1; acc[e] += (double)w.z * h2; acc[e] += (double)w.w * h3;
-            }
-#pragma unroll
-        for (int e = 0; e < 16; ++e)
-            if (e < n2) {
-                const float4 w = *reinterpret_cast<const float4 *>(a.wg2 + (size_t)e * a.H + i);
-                acc[16 + e] += (double)w.x * h0; acc[16 + e] += (double)w.y * h1; acc[16 + e] += (double)w.z * h2; acc[16 + e] += (double)w.w * h3;
-            }
-    }
-#pragma unroll
-    for (int e = 0; e < 32; ++e) {
-        const bool live = (e < 16) ? (e < n1) : (e - 16 < n2);
-        if (live) {
-            const double v = wave_sum_f64(acc[e]);
-            if (lane == 0) red[wv][e] = v;
-        }
-    }
-    __syncthreads();
-    if (tid < 32) {
-        const bool live = (tid < 16) ? (tid < n1) : (tid - 16 < n2);
-        if (live) {
-            double t = 0.0;
-            for (int w = 0; w < GATE_WAVES; ++w) t += red[w][tid];
-            tot[tid] = t;
-        }
-    }
-    __syncthreads();
-    if (tid == 0) {
-        GateHostOut *o = a.out;
-        if (n1) {
-            // top-K by (logit descending, index ascending)
-            int chosen[4];
-            for (int j = 0; j < a.K; ++j) {
-                int best = -1;
-                for (int e = 0; e < n1; ++e) {
-                    bool used = false;
-                    for (int q = 0; q < j; ++q) used |= (chosen[q] == e);
-                    if (used) continue;
-                    if (best < 0 || tot[e] > tot[best]) best = e;
-                }
-                chosen[j] = best;
-            }
-            // softmax over all experts, renormalised over the chosen ones == softmax over the chosen logits
-            const double zmax = tot[chosen[0]];
-            double p[4], ps = 0.0;
-            for (int j = 0; j < a.K; ++j) { p[j] = exp(tot[chosen[j]] - zmax); ps += p[j]; }
-            for (int j = 0; j < a.K; ++j) {
-                o->idx[b * a.K + j] = chosen[j];
-                o->w[b * a.K + j] = (float)(p[j] / ps);
-            }
-            for (int e = 0; e < n1; ++e) o->logits[b * n1 + e] = tot[e];
-        }
-        if (n2) {
-            double zmax = tot[16];
-            for (int e = 1; e < n2; ++e) zmax = tot[16 + e] > zmax ? tot[16 + e] : zmax;
-            double pe[16], ps = 0.0;
-            for (int e = 0; e < n2; ++e) { pe[e] = exp(tot[16 + e] - zmax); ps += pe[e]; }
-            for (int e = 0; e < n2; ++e) o->spec_p[b * n2 + e] = pe[e] / ps;
-        }
-        __threadfence_system();
-        __hip_atomic_fetch_add(&o->done, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
-    }
-}
-
-// ---------------------------------------------------------------------------------------------
-// fused dequant-GEMV, 4-bit codes
-// ---------------------------------------------------------------------------------------------
-
-struct FfnEntry {
-    const uint8_t *blob;            // device buffer holding the expert
-    int32_t n_tok;                  // 1..MAX_NT tokens routed to this expert in this entry
-    int32_t tok[MAX_NT];            // token (batch row) of each
-    int32_t pair[MAX_NT];           // row of the activation scratch a[pair][F] (= b*K + j)
-    float w[MAX_NT];                // combine weight of each
-};
-
-struct FfnArgs {
-    FfnEntry e[MAX_ENTRIES];
-    const uint16_t *h;              // [B][H] fp16 gate input
-    uint16_t *a;                    // [B*K][F] fp16 SwiGLU activations
-    float *yacc;                    // [B][H] fp32 accumulators (cleared by the gate kernel)
-    int32_t H, F, group;
-    uint32_t stride13, meta13;      // w1/w3 row: stride and offset of the (scale, zero) pairs
-    uint32_t stride2, meta2;        // w2 row
-    uint64_t off_w2;
-    int32_t rows_per_block;         // w2 kernel
-};
-
-// Per-lane activation state for one 32-code chunk: 16 half2 registers plus the two constants of the
-// factorisation.  Element i of a word's 8 codes has bias 1024 if i%4 < 2, else 64.
-struct Chunk {
-    h2_t h[16];
-    float bias_dot;   // sum_i bias_i * h_i
-    float hsum;       // sum_i h_i
-};
-
-__device__ __forceinline__ void load_chunk(Chunk &c, const uint16_t *vec, int chunk, bool live)
-{
-    const uint4 *p = reinterpret_cast<const uint4 *>(vec + (size_t)chunk * 32);
-    uint32_t w[16];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        uint4 v = live ? p[i] : make_uint4(0, 0, 0, 0);
-        w[4 * i] = v.x; w[4 * i + 1] = v.y; w[4 * i + 2] = v.z; w[4 * i + 3] = v.w;
-    }
-    float bd = 0.f, hs = 0.f;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        c.h[i] = as_h2(w[i]);
-        const float x0 = (float)c.h[i].x, x1 = (float)c.h[i].y;
-        hs += x0 + x1;
-        bd += ((i & 1) ? 64.f : 1024.f) * (x0 + x1);
-    }
-    c.bias_dot = bd;
-    c.hsum = hs;
-}
-
-// sum_i q_i h_i over the 32 codes of one uint4 (bias already folded into `start`)
-__device__ __forceinline__ float dot_q4(const uint4 &q, const Chunk &c, float start)
-{
-    float d = start;
-    const uint32_t w[4] = {q.x, q.y, q.z, q.w};
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const uint32_t lo = w[i], hi = w[i] >> 8;
-        d = __builtin_amdgcn_fdot2(as_h2((lo & 0x000F000Fu) | 0x64006400u), c.h[4 * i + 0], d, false);
-        d = __builtin_amdgcn_fdot2(as_h2((lo & 0x00F000F0u) | 0x54005400u), c.h[4 * i + 1], d, false);
-        d = __builtin_amdgcn_fdot2(as_h2((hi & 0x000F000Fu) | 0x64006400u), c.h[4 * i + 2], d, false);
-        d = __builtin_amdgcn_fdot2(as_h2((hi & 0x00F000F0u) | 0x54005400u), c.h[4 * i + 3], d, false);
-    }
-    return d;
-}
-
-// Weight loads.  Every weight byte is used exactly once per step, so the loads carry the streaming
-// (non-temporal) hint: they need not displace the activations and gate matrices from L2.
-#ifndef MOE_NT_LOADS
-#define MOE_NT_LOADS 1
-#endif
-typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ uint4 ldw4(const void *p, int idx)
-{
-#if MOE_NT_LOADS
-    const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p) + idx);
-#else
-    const u32x4_t v = reinterpret_cast<const u32x4_t *>(p)[idx];
-#endif
-    return make_uint4(v.x, v.y, v.z, v.w);
-}
-__device__ __forceinline__ uint32_t ldw1(const void *p, int idx)
-{
-#if MOE_NT_LOADS
-    return __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(p) + idx);
-#else
-    return reinterpret_cast<const uint32_t *>(p)[idx];
-#endif
-}
-
-__device__ __forceinline__ float silu_mul(float u, float v) { return u / (1.f + __expf(-u)) * v; }
-
-#ifndef MOE_W13_WAVES
-#define MOE_W13_WAVES 4
-#endif
-constexpr int W13_WAVES = MOE_W13_WAVES;
-
-template <int KCH>
-struct Row13 {
-    uint4 q1[KCH], q3[KCH];
-    uint32_t m1[KCH], m3[KCH];
-};
-
-// K2: a[pair][r] = silu(W1^ h)[r] * (W3^ h)[r].  grid = (row blocks, entries); a wave walks rows
-// r = wave_id, wave_id + n_waves, ... with G of them in flight; KCH = ceil(H / 2048) chunks per lane per row.
-template <int KCH, int NT, int G>
-__global__ __launch_bounds__(W13_WAVES *WAVE) void k_w13_q4(FfnArgs A)
-{
-    const FfnEntry &en = A.e[blockIdx.y];
-    const int lane = threadIdx.x & 63;
-    const int wave = blockIdx.x * W13_WAVES + (threadIdx.x >> 6), n_waves = gridDim.x * W13_WAVES;
-    const int n_chunks = A.H / 32;
-    const int gshift = (A.group == 32) ? 0 : (A.group == 64 ? 1 : 2);
-    const uint8_t *base = en.blob;
-
-    int cidx[KCH];
-    bool live[KCH];
-#pragma unroll
-    for (int k = 0; k < KCH; ++k) {
-        live[k] = k * 64 + lane < n_chunks;
-        cidx[k] = live[k] ? k * 64 + lane : 0;
-    }
-    auto load_row = [&](Row13<KCH> &rb, int r) {
-        const uint8_t *r1 = base + (size_t)(2 * r) * A.stride13, *r3 = r1 + A.stride13;
-#pragma unroll
-        for (int k = 0; k < KCH; ++k) {
-            rb.q1[k] = ldw4(r1, cidx[k]);
-            rb.q3[k] = ldw4(r3, cidx[k]);
-            rb.m1[k] = ldw1(r1 + A.meta13, cidx[k] >> gshift);
-            rb.m3[k] = ldw1(r3 + A.meta13, cidx[k] >> gshift);
-        }
-    };
-
-    // Rows past the end are clamped to the last row (a redundant, cached read) and not stored, so the loop
-    // body has no branch around a load and the compiler can wait for exactly the oldest row in flight.
-    const int last = A.F - 1;
-    const int iters = (A.F + n_waves - 1) / n_waves;
-    // weights first (HBM latency), then the activations (L2)
-    Row13<KCH> ring[G];
-#pragma unroll
-    for (int s = 0; s < G; ++s) load_row(ring[s], min(wave + s * n_waves, last));
-
-    Chunk hc[NT][KCH];
-#pragma unroll
-    for (int t = 0; t < NT; ++t) {
-        const int tok = en.tok[t < en.n_tok ? t : 0];
-#pragma unroll
-        for (int k = 0; k < KCH; ++k) load_chunk(hc[t][k], A.h + (size_t)tok * A.H, cidx[k], live[k]);
-    }
-
-    for (int it = 0; it < iters; it += G) {
-#pragma unroll
-        for (int s = 0; s < G; ++s) {
-            const int r = wave + (it + s) * n_waves;
-            float u[NT], v[NT];
-#pragma unroll
-            for (int t = 0; t < NT; ++t) { u[t] = 0.f; v[t] = 0.f; }
-#pragma unroll
-            for (int k = 0; k < KCH; ++k) {
-                const float s1 = live[k] ? lo_half(ring[s].m1[k]) : 0.f, z1 = hi_half(ring[s].m1[k]);
-                const float s3 = live[k] ? lo_half(ring[s].m3[k]) : 0.f, z3 = hi_half(ring[s].m3[k]);
-#pragma unroll
-                for (int t = 0; t < NT; ++t) {
-                    const float d1 = dot_q4(ring[s].q1[k], hc[t][k], -hc[t][k].bias_dot);
-                    const float d3 = dot_q4(ring[s].q3[k], hc[t][k], -hc[t][k].bias_dot);
-                    u[t] = fmaf(s1, fmaf(-z1, hc[t][k].hsum, d1), u[t]);
-                    v[t] = fmaf(s3, fmaf(-z3, hc[t][k].hsum, d3), v[t]);
-                }
-            }
-            load_row(ring[s], min(r + G * n_waves, last));
-#pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                const float us = wave_sum_l63(u[t]), vs = wave_sum_l63(v[t]);
-                if (lane == 63 && t < en.n_tok && r < A.F) {
-                    const _Float16 av = (_Float16)silu_mul(us, vs);
-                    A.a[(size_t)en.pair[t] * A.F + r] = __builtin_bit_cast(uint16_t, av);
-                }
-            }
-        }
-    }
-}
-
-struct Row2 {
-    uint4 q;
-    uint32_t m;
-};
-
-// K3: yacc[tok][r] += w * (W2^ a[pair])[r].  grid = (row blocks, entries); block = CS waves, wave cs
-// owns column chunk cs*64 + lane of every row of the block (G rows in flight); partial sums meet in LDS.
-template <int NT, int G>
-__global__ __launch_bounds__(1024) void k_w2_q4(FfnArgs A)
-{
-    extern __shared__ float red[];                       // [rows_per_block][NT][CS]
-    const FfnEntry &en = A.e[blockIdx.y];
-    const int lane = threadIdx.x & 63, cs = threadIdx.x >> 6, CS = blockDim.x >> 6;
-    const int n_chunks = A.F / 32;
-    const int c = cs * 64 + lane;
-    const bool live = c < n_chunks;
-    const int cc = live ? c : 0;
-    const int gshift = (A.group == 32) ? 0 : (A.group == 64 ? 1 : 2);
-    const int R = A.rows_per_block;
-    const int row0 = blockIdx.x * R;
-    const int row_end = min(row0 + R, A.H);
-    const uint8_t *base = en.blob + A.off_w2;
-
-    auto load_row = [&](Row2 &rb, int row) {
-        const uint8_t *rp = base + (size_t)row * A.stride2;
-        rb.q = ldw4(rp, cc);
-        rb.m = ldw1(rp + A.meta2, cc >> gshift);
-    };
-    // rows past the block's end are clamped (redundant cached reads) and their results dropped: no branch around a load
-    const int last = row_end - 1;
-    Row2 ring[G];
-#pragma unroll
-    for (int s = 0; s < G; ++s) load_row(ring[s], min(row0 + s, last));
-
-    Chunk ac[NT];
-#pragma unroll
-    for (int t = 0; t < NT; ++t) load_chunk(ac[t], A.a + (size_t)en.pair[t < en.n_tok ? t : 0] * A.F, cc, live);
-
-    for (int rbase = row0; rbase < row_end; rbase += G) {
-#pragma unroll
-        for (int s = 0; s < G; ++s) {
-            const int row = rbase + s;
-            const float sc = live ? lo_half(ring[s].m) : 0.f, z = hi_half(ring[s].m);
-            float part[NT];
-#pragma unroll
-            for (int t = 0; t < NT; ++t) part[t] = sc * fmaf(-z, ac[t].hsum, dot_q4(ring[s].q, ac[t], -ac[t].bias_dot));
-            load_row(ring[s], min(row + G, last));
-#pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                const float p = wave_sum_l63(part[t]);
-                if (lane == 63 && row < row_end) red[((row - row0) * NT + t) * CS + cs] = p;
-            }
-        }
-    }
-    __syncthreads();
-    for (int i = threadIdx.x; i < (row_end - row0) * NT; i += blockDim.x) {
-        const int rr = i / NT, t = i % NT;
-        if (t < en.n_tok) {
-            float s = 0.f;
-            for (int k = 0; k < CS; ++k) s += red[i * CS + k];
-            atomicAdd(&A.yacc[(size_t)en.tok[t] * A.H + row0 + rr], en.w[t] * s);
-        }
-    }
-}
-
-template <int CH>
-struct RowW2 {
-    uint4 q[CH];
-    uint32_t m[CH];
-};
-
-// K3, row-per-wave form for few tokens per expert: a wave owns whole rows of W2 (CH = ceil(F / 2048)
-// chunks per lane), keeps the complete activation vector a[pair] in registers (affordable because the
-// kernel runs at one wave per SIMD), and needs no LDS and no block-level synchronisation.
-// grid = (row blocks, entries), block = 4 waves; rows r = wave_id, wave_id + n_waves, ... with G in flight.
-template <int CH, int NT, int G>
-__global__ __launch_bounds__(W13_WAVES *WAVE) void k_w2_rows_q4(FfnArgs A)
-{
-    const FfnEntry &en = A.e[blockIdx.y];
-    const int lane = threadIdx.x & 63;
-    const int wave = blockIdx.x * W13_WAVES + (threadIdx.x >> 6), n_waves = gridDim.x * W13_WAVES;
-    const int n_chunks = A.F / 32;
-    const int gshift = (A.group == 32) ? 0 : (A.group == 64 ? 1 : 2);
-    const uint8_t *base = en.blob + A.off_w2;
-
-    int cidx[CH];
-    bool live[CH];
-#pragma unroll
-    for (int k = 0; k < CH; ++k) {
-        live[k] = k * 64 + lane < n_chunks;
-        cidx[k] = live[k] ? k * 64 + lane : 0;
-    }
-    auto load_row = [&](RowW2<CH> &rb, int r) {
-        const uint8_t *rp = base + (size_t)r * A.stride2;
-#pragma unroll
-        for (int k = 0; k < CH; ++k) {
-            rb.q[k] = ldw4(rp, cidx[k]);
-            rb.m[k] = ldw1(rp + A.meta2, cidx[k] >> gshift);
-        }
-    };
-    const int last = A.H - 1;
-    const int iters = (A.H + n_waves - 1) / n_waves;
-    RowW2<CH> ring[G];
-#pragma unroll
-    for (int s = 0; s < G; ++s) load_row(ring[s], min(wave + s * n_waves, last));
-
-    Chunk ac[NT][CH];
-#pragma unroll
-    for (int t = 0; t < NT; ++t) {
-        const uint16_t *av = A.a + (size_t)en.pair[t < en.n_tok ? t : 0] * A.F;
-#pragma unroll
-        for (int k = 0; k < CH; ++k) load_chunk(ac[t][k], av, cidx[k], live[k]);
-    }
-
-    for (int it = 0; it < iters; it += G) {
-#pragma unroll
-        for (int s = 0; s < G; ++s) {
-            const int r = wave + (it + s) * n_waves;
-            float acc[NT];
-#pragma unroll
-            for (int t = 0; t < NT; ++t) acc[t] = 0.f;
-#pragma unroll
-            for (int k = 0; k < CH; ++k) {
-                const float sc = live[k] ? lo_half(ring[s].m[k]) : 0.f, z = hi_half(ring[s].m[k]);
-#pragma unroll
-                for (int t = 0; t < NT; ++t)
-                    acc[t] = fmaf(sc, fmaf(-z, ac[t][k].hsum, dot_q4(ring[s].q[k], ac[t][k], -ac[t][k].bias_dot)), acc[t]);
-            }
-            load_row(ring[s], min(r + G * n_waves, last));
-#pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                const float y = wave_sum_l63(acc[t]);
-                if (lane == 63 && t < en.n_tok && r < A.H) atomicAdd(&A.yacc[(size_t)en.tok[t] * A.H + r], en.w[t] * y);
-            }
-        }
-    }
-}
-
-// x_out = fp16(x + yacc)
-__global__ void k_residual(const uint16_t *x, const float *yacc, uint16_t *x_out, int n)
-{
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) {
-        const float v = (float)__builtin_bit_cast(_Float16, x[i]) + yacc[i];
-        x_out[i] = __builtin_bit_cast(uint16_t, (_Float16)v);
-    }
-}
-
-// ---------------------------------------------------------------------------------------------
-// calibration probes: plain streaming read and plain copy of a device buffer
-// ---------------------------------------------------------------------------------------------
-
-// Every thread reads uint4s grid-strided, 4 in flight; the xor of everything lands in out[block] so the
-// loads cannot be dropped.  n16 = number of 16-byte words.
-__global__ __launch_bounds__(256) void k_probe_read(const uint4 *src, size_t n16, uint32_t *out)
-{
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
-    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    uint32_t acc = 0;
-    for (; i + 7 * stride < n16; i += 8 * stride) {
-        uint4 v[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) v[j] = ldw4(src + i + j * stride, 0);
-#pragma unroll
-        for (int j = 0; j < 8; ++j) acc ^= v[j].x ^ v[j].y ^ v[j].z ^ v[j].w;
-    }
-    for (; i < n16; i += stride) {
-        const uint4 a = src[i];
-        acc ^= a.x ^ a.y ^ a.z ^ a.w;
-    }
-    if (acc == 0x9e3779b9u) out[blockIdx.x] = acc;      // practically never: keeps the loads alive without a store stream
-}
-
-__global__ __launch_bounds__(256) void k_probe_copy(const uint4 *src, uint4 *dst, size_t n16)
-{
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
-}
-
-}  // namespace moe
+#include "kernels_common.h"
+#include "kernels_gate.h"
+#include "kernels_gemv.h"

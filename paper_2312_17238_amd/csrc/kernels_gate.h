@@ -1,0 +1,155 @@
+// Gate kernel: RMSNorm + linear gate + top-k, plus the next layer's gate for speculative loading
+// (Sec. 2.1, Sec. 3.2), all decisions in fp64.
+#pragma once
+#include "kernels_common.h"
+
+namespace moe {
+
+// ---------------------------------------------------------------------------------------------
+// K1: RMSNorm + gate + top-k (+ next layer's gate for speculative loading)
+// ---------------------------------------------------------------------------------------------
+
+struct GateHostOut {                // lives in host-mapped pinned memory; written by the kernel
+    int32_t idx[64 * 4];            // [b*K + j]
+    float w[64 * 4];
+    double logits[64 * 16];         // [b*E + e]
+    double spec_p[64 * 16];         // [b*E2 + e] next-layer gate probabilities per token
+    uint32_t done;                  // incremented once per block, system scope, after its results
+};
+
+struct GateArgs {
+    const uint16_t *x;              // [B][H] fp16
+    const float *wg;                // [E][H] fp32 or null (speculative gate only)
+    const float *wg2;               // [E2][H] fp32 or null
+    const uint16_t *gamma;          // [H] fp16 or null (gain 1)
+    uint16_t *h_out;                // [B][H] fp16 or null
+    uint16_t *h_out2;               // optional second copy
+    float *yacc;                    // [B][H] fp32 to clear, or null
+    GateHostOut *out;
+    double eps;                     // 0: no norm
+    int32_t H, E, E2, K;
+};
+
+constexpr int GATE_THREADS = 1024;
+constexpr int GATE_WAVES = GATE_THREADS / WAVE;
+
+// One block per token, 4 consecutive elements per thread and pass.  All decisions are taken in fp64:
+// the products fp32 x fp16 are exact in fp64 and the sums differ from any other fp64 summation order
+// only at the 1e-16 level, so routing equals an fp64 reference except on ties closer than that.
+__global__ __launch_bounds__(GATE_THREADS) void k_gate(GateArgs a)
+{
+    __shared__ double red[GATE_WAVES][32];
+    __shared__ double tot[33];
+    const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const uint16_t *x = a.x + (size_t)b * a.H;
+    const int n1 = a.wg ? a.E : 0, n2 = a.wg2 ? a.E2 : 0;
+
+    double scale = 1.0;
+    if (a.eps > 0.0) {
+        double ss = 0.0;
+        for (int i = tid * 4; i < a.H; i += GATE_THREADS * 4) {
+            const uint2 p = *reinterpret_cast<const uint2 *>(x + i);
+            const double v0 = half_bits_to_f64(p.x & 0xffff), v1 = half_bits_to_f64(p.x >> 16);
+            const double v2 = half_bits_to_f64(p.y & 0xffff), v3 = half_bits_to_f64(p.y >> 16);
+            ss += v0 * v0; ss += v1 * v1; ss += v2 * v2; ss += v3 * v3;
+        }
+        ss = wave_sum_f64(ss);
+        if (lane == 0) red[wv][0] = ss;
+        __syncthreads();
+        if (tid == 0) {
+            double t = 0.0;
+            for (int w = 0; w < GATE_WAVES; ++w) t += red[w][0];
+            tot[32] = 1.0 / sqrt(t / (double)a.H + a.eps);
+        }
+        __syncthreads();
+        scale = tot[32];
+    }
+
+    double acc[32];
+#pragma unroll
+    for (int e = 0; e < 32; ++e) acc[e] = 0.0;
+    for (int i = tid * 4; i < a.H; i += GATE_THREADS * 4) {
+        const uint2 p = *reinterpret_cast<const uint2 *>(x + i);
+        uint16_t hv[4] = {(uint16_t)(p.x & 0xffff), (uint16_t)(p.x >> 16), (uint16_t)(p.y & 0xffff), (uint16_t)(p.y >> 16)};
+        if (a.eps > 0.0) {
+            uint2 g = make_uint2(0x3c003c00u, 0x3c003c00u);
+            if (a.gamma) g = *reinterpret_cast<const uint2 *>(a.gamma + i);
+            const uint16_t gv[4] = {(uint16_t)(g.x & 0xffff), (uint16_t)(g.x >> 16), (uint16_t)(g.y & 0xffff), (uint16_t)(g.y >> 16)};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) hv[j] = f64_to_f16_rne(half_bits_to_f64(hv[j]) * scale * half_bits_to_f64(gv[j]));
+        }
+        const uint2 ho = make_uint2((uint32_t)hv[0] | (uint32_t)hv[1] << 16, (uint32_t)hv[2] | (uint32_t)hv[3] << 16);
+        if (a.h_out) *reinterpret_cast<uint2 *>(a.h_out + (size_t)b * a.H + i) = ho;
+        if (a.h_out2) *reinterpret_cast<uint2 *>(a.h_out2 + (size_t)b * a.H + i) = ho;
+        if (a.yacc) *reinterpret_cast<float4 *>(a.yacc + (size_t)b * a.H + i) = make_float4(0.f, 0.f, 0.f, 0.f);
+        const double h0 = half_bits_to_f64(hv[0]), h1 = half_bits_to_f64(hv[1]), h2 = half_bits_to_f64(hv[2]),
+                     h3 = half_bits_to_f64(hv[3]);
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+            if (e < n1) {
+                const float4 w = *reinterpret_cast<const float4 *>(a.wg + (size_t)e * a.H + i);
+                acc[e] += (double)w.x * h0; acc[e] += (double)w.y * h1; acc[e] += (double)w.z * h2; acc[e] += (double)w.w * h3;
+            }
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+            if (e < n2) {
+                const float4 w = *reinterpret_cast<const float4 *>(a.wg2 + (size_t)e * a.H + i);
+                acc[16 + e] += (double)w.x * h0; acc[16 + e] += (double)w.y * h1; acc[16 + e] += (double)w.z * h2; acc[16 + e] += (double)w.w * h3;
+            }
+    }
+#pragma unroll
+    for (int e = 0; e < 32; ++e) {
+        const bool live = (e < 16) ? (e < n1) : (e - 16 < n2);
+        if (live) {
+            const double v = wave_sum_f64(acc[e]);
+            if (lane == 0) red[wv][e] = v;
+        }
+    }
+    __syncthreads();
+    if (tid < 32) {
+        const bool live = (tid < 16) ? (tid < n1) : (tid - 16 < n2);
+        if (live) {
+            double t = 0.0;
+            for (int w = 0; w < GATE_WAVES; ++w) t += red[w][tid];
+            tot[tid] = t;
+        }
+    }
+    __syncthreads();
+    if (tid == 0) {
+        GateHostOut *o = a.out;
+        if (n1) {
+            // top-K by (logit descending, index ascending)
+            int chosen[4];
+            for (int j = 0; j < a.K; ++j) {
+                int best = -1;
+                for (int e = 0; e < n1; ++e) {
+                    bool used = false;
+                    for (int q = 0; q < j; ++q) used |= (chosen[q] == e);
+                    if (used) continue;
+                    if (best < 0 || tot[e] > tot[best]) best = e;
+                }
+                chosen[j] = best;
+            }
+            // softmax over all experts, renormalised over the chosen ones == softmax over the chosen logits
+            const double zmax = tot[chosen[0]];
+            double p[4], ps = 0.0;
+            for (int j = 0; j < a.K; ++j) { p[j] = exp(tot[chosen[j]] - zmax); ps += p[j]; }
+            for (int j = 0; j < a.K; ++j) {
+                o->idx[b * a.K + j] = chosen[j];
+                o->w[b * a.K + j] = (float)(p[j] / ps);
+            }
+            for (int e = 0; e < n1; ++e) o->logits[b * n1 + e] = tot[e];
+        }
+        if (n2) {
+            double zmax = tot[16];
+            for (int e = 1; e < n2; ++e) zmax = tot[16 + e] > zmax ? tot[16 + e] : zmax;
+            double pe[16], ps = 0.0;
+            for (int e = 0; e < n2; ++e) { pe[e] = exp(tot[16 + e] - zmax); ps += pe[e]; }
+            for (int e = 0; e < n2; ++e) o->spec_p[b * n2 + e] = pe[e] / ps;
+        }
+        __threadfence_system();
+        __hip_atomic_fetch_add(&o->done, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+    }
+}
+
+}  // namespace moe

@@ -15,10 +15,12 @@
 // (scale, zero) pair, 8 bytes per group; element i sits at bit 2*(i/2) of the low (i even) or
 // high (i odd) half-word.
 //
-// 3-bit codes (group 64): stored as a 2-bit plane (low two bits, packed like the 2-bit format,
-// 16 per word) and a 1-bit plane (the high bit, 32 per word: element i at bit i/2 of the low or
-// high half-word); per row: all 2-bit-plane words, then all 1-bit-plane words, then the pairs.
-// 3.0 bits per weight, the same as dense packing.
+// 3-bit codes (group 64): a row is three regions, each indexed by the group (64 consecutive codes):
+// region A, 16 bytes per group; region B, 8 bytes per group; then the (scale, zero) pairs, 4 bytes per
+// group.  With T_j (j = 0..7) the eight 32-bit words the 64 codes would occupy in the 4-bit layout above
+// (3-bit value in each nibble), A_i = (T_2i & 0x33333333) | (T_2i+1 & 0x33333333) << 2 holds the low two
+// bits of two such words and B_i = sum_j ((T_4i+j >> 2) & 0x11111111) << j the third bits of four, so a
+// decoder rebuilds T_j with three bit operations and reuses the 4-bit arithmetic.  3.0 bits per weight.
 #pragma once
 #include <cstdint>
 #include <cstring>
@@ -52,6 +54,10 @@ inline MatLayout mat_layout(uint32_t rows, uint32_t cols, int bits, int group)
         m.code_bytes = groups * 8;
         m.meta_off = 0;
         m.row_stride = align_up(m.code_bytes, 16);
+    } else if (bits == 3) {                // per group of 64: 16 B (region A) + 8 B (region B) + 4 B pair
+        m.code_bytes = groups * 24;
+        m.meta_off = m.code_bytes;
+        m.row_stride = align_up(groups * 28, 16);
     } else {
         m.code_bytes = cols * bits / 8;
         m.meta_off = m.code_bytes;
@@ -118,21 +124,23 @@ inline void pack_row(const BlobLayout &b, const MatLayout &m, const uint8_t *cod
             w[2 * g + 1] = (uint32_t)scale[g] | (uint32_t)zero[g] << 16;
         }
         return;
-    } else {  // 3-bit: 2-bit plane then 1-bit plane
-        uint32_t *lo = w, *hi = w + cols / 16;
-        for (uint32_t i = 0; i < cols / 16; ++i) {
-            const uint8_t *c = codes + 16 * i;
-            uint32_t v = 0;
-            for (int n = 0; n < 8; ++n)
-                v |= (uint32_t)(c[2 * n] & 3) << (2 * n) | (uint32_t)(c[2 * n + 1] & 3) << (16 + 2 * n);
-            lo[i] = v;
-        }
-        for (uint32_t i = 0; i < cols / 32; ++i) {
-            const uint8_t *c = codes + 32 * i;
-            uint32_t v = 0;
-            for (int n = 0; n < 16; ++n)
-                v |= (uint32_t)((c[2 * n] >> 2) & 1) << n | (uint32_t)((c[2 * n + 1] >> 2) & 1) << (16 + n);
-            hi[i] = v;
+    } else {  // 3-bit: regions A and B per group of 64
+        uint32_t *ra = w, *rb = w + groups * 4;
+        for (uint32_t g = 0; g < groups; ++g) {
+            const uint8_t *c = codes + 64 * g;
+            uint32_t t[8];
+            for (int j = 0; j < 8; ++j) {
+                uint32_t v = 0;
+                for (int n = 0; n < 4; ++n)
+                    v |= (uint32_t)(c[8 * j + 2 * n] & 7) << (4 * n) | (uint32_t)(c[8 * j + 2 * n + 1] & 7) << (16 + 4 * n);
+                t[j] = v;
+            }
+            for (int i = 0; i < 4; ++i) ra[4 * g + i] = (t[2 * i] & 0x33333333u) | (t[2 * i + 1] & 0x33333333u) << 2;
+            for (int i = 0; i < 2; ++i) {
+                uint32_t v = 0;
+                for (int j = 0; j < 4; ++j) v |= ((t[4 * i + j] >> 2) & 0x11111111u) << j;
+                rb[2 * g + i] = v;
+            }
         }
     }
     uint32_t *meta = reinterpret_cast<uint32_t *>(dst + m.meta_off);
@@ -153,10 +161,10 @@ inline void peek_row(const BlobLayout &b, const MatLayout &m, const uint8_t *src
         *code = (v >> (2 * (i / 2) + 16 * (i & 1))) & 3;
         meta = w[2 * g + 1];
     } else {
-        uint32_t v = w[col / 16], i = col % 16;
-        uint32_t low = (v >> (2 * (i / 2) + 16 * (i & 1))) & 3;
-        uint32_t u = w[m.cols / 16 + col / 32], j = col % 32;
-        uint32_t high = (u >> ((j / 2) + 16 * (j & 1))) & 1;
+        const uint32_t groups = m.cols / b.group, e = col % 64, j = e / 8, pos = e % 8;
+        const uint32_t p = 4 * (pos / 2) + 16 * (pos & 1);
+        const uint32_t low = (w[4 * g + j / 2] >> (p + 2 * (j & 1))) & 3;
+        const uint32_t high = (w[groups * 4 + 2 * g + j / 4] >> (p + (j % 4))) & 1;
         *code = (uint8_t)(low | high << 2);
         meta = reinterpret_cast<const uint32_t *>(src + m.meta_off)[g];
     }

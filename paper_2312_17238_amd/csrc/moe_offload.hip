@@ -96,7 +96,7 @@ struct moe_ctx {
     GateHostOut *gate_out_dev = nullptr;// the same memory as the device sees it
     hipEvent_t ev_gate = nullptr, ev_compute = nullptr;
     int32_t n_layers = 0;
-    int32_t w13_blocks = 256, w13_ring = 2, w2_rows = 32, w2_ring = 4, w2_form = 0, w2_blocks = 256;
+    int32_t w13_blocks = 256, w2_rows = 32;
     bool sync_wait = false;
 };
 
@@ -119,7 +119,7 @@ static bool ctx_cfg_ok(const moe_ctx_config_t *c)
 {
     return c && c->n_staging >= 0 && c->n_staging <= 64 && c->max_batch >= 1 && c->max_batch <= MOE_MAX_BATCH &&
            c->max_hidden >= 64 && c->max_hidden % 64 == 0 && c->max_hidden <= 8192 && c->max_ffn >= 64 &&
-           c->max_ffn % 64 == 0 && c->max_ffn <= 32768 && c->max_top_k >= 1 && c->max_top_k <= MOE_MAX_TOPK &&
+           c->max_ffn % 64 == 0 && c->max_ffn <= 16384 && c->max_top_k >= 1 && c->max_top_k <= MOE_MAX_TOPK &&
            c->max_expert_bytes > 0;
 }
 
@@ -201,9 +201,7 @@ extern "C" int32_t moe_ctx_create(const moe_ctx_config_t *cfg, void *dev_arena, 
     c->bufs.resize(cfg->n_staging);
     for (int i = 0; i < cfg->n_staging; ++i) c->pool.free_staging.push_back(i);
     c->w13_blocks = std::max(1, env_int("MOE_W13_BLOCKS", c->w13_blocks));
-    c->w13_ring = env_int("MOE_W13_RING", c->w13_ring);
     c->w2_rows = std::max(4, env_int("MOE_W2_ROWS", c->w2_rows));
-    c->w2_ring = env_int("MOE_W2_RING", c->w2_ring);
     c->sync_wait = env_int("MOE_SYNC_WAIT", 0) != 0;
     if (c->host_only) {
         c->gate_out = static_cast<GateHostOut *>(calloc(1, sizeof(GateHostOut)));
@@ -286,7 +284,6 @@ extern "C" int32_t moe_layer_create(moe_ctx_t *ctx, const moe_layer_config_t *cf
     *out = nullptr;
     if (!ctx) return fail(MOE_EINVAL, "moe_layer_create: ctx is null");
     if (!layer_cfg_ok(cfg)) return fail(MOE_EINVAL, "moe_layer_create: bad or unsupported configuration");
-    if (cfg->bits != 4) return fail(MOE_EINVAL, "moe_layer_create: only 4-bit experts have kernels so far");
     if (!gate_w_host || !pinned_host_mem) return fail(MOE_EINVAL, "moe_layer_create: null gate or host arena");
     BlobLayout lay = blob_layout(cfg->hidden, cfg->ffn, cfg->bits, cfg->group);
     if (lay.total > ctx->buf_bytes) return fail(MOE_EINVAL, "moe_layer_create: expert blob (%llu B) exceeds the context's buffer size (%llu B)", (unsigned long long)lay.total, (unsigned long long)ctx->buf_bytes);
@@ -651,68 +648,49 @@ static int32_t launch_gate(moe_ctx *c, const GateArgs &ga, int32_t batch)
     return wait_gate(c, (uint32_t)batch);
 }
 
-template <int KCH, int NT>
-static int32_t launch_w13_g(moe_ctx *c, int g, uint64_t bytes, dim3 grid, const FfnArgs &A)
+// Activation registers per (chunk, token) of each format: the budget that limits tokens per entry.
+template <int BITS> constexpr int act_regs() { return BITS == 3 ? 34 : (BITS == 2 ? 20 : 18); }
+constexpr int ACT_REG_BUDGET = 160;
+
+static int chunks_per_lane(int cols, int bits)      // 64-lane passes over one row (1, 2 or 4; 0 = too wide)
 {
-    const dim3 block(W13_WAVES * WAVE);
-    if constexpr (KCH * NT >= 8) {
-        return launch_timed(c, PROF_W13, bytes, k_w13_q4<KCH, NT, 1>, grid, block, 0, A);
-    } else if constexpr (KCH * NT >= 4) {
-        if (g >= 2) return launch_timed(c, PROF_W13, bytes, k_w13_q4<KCH, NT, 2>, grid, block, 0, A);
-        return launch_timed(c, PROF_W13, bytes, k_w13_q4<KCH, NT, 1>, grid, block, 0, A);
-    } else {
-        if (g >= 4) return launch_timed(c, PROF_W13, bytes, k_w13_q4<KCH, NT, 4>, grid, block, 0, A);
-        if (g >= 2) return launch_timed(c, PROF_W13, bytes, k_w13_q4<KCH, NT, 2>, grid, block, 0, A);
-        return launch_timed(c, PROF_W13, bytes, k_w13_q4<KCH, NT, 1>, grid, block, 0, A);
-    }
+    const int n = (cols / (bits == 3 ? 64 : 32) + 63) / 64;
+    return n <= 1 ? 1 : (n <= 2 ? 2 : (n <= 4 ? 4 : 0));
 }
 
-template <int KCH>
-static int32_t launch_w13(moe_ctx *c, int nt, int g, uint64_t bytes, dim3 grid, const FfnArgs &A)
+static int max_tokens_per_entry(int hidden, int bits)
 {
-    if (nt == 1) return launch_w13_g<KCH, 1>(c, g, bytes, grid, A);
-    if (nt == 2) return launch_w13_g<KCH, 2>(c, g, bytes, grid, A);
-    if constexpr (KCH <= 2) return launch_w13_g<KCH, 4>(c, g, bytes, grid, A);
-    return fail(MOE_EINVAL, "no kernel for this shape and batch");
+    const int kch = std::max(1, chunks_per_lane(hidden, bits));
+    const int regs = bits == 3 ? 34 : (bits == 2 ? 20 : 18);
+    const int n = ACT_REG_BUDGET / (kch * regs);
+    return n >= 4 ? 4 : (n >= 2 ? 2 : 1);
 }
 
-template <int NT>
-static int32_t launch_w2(moe_ctx *c, int g, uint64_t bytes, dim3 grid, dim3 block, size_t shm, const FfnArgs &A)
+template <int BITS, int KCH, int NT>
+static int32_t launch_w13_t(moe_ctx *c, uint64_t bytes, dim3 grid, const FfnArgs &A)
 {
-    if (g >= 16) return launch_timed(c, PROF_W2, bytes, k_w2_q4<NT, 16>, grid, block, shm, A);
-    if (g >= 8) return launch_timed(c, PROF_W2, bytes, k_w2_q4<NT, 8>, grid, block, shm, A);
-    return launch_timed(c, PROF_W2, bytes, k_w2_q4<NT, 4>, grid, block, shm, A);
+    if constexpr (KCH * NT * act_regs<BITS>() <= ACT_REG_BUDGET)
+        return launch_timed(c, PROF_W13, bytes, k_w13<BITS, KCH, NT, 2>, grid, dim3(W13_WAVES * WAVE), 0, A);
+    else
+        return fail(MOE_EINVAL, "no w1/w3 kernel for %d chunks per lane and %d tokens per entry", KCH, NT);
 }
 
-template <int NT, int CH>
-static int32_t launch_w2_rows_g(moe_ctx *c, int g, uint64_t bytes, dim3 grid, const FfnArgs &A)
+template <int BITS, int KCH>
+static int32_t launch_w13_k(moe_ctx *c, int nt, uint64_t bytes, dim3 grid, const FfnArgs &A)
 {
-    const dim3 block(W13_WAVES * WAVE);
-    if (g >= 4 && CH * NT <= 8) return launch_timed(c, PROF_W2, bytes, k_w2_rows_q4<CH, NT, 4>, grid, block, 0, A);
-    if (g >= 3 && CH * NT <= 8) return launch_timed(c, PROF_W2, bytes, k_w2_rows_q4<CH, NT, 3>, grid, block, 0, A);
-    if (g >= 2) return launch_timed(c, PROF_W2, bytes, k_w2_rows_q4<CH, NT, 2>, grid, block, 0, A);
-    return launch_timed(c, PROF_W2, bytes, k_w2_rows_q4<CH, NT, 1>, grid, block, 0, A);
+    if (nt == 1) return launch_w13_t<BITS, KCH, 1>(c, bytes, grid, A);
+    if (nt == 2) return launch_w13_t<BITS, KCH, 2>(c, bytes, grid, A);
+    return launch_w13_t<BITS, KCH, 4>(c, bytes, grid, A);
 }
 
-template <int NT>
-static int32_t launch_w2_rows(moe_ctx *c, int ch, int g, uint64_t bytes, dim3 grid, const FfnArgs &A)
-{
-    switch (ch) {
-    case 1: return launch_w2_rows_g<NT, 1>(c, g, bytes, grid, A);
-    case 2: return launch_w2_rows_g<NT, 2>(c, g, bytes, grid, A);
-    case 4: return launch_w2_rows_g<NT, 4>(c, g, bytes, grid, A);
-    case 7: return launch_w2_rows_g<NT, 7>(c, g, bytes, grid, A);
-    default: return launch_w2_rows_g<NT, 8>(c, g, bytes, grid, A);
-    }
-}
-
-static int32_t launch_ffn(moe_layer *l, const std::vector<FfnEntry> &entries, int nt)
+template <int BITS>
+static int32_t launch_ffn_fmt(moe_layer *l, const std::vector<FfnEntry> &entries, int nt)
 {
     moe_ctx *c = l->ctx;
     const BlobLayout &b = l->lay;
-    const int kch = (b.hidden / 32 + 63) / 64 > 2 ? 4 : (b.hidden / 32 + 63) / 64;   // chunks per lane per w1/w3 row
-    const int cs = (b.ffn / 32 + 63) / 64;                                           // waves per block for w2
-    if ((b.hidden / 32 + 63) / 64 > 4 || cs > 16) return fail(MOE_EINVAL, "shape too large for the GEMV kernels");
+    const int kch = chunks_per_lane(b.hidden, BITS);                          // per w1/w3 row
+    const int cs = (b.ffn / Fmt<BITS>::CODES + 63) / 64;                      // waves per block for w2
+    if (kch == 0 || cs > 8) return fail(MOE_EINVAL, "shape too large for the GEMV kernels");
     for (size_t first = 0; first < entries.size(); first += MAX_ENTRIES) {
         const int n = (int)std::min<size_t>(MAX_ENTRIES, entries.size() - first);
         FfnArgs A{};
@@ -735,27 +713,28 @@ static int32_t launch_ffn(moe_layer *l, const std::vector<FfnEntry> &entries, in
         const int bx = std::max(1, std::min((b.ffn + W13_WAVES - 1) / W13_WAVES, c->w13_blocks / n));
         const dim3 g13(bx, n);
         int32_t rc;
-        if (kch == 1) rc = launch_w13<1>(c, nt, c->w13_ring, bytes13, g13, A);
-        else if (kch == 2) rc = launch_w13<2>(c, nt, c->w13_ring, bytes13, g13, A);
-        else rc = launch_w13<4>(c, nt, c->w13_ring, bytes13, g13, A);
+        if (kch == 1) rc = launch_w13_k<BITS, 1>(c, nt, bytes13, g13, A);
+        else if (kch == 2) rc = launch_w13_k<BITS, 2>(c, nt, bytes13, g13, A);
+        else rc = launch_w13_k<BITS, 4>(c, nt, bytes13, g13, A);
         if (rc) return rc;
-        if (c->w2_form == 1 && nt <= 2 && cs <= 8) {
-            // row-per-wave form: whole activation vector in registers
-            const int bx2 = std::max(1, std::min((b.hidden + W13_WAVES - 1) / W13_WAVES, c->w2_blocks / n));
-            const dim3 gr(bx2, n);
-            const int ch = cs <= 1 ? 1 : (cs <= 2 ? 2 : (cs <= 4 ? 4 : (cs <= 7 ? 7 : 8)));
-            if (nt == 1) rc = launch_w2_rows<1>(c, ch, c->w2_ring, bytes2, gr, A);
-            else rc = launch_w2_rows<2>(c, ch, c->w2_ring, bytes2, gr, A);
-        } else {
-            const dim3 g2((b.hidden + A.rows_per_block - 1) / A.rows_per_block, n), blk(cs * WAVE);
-            const size_t shm = (size_t)A.rows_per_block * nt * cs * sizeof(float);
-            if (nt == 1) rc = launch_w2<1>(c, c->w2_ring, bytes2, g2, blk, shm, A);
-            else if (nt == 2) rc = launch_w2<2>(c, c->w2_ring, bytes2, g2, blk, shm, A);
-            else rc = launch_w2<4>(c, c->w2_ring, bytes2, g2, blk, shm, A);
-        }
+        const dim3 g2((b.hidden + A.rows_per_block - 1) / A.rows_per_block, n), blk(cs * WAVE);
+        const size_t shm = (size_t)A.rows_per_block * nt * cs * sizeof(float);
+        if (nt == 1) rc = launch_timed(c, PROF_W2, bytes2, k_w2<BITS, 1, 4>, g2, blk, shm, A);
+        else if (nt == 2) rc = launch_timed(c, PROF_W2, bytes2, k_w2<BITS, 2, 4>, g2, blk, shm, A);
+        else rc = launch_timed(c, PROF_W2, bytes2, k_w2<BITS, 4, 4>, g2, blk, shm, A);
         if (rc) return rc;
     }
     return MOE_OK;
+}
+
+static int32_t launch_ffn(moe_layer *l, const std::vector<FfnEntry> &entries, int nt)
+{
+    switch (l->lay.bits) {
+    case 4: return launch_ffn_fmt<4>(l, entries, nt);
+    case 3: return launch_ffn_fmt<3>(l, entries, nt);
+    case 2: return launch_ffn_fmt<2>(l, entries, nt);
+    default: return fail(MOE_EINVAL, "unsupported bit width %d", l->lay.bits);
+    }
 }
 
 extern "C" int32_t moe_layer_step(moe_layer_t *l, moe_layer_t *next, const uint16_t *x_in, int32_t batch,
@@ -814,8 +793,7 @@ extern "C" int32_t moe_layer_step(moe_layer_t *l, moe_layer_t *next, const uint1
         for (int i = 0; i < batch * cf.top_k; ++i) n += (idx[i] == a.expert);
         max_tok = std::max(max_tok, n);
     }
-    int nt = max_tok == 1 ? 1 : (max_tok == 2 ? 2 : 4);
-    if (cf.hidden > 4096 && nt > 2) nt = 2;             // register budget of the widest w1/w3 variant
+    const int nt = std::min(max_tok == 1 ? 1 : (max_tok == 2 ? 2 : 4), max_tokens_per_entry(cf.hidden, cf.bits));
 
     size_t next_demand = 0;
     for (size_t p = 0; p < passes.size(); ++p) {
@@ -967,11 +945,7 @@ extern "C" int32_t moe_ctx_set_option(moe_ctx_t *c, const char *name, int32_t va
     if (!c || !name) return fail(MOE_EINVAL, "moe_ctx_set_option: null argument");
     const std::string n(name);
     if (n == "w13_blocks" && value >= 1) c->w13_blocks = value;
-    else if (n == "w13_ring" && value >= 1) c->w13_ring = value;
     else if (n == "w2_rows" && value >= 1 && value <= 256) c->w2_rows = value;
-    else if (n == "w2_ring" && value >= 1) c->w2_ring = value;
-    else if (n == "w2_form" && (value == 0 || value == 1)) c->w2_form = value;
-    else if (n == "w2_blocks" && value >= 1) c->w2_blocks = value;
     else if (n == "sync_wait") c->sync_wait = value != 0;
     else return fail(MOE_EINVAL, "moe_ctx_set_option: unknown option or bad value: %s = %d", name, value);
     return MOE_OK;

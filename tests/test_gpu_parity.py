@@ -211,3 +211,62 @@ def test_mixtral_layer_small_cache_batch4():
     _, sim, errs = run_teacher_forced(model, xs, c_ffn.expert_ffn, check_ffn=lambda t, l: True)
     say(f"mixtral layer k=4 B=4: max rel-rms {max(e[1] for e in errs):.2e}")
     model.close()
+
+
+def test_mixtral_stack_full_size_sampled():
+    """The headline workload at full size (32 layers, 256 experts of 99 MB in pinned host memory, LRU k=2,
+    prefetch m=2, b=4) in the launch configuration bench.py times: routing, cache trace and prefetch decisions
+    checked on every (token, layer); the FFN output on sampled ones the C oracle can compute one by one."""
+    c = W.CONFIGS["mixtral_stack"]
+    say("mixtral stack: build (256 experts)")
+    model = Model(c.layers, c.hidden, c.ffn, c.n_experts, c.top_k, None, c.cache_slots, c.prefetch_m, c.rms_eps,
+                  seed=c.seed, keep_layers=[])
+    T = 5
+    xs = W.hidden_ar1(c.seed, T, 1, c.hidden)
+    say("mixtral stack: teacher-forced run")
+    sample = lambda t, l: (t, l) in {(0, 0), (1, 7), (2, 19), (3, 31), (4, 12)}
+    outs, sim, errs = run_teacher_forced(model, xs, c_ffn.expert_ffn, check_ffn=sample)
+    assert len(errs) == 5
+    say(f"mixtral stack: max abs {max(e[0] for e in errs):.2e} max rel-rms {max(e[1] for e in errs):.2e}")
+    tot = model.stack.total_stats()
+    assert tot["needed"] == 2 * T * c.layers
+    assert tot["misses"] == sum(s.misses for s in sim.stats) and tot["prefetch_hits"] == sum(s.prefetch_hits for s in sim.stats)
+    # the same tokens through the asynchronous stack entry point (what bench.py calls): bit-identical outputs
+    model.stack.reset()
+    dev = model.stack.device
+    x_in = torch.empty(1, c.hidden, dtype=torch.float16, device=dev)
+    x_out = torch.empty_like(x_in)
+    for t in range(T):
+        x_in.copy_(xs[t])
+        torch.cuda.synchronize()
+        model.stack.step(x_in, x_out, None)
+        model.stack.synchronize()
+        assert (x_out.cpu().numpy().view(np.uint16) == outs[t].view(np.uint16)).all(), f"async stack differs at token {t}"
+    assert model.stack.total_stats() == tot
+    model.close()
+
+
+@pytest.mark.parametrize("formats,Bn", [([(2, 16)] * 3, 1), ([(3, 64)] * 3, 1), ([(2, 16), (3, 64), (4, 64)], 1),
+                                        ([(3, 64), (2, 16), (4, 32)], 4), ([(4, 128), (3, 64), (2, 16)], 2)])
+def test_small_stack_low_bit_formats(formats, Bn):
+    """2-bit g16 and 3-bit g64 experts (and other 4-bit group sizes), formats mixed per layer so the shared
+    buffer pool holds blobs of different sizes; LRU k=4, prefetch 2."""
+    L, H, F = len(formats), 256, 512
+    say(f"low-bit stack {formats} B={Bn}")
+    model = Model(L, H, F, 8, 2, formats, 4, 2, 1e-5, max_batch=Bn, seed=21)
+    xs = W.hidden_ar1(21, 16, Bn, H)
+    _, sim, errs = run_teacher_forced(model, xs, O.expert_ffn)
+    say(f"  max abs {max(e[0] for e in errs):.2e} max rel-rms {max(e[1] for e in errs):.2e}")
+    model.close()
+
+
+@pytest.mark.parametrize("bits,group", [(2, 16), (3, 64)])
+def test_mixtral_layer_low_bit(bits, group):
+    """One Mixtral-shaped layer with 2-bit g16 / 3-bit g64 experts, k=4, C oracle on every token."""
+    c = W.CONFIGS["mixtral_layer"]
+    say(f"mixtral layer {bits}-bit g{group}: build")
+    model = Model(1, c.hidden, c.ffn, c.n_experts, c.top_k, [(bits, group)], 4, 0, 0.0, seed=c.seed)
+    xs = W.hidden_ar1(c.seed, 4, 1, c.hidden)
+    _, sim, errs = run_teacher_forced(model, xs, c_ffn.expert_ffn)
+    say(f"  max abs {max(e[0] for e in errs):.2e} max rel-rms {max(e[1] for e in errs):.2e}")
+    model.close()

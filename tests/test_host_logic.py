@@ -32,6 +32,9 @@ def test_blob_sizes_match_the_format_arithmetic():
     P = 3 * 4096 * 14336
     assert B.moe_expert_blob_bytes(4096, 14336, 4, 64) == P // 2 + P // 64 * 4 == 99_090_432
     assert B.moe_expert_blob_bytes(256, 512, 4, 64) == 221_184
+    # 3-bit g64 (3.0 bits per code) and 2-bit g16, same metadata rule
+    assert B.moe_expert_blob_bytes(4096, 14336, 3, 64) == P * 3 // 8 + P // 64 * 4 == 77_070_336
+    assert B.moe_expert_blob_bytes(4096, 14336, 2, 16) == P // 4 + P // 16 * 4 == 88_080_384
     assert B.moe_expert_blob_bytes(4096, 14336, 5, 64) == 0
     assert B.moe_expert_blob_bytes(100, 512, 4, 64) == 0
 
@@ -99,19 +102,19 @@ def test_warm_start_reset_and_ablation_flags():
     st.close()
 
 
-@pytest.mark.parametrize("group", [32, 64, 128])
-def test_packed_blob_reads_back_every_code(group):
-    rng = np.random.default_rng(group)
+@pytest.mark.parametrize("bits,group", [(4, 32), (4, 64), (4, 128), (3, 64), (2, 16)])
+def test_packed_blob_reads_back_every_code(bits, group):
+    rng = np.random.default_rng(group + bits)
     H, F, E = 128, 256, 2
-    st = Stack([layer_config(H, F, E, 2, 4, group, 2)], [torch.zeros(E, H)], host_only=True)
+    st = Stack([layer_config(H, F, E, 2, bits, group, 2)], [torch.zeros(E, H)], host_only=True)
     lay = st.layers[0]
     mats = {}
     for e in range(E):
         for mtx, (r, c) in enumerate(((F, H), (F, H), (H, F))):
-            q = rng.integers(0, 16, size=(r, c)).astype(np.uint8)
-            if e == 0 and mtx == 0:                       # exhaustive code patterns in the first row
-                q[0, :] = np.arange(c) % 16
-                q[1, :] = (np.arange(c) // 16) % 16
+            q = rng.integers(0, 1 << bits, size=(r, c)).astype(np.uint8)
+            if e == 0 and mtx == 0:                       # exhaustive code patterns in the first rows
+                q[0, :] = np.arange(c) % (1 << bits)
+                q[1, :] = (np.arange(c) // (1 << bits)) % (1 << bits)
             s = rng.integers(0, 1 << 16, size=(r, c // group)).astype(np.uint16)
             z = rng.integers(0, 1 << 16, size=(r, c // group)).astype(np.uint16)
             mats[(e, mtx)] = (q, s, z)
@@ -122,7 +125,7 @@ def test_packed_blob_reads_back_every_code(group):
             for c in range(q.shape[1]):
                 assert B.moe_layer_peek_weight(lay, e, mtx, r, c) == (q[r, c], s[r, c // group], z[r, c // group])
     # total bytes: every expert's blob is filled completely and the blobs do not overlap
-    assert B.moe_layer_host_bytes(st.cfgs[0]) == E * B.moe_expert_blob_bytes(H, F, 4, group)
+    assert B.moe_layer_host_bytes(st.cfgs[0]) == E * B.moe_expert_blob_bytes(H, F, bits, group)
     st.close()
 
 
@@ -146,7 +149,7 @@ def test_error_codes():
                                              cache_slots=2), **kw})
     for bad in (mk(cache_slots=1), mk(cache_slots=9), mk(top_k=5), mk(n_experts=17), mk(bits=5), mk(group=48),
                 mk(hidden=96), mk(prefetch_m=5), mk(rms_eps=-1.0), mk(init_policy=2), mk(hidden=128),
-                mk(bits=3), mk(bits=2, group=16)):
+                mk(bits=3, group=32), mk(bits=2, group=64)):
         expect(B.MOE_EINVAL, B.moe_layer_create, ctx, bad, gw.ctypes.data, None, None, host.ctypes.data)
     expect(B.MOE_EINVAL, B.moe_layer_create, ctx, mk(), None, None, None, host.ctypes.data)
     expect(B.MOE_EINVAL, B.moe_layer_create, ctx, mk(), gw.ctypes.data, None, None, None)
