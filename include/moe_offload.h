@@ -221,18 +221,21 @@ int32_t moe_layer_set_flags(moe_layer_t *layer, int32_t flags);
 int32_t moe_ctx_read_y(moe_ctx_t *ctx, int32_t batch, int32_t hidden, float *y_host);
 
 /* Optional timing of the engine's own launches, with HIP events recorded on the stream each launch is
- * enqueued on (gate, w1/w3 kernel, w2 kernel: compute stream; expert copies: copy stream).
+ * enqueued on (gate, w1/w3 kernel, w2 kernel, one-launch single-token FFN kernel `ffn`: compute stream;
+ * expert copies: copy stream).
  * `bytes` are algorithmic: each distinct expert a launch touches counts its packed w1+w3 (or w2) once;
  * a copy counts the blob.  enable(1) clears the accumulators; read waits for both streams. */
 typedef struct { uint64_t launches; uint64_t bytes; double total_ms; } moe_profile_entry_t;
-typedef struct { moe_profile_entry_t gate, w13, w2, copy; } moe_profile_t;
+typedef struct { moe_profile_entry_t gate, w13, w2, copy, ffn; } moe_profile_t;
 int32_t moe_ctx_profile_enable(moe_ctx_t *ctx, int32_t on);
 int32_t moe_ctx_profile_read(moe_ctx_t *ctx, moe_profile_t *out);
 
 /* Launch-shape tuning knobs (defaults are the measured best for Mixtral shapes on MI355X):
  *   "w13_blocks" total thread blocks of the w1/w3 kernel (default 256: one per compute unit);
  *   "w2_rows"    output rows per block of the w2 kernel (default 32);
- *   "sync_wait"  1: wait for the gate result with hipStreamSynchronize instead of polling host-mapped memory. */
+ *   "sync_wait"  1: wait for the gate result with hipStreamSynchronize instead of polling host-mapped memory;
+ *   "fused"      1 (default): a single-token step runs its expert FFN, combine and residual as one persistent
+ *                launch with a grid barrier; 0: always the separate w1/w3, w2 and residual kernels. */
 int32_t moe_ctx_set_option(moe_ctx_t *ctx, const char *name, int32_t value);
 
 /* Calibration probe, independent of any context: `iters` launches of a plain streaming-read kernel over

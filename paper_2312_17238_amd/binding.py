@@ -84,7 +84,8 @@ class ProfileEntry(C.Structure):
 
 
 class Profile(C.Structure):
-    _fields_ = [("gate", ProfileEntry), ("w13", ProfileEntry), ("w2", ProfileEntry), ("copy", ProfileEntry)]
+    _fields_ = [("gate", ProfileEntry), ("w13", ProfileEntry), ("w2", ProfileEntry), ("copy", ProfileEntry),
+                ("ffn", ProfileEntry)]
 
     def as_dict(self):
         return {k: {"launches": int(getattr(self, k).launches), "bytes": int(getattr(self, k).bytes),

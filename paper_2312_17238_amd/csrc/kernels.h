@@ -3,3 +3,4 @@
 #include "kernels_common.h"
 #include "kernels_gate.h"
 #include "kernels_gemv.h"
+#include "kernels_fused.h"

@@ -135,6 +135,20 @@ __device__ __forceinline__ uint32_t ldw1(const void *p, int idx)
 #endif
 }
 
-__device__ __forceinline__ float silu_mul(float u, float v) { return u / (1.f + __expf(-u)) * v; }
+// silu(u) * v; the reciprocal is the hardware approximation (1 ulp), far below the fp16 rounding that follows
+__device__ __forceinline__ float silu_mul(float u, float v) { return u * __builtin_amdgcn_rcpf(1.f + __expf(-u)) * v; }
+
+// (a & mask) | k in one instruction.  gfx9 VOP3 encodings take no 32-bit literals and at most one scalar
+// operand, so the compiler splits this into v_and + v_or with literals; with the mask in an SGPR and k in a
+// VGPR it is a single v_and_or_b32.
+__device__ __forceinline__ uint32_t and_or(uint32_t a, uint32_t mask, uint32_t k)
+{
+    uint32_t d;
+    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "s"(mask), "v"(k));
+    return d;
+}
+
+// wave-uniform value as a scalar, so that addresses derived from it are computed on the scalar unit
+__device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
 
 }  // namespace moe

@@ -15,6 +15,7 @@ struct GateHostOut {                // lives in host-mapped pinned memory; writt
     double logits[64 * 16];         // [b*E + e]
     double spec_p[64 * 16];         // [b*E2 + e] next-layer gate probabilities per token
     uint32_t done;                  // incremented once per block, system scope, after its results
+    uint32_t ffn_error;             // set by the fused FFN kernel if its grid barrier gave up
 };
 
 struct GateArgs {

@@ -47,10 +47,10 @@ struct RowGeom {
 __device__ __forceinline__ float dot_word4(uint32_t w, const h2_t *h, float d)
 {
     const uint32_t hi = w >> 8;
-    d = __builtin_amdgcn_fdot2(as_h2((w & 0x000F000Fu) | 0x64006400u), h[0], d, false);
-    d = __builtin_amdgcn_fdot2(as_h2((w & 0x00F000F0u) | 0x54005400u), h[1], d, false);
-    d = __builtin_amdgcn_fdot2(as_h2((hi & 0x000F000Fu) | 0x64006400u), h[2], d, false);
-    d = __builtin_amdgcn_fdot2(as_h2((hi & 0x00F000F0u) | 0x54005400u), h[3], d, false);
+    d = __builtin_amdgcn_fdot2(as_h2(and_or(w, 0x000F000Fu, 0x64006400u)), h[0], d, false);
+    d = __builtin_amdgcn_fdot2(as_h2(and_or(w, 0x00F000F0u, 0x54005400u)), h[1], d, false);
+    d = __builtin_amdgcn_fdot2(as_h2(and_or(hi, 0x000F000Fu, 0x64006400u)), h[2], d, false);
+    d = __builtin_amdgcn_fdot2(as_h2(and_or(hi, 0x00F000F0u, 0x54005400u)), h[3], d, false);
     return d;
 }
 
@@ -143,14 +143,14 @@ struct Fmt<2> {
     static __device__ __forceinline__ float dot_word2(uint32_t w, const h2_t *h, float d)
     {
         const uint32_t hi = w >> 10;
-        d = __builtin_amdgcn_fdot2(as_h2((w & 0x00030003u) | 0x64006400u), h[0], d, false);
-        d = __builtin_amdgcn_fdot2(as_h2((w & 0x000C000Cu) | 0x5C005C00u), h[1], d, false);
-        d = __builtin_amdgcn_fdot2(as_h2((w & 0x00300030u) | 0x54005400u), h[2], d, false);
-        d = __builtin_amdgcn_fdot2(as_h2((w & 0x00C000C0u) | 0x4C004C00u), h[3], d, false);
-        d = __builtin_amdgcn_fdot2(as_h2((w & 0x03000300u) | 0x44004400u), h[4], d, false);
-        d = __builtin_amdgcn_fdot2(as_h2((hi & 0x00030003u) | 0x64006400u), h[5], d, false);
-        d = __builtin_amdgcn_fdot2(as_h2((hi & 0x000C000Cu) | 0x5C005C00u), h[6], d, false);
-        d = __builtin_amdgcn_fdot2(as_h2((hi & 0x00300030u) | 0x54005400u), h[7], d, false);
+        d = __builtin_amdgcn_fdot2(as_h2(and_or(w, 0x00030003u, 0x64006400u)), h[0], d, false);
+        d = __builtin_amdgcn_fdot2(as_h2(and_or(w, 0x000C000Cu, 0x5C005C00u)), h[1], d, false);
+        d = __builtin_amdgcn_fdot2(as_h2(and_or(w, 0x00300030u, 0x54005400u)), h[2], d, false);
+        d = __builtin_amdgcn_fdot2(as_h2(and_or(w, 0x00C000C0u, 0x4C004C00u)), h[3], d, false);
+        d = __builtin_amdgcn_fdot2(as_h2(and_or(w, 0x03000300u, 0x44004400u)), h[4], d, false);
+        d = __builtin_amdgcn_fdot2(as_h2(and_or(hi, 0x00030003u, 0x64006400u)), h[5], d, false);
+        d = __builtin_amdgcn_fdot2(as_h2(and_or(hi, 0x000C000Cu, 0x5C005C00u)), h[6], d, false);
+        d = __builtin_amdgcn_fdot2(as_h2(and_or(hi, 0x00300030u, 0x54005400u)), h[7], d, false);
         return d;
     }
     static __device__ __forceinline__ float contrib(const Row &r, const Act &a, bool live)
@@ -205,7 +205,7 @@ struct Fmt<3> {
             const uint32_t lo = (j & 1) ? (A[j / 2] >> 2) : A[j / 2];
             const uint32_t bsrc = B[j / 4];
             const uint32_t hb = (j % 4) == 0 ? (bsrc << 2) : ((j % 4) == 1 ? (bsrc << 1) : ((j % 4) == 2 ? bsrc : (bsrc >> 1)));
-            const uint32_t t = (lo & 0x33333333u) | (hb & 0x44444444u);
+            const uint32_t t = and_or(lo, 0x33333333u, hb & 0x44444444u);
             d = dot_word4(t, a.h + 4 * j, d);
         }
         const float s = live ? lo_half(r.m) : 0.f;
@@ -236,7 +236,7 @@ __global__ __launch_bounds__(W13_WAVES *WAVE) void k_w13(FfnArgs A)
     using F = Fmt<BITS>;
     const FfnEntry &en = A.e[blockIdx.y];
     const int lane = threadIdx.x & 63;
-    const int wave = blockIdx.x * W13_WAVES + (threadIdx.x >> 6), n_waves = gridDim.x * W13_WAVES;
+    const int wave = uniform(blockIdx.x * W13_WAVES + (threadIdx.x >> 6)), n_waves = gridDim.x * W13_WAVES;
     const int n_chunks = A.H / F::CODES;
     const RowGeom geo = row_geom<BITS>(A.meta13, A.H, A.group);
     const uint8_t *base = en.blob;
@@ -307,7 +307,7 @@ __global__ __launch_bounds__(512) void k_w2(FfnArgs A)
     using F = Fmt<BITS>;
     extern __shared__ float red[];                       // [rows_per_block][NT][CS]
     const FfnEntry &en = A.e[blockIdx.y];
-    const int lane = threadIdx.x & 63, cs = threadIdx.x >> 6, CS = blockDim.x >> 6;
+    const int lane = threadIdx.x & 63, cs = uniform(threadIdx.x >> 6), CS = blockDim.x >> 6;
     const int n_chunks = A.F / F::CODES;
     const int c = cs * 64 + lane;
     const bool live = c < n_chunks;

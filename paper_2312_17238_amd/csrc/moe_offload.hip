@@ -67,7 +67,7 @@ struct PoolBuf {
 };
 
 // Optional timing of the engine's own launches with HIP events recorded on the stream each launch goes to.
-enum { PROF_GATE = 0, PROF_W13 = 1, PROF_W2 = 2, PROF_COPY = 3, PROF_KINDS = 4 };
+enum { PROF_GATE = 0, PROF_W13 = 1, PROF_W2 = 2, PROF_COPY = 3, PROF_FFN = 4, PROF_KINDS = 5 };
 
 struct ProfKind {
     std::vector<hipEvent_t> start, stop;   // created on demand, reused after a drain
@@ -97,6 +97,10 @@ struct moe_ctx {
     hipEvent_t ev_gate = nullptr, ev_compute = nullptr;
     int32_t n_layers = 0;
     int32_t w13_blocks = 256, w2_rows = 32;
+    bool fused = true;                  // single-token steps use the one-launch FFN kernel
+    int32_t n_cu = 0;                   // compute units: grid size of the persistent kernel
+    uint32_t *barrier = nullptr;        // device counter of its grid barrier
+    uint32_t barrier_count = 0;         // value it reaches after all launches enqueued so far
     bool sync_wait = false;
 };
 
@@ -131,7 +135,7 @@ static bool layer_cfg_ok(const moe_layer_config_t *c)
            (c->init_policy == 0 || c->init_policy == 1) && blob_layout(c->hidden, c->ffn, c->bits, c->group).ok;
 }
 
-struct ScratchPlan { uint64_t staging, h, a, yacc, x0, x1, total; };
+struct ScratchPlan { uint64_t staging, h, a, yacc, x0, x1, barrier, total; };
 
 static ScratchPlan plan_scratch(const moe_ctx_config_t *c)
 {
@@ -144,6 +148,7 @@ static ScratchPlan plan_scratch(const moe_ctx_config_t *c)
     p.yacc = off; off += align_u64((uint64_t)c->max_batch * c->max_hidden * 4, 256);
     p.x0 = off;   off += align_u64((uint64_t)c->max_batch * c->max_hidden * 2, 256);
     p.x1 = off;   off += align_u64((uint64_t)c->max_batch * c->max_hidden * 2, 256);
+    p.barrier = off; off += 256;
     p.total = off;
     return p;
 }
@@ -222,7 +227,17 @@ extern "C" int32_t moe_ctx_create(const moe_ctx_config_t *cfg, void *dev_arena, 
     c->yacc = reinterpret_cast<float *>(base + p.yacc);
     c->xbuf[0] = reinterpret_cast<uint16_t *>(base + p.x0);
     c->xbuf[1] = reinterpret_cast<uint16_t *>(base + p.x1);
-    hipError_t e = hipHostMalloc(reinterpret_cast<void **>(&c->gate_out), sizeof(GateHostOut), hipHostMallocMapped);
+    c->barrier = reinterpret_cast<uint32_t *>(base + p.barrier);
+    c->fused = env_int("MOE_FUSED", 1) != 0;
+    hipError_t e = hipMemset(c->barrier, 0, 256);
+    if (e == hipSuccess) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        e = hipGetDevice(&dev);
+        if (e == hipSuccess) e = hipGetDeviceProperties(&prop, dev);
+        if (e == hipSuccess) c->n_cu = prop.multiProcessorCount;
+    }
+    if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void **>(&c->gate_out), sizeof(GateHostOut), hipHostMallocMapped);
     if (e == hipSuccess) e = hipHostGetDevicePointer(reinterpret_cast<void **>(&c->gate_out_dev), c->gate_out, 0);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_gate, hipEventDisableTiming);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_compute, hipEventDisableTiming);
@@ -487,7 +502,7 @@ extern "C" int32_t moe_ctx_profile_read(moe_ctx_t *c, moe_profile_t *out)
     if (c->host_only) return fail(MOE_ESTATE, "moe_ctx_profile_read: host-only context");
     HIPCHK(hipStreamSynchronize(c->compute));
     HIPCHK(hipStreamSynchronize(c->copy));
-    moe_profile_entry_t *dst[PROF_KINDS] = {&out->gate, &out->w13, &out->w2, &out->copy};
+    moe_profile_entry_t *dst[PROF_KINDS] = {&out->gate, &out->w13, &out->w2, &out->copy, &out->ffn};
     for (int k = 0; k < PROF_KINDS; ++k) {
         int32_t rc = prof_drain(c, k);
         if (rc) return rc;
@@ -648,6 +663,14 @@ static int32_t launch_gate(moe_ctx *c, const GateArgs &ga, int32_t batch)
     return wait_gate(c, (uint32_t)batch);
 }
 
+// Rows each wave keeps in flight (ring depth) in the w1/w3 and the w2 kernel.
+#ifndef MOE_W13_G
+#define MOE_W13_G 2
+#endif
+#ifndef MOE_W2_G
+#define MOE_W2_G 4
+#endif
+
 // Activation registers per (chunk, token) of each format: the budget that limits tokens per entry.
 template <int BITS> constexpr int act_regs() { return BITS == 3 ? 34 : (BITS == 2 ? 20 : 18); }
 constexpr int ACT_REG_BUDGET = 160;
@@ -670,7 +693,7 @@ template <int BITS, int KCH, int NT>
 static int32_t launch_w13_t(moe_ctx *c, uint64_t bytes, dim3 grid, const FfnArgs &A)
 {
     if constexpr (KCH * NT * act_regs<BITS>() <= ACT_REG_BUDGET)
-        return launch_timed(c, PROF_W13, bytes, k_w13<BITS, KCH, NT, 2>, grid, dim3(W13_WAVES * WAVE), 0, A);
+        return launch_timed(c, PROF_W13, bytes, k_w13<BITS, KCH, NT, MOE_W13_G>, grid, dim3(W13_WAVES * WAVE), 0, A);
     else
         return fail(MOE_EINVAL, "no w1/w3 kernel for %d chunks per lane and %d tokens per entry", KCH, NT);
 }
@@ -719,12 +742,49 @@ static int32_t launch_ffn_fmt(moe_layer *l, const std::vector<FfnEntry> &entries
         if (rc) return rc;
         const dim3 g2((b.hidden + A.rows_per_block - 1) / A.rows_per_block, n), blk(cs * WAVE);
         const size_t shm = (size_t)A.rows_per_block * nt * cs * sizeof(float);
-        if (nt == 1) rc = launch_timed(c, PROF_W2, bytes2, k_w2<BITS, 1, 4>, g2, blk, shm, A);
-        else if (nt == 2) rc = launch_timed(c, PROF_W2, bytes2, k_w2<BITS, 2, 4>, g2, blk, shm, A);
-        else rc = launch_timed(c, PROF_W2, bytes2, k_w2<BITS, 4, 4>, g2, blk, shm, A);
+        if (nt == 1) rc = launch_timed(c, PROF_W2, bytes2, k_w2<BITS, 1, MOE_W2_G>, g2, blk, shm, A);
+        else if (nt == 2) rc = launch_timed(c, PROF_W2, bytes2, k_w2<BITS, 2, MOE_W2_G>, g2, blk, shm, A);
+        else rc = launch_timed(c, PROF_W2, bytes2, k_w2<BITS, 4, MOE_W2_G>, g2, blk, shm, A);
         if (rc) return rc;
     }
     return MOE_OK;
+}
+
+// The one-launch path for a single token; returns MOE_OK with *done = false when the shape does not fit it.
+template <int BITS>
+static int32_t launch_fused_fmt(moe_layer *l, const FusedArgs &A0, bool *done)
+{
+    moe_ctx *c = l->ctx;
+    const BlobLayout &b = l->lay;
+    const int kch = chunks_per_lane(b.hidden, BITS);
+    const int cs = (b.ffn / Fmt<BITS>::CODES + 63) / 64;
+    const int grid = c->n_cu;
+    const int rows = (b.hidden + grid - 1) / grid;
+    *done = false;
+    if (kch == 0 || kch > 2 || (BITS == 3 && kch > 1) || cs > 8 || cs * A0.n_exp > FUSED_WAVES || rows > 64 || grid < 1)
+        return MOE_OK;
+    FusedArgs A = A0;
+    A.rows_per_block = rows;
+    A.barrier = c->barrier;
+    c->barrier_count += (uint32_t)grid;
+    A.barrier_target = c->barrier_count;
+    A.error_flag = &c->gate_out_dev->ffn_error;
+    const uint64_t bytes = (uint64_t)A.n_exp * (2 * (uint64_t)b.ffn * b.m13.row_stride + (uint64_t)b.hidden * b.m2.row_stride);
+    const dim3 g(grid), blk(FUSED_WAVES * WAVE);
+    *done = true;
+    if (kch == 1) return launch_timed(c, PROF_FFN, bytes, k_ffn_token<BITS, 1, 2, 4>, g, blk, 0, A);
+    if constexpr (BITS != 3) return launch_timed(c, PROF_FFN, bytes, k_ffn_token<BITS, 2, 2, 4>, g, blk, 0, A);
+    return fail(MOE_EINVAL, "no fused kernel for this shape");
+}
+
+static int32_t launch_fused(moe_layer *l, const FusedArgs &A, bool *done)
+{
+    switch (l->lay.bits) {
+    case 4: return launch_fused_fmt<4>(l, A, done);
+    case 3: return launch_fused_fmt<3>(l, A, done);
+    case 2: return launch_fused_fmt<2>(l, A, done);
+    default: *done = false; return MOE_OK;
+    }
 }
 
 static int32_t launch_ffn(moe_layer *l, const std::vector<FfnEntry> &entries, int nt)
@@ -795,6 +855,10 @@ extern "C" int32_t moe_layer_step(moe_layer_t *l, moe_layer_t *next, const uint1
     }
     const int nt = std::min(max_tok == 1 ? 1 : (max_tok == 2 ? 2 : 4), max_tokens_per_entry(cf.hidden, cf.bits));
 
+    if (c->gate_out->ffn_error) return fail(MOE_ESTATE, "an earlier fused FFN kernel gave up waiting at its grid barrier");
+    const bool try_fused = c->fused && batch == 1 && passes.size() == 1 && plan.access.size() <= 2 &&
+                           (int)plan.access.size() == cf.top_k && !plan.victim_needed;
+    bool fused_done = false;
     size_t next_demand = 0;
     for (size_t p = 0; p < passes.size(); ++p) {
         if (p > 0) {
@@ -819,8 +883,21 @@ extern "C" int32_t moe_layer_step(moe_layer_t *l, moe_layer_t *next, const uint1
             }
             if (en.n_tok) entries.push_back(en);
         }
-        rc = launch_ffn(l, entries, nt);
-        if (rc) return rc;
+        if (try_fused) {
+            FusedArgs fa{};
+            fa.n_exp = (int32_t)entries.size();
+            for (int i = 0; i < fa.n_exp; ++i) { fa.blob[i] = entries[i].blob; fa.w[i] = entries[i].w[0]; }
+            fa.h = c->h_buf; fa.x = x_in; fa.x_out = x_out; fa.a = c->a_buf; fa.y = c->yacc;
+            fa.H = l->lay.hidden; fa.F = l->lay.ffn; fa.group = l->lay.group;
+            fa.stride13 = l->lay.m13.row_stride; fa.meta13 = l->lay.m13.meta_off;
+            fa.stride2 = l->lay.m2.row_stride; fa.meta2 = l->lay.m2.meta_off; fa.off_w2 = l->lay.off_w2;
+            rc = launch_fused(l, fa, &fused_done);
+            if (rc) return rc;
+        }
+        if (!fused_done) {
+            rc = launch_ffn(l, entries, nt);
+            if (rc) return rc;
+        }
     }
     if (plan.victim_needed || passes.size() > 1) {
         // a buffer freed during this step may still be read by its kernels: speculative copies wait for them
@@ -828,9 +905,11 @@ extern "C" int32_t moe_layer_step(moe_layer_t *l, moe_layer_t *next, const uint1
         HIPCHK(hipStreamWaitEvent(c->copy, c->ev_compute, 0));
         for (const CopyOp &op : plan.spec) { rc = issue_copy(c, next, op); if (rc) return rc; }
     }
-    const int n = batch * cf.hidden;
-    hipLaunchKernelGGL(k_residual, dim3((n + 255) / 256), dim3(256), 0, c->compute, x_in, c->yacc, x_out, n);
-    HIPCHK(hipGetLastError());
+    if (!fused_done) {
+        const int n = batch * cf.hidden;
+        hipLaunchKernelGGL(k_residual, dim3((n + 255) / 256), dim3(256), 0, c->compute, x_in, c->yacc, x_out, n);
+        HIPCHK(hipGetLastError());
+    }
     return MOE_OK;
 }
 
@@ -947,6 +1026,7 @@ extern "C" int32_t moe_ctx_set_option(moe_ctx_t *c, const char *name, int32_t va
     if (n == "w13_blocks" && value >= 1) c->w13_blocks = value;
     else if (n == "w2_rows" && value >= 1 && value <= 256) c->w2_rows = value;
     else if (n == "sync_wait") c->sync_wait = value != 0;
+    else if (n == "fused") c->fused = value != 0;
     else return fail(MOE_EINVAL, "moe_ctx_set_option: unknown option or bad value: %s = %d", name, value);
     return MOE_OK;
 }

@@ -270,3 +270,24 @@ def test_mixtral_layer_low_bit(bits, group):
     _, sim, errs = run_teacher_forced(model, xs, c_ffn.expert_ffn)
     say(f"  max abs {max(e[0] for e in errs):.2e} max rel-rms {max(e[1] for e in errs):.2e}")
     model.close()
+
+
+@pytest.mark.parametrize("formats", [[(4, 64)] * 2, [(3, 64), (2, 16)]])
+def test_one_launch_ffn_equals_separate_kernels(formats):
+    """Single-token steps run the expert FFN as one persistent launch with a grid barrier; switching it off
+    (separate w1/w3, w2 and residual kernels) must give bit-identical outputs, traces and statistics."""
+    L, H, F = len(formats), 256, 512
+    xs = W.hidden_ar1(31, 24, 1, H)
+    outs = {}
+    for fused in (1, 0):
+        model = Model(L, H, F, 8, 2, formats, 2, 2, 1e-5, seed=31)
+        B.moe_ctx_set_option(model.stack.ctx, "fused", fused)
+        B.moe_ctx_profile_enable(model.stack.ctx, True)
+        o, sim, errs = run_teacher_forced(model, xs, O.expert_ffn)
+        prof = B.moe_ctx_profile_read(model.stack.ctx).as_dict()
+        assert (prof["ffn"]["launches"] > 0) == bool(fused) and (prof["w13"]["launches"] > 0) == (not fused)
+        outs[fused] = (o, model.stack.total_stats())
+        model.close()
+    for a, b in zip(outs[1][0], outs[0][0]):
+        assert (a.view(np.uint16) == b.view(np.uint16)).all()
+    assert outs[1][1] == outs[0][1]
