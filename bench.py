@@ -106,7 +106,8 @@ def main() -> int:
     ap.add_argument("--group", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true", help="do not record HIP events around the engine's launches")
-    ap.add_argument("--no-fused", action="store_true", help="single-token steps use the separate w1/w3, w2 and residual kernels")
+    ap.add_argument("--fused", action="store_true", help="single-token steps run w1/w3 and w2 as one persistent launch")
+    ap.add_argument("--no-token-path", action="store_true", help="single-token steps use the general kernels (atomics + residual kernel)")
     ap.add_argument("--no-probe", action="store_true", help="skip the plain streaming-read / copy calibration kernels")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -142,8 +143,10 @@ def main() -> int:
     stack, gates, gamma, kept = build_model(shape, formats, batch, device, keep_layers)
     if args.no_cache:
         stack.set_flags(B.MOE_LAYER_NO_CACHE)
-    if args.no_fused:
-        B.moe_ctx_set_option(stack.ctx, "fused", 0)
+    if args.fused:
+        B.moe_ctx_set_option(stack.ctx, "fused", 1)
+    if args.no_token_path:
+        B.moe_ctx_set_option(stack.ctx, "token_path", 0)
     xs = (W.hidden_iid if shape.hidden_kind == "iid" else W.hidden_ar1)(shape.seed, n_tok, batch, shape.hidden)
     x_dev = xs.to(device)                                   # inputs resident in HBM before the timed region
     x_out = torch.empty(batch, shape.hidden, dtype=torch.float16, device=device)

@@ -234,8 +234,11 @@ int32_t moe_ctx_profile_read(moe_ctx_t *ctx, moe_profile_t *out);
  *   "w13_blocks" total thread blocks of the w1/w3 kernel (default 256: one per compute unit);
  *   "w2_rows"    output rows per block of the w2 kernel (default 32);
  *   "sync_wait"  1: wait for the gate result with hipStreamSynchronize instead of polling host-mapped memory;
- *   "fused"      1 (default): a single-token step runs its expert FFN, combine and residual as one persistent
- *                launch with a grid barrier; 0: always the separate w1/w3, w2 and residual kernels. */
+ *   "token_path" 1 (default): a single-token step runs w2 with the combine and the residual add inside the
+ *                kernel (one block sees both experts' rows; no atomics, no separate residual kernel);
+ *                0: the general kernels also for one token;
+ *   "fused"      1: such a step runs w1/w3 and w2 as ONE persistent launch with a grid barrier (measured
+ *                slower than two launches on MI355X, hence default 0). */
 int32_t moe_ctx_set_option(moe_ctx_t *ctx, const char *name, int32_t value);
 
 /* Calibration probe, independent of any context: `iters` launches of a plain streaming-read kernel over

@@ -9,23 +9,29 @@
 // Phase 2: block b owns output rows [b*R, (b+1)*R); waves [e*CS, (e+1)*CS) own the column chunks of expert e.
 #pragma once
 #include "kernels_gemv.h"
+#ifndef MOE_FUSED_COHERENT_A
+#define MOE_FUSED_COHERENT_A 0
+#endif
+
 
 namespace moe {
 
 constexpr int FUSED_WAVES = 16;
-constexpr uint32_t BARRIER_SPIN_LIMIT = 4000000;   // polls of ~100 ns: gives up after a fraction of a second
+constexpr int FUSED_MAX_ITEMS = 64;                // (expert, row) pairs of w1/w3 per wave
+constexpr uint32_t BARRIER_SPIN_LIMIT = 2000000;   // polls of ~200 ns: gives up after a fraction of a second
 
 struct FusedArgs {
     const uint8_t *blob[2];         // the token's experts (n_exp of them)
     float w[2];                     // their combine weights
+    int32_t a_row[2];               // row of the scratch a[.][F] each expert's activations live in
     int32_t n_exp;
     const uint16_t *h;              // [H] gate input of the token
     const uint16_t *x;              // [H] residual stream in
     uint16_t *x_out;                // [H]
     uint16_t *a;                    // [n_exp][F] scratch
     float *y;                       // [H] block output before the residual add (diagnostic copy)
-    uint32_t *barrier;              // device counter, only ever incremented
-    uint32_t barrier_target;        // value the counter reaches when every block of this launch has arrived
+    uint32_t *barrier;              // device flags, one per block: the epoch of the last launch the block arrived in
+    uint32_t barrier_target;        // this launch's epoch (increases by one per launch)
     uint32_t *error_flag;           // host-visible: set if the barrier gave up
     int32_t H, F, group;
     uint32_t stride13, meta13, stride2, meta2;
@@ -35,23 +41,102 @@ struct FusedArgs {
 
 // All blocks of the grid meet here.  Bounded: a block that waits too long raises the error flag and goes
 // on (its results are then invalid, which the host reports), so every wave always reaches the kernel's end.
-__device__ __forceinline__ void grid_barrier(uint32_t *counter, uint32_t target, uint32_t *error_flag)
+//
+// Visibility of the activations a across the barrier does not use agent-scope fences (on this multi-die part
+// they write back and invalidate whole L2 slices, once per executing wave): a is written with agent-scope
+// stores (write-through) and read back with agent-scope loads (no stale copy in a die's L2 can be hit); a
+// wave only has to wait for its own stores to be acknowledged before its block arrives.
+//
+// The barrier itself avoids read-modify-write atomics (device-scope atomics are executed at the memory side
+// and 256 of them on one address serialise for ~10 us): block b publishes flags[b] = epoch with one store,
+// and every block polls all flags, one flag per thread, until none is behind the epoch.
+__device__ __forceinline__ void grid_barrier(uint32_t *flags, uint32_t epoch, uint32_t *error_flag)
 {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // this wave's stores are complete
     __syncthreads();
-    if (threadIdx.x == 0) {
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-        __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        uint32_t spins = 0;
-        while ((int32_t)(__hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - target) < 0) {
-            __builtin_amdgcn_s_sleep(4);
-            if (++spins > BARRIER_SPIN_LIMIT) {
-                __hip_atomic_store(error_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-                break;
-            }
+    if (threadIdx.x == 0) __hip_atomic_store(flags + blockIdx.x, epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    for (uint32_t spins = 0;; ++spins) {
+        int ok = 1;
+        for (uint32_t i = threadIdx.x; i < gridDim.x; i += blockDim.x)
+            ok &= (int32_t)(__hip_atomic_load(flags + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - epoch) >= 0;
+        if (__syncthreads_and(ok)) break;
+        if (spins > BARRIER_SPIN_LIMIT) {
+            if (threadIdx.x == 0) __hip_atomic_store(error_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+            break;
+        }
+        __builtin_amdgcn_s_sleep(2);
+    }
+}
+
+// the fused kernel's own activation loader: the same Act as Fmt::load_act, read with agent-scope loads
+template <int BITS>
+__device__ __forceinline__ void load_act_coherent(typename Fmt<BITS>::Act &a, const uint16_t *vec, int c, bool live)
+{
+    constexpr int N8 = Fmt<BITS>::CODES / 4;              // 8-byte words per chunk
+    __attribute__((aligned(16))) uint16_t tmp[Fmt<BITS>::CODES];
+    const uint64_t *p = reinterpret_cast<const uint64_t *>(vec + (size_t)c * Fmt<BITS>::CODES);
+#pragma unroll
+    for (int i = 0; i < N8; ++i)
+        reinterpret_cast<uint64_t *>(tmp)[i] = __hip_atomic_load(p + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    Fmt<BITS>::load_act(a, tmp, 0, live);
+}
+
+// y[r] = sum_e w_e (W2_e a_e)[r];  x_out = fp16(x + y), for the rows of this block.  Waves [e*CS, (e+1)*CS)
+// own the column chunks of expert e; BARRIER: wait for the whole grid between requesting the first rows of
+// w2 (which do not depend on a) and reading a.
+template <int BITS, int G2, bool BARRIER>
+__device__ __forceinline__ void token_w2_phase(const FusedArgs &A, float *red, int wv, int lane)
+{
+    using F = Fmt<BITS>;
+    const int n_chunks2 = A.F / F::CODES;
+    const int CS = (n_chunks2 + 63) / 64;
+    const int e2 = wv / CS, cs = wv - e2 * CS;
+    const bool active = e2 < A.n_exp;
+    const int c = cs * 64 + lane;
+    const bool live2 = active && c < n_chunks2;
+    const int cc = live2 ? c : 0;
+    const RowGeom geo2 = row_geom<BITS>(A.meta2, A.F, A.group);
+    const int R = A.rows_per_block;
+    const int row0 = blockIdx.x * R;
+    const int row_end = min(row0 + R, A.H);
+    const int last2 = max(row_end - 1, 0);
+    const uint8_t *base2 = A.blob[active ? e2 : 0] + A.off_w2;
+    typename F::Row ring2[G2];
+#pragma unroll
+    for (int s = 0; s < G2; ++s) F::load(ring2[s], base2 + (size_t)min(row0 + s, last2) * A.stride2, geo2, cc);
+
+    if (BARRIER) grid_barrier(A.barrier, A.barrier_target, A.error_flag);
+
+    typename F::Act ac;
+#if MOE_FUSED_COHERENT_A
+    load_act_coherent<BITS>(ac, A.a + (size_t)A.a_row[active ? e2 : 0] * A.F, cc, live2);
+#else
+    F::load_act(ac, A.a + (size_t)A.a_row[active ? e2 : 0] * A.F, cc, live2);
+#endif
+    for (int rbase = row0; rbase < row_end; rbase += G2) {
+#pragma unroll
+        for (int s = 0; s < G2; ++s) {
+            const int row = rbase + s;
+            const float part = F::contrib(ring2[s], ac, live2);
+            F::load(ring2[s], base2 + (size_t)min(row + G2, last2) * A.stride2, geo2, cc);
+            const float p = wave_sum_l63(part);
+            if (lane == 63 && active && row < row_end) red[(e2 * 8 + cs) * 64 + (row - row0)] = p;
         }
     }
     __syncthreads();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    const int rr = threadIdx.x;
+    if (rr < row_end - row0) {
+        float y = 0.f;
+        for (int e = 0; e < A.n_exp; ++e) {
+            float s = 0.f;
+            for (int k = 0; k < CS; ++k) s += red[(e * 8 + k) * 64 + rr];
+            y += A.w[e] * s;
+        }
+        const int row = row0 + rr;
+        A.y[row] = y;
+        const float v = (float)__builtin_bit_cast(_Float16, A.x[row]) + y;
+        A.x_out[row] = __builtin_bit_cast(uint16_t, (_Float16)v);
+    }
 }
 
 template <int BITS, int KCH, int G1, int G2>
@@ -59,6 +144,7 @@ __global__ __launch_bounds__(FUSED_WAVES *WAVE) void k_ffn_token(FusedArgs A)
 {
     using F = Fmt<BITS>;
     __shared__ float red[2 * 8 * 64];                    // [expert][cs][row], rows_per_block <= 64
+    __shared__ uint16_t a_stage[FUSED_WAVES][FUSED_MAX_ITEMS];   // a wave's outputs until the end of phase 1
     const int lane = threadIdx.x & 63;
     const int wv = uniform(threadIdx.x >> 6);
     const int gw = uniform(blockIdx.x * FUSED_WAVES + wv), n_waves = gridDim.x * FUSED_WAVES;
@@ -104,61 +190,30 @@ __global__ __launch_bounds__(FUSED_WAVES *WAVE) void k_ffn_token(FusedArgs A)
                 }
                 load_item(ring[s], min(item + G1 * n_waves, last));
                 const float us = wave_sum_l63(u), vs = wave_sum_l63(v);
-                if (lane == 63 && item < items) {
-                    const _Float16 av = (_Float16)silu_mul(us, vs);
-                    A.a[item] = __builtin_bit_cast(uint16_t, av);     // a is [n_exp][F], item = e*F + r
-                }
+                // Results wait in LDS: a global store here would sit between the loads in the in-order
+                // vmcnt queue, and an agent-scope (write-through) store is slow to be acknowledged.
+                if (lane == 63) a_stage[wv][it + s] = __builtin_bit_cast(uint16_t, (_Float16)silu_mul(us, vs));
             }
         }
-    }
-
-    // ---------------- phase 2: y[r] = sum_e w_e (W2_e a_e)[r];  x_out = fp16(x + y) ----------------
-    const int n_chunks2 = A.F / F::CODES;
-    const int CS = (n_chunks2 + 63) / 64;
-    const int e2 = wv / CS, cs = wv - e2 * CS;
-    const bool active = e2 < A.n_exp;
-    const int c = cs * 64 + lane;
-    const bool live2 = active && c < n_chunks2;
-    const int cc = live2 ? c : 0;
-    const RowGeom geo2 = row_geom<BITS>(A.meta2, A.F, A.group);
-    const int R = A.rows_per_block;
-    const int row0 = blockIdx.x * R;
-    const int row_end = min(row0 + R, A.H);
-    const int last2 = max(row_end - 1, 0);
-    const uint8_t *base2 = A.blob[active ? e2 : 0] + A.off_w2;
-    typename F::Row ring2[G2];
-    // request the first rows of w2 before the barrier: they do not depend on a
-#pragma unroll
-    for (int s = 0; s < G2; ++s) F::load(ring2[s], base2 + (size_t)min(row0 + s, last2) * A.stride2, geo2, cc);
-
-    grid_barrier(A.barrier, A.barrier_target, A.error_flag);
-
-    typename F::Act ac;
-    F::load_act(ac, A.a + (size_t)(active ? e2 : 0) * A.F, cc, live2);
-    for (int rbase = row0; rbase < row_end; rbase += G2) {
-#pragma unroll
-        for (int s = 0; s < G2; ++s) {
-            const int row = rbase + s;
-            const float part = F::contrib(ring2[s], ac, live2);
-            F::load(ring2[s], base2 + (size_t)min(row + G2, last2) * A.stride2, geo2, cc);
-            const float p = wave_sum_l63(part);
-            if (lane == 63 && active && row < row_end) red[(e2 * 8 + cs) * 64 + (row - row0)] = p;
+        // item = e*F + r goes to a[a_row[e]][r]; written with agent scope so that other dies see it after the barrier
+        const int item = gw + lane * n_waves;
+        if (lane < iters && item < items) {
+            const int e = item >= A.F ? 1 : 0;
+            __hip_atomic_store(A.a + (size_t)A.a_row[e] * A.F + (item - e * A.F), a_stage[wv][lane], __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
         }
     }
-    __syncthreads();
-    const int rr = threadIdx.x;
-    if (rr < row_end - row0) {
-        float y = 0.f;
-        for (int e = 0; e < A.n_exp; ++e) {
-            float s = 0.f;
-            for (int k = 0; k < CS; ++k) s += red[(e * 8 + k) * 64 + rr];
-            y += A.w[e] * s;
-        }
-        const int row = row0 + rr;
-        A.y[row] = y;
-        const float v = (float)__builtin_bit_cast(_Float16, A.x[row]) + y;
-        A.x_out[row] = __builtin_bit_cast(uint16_t, (_Float16)v);
-    }
+
+    token_w2_phase<BITS, G2, true>(A, red, wv, lane);
+}
+
+// The w2 half on its own (after k_w13): same combine and residual without atomics or a further kernel.
+// grid = ceil(H / rows_per_block) blocks of n_exp * CS waves.
+template <int BITS, int G2>
+__global__ __launch_bounds__(FUSED_WAVES *WAVE) void k_w2_token(FusedArgs A)
+{
+    __shared__ float red[2 * 8 * 64];
+    token_w2_phase<BITS, G2, false>(A, red, uniform(threadIdx.x >> 6), threadIdx.x & 63);
 }
 
 }  // namespace moe

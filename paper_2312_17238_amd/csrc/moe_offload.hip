@@ -79,7 +79,8 @@ struct ProfKind {
 struct Profiler {
     bool on = false;
     ProfKind kind[PROF_KINDS];
-    static constexpr size_t RING = 20000;
+    static constexpr size_t RING = 20000;      // pairs per kind before a drain (which synchronises) is needed
+    static constexpr size_t PREALLOC = 8192;   // pairs per kind created when profiling is switched on
 };
 
 struct moe_ctx {
@@ -97,7 +98,8 @@ struct moe_ctx {
     hipEvent_t ev_gate = nullptr, ev_compute = nullptr;
     int32_t n_layers = 0;
     int32_t w13_blocks = 256, w2_rows = 32;
-    bool fused = true;                  // single-token steps use the one-launch FFN kernel
+    bool token_path = true;             // single-token steps: w2 kernel with in-kernel combine + residual (no atomics)
+    bool fused = false;                 // ... and w1/w3 + w2 as one persistent launch with a grid barrier
     int32_t n_cu = 0;                   // compute units: grid size of the persistent kernel
     uint32_t *barrier = nullptr;        // device counter of its grid barrier
     uint32_t barrier_count = 0;         // value it reaches after all launches enqueued so far
@@ -148,7 +150,7 @@ static ScratchPlan plan_scratch(const moe_ctx_config_t *c)
     p.yacc = off; off += align_u64((uint64_t)c->max_batch * c->max_hidden * 4, 256);
     p.x0 = off;   off += align_u64((uint64_t)c->max_batch * c->max_hidden * 2, 256);
     p.x1 = off;   off += align_u64((uint64_t)c->max_batch * c->max_hidden * 2, 256);
-    p.barrier = off; off += 256;
+    p.barrier = off; off += 4096;     // one flag per block of the persistent kernel (at most 1024 compute units)
     p.total = off;
     return p;
 }
@@ -228,8 +230,8 @@ extern "C" int32_t moe_ctx_create(const moe_ctx_config_t *cfg, void *dev_arena, 
     c->xbuf[0] = reinterpret_cast<uint16_t *>(base + p.x0);
     c->xbuf[1] = reinterpret_cast<uint16_t *>(base + p.x1);
     c->barrier = reinterpret_cast<uint32_t *>(base + p.barrier);
-    c->fused = env_int("MOE_FUSED", 1) != 0;
-    hipError_t e = hipMemset(c->barrier, 0, 256);
+    c->fused = env_int("MOE_FUSED", 0) != 0;
+    hipError_t e = hipMemset(c->barrier, 0, 4096);
     if (e == hipSuccess) {
         int dev = 0;
         hipDeviceProp_t prop;
@@ -491,6 +493,14 @@ extern "C" int32_t moe_ctx_profile_enable(moe_ctx_t *c, int32_t on)
     for (int k = 0; k < PROF_KINDS; ++k) {
         ProfKind &p = c->prof.kind[k];
         p.used = 0; p.launches = 0; p.bytes = 0; p.ms = 0.0;
+        // create the events up front, so that no event is created inside a region the caller is timing
+        while (on && p.start.size() < Profiler::PREALLOC) {
+            hipEvent_t a, b;
+            HIPCHK(hipEventCreate(&a));
+            HIPCHK(hipEventCreate(&b));
+            p.start.push_back(a);
+            p.stop.push_back(b);
+        }
     }
     c->prof.on = on != 0;
     return MOE_OK;
@@ -670,6 +680,9 @@ static int32_t launch_gate(moe_ctx *c, const GateArgs &ga, int32_t batch)
 #ifndef MOE_W2_G
 #define MOE_W2_G 4
 #endif
+#ifndef MOE_FUSED_G2
+#define MOE_FUSED_G2 8
+#endif
 
 // Activation registers per (chunk, token) of each format: the budget that limits tokens per entry.
 template <int BITS> constexpr int act_regs() { return BITS == 3 ? 34 : (BITS == 2 ? 20 : 18); }
@@ -707,7 +720,7 @@ static int32_t launch_w13_k(moe_ctx *c, int nt, uint64_t bytes, dim3 grid, const
 }
 
 template <int BITS>
-static int32_t launch_ffn_fmt(moe_layer *l, const std::vector<FfnEntry> &entries, int nt)
+static int32_t launch_ffn_fmt(moe_layer *l, const std::vector<FfnEntry> &entries, int nt, bool w13_only)
 {
     moe_ctx *c = l->ctx;
     const BlobLayout &b = l->lay;
@@ -740,6 +753,7 @@ static int32_t launch_ffn_fmt(moe_layer *l, const std::vector<FfnEntry> &entries
         else if (kch == 2) rc = launch_w13_k<BITS, 2>(c, nt, bytes13, g13, A);
         else rc = launch_w13_k<BITS, 4>(c, nt, bytes13, g13, A);
         if (rc) return rc;
+        if (w13_only) continue;
         const dim3 g2((b.hidden + A.rows_per_block - 1) / A.rows_per_block, n), blk(cs * WAVE);
         const size_t shm = (size_t)A.rows_per_block * nt * cs * sizeof(float);
         if (nt == 1) rc = launch_timed(c, PROF_W2, bytes2, k_w2<BITS, 1, MOE_W2_G>, g2, blk, shm, A);
@@ -752,7 +766,7 @@ static int32_t launch_ffn_fmt(moe_layer *l, const std::vector<FfnEntry> &entries
 
 // The one-launch path for a single token; returns MOE_OK with *done = false when the shape does not fit it.
 template <int BITS>
-static int32_t launch_fused_fmt(moe_layer *l, const FusedArgs &A0, bool *done)
+static int32_t launch_token_fmt(moe_layer *l, const FusedArgs &A0, bool one_launch, bool probe_only, bool *done)
 {
     moe_ctx *c = l->ctx;
     const BlobLayout &b = l->lay;
@@ -761,38 +775,46 @@ static int32_t launch_fused_fmt(moe_layer *l, const FusedArgs &A0, bool *done)
     const int grid = c->n_cu;
     const int rows = (b.hidden + grid - 1) / grid;
     *done = false;
-    if (kch == 0 || kch > 2 || (BITS == 3 && kch > 1) || cs > 8 || cs * A0.n_exp > FUSED_WAVES || rows > 64 || grid < 1)
+    const int items_per_wave = (A0.n_exp * b.ffn + grid * FUSED_WAVES - 1) / (grid * FUSED_WAVES);
+    if (kch == 0 || kch > 2 || (BITS == 3 && kch > 1) || cs > 8 || cs * A0.n_exp > FUSED_WAVES || rows > 64 || grid < 1 || grid > 1024 ||
+        items_per_wave + 2 > FUSED_MAX_ITEMS)
         return MOE_OK;
+    *done = true;
+    if (probe_only) return MOE_OK;
     FusedArgs A = A0;
     A.rows_per_block = rows;
+    if (!one_launch) {
+        // w2 half only (k_w13 ran before): blocks of n_exp * CS waves, no barrier
+        const uint64_t bytes2 = (uint64_t)A.n_exp * b.hidden * b.m2.row_stride;
+        return launch_timed(c, PROF_W2, bytes2, k_w2_token<BITS, 4>, dim3((b.hidden + rows - 1) / rows),
+                            dim3(A.n_exp * cs * WAVE), 0, A);
+    }
     A.barrier = c->barrier;
-    c->barrier_count += (uint32_t)grid;
-    A.barrier_target = c->barrier_count;
+    A.barrier_target = ++c->barrier_count;
     A.error_flag = &c->gate_out_dev->ffn_error;
     const uint64_t bytes = (uint64_t)A.n_exp * (2 * (uint64_t)b.ffn * b.m13.row_stride + (uint64_t)b.hidden * b.m2.row_stride);
     const dim3 g(grid), blk(FUSED_WAVES * WAVE);
-    *done = true;
-    if (kch == 1) return launch_timed(c, PROF_FFN, bytes, k_ffn_token<BITS, 1, 2, 4>, g, blk, 0, A);
-    if constexpr (BITS != 3) return launch_timed(c, PROF_FFN, bytes, k_ffn_token<BITS, 2, 2, 4>, g, blk, 0, A);
+    if (kch == 1) return launch_timed(c, PROF_FFN, bytes, k_ffn_token<BITS, 1, 2, MOE_FUSED_G2>, g, blk, 0, A);
+    if constexpr (BITS != 3) return launch_timed(c, PROF_FFN, bytes, k_ffn_token<BITS, 2, 2, MOE_FUSED_G2>, g, blk, 0, A);
     return fail(MOE_EINVAL, "no fused kernel for this shape");
 }
 
-static int32_t launch_fused(moe_layer *l, const FusedArgs &A, bool *done)
+static int32_t launch_token(moe_layer *l, const FusedArgs &A, bool one_launch, bool probe_only, bool *done)
 {
     switch (l->lay.bits) {
-    case 4: return launch_fused_fmt<4>(l, A, done);
-    case 3: return launch_fused_fmt<3>(l, A, done);
-    case 2: return launch_fused_fmt<2>(l, A, done);
+    case 4: return launch_token_fmt<4>(l, A, one_launch, probe_only, done);
+    case 3: return launch_token_fmt<3>(l, A, one_launch, probe_only, done);
+    case 2: return launch_token_fmt<2>(l, A, one_launch, probe_only, done);
     default: *done = false; return MOE_OK;
     }
 }
 
-static int32_t launch_ffn(moe_layer *l, const std::vector<FfnEntry> &entries, int nt)
+static int32_t launch_ffn(moe_layer *l, const std::vector<FfnEntry> &entries, int nt, bool w13_only = false)
 {
     switch (l->lay.bits) {
-    case 4: return launch_ffn_fmt<4>(l, entries, nt);
-    case 3: return launch_ffn_fmt<3>(l, entries, nt);
-    case 2: return launch_ffn_fmt<2>(l, entries, nt);
+    case 4: return launch_ffn_fmt<4>(l, entries, nt, w13_only);
+    case 3: return launch_ffn_fmt<3>(l, entries, nt, w13_only);
+    case 2: return launch_ffn_fmt<2>(l, entries, nt, w13_only);
     default: return fail(MOE_EINVAL, "unsupported bit width %d", l->lay.bits);
     }
 }
@@ -856,7 +878,7 @@ extern "C" int32_t moe_layer_step(moe_layer_t *l, moe_layer_t *next, const uint1
     const int nt = std::min(max_tok == 1 ? 1 : (max_tok == 2 ? 2 : 4), max_tokens_per_entry(cf.hidden, cf.bits));
 
     if (c->gate_out->ffn_error) return fail(MOE_ESTATE, "an earlier fused FFN kernel gave up waiting at its grid barrier");
-    const bool try_fused = c->fused && batch == 1 && passes.size() == 1 && plan.access.size() <= 2 &&
+    const bool try_fused = c->token_path && batch == 1 && passes.size() == 1 && plan.access.size() <= 2 &&
                            (int)plan.access.size() == cf.top_k && !plan.victim_needed;
     bool fused_done = false;
     size_t next_demand = 0;
@@ -886,12 +908,18 @@ extern "C" int32_t moe_layer_step(moe_layer_t *l, moe_layer_t *next, const uint1
         if (try_fused) {
             FusedArgs fa{};
             fa.n_exp = (int32_t)entries.size();
-            for (int i = 0; i < fa.n_exp; ++i) { fa.blob[i] = entries[i].blob; fa.w[i] = entries[i].w[0]; }
+            for (int i = 0; i < fa.n_exp; ++i) { fa.blob[i] = entries[i].blob; fa.w[i] = entries[i].w[0]; fa.a_row[i] = entries[i].pair[0]; }
             fa.h = c->h_buf; fa.x = x_in; fa.x_out = x_out; fa.a = c->a_buf; fa.y = c->yacc;
             fa.H = l->lay.hidden; fa.F = l->lay.ffn; fa.group = l->lay.group;
             fa.stride13 = l->lay.m13.row_stride; fa.meta13 = l->lay.m13.meta_off;
             fa.stride2 = l->lay.m2.row_stride; fa.meta2 = l->lay.m2.meta_off; fa.off_w2 = l->lay.off_w2;
-            rc = launch_fused(l, fa, &fused_done);
+            if (c->fused) {
+                rc = launch_token(l, fa, true, false, &fused_done);
+            } else {
+                rc = launch_token(l, fa, false, true, &fused_done);       // does the shape fit the token kernels?
+                if (!rc && fused_done) rc = launch_ffn(l, entries, nt, true);
+                if (!rc && fused_done) rc = launch_token(l, fa, false, false, &fused_done);
+            }
             if (rc) return rc;
         }
         if (!fused_done) {
@@ -1027,6 +1055,7 @@ extern "C" int32_t moe_ctx_set_option(moe_ctx_t *c, const char *name, int32_t va
     else if (n == "w2_rows" && value >= 1 && value <= 256) c->w2_rows = value;
     else if (n == "sync_wait") c->sync_wait = value != 0;
     else if (n == "fused") c->fused = value != 0;
+    else if (n == "token_path") c->token_path = value != 0;
     else return fail(MOE_EINVAL, "moe_ctx_set_option: unknown option or bad value: %s = %d", name, value);
     return MOE_OK;
 }

@@ -273,21 +273,25 @@ def test_mixtral_layer_low_bit(bits, group):
 
 
 @pytest.mark.parametrize("formats", [[(4, 64)] * 2, [(3, 64), (2, 16)]])
-def test_one_launch_ffn_equals_separate_kernels(formats):
-    """Single-token steps run the expert FFN as one persistent launch with a grid barrier; switching it off
-    (separate w1/w3, w2 and residual kernels) must give bit-identical outputs, traces and statistics."""
+def test_single_token_kernel_variants_agree(formats):
+    """A single-token step has three implementations: the general kernels (atomics + residual kernel), the
+    w2 kernel with in-kernel combine and residual (default), and one persistent launch with a grid barrier.
+    All three must give bit-identical outputs, traces and statistics."""
     L, H, F = len(formats), 256, 512
     xs = W.hidden_ar1(31, 24, 1, H)
     outs = {}
-    for fused in (1, 0):
+    for name, token_path, fused in (("general", 0, 0), ("token", 1, 0), ("one_launch", 1, 1)):
         model = Model(L, H, F, 8, 2, formats, 2, 2, 1e-5, seed=31)
+        B.moe_ctx_set_option(model.stack.ctx, "token_path", token_path)
         B.moe_ctx_set_option(model.stack.ctx, "fused", fused)
         B.moe_ctx_profile_enable(model.stack.ctx, True)
         o, sim, errs = run_teacher_forced(model, xs, O.expert_ffn)
         prof = B.moe_ctx_profile_read(model.stack.ctx).as_dict()
-        assert (prof["ffn"]["launches"] > 0) == bool(fused) and (prof["w13"]["launches"] > 0) == (not fused)
-        outs[fused] = (o, model.stack.total_stats())
+        assert (prof["ffn"]["launches"] > 0) == (name == "one_launch")
+        assert (prof["w13"]["launches"] > 0) == (name != "one_launch")
+        outs[name] = (o, model.stack.total_stats())
         model.close()
-    for a, b in zip(outs[1][0], outs[0][0]):
-        assert (a.view(np.uint16) == b.view(np.uint16)).all()
-    assert outs[1][1] == outs[0][1]
+    for other in ("token", "one_launch"):
+        for a, b in zip(outs["general"][0], outs[other][0]):
+            assert (a.view(np.uint16) == b.view(np.uint16)).all(), other
+        assert outs["general"][1] == outs[other][1]
