@@ -237,6 +237,8 @@ int32_t moe_ctx_profile_read(moe_ctx_t *ctx, moe_profile_t *out);
  *   "token_path" 1 (default): a single-token step runs w2 with the combine and the residual add inside the
  *                kernel (one block sees both experts' rows; no atomics, no separate residual kernel);
  *                0: the general kernels also for one token;
+ *   "mfma_min_batch" batches at least this large (default 16) run 4-bit group-64 experts on the matrix cores
+ *                (grouped dequantize+GEMM); smaller batches, and other formats, use the GEMV kernels;
  *   "fused"      1: such a step runs w1/w3 and w2 as ONE persistent launch with a grid barrier (measured
  *                slower than two launches on MI355X, hence default 0). */
 int32_t moe_ctx_set_option(moe_ctx_t *ctx, const char *name, int32_t value);

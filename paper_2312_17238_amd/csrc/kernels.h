@@ -4,3 +4,4 @@
 #include "kernels_gate.h"
 #include "kernels_gemv.h"
 #include "kernels_fused.h"
+#include "kernels_mfma.h"

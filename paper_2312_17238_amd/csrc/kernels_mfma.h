@@ -1,0 +1,194 @@
+// Grouped dequantize+GEMM on the matrix cores for batched decode: when several tokens are routed to the same
+// expert the step is a real contraction, U[t][r] = sum_k h[t][k] W^[r][k] over the tokens t of that expert.
+// 4-bit codes with group 64 (the batched configuration); other formats stay on the GEMV kernels.
+//
+// v_mfma_f32_32x32x16_f16 with M = tokens (A operand = activations, staged through LDS and shared by the
+// block's waves), N = 32 output rows per wave (B operand = weights, loaded straight from HBM into the
+// lane that feeds them: lane l supplies row l%32, codes 32*(l/32)..+31 of the current group, i.e. one uint4).
+// A lane's accumulators all belong to ONE output row (its column of D), so the group's scale and zero are two
+// per-lane scalars and the factorisation  sum (q - z) s h = s (sum q h - z sum h)  costs two FMAs per
+// accumulator and group; sum q h is exact in the MFMA (codes 0..15 as fp16, fp32 accumulation) and the
+// per-(token, group) sums of h come from a small table computed once per step.
+//
+// D layout of the 32x32 MFMA: lane l, register i  ->  row (token) m = 8*(i/4) + 4*(l/32) + i%4, column l%32.
+#pragma once
+#include "kernels_common.h"
+
+namespace moe {
+
+typedef _Float16 h8_t __attribute__((ext_vector_type(8)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+
+constexpr int MF_WAVES = 4;                  // waves per block
+constexpr int MF_ROWS = MF_WAVES * 32;       // output rows per block
+constexpr int MF_KC = 256;                   // codes per K chunk (4 groups)
+constexpr int MF_PITCH = MF_KC + 8;          // LDS row pitch in halves (16 B pad against bank conflicts)
+constexpr int MF_MAX_PAIRS = 256;            // (token, expert) pairs per step: batch * top_k
+
+struct MfmaEntry {
+    const uint8_t *blob;
+    int32_t n_tok;                           // tokens routed to this expert (<= 64)
+    int32_t first;                           // its slice of the pair tables
+};
+
+struct MfmaArgs {
+    MfmaEntry e[16];
+    uint8_t tok[MF_MAX_PAIRS];               // token (batch row) of each pair, grouped by expert
+    uint8_t pair[MF_MAX_PAIRS];              // row of a[.][F] of each pair (= b*K + j)
+    float w[MF_MAX_PAIRS];                   // combine weight of each pair
+    const uint16_t *act;                     // w1/w3: h [B][H];   w2: a [B*K][F]
+    const float *gsum;                       // per-(row of act, group of 64) sums of act
+    uint16_t *a;                             // w1/w3 output
+    float *yacc;                             // w2 output (accumulated)
+    int32_t K, N;                            // contraction length, output rows of the matrix
+    uint32_t stride, meta_off;               // row stride and offset of the (scale, zero) pairs
+    uint64_t mat_off;                        // byte offset of the matrix inside the blob
+};
+
+// sums of groups of 64 consecutive fp16 values: out[v][g] = sum_i vec[v][64 g + i], one thread per (v, g)
+__global__ void k_group_sums(const uint16_t *vec, float *out, int n_vec, int K)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x, groups = K / 64;
+    if (i >= n_vec * groups) return;
+    const uint4 *p = reinterpret_cast<const uint4 *>(vec + (size_t)(i / groups) * K + (size_t)(i % groups) * 64);
+    float s = 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const uint4 v = p[j];
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) s += (float)as_h2(w[q]).x + (float)as_h2(w[q]).y;
+    }
+    out[i] = s;
+}
+
+// 8 codes of one word as 8 exact fp16 integers, in the order of the contraction index
+__device__ __forceinline__ h8_t codes_to_h8(uint32_t w)
+{
+    const h2_t m1024 = {(_Float16)-1024.f, (_Float16)-1024.f}, m64 = {(_Float16)-64.f, (_Float16)-64.f};
+    const uint32_t hi = w >> 8;
+    const h2_t t0 = as_h2(and_or(w, 0x000F000Fu, 0x64006400u)) + m1024;
+    const h2_t t1 = as_h2(and_or(w, 0x00F000F0u, 0x54005400u)) + m64;
+    const h2_t t2 = as_h2(and_or(hi, 0x000F000Fu, 0x64006400u)) + m1024;
+    const h2_t t3 = as_h2(and_or(hi, 0x00F000F0u, 0x54005400u)) + m64;
+    h8_t r;
+    r[0] = t0.x; r[1] = t0.y; r[2] = t1.x; r[3] = t1.y; r[4] = t2.x; r[5] = t2.y; r[6] = t3.x; r[7] = t3.y;
+    return r;
+}
+
+// W13 = true : a[pair][r] = silu(W1^ h)[r] * (W3^ h)[r] for the rows of this block and all tokens of the entry.
+// W13 = false: yacc[tok][r] += w * (W2^ a[pair])[r].
+// grid = (ceil(N / 128), entries); MT = 32-token tiles (1 or 2).
+template <bool W13, int MT>
+__global__ __launch_bounds__(MF_WAVES *WAVE) void k_mfma_q4(MfmaArgs A)
+{
+    constexpr int NS = W13 ? 2 : 1;                                   // weight streams
+    __shared__ __attribute__((aligned(16))) uint16_t tile[MT * 32 * MF_PITCH];
+    __shared__ __attribute__((aligned(16))) float gs[4][2][MT][16];   // [group][lane half][tile][register]
+    const MfmaEntry &en = A.e[blockIdx.y];
+    const int tid = threadIdx.x, lane = tid & 63, wv = uniform(tid >> 6);
+    const int col = lane & 31, kh = lane >> 5;
+    const int r = blockIdx.x * MF_ROWS + wv * 32 + col;               // this lane's output row
+    const int rc = min(r, A.N - 1);
+    const uint8_t *row[NS];
+#pragma unroll
+    for (int s = 0; s < NS; ++s) row[s] = en.blob + A.mat_off + (size_t)(W13 ? 2 * rc + s : rc) * A.stride;
+
+    f32x16_t acc[NS][MT];
+#pragma unroll
+    for (int s = 0; s < NS; ++s)
+#pragma unroll
+        for (int t = 0; t < MT; ++t)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[s][t][i] = 0.f;
+
+    const int n_chunks = A.K / MF_KC;
+    for (int kc = 0; kc < n_chunks; ++kc) {
+        // weights of this chunk: 4 groups x (one uint4 + one pair) per stream, straight to registers
+        uint4 q[NS][4];
+        uint32_t m[NS][4];
+#pragma unroll
+        for (int s = 0; s < NS; ++s)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                q[s][g] = ldw4(row[s], (kc * 4 + g) * 2 + kh);
+                m[s][g] = ldw1(row[s] + A.meta_off, kc * 4 + g);
+            }
+        __syncthreads();                                              // the previous chunk's tile is no longer read
+        // activation tile [MT*32 tokens][256] and the matching group sums
+        for (int i = tid; i < MT * 32 * (MF_KC / 8); i += MF_WAVES * WAVE) {
+            const int t = i / (MF_KC / 8), p = i % (MF_KC / 8);
+            uint4 v = make_uint4(0, 0, 0, 0);
+            if (t < en.n_tok) {
+                const int src = W13 ? A.tok[en.first + t] : A.pair[en.first + t];
+                v = *reinterpret_cast<const uint4 *>(A.act + (size_t)src * A.K + (size_t)kc * MF_KC + p * 8);
+            }
+            *reinterpret_cast<uint4 *>(tile + t * MF_PITCH + p * 8) = v;
+        }
+        for (int i = tid; i < MT * 32 * 4; i += MF_WAVES * WAVE) {
+            const int t = i / 4, g = i % 4;
+            float v = 0.f;
+            if (t < en.n_tok) {
+                const int src = W13 ? A.tok[en.first + t] : A.pair[en.first + t];
+                v = A.gsum[(size_t)src * (A.K / 64) + kc * 4 + g];
+            }
+            const int tt = t & 31;                                    // token tt of tile t/32 sits in register
+            gs[g][(tt >> 2) & 1][t >> 5][(tt >> 3) * 4 + (tt & 3)] = v;   // (tt/8)*4 + tt%4 of lane half (tt/4)%2
+        }
+        __syncthreads();
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            h8_t b[NS][4];
+#pragma unroll
+            for (int s = 0; s < NS; ++s) {
+                b[s][0] = codes_to_h8(q[s][g].x);
+                b[s][1] = codes_to_h8(q[s][g].y);
+                b[s][2] = codes_to_h8(q[s][g].z);
+                b[s][3] = codes_to_h8(q[s][g].w);
+            }
+#pragma unroll
+            for (int t = 0; t < MT; ++t) {
+                f32x16_t cg[NS];
+#pragma unroll
+                for (int s = 0; s < NS; ++s)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) cg[s][i] = 0.f;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const h8_t av = *reinterpret_cast<const h8_t *>(tile + (t * 32 + col) * MF_PITCH + g * 64 + kh * 32 + j * 8);
+#pragma unroll
+                    for (int s = 0; s < NS; ++s) cg[s] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av, b[s][j], cg[s], 0, 0, 0);
+                }
+                float hs[16];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float4 v = *reinterpret_cast<const float4 *>(&gs[g][kh][t][4 * i]);
+                    hs[4 * i] = v.x; hs[4 * i + 1] = v.y; hs[4 * i + 2] = v.z; hs[4 * i + 3] = v.w;
+                }
+#pragma unroll
+                for (int s = 0; s < NS; ++s) {
+                    const float sc = lo_half(m[s][g]), nz = -hi_half(m[s][g]);
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) acc[s][t][i] = fmaf(sc, fmaf(nz, hs[i], cg[s][i]), acc[s][t][i]);
+                }
+            }
+        }
+    }
+    if (r >= A.N) return;
+#pragma unroll
+    for (int t = 0; t < MT; ++t)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int tok = t * 32 + 8 * (i / 4) + 4 * kh + (i % 4);
+            if (tok < en.n_tok) {
+                if (W13) {
+                    const _Float16 av = (_Float16)silu_mul(acc[0][t][i], acc[NS - 1][t][i]);
+                    A.a[(size_t)A.pair[en.first + tok] * A.N + r] = __builtin_bit_cast(uint16_t, av);
+                } else {
+                    atomicAdd(&A.yacc[(size_t)A.tok[en.first + tok] * A.N + r], A.w[en.first + tok] * acc[0][t][i]);
+                }
+            }
+        }
+}
+
+}  // namespace moe

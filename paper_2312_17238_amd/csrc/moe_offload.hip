@@ -98,6 +98,8 @@ struct moe_ctx {
     hipEvent_t ev_gate = nullptr, ev_compute = nullptr;
     int32_t n_layers = 0;
     int32_t w13_blocks = 256, w2_rows = 32;
+    float *gs_h = nullptr, *gs_a = nullptr;   // group sums of h and of a for the matrix-core path
+    int32_t mfma_min_batch = 16;        // batches at least this large use the matrix-core kernels (4-bit g64)
     bool token_path = true;             // single-token steps: w2 kernel with in-kernel combine + residual (no atomics)
     bool fused = false;                 // ... and w1/w3 + w2 as one persistent launch with a grid barrier
     int32_t n_cu = 0;                   // compute units: grid size of the persistent kernel
@@ -137,7 +139,7 @@ static bool layer_cfg_ok(const moe_layer_config_t *c)
            (c->init_policy == 0 || c->init_policy == 1) && blob_layout(c->hidden, c->ffn, c->bits, c->group).ok;
 }
 
-struct ScratchPlan { uint64_t staging, h, a, yacc, x0, x1, barrier, total; };
+struct ScratchPlan { uint64_t staging, h, a, yacc, x0, x1, barrier, gs_h, gs_a, total; };
 
 static ScratchPlan plan_scratch(const moe_ctx_config_t *c)
 {
@@ -150,6 +152,8 @@ static ScratchPlan plan_scratch(const moe_ctx_config_t *c)
     p.yacc = off; off += align_u64((uint64_t)c->max_batch * c->max_hidden * 4, 256);
     p.x0 = off;   off += align_u64((uint64_t)c->max_batch * c->max_hidden * 2, 256);
     p.x1 = off;   off += align_u64((uint64_t)c->max_batch * c->max_hidden * 2, 256);
+    p.gs_h = off; off += align_u64((uint64_t)c->max_batch * (c->max_hidden / 64) * 4, 256);
+    p.gs_a = off; off += align_u64((uint64_t)c->max_batch * c->max_top_k * (c->max_ffn / 64) * 4, 256);
     p.barrier = off; off += 4096;     // one flag per block of the persistent kernel (at most 1024 compute units)
     p.total = off;
     return p;
@@ -230,6 +234,9 @@ extern "C" int32_t moe_ctx_create(const moe_ctx_config_t *cfg, void *dev_arena, 
     c->xbuf[0] = reinterpret_cast<uint16_t *>(base + p.x0);
     c->xbuf[1] = reinterpret_cast<uint16_t *>(base + p.x1);
     c->barrier = reinterpret_cast<uint32_t *>(base + p.barrier);
+    c->gs_h = reinterpret_cast<float *>(base + p.gs_h);
+    c->gs_a = reinterpret_cast<float *>(base + p.gs_a);
+    c->mfma_min_batch = env_int("MOE_MFMA_MIN_BATCH", 16);
     c->fused = env_int("MOE_FUSED", 0) != 0;
     hipError_t e = hipMemset(c->barrier, 0, 4096);
     if (e == hipSuccess) {
@@ -809,6 +816,53 @@ static int32_t launch_token(moe_layer *l, const FusedArgs &A, bool one_launch, b
     }
 }
 
+// Matrix-core path for one pass: every expert of the pass with all its tokens, two launches (w1/w3, w2)
+// plus the group-sum tables of their activation operands.
+struct PassExpert { const uint8_t *blob; std::vector<int> pairs; };
+
+static int32_t launch_mfma(moe_layer *l, const std::vector<PassExpert> &experts, const float *w, int batch, bool first_pass)
+{
+    moe_ctx *c = l->ctx;
+    const BlobLayout &b = l->lay;
+    const int K = l->cfg.top_k;
+    MfmaArgs A{};
+    int n = 0, first = 0, max_tok = 0;
+    for (const PassExpert &pe : experts) {
+        A.e[n].blob = pe.blob;
+        A.e[n].n_tok = (int32_t)pe.pairs.size();
+        A.e[n].first = first;
+        for (int q : pe.pairs) {
+            A.tok[first] = (uint8_t)(q / K);
+            A.pair[first] = (uint8_t)q;
+            A.w[first] = w[q];
+            ++first;
+        }
+        max_tok = std::max(max_tok, (int)pe.pairs.size());
+        ++n;
+    }
+    const uint64_t bytes13 = (uint64_t)n * 2 * b.ffn * b.m13.row_stride, bytes2 = (uint64_t)n * b.hidden * b.m2.row_stride;
+    const dim3 blk(MF_WAVES * WAVE);
+    if (first_pass) {
+        const int items = batch * (b.hidden / 64);
+        hipLaunchKernelGGL(k_group_sums, dim3((items + 255) / 256), dim3(256), 0, c->compute, c->h_buf, c->gs_h, batch, b.hidden);
+        HIPCHK(hipGetLastError());
+    }
+    A.act = c->h_buf; A.gsum = c->gs_h; A.a = c->a_buf; A.yacc = c->yacc;
+    A.K = b.hidden; A.N = b.ffn; A.stride = b.m13.row_stride; A.meta_off = b.m13.meta_off; A.mat_off = b.off_w13;
+    const dim3 g13((b.ffn + MF_ROWS - 1) / MF_ROWS, n);
+    int32_t rc = max_tok > 32 ? launch_timed(c, PROF_W13, bytes13, k_mfma_q4<true, 2>, g13, blk, 0, A)
+                              : launch_timed(c, PROF_W13, bytes13, k_mfma_q4<true, 1>, g13, blk, 0, A);
+    if (rc) return rc;
+    const int items = batch * K * (b.ffn / 64);
+    hipLaunchKernelGGL(k_group_sums, dim3((items + 255) / 256), dim3(256), 0, c->compute, c->a_buf, c->gs_a, batch * K, b.ffn);
+    HIPCHK(hipGetLastError());
+    A.act = c->a_buf; A.gsum = c->gs_a;
+    A.K = b.ffn; A.N = b.hidden; A.stride = b.m2.row_stride; A.meta_off = b.m2.meta_off; A.mat_off = b.off_w2;
+    const dim3 g2((b.hidden + MF_ROWS - 1) / MF_ROWS, n);
+    return max_tok > 32 ? launch_timed(c, PROF_W2, bytes2, k_mfma_q4<false, 2>, g2, blk, 0, A)
+                        : launch_timed(c, PROF_W2, bytes2, k_mfma_q4<false, 1>, g2, blk, 0, A);
+}
+
 static int32_t launch_ffn(moe_layer *l, const std::vector<FfnEntry> &entries, int nt, bool w13_only = false)
 {
     switch (l->lay.bits) {
@@ -881,6 +935,8 @@ extern "C" int32_t moe_layer_step(moe_layer_t *l, moe_layer_t *next, const uint1
     const bool try_fused = c->token_path && batch == 1 && passes.size() == 1 && plan.access.size() <= 2 &&
                            (int)plan.access.size() == cf.top_k && !plan.victim_needed;
     bool fused_done = false;
+    const bool use_mfma = batch >= c->mfma_min_batch && cf.bits == 4 && cf.group == 64 && cf.hidden % MF_KC == 0 &&
+                          cf.ffn % MF_KC == 0 && batch * cf.top_k <= MF_MAX_PAIRS;
     size_t next_demand = 0;
     for (size_t p = 0; p < passes.size(); ++p) {
         if (p > 0) {
@@ -891,6 +947,22 @@ extern "C" int32_t moe_layer_step(moe_layer_t *l, moe_layer_t *next, const uint1
             if (plan.access[i].status == MOE_MISS) { rc = issue_copy(c, l, plan.demand[next_demand++]); if (rc) return rc; }
         if (p + 1 == passes.size() && !plan.victim_needed && passes.size() == 1)
             for (const CopyOp &op : plan.spec) { rc = issue_copy(c, next, op); if (rc) return rc; }
+        if (use_mfma) {
+            std::vector<PassExpert> pes;
+            for (int i : passes[p]) {
+                const AccessRec &a = plan.access[i];
+                PoolBuf &pb = c->bufs[a.buf];
+                if (pb.pending) { HIPCHK(hipStreamWaitEvent(c->compute, pb.ready, 0)); pb.pending = false; }
+                PassExpert pe;
+                pe.blob = pb.ptr;
+                for (int q = 0; q < batch * cf.top_k; ++q)
+                    if (idx[q] == a.expert) pe.pairs.push_back(q);
+                pes.push_back(pe);
+            }
+            rc = launch_mfma(l, pes, w, batch, p == 0);
+            if (rc) return rc;
+            continue;
+        }
         std::vector<FfnEntry> entries;
         for (int i : passes[p]) {
             const AccessRec &a = plan.access[i];
@@ -1056,6 +1128,7 @@ extern "C" int32_t moe_ctx_set_option(moe_ctx_t *c, const char *name, int32_t va
     else if (n == "sync_wait") c->sync_wait = value != 0;
     else if (n == "fused") c->fused = value != 0;
     else if (n == "token_path") c->token_path = value != 0;
+    else if (n == "mfma_min_batch" && value >= 1) c->mfma_min_batch = value;
     else return fail(MOE_EINVAL, "moe_ctx_set_option: unknown option or bad value: %s = %d", name, value);
     return MOE_OK;
 }
