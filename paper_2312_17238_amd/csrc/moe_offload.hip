@@ -687,6 +687,12 @@ static int32_t launch_gate(moe_ctx *c, const GateArgs &ga, int32_t batch)
 #ifndef MOE_W2_G
 #define MOE_W2_G 4
 #endif
+#ifndef MOE_MFMA_W13_WAVES
+#define MOE_MFMA_W13_WAVES 4      // waves (32 output rows each) per block of the matrix-core w1/w3 kernel
+#endif
+#ifndef MOE_MFMA_W2_WAVES
+#define MOE_MFMA_W2_WAVES 2       // ... of the w2 kernel (fewer rows in total, so smaller blocks fill the chip)
+#endif
 #ifndef MOE_FUSED_G2
 #define MOE_FUSED_G2 8
 #endif
@@ -841,7 +847,7 @@ static int32_t launch_mfma(moe_layer *l, const std::vector<PassExpert> &experts,
         ++n;
     }
     const uint64_t bytes13 = (uint64_t)n * 2 * b.ffn * b.m13.row_stride, bytes2 = (uint64_t)n * b.hidden * b.m2.row_stride;
-    const dim3 blk(MF_WAVES * WAVE);
+    constexpr int W13W = MOE_MFMA_W13_WAVES, W2W = MOE_MFMA_W2_WAVES;
     if (first_pass) {
         const int items = batch * (b.hidden / 64);
         hipLaunchKernelGGL(k_group_sums, dim3((items + 255) / 256), dim3(256), 0, c->compute, c->h_buf, c->gs_h, batch, b.hidden);
@@ -849,18 +855,18 @@ static int32_t launch_mfma(moe_layer *l, const std::vector<PassExpert> &experts,
     }
     A.act = c->h_buf; A.gsum = c->gs_h; A.a = c->a_buf; A.yacc = c->yacc;
     A.K = b.hidden; A.N = b.ffn; A.stride = b.m13.row_stride; A.meta_off = b.m13.meta_off; A.mat_off = b.off_w13;
-    const dim3 g13((b.ffn + MF_ROWS - 1) / MF_ROWS, n);
-    int32_t rc = max_tok > 32 ? launch_timed(c, PROF_W13, bytes13, k_mfma_q4<true, 2>, g13, blk, 0, A)
-                              : launch_timed(c, PROF_W13, bytes13, k_mfma_q4<true, 1>, g13, blk, 0, A);
+    const dim3 g13((b.ffn + W13W * 32 - 1) / (W13W * 32), n), blk13(W13W * WAVE);
+    int32_t rc = max_tok > 32 ? launch_timed(c, PROF_W13, bytes13, k_mfma_q4<true, 2, W13W>, g13, blk13, 0, A)
+                              : launch_timed(c, PROF_W13, bytes13, k_mfma_q4<true, 1, W13W>, g13, blk13, 0, A);
     if (rc) return rc;
     const int items = batch * K * (b.ffn / 64);
     hipLaunchKernelGGL(k_group_sums, dim3((items + 255) / 256), dim3(256), 0, c->compute, c->a_buf, c->gs_a, batch * K, b.ffn);
     HIPCHK(hipGetLastError());
     A.act = c->a_buf; A.gsum = c->gs_a;
     A.K = b.ffn; A.N = b.hidden; A.stride = b.m2.row_stride; A.meta_off = b.m2.meta_off; A.mat_off = b.off_w2;
-    const dim3 g2((b.hidden + MF_ROWS - 1) / MF_ROWS, n);
-    return max_tok > 32 ? launch_timed(c, PROF_W2, bytes2, k_mfma_q4<false, 2>, g2, blk, 0, A)
-                        : launch_timed(c, PROF_W2, bytes2, k_mfma_q4<false, 1>, g2, blk, 0, A);
+    const dim3 g2((b.hidden + W2W * 32 - 1) / (W2W * 32), n), blk2(W2W * WAVE);
+    return max_tok > 32 ? launch_timed(c, PROF_W2, bytes2, k_mfma_q4<false, 2, W2W>, g2, blk2, 0, A)
+                        : launch_timed(c, PROF_W2, bytes2, k_mfma_q4<false, 1, W2W>, g2, blk2, 0, A);
 }
 
 static int32_t launch_ffn(moe_layer *l, const std::vector<FfnEntry> &entries, int nt, bool w13_only = false)
