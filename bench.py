@@ -26,7 +26,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 # HBM bytes per launch (read + written) of the dominant kernel from hardware counters, valid for the default
 # workload and launch shape only (4-bit g64 Mixtral experts, batch 1): FETCH_SIZE and WRITE_SIZE of two
 # rocprofv3 --pmc runs, scaled by the copy probe; see profiles/hbm_traffic_gemv_kernels_4bit.md
-PMC_TRAFFIC_W13_4BIT_B1 = 132_593_967
+PMC_TRAFFIC_W13_4BIT_B1 = 132_577_126
 PMC_TRAFFIC_FFN_4BIT_B1 = None   # filled from profiles/ once the counters of the fused kernel are collected
 LINK_PEAK_GBS = 64.0           # PCIe Gen5 x16, one direction, nominal
 
@@ -219,7 +219,7 @@ def main() -> int:
     elif prof:
         w13, w2, cp, gt = prof["w13"], prof["w2"], prof["copy"], prof["gate"]
         ach = w13["bytes"] / max(w13["total_ms"], 1e-9) / 1e6      # GB/s
-        result["roofline"] = {"bound": "hbm", "kernel": "k_w13_q4 (fused dequant-GEMV w1,w3 -> SiLU*mul)",
+        result["roofline"] = {"bound": "hbm", "kernel": "k_w13 (fused dequant-GEMV w1,w3 -> SiLU*mul)",
                               "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
                               "traffic": PMC_TRAFFIC_W13_4BIT_B1 if (batch == 1 and set(formats) == {(4, 64)}
                                                                      and shape.hidden == 4096 and shape.ffn == 14336) else None,
@@ -228,7 +228,7 @@ def main() -> int:
                               "avg_us": 1e3 * w13["total_ms"] / max(1, w13["launches"]),
                               "measured_read_probe_gbs": probe["read_gbs"] if probe else None}
         a2 = w2["bytes"] / max(w2["total_ms"], 1e-9) / 1e6
-        result["roofline_w2"] = {"bound": "hbm", "kernel": "k_w2_q4 (fused dequant-GEMV w2 -> weighted accumulate)",
+        result["roofline_w2"] = {"bound": "hbm", "kernel": "k_w2 / k_w2_token (fused dequant-GEMV w2 -> combine -> residual)",
                                  "achieved": a2, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": a2 / HBM_PEAK_GBS,
                                  "launches": w2["launches"], "avg_us": 1e3 * w2["total_ms"] / max(1, w2["launches"])}
         both = (w13["bytes"] + w2["bytes"]) / max(w13["total_ms"] + w2["total_ms"], 1e-9) / 1e6
