@@ -343,3 +343,30 @@ def test_mixtral_layer_batch16_matrix_cores():
     _, sim, errs = run_teacher_forced(model, xs, c_ffn.expert_ffn)
     say(f"  max abs {max(e[0] for e in errs):.2e} max rel-rms {max(e[1] for e in errs):.2e}")
     model.close()
+
+
+def test_rmsnorm_small_and_large_inputs_bit_exact():
+    """eps dominates for tiny inputs and the straight fp64->fp16 rounding matters for large ones: h must equal
+    the oracle's bit for bit over magnitudes from fp16 subnormals to near overflow."""
+    from paper_2312_17238_amd.engine import Stack, layer_config
+    H, F = 256, 512
+    gate = W.gate_weight(9, 0, 8, H)
+    st = Stack([layer_config(H, F, 8, 2, 4, 64, 8, 0, 1e-5)], [gate], None, max_batch=8)
+    for e in range(8):
+        for mtx, (q, s, z) in enumerate(W.quantized_expert(9, 0, e, H, F, 4, 64)):
+            st.load_expert(0, e, mtx, q, s, z)
+    base = W.hidden_iid(9, 1, 8, H)[0].float()
+    scales = torch.tensor([2.0 ** -20, 2.0 ** -12, 2.0 ** -8, 2.0 ** -4, 1.0, 16.0, 1024.0, 12000.0]).unsqueeze(1)
+    x = (base * scales).clamp(-60000, 60000).to(torch.float16)
+    dev = st.device
+    xd = x.to(dev); out = torch.empty_like(xd); h = torch.empty_like(xd)
+    tr = B.StepTrace()
+    st.step_layer(0, xd, out, h, tr)
+    st.synchronize()
+    gam = np.ones(H, np.float16)
+    want = O.rmsnorm(x.numpy(), gam, 1e-5)
+    assert (h.cpu().numpy().view(np.uint16) == want.view(np.uint16)).all()
+    for b in range(8):
+        idx, w, z = O.route(gate.numpy(), want[b], 2)
+        assert tr.routing()[b] == idx
+    st.close()

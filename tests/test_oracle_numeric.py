@@ -240,6 +240,11 @@ def test_rmsnorm_closed_forms():
     # constant vector: h = c / sqrt(c^2 + eps)
     c = np.full(H, 0.5, dtype=np.float16)
     assert (O.rmsnorm(c, g, eps) == np.float16(0.5 / math.sqrt(0.25 + e32))).all()
+    # eps matters when x is small: c = 2^-8 has c^2 = 1.5e-5, comparable to eps; and the zero vector stays zero
+    small = np.full(H, 2.0 ** -8, dtype=np.float16)
+    assert (O.rmsnorm(small, g, eps) == np.float16(2.0 ** -8 / math.sqrt(2.0 ** -16 + e32))).all()
+    assert float(O.rmsnorm(small, g, eps)[0]) < 0.8
+    assert (O.rmsnorm(np.zeros(H, np.float16), g, eps) == 0).all()
     # gain is applied per element, after the normalisation
     g2 = g.copy(); g2[7] = 2.0
     h2 = O.rmsnorm(x, g2, eps)
