@@ -106,6 +106,8 @@ def main() -> int:
     ap.add_argument("--group", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true", help="do not record HIP events around the engine's launches")
+    ap.add_argument("--spec-head-mb", type=int, default=4,
+                    help="speculative loads copy only the first N MiB until the guess is confirmed (0: whole expert, as in the paper)")
     ap.add_argument("--fused", action="store_true", help="single-token steps run w1/w3 and w2 as one persistent launch")
     ap.add_argument("--no-token-path", action="store_true", help="single-token steps use the general kernels (atomics + residual kernel)")
     ap.add_argument("--no-probe", action="store_true", help="skip the plain streaming-read / copy calibration kernels")
@@ -143,6 +145,7 @@ def main() -> int:
     stack, gates, gamma, kept = build_model(shape, formats, batch, device, keep_layers)
     if args.no_cache:
         stack.set_flags(B.MOE_LAYER_NO_CACHE)
+    B.moe_ctx_set_option(stack.ctx, "spec_head_mb", args.spec_head_mb)
     if args.fused:
         B.moe_ctx_set_option(stack.ctx, "fused", 1)
     if args.no_token_path:
@@ -197,13 +200,20 @@ def main() -> int:
                                f"{shape.n_experts} experts top-{shape.top_k}, formats {sorted(set(formats))}, "
                                f"LRU k={shape.cache_slots}, prefetch m={shape.prefetch_m}, b=4 staging buffers, "
                                f"batch {batch}, {shape.hidden_kind} hidden states, seed {shape.seed}",
-                   "no_cache": bool(args.no_cache)},
+                   "no_cache": bool(args.no_cache), "spec_head_mb": args.spec_head_mb},
     }
     link_bytes = d["bytes_h2d_demand"] + d["bytes_h2d_spec"]
     result["cache"] = {"needed": d["needed"], "hits": d["hits"], "prefetch_hits": d["prefetch_hits"], "misses": d["misses"],
                        "spec_issued": d["spec_issued"], "spec_wasted": d["spec_wasted"],
                        "recall": (d["hits"] + d["prefetch_hits"]) / max(1, d["needed"]),
                        "link_bytes_per_token": link_bytes / tokens}
+    # the step can be no faster than its bytes over the slower of the two pipes (nominal peaks)
+    hbm_bytes_per_token = 2.0 * sum(stack.blob_bytes) * batch / max(1, batch) if batch == 1 else None
+    t_link = (link_bytes / tokens) / (LINK_PEAK_GBS * 1e9)
+    t_hbm = (hbm_bytes_per_token / (HBM_PEAK_GBS * 1e9)) if hbm_bytes_per_token else 0.0
+    bound_tps = 1.0 / max(t_link, t_hbm, 1e-12)
+    result["step_bound"] = {"tokens_per_s_at_nominal_peaks": bound_tps, "frac": (tokens / dt) / bound_tps,
+                            "link_s_per_token": t_link, "hbm_s_per_token": t_hbm if hbm_bytes_per_token else None}
     if prof and prof["ffn"]["launches"]:
         # single-token steps run the expert FFN as one persistent launch: that kernel is the dominant one
         ff, cp, gt = prof["ffn"], prof["copy"], prof["gate"]

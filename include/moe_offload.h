@@ -239,6 +239,10 @@ int32_t moe_ctx_profile_read(moe_ctx_t *ctx, moe_profile_t *out);
  *                0: the general kernels also for one token;
  *   "mfma_min_batch" batches at least this large (default 16) run 4-bit group-64 experts on the matrix cores
  *                (grouped dequantize+GEMM); smaller batches, and other formats, use the GEMV kernels;
+ *   "spec_head_mb" 0 (default): a speculative load copies the whole expert at once, as the paper describes;
+ *                N > 0: it copies only the first N MiB, and the rest is fetched (like a demand load) when the next
+ *                layer confirms the guess.  Decisions, traces and results are identical; only how many bytes a wrong
+ *                guess costs changes (N MiB instead of a whole expert).  Meant for links that are already saturated;
  *   "fused"      1: such a step runs w1/w3 and w2 as ONE persistent launch with a grid barrier (measured
  *                slower than two launches on MI355X, hence default 0). */
 int32_t moe_ctx_set_option(moe_ctx_t *ctx, const char *name, int32_t value);

@@ -14,7 +14,7 @@ namespace moe {
 
 struct StagedGuess { int32_t expert; int32_t buf; };
 
-struct CopyOp { int32_t expert; int32_t buf; };              // host blob of `expert` -> pool buffer `buf`
+struct CopyOp { int32_t expert; int32_t buf; uint64_t offset = 0, bytes = 0; };   // bytes [offset, offset+bytes) of the host blob of `expert` -> pool buffer `buf`
 
 struct AccessRec { int32_t expert, status, slot, victim, buf; };
 

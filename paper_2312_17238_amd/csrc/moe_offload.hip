@@ -64,6 +64,7 @@ struct PoolBuf {
     uint8_t *ptr = nullptr;
     hipEvent_t ready = nullptr;   // recorded on the copy stream after the last copy into this buffer
     bool pending = false;         // a copy was recorded that the compute stream has not yet waited on
+    uint64_t have = 0;            // staging use: bytes of the guessed expert requested so far (head of a speculative load)
 };
 
 // Optional timing of the engine's own launches with HIP events recorded on the stream each launch goes to.
@@ -100,6 +101,8 @@ struct moe_ctx {
     int32_t w13_blocks = 256, w2_rows = 32;
     float *gs_h = nullptr, *gs_a = nullptr;   // group sums of h and of a for the matrix-core path
     int32_t mfma_min_batch = 16;        // batches at least this large use the matrix-core kernels (4-bit g64)
+    uint64_t spec_head_bytes = 0;       // 0: a speculative load moves the whole expert at once (as the paper describes);
+                                        // > 0: only this many leading bytes, the rest when the guess is confirmed
     bool token_path = true;             // single-token steps: w2 kernel with in-kernel combine + residual (no atomics)
     bool fused = false;                 // ... and w1/w3 + w2 as one persistent launch with a grid barrier
     int32_t n_cu = 0;                   // compute units: grid size of the persistent kernel
@@ -536,7 +539,8 @@ extern "C" int32_t moe_ctx_profile_read(moe_ctx_t *c, moe_profile_t *out)
 
 struct StepPlan {
     std::vector<AccessRec> access;
-    std::vector<CopyOp> demand;     // in access order
+    std::vector<CopyOp> demand;     // misses, and the tails of confirmed speculative loads
+    std::vector<int> demand_of;     // per access: index into `demand`, or -1
     std::vector<CopyOp> spec;       // for the next layer
     bool victim_needed = false;     // an expert needed in this step was evicted during it
 };
@@ -552,15 +556,40 @@ static int32_t plan_step(moe_layer *l, moe_layer *next, const int32_t *idx, int3
     }
     std::sort(needed.begin(), needed.end());
     needed.erase(std::unique(needed.begin(), needed.end()), needed.end());
-    resolve_accesses(l->cache, l->ctx->pool, l->st, needed, (cf.flags & MOE_LAYER_NO_CACHE) != 0, plan.access, plan.demand);
-    for (const AccessRec &a : plan.access)
+    std::vector<CopyOp> misses;
+    resolve_accesses(l->cache, l->ctx->pool, l->st, needed, (cf.flags & MOE_LAYER_NO_CACHE) != 0, plan.access, misses);
+    size_t next_miss = 0;
+    for (const AccessRec &a : plan.access) {
         if (a.victim >= 0 && std::binary_search(needed.begin(), needed.end(), a.victim)) plan.victim_needed = true;
-    l->st.bytes_demand += (uint64_t)plan.demand.size() * l->lay.total;
+        PoolBuf &pb = l->ctx->bufs[a.buf];
+        int di = -1;
+        if (a.status == MOE_MISS) {
+            CopyOp op = misses[next_miss++];
+            op.offset = 0; op.bytes = l->lay.total;
+            l->st.bytes_demand += op.bytes;
+            di = (int)plan.demand.size();
+            plan.demand.push_back(op);
+        } else if (a.status == MOE_PREFETCH_HIT && pb.have < l->lay.total) {
+            // the guess was right but only its head was requested: the rest is fetched now, like a demand load
+            CopyOp op{a.expert, a.buf, pb.have, l->lay.total - pb.have};
+            l->st.bytes_spec += op.bytes;
+            di = (int)plan.demand.size();
+            plan.demand.push_back(op);
+        }
+        if (a.status != MOE_HIT) pb.have = l->lay.total;
+        plan.demand_of.push_back(di);
+    }
     std::vector<int32_t> guess, issued;
     if (next && guess_score && next->cfg.prefetch_m > 0) {
         guess = top_m(guess_score, next->cfg.n_experts, next->cfg.prefetch_m);
         stage_guesses(next->cache, l->ctx->pool, next->st, guess, issued, plan.spec);
-        next->st.bytes_spec += (uint64_t)plan.spec.size() * next->lay.total;
+        for (CopyOp &op : plan.spec) {
+            const uint64_t head = l->ctx->spec_head_bytes;
+            op.offset = 0;
+            op.bytes = head ? std::min<uint64_t>(head, next->lay.total) : next->lay.total;
+            l->ctx->bufs[op.buf].have = op.bytes;
+            next->st.bytes_spec += op.bytes;
+        }
     }
     if (tr) {
         tr->batch = batch; tr->top_k = cf.top_k; tr->n_experts = cf.n_experts;
@@ -580,9 +609,9 @@ static int32_t issue_copy(moe_ctx *c, const moe_layer *owner, const CopyOp &op)
 {
     PoolBuf &b = c->bufs[op.buf];
     int ps;
-    int32_t rc = prof_begin(c, PROF_COPY, c->copy, owner->lay.total, &ps);
+    int32_t rc = prof_begin(c, PROF_COPY, c->copy, op.bytes, &ps);
     if (rc) return rc;
-    HIPCHK(hipMemcpyAsync(b.ptr, owner->host_blobs + (uint64_t)op.expert * owner->lay.total, owner->lay.total,
+    HIPCHK(hipMemcpyAsync(b.ptr + op.offset, owner->host_blobs + (uint64_t)op.expert * owner->lay.total + op.offset, op.bytes,
                           hipMemcpyHostToDevice, c->copy));
     rc = prof_end(c, PROF_COPY, c->copy, ps);
     if (rc) return rc;
@@ -943,14 +972,13 @@ extern "C" int32_t moe_layer_step(moe_layer_t *l, moe_layer_t *next, const uint1
     bool fused_done = false;
     const bool use_mfma = batch >= c->mfma_min_batch && cf.bits == 4 && cf.group == 64 && cf.hidden % MF_KC == 0 &&
                           cf.ffn % MF_KC == 0 && batch * cf.top_k <= MF_MAX_PAIRS;
-    size_t next_demand = 0;
     for (size_t p = 0; p < passes.size(); ++p) {
         if (p > 0) {
             HIPCHK(hipEventRecord(c->ev_compute, c->compute));
             HIPCHK(hipStreamWaitEvent(c->copy, c->ev_compute, 0));
         }
         for (int i : passes[p])
-            if (plan.access[i].status == MOE_MISS) { rc = issue_copy(c, l, plan.demand[next_demand++]); if (rc) return rc; }
+            if (plan.demand_of[i] >= 0) { rc = issue_copy(c, l, plan.demand[plan.demand_of[i]]); if (rc) return rc; }
         if (p + 1 == passes.size() && !plan.victim_needed && passes.size() == 1)
             for (const CopyOp &op : plan.spec) { rc = issue_copy(c, next, op); if (rc) return rc; }
         if (use_mfma) {
@@ -1040,7 +1068,12 @@ extern "C" int32_t moe_layer_prefetch(moe_layer_t *l, const uint16_t *h_dev, int
     std::vector<int32_t> guess = top_m(score, l->cfg.n_experts, l->cfg.prefetch_m), issued;
     std::vector<CopyOp> copies;
     stage_guesses(l->cache, c->pool, l->st, guess, issued, copies);
-    l->st.bytes_spec += (uint64_t)copies.size() * l->lay.total;
+    for (CopyOp &op : copies) {
+        op.offset = 0;
+        op.bytes = c->spec_head_bytes ? std::min<uint64_t>(c->spec_head_bytes, l->lay.total) : l->lay.total;
+        c->bufs[op.buf].have = op.bytes;
+        l->st.bytes_spec += op.bytes;
+    }
     for (const CopyOp &op : copies) { rc = issue_copy(c, l, op); if (rc) return rc; }
     if (trace) {
         trace->n_guess = (int32_t)guess.size();
@@ -1134,6 +1167,7 @@ extern "C" int32_t moe_ctx_set_option(moe_ctx_t *c, const char *name, int32_t va
     else if (n == "sync_wait") c->sync_wait = value != 0;
     else if (n == "fused") c->fused = value != 0;
     else if (n == "token_path") c->token_path = value != 0;
+    else if (n == "spec_head_mb" && value >= 0) c->spec_head_bytes = (uint64_t)value << 20;
     else if (n == "mfma_min_batch" && value >= 1) c->mfma_min_batch = value;
     else return fail(MOE_EINVAL, "moe_ctx_set_option: unknown option or bad value: %s = %d", name, value);
     return MOE_OK;

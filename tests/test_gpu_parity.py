@@ -370,3 +370,28 @@ def test_rmsnorm_small_and_large_inputs_bit_exact():
         idx, w, z = O.route(gate.numpy(), want[b], 2)
         assert tr.routing()[b] == idx
     st.close()
+
+
+def test_speculative_head_then_tail_is_invisible_in_results():
+    """Option spec_head_mb: a speculative load moves only the head of the expert and the rest once the guess is
+    confirmed.  Decisions, traces, statistics (except bytes) and outputs must be identical to whole-expert loads."""
+    c = W.CONFIGS["mixtral_layer"]
+    L, T = 3, 6
+    xs = W.hidden_ar1(51, T, 1, c.hidden)
+    res = {}
+    for head in (0, 8):
+        model = Model(L, c.hidden, c.ffn, 8, 2, None, 2, 2, 1e-5, seed=51, keep_layers=[])
+        B.moe_ctx_set_option(model.stack.ctx, "spec_head_mb", head)
+        outs, sim, errs = run_teacher_forced(model, xs, c_ffn.expert_ffn, check_ffn=lambda t, l: (t, l) in {(1, 1), (4, 2)})
+        res[head] = (outs, model.stack.total_stats())
+        model.close()
+    for a, b in zip(res[0][0], res[8][0]):
+        assert (a.view(np.uint16) == b.view(np.uint16)).all()
+    s0, s8 = res[0][1], res[8][1]
+    for k in s0:
+        if k != "bytes_h2d_spec":
+            assert s0[k] == s8[k], k
+    blob = B.moe_expert_blob_bytes(c.hidden, c.ffn, 4, 64)
+    assert s0["bytes_h2d_spec"] == s0["spec_issued"] * blob
+    assert s8["bytes_h2d_spec"] == s8["spec_issued"] * (8 << 20) + s8["prefetch_hits"] * (blob - (8 << 20))
+    assert s8["prefetch_hits"] > 0 and s8["spec_wasted"] > 0
