@@ -100,6 +100,7 @@ struct moe_ctx {
     int32_t n_layers = 0;
     int32_t w13_blocks = 256, w2_rows = 32;
     float *gs_h = nullptr, *gs_a = nullptr;   // group sums of h and of a for the matrix-core path
+    int32_t mfma_form = 1;              // 1: row-streaming matrix-core kernels, 0: direct-to-lane form
     int32_t mfma_min_batch = 16;        // batches at least this large use the matrix-core kernels (4-bit g64)
     uint64_t spec_head_bytes = 0;       // 0: a speculative load moves the whole expert at once (as the paper describes);
                                         // > 0: only this many leading bytes, the rest when the guess is confirmed
@@ -877,13 +878,40 @@ static int32_t launch_mfma(moe_layer *l, const std::vector<PassExpert> &experts,
     }
     const uint64_t bytes13 = (uint64_t)n * 2 * b.ffn * b.m13.row_stride, bytes2 = (uint64_t)n * b.hidden * b.m2.row_stride;
     constexpr int W13W = MOE_MFMA_W13_WAVES, W2W = MOE_MFMA_W2_WAVES;
-    if (first_pass) {
+    if (first_pass && c->mfma_form != 1) {
         const int items = batch * (b.hidden / 64);
         hipLaunchKernelGGL(k_group_sums, dim3((items + 255) / 256), dim3(256), 0, c->compute, c->h_buf, c->gs_h, batch, b.hidden);
         HIPCHK(hipGetLastError());
     }
     A.act = c->h_buf; A.gsum = c->gs_h; A.a = c->a_buf; A.yacc = c->yacc;
     A.K = b.hidden; A.N = b.ffn; A.stride = b.m13.row_stride; A.meta_off = b.m13.meta_off; A.mat_off = b.off_w13;
+    // LDS of the row-streaming form: 32 staged rows (codes + pairs) or the final reduction buffer
+    auto rows_lds = [&](int K, int mt) {
+        const int sg = std::min(K / 64, MF2_SEG);
+        return std::max<size_t>((size_t)32 * (sg * 32 + 16) + (size_t)32 * ((sg + 3) & ~3) * 4, (size_t)MF2_WAVES * mt * 16 * 64 * 4);
+    };
+    static bool lds_attr_set = false;      // these kernels stage 72 KB: above the default dynamic LDS limit
+    if (!lds_attr_set) {
+        const int lim = 96 * 1024;
+        HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_rows_q4<true, 1>), hipFuncAttributeMaxDynamicSharedMemorySize, lim));
+        HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_rows_q4<true, 2>), hipFuncAttributeMaxDynamicSharedMemorySize, lim));
+        HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_rows_q4<false, 1>), hipFuncAttributeMaxDynamicSharedMemorySize, lim));
+        HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_rows_q4<false, 2>), hipFuncAttributeMaxDynamicSharedMemorySize, lim));
+        lds_attr_set = true;
+    }
+    const int mt = max_tok > 32 ? 2 : 1;
+    const dim3 blkr(MF2_WAVES * WAVE);
+    if (c->mfma_form == 1) {
+        const dim3 gr13((2 * b.ffn + 31) / 32, n);
+        int32_t rr = mt == 2 ? launch_timed(c, PROF_W13, bytes13, k_mfma_rows_q4<true, 2>, gr13, blkr, rows_lds(b.hidden, 2), A)
+                             : launch_timed(c, PROF_W13, bytes13, k_mfma_rows_q4<true, 1>, gr13, blkr, rows_lds(b.hidden, 1), A);
+        if (rr) return rr;
+        A.act = c->a_buf; A.gsum = c->gs_a;
+        A.K = b.ffn; A.N = b.hidden; A.stride = b.m2.row_stride; A.meta_off = b.m2.meta_off; A.mat_off = b.off_w2;
+        const dim3 gr2((b.hidden + 31) / 32, n);
+        return mt == 2 ? launch_timed(c, PROF_W2, bytes2, k_mfma_rows_q4<false, 2>, gr2, blkr, rows_lds(b.ffn, 2), A)
+                       : launch_timed(c, PROF_W2, bytes2, k_mfma_rows_q4<false, 1>, gr2, blkr, rows_lds(b.ffn, 1), A);
+    }
     const dim3 g13((b.ffn + W13W * 32 - 1) / (W13W * 32), n), blk13(W13W * WAVE);
     int32_t rc = max_tok > 32 ? launch_timed(c, PROF_W13, bytes13, k_mfma_q4<true, 2, W13W>, g13, blk13, 0, A)
                               : launch_timed(c, PROF_W13, bytes13, k_mfma_q4<true, 1, W13W>, g13, blk13, 0, A);
@@ -1169,6 +1197,7 @@ extern "C" int32_t moe_ctx_set_option(moe_ctx_t *c, const char *name, int32_t va
     else if (n == "token_path") c->token_path = value != 0;
     else if (n == "spec_head_mb" && value >= 0) c->spec_head_bytes = (uint64_t)value << 20;
     else if (n == "mfma_min_batch" && value >= 1) c->mfma_min_batch = value;
+    else if (n == "mfma_form" && (value == 0 || value == 1)) c->mfma_form = value;
     else return fail(MOE_EINVAL, "moe_ctx_set_option: unknown option or bad value: %s = %d", name, value);
     return MOE_OK;
 }
