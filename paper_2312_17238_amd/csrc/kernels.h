@@ -5,3 +5,4 @@
 #include "kernels_gemv.h"
 #include "kernels_fused.h"
 #include "kernels_mfma.h"
+#include "kernels_mfma_stream.h"

@@ -264,26 +264,42 @@ __global__ __launch_bounds__(MF2_WAVES *WAVE) void k_mfma_rows_q4(MfmaArgs A)
     h8_t ones;
 #pragma unroll
     for (int i = 0; i < 8; ++i) ones[i] = (_Float16)1.f;
-    // activation rows of this lane's token (A operand: lane l feeds token l%32 of the tile)
+    // activation rows of this lane's token (A operand: lane l feeds token l%32 of the tile); lanes past the
+    // entry's last token read its first token again, their results are never stored
     const uint16_t *arow[MT];
-    bool tok_live[MT];
 #pragma unroll
     for (int t = 0; t < MT; ++t) {
-        const int tk = t * 32 + col;
-        tok_live[t] = tk < en.n_tok;
-        const int src = tok_live[t] ? (W13 ? A.tok[en.first + tk] : A.pair[en.first + tk]) : 0;
-        arow[t] = A.act + (size_t)src * A.K;
+        const int tk = t * 32 + col < en.n_tok ? t * 32 + col : 0;
+        arow[t] = A.act + (size_t)(W13 ? A.tok[en.first + tk] : A.pair[en.first + tk]) * A.K;
     }
-
     auto load_a = [&](h8_t (&av)[MT][4], int g) {                     // one group's A operands for this lane's token(s)
 #pragma unroll
         for (int t = 0; t < MT; ++t)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                uint4 v = make_uint4(0, 0, 0, 0);
-                if (tok_live[t]) v = *reinterpret_cast<const uint4 *>(arow[t] + (size_t)g * 64 + kh * 32 + j * 8);
-                av[t][j] = __builtin_bit_cast(h8_t, v);
+            for (int j = 0; j < 4; ++j)
+                av[t][j] = __builtin_bit_cast(h8_t, *reinterpret_cast<const uint4 *>(arow[t] + (size_t)g * 64 + kh * 32 + j * 8));
+    };
+    auto multiply = [&](const h8_t (&av)[MT][4], int g) {             // group g of the staged segment
+        const uint4 q = *reinterpret_cast<const uint4 *>(lds_codes + col * code_pitch + g * 32 + kh * 16);
+        const uint32_t m = lds_meta[col * meta_pitch + g];
+        const float sc = lo_half(m), z = hi_half(m);
+        h8_t b[4];
+        {
+            b[0] = codes_to_h8(q.x); b[1] = codes_to_h8(q.y); b[2] = codes_to_h8(q.z); b[3] = codes_to_h8(q.w);
+#pragma unroll
+            for (int t = 0; t < MT; ++t) {
+                f32x16_t cg, chs;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) { cg[i] = 0.f; chs[i] = 0.f; }
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    cg = __builtin_amdgcn_mfma_f32_32x32x16_f16(av[t][j], b[j], cg, 0, 0, 0);
+                    chs = __builtin_amdgcn_mfma_f32_32x32x16_f16(av[t][j], ones, chs, 0, 0, 0);
+                }
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[t][i] = fmaf(sc, fmaf(-z, chs[i], cg[i]), acc[t][i]);
             }
+        }
     };
     constexpr int THREADS = MF2_WAVES * WAVE;
     constexpr int CP = MF2_SEG * 2 * 32 / THREADS;                    // code pieces per thread of a full segment (16)
@@ -307,8 +323,8 @@ __global__ __launch_bounds__(MF2_WAVES *WAVE) void k_mfma_rows_q4(MfmaArgs A)
             const int rr = pp / mpr, c = pp - rr * mpr;
             mstage[i] = ldw4(mat + (size_t)min(row0 + rr, n_rows - 1) * A.stride + A.meta_off, g0 / 4 + c);
         }
-        h8_t a_cur[MT][4], a_nxt[MT][4];
-        if (wv < sg) load_a(a_cur, g0 + wv);                          // first A operands travel during the copy
+        h8_t a_even[MT][4], a_odd[MT][4];
+        load_a(a_even, g0 + min(wv, sg - 1));                         // first A operands travel during the copy
 #pragma unroll
         for (int i = 0; i < CP; ++i) {
             const int p = tid + i * THREADS;
@@ -326,31 +342,13 @@ __global__ __launch_bounds__(MF2_WAVES *WAVE) void k_mfma_rows_q4(MfmaArgs A)
             }
         }
         __syncthreads();
-        // ---- multiply: wave wv takes groups wv, wv+4, ...; the next group's A operands are requested first
-        for (int g = wv; g < sg; g += MF2_WAVES) {
-            load_a(a_nxt, g0 + min(g + MF2_WAVES, sg - 1));
-            const uint4 q = *reinterpret_cast<const uint4 *>(lds_codes + col * code_pitch + g * 32 + kh * 16);
-            const uint32_t m = lds_meta[col * meta_pitch + g];
-            h8_t b[4];
-            b[0] = codes_to_h8(q.x); b[1] = codes_to_h8(q.y); b[2] = codes_to_h8(q.z); b[3] = codes_to_h8(q.w);
-            const float sc = lo_half(m), nz = -hi_half(m);
-#pragma unroll
-            for (int t = 0; t < MT; ++t) {
-                f32x16_t cg, chs;
-#pragma unroll
-                for (int i = 0; i < 16; ++i) { cg[i] = 0.f; chs[i] = 0.f; }
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    cg = __builtin_amdgcn_mfma_f32_32x32x16_f16(a_cur[t][j], b[j], cg, 0, 0, 0);
-                    chs = __builtin_amdgcn_mfma_f32_32x32x16_f16(a_cur[t][j], ones, chs, 0, 0, 0);
-                }
-#pragma unroll
-                for (int i = 0; i < 16; ++i) acc[t][i] = fmaf(sc, fmaf(nz, chs[i], cg[i]), acc[t][i]);
-            }
-#pragma unroll
-            for (int t = 0; t < MT; ++t)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) a_cur[t][j] = a_nxt[t][j];
+        // ---- multiply: wave wv takes groups wv, wv+4, ...; two per trip, each one's A operands requested while
+        // the other is multiplied (past the end the last group is read again and not used)
+        for (int g = wv; g < sg; g += 2 * MF2_WAVES) {
+            load_a(a_odd, g0 + min(g + MF2_WAVES, sg - 1));
+            multiply(a_even, g);
+            load_a(a_even, g0 + min(g + 2 * MF2_WAVES, sg - 1));
+            if (g + MF2_WAVES < sg) multiply(a_odd, g + MF2_WAVES);
         }
         __syncthreads();                                              // before the next segment overwrites LDS
     }

@@ -1,0 +1,260 @@
+// Grouped dequantize+GEMM on the matrix cores, streaming form: persistent blocks with producer and consumer
+// waves, built so that the weights cross HBM once in long coalesced reads and the vector unit does the
+// minimum of work per weight.
+//
+// Work item  = 128 consecutive MEMORY rows of one matrix of one (expert, token tile) entry, over one part of K
+//              (w1/w3, whose rows are interleaved in the blob, always take all of K: their epilogue needs the
+//              complete sums; w2 may split K, its result is accumulated with atomics anyway).
+// Step       = one segment of 16 groups (1024 codes) of a work item: 128 rows x (512 B codes + 64 B pairs) = 72 KB.
+// Block      = 8 waves.  Waves 4-7 (producers) copy the NEXT step's 72 KB from HBM through registers into one of
+//              two LDS buffers, fully coalesced; waves 0-3 (consumers) multiply the CURRENT step out of the other
+//              buffer.  Both roles meet at one barrier per step; a block walks its items (blockIdx.x, +gridDim.x,
+//              ...) without draining the pipeline in between.  The roles are separate because memory loads
+//              return in order per wave: a wave that waits for its small L2 operand loads would also wait for
+//              every older HBM load it has in flight.
+// Consumer   = wave w takes groups w, w+4, w+8, w+12 of the step for all four 32-row tiles: the A operand
+//              (activations of up to 32 tokens, 16 B per lane and MFMA, from L2) is loaded once per group, two
+//              groups ahead, and reused by the four tiles; the B operand comes from LDS as codes, is
+//              dequantised to fp16 in registers, w = (q - z) s computed as (q - rint(z)) s + (rint(z) - z) s
+//              with one rounding, and the MFMA accumulates across all groups of the item (Sec. 4.2 runs the
+//              experts on dequantised fp16 weights; the GEMV kernels keep more).  At the end of an item the four
+//              waves add their partial sums through the LDS buffer just consumed and wave w finishes tile w.
+//
+// MFMA layouts (v_mfma_f32_32x32x16_f16): A lane l = row (token) l%32, k-slot l/32; B lane l = column (memory
+// row) l%32, k-slot l/32; D lane l, register i = row 8*(i/4) + 4*(l/32) + i%4, column l%32.
+#pragma once
+#include "kernels_mfma.h"
+
+namespace moe {
+
+constexpr int TL_CONSUMERS = 4, TL_PRODUCERS = 4;
+constexpr int TL_THREADS = (TL_CONSUMERS + TL_PRODUCERS) * WAVE;
+constexpr int TL_RT = 4;                                 // 32-row tiles per item
+constexpr int TL_ROWS = TL_RT * 32;
+constexpr int TL_SG = 16;                                // groups per step
+constexpr int TL_CODE_PITCH = TL_SG * 32 + 16;           // bytes per staged row of codes (+16: bank spread)
+constexpr int TL_META_PITCH = TL_SG + 1;                 // words per staged row of pairs (odd: bank spread)
+constexpr int TL_BUF_BYTES = TL_ROWS * TL_CODE_PITCH + TL_ROWS * TL_META_PITCH * 4;
+constexpr int TL_LDS_BYTES = 2 * TL_BUF_BYTES;
+constexpr int TL_CP = TL_ROWS * TL_SG * 2 / (TL_PRODUCERS * WAVE);     // 16-byte code pieces per producer thread (16)
+constexpr int TL_MP = TL_ROWS * (TL_SG / 4) / (TL_PRODUCERS * WAVE);   // 16-byte pair pieces per producer thread (2)
+static_assert(TL_CONSUMERS * TL_RT * 16 * 64 * 4 <= TL_BUF_BYTES, "reduction buffer must fit one staging buffer");
+
+struct TileArgs {
+    MfmaEntry e[32];                         // (expert, token tile) entries
+    uint8_t tok[MF_MAX_PAIRS];
+    uint8_t pair[MF_MAX_PAIRS];
+    float w[MF_MAX_PAIRS];
+    const uint16_t *act;                     // w1/w3: h [B][H];   w2: a [B*K][F]
+    uint16_t *a;                             // w1/w3 output
+    float *yacc;                             // w2 output (accumulated)
+    int32_t K, N;                            // contraction length, output rows of the matrix
+    uint32_t stride, meta_off;
+    uint64_t mat_off;
+    int32_t row_blocks, k_parts, seg_per_part, n_items;   // item = ((entry * row_blocks) + row block) * k_parts + part
+};
+
+struct TileStep { int it, seg, seg_hi, rb, e; bool valid; };
+
+// eight codes -> eight fp16 weights: exact integer q - rint(z) first, then one fused multiply-add
+__device__ __forceinline__ h8_t codes_to_w8(uint32_t w, h2_t b1024, h2_t b64, h2_t s2, h2_t c2)
+{
+    const uint32_t hi = w >> 8;
+    const h2_t t0 = __builtin_elementwise_fma(as_h2(and_or(w, 0x000F000Fu, 0x64006400u)) + b1024, s2, c2);
+    const h2_t t1 = __builtin_elementwise_fma(as_h2(and_or(w, 0x00F000F0u, 0x54005400u)) + b64, s2, c2);
+    const h2_t t2 = __builtin_elementwise_fma(as_h2(and_or(hi, 0x000F000Fu, 0x64006400u)) + b1024, s2, c2);
+    const h2_t t3 = __builtin_elementwise_fma(as_h2(and_or(hi, 0x00F000F0u, 0x54005400u)) + b64, s2, c2);
+    h8_t r;
+    r[0] = t0.x; r[1] = t0.y; r[2] = t1.x; r[3] = t1.y; r[4] = t2.x; r[5] = t2.y; r[6] = t3.x; r[7] = t3.y;
+    return r;
+}
+
+template <bool W13>
+__global__ __launch_bounds__(TL_THREADS) void k_mfma_stream_q4(TileArgs A)
+{
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    const int tid = threadIdx.x, lane = tid & 63, wv = uniform(tid >> 6);
+    const bool producer = wv >= TL_CONSUMERS;
+    const int col = lane & 31, kh = lane >> 5;
+    const int n_rows = W13 ? 2 * A.N : A.N;
+    const int groups = A.K / 64, n_seg = (groups + TL_SG - 1) / TL_SG;
+
+    auto at = [&](int it, int seg_or_first) -> TileStep {            // seg_or_first < 0: first step of item `it`
+        TileStep s;
+        s.it = it;
+        s.valid = it < A.n_items;
+        const int part = it % A.k_parts, t = it / A.k_parts;
+        s.rb = t % A.row_blocks;
+        s.e = s.valid ? t / A.row_blocks : 0;
+        const int lo = part * A.seg_per_part;
+        s.seg_hi = min(n_seg, lo + A.seg_per_part);
+        s.seg = seg_or_first < 0 ? lo : seg_or_first;
+        return s;
+    };
+    auto next = [&](const TileStep &s) -> TileStep {
+        if (s.seg + 1 < s.seg_hi) { TileStep n = s; n.seg++; return n; }
+        return at(s.it + (int)gridDim.x, -1);
+    };
+    auto seg_groups = [&](const TileStep &s) { return min(TL_SG, groups - s.seg * TL_SG); };
+
+    TileStep cur = at(blockIdx.x, -1);
+    if (!cur.valid) return;                                          // whole block, before any barrier
+    TileStep nxt = next(cur);
+    int buf = 0;
+
+    // ---------------- producer state ----------------
+    uint4 st_c[TL_CP], st_m[TL_MP];
+    const int ptid = tid - TL_CONSUMERS * WAVE;
+    auto fetch = [&](const TileStep &s) {
+        const uint8_t *mat = A.e[s.e].blob + A.mat_off;
+        const int g0 = s.seg * TL_SG, sg = seg_groups(s), row0 = s.rb * TL_ROWS;
+#pragma unroll
+        for (int i = 0; i < TL_CP; ++i) {
+            const int p = ptid + i * TL_PRODUCERS * WAVE, r = p >> 5, c = p & 31;
+            st_c[i] = ldw4(mat + (size_t)min(row0 + r, n_rows - 1) * A.stride, g0 * 2 + (c < 2 * sg ? c : 0));
+        }
+#pragma unroll
+        for (int i = 0; i < TL_MP; ++i) {
+            const int p = ptid + i * TL_PRODUCERS * WAVE, r = p >> 2, c = p & 3;
+            st_m[i] = ldw4(mat + (size_t)min(row0 + r, n_rows - 1) * A.stride + A.meta_off, g0 / 4 + (c < (sg + 3) / 4 ? c : 0));
+        }
+    };
+    auto commit = [&](int b) {                                       // pieces past a short segment hold copies nobody reads
+        uint8_t *codes = lds + b * TL_BUF_BYTES;
+        uint32_t *meta = reinterpret_cast<uint32_t *>(codes + TL_ROWS * TL_CODE_PITCH);
+#pragma unroll
+        for (int i = 0; i < TL_CP; ++i) {
+            const int p = ptid + i * TL_PRODUCERS * WAVE, r = p >> 5, c = p & 31;
+            *reinterpret_cast<uint4 *>(codes + r * TL_CODE_PITCH + c * 16) = st_c[i];
+        }
+#pragma unroll
+        for (int i = 0; i < TL_MP; ++i) {
+            const int p = ptid + i * TL_PRODUCERS * WAVE, r = p >> 2, c = p & 3;
+            uint32_t *d = meta + r * TL_META_PITCH + c * 4;
+            d[0] = st_m[i].x; d[1] = st_m[i].y; d[2] = st_m[i].z; d[3] = st_m[i].w;
+        }
+    };
+
+    // ---------------- consumer state ----------------
+    f32x16_t acc[TL_RT];
+#pragma unroll
+    for (int rt = 0; rt < TL_RT; ++rt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[rt][i] = 0.f;
+    h8_t av[4][4];                                                   // A operands of the step's four groups of this wave
+    auto token_row = [&](const TileStep &s) -> const uint16_t * {    // lanes past the last token read the first again
+        const MfmaEntry &en = A.e[s.e];
+        const int tk = col < en.n_tok ? col : 0;
+        return A.act + (size_t)(W13 ? A.tok[en.first + tk] : A.pair[en.first + tk]) * A.K;
+    };
+    auto load_a = [&](h8_t (&dst)[4], const uint16_t *row, const TileStep &s, int j) {
+        const int g = s.seg * TL_SG + min(wv + TL_CONSUMERS * j, seg_groups(s) - 1);
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            dst[q] = __builtin_bit_cast(h8_t, *reinterpret_cast<const uint4 *>(row + (size_t)g * 64 + kh * 32 + q * 8));
+    };
+    auto multiply = [&](const h8_t (&a)[4], int b, int gl) {
+        const uint8_t *codes = lds + b * TL_BUF_BYTES;
+        const uint32_t *meta = reinterpret_cast<const uint32_t *>(codes + TL_ROWS * TL_CODE_PITCH);
+#pragma unroll
+        for (int rt = 0; rt < TL_RT; ++rt) {
+            const int r = rt * 32 + col;
+            const uint4 q = *reinterpret_cast<const uint4 *>(codes + r * TL_CODE_PITCH + gl * 32 + kh * 16);
+            const uint32_t m = meta[r * TL_META_PITCH + gl];
+            const _Float16 s16 = __builtin_bit_cast(_Float16, (uint16_t)(m & 0xffff));
+            const _Float16 z16 = __builtin_bit_cast(_Float16, (uint16_t)(m >> 16));
+            const _Float16 zi = __builtin_rintf16(z16);
+            const _Float16 c16 = (zi - z16) * s16, k1024 = (_Float16)-1024.f - zi, k64 = (_Float16)-64.f - zi;
+            const h2_t s2 = {s16, s16}, c2 = {c16, c16}, b1024 = {k1024, k1024}, b64 = {k64, k64};
+            h8_t b[4];
+            b[0] = codes_to_w8(q.x, b1024, b64, s2, c2); b[1] = codes_to_w8(q.y, b1024, b64, s2, c2);
+            b[2] = codes_to_w8(q.z, b1024, b64, s2, c2); b[3] = codes_to_w8(q.w, b1024, b64, s2, c2);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc[rt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[j], b[j], acc[rt], 0, 0, 0);
+        }
+    };
+    auto finish_item = [&](const TileStep &s, int b) {               // after the partial sums are in LDS buffer b
+        const float *red = reinterpret_cast<const float *>(lds + b * TL_BUF_BYTES);   // [wave][tile][16][64]
+        const MfmaEntry &en = A.e[s.e];
+        const int mrow = s.rb * TL_ROWS + wv * 32 + col;             // wave w finishes tile w; this lane's memory row
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            float v = 0.f;
+#pragma unroll
+            for (int w = 0; w < TL_CONSUMERS; ++w) v += red[((w * TL_RT + wv) * 16 + i) * 64 + lane];
+            const int tok = 8 * (i / 4) + 4 * kh + (i % 4);
+            if (W13) {
+                const float other = dpp_f<0xB1>(v);                  // neighbouring column: v of the pair for even lanes
+                if ((lane & 1) == 0 && tok < en.n_tok && mrow < n_rows) {
+                    const _Float16 r = (_Float16)silu_mul(v, other);
+                    A.a[(size_t)A.pair[en.first + tok] * A.N + (mrow >> 1)] = __builtin_bit_cast(uint16_t, r);
+                }
+            } else if (tok < en.n_tok && mrow < n_rows) {
+                atomicAdd(&A.yacc[(size_t)A.tok[en.first + tok] * A.N + mrow], A.w[en.first + tok] * v);
+            }
+        }
+    };
+
+    // The two roles run separate loops over the same sequence of steps and meet at the same barriers: one at the
+    // end of every step, two more where an item ends (partial sums into the consumed buffer, then the epilogue).
+    if (producer) {
+        fetch(cur);
+        commit(0);
+        __syncthreads();
+        while (true) {
+            const bool item_ends = !nxt.valid || nxt.it != cur.it;
+            if (nxt.valid) fetch(nxt);
+            if (item_ends) {
+                __syncthreads();
+                __syncthreads();
+            }
+            if (nxt.valid) commit(buf ^ 1);
+            __syncthreads();                                         // next buffer filled, this one free again
+            if (!nxt.valid) break;
+            cur = nxt;
+            nxt = next(cur);
+            buf ^= 1;
+        }
+        return;
+    }
+
+    const uint16_t *arow = token_row(cur);
+    load_a(av[0], arow, cur, 0);
+    load_a(av[1], arow, cur, 1);
+    __syncthreads();
+    while (true) {
+        const bool item_ends = !nxt.valid || nxt.it != cur.it;
+        const TileStep &after = nxt.valid ? nxt : cur;               // past the last step: re-read, never used
+        const uint16_t *arow_next = token_row(after);
+        const int sg = seg_groups(cur);
+        load_a(av[2], arow, cur, 2);
+        if (wv < sg) multiply(av[0], buf, wv);
+        load_a(av[3], arow, cur, 3);
+        if (wv + TL_CONSUMERS < sg) multiply(av[1], buf, wv + TL_CONSUMERS);
+        load_a(av[0], arow_next, after, 0);
+        if (wv + 2 * TL_CONSUMERS < sg) multiply(av[2], buf, wv + 2 * TL_CONSUMERS);
+        load_a(av[1], arow_next, after, 1);
+        if (wv + 3 * TL_CONSUMERS < sg) multiply(av[3], buf, wv + 3 * TL_CONSUMERS);
+        arow = arow_next;
+        if (item_ends) {
+            __syncthreads();                                         // every consumer is done reading buffer `buf`
+            float *red = reinterpret_cast<float *>(lds + buf * TL_BUF_BYTES);
+#pragma unroll
+            for (int rt = 0; rt < TL_RT; ++rt)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    red[((wv * TL_RT + rt) * 16 + i) * 64 + lane] = acc[rt][i];
+                    acc[rt][i] = 0.f;
+                }
+            __syncthreads();
+            finish_item(cur, buf);
+        }
+        __syncthreads();
+        if (!nxt.valid) break;
+        cur = nxt;
+        nxt = next(cur);
+        buf ^= 1;
+    }
+}
+
+}  // namespace moe

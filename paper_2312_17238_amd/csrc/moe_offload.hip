@@ -100,7 +100,7 @@ struct moe_ctx {
     int32_t n_layers = 0;
     int32_t w13_blocks = 256, w2_rows = 32;
     float *gs_h = nullptr, *gs_a = nullptr;   // group sums of h and of a for the matrix-core path
-    int32_t mfma_form = 1;              // 1: row-streaming matrix-core kernels, 0: direct-to-lane form
+    int32_t mfma_form = 2;              // matrix-core kernels: 0 direct-to-lane, 1 row-streaming with fp32 group scaling, 2 persistent streaming form with fp16 weights
     int32_t mfma_min_batch = 16;        // batches at least this large use the matrix-core kernels (4-bit g64)
     uint64_t spec_head_bytes = 0;       // 0: a speculative load moves the whole expert at once (as the paper describes);
                                         // > 0: only this many leading bytes, the rest when the guess is confirmed
@@ -856,6 +856,61 @@ static int32_t launch_token(moe_layer *l, const FusedArgs &A, bool one_launch, b
 // plus the group-sum tables of their activation operands.
 struct PassExpert { const uint8_t *blob; std::vector<int> pairs; };
 
+// Streaming matrix-core form: persistent producer/consumer blocks over (entry, 128-row block, K part) items.
+// An expert with more than 32 tokens becomes two entries (token tiles) that read the same weights.
+static int32_t launch_mfma_stream(moe_layer *l, const std::vector<PassExpert> &experts, const float *w)
+{
+    moe_ctx *c = l->ctx;
+    const BlobLayout &b = l->lay;
+    const int K = l->cfg.top_k;
+    TileArgs A{};
+    int n = 0, first = 0;
+    for (const PassExpert &pe : experts)
+        for (size_t t0 = 0; t0 < pe.pairs.size(); t0 += 32) {
+            if (n >= 32) return fail(MOE_EINVAL, "more than 32 (expert, token tile) entries in one pass");
+            const size_t t1 = std::min(pe.pairs.size(), t0 + 32);
+            A.e[n].blob = pe.blob;
+            A.e[n].n_tok = (int32_t)(t1 - t0);
+            A.e[n].first = first;
+            for (size_t i = t0; i < t1; ++i) {
+                const int q = pe.pairs[i];
+                A.tok[first] = (uint8_t)(q / K);
+                A.pair[first] = (uint8_t)q;
+                A.w[first] = w[q];
+                ++first;
+            }
+            ++n;
+        }
+    static bool lds_attr_set = false;      // two 74.5 KB staging buffers: above the default dynamic LDS limit
+    if (!lds_attr_set) {
+        HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_stream_q4<true>), hipFuncAttributeMaxDynamicSharedMemorySize, TL_LDS_BYTES));
+        HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_stream_q4<false>), hipFuncAttributeMaxDynamicSharedMemorySize, TL_LDS_BYTES));
+        lds_attr_set = true;
+    }
+    const int n_cu = c->n_cu > 0 ? c->n_cu : 256;
+    auto shape = [&](int rows, int Kdim, bool may_split) {
+        const int n_seg = (Kdim / 64 + TL_SG - 1) / TL_SG;
+        A.row_blocks = (rows + TL_ROWS - 1) / TL_ROWS;
+        int parts = 1;
+        if (may_split) parts = std::min(n_seg, std::max(1, (2 * n_cu + n * A.row_blocks - 1) / (n * A.row_blocks)));
+        A.seg_per_part = (n_seg + parts - 1) / parts;
+        A.k_parts = (n_seg + A.seg_per_part - 1) / A.seg_per_part;       // no empty part
+        A.n_items = n * A.row_blocks * A.k_parts;
+        return dim3(std::min(A.n_items, n_cu));
+    };
+    const uint64_t bytes13 = (uint64_t)n * 2 * b.ffn * b.m13.row_stride, bytes2 = (uint64_t)n * b.hidden * b.m2.row_stride;
+    A.a = c->a_buf; A.yacc = c->yacc;
+    A.act = c->h_buf;
+    A.K = b.hidden; A.N = b.ffn; A.stride = b.m13.row_stride; A.meta_off = b.m13.meta_off; A.mat_off = b.off_w13;
+    const dim3 g13 = shape(2 * b.ffn, b.hidden, false);
+    int32_t rc = launch_timed(c, PROF_W13, bytes13, k_mfma_stream_q4<true>, g13, dim3(TL_THREADS), TL_LDS_BYTES, A);
+    if (rc) return rc;
+    A.act = c->a_buf;
+    A.K = b.ffn; A.N = b.hidden; A.stride = b.m2.row_stride; A.meta_off = b.m2.meta_off; A.mat_off = b.off_w2;
+    const dim3 g2 = shape(b.hidden, b.ffn, true);
+    return launch_timed(c, PROF_W2, bytes2, k_mfma_stream_q4<false>, g2, dim3(TL_THREADS), TL_LDS_BYTES, A);
+}
+
 static int32_t launch_mfma(moe_layer *l, const std::vector<PassExpert> &experts, const float *w, int batch, bool first_pass)
 {
     moe_ctx *c = l->ctx;
@@ -878,7 +933,7 @@ static int32_t launch_mfma(moe_layer *l, const std::vector<PassExpert> &experts,
     }
     const uint64_t bytes13 = (uint64_t)n * 2 * b.ffn * b.m13.row_stride, bytes2 = (uint64_t)n * b.hidden * b.m2.row_stride;
     constexpr int W13W = MOE_MFMA_W13_WAVES, W2W = MOE_MFMA_W2_WAVES;
-    if (first_pass && c->mfma_form != 1) {
+    if (first_pass && c->mfma_form == 0) {
         const int items = batch * (b.hidden / 64);
         hipLaunchKernelGGL(k_group_sums, dim3((items + 255) / 256), dim3(256), 0, c->compute, c->h_buf, c->gs_h, batch, b.hidden);
         HIPCHK(hipGetLastError());
@@ -890,25 +945,24 @@ static int32_t launch_mfma(moe_layer *l, const std::vector<PassExpert> &experts,
         const int sg = std::min(K / 64, MF2_SEG);
         return std::max<size_t>((size_t)32 * (sg * 32 + 16) + (size_t)32 * ((sg + 3) & ~3) * 4, (size_t)MF2_WAVES * mt * 16 * 64 * 4);
     };
-    static bool lds_attr_set = false;      // these kernels stage 72 KB: above the default dynamic LDS limit
-    if (!lds_attr_set) {
-        const int lim = 96 * 1024;
-        HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_rows_q4<true, 1>), hipFuncAttributeMaxDynamicSharedMemorySize, lim));
-        HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_rows_q4<true, 2>), hipFuncAttributeMaxDynamicSharedMemorySize, lim));
-        HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_rows_q4<false, 1>), hipFuncAttributeMaxDynamicSharedMemorySize, lim));
-        HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_rows_q4<false, 2>), hipFuncAttributeMaxDynamicSharedMemorySize, lim));
-        lds_attr_set = true;
-    }
     const int mt = max_tok > 32 ? 2 : 1;
-    const dim3 blkr(MF2_WAVES * WAVE);
+    if (c->mfma_form == 2) return launch_mfma_stream(l, experts, w);
     if (c->mfma_form == 1) {
-        const dim3 gr13((2 * b.ffn + 31) / 32, n);
+        static bool lds_attr_set = false;  // these kernels stage 72 KB: above the default dynamic LDS limit
+        if (!lds_attr_set) {
+            const int lim = 96 * 1024;
+            HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_rows_q4<true, 1>), hipFuncAttributeMaxDynamicSharedMemorySize, lim));
+            HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_rows_q4<true, 2>), hipFuncAttributeMaxDynamicSharedMemorySize, lim));
+            HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_rows_q4<false, 1>), hipFuncAttributeMaxDynamicSharedMemorySize, lim));
+            HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_rows_q4<false, 2>), hipFuncAttributeMaxDynamicSharedMemorySize, lim));
+            lds_attr_set = true;
+        }
+        const dim3 blkr(MF2_WAVES * WAVE), gr13((2 * b.ffn + 31) / 32, n), gr2((b.hidden + 31) / 32, n);
         int32_t rr = mt == 2 ? launch_timed(c, PROF_W13, bytes13, k_mfma_rows_q4<true, 2>, gr13, blkr, rows_lds(b.hidden, 2), A)
                              : launch_timed(c, PROF_W13, bytes13, k_mfma_rows_q4<true, 1>, gr13, blkr, rows_lds(b.hidden, 1), A);
         if (rr) return rr;
         A.act = c->a_buf; A.gsum = c->gs_a;
         A.K = b.ffn; A.N = b.hidden; A.stride = b.m2.row_stride; A.meta_off = b.m2.meta_off; A.mat_off = b.off_w2;
-        const dim3 gr2((b.hidden + 31) / 32, n);
         return mt == 2 ? launch_timed(c, PROF_W2, bytes2, k_mfma_rows_q4<false, 2>, gr2, blkr, rows_lds(b.ffn, 2), A)
                        : launch_timed(c, PROF_W2, bytes2, k_mfma_rows_q4<false, 1>, gr2, blkr, rows_lds(b.ffn, 1), A);
     }
@@ -1197,7 +1251,7 @@ extern "C" int32_t moe_ctx_set_option(moe_ctx_t *c, const char *name, int32_t va
     else if (n == "token_path") c->token_path = value != 0;
     else if (n == "spec_head_mb" && value >= 0) c->spec_head_bytes = (uint64_t)value << 20;
     else if (n == "mfma_min_batch" && value >= 1) c->mfma_min_batch = value;
-    else if (n == "mfma_form" && (value == 0 || value == 1)) c->mfma_form = value;
+    else if (n == "mfma_form" && value >= 0 && value <= 2) c->mfma_form = value;
     else return fail(MOE_EINVAL, "moe_ctx_set_option: unknown option or bad value: %s = %d", name, value);
     return MOE_OK;
 }
