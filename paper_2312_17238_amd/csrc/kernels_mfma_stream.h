@@ -35,7 +35,8 @@ constexpr int TL_SG = 16;                                // groups per step
 constexpr int TL_CODE_PITCH = TL_SG * 32 + 16;           // bytes per staged row of codes (+16: bank spread)
 constexpr int TL_META_PITCH = TL_SG + 1;                 // words per staged row of pairs (odd: bank spread)
 constexpr int TL_BUF_BYTES = TL_ROWS * TL_CODE_PITCH + TL_ROWS * TL_META_PITCH * 4;
-constexpr int TL_LDS_BYTES = 2 * TL_BUF_BYTES;
+constexpr int TL_TABLE_BYTES = MF_MAX_PAIRS * 6;         // token, pair (bytes) and combine weight (float) of every pair
+constexpr int TL_LDS_BYTES = 2 * TL_BUF_BYTES + TL_TABLE_BYTES;
 constexpr int TL_CP = TL_ROWS * TL_SG * 2 / (TL_PRODUCERS * WAVE);     // 16-byte code pieces per producer thread (16)
 constexpr int TL_MP = TL_ROWS * (TL_SG / 4) / (TL_PRODUCERS * WAVE);   // 16-byte pair pieces per producer thread (2)
 static_assert(TL_CONSUMERS * TL_RT * 16 * 64 * 4 <= TL_BUF_BYTES, "reduction buffer must fit one staging buffer");
@@ -51,6 +52,7 @@ struct TileArgs {
     int32_t K, N;                            // contraction length, output rows of the matrix
     uint32_t stride, meta_off;
     uint64_t mat_off;
+    int32_t debug;
     int32_t row_blocks, k_parts, seg_per_part, n_items;   // item = ((entry * row_blocks) + row block) * k_parts + part
 };
 
@@ -99,6 +101,15 @@ __global__ __launch_bounds__(TL_THREADS) void k_mfma_stream_q4(TileArgs A)
 
     TileStep cur = at(blockIdx.x, -1);
     if (!cur.valid) return;                                          // whole block, before any barrier
+    // the pair tables move from the kernel arguments to LDS once: the steps look them up with per-lane indices
+    float *l_w = reinterpret_cast<float *>(lds + 2 * TL_BUF_BYTES);
+    uint8_t *l_tok = reinterpret_cast<uint8_t *>(l_w + MF_MAX_PAIRS), *l_pair = l_tok + MF_MAX_PAIRS;
+    if (tid < MF_MAX_PAIRS) {
+        l_w[tid] = A.w[tid];
+        l_tok[tid] = A.tok[tid];
+        l_pair[tid] = A.pair[tid];
+    }
+    __syncthreads();
     TileStep nxt = next(cur);
     int buf = 0;
 
@@ -145,7 +156,7 @@ __global__ __launch_bounds__(TL_THREADS) void k_mfma_stream_q4(TileArgs A)
     auto token_row = [&](const TileStep &s) -> const uint16_t * {    // lanes past the last token read the first again
         const MfmaEntry &en = A.e[s.e];
         const int tk = col < en.n_tok ? col : 0;
-        return A.act + (size_t)(W13 ? A.tok[en.first + tk] : A.pair[en.first + tk]) * A.K;
+        return A.act + (size_t)(W13 ? l_tok[en.first + tk] : l_pair[en.first + tk]) * A.K;
     };
     auto load_a = [&](h8_t (&dst)[4], const uint16_t *row, const TileStep &s, int j) {
         const int g = s.seg * TL_SG + min(wv + TL_CONSUMERS * j, seg_groups(s) - 1);
@@ -153,30 +164,52 @@ __global__ __launch_bounds__(TL_THREADS) void k_mfma_stream_q4(TileArgs A)
         for (int q = 0; q < 4; ++q)
             dst[q] = __builtin_bit_cast(h8_t, *reinterpret_cast<const uint4 *>(row + (size_t)g * 64 + kh * 32 + q * 8));
     };
-    auto multiply = [&](const h8_t (&a)[4], int b, int gl) {
+    // One unit = one group of one 32-row tile.  Its codes and pair are read from LDS one unit ahead of their use,
+    // so that the single consumer wave of a SIMD does not sit out the LDS latency sixteen times per step.
+    auto unit_load = [&](int b, int gl, int rt, uint4 &q, uint32_t &m) {
         const uint8_t *codes = lds + b * TL_BUF_BYTES;
         const uint32_t *meta = reinterpret_cast<const uint32_t *>(codes + TL_ROWS * TL_CODE_PITCH);
+        const int r = rt * 32 + col;
+        q = *reinterpret_cast<const uint4 *>(codes + r * TL_CODE_PITCH + gl * 32 + kh * 16);
+        m = meta[r * TL_META_PITCH + gl];
+    };
+    auto unit_multiply = [&](const h8_t (&a)[4], const uint4 &q, uint32_t m, int rt) {
+        const _Float16 s16 = __builtin_bit_cast(_Float16, (uint16_t)(m & 0xffff));
+        const _Float16 z16 = __builtin_bit_cast(_Float16, (uint16_t)(m >> 16));
+        const _Float16 zi = __builtin_rintf16(z16);
+        const _Float16 c16 = (zi - z16) * s16, k1024 = (_Float16)-1024.f - zi, k64 = (_Float16)-64.f - zi;
+        const h2_t s2 = {s16, s16}, c2 = {c16, c16}, b1024 = {k1024, k1024}, b64 = {k64, k64};
+        h8_t b[4];
+        b[0] = codes_to_w8(q.x, b1024, b64, s2, c2); b[1] = codes_to_w8(q.y, b1024, b64, s2, c2);
+        b[2] = codes_to_w8(q.z, b1024, b64, s2, c2); b[3] = codes_to_w8(q.w, b1024, b64, s2, c2);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[rt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[j], b[j], acc[rt], 0, 0, 0);
+    };
+    uint4 q_next = make_uint4(0, 0, 0, 0);
+    uint32_t m_next = 0;
+    auto group_multiply = [&](const h8_t (&a)[4], int b, int gl, int sg) {   // q_next/m_next hold tile 0 of group gl
 #pragma unroll
         for (int rt = 0; rt < TL_RT; ++rt) {
-            const int r = rt * 32 + col;
-            const uint4 q = *reinterpret_cast<const uint4 *>(codes + r * TL_CODE_PITCH + gl * 32 + kh * 16);
-            const uint32_t m = meta[r * TL_META_PITCH + gl];
-            const _Float16 s16 = __builtin_bit_cast(_Float16, (uint16_t)(m & 0xffff));
-            const _Float16 z16 = __builtin_bit_cast(_Float16, (uint16_t)(m >> 16));
-            const _Float16 zi = __builtin_rintf16(z16);
-            const _Float16 c16 = (zi - z16) * s16, k1024 = (_Float16)-1024.f - zi, k64 = (_Float16)-64.f - zi;
-            const h2_t s2 = {s16, s16}, c2 = {c16, c16}, b1024 = {k1024, k1024}, b64 = {k64, k64};
-            h8_t b[4];
-            b[0] = codes_to_w8(q.x, b1024, b64, s2, c2); b[1] = codes_to_w8(q.y, b1024, b64, s2, c2);
-            b[2] = codes_to_w8(q.z, b1024, b64, s2, c2); b[3] = codes_to_w8(q.w, b1024, b64, s2, c2);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) acc[rt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[j], b[j], acc[rt], 0, 0, 0);
+            const uint4 q = q_next;
+            const uint32_t m = m_next;
+            if (rt + 1 < TL_RT) unit_load(b, gl, rt + 1, q_next, m_next);
+            else if (gl + TL_CONSUMERS < sg) unit_load(b, gl + TL_CONSUMERS, 0, q_next, m_next);
+            unit_multiply(a, q, m, rt);
         }
     };
     auto finish_item = [&](const TileStep &s, int b) {               // after the partial sums are in LDS buffer b
         const float *red = reinterpret_cast<const float *>(lds + b * TL_BUF_BYTES);   // [wave][tile][16][64]
         const MfmaEntry &en = A.e[s.e];
         const int mrow = s.rb * TL_ROWS + wv * 32 + col;             // wave w finishes tile w; this lane's memory row
+        // the sixteen tokens of this lane's accumulators: table look-ups first, all in flight together
+        int dst[16];
+        float wgt[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int tk = en.first + min(8 * (i / 4) + 4 * kh + (i % 4), en.n_tok - 1);
+            dst[i] = W13 ? l_pair[tk] : l_tok[tk];
+            wgt[i] = W13 ? 0.f : l_w[tk];
+        }
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
             float v = 0.f;
@@ -185,12 +218,10 @@ __global__ __launch_bounds__(TL_THREADS) void k_mfma_stream_q4(TileArgs A)
             const int tok = 8 * (i / 4) + 4 * kh + (i % 4);
             if (W13) {
                 const float other = dpp_f<0xB1>(v);                  // neighbouring column: v of the pair for even lanes
-                if ((lane & 1) == 0 && tok < en.n_tok && mrow < n_rows) {
-                    const _Float16 r = (_Float16)silu_mul(v, other);
-                    A.a[(size_t)A.pair[en.first + tok] * A.N + (mrow >> 1)] = __builtin_bit_cast(uint16_t, r);
-                }
+                if ((lane & 1) == 0 && tok < en.n_tok && mrow < n_rows)
+                    A.a[(size_t)dst[i] * A.N + (mrow >> 1)] = __builtin_bit_cast(uint16_t, (_Float16)silu_mul(v, other));
             } else if (tok < en.n_tok && mrow < n_rows) {
-                atomicAdd(&A.yacc[(size_t)A.tok[en.first + tok] * A.N + mrow], A.w[en.first + tok] * v);
+                atomicAdd(&A.yacc[(size_t)dst[i] * A.N + mrow], wgt[i] * v);
             }
         }
     };
@@ -203,12 +234,12 @@ __global__ __launch_bounds__(TL_THREADS) void k_mfma_stream_q4(TileArgs A)
         __syncthreads();
         while (true) {
             const bool item_ends = !nxt.valid || nxt.it != cur.it;
-            if (nxt.valid) fetch(nxt);
+            if (nxt.valid && !(A.debug & 1)) fetch(nxt);
             if (item_ends) {
                 __syncthreads();
                 __syncthreads();
             }
-            if (nxt.valid) commit(buf ^ 1);
+            if (nxt.valid && !(A.debug & 1)) commit(buf ^ 1);
             __syncthreads();                                         // next buffer filled, this one free again
             if (!nxt.valid) break;
             cur = nxt;
@@ -226,15 +257,19 @@ __global__ __launch_bounds__(TL_THREADS) void k_mfma_stream_q4(TileArgs A)
         const bool item_ends = !nxt.valid || nxt.it != cur.it;
         const TileStep &after = nxt.valid ? nxt : cur;               // past the last step: re-read, never used
         const uint16_t *arow_next = token_row(after);
-        const int sg = seg_groups(cur);
+        int sg = seg_groups(cur);
+        if (wv < sg) unit_load(buf, wv, 0, q_next, m_next);
+        if (A.debug & 2) sg = 0;
+        if (!(A.debug & 4)) {
         load_a(av[2], arow, cur, 2);
-        if (wv < sg) multiply(av[0], buf, wv);
+        if (wv < sg) group_multiply(av[0], buf, wv, sg);
         load_a(av[3], arow, cur, 3);
-        if (wv + TL_CONSUMERS < sg) multiply(av[1], buf, wv + TL_CONSUMERS);
-        load_a(av[0], arow_next, after, 0);
-        if (wv + 2 * TL_CONSUMERS < sg) multiply(av[2], buf, wv + 2 * TL_CONSUMERS);
-        load_a(av[1], arow_next, after, 1);
-        if (wv + 3 * TL_CONSUMERS < sg) multiply(av[3], buf, wv + 3 * TL_CONSUMERS);
+        }
+        if (wv + TL_CONSUMERS < sg) group_multiply(av[1], buf, wv + TL_CONSUMERS, sg);
+        if (!(A.debug & 4)) load_a(av[0], arow_next, after, 0);
+        if (wv + 2 * TL_CONSUMERS < sg) group_multiply(av[2], buf, wv + 2 * TL_CONSUMERS, sg);
+        if (!(A.debug & 4)) load_a(av[1], arow_next, after, 1);
+        if (wv + 3 * TL_CONSUMERS < sg) group_multiply(av[3], buf, wv + 3 * TL_CONSUMERS, sg);
         arow = arow_next;
         if (item_ends) {
             __syncthreads();                                         // every consumer is done reading buffer `buf`
@@ -247,7 +282,7 @@ __global__ __launch_bounds__(TL_THREADS) void k_mfma_stream_q4(TileArgs A)
                     acc[rt][i] = 0.f;
                 }
             __syncthreads();
-            finish_item(cur, buf);
+            if (!(A.debug & 8)) finish_item(cur, buf);
         }
         __syncthreads();
         if (!nxt.valid) break;
