@@ -146,7 +146,6 @@ def main() -> int:
     if args.no_cache:
         stack.set_flags(B.MOE_LAYER_NO_CACHE)
     B.moe_ctx_set_option(stack.ctx, "spec_head_mb", args.spec_head_mb)
-    if os.environ.get("MOE_MFMA_DEBUG"): B.moe_ctx_set_option(stack.ctx, "mfma_debug", int(os.environ["MOE_MFMA_DEBUG"]))  # TEMP
     if args.fused:
         B.moe_ctx_set_option(stack.ctx, "fused", 1)
     if args.no_token_path:

@@ -1,24 +1,23 @@
-// Grouped dequantize+GEMM on the matrix cores, streaming form: persistent blocks with producer and consumer
-// waves, built so that the weights cross HBM once in long coalesced reads and the vector unit does the
-// minimum of work per weight.
+// Grouped dequantize+GEMM on the matrix cores, streaming form: persistent blocks built so that the weights
+// cross HBM once in long coalesced reads, every load is issued a whole step before its use, and the vector
+// unit does the minimum of work per weight.
 //
 // Work item  = 128 consecutive MEMORY rows of one matrix of one (expert, token tile) entry, over one part of K
 //              (w1/w3, whose rows are interleaved in the blob, always take all of K: their epilogue needs the
 //              complete sums; w2 may split K, its result is accumulated with atomics anyway).
 // Step       = one segment of 16 groups (1024 codes) of a work item: 128 rows x (512 B codes + 64 B pairs) = 72 KB.
-// Block      = 8 waves.  Waves 4-7 (producers) copy the NEXT step's 72 KB from HBM through registers into one of
-//              two LDS buffers, fully coalesced; waves 0-3 (consumers) multiply the CURRENT step out of the other
-//              buffer.  Both roles meet at one barrier per step; a block walks its items (blockIdx.x, +gridDim.x,
-//              ...) without draining the pipeline in between.  The roles are separate because memory loads
-//              return in order per wave: a wave that waits for its small L2 operand loads would also wait for
-//              every older HBM load it has in flight.
-// Consumer   = wave w takes groups w, w+4, w+8, w+12 of the step for all four 32-row tiles: the A operand
-//              (activations of up to 32 tokens, 16 B per lane and MFMA, from L2) is loaded once per group, two
-//              groups ahead, and reused by the four tiles; the B operand comes from LDS as codes, is
-//              dequantised to fp16 in registers, w = (q - z) s computed as (q - rint(z)) s + (rint(z) - z) s
-//              with one rounding, and the MFMA accumulates across all groups of the item (Sec. 4.2 runs the
-//              experts on dequantised fp16 weights; the GEMV kernels keep more).  At the end of an item the four
-//              waves add their partial sums through the LDS buffer just consumed and wave w finishes tile w.
+// Block      = 8 waves, one per compute unit, walking its items (blockIdx.x, +gridDim.x, ...) as one sequence of
+//              steps.  During step s every wave first requests what step s+1 needs -- its own A operands
+//              (activations of up to 32 tokens, from L2) and its share of the 72 KB of weights (from HBM, into
+//              registers) -- then multiplies step s out of one of two LDS buffers, then stores the arrived weights
+//              to the other buffer; one barrier per step.  Memory loads return in order per wave, so nothing
+//              inside the multiply may wait for a load: that is why the A operands travel a full step ahead.
+// Wave w     = groups w and w+8 of the step for all four 32-row tiles: A operand once per group, reused by the four
+//              tiles; B operand from LDS as codes (read one tile ahead), dequantised to fp16 in registers,
+//              w = (q - z) s computed as (q - rint(z)) s + (rint(z) - z) s with one rounding, and the MFMA
+//              accumulates across all groups of the item (Sec. 4.2 runs the experts on dequantised fp16
+//              weights; the GEMV kernels keep more).  At the end of an item the eight waves add their partial
+//              sums through the LDS buffer just consumed, two tiles at a time, in a fixed order.
 //
 // MFMA layouts (v_mfma_f32_32x32x16_f16): A lane l = row (token) l%32, k-slot l/32; B lane l = column (memory
 // row) l%32, k-slot l/32; D lane l, register i = row 8*(i/4) + 4*(l/32) + i%4, column l%32.
@@ -27,19 +26,21 @@
 
 namespace moe {
 
-constexpr int TL_CONSUMERS = 4, TL_PRODUCERS = 4;
-constexpr int TL_THREADS = (TL_CONSUMERS + TL_PRODUCERS) * WAVE;
+constexpr int TL_WAVES = 8;
+constexpr int TL_THREADS = TL_WAVES * WAVE;
 constexpr int TL_RT = 4;                                 // 32-row tiles per item
 constexpr int TL_ROWS = TL_RT * 32;
 constexpr int TL_SG = 16;                                // groups per step
+constexpr int TL_GPW = TL_SG / TL_WAVES;                 // groups per wave and step (2)
 constexpr int TL_CODE_PITCH = TL_SG * 32 + 16;           // bytes per staged row of codes (+16: bank spread)
 constexpr int TL_META_PITCH = TL_SG + 1;                 // words per staged row of pairs (odd: bank spread)
 constexpr int TL_BUF_BYTES = TL_ROWS * TL_CODE_PITCH + TL_ROWS * TL_META_PITCH * 4;
 constexpr int TL_TABLE_BYTES = MF_MAX_PAIRS * 6;         // token, pair (bytes) and combine weight (float) of every pair
 constexpr int TL_LDS_BYTES = 2 * TL_BUF_BYTES + TL_TABLE_BYTES;
-constexpr int TL_CP = TL_ROWS * TL_SG * 2 / (TL_PRODUCERS * WAVE);     // 16-byte code pieces per producer thread (16)
-constexpr int TL_MP = TL_ROWS * (TL_SG / 4) / (TL_PRODUCERS * WAVE);   // 16-byte pair pieces per producer thread (2)
-static_assert(TL_CONSUMERS * TL_RT * 16 * 64 * 4 <= TL_BUF_BYTES, "reduction buffer must fit one staging buffer");
+constexpr int TL_CP = TL_ROWS * TL_SG * 2 / TL_THREADS;  // 16-byte code pieces per thread and step (8)
+constexpr int TL_MP = TL_ROWS * (TL_SG / 4) / TL_THREADS;   // 16-byte pair pieces per thread and step (1)
+static_assert(TL_WAVES * 2 * 16 * 64 * 4 <= TL_BUF_BYTES, "one reduction round (two tiles of every wave) must fit a staging buffer");
+static_assert(TL_CP * TL_THREADS == TL_ROWS * TL_SG * 2 && TL_MP * TL_THREADS == TL_ROWS * (TL_SG / 4), "pieces must divide evenly");
 
 struct TileArgs {
     MfmaEntry e[32];                         // (expert, token tile) entries
@@ -52,7 +53,6 @@ struct TileArgs {
     int32_t K, N;                            // contraction length, output rows of the matrix
     uint32_t stride, meta_off;
     uint64_t mat_off;
-    int32_t debug;
     int32_t row_blocks, k_parts, seg_per_part, n_items;   // item = ((entry * row_blocks) + row block) * k_parts + part
 };
 
@@ -76,30 +76,28 @@ __global__ __launch_bounds__(TL_THREADS) void k_mfma_stream_q4(TileArgs A)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const int tid = threadIdx.x, lane = tid & 63, wv = uniform(tid >> 6);
-    const bool producer = wv >= TL_CONSUMERS;
     const int col = lane & 31, kh = lane >> 5;
     const int n_rows = W13 ? 2 * A.N : A.N;
     const int groups = A.K / 64, n_seg = (groups + TL_SG - 1) / TL_SG;
 
-    auto at = [&](int it, int seg_or_first) -> TileStep {            // seg_or_first < 0: first step of item `it`
+    auto first_step = [&](int it) -> TileStep {
         TileStep s;
         s.it = it;
         s.valid = it < A.n_items;
         const int part = it % A.k_parts, t = it / A.k_parts;
         s.rb = t % A.row_blocks;
         s.e = s.valid ? t / A.row_blocks : 0;
-        const int lo = part * A.seg_per_part;
-        s.seg_hi = min(n_seg, lo + A.seg_per_part);
-        s.seg = seg_or_first < 0 ? lo : seg_or_first;
+        s.seg = part * A.seg_per_part;
+        s.seg_hi = min(n_seg, s.seg + A.seg_per_part);
         return s;
     };
     auto next = [&](const TileStep &s) -> TileStep {
         if (s.seg + 1 < s.seg_hi) { TileStep n = s; n.seg++; return n; }
-        return at(s.it + (int)gridDim.x, -1);
+        return first_step(s.it + (int)gridDim.x);
     };
     auto seg_groups = [&](const TileStep &s) { return min(TL_SG, groups - s.seg * TL_SG); };
 
-    TileStep cur = at(blockIdx.x, -1);
+    TileStep cur = first_step(blockIdx.x);
     if (!cur.valid) return;                                          // whole block, before any barrier
     // the pair tables move from the kernel arguments to LDS once: the steps look them up with per-lane indices
     float *l_w = reinterpret_cast<float *>(lds + 2 * TL_BUF_BYTES);
@@ -113,20 +111,19 @@ __global__ __launch_bounds__(TL_THREADS) void k_mfma_stream_q4(TileArgs A)
     TileStep nxt = next(cur);
     int buf = 0;
 
-    // ---------------- producer state ----------------
+    // ---------------- weights: HBM -> registers -> LDS ----------------
     uint4 st_c[TL_CP], st_m[TL_MP];
-    const int ptid = tid - TL_CONSUMERS * WAVE;
     auto fetch = [&](const TileStep &s) {
         const uint8_t *mat = A.e[s.e].blob + A.mat_off;
         const int g0 = s.seg * TL_SG, sg = seg_groups(s), row0 = s.rb * TL_ROWS;
 #pragma unroll
         for (int i = 0; i < TL_CP; ++i) {
-            const int p = ptid + i * TL_PRODUCERS * WAVE, r = p >> 5, c = p & 31;
+            const int p = tid + i * TL_THREADS, r = p >> 5, c = p & 31;
             st_c[i] = ldw4(mat + (size_t)min(row0 + r, n_rows - 1) * A.stride, g0 * 2 + (c < 2 * sg ? c : 0));
         }
 #pragma unroll
         for (int i = 0; i < TL_MP; ++i) {
-            const int p = ptid + i * TL_PRODUCERS * WAVE, r = p >> 2, c = p & 3;
+            const int p = tid + i * TL_THREADS, r = p >> 2, c = p & 3;
             st_m[i] = ldw4(mat + (size_t)min(row0 + r, n_rows - 1) * A.stride + A.meta_off, g0 / 4 + (c < (sg + 3) / 4 ? c : 0));
         }
     };
@@ -135,37 +132,39 @@ __global__ __launch_bounds__(TL_THREADS) void k_mfma_stream_q4(TileArgs A)
         uint32_t *meta = reinterpret_cast<uint32_t *>(codes + TL_ROWS * TL_CODE_PITCH);
 #pragma unroll
         for (int i = 0; i < TL_CP; ++i) {
-            const int p = ptid + i * TL_PRODUCERS * WAVE, r = p >> 5, c = p & 31;
+            const int p = tid + i * TL_THREADS, r = p >> 5, c = p & 31;
             *reinterpret_cast<uint4 *>(codes + r * TL_CODE_PITCH + c * 16) = st_c[i];
         }
 #pragma unroll
         for (int i = 0; i < TL_MP; ++i) {
-            const int p = ptid + i * TL_PRODUCERS * WAVE, r = p >> 2, c = p & 3;
+            const int p = tid + i * TL_THREADS, r = p >> 2, c = p & 3;
             uint32_t *d = meta + r * TL_META_PITCH + c * 4;
             d[0] = st_m[i].x; d[1] = st_m[i].y; d[2] = st_m[i].z; d[3] = st_m[i].w;
         }
     };
 
-    // ---------------- consumer state ----------------
+    // ---------------- multiply ----------------
     f32x16_t acc[TL_RT];
 #pragma unroll
     for (int rt = 0; rt < TL_RT; ++rt)
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[rt][i] = 0.f;
-    h8_t av[4][4];                                                   // A operands of the step's four groups of this wave
     auto token_row = [&](const TileStep &s) -> const uint16_t * {    // lanes past the last token read the first again
         const MfmaEntry &en = A.e[s.e];
         const int tk = col < en.n_tok ? col : 0;
         return A.act + (size_t)(W13 ? l_tok[en.first + tk] : l_pair[en.first + tk]) * A.K;
     };
-    auto load_a = [&](h8_t (&dst)[4], const uint16_t *row, const TileStep &s, int j) {
-        const int g = s.seg * TL_SG + min(wv + TL_CONSUMERS * j, seg_groups(s) - 1);
+    auto load_a = [&](h8_t (&dst)[TL_GPW][4], const TileStep &s) {   // this wave's A operands of step s
+        const uint16_t *row = token_row(s);
 #pragma unroll
-        for (int q = 0; q < 4; ++q)
-            dst[q] = __builtin_bit_cast(h8_t, *reinterpret_cast<const uint4 *>(row + (size_t)g * 64 + kh * 32 + q * 8));
+        for (int j = 0; j < TL_GPW; ++j) {
+            const int g = s.seg * TL_SG + min(wv + TL_WAVES * j, seg_groups(s) - 1);
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                dst[j][q] = __builtin_bit_cast(h8_t, *reinterpret_cast<const uint4 *>(row + (size_t)g * 64 + kh * 32 + q * 8));
+        }
     };
-    // One unit = one group of one 32-row tile.  Its codes and pair are read from LDS one unit ahead of their use,
-    // so that the single consumer wave of a SIMD does not sit out the LDS latency sixteen times per step.
+    // One unit = one group of one 32-row tile; its codes and pair are read from LDS one unit ahead of their use.
     auto unit_load = [&](int b, int gl, int rt, uint4 &q, uint32_t &m) {
         const uint8_t *codes = lds + b * TL_BUF_BYTES;
         const uint32_t *meta = reinterpret_cast<const uint32_t *>(codes + TL_ROWS * TL_CODE_PITCH);
@@ -193,102 +192,85 @@ __global__ __launch_bounds__(TL_THREADS) void k_mfma_stream_q4(TileArgs A)
             const uint4 q = q_next;
             const uint32_t m = m_next;
             if (rt + 1 < TL_RT) unit_load(b, gl, rt + 1, q_next, m_next);
-            else if (gl + TL_CONSUMERS < sg) unit_load(b, gl + TL_CONSUMERS, 0, q_next, m_next);
+            else if (gl + TL_WAVES < sg) unit_load(b, gl + TL_WAVES, 0, q_next, m_next);
             unit_multiply(a, q, m, rt);
         }
     };
-    auto finish_item = [&](const TileStep &s, int b) {               // after the partial sums are in LDS buffer b
-        const float *red = reinterpret_cast<const float *>(lds + b * TL_BUF_BYTES);   // [wave][tile][16][64]
+
+    // ---------------- end of an item: add the eight waves' partial sums, finish, store ----------------
+    // Two rounds of two tiles each through LDS buffer b (free: every wave is past its last read of it).  In a
+    // round wave v owns tile v/4 of the pair and registers 4 (v%4) .. +3, i.e. tokens 8 (v%4) + 4 (l/32) + 0..3.
+    auto finish_item = [&](const TileStep &s, int b) {
+        float *red = reinterpret_cast<float *>(lds + b * TL_BUF_BYTES);   // [wave][tile of the round][16][64]
         const MfmaEntry &en = A.e[s.e];
-        const int mrow = s.rb * TL_ROWS + wv * 32 + col;             // wave w finishes tile w; this lane's memory row
-        // the sixteen tokens of this lane's accumulators: table look-ups first, all in flight together
-        int dst[16];
-        float wgt[16];
+        int dst[4];
+        float wgt[4];
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int tk = en.first + min(8 * (i / 4) + 4 * kh + (i % 4), en.n_tok - 1);
-            dst[i] = W13 ? l_pair[tk] : l_tok[tk];
-            wgt[i] = W13 ? 0.f : l_w[tk];
+        for (int ii = 0; ii < 4; ++ii) {
+            const int tk = en.first + min(8 * (wv & 3) + 4 * kh + ii, en.n_tok - 1);
+            dst[ii] = W13 ? l_pair[tk] : l_tok[tk];
+            wgt[ii] = W13 ? 0.f : l_w[tk];
         }
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            float v = 0.f;
+        for (int round = 0; round < TL_RT / 2; ++round) {
+            __syncthreads();                                         // buffer free (first round) / previous round read
 #pragma unroll
-            for (int w = 0; w < TL_CONSUMERS; ++w) v += red[((w * TL_RT + wv) * 16 + i) * 64 + lane];
-            const int tok = 8 * (i / 4) + 4 * kh + (i % 4);
-            if (W13) {
-                const float other = dpp_f<0xB1>(v);                  // neighbouring column: v of the pair for even lanes
-                if ((lane & 1) == 0 && tok < en.n_tok && mrow < n_rows)
-                    A.a[(size_t)dst[i] * A.N + (mrow >> 1)] = __builtin_bit_cast(uint16_t, (_Float16)silu_mul(v, other));
-            } else if (tok < en.n_tok && mrow < n_rows) {
-                atomicAdd(&A.yacc[(size_t)dst[i] * A.N + mrow], wgt[i] * v);
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    red[((wv * 2 + t) * 16 + i) * 64 + lane] = acc[round * 2 + t][i];
+                    acc[round * 2 + t][i] = 0.f;
+                }
+            __syncthreads();
+            const int t = wv >> 2;
+            const int mrow = s.rb * TL_ROWS + (round * 2 + t) * 32 + col;
+#pragma unroll
+            for (int ii = 0; ii < 4; ++ii) {
+                const int i = (wv & 3) * 4 + ii;
+                float v = 0.f;
+#pragma unroll
+                for (int w = 0; w < TL_WAVES; ++w) v += red[((w * 2 + t) * 16 + i) * 64 + lane];
+                const int tok = 8 * (wv & 3) + 4 * kh + ii;
+                if (W13) {
+                    const float other = dpp_f<0xB1>(v);              // neighbouring column: v of the pair for even lanes
+                    if ((lane & 1) == 0 && tok < en.n_tok && mrow < n_rows)
+                        A.a[(size_t)dst[ii] * A.N + (mrow >> 1)] = __builtin_bit_cast(uint16_t, (_Float16)silu_mul(v, other));
+                } else if (tok < en.n_tok && mrow < n_rows) {
+                    atomicAdd(&A.yacc[(size_t)dst[ii] * A.N + mrow], wgt[ii] * v);
+                }
             }
         }
     };
 
-    // The two roles run separate loops over the same sequence of steps and meet at the same barriers: one at the
-    // end of every step, two more where an item ends (partial sums into the consumed buffer, then the epilogue).
-    if (producer) {
-        fetch(cur);
-        commit(0);
-        __syncthreads();
-        while (true) {
-            const bool item_ends = !nxt.valid || nxt.it != cur.it;
-            if (nxt.valid && !(A.debug & 1)) fetch(nxt);
-            if (item_ends) {
-                __syncthreads();
-                __syncthreads();
-            }
-            if (nxt.valid && !(A.debug & 1)) commit(buf ^ 1);
-            __syncthreads();                                         // next buffer filled, this one free again
-            if (!nxt.valid) break;
-            cur = nxt;
-            nxt = next(cur);
-            buf ^= 1;
-        }
-        return;
-    }
-
-    const uint16_t *arow = token_row(cur);
-    load_a(av[0], arow, cur, 0);
-    load_a(av[1], arow, cur, 1);
-    __syncthreads();
-    while (true) {
+    // ---------------- one step; true when it was the block's last ----------------
+    auto step = [&](const h8_t (&a_use)[TL_GPW][4], h8_t (&a_load)[TL_GPW][4]) -> bool {
         const bool item_ends = !nxt.valid || nxt.it != cur.it;
-        const TileStep &after = nxt.valid ? nxt : cur;               // past the last step: re-read, never used
-        const uint16_t *arow_next = token_row(after);
-        int sg = seg_groups(cur);
-        if (wv < sg) unit_load(buf, wv, 0, q_next, m_next);
-        if (A.debug & 2) sg = 0;
-        if (!(A.debug & 4)) {
-        load_a(av[2], arow, cur, 2);
-        if (wv < sg) group_multiply(av[0], buf, wv, sg);
-        load_a(av[3], arow, cur, 3);
+        load_a(a_load, nxt.valid ? nxt : cur);                       // past the last step: re-read, never used
+        if (nxt.valid) fetch(nxt);
+        const int sg = seg_groups(cur);
+        if (wv < sg) {
+            unit_load(buf, wv, 0, q_next, m_next);
+            group_multiply(a_use[0], buf, wv, sg);
         }
-        if (wv + TL_CONSUMERS < sg) group_multiply(av[1], buf, wv + TL_CONSUMERS, sg);
-        if (!(A.debug & 4)) load_a(av[0], arow_next, after, 0);
-        if (wv + 2 * TL_CONSUMERS < sg) group_multiply(av[2], buf, wv + 2 * TL_CONSUMERS, sg);
-        if (!(A.debug & 4)) load_a(av[1], arow_next, after, 1);
-        if (wv + 3 * TL_CONSUMERS < sg) group_multiply(av[3], buf, wv + 3 * TL_CONSUMERS, sg);
-        arow = arow_next;
-        if (item_ends) {
-            __syncthreads();                                         // every consumer is done reading buffer `buf`
-            float *red = reinterpret_cast<float *>(lds + buf * TL_BUF_BYTES);
-#pragma unroll
-            for (int rt = 0; rt < TL_RT; ++rt)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    red[((wv * TL_RT + rt) * 16 + i) * 64 + lane] = acc[rt][i];
-                    acc[rt][i] = 0.f;
-                }
-            __syncthreads();
-            if (!(A.debug & 8)) finish_item(cur, buf);
-        }
-        __syncthreads();
-        if (!nxt.valid) break;
+        if (wv + TL_WAVES < sg) group_multiply(a_use[1], buf, wv + TL_WAVES, sg);
+        if (item_ends) finish_item(cur, buf);
+        if (nxt.valid) commit(buf ^ 1);
+        __syncthreads();                                             // next buffer filled, this one free again
+        if (!nxt.valid) return true;
         cur = nxt;
         nxt = next(cur);
         buf ^= 1;
+        return false;
+    };
+
+    h8_t a0[TL_GPW][4], a1[TL_GPW][4];
+    load_a(a0, cur);
+    fetch(cur);
+    commit(0);
+    __syncthreads();
+    while (true) {
+        if (step(a0, a1)) break;
+        if (step(a1, a0)) break;
     }
 }
 

@@ -100,7 +100,6 @@ struct moe_ctx {
     int32_t n_layers = 0;
     int32_t w13_blocks = 256, w2_rows = 32;
     float *gs_h = nullptr, *gs_a = nullptr;   // group sums of h and of a for the matrix-core path
-    int32_t mfma_debug = 0;
     int32_t mfma_form = 2;              // matrix-core kernels: 0 direct-to-lane, 1 row-streaming with fp32 group scaling, 2 persistent streaming form with fp16 weights
     int32_t mfma_min_batch = 16;        // batches at least this large use the matrix-core kernels (4-bit g64)
     uint64_t spec_head_bytes = 0;       // 0: a speculative load moves the whole expert at once (as the paper describes);
@@ -857,7 +856,7 @@ static int32_t launch_token(moe_layer *l, const FusedArgs &A, bool one_launch, b
 // plus the group-sum tables of their activation operands.
 struct PassExpert { const uint8_t *blob; std::vector<int> pairs; };
 
-// Streaming matrix-core form: persistent producer/consumer blocks over (entry, 128-row block, K part) items.
+// Streaming matrix-core form: persistent blocks over (entry, 128-row block, K part) items.
 // An expert with more than 32 tokens becomes two entries (token tiles) that read the same weights.
 static int32_t launch_mfma_stream(moe_layer *l, const std::vector<PassExpert> &experts, const float *w)
 {
@@ -865,7 +864,6 @@ static int32_t launch_mfma_stream(moe_layer *l, const std::vector<PassExpert> &e
     const BlobLayout &b = l->lay;
     const int K = l->cfg.top_k;
     TileArgs A{};
-    A.debug = c->mfma_debug;
     int n = 0, first = 0;
     for (const PassExpert &pe : experts)
         for (size_t t0 = 0; t0 < pe.pairs.size(); t0 += 32) {
@@ -1253,7 +1251,6 @@ extern "C" int32_t moe_ctx_set_option(moe_ctx_t *c, const char *name, int32_t va
     else if (n == "token_path") c->token_path = value != 0;
     else if (n == "spec_head_mb" && value >= 0) c->spec_head_bytes = (uint64_t)value << 20;
     else if (n == "mfma_min_batch" && value >= 1) c->mfma_min_batch = value;
-    else if (n == "mfma_debug") c->mfma_debug = value;
     else if (n == "mfma_form" && value >= 0 && value <= 2) c->mfma_form = value;
     else return fail(MOE_EINVAL, "moe_ctx_set_option: unknown option or bad value: %s = %d", name, value);
     return MOE_OK;
