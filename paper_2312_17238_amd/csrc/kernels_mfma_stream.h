@@ -5,18 +5,19 @@
 // Work item  = 128 consecutive MEMORY rows of one matrix of one (expert, token tile) entry, over one part of K
 //              (w1/w3, whose rows are interleaved in the blob, always take all of K: their epilogue needs the
 //              complete sums; w2 may split K, its result is accumulated with atomics anyway).
-// Step       = one segment of 16 groups (1024 codes) of a work item: 128 rows x (512 B codes + 64 B pairs) = 72 KB.
-// Block      = 8 waves, one per compute unit, walking its items (blockIdx.x, +gridDim.x, ...) as one sequence of
+// Step       = one segment of 8 groups (512 codes) of a work item: 128 rows x (256 B codes + 32 B pairs) = 36 KB.
+// Block      = 4 waves, two blocks per compute unit (their phases drift apart, so one block's loads overlap the
+//              other's arithmetic), each walking its items (blockIdx.x, +gridDim.x, ...) as one sequence of
 //              steps.  During step s every wave first requests what step s+1 needs -- its own A operands
-//              (activations of up to 32 tokens, from L2) and its share of the 72 KB of weights (from HBM, into
+//              (activations of up to 32 tokens, from L2) and its share of the 36 KB of weights (from HBM, into
 //              registers) -- then multiplies step s out of one of two LDS buffers, then stores the arrived weights
 //              to the other buffer; one barrier per step.  Memory loads return in order per wave, so nothing
 //              inside the multiply may wait for a load: that is why the A operands travel a full step ahead.
-// Wave w     = groups w and w+8 of the step for all four 32-row tiles: A operand once per group, reused by the four
+// Wave w     = groups w and w+4 of the step for all four 32-row tiles: A operand once per group, reused by the four
 //              tiles; B operand from LDS as codes (read one tile ahead), dequantised to fp16 in registers,
 //              w = (q - z) s computed as (q - rint(z)) s + (rint(z) - z) s with one rounding, and the MFMA
 //              accumulates across all groups of the item (Sec. 4.2 runs the experts on dequantised fp16
-//              weights; the GEMV kernels keep more).  At the end of an item the eight waves add their partial
+//              weights; the GEMV kernels keep more).  At the end of an item the waves add their partial
 //              sums through the LDS buffer just consumed, two tiles at a time, in a fixed order.
 //
 // MFMA layouts (v_mfma_f32_32x32x16_f16): A lane l = row (token) l%32, k-slot l/32; B lane l = column (memory
@@ -26,21 +27,30 @@
 
 namespace moe {
 
-constexpr int TL_WAVES = 8;
+#ifndef MOE_TL_WAVES
+#define MOE_TL_WAVES 4
+#define MOE_TL_BLOCKS_PER_CU 2
+#define MOE_TL_SG 8
+#endif
+constexpr int TL_WAVES = MOE_TL_WAVES;
+constexpr int TL_BLOCKS_PER_CU = MOE_TL_BLOCKS_PER_CU;
 constexpr int TL_THREADS = TL_WAVES * WAVE;
 constexpr int TL_RT = 4;                                 // 32-row tiles per item
 constexpr int TL_ROWS = TL_RT * 32;
-constexpr int TL_SG = 16;                                // groups per step
+constexpr int TL_SG = MOE_TL_SG;                         // groups per step
 constexpr int TL_GPW = TL_SG / TL_WAVES;                 // groups per wave and step (2)
 constexpr int TL_CODE_PITCH = TL_SG * 32 + 16;           // bytes per staged row of codes (+16: bank spread)
 constexpr int TL_META_PITCH = TL_SG + 1;                 // words per staged row of pairs (odd: bank spread)
 constexpr int TL_BUF_BYTES = TL_ROWS * TL_CODE_PITCH + TL_ROWS * TL_META_PITCH * 4;
 constexpr int TL_TABLE_BYTES = MF_MAX_PAIRS * 6;         // token, pair (bytes) and combine weight (float) of every pair
 constexpr int TL_LDS_BYTES = 2 * TL_BUF_BYTES + TL_TABLE_BYTES;
-constexpr int TL_CP = TL_ROWS * TL_SG * 2 / TL_THREADS;  // 16-byte code pieces per thread and step (8)
-constexpr int TL_MP = TL_ROWS * (TL_SG / 4) / TL_THREADS;   // 16-byte pair pieces per thread and step (1)
+constexpr int TL_CPR = TL_SG * 2, TL_MPR = TL_SG / 4;    // 16-byte code / pair pieces per staged row
+constexpr int TL_CP = TL_ROWS * TL_CPR / TL_THREADS;     // code pieces per thread and step (8)
+constexpr int TL_MP = TL_ROWS * TL_MPR / TL_THREADS;     // pair pieces per thread and step (1)
+constexpr int TL_NI = 2 * 16 / TL_WAVES;                 // accumulator registers a wave finishes per reduction round
 static_assert(TL_WAVES * 2 * 16 * 64 * 4 <= TL_BUF_BYTES, "one reduction round (two tiles of every wave) must fit a staging buffer");
-static_assert(TL_CP * TL_THREADS == TL_ROWS * TL_SG * 2 && TL_MP * TL_THREADS == TL_ROWS * (TL_SG / 4), "pieces must divide evenly");
+static_assert(TL_CP * TL_THREADS == TL_ROWS * TL_CPR && TL_MP * TL_THREADS == TL_ROWS * TL_MPR, "pieces must divide evenly");
+static_assert(TL_SG % 4 == 0 && (TL_CPR & (TL_CPR - 1)) == 0 && (TL_MPR & (TL_MPR - 1)) == 0, "pieces per row must be powers of two");
 
 struct TileArgs {
     MfmaEntry e[32];                         // (expert, token tile) entries
@@ -72,7 +82,7 @@ __device__ __forceinline__ h8_t codes_to_w8(uint32_t w, h2_t b1024, h2_t b64, h2
 }
 
 template <bool W13>
-__global__ __launch_bounds__(TL_THREADS) void k_mfma_stream_q4(TileArgs A)
+__global__ __launch_bounds__(TL_THREADS, TL_BLOCKS_PER_CU) void k_mfma_stream_q4(TileArgs A)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const int tid = threadIdx.x, lane = tid & 63, wv = uniform(tid >> 6);
@@ -118,12 +128,12 @@ __global__ __launch_bounds__(TL_THREADS) void k_mfma_stream_q4(TileArgs A)
         const int g0 = s.seg * TL_SG, sg = seg_groups(s), row0 = s.rb * TL_ROWS;
 #pragma unroll
         for (int i = 0; i < TL_CP; ++i) {
-            const int p = tid + i * TL_THREADS, r = p >> 5, c = p & 31;
+            const int p = tid + i * TL_THREADS, r = p / TL_CPR, c = p % TL_CPR;
             st_c[i] = ldw4(mat + (size_t)min(row0 + r, n_rows - 1) * A.stride, g0 * 2 + (c < 2 * sg ? c : 0));
         }
 #pragma unroll
         for (int i = 0; i < TL_MP; ++i) {
-            const int p = tid + i * TL_THREADS, r = p >> 2, c = p & 3;
+            const int p = tid + i * TL_THREADS, r = p / TL_MPR, c = p % TL_MPR;
             st_m[i] = ldw4(mat + (size_t)min(row0 + r, n_rows - 1) * A.stride + A.meta_off, g0 / 4 + (c < (sg + 3) / 4 ? c : 0));
         }
     };
@@ -132,12 +142,12 @@ __global__ __launch_bounds__(TL_THREADS) void k_mfma_stream_q4(TileArgs A)
         uint32_t *meta = reinterpret_cast<uint32_t *>(codes + TL_ROWS * TL_CODE_PITCH);
 #pragma unroll
         for (int i = 0; i < TL_CP; ++i) {
-            const int p = tid + i * TL_THREADS, r = p >> 5, c = p & 31;
+            const int p = tid + i * TL_THREADS, r = p / TL_CPR, c = p % TL_CPR;
             *reinterpret_cast<uint4 *>(codes + r * TL_CODE_PITCH + c * 16) = st_c[i];
         }
 #pragma unroll
         for (int i = 0; i < TL_MP; ++i) {
-            const int p = tid + i * TL_THREADS, r = p >> 2, c = p & 3;
+            const int p = tid + i * TL_THREADS, r = p / TL_MPR, c = p % TL_MPR;
             uint32_t *d = meta + r * TL_META_PITCH + c * 4;
             d[0] = st_m[i].x; d[1] = st_m[i].y; d[2] = st_m[i].z; d[3] = st_m[i].w;
         }
@@ -198,16 +208,18 @@ __global__ __launch_bounds__(TL_THREADS) void k_mfma_stream_q4(TileArgs A)
     };
 
     // ---------------- end of an item: add the eight waves' partial sums, finish, store ----------------
-    // Two rounds of two tiles each through LDS buffer b (free: every wave is past its last read of it).  In a
-    // round wave v owns tile v/4 of the pair and registers 4 (v%4) .. +3, i.e. tokens 8 (v%4) + 4 (l/32) + 0..3.
+    // Rounds of two tiles each through LDS buffer b (free: every wave is past its last read of it).  In a round
+    // the waves share the 2 x 16 accumulator registers evenly: wave v owns TL_NI consecutive ones of one tile.
     auto finish_item = [&](const TileStep &s, int b) {
         float *red = reinterpret_cast<float *>(lds + b * TL_BUF_BYTES);   // [wave][tile of the round][16][64]
         const MfmaEntry &en = A.e[s.e];
-        int dst[4];
-        float wgt[4];
+        const int t = wv / (TL_WAVES / 2), i0 = (wv % (TL_WAVES / 2)) * TL_NI;   // tile of the round, first register
+        int dst[TL_NI];
+        float wgt[TL_NI];
 #pragma unroll
-        for (int ii = 0; ii < 4; ++ii) {
-            const int tk = en.first + min(8 * (wv & 3) + 4 * kh + ii, en.n_tok - 1);
+        for (int ii = 0; ii < TL_NI; ++ii) {
+            const int i = i0 + ii;
+            const int tk = en.first + min(8 * (i / 4) + 4 * kh + (i % 4), en.n_tok - 1);
             dst[ii] = W13 ? l_pair[tk] : l_tok[tk];
             wgt[ii] = W13 ? 0.f : l_w[tk];
         }
@@ -222,15 +234,14 @@ __global__ __launch_bounds__(TL_THREADS) void k_mfma_stream_q4(TileArgs A)
                     acc[round * 2 + t][i] = 0.f;
                 }
             __syncthreads();
-            const int t = wv >> 2;
             const int mrow = s.rb * TL_ROWS + (round * 2 + t) * 32 + col;
 #pragma unroll
-            for (int ii = 0; ii < 4; ++ii) {
-                const int i = (wv & 3) * 4 + ii;
+            for (int ii = 0; ii < TL_NI; ++ii) {
+                const int i = i0 + ii;
                 float v = 0.f;
 #pragma unroll
                 for (int w = 0; w < TL_WAVES; ++w) v += red[((w * 2 + t) * 16 + i) * 64 + lane];
-                const int tok = 8 * (wv & 3) + 4 * kh + ii;
+                const int tok = 8 * (i / 4) + 4 * kh + (i % 4);
                 if (W13) {
                     const float other = dpp_f<0xB1>(v);              // neighbouring column: v of the pair for even lanes
                     if ((lane & 1) == 0 && tok < en.n_tok && mrow < n_rows)
@@ -254,7 +265,9 @@ __global__ __launch_bounds__(TL_THREADS) void k_mfma_stream_q4(TileArgs A)
         }
         if (wv + TL_WAVES < sg) group_multiply(a_use[1], buf, wv + TL_WAVES, sg);
         if (item_ends) finish_item(cur, buf);
-        if (nxt.valid) commit(buf ^ 1);
+        // unconditional (after the last step it stores stale registers nobody reads): the wait for the loads above
+        // then sits on every path, and the next step starts with nothing in flight as far as the compiler can tell
+        commit(buf ^ 1);
         __syncthreads();                                             // next buffer filled, this one free again
         if (!nxt.valid) return true;
         cur = nxt;
@@ -267,6 +280,7 @@ __global__ __launch_bounds__(TL_THREADS) void k_mfma_stream_q4(TileArgs A)
     load_a(a0, cur);
     fetch(cur);
     commit(0);
+    __builtin_amdgcn_s_waitcnt(0x0F70);                              // vmcnt(0): the loop starts with nothing in flight
     __syncthreads();
     while (true) {
         if (step(a0, a1)) break;

@@ -881,7 +881,7 @@ static int32_t launch_mfma_stream(moe_layer *l, const std::vector<PassExpert> &e
             }
             ++n;
         }
-    static bool lds_attr_set = false;      // two 74.5 KB staging buffers: above the default dynamic LDS limit
+    static bool lds_attr_set = false;      // staging buffers above the default dynamic LDS limit
     if (!lds_attr_set) {
         HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_stream_q4<true>), hipFuncAttributeMaxDynamicSharedMemorySize, TL_LDS_BYTES));
         HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_stream_q4<false>), hipFuncAttributeMaxDynamicSharedMemorySize, TL_LDS_BYTES));
@@ -896,7 +896,7 @@ static int32_t launch_mfma_stream(moe_layer *l, const std::vector<PassExpert> &e
         A.seg_per_part = (n_seg + parts - 1) / parts;
         A.k_parts = (n_seg + A.seg_per_part - 1) / A.seg_per_part;       // no empty part
         A.n_items = n * A.row_blocks * A.k_parts;
-        return dim3(std::min(A.n_items, n_cu));
+        return dim3(std::min(A.n_items, TL_BLOCKS_PER_CU * n_cu));
     };
     const uint64_t bytes13 = (uint64_t)n * 2 * b.ffn * b.m13.row_stride, bytes2 = (uint64_t)n * b.hidden * b.m2.row_stride;
     A.a = c->a_buf; A.yacc = c->yacc;
