@@ -14,7 +14,8 @@ struct GateHostOut {                // lives in host-mapped pinned memory; writt
     float w[64 * 4];
     double logits[64 * 16];         // [b*E + e]
     double spec_p[64 * 16];         // [b*E2 + e] next-layer gate probabilities per token
-    uint32_t done;                  // incremented once per block, system scope, after its results
+    uint32_t done[64];              // [b] = sequence number of the launch, stored by block b after its results
+                                    // (system-scope release; one word per block: posted writes, no round trips)
     uint32_t ffn_error;             // set by the fused FFN kernel if its grid barrier gave up
 };
 
@@ -29,6 +30,7 @@ struct GateArgs {
     GateHostOut *out;
     double eps;                     // 0: no norm
     int32_t H, E, E2, K;
+    uint32_t seq;                   // value to publish in out->done[b]
 };
 
 constexpr int GATE_THREADS = 1024;
@@ -148,8 +150,7 @@ __global__ __launch_bounds__(GATE_THREADS) void k_gate(GateArgs a)
             for (int e = 0; e < n2; ++e) { pe[e] = exp(tot[16 + e] - zmax); ps += pe[e]; }
             for (int e = 0; e < n2; ++e) o->spec_p[b * n2 + e] = pe[e] / ps;
         }
-        __threadfence_system();
-        __hip_atomic_fetch_add(&o->done, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+        __hip_atomic_store(&o->done[b], a.seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
     }
 }
 

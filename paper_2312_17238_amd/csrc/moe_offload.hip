@@ -99,6 +99,7 @@ struct moe_ctx {
     hipEvent_t ev_gate = nullptr, ev_compute = nullptr;
     int32_t n_layers = 0;
     int32_t w13_blocks = 256, w2_rows = 32;
+    uint32_t gate_seq = 0;              // sequence number of the last gate launch
     float *gs_h = nullptr, *gs_a = nullptr;   // group sums of h and of a for the matrix-core path
     int32_t mfma_form = 2;              // matrix-core kernels: 0 direct-to-lane, 1 row-streaming with fp32 group scaling, 2 persistent streaming form with fp16 weights
     int32_t mfma_min_batch = 16;        // batches at least this large use the matrix-core kernels (4-bit g64)
@@ -651,24 +652,28 @@ extern "C" int32_t moe_layer_resolve(moe_layer_t *l, moe_layer_t *next, const in
 // the GPU step
 // ---------------------------------------------------------------------------------------------
 
-static int32_t wait_gate(moe_ctx *c, uint32_t expect)
+// Wait until every block of the gate kernel has published the launch's sequence number next to its results.
+static int32_t wait_gate(moe_ctx *c, int32_t batch, uint32_t seq)
 {
+    volatile uint32_t *flag = c->gate_out->done;
     if (c->sync_wait) {
         HIPCHK(hipStreamSynchronize(c->compute));
     } else {
-        volatile uint32_t *flag = &c->gate_out->done;
-        for (uint64_t spin = 0;; ++spin) {
-            if (*flag == expect) break;
+        int b = 0;
+        for (uint64_t spin = 0; b < batch; ++spin) {
+            while (b < batch && flag[b] == seq) ++b;
+            if (b == batch) break;
             if (spin > 4096 && (spin & 255) == 0) {
                 hipError_t q = hipEventQuery(c->ev_gate);
-                if (q == hipSuccess) break;            // kernel over: the flag is re-read below
+                if (q == hipSuccess) break;            // kernel over: the flags are re-read below
                 if (q != hipErrorNotReady) { g_hip_err = (int32_t)q; return fail(MOE_EHIP, "gate kernel failed: %s", hipGetErrorString(q)); }
             }
             __builtin_ia32_pause();
         }
     }
     std::atomic_thread_fence(std::memory_order_acquire);
-    if (c->gate_out->done != expect) return fail(MOE_ESTATE, "gate kernel finished but published %u of %u results", c->gate_out->done, expect);
+    for (int b = 0; b < batch; ++b)
+        if (flag[b] != seq) return fail(MOE_ESTATE, "gate kernel finished but token %d published no result", b);
     return MOE_OK;
 }
 
@@ -700,14 +705,14 @@ static int32_t launch_timed(moe_ctx *c, int kind, uint64_t bytes, K kernel, dim3
     return MOE_OK;
 }
 
-static int32_t launch_gate(moe_ctx *c, const GateArgs &ga, int32_t batch)
+static int32_t launch_gate(moe_ctx *c, GateArgs ga, int32_t batch)
 {
-    c->gate_out->done = 0;
-    std::atomic_thread_fence(std::memory_order_release);
+    if (++c->gate_seq == 0) ++c->gate_seq;             // 0 is what a fresh context holds
+    ga.seq = c->gate_seq;
     int32_t rc = launch_timed(c, PROF_GATE, 0, k_gate, dim3(batch), dim3(GATE_THREADS), 0, ga);
     if (rc) return rc;
     if (!c->sync_wait) HIPCHK(hipEventRecord(c->ev_gate, c->compute));
-    return wait_gate(c, (uint32_t)batch);
+    return wait_gate(c, batch, ga.seq);
 }
 
 // Rows each wave keeps in flight (ring depth) in the w1/w3 and the w2 kernel.
