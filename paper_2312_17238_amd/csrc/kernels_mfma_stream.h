@@ -134,7 +134,9 @@ __global__ __launch_bounds__(TL_THREADS, TL_BLOCKS_PER_CU) void k_mfma_stream_q4
 #pragma unroll
         for (int i = 0; i < TL_MP; ++i) {
             const int p = tid + i * TL_THREADS, r = p / TL_MPR, c = p % TL_MPR;
-            st_m[i] = ldw4(mat + (size_t)min(row0 + r, n_rows - 1) * A.stride + A.meta_off, g0 / 4 + (c < (sg + 3) / 4 ? c : 0));
+            // a step takes 32 B of a row's pairs, its neighbours in the cache line belong to the next steps: a
+            // plain load, so that L2 keeps the line (the streaming hint would fetch it from HBM once per step)
+            st_m[i] = reinterpret_cast<const uint4 *>(mat + (size_t)min(row0 + r, n_rows - 1) * A.stride + A.meta_off)[g0 / 4 + (c < (sg + 3) / 4 ? c : 0)];
         }
     };
     auto commit = [&](int b) {                                       // pieces past a short segment hold copies nobody reads
