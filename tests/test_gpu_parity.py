@@ -403,3 +403,43 @@ def test_speculative_head_then_tail_is_invisible_in_results():
     assert s0["bytes_h2d_spec"] == s0["spec_issued"] * blob
     assert s8["bytes_h2d_spec"] == s8["spec_issued"] * (8 << 20) + s8["prefetch_hits"] * (blob - (8 << 20))
     assert s8["prefetch_hits"] > 0 and s8["spec_wasted"] > 0
+
+
+@pytest.mark.parametrize("E,K,k,m,Bn,T,path", [
+    (16, 4, 4, 4, 64, 3, "gemv"),      # every limit of the ABI at once: 16 experts, top-4, 4 guesses, batch 64 (256 pairs)
+    (16, 4, 4, 4, 64, 3, "matrix"),    # the same through the matrix cores (up to 16 needed experts over 4 slots: 4 passes)
+    (16, 4, 16, 2, 17, 3, "matrix"),   # all 16 resident, ragged batch
+    (2, 2, 2, 2, 1, 8, "gemv"),        # top_k = E: both experts always selected, the gate only sets the weights
+    (4, 1, 1, 1, 2, 8, "gemv"),        # top-1 with a single slot: every change of expert is a miss
+    (3, 2, 3, 0, 5, 4, "gemv"),        # odd expert count, no speculation, batch between the GEMV chunk sizes
+])
+def test_limits_and_degenerate_shapes(E, K, k, m, Bn, T, path):
+    """The extremes the interface allows (MOE_MAX_EXPERTS, MOE_MAX_TOPK, MOE_MAX_GUESS, MOE_MAX_BATCH) and the
+    degenerate shapes of the method, every decision and every output row checked against the oracle."""
+    L, H, F = 3, 256, 512
+    say(f"limits E={E} K={K} k={k} m={m} B={Bn} {path}")
+    model = Model(L, H, F, E, K, None, k, m, 1e-5, max_batch=Bn, seed=51)
+    B.moe_ctx_set_option(model.stack.ctx, "mfma_min_batch", 16 if path == "matrix" else 1000)
+    B.moe_ctx_profile_enable(model.stack.ctx, True)
+    xs = W.hidden_ar1(51, T, Bn, H)
+    _, sim, errs = run_teacher_forced(model, xs, O.expert_ffn)
+    prof = B.moe_ctx_profile_read(model.stack.ctx).as_dict()
+    assert prof["w13"]["launches"] > 0
+    tot = model.stack.total_stats()
+    assert tot["needed"] == sum(s.needed for s in sim.stats)
+    assert tot["misses"] == sum(s.misses for s in sim.stats)
+    say(f"  max abs {max(e[0] for e in errs):.2e} max rel-rms {max(e[1] for e in errs):.2e} misses {tot['misses']}")
+    model.close()
+
+
+def test_largest_supported_matrices():
+    """H = 8192, F = 16384 (the largest shapes the kernels accept: four 2048-code chunks per w1/w3 row, eight per w2
+    row), two experts, one token at a time, C oracle on every row."""
+    H, F = 8192, 16384
+    say("largest matrices: build")
+    model = Model(1, H, F, 2, 2, None, 2, 0, 1e-5, seed=53)
+    xs = W.hidden_ar1(53, 2, 1, H)
+    say("largest matrices: run")
+    _, sim, errs = run_teacher_forced(model, xs, c_ffn.expert_ffn)
+    say(f"  max abs {max(e[0] for e in errs):.2e} max rel-rms {max(e[1] for e in errs):.2e}")
+    model.close()
