@@ -342,12 +342,14 @@ def test_matrix_core_path_agrees_with_gemv_path(form, rel):
     assert d < rel * max(1.0, np.abs(res["gemv"][0]).max()), d
 
 
-def test_mixtral_layer_batch16_matrix_cores():
-    """Mixtral-shaped layer, batch 16, k=4 (8 needed experts over 4 slots: several passes), C oracle on every row."""
+@pytest.mark.parametrize("Bn,T,k", [(16, 2, 4), (64, 1, 8)])
+def test_mixtral_layer_batch16_matrix_cores(Bn, T, k):
+    """Mixtral-shaped layer on the matrix cores, C oracle on every row: batch 16 with k=4 (8 needed experts over 4
+    slots: several passes) and batch 64 with every expert resident (the launch shape bench.py times for the kernels)."""
     c = W.CONFIGS["mixtral_layer"]
-    say("mixtral layer B=16 matrix cores: build")
-    model = Model(1, c.hidden, c.ffn, c.n_experts, c.top_k, None, 4, 0, 0.0, max_batch=16, seed=c.seed)
-    xs = W.hidden_ar1(c.seed, 2, 16, c.hidden)
+    say(f"mixtral layer B={Bn} k={k} matrix cores: build")
+    model = Model(1, c.hidden, c.ffn, c.n_experts, c.top_k, None, k, 0, 0.0, max_batch=Bn, seed=c.seed)
+    xs = W.hidden_ar1(c.seed, T, Bn, c.hidden)
     _, sim, errs = run_teacher_forced(model, xs, c_ffn.expert_ffn)
     say(f"  max abs {max(e[0] for e in errs):.2e} max rel-rms {max(e[1] for e in errs):.2e}")
     model.close()
