@@ -168,13 +168,31 @@ def main() -> int:
                  "copy_gbs_each_way": (1 << 30) / ms_c / 1e6, "copy_bytes": 1 << 30}
         del src, dst
         torch.cuda.empty_cache()
-        log(f"probe: streaming read {probe['read_gbs']:.0f} GB/s, copy {probe['copy_gbs_each_way']:.0f} GB/s each way")
+        # the host link alone: pinned -> device copies of one expert blob, back to back on one stream
+        blob = max(stack.blob_bytes)
+        hsrc = torch.empty(blob, dtype=torch.uint8, pin_memory=True).zero_()
+        ddst = torch.empty(blob, dtype=torch.uint8, device=device)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ddst.copy_(hsrc, non_blocking=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(8):
+            ddst.copy_(hsrc, non_blocking=True)
+        e1.record()
+        torch.cuda.synchronize()
+        probe["h2d_gbs"] = 8 * blob / e0.elapsed_time(e1) / 1e6
+        probe["h2d_bytes_per_copy"] = blob
+        del hsrc, ddst
+        torch.cuda.empty_cache()
+        log(f"probe: streaming read {probe['read_gbs']:.0f} GB/s, copy {probe['copy_gbs_each_way']:.0f} GB/s each way, "
+            f"pinned host->device {probe['h2d_gbs']:.1f} GB/s")
 
     for t in range(args.warmup):
         stack.step(x_dev[t], x_out)
     stack.synchronize()
     torch.cuda.synchronize()
     before = stack.total_stats()
+    layers_before = stack.stats()
     if not args.no_profile:
         B.moe_ctx_profile_enable(stack.ctx, True)
     t0 = time.perf_counter()
@@ -184,6 +202,7 @@ def main() -> int:
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     after = stack.total_stats()
+    layers_after = stack.stats()
     prof = None if args.no_profile else B.moe_ctx_profile_read(stack.ctx).as_dict()
     if not args.no_profile:
         B.moe_ctx_profile_enable(stack.ctx, False)
@@ -207,6 +226,10 @@ def main() -> int:
                        "spec_issued": d["spec_issued"], "spec_wasted": d["spec_wasted"],
                        "recall": (d["hits"] + d["prefetch_hits"]) / max(1, d["needed"]),
                        "link_bytes_per_token": link_bytes / tokens}
+    # per layer: LRU hit ratio and recall (hits + prefetch hits) over the timed steps
+    per_layer = [{k: a[k] - b[k] for k in ("needed", "hits", "prefetch_hits")} for a, b in zip(layers_after, layers_before)]
+    result["cache"]["per_layer_hit_ratio"] = [round(x["hits"] / max(1, x["needed"]), 3) for x in per_layer]
+    result["cache"]["per_layer_recall"] = [round((x["hits"] + x["prefetch_hits"]) / max(1, x["needed"]), 3) for x in per_layer]
     # the step can be no faster than its bytes over the slower of the two pipes (nominal peaks)
     hbm_bytes_per_token = 2.0 * sum(stack.blob_bytes) * batch / max(1, batch) if batch == 1 else None
     t_link = (link_bytes / tokens) / (LINK_PEAK_GBS * 1e9)
@@ -229,7 +252,9 @@ def main() -> int:
     elif prof:
         w13, w2, cp, gt = prof["w13"], prof["w2"], prof["copy"], prof["gate"]
         ach = w13["bytes"] / max(w13["total_ms"], 1e-9) / 1e6      # GB/s
-        result["roofline"] = {"bound": "hbm", "kernel": "k_w13 (fused dequant-GEMV w1,w3 -> SiLU*mul)",
+        matrix_cores = batch >= 16 and set(formats) == {(4, 64)}
+        result["roofline"] = {"bound": "hbm", "kernel": "k_mfma_stream_q4<true> (grouped dequant-GEMM w1,w3 -> SiLU*mul)" if matrix_cores
+                              else "k_w13 (fused dequant-GEMV w1,w3 -> SiLU*mul)",
                               "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
                               "traffic": PMC_TRAFFIC_W13_4BIT_B1 if (batch == 1 and set(formats) == {(4, 64)}
                                                                      and shape.hidden == 4096 and shape.ffn == 14336) else None,
@@ -238,7 +263,8 @@ def main() -> int:
                               "avg_us": 1e3 * w13["total_ms"] / max(1, w13["launches"]),
                               "measured_read_probe_gbs": probe["read_gbs"] if probe else None}
         a2 = w2["bytes"] / max(w2["total_ms"], 1e-9) / 1e6
-        result["roofline_w2"] = {"bound": "hbm", "kernel": "k_w2 / k_w2_token (fused dequant-GEMV w2 -> combine -> residual)",
+        result["roofline_w2"] = {"bound": "hbm", "kernel": "k_mfma_stream_q4<false> (grouped dequant-GEMM w2 -> combine)" if matrix_cores
+                                 else "k_w2 / k_w2_token (fused dequant-GEMV w2 -> combine -> residual)",
                                  "achieved": a2, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": a2 / HBM_PEAK_GBS,
                                  "launches": w2["launches"], "avg_us": 1e3 * w2["total_ms"] / max(1, w2["launches"])}
         both = (w13["bytes"] + w2["bytes"]) / max(w13["total_ms"] + w2["total_ms"], 1e-9) / 1e6
@@ -249,6 +275,7 @@ def main() -> int:
             ac = cp["bytes"] / max(cp["total_ms"], 1e-9) / 1e6
             result["link"] = {"bound": "host-link", "achieved": ac, "peak": LINK_PEAK_GBS, "unit": "GB/s",
                               "frac": ac / LINK_PEAK_GBS, "copies": cp["launches"],
+                              "measured_h2d_probe_gbs": probe.get("h2d_gbs") if probe else None,
                               "busy_frac_of_wall": cp["total_ms"] / (1e3 * dt),
                               "wall_gbs": link_bytes / dt / 1e9}
         result["gate_avg_us"] = 1e3 * gt["total_ms"] / max(1, gt["launches"])
