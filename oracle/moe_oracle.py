@@ -287,3 +287,40 @@ class ExpertCacheSim:
                     self.stats[l + 1].spec_issued += 1
                 decisions.append((e, issue))
         return trace, decisions
+
+
+class SwapPlacement:
+    """Where every expert of one layer lives when host memory cannot hold them all (Sec. 3.3).
+
+    An expert is in exactly one buffer: on the device (one of the k cache slots) or in one of the
+    host buffers.  Loading an expert onto the device sends the evicted one back to the host, so the
+    counts on both sides never change.  Reading of what the paper leaves open: there are
+    E - k + 1 host buffers, one of them empty ("spare"); the evicted expert is written into the
+    spare, and the buffer the loaded expert came from becomes the spare -- so the write never has to
+    wait for the load to finish reading.  Experts 0..k-1 start on the device, expert e >= k starts in
+    host buffer e - k, the spare is buffer E - k.
+    """
+
+    def __init__(self, n_experts: int, k: int):
+        self.E, self.k = n_experts, k
+        self.host_buf_of = [-1 if e < k else e - k for e in range(n_experts)]
+        self.spare = n_experts - k
+        self.writebacks = 0
+
+    def apply(self, accesses: Sequence[Access]) -> None:
+        """Follow the accesses of one step (as ExpertCacheSim.step returns them, warm-started)."""
+        for a in accesses:
+            if a.status == HIT:
+                continue
+            if a.victim < 0:
+                raise ValueError("swap placement needs a full cache: every load evicts")
+            came_from = self.host_buf_of[a.expert]
+            if came_from < 0 or self.host_buf_of[a.victim] >= 0:
+                raise ValueError("placement and cache trace disagree")
+            self.host_buf_of[a.victim] = self.spare
+            self.spare = came_from
+            self.host_buf_of[a.expert] = -1
+            self.writebacks += 1
+
+    def on_device(self) -> List[int]:
+        return sorted(e for e in range(self.E) if self.host_buf_of[e] < 0)

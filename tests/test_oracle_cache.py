@@ -227,3 +227,44 @@ def test_zero_experts_make_the_speculative_guess_exact():
         guess = O.prefetch_guess(O.prefetch_scores(wg1, r0.h), 2)
         r1 = O.moe_block(r0.x_out, wg1, [zero_expert] * E, g, 2, gam, 1e-5)
         assert guess == r1.idx
+
+
+def test_swap_placement_keeps_every_expert_in_exactly_one_buffer():
+    """Sec. 3.3, hosts that cannot hold all experts: after any sequence of steps the experts on the device are
+    exactly the cache contents, the E-k others occupy E-k distinct host buffers, the spare is the one remaining
+    buffer, and there was one write-back per eviction (= per miss or used guess, the cache being full from the start).
+    Brute force over random top-2 traces for several (E, k)."""
+    rng = np.random.default_rng(11)
+    for E, k, m in ((8, 2, 2), (8, 4, 1), (5, 3, 2), (3, 2, 0), (16, 4, 4)):
+        sim = O.ExpertCacheSim(2, E, k, 4, warm=True)
+        place = [O.SwapPlacement(E, k) for _ in range(2)]
+        history = [[list(range(k))], [list(range(k))]]
+        for t in range(200):
+            for l in range(2):
+                sel = [sorted(rng.choice(E, size=min(2, E), replace=False).tolist()) for _ in range(int(rng.integers(1, 3)))]
+                guess = rng.permutation(E)[:m].tolist() if (l == 0 and m) else None
+                acc, _ = sim.step(l, sel, guess)
+                place[l].apply(acc)
+                assert place[l].on_device() == sim.contents(l)
+                host = [place[l].host_buf_of[e] for e in range(E) if place[l].host_buf_of[e] >= 0]
+                assert len(host) == E - k and len(set(host)) == E - k
+                assert sorted(host + [place[l].spare]) == list(range(E - k + 1))
+        for l in range(2):
+            assert place[l].writebacks == sim.stats[l].evictions == sim.stats[l].misses + sim.stats[l].prefetch_hits
+
+
+def test_swap_placement_hand_worked_trace():
+    """E=4, k=2: experts 0,1 on the device, 2 -> host buffer 0, 3 -> host buffer 1, spare = buffer 2.
+    Need {2}: 0 (least recent) is evicted into the spare (2), buffer 0 becomes the spare.
+    Need {3}: 1 is evicted into buffer 0, buffer 1 becomes the spare.  Need {0}: 2 leaves into buffer 1, spare = 2."""
+    sim = O.ExpertCacheSim(1, 4, 2, 4, warm=True)
+    p = O.SwapPlacement(4, 2)
+    assert (p.host_buf_of, p.spare) == ([-1, -1, 0, 1], 2)
+    p.apply(sim.step(0, [[2]])[0])
+    assert (p.host_buf_of, p.spare) == ([2, -1, -1, 1], 0)
+    p.apply(sim.step(0, [[3]])[0])
+    assert (p.host_buf_of, p.spare) == ([2, 0, -1, -1], 1)
+    p.apply(sim.step(0, [[0]])[0])
+    assert (p.host_buf_of, p.spare) == ([-1, 0, 1, -1], 2)
+    p.apply(sim.step(0, [[0, 3]])[0])          # both resident: nothing moves
+    assert (p.host_buf_of, p.spare, p.writebacks) == ([-1, 0, 1, -1], 2, 3)
