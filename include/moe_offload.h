@@ -75,8 +75,16 @@ typedef struct {
 } moe_ctx_config_t;
 
 enum {
-    MOE_LAYER_NO_CACHE = 1    /* ablation "without LRU cache": residency is forgotten before every step,
+    MOE_LAYER_NO_CACHE = 1,   /* ablation "without LRU cache": residency is forgotten before every step,
                                  so every needed expert is a demand copy (or a prefetch hit)       */
+    MOE_LAYER_SWAP     = 2    /* hosts that cannot hold every expert (Sec. 3.3): an expert lives in exactly one
+                                 buffer, on the host or on the device.  Experts 0..k-1 start on the device
+                                 (init_policy must be 1), the other E-k in host buffers, and the pinned arena
+                                 has E-k+1 buffers (one spare).  Loading an expert also writes the evicted one
+                                 back to the host, into the spare buffer, on a stream of the library's own; the
+                                 buffer the loaded expert vacated is the next spare.  Decisions, traces and
+                                 results are those of the plain mode.  Set at creation only; excludes
+                                 MOE_LAYER_NO_CACHE and moe_layer_reset                                */
 };
 
 typedef struct {
@@ -124,6 +132,7 @@ typedef struct {
     uint64_t spec_wasted;     /* ... of which this layer did not use                             */
     uint64_t bytes_h2d_demand;
     uint64_t bytes_h2d_spec;
+    uint64_t bytes_d2h_writeback; /* MOE_LAYER_SWAP: evicted experts written back to host buffers    */
 } moe_stats_t;                /* "expert recall" (Sec. 4.1) = (hits + prefetch_hits) / needed    */
 
 /* ---- sizes ---------------------------------------------------------------------------------- */
@@ -162,7 +171,8 @@ int32_t moe_layer_destroy(moe_layer_t *layer);
  * row-major [out][in].  codes: one byte per weight, values < 2^bits.  scale/zero: fp16 bits,
  * [out][in/group], groups along `in`; the stored weight is (code - zero) * scale (Sec. 4.2).
  * All host memory, read during the call only.  The library repacks into the expert's blob in the
- * pinned arena; with init_policy 1, experts 0..k-1 are also copied to their slots once complete. */
+ * pinned arena; with init_policy 1, experts 0..k-1 are also copied to their slots once complete (with
+ * MOE_LAYER_SWAP they are packed in ordinary memory of the library's own and keep no host copy). */
 int32_t moe_layer_load_expert(moe_layer_t *layer, int32_t expert, int32_t matrix, const uint8_t *codes,
                               const uint16_t *scale_f16, const uint16_t *zero_f16);
 /* Read one weight back out of the packed host blob (checks the private layout without a GPU). */
@@ -209,6 +219,10 @@ int32_t moe_layer_stats(const moe_layer_t *layer, moe_stats_t *out);
  * staged[MOE_MAX_EXPERTS] (n_staged ids speculatively loaded for this layer).  Any pointer may be NULL. */
 int32_t moe_layer_cache_state(const moe_layer_t *layer, int32_t *slot_expert, uint64_t *slot_stamp,
                               int32_t *staged, int32_t *n_staged);
+/* MOE_LAYER_SWAP: where every expert's blob is.  host_buf_of[E]: index of the host buffer that holds expert e,
+ * or -1 while it is on the device; *spare_host: the host buffer holding nothing.  Without the flag expert e is in
+ * buffer e and *spare_host is -1.  Either pointer may be NULL. */
+int32_t moe_layer_placement(const moe_layer_t *layer, int32_t *host_buf_of, int32_t *spare_host);
 /* Forget residency, staged guesses and statistics (cold cache, or warm per init_policy). Waits for both streams. */
 int32_t moe_layer_reset(moe_layer_t *layer);
 /* Change m, the number of experts its predecessor guesses for this layer (ablation "without pre-loading"). */
@@ -222,11 +236,11 @@ int32_t moe_ctx_read_y(moe_ctx_t *ctx, int32_t batch, int32_t hidden, float *y_h
 
 /* Optional timing of the engine's own launches, with HIP events recorded on the stream each launch is
  * enqueued on (gate, w1/w3 kernel, w2 kernel, one-launch single-token FFN kernel `ffn`: compute stream;
- * expert copies: copy stream).
+ * expert copies: copy stream; write-backs of evicted experts in swap mode: the library's write-back stream).
  * `bytes` are algorithmic: each distinct expert a launch touches counts its packed w1+w3 (or w2) once;
  * a copy counts the blob.  enable(1) clears the accumulators; read waits for both streams. */
 typedef struct { uint64_t launches; uint64_t bytes; double total_ms; } moe_profile_entry_t;
-typedef struct { moe_profile_entry_t gate, w13, w2, copy, ffn; } moe_profile_t;
+typedef struct { moe_profile_entry_t gate, w13, w2, copy, ffn, writeback; } moe_profile_t;
 int32_t moe_ctx_profile_enable(moe_ctx_t *ctx, int32_t on);
 int32_t moe_ctx_profile_read(moe_ctx_t *ctx, moe_profile_t *out);
 

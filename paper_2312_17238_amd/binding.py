@@ -18,12 +18,13 @@ MOE_OK, MOE_EINVAL, MOE_ESTATE, MOE_ENOMEM, MOE_EHIP = 0, -1, -2, -3, -4
 MOE_HIT, MOE_PREFETCH_HIT, MOE_MISS = 0, 1, 2
 MOE_CTX_HOST_ONLY = 1
 MOE_LAYER_NO_CACHE = 1
+MOE_LAYER_SWAP = 2
 
 EXPORTS = [
     "moe_expert_blob_bytes", "moe_ctx_dev_bytes", "moe_layer_dev_bytes", "moe_layer_host_bytes",
     "moe_ctx_create", "moe_ctx_destroy", "moe_layer_create", "moe_layer_destroy",
     "moe_layer_load_expert", "moe_layer_peek_weight", "moe_layer_step", "moe_layer_prefetch",
-    "moe_stack_step", "moe_layer_resolve", "moe_layer_stats", "moe_layer_cache_state",
+    "moe_stack_step", "moe_layer_resolve", "moe_layer_stats", "moe_layer_cache_state", "moe_layer_placement",
     "moe_layer_reset", "moe_ctx_read_y", "moe_ctx_profile_enable", "moe_ctx_profile_read", "moe_ctx_set_option", "moe_probe_bandwidth", "moe_layer_set_prefetch", "moe_layer_set_flags", "moe_last_error", "moe_last_hip_error",
 ]
 
@@ -73,7 +74,8 @@ class StepTrace(C.Structure):
 
 class Stats(C.Structure):
     _fields_ = [(n, C.c_uint64) for n in ("steps", "needed", "hits", "prefetch_hits", "misses", "evictions",
-                                          "spec_issued", "spec_wasted", "bytes_h2d_demand", "bytes_h2d_spec")]
+                                          "spec_issued", "spec_wasted", "bytes_h2d_demand", "bytes_h2d_spec",
+                                          "bytes_d2h_writeback")]
 
     def as_dict(self):
         return {n: int(getattr(self, n)) for n, _ in self._fields_}
@@ -85,7 +87,7 @@ class ProfileEntry(C.Structure):
 
 class Profile(C.Structure):
     _fields_ = [("gate", ProfileEntry), ("w13", ProfileEntry), ("w2", ProfileEntry), ("copy", ProfileEntry),
-                ("ffn", ProfileEntry)]
+                ("ffn", ProfileEntry), ("writeback", ProfileEntry)]
 
     def as_dict(self):
         return {k: {"launches": int(getattr(self, k).launches), "bytes": int(getattr(self, k).bytes),
@@ -132,6 +134,7 @@ def lib() -> C.CDLL:
     L.moe_layer_resolve.argtypes = [vp, vp, C.POINTER(i32), i32, C.POINTER(C.c_double), C.POINTER(StepTrace)]
     L.moe_layer_stats.argtypes = [vp, C.POINTER(Stats)]
     L.moe_layer_cache_state.argtypes = [vp, C.POINTER(i32), C.POINTER(u64), C.POINTER(i32), C.POINTER(i32)]
+    L.moe_layer_placement.argtypes = [vp, C.POINTER(i32), C.POINTER(i32)]
     L.moe_layer_reset.argtypes = [vp]
     L.moe_ctx_read_y.argtypes = [vp, i32, i32, vp]
     L.moe_ctx_profile_enable.argtypes = [vp, i32]
@@ -239,6 +242,13 @@ def moe_layer_cache_state(layer, k: int):
     st, n = (C.c_int32 * MOE_MAX_EXPERTS)(), C.c_int32()
     check(lib().moe_layer_cache_state(layer, se, ss, st, C.byref(n)))
     return list(se), list(ss), list(st)[: n.value]
+
+
+def moe_layer_placement(layer, n_experts: int):
+    """(host buffer of each expert or -1 while it is on the device, spare host buffer)."""
+    hb, sp = (C.c_int32 * n_experts)(), C.c_int32()
+    check(lib().moe_layer_placement(layer, hb, C.byref(sp)))
+    return list(hb), sp.value
 
 
 def moe_layer_reset(layer) -> None:

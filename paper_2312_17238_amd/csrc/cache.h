@@ -5,6 +5,12 @@
 // layers, replace nothing when they arrive, and on use replace the next layer's least recently used
 // entry; the total number of equal-size buffers is fixed.  Buffers are identified by an index into
 // the context's pool, so "replace" is an exchange of indices, never a device copy.
+//
+// Sec. 3.3 also describes hosts that cannot hold every expert: experts are then split between host and
+// device buffers, and loading one writes the evicted one back ("swap").  The decisions are the same; what
+// changes is which buffer a miss is loaded into (a free staging buffer when there is one, so that the load
+// does not wait for the evicted expert to drain out of the slot's old buffer) and the record of the buffer
+// the victim has to be read from.
 #pragma once
 #include <algorithm>
 #include <cstdint>
@@ -14,9 +20,9 @@ namespace moe {
 
 struct StagedGuess { int32_t expert; int32_t buf; };
 
-struct CopyOp { int32_t expert; int32_t buf; uint64_t offset = 0, bytes = 0; };   // bytes [offset, offset+bytes) of the host blob of `expert` -> pool buffer `buf`
+struct CopyOp { int32_t expert; int32_t buf; uint64_t offset = 0, bytes = 0; int32_t host_buf = -1; };   // bytes [offset, offset+bytes) of the host blob of `expert` (in host buffer host_buf) -> pool buffer `buf`
 
-struct AccessRec { int32_t expert, status, slot, victim, buf; };
+struct AccessRec { int32_t expert, status, slot, victim, buf; int32_t victim_buf = -1; };   // victim_buf: pool buffer the victim occupied
 
 struct LayerCache {
     int32_t k = 0, n_experts = 0;
@@ -41,7 +47,7 @@ struct LayerCache {
 
 struct Counters {
     uint64_t steps = 0, needed = 0, hits = 0, prefetch_hits = 0, misses = 0, evictions = 0, spec_issued = 0,
-             spec_wasted = 0, bytes_demand = 0, bytes_spec = 0;
+             spec_wasted = 0, bytes_demand = 0, bytes_spec = 0, bytes_writeback = 0;
 };
 
 struct BufferPool {
@@ -51,8 +57,10 @@ struct BufferPool {
 
 // Resolve the accesses of one step: `needed` ascending and distinct.  Resident experts are touched
 // first, then absent ones, each in ascending id.  Appends demand copies to `copies`.
+// swap: a miss that evicts takes a free staging buffer for the slot, when there is one, and frees the victim's.
 inline void resolve_accesses(LayerCache &c, BufferPool &pool, Counters &st, const std::vector<int32_t> &needed,
-                             bool forget_first, std::vector<AccessRec> &out, std::vector<CopyOp> &copies)
+                             bool forget_first, std::vector<AccessRec> &out, std::vector<CopyOp> &copies,
+                             bool swap = false)
 {
     if (forget_first)
         for (int s = 0; s < c.k; ++s) c.slot_expert[s] = -1;
@@ -63,7 +71,7 @@ inline void resolve_accesses(LayerCache &c, BufferPool &pool, Counters &st, cons
         if (s < 0) continue;
         c.slot_stamp[s] = ++pool.clock;
         st.hits++;
-        out.push_back({e, 0 /*HIT*/, s, -1, c.slot_buf[s]});
+        out.push_back({e, 0 /*HIT*/, s, -1, c.slot_buf[s], -1});
     }
     const size_t n_res = out.size();
     for (int32_t e : needed) {
@@ -82,6 +90,7 @@ inline void resolve_accesses(LayerCache &c, BufferPool &pool, Counters &st, cons
         }
         int g = c.find_staged(e);
         int32_t status;
+        const int32_t old_buf = c.slot_buf[s];
         if (g >= 0) {                       // used guess: its buffer becomes the slot, the slot's old buffer is freed
             status = 1;                     // PREFETCH_HIT
             std::swap(c.slot_buf[s], c.staged[g].buf);
@@ -90,12 +99,17 @@ inline void resolve_accesses(LayerCache &c, BufferPool &pool, Counters &st, cons
             st.prefetch_hits++;
         } else {
             status = 2;                     // MISS
+            if (swap && victim >= 0 && !pool.free_staging.empty()) {
+                auto it = std::min_element(pool.free_staging.begin(), pool.free_staging.end());
+                c.slot_buf[s] = *it;        // one buffer taken, one given back: the number of free buffers,
+                *it = old_buf;              // the only thing decisions depend on, does not change
+            }
             copies.push_back({e, c.slot_buf[s]});
             st.misses++;
         }
         c.slot_expert[s] = e;
         c.slot_stamp[s] = ++pool.clock;
-        out.push_back({e, status, s, victim, c.slot_buf[s]});
+        out.push_back({e, status, s, victim, c.slot_buf[s], victim >= 0 ? old_buf : -1});
     }
     // guesses this step did not use are dropped; their buffers are free again
     st.spec_wasted += c.staged.size();

@@ -65,10 +65,12 @@ struct PoolBuf {
     hipEvent_t ready = nullptr;   // recorded on the copy stream after the last copy into this buffer
     bool pending = false;         // a copy was recorded that the compute stream has not yet waited on
     uint64_t have = 0;            // staging use: bytes of the guessed expert requested so far (head of a speculative load)
+    hipEvent_t drained = nullptr; // swap mode: recorded on the write-back stream after the evicted expert left this buffer
+    bool draining = false;        // a write-back out of this buffer was recorded that no later copy into it has waited on
 };
 
 // Optional timing of the engine's own launches with HIP events recorded on the stream each launch goes to.
-enum { PROF_GATE = 0, PROF_W13 = 1, PROF_W2 = 2, PROF_COPY = 3, PROF_FFN = 4, PROF_KINDS = 5 };
+enum { PROF_GATE = 0, PROF_W13 = 1, PROF_W2 = 2, PROF_COPY = 3, PROF_FFN = 4, PROF_WRITEBACK = 5, PROF_KINDS = 6 };
 
 struct ProfKind {
     std::vector<hipEvent_t> start, stop;   // created on demand, reused after a drain
@@ -89,6 +91,7 @@ struct moe_ctx {
     Profiler prof;
     bool host_only = false;
     hipStream_t compute = nullptr, copy = nullptr;
+    hipStream_t writeback = nullptr;    // device -> host copies of evicted experts (layers with MOE_LAYER_SWAP); created on first use
     uint64_t buf_bytes = 0;
     std::vector<PoolBuf> bufs;          // [0, n_staging): staging; layers append their slots
     BufferPool pool;
@@ -124,7 +127,20 @@ struct moe_layer {
     uint8_t *host_blobs = nullptr;
     std::vector<uint32_t> loaded;       // bit m set: matrix m of the expert was loaded
     std::vector<int32_t> own_bufs;      // the k pool buffers created for this layer
+    // Where each expert's blob lives on the host: buffer index into host_blobs, or -1 while it is on the device
+    // (swap mode only; otherwise expert e stays in buffer e for good).
+    bool swap = false;
+    std::vector<int32_t> host_buf_of;
+    int32_t spare_host = -1;            // swap mode: the one host buffer holding no expert
+    std::vector<int32_t> host_reader;   // per host buffer: pool buffer whose `ready` event covers its last read, or -1
+    std::vector<int32_t> host_writer;   // per host buffer: pool buffer whose `drained` event covers its last write, or -1
+    std::vector<std::vector<uint8_t>> pack_tmp;   // swap mode: experts 0..k-1 are packed here until they move to the device
 };
+
+static int32_t n_host_bufs(const moe_layer_config_t &c)
+{
+    return (c.flags & MOE_LAYER_SWAP) ? c.n_experts - c.cache_slots + 1 : c.n_experts;
+}
 
 static uint64_t align_u64(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
 
@@ -141,7 +157,9 @@ static bool layer_cfg_ok(const moe_layer_config_t *c)
     return c && c->n_experts >= 1 && c->n_experts <= MOE_MAX_EXPERTS && c->top_k >= 1 && c->top_k <= MOE_MAX_TOPK &&
            c->top_k <= c->n_experts && c->cache_slots >= c->top_k && c->cache_slots <= c->n_experts &&
            c->prefetch_m >= 0 && c->prefetch_m <= MOE_MAX_GUESS && c->rms_eps >= 0.f &&
-           (c->init_policy == 0 || c->init_policy == 1) && blob_layout(c->hidden, c->ffn, c->bits, c->group).ok;
+           (c->init_policy == 0 || c->init_policy == 1) && (c->flags & ~(MOE_LAYER_NO_CACHE | MOE_LAYER_SWAP)) == 0 &&
+           (!(c->flags & MOE_LAYER_SWAP) || (c->init_policy == 1 && !(c->flags & MOE_LAYER_NO_CACHE))) &&
+           blob_layout(c->hidden, c->ffn, c->bits, c->group).ok;
 }
 
 struct ScratchPlan { uint64_t staging, h, a, yacc, x0, x1, barrier, gs_h, gs_a, total; };
@@ -190,7 +208,7 @@ extern "C" uint64_t moe_layer_dev_bytes(const moe_ctx_t *ctx, const moe_layer_co
 extern "C" uint64_t moe_layer_host_bytes(const moe_layer_config_t *cfg)
 {
     if (!layer_cfg_ok(cfg)) return 0;
-    return blob_layout(cfg->hidden, cfg->ffn, cfg->bits, cfg->group).total * (uint64_t)cfg->n_experts;
+    return blob_layout(cfg->hidden, cfg->ffn, cfg->bits, cfg->group).total * (uint64_t)n_host_bufs(*cfg);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -255,8 +273,10 @@ extern "C" int32_t moe_ctx_create(const moe_ctx_config_t *cfg, void *dev_arena, 
     if (e == hipSuccess) e = hipHostGetDevicePointer(reinterpret_cast<void **>(&c->gate_out_dev), c->gate_out, 0);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_gate, hipEventDisableTiming);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_compute, hipEventDisableTiming);
-    for (int i = 0; i < cfg->n_staging && e == hipSuccess; ++i)
+    for (int i = 0; i < cfg->n_staging && e == hipSuccess; ++i) {
         e = hipEventCreateWithFlags(&c->bufs[i].ready, hipEventDisableTiming);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&c->bufs[i].drained, hipEventDisableTiming);
+    }
     if (e != hipSuccess) {
         g_hip_err = (int32_t)e;
         moe_ctx_destroy(c);
@@ -275,8 +295,11 @@ extern "C" int32_t moe_ctx_destroy(moe_ctx_t *c)
     } else {
         if (c->compute) (void)hipStreamSynchronize(c->compute);
         if (c->copy) (void)hipStreamSynchronize(c->copy);
-        for (PoolBuf &b : c->bufs)
+        if (c->writeback) { (void)hipStreamSynchronize(c->writeback); (void)hipStreamDestroy(c->writeback); }
+        for (PoolBuf &b : c->bufs) {
             if (b.ready) (void)hipEventDestroy(b.ready);
+            if (b.drained) (void)hipEventDestroy(b.drained);
+        }
         for (int k = 0; k < PROF_KINDS; ++k) {
             for (hipEvent_t e : c->prof.kind[k].start) (void)hipEventDestroy(e);
             for (hipEvent_t e : c->prof.kind[k].stop) (void)hipEventDestroy(e);
@@ -326,6 +349,14 @@ extern "C" int32_t moe_layer_create(moe_ctx_t *ctx, const moe_layer_config_t *cf
     l->lay = lay;
     l->host_blobs = static_cast<uint8_t *>(pinned_host_mem);
     l->loaded.assign(cfg->n_experts, 0);
+    l->swap = (cfg->flags & MOE_LAYER_SWAP) != 0;
+    l->host_buf_of.resize(cfg->n_experts);
+    for (int e = 0; e < cfg->n_experts; ++e)            // swap: experts 0..k-1 start on the device, the rest fill the host buffers
+        l->host_buf_of[e] = l->swap ? (e < cfg->cache_slots ? -1 : e - cfg->cache_slots) : e;
+    l->spare_host = l->swap ? cfg->n_experts - cfg->cache_slots : -1;
+    l->host_reader.assign(n_host_bufs(*cfg), -1);
+    l->host_writer.assign(n_host_bufs(*cfg), -1);
+    l->pack_tmp.resize(l->swap ? cfg->cache_slots : 0);
     const int first = (int)ctx->bufs.size();
     if (!ctx->host_only) {
         if (!dev_mem || ((uintptr_t)dev_mem & 255)) { delete l; return fail(MOE_EINVAL, "moe_layer_create: device memory null or not 256-byte aligned"); }
@@ -344,9 +375,12 @@ extern "C" int32_t moe_layer_create(moe_ctx_t *ctx, const moe_layer_config_t *cf
         for (int s = 0; s < cfg->cache_slots && e == hipSuccess; ++s) {
             fresh[s].ptr = base + ctx->buf_bytes * s;
             e = hipEventCreateWithFlags(&fresh[s].ready, hipEventDisableTiming);
+            if (e == hipSuccess) e = hipEventCreateWithFlags(&fresh[s].drained, hipEventDisableTiming);
         }
+        if (e == hipSuccess && (cfg->flags & MOE_LAYER_SWAP) && !ctx->writeback)
+            e = hipStreamCreateWithFlags(&ctx->writeback, hipStreamNonBlocking);
         if (e != hipSuccess) {
-            for (PoolBuf &b : fresh) if (b.ready) (void)hipEventDestroy(b.ready);
+            for (PoolBuf &b : fresh) { if (b.ready) (void)hipEventDestroy(b.ready); if (b.drained) (void)hipEventDestroy(b.drained); }
             g_hip_err = (int32_t)e;
             delete l;
             return fail(MOE_EHIP, "moe_layer_create: HIP set-up failed: %s", hipGetErrorString(e));
@@ -368,6 +402,7 @@ extern "C" int32_t moe_layer_destroy(moe_layer_t *l)
     if (!l->ctx->host_only) {
         (void)hipStreamSynchronize(l->ctx->compute);
         (void)hipStreamSynchronize(l->ctx->copy);
+        if (l->ctx->writeback) (void)hipStreamSynchronize(l->ctx->writeback);
     }
     l->ctx->n_layers--;
     delete l;   // pool buffers and their events stay with the context until it is destroyed
@@ -381,6 +416,15 @@ static bool all_loaded(const moe_layer *l)
     return true;
 }
 
+// Host memory of expert e's blob: its host buffer, or, in swap mode while an expert that starts on the device is
+// still being loaded, its packing area.  nullptr when the blob is on the device only.
+static uint8_t *host_blob(moe_layer *l, int32_t e)
+{
+    if (l->host_buf_of[e] >= 0) return l->host_blobs + (uint64_t)l->host_buf_of[e] * l->lay.total;
+    if (l->swap && e < (int32_t)l->pack_tmp.size() && !l->pack_tmp[e].empty()) return l->pack_tmp[e].data();
+    return nullptr;
+}
+
 static int32_t warm_fill(moe_layer *l, int32_t e)
 {
     // init_policy 1: expert e < k sits in slot e from the start
@@ -389,8 +433,9 @@ static int32_t warm_fill(moe_layer *l, int32_t e)
     c.slot_stamp[e] = ++l->ctx->pool.clock;
     if (!l->ctx->host_only) {
         PoolBuf &b = l->ctx->bufs[c.slot_buf[e]];
-        HIPCHK(hipMemcpy(b.ptr, l->host_blobs + (uint64_t)e * l->lay.total, l->lay.total, hipMemcpyHostToDevice));
+        HIPCHK(hipMemcpy(b.ptr, host_blob(l, e), l->lay.total, hipMemcpyHostToDevice));
     }
+    if (l->swap) std::vector<uint8_t>().swap(l->pack_tmp[e]);    // the device copy is now the only one
     return MOE_OK;
 }
 
@@ -402,7 +447,13 @@ extern "C" int32_t moe_layer_load_expert(moe_layer_t *l, int32_t expert, int32_t
         return fail(MOE_EINVAL, "moe_layer_load_expert: expert %d / matrix %d out of range", expert, matrix);
     const BlobLayout &b = l->lay;
     const MatLayout &m = mat_of(b, matrix);
-    uint8_t *blob = l->host_blobs + (uint64_t)expert * b.total;
+    if (l->swap && expert < l->cfg.cache_slots) {
+        if (l->loaded[expert] == 7u) return fail(MOE_ESTATE, "moe_layer_load_expert: expert %d already moved to the device (swap mode)", expert);
+        if (l->pack_tmp[expert].empty()) {
+            try { l->pack_tmp[expert].resize(b.total); } catch (...) { return fail(MOE_ENOMEM, "moe_layer_load_expert: out of host memory"); }
+        }
+    }
+    uint8_t *blob = host_blob(l, expert);
     const uint32_t groups = m.cols / b.group;
     const uint32_t qmax = (1u << b.bits) - 1;
     const unsigned hw = std::max(1u, std::min(16u, std::thread::hardware_concurrency()));
@@ -444,7 +495,9 @@ extern "C" int32_t moe_layer_peek_weight(const moe_layer_t *l, int32_t expert, i
     if (row < 0 || (uint32_t)row >= m.rows || col < 0 || (uint32_t)col >= m.cols)
         return fail(MOE_EINVAL, "moe_layer_peek_weight: row or column out of range");
     if (!(l->loaded[expert] & (1u << matrix))) return fail(MOE_ESTATE, "moe_layer_peek_weight: matrix not loaded");
-    peek_row(l->lay, m, l->host_blobs + (uint64_t)expert * l->lay.total + row_offset(l->lay, matrix, row), col, code, scale, zero);
+    const uint8_t *blob = host_blob(const_cast<moe_layer *>(l), expert);
+    if (!blob) return fail(MOE_ESTATE, "moe_layer_peek_weight: expert %d is on the device only (swap mode)", expert);
+    peek_row(l->lay, m, blob + row_offset(l->lay, matrix, row), col, code, scale, zero);
     return MOE_OK;
 }
 
@@ -502,6 +555,7 @@ extern "C" int32_t moe_ctx_profile_enable(moe_ctx_t *c, int32_t on)
     if (c->host_only) return fail(MOE_ESTATE, "moe_ctx_profile_enable: host-only context");
     HIPCHK(hipStreamSynchronize(c->compute));
     HIPCHK(hipStreamSynchronize(c->copy));
+    if (c->writeback) HIPCHK(hipStreamSynchronize(c->writeback));
     for (int k = 0; k < PROF_KINDS; ++k) {
         ProfKind &p = c->prof.kind[k];
         p.used = 0; p.launches = 0; p.bytes = 0; p.ms = 0.0;
@@ -524,7 +578,8 @@ extern "C" int32_t moe_ctx_profile_read(moe_ctx_t *c, moe_profile_t *out)
     if (c->host_only) return fail(MOE_ESTATE, "moe_ctx_profile_read: host-only context");
     HIPCHK(hipStreamSynchronize(c->compute));
     HIPCHK(hipStreamSynchronize(c->copy));
-    moe_profile_entry_t *dst[PROF_KINDS] = {&out->gate, &out->w13, &out->w2, &out->copy, &out->ffn};
+    if (c->writeback) HIPCHK(hipStreamSynchronize(c->writeback));
+    moe_profile_entry_t *dst[PROF_KINDS] = {&out->gate, &out->w13, &out->w2, &out->copy, &out->ffn, &out->writeback};
     for (int k = 0; k < PROF_KINDS; ++k) {
         int32_t rc = prof_drain(c, k);
         if (rc) return rc;
@@ -544,6 +599,8 @@ struct StepPlan {
     std::vector<CopyOp> demand;     // misses, and the tails of confirmed speculative loads
     std::vector<int> demand_of;     // per access: index into `demand`, or -1
     std::vector<CopyOp> spec;       // for the next layer
+    std::vector<CopyOp> writeback;  // swap mode: evicted expert `expert` from pool buffer `buf` to host buffer `host_buf`
+    std::vector<int> writeback_of;  // per access: index into `writeback`, or -1
     bool victim_needed = false;     // an expert needed in this step was evicted during it
 };
 
@@ -559,7 +616,7 @@ static int32_t plan_step(moe_layer *l, moe_layer *next, const int32_t *idx, int3
     std::sort(needed.begin(), needed.end());
     needed.erase(std::unique(needed.begin(), needed.end()), needed.end());
     std::vector<CopyOp> misses;
-    resolve_accesses(l->cache, l->ctx->pool, l->st, needed, (cf.flags & MOE_LAYER_NO_CACHE) != 0, plan.access, misses);
+    resolve_accesses(l->cache, l->ctx->pool, l->st, needed, (cf.flags & MOE_LAYER_NO_CACHE) != 0, plan.access, misses, l->swap);
     size_t next_miss = 0;
     for (const AccessRec &a : plan.access) {
         if (a.victim >= 0 && std::binary_search(needed.begin(), needed.end(), a.victim)) plan.victim_needed = true;
@@ -567,19 +624,34 @@ static int32_t plan_step(moe_layer *l, moe_layer *next, const int32_t *idx, int3
         int di = -1;
         if (a.status == MOE_MISS) {
             CopyOp op = misses[next_miss++];
-            op.offset = 0; op.bytes = l->lay.total;
+            op.offset = 0; op.bytes = l->lay.total; op.host_buf = l->host_buf_of[a.expert];
             l->st.bytes_demand += op.bytes;
             di = (int)plan.demand.size();
             plan.demand.push_back(op);
         } else if (a.status == MOE_PREFETCH_HIT && pb.have < l->lay.total) {
             // the guess was right but only its head was requested: the rest is fetched now, like a demand load
-            CopyOp op{a.expert, a.buf, pb.have, l->lay.total - pb.have};
+            CopyOp op{a.expert, a.buf, pb.have, l->lay.total - pb.have, l->host_buf_of[a.expert]};
             l->st.bytes_spec += op.bytes;
             di = (int)plan.demand.size();
             plan.demand.push_back(op);
         }
         if (a.status != MOE_HIT) pb.have = l->lay.total;
         plan.demand_of.push_back(di);
+        // swap mode (Sec. 3.3): the expert that came in vacates its host buffer, the evicted one goes back to the
+        // host -- into the buffer that was spare, so that this write need not wait for the load's read; the
+        // vacated buffer is the spare from now on.
+        int wi = -1;
+        if (l->swap && a.status != MOE_HIT) {
+            if (a.victim < 0 || l->host_buf_of[a.expert] < 0) return fail(MOE_ESTATE, "swap bookkeeping out of step for expert %d", a.expert);
+            CopyOp wb{a.victim, a.victim_buf, 0, l->lay.total, l->spare_host};
+            l->host_buf_of[a.victim] = l->spare_host;
+            l->spare_host = l->host_buf_of[a.expert];
+            l->host_buf_of[a.expert] = -1;
+            l->st.bytes_writeback += wb.bytes;
+            wi = (int)plan.writeback.size();
+            plan.writeback.push_back(wb);
+        }
+        plan.writeback_of.push_back(wi);
     }
     std::vector<int32_t> guess, issued;
     if (next && guess_score && next->cfg.prefetch_m > 0) {
@@ -589,6 +661,7 @@ static int32_t plan_step(moe_layer *l, moe_layer *next, const int32_t *idx, int3
             const uint64_t head = l->ctx->spec_head_bytes;
             op.offset = 0;
             op.bytes = head ? std::min<uint64_t>(head, next->lay.total) : next->lay.total;
+            op.host_buf = next->host_buf_of[op.expert];
             l->ctx->bufs[op.buf].have = op.bytes;
             next->st.bytes_spec += op.bytes;
         }
@@ -607,19 +680,64 @@ static int32_t plan_step(moe_layer *l, moe_layer *next, const int32_t *idx, int3
     return MOE_OK;
 }
 
-static int32_t issue_copy(moe_ctx *c, const moe_layer *owner, const CopyOp &op)
+static int32_t issue_copy(moe_ctx *c, moe_layer *owner, const CopyOp &op)
 {
     PoolBuf &b = c->bufs[op.buf];
+    if (op.host_buf < 0) return fail(MOE_ESTATE, "expert %d has no host buffer to load from", op.expert);
+    // swap mode: the target may still be draining an evicted expert, the source may still be receiving one
+    if (b.draining) { HIPCHK(hipStreamWaitEvent(c->copy, b.drained, 0)); b.draining = false; }
+    if (owner->host_writer[op.host_buf] >= 0) {
+        HIPCHK(hipStreamWaitEvent(c->copy, c->bufs[owner->host_writer[op.host_buf]].drained, 0));
+        owner->host_writer[op.host_buf] = -1;
+    }
     int ps;
     int32_t rc = prof_begin(c, PROF_COPY, c->copy, op.bytes, &ps);
     if (rc) return rc;
-    HIPCHK(hipMemcpyAsync(b.ptr + op.offset, owner->host_blobs + (uint64_t)op.expert * owner->lay.total + op.offset, op.bytes,
+    HIPCHK(hipMemcpyAsync(b.ptr + op.offset, owner->host_blobs + (uint64_t)op.host_buf * owner->lay.total + op.offset, op.bytes,
                           hipMemcpyHostToDevice, c->copy));
     rc = prof_end(c, PROF_COPY, c->copy, ps);
     if (rc) return rc;
     HIPCHK(hipEventRecord(b.ready, c->copy));
     b.pending = true;
+    owner->host_reader[op.host_buf] = op.buf;
     return MOE_OK;
+}
+
+// Swap mode: the evicted expert leaves pool buffer op.buf for host buffer op.host_buf on the write-back stream.
+// The caller has made sure that no kernel still reads the buffer (as for a copy that overwrites it).
+static int32_t issue_writeback(moe_ctx *c, moe_layer *owner, const CopyOp &op)
+{
+    PoolBuf &b = c->bufs[op.buf];
+    if (owner->host_reader[op.host_buf] >= 0) {      // the load that vacated the target must have read all of it
+        HIPCHK(hipStreamWaitEvent(c->writeback, c->bufs[owner->host_reader[op.host_buf]].ready, 0));
+        owner->host_reader[op.host_buf] = -1;
+    }
+    HIPCHK(hipStreamWaitEvent(c->writeback, b.ready, 0));   // the victim's own load (it may have come in earlier in this very step)
+    int ps;
+    int32_t rc = prof_begin(c, PROF_WRITEBACK, c->writeback, op.bytes, &ps);
+    if (rc) return rc;
+    HIPCHK(hipMemcpyAsync(owner->host_blobs + (uint64_t)op.host_buf * owner->lay.total, b.ptr, op.bytes, hipMemcpyDeviceToHost, c->writeback));
+    rc = prof_end(c, PROF_WRITEBACK, c->writeback, ps);
+    if (rc) return rc;
+    HIPCHK(hipEventRecord(b.drained, c->writeback));
+    b.draining = true;
+    owner->host_writer[op.host_buf] = op.buf;
+    return MOE_OK;
+}
+
+// The transfers one access asks for: its load (a miss, or the tail of a confirmed guess) and, in swap mode, the
+// write-back of the expert it evicted.  The load goes first, so that it is not queued behind anything, unless
+// it targets the very buffer the victim still sits in (no staging buffer was free): then the victim leaves first
+// and the load waits for that.
+static int32_t issue_access_transfers(moe_ctx *c, moe_layer *l, const StepPlan &plan, int i)
+{
+    const int di = plan.demand_of[i], wi = plan.writeback_of[i];
+    const bool victim_first = di >= 0 && wi >= 0 && plan.demand[di].buf == plan.writeback[wi].buf;
+    int32_t rc = MOE_OK;
+    if (victim_first) rc = issue_writeback(c, l, plan.writeback[wi]);
+    if (!rc && di >= 0) rc = issue_copy(c, l, plan.demand[di]);
+    if (!rc && wi >= 0 && !victim_first) rc = issue_writeback(c, l, plan.writeback[wi]);
+    return rc;
 }
 
 static int32_t check_step_args(const moe_layer *l, const moe_layer *next, int32_t batch)
@@ -642,7 +760,7 @@ extern "C" int32_t moe_layer_resolve(moe_layer_t *l, moe_layer_t *next, const in
     rc = plan_step(l, next, expert_idx, batch, guess_score, trace, plan);
     if (rc) return rc;
     if (!l->ctx->host_only) {
-        for (const CopyOp &op : plan.demand) { rc = issue_copy(l->ctx, l, op); if (rc) return rc; }
+        for (int i = 0; i < (int)plan.access.size(); ++i) { rc = issue_access_transfers(l->ctx, l, plan, i); if (rc) return rc; }
         for (const CopyOp &op : plan.spec) { rc = issue_copy(l->ctx, next, op); if (rc) return rc; }
     }
     return MOE_OK;
@@ -1064,8 +1182,7 @@ extern "C" int32_t moe_layer_step(moe_layer_t *l, moe_layer_t *next, const uint1
             HIPCHK(hipEventRecord(c->ev_compute, c->compute));
             HIPCHK(hipStreamWaitEvent(c->copy, c->ev_compute, 0));
         }
-        for (int i : passes[p])
-            if (plan.demand_of[i] >= 0) { rc = issue_copy(c, l, plan.demand[plan.demand_of[i]]); if (rc) return rc; }
+        for (int i : passes[p]) { rc = issue_access_transfers(c, l, plan, i); if (rc) return rc; }
         if (p + 1 == passes.size() && !plan.victim_needed && passes.size() == 1)
             for (const CopyOp &op : plan.spec) { rc = issue_copy(c, next, op); if (rc) return rc; }
         if (use_mfma) {
@@ -1158,6 +1275,7 @@ extern "C" int32_t moe_layer_prefetch(moe_layer_t *l, const uint16_t *h_dev, int
     for (CopyOp &op : copies) {
         op.offset = 0;
         op.bytes = c->spec_head_bytes ? std::min<uint64_t>(c->spec_head_bytes, l->lay.total) : l->lay.total;
+        op.host_buf = l->host_buf_of[op.expert];
         c->bufs[op.buf].have = op.bytes;
         l->st.bytes_spec += op.bytes;
     }
@@ -1197,7 +1315,8 @@ extern "C" int32_t moe_layer_stats(const moe_layer_t *l, moe_stats_t *o)
 {
     if (!l || !o) return fail(MOE_EINVAL, "moe_layer_stats: null argument");
     const Counters &s = l->st;
-    *o = {s.steps, s.needed, s.hits, s.prefetch_hits, s.misses, s.evictions, s.spec_issued, s.spec_wasted, s.bytes_demand, s.bytes_spec};
+    *o = {s.steps, s.needed, s.hits, s.prefetch_hits, s.misses, s.evictions, s.spec_issued, s.spec_wasted, s.bytes_demand, s.bytes_spec,
+          s.bytes_writeback};
     return MOE_OK;
 }
 
@@ -1215,9 +1334,19 @@ extern "C" int32_t moe_layer_cache_state(const moe_layer_t *l, int32_t *slot_exp
     return MOE_OK;
 }
 
+extern "C" int32_t moe_layer_placement(const moe_layer_t *l, int32_t *host_buf_of, int32_t *spare_host)
+{
+    if (!l) return fail(MOE_EINVAL, "moe_layer_placement: layer is null");
+    if (host_buf_of)
+        for (int e = 0; e < l->cfg.n_experts; ++e) host_buf_of[e] = l->host_buf_of[e];
+    if (spare_host) *spare_host = l->spare_host;
+    return MOE_OK;
+}
+
 extern "C" int32_t moe_layer_reset(moe_layer_t *l)
 {
     if (!l) return fail(MOE_EINVAL, "moe_layer_reset: layer is null");
+    if (l->swap) return fail(MOE_ESTATE, "moe_layer_reset: a layer in swap mode cannot return to its initial placement; create it again");
     moe_ctx *c = l->ctx;
     if (!c->host_only) {
         HIPCHK(hipStreamSynchronize(c->compute));
@@ -1299,6 +1428,7 @@ extern "C" int32_t moe_layer_set_prefetch(moe_layer_t *l, int32_t m)
 extern "C" int32_t moe_layer_set_flags(moe_layer_t *l, int32_t flags)
 {
     if (!l || (flags & ~MOE_LAYER_NO_CACHE)) return fail(MOE_EINVAL, "moe_layer_set_flags: bad argument");
-    l->cfg.flags = flags;
+    if (l->swap && flags) return fail(MOE_EINVAL, "moe_layer_set_flags: a layer in swap mode cannot forget residency");
+    l->cfg.flags = flags | (l->swap ? MOE_LAYER_SWAP : 0);
     return MOE_OK;
 }

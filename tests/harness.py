@@ -25,14 +25,14 @@ class Model:
 
     def __init__(self, L, H, F, E=8, K=2, formats: Optional[Sequence[Tuple[int, int]]] = None, k=2, m=0,
                  rms_eps=0.0, b=4, max_batch=1, seed=0, device="cuda:0", keep_layers: Optional[Sequence[int]] = None,
-                 init_policy=0):
+                 init_policy=0, flags=0):
         self.L, self.H, self.F, self.E, self.K, self.k, self.m, self.eps = L, H, F, E, K, k, m, rms_eps
         self.formats = list(formats) if formats else [(4, 64)] * L
         self.seed = seed
         self.device = device
         self.gate = [W.gate_weight(seed, l, E, H) for l in range(L)]
         self.gamma = [W.rms_gamma(H) for _ in range(L)] if rms_eps > 0 else None
-        cfgs = [layer_config(H, F, E, K, self.formats[l][0], self.formats[l][1], k, m, rms_eps, init_policy)
+        cfgs = [layer_config(H, F, E, K, self.formats[l][0], self.formats[l][1], k, m, rms_eps, init_policy, flags)
                 for l in range(L)]
         self.stack = Stack(cfgs, self.gate, self.gamma, n_staging=b, max_batch=max_batch, device=device)
         self.experts: Dict[Tuple[int, int], list] = {}

@@ -26,8 +26,9 @@ def say(msg):
 
 
 def run_teacher_forced(model: Model, xs: torch.Tensor, ffn, check_ffn=lambda t, l: True, prefetch=True, b=4,
-                       sim=None):
-    """xs: [T][B][H] fp16 (CPU).  Runs layer by layer, checks every decision, returns (final x per token, sim, errs)."""
+                       sim=None, placement=None):
+    """xs: [T][B][H] fp16 (CPU).  Runs layer by layer, checks every decision, returns (final x per token, sim, errs).
+    placement: per layer an oracle SwapPlacement to follow and compare with the engine's after every step."""
     L, E, K = model.L, model.E, model.K
     T, Bn, H = xs.shape
     sim = sim or O.ExpertCacheSim(L, E, model.k, b)
@@ -59,6 +60,10 @@ def run_teacher_forced(model: Model, xs: torch.Tensor, ffn, check_ffn=lambda t, 
             acc, dec = sim.step(l, sel, guess)
             assert tr.accesses() == [(a.expert, a.status, a.slot, a.victim) for a in acc], f"cache trace differs t={t} l={l}"
             assert tr.guesses() == [(e, i) for e, i in dec], f"prefetch decisions differ t={t} l={l}"
+            if placement is not None:
+                placement[l].apply(acc)
+                assert B.moe_layer_placement(model.stack.layers[l], E) == (placement[l].host_buf_of, placement[l].spare), \
+                    f"placement differs t={t} l={l}"
             if check_ffn(t, l):
                 y_gpu = model.stack.read_y(Bn, H)
                 x_out = xb[l + 1].cpu().numpy()
@@ -444,4 +449,52 @@ def test_largest_supported_matrices():
     say("largest matrices: run")
     _, sim, errs = run_teacher_forced(model, xs, c_ffn.expert_ffn)
     say(f"  max abs {max(e[0] for e in errs):.2e} max rel-rms {max(e[1] for e in errs):.2e}")
+    model.close()
+
+
+@pytest.mark.parametrize("H,F,k,m,Bn,T,head_mb", [(256, 512, 2, 2, 1, 48, 0), (1024, 2048, 2, 2, 1, 20, 1), (256, 512, 4, 2, 4, 12, 0),
+                                                  (256, 512, 4, 2, 16, 6, 0), (256, 512, 2, 1, 8, 6, 0)])
+def test_swap_eviction_keeps_every_expert_intact(H, F, k, m, Bn, T, head_mb):
+    """Sec. 3.3, hosts that cannot hold every expert (MOE_LAYER_SWAP): every load writes the evicted expert back
+    to the host.  Over many swaps every decision still equals the oracle's, every expert sits where the oracle's
+    placement says, every output row is in tolerance (a blob damaged on its way out or back would show as soon as
+    the expert is used again), and the outputs are bit-identical to the same stack without swapping.  The 3.5 MB
+    blobs of the H=1024 case with a 1 MiB head also cover a confirmed guess whose tail is read from the host buffer
+    the expert is about to vacate."""
+    L, E = 4, 8
+    xs = W.hidden_ar1(61, T, Bn, H)
+    outs = {}
+    for name, flags in (("swap", B.MOE_LAYER_SWAP), ("plain", 0)):
+        say(f"swap eviction k={k} m={m} B={Bn} head={head_mb} MiB: {name}")
+        model = Model(L, H, F, E, 2, None, k, m, 1e-5, max_batch=Bn, seed=61, init_policy=1, flags=flags)
+        B.moe_ctx_set_option(model.stack.ctx, "spec_head_mb", head_mb)
+        sim = O.ExpertCacheSim(L, E, k, 4, warm=True)
+        place = [O.SwapPlacement(E, k) for _ in range(L)] if flags else None
+        o, sim, errs = run_teacher_forced(model, xs, O.expert_ffn, sim=sim, placement=place)
+        tot = model.stack.total_stats()
+        blob = model.stack.blob_bytes[0]
+        if flags:
+            assert tot["bytes_d2h_writeback"] == sum(p.writebacks for p in place) * blob == tot["evictions"] * blob > 0
+        else:
+            assert tot["bytes_d2h_writeback"] == 0
+        outs[name] = (o, {n: v for n, v in tot.items() if n != "bytes_d2h_writeback"})
+        say(f"  max rel-rms {max(e[1] for e in errs):.2e} evictions {tot['evictions']}")
+        model.close()
+    for a, b in zip(outs["swap"][0], outs["plain"][0]):
+        assert (a.view(np.uint16) == b.view(np.uint16)).all()
+    assert outs["swap"][1] == outs["plain"][1]
+
+
+def test_swap_eviction_mixtral_layer():
+    """One Mixtral-shaped layer in swap mode, k=2: 99 MB blobs travel both ways; C oracle on every token."""
+    c = W.CONFIGS["mixtral_layer"]
+    say("swap eviction, mixtral layer: build")
+    model = Model(1, c.hidden, c.ffn, c.n_experts, c.top_k, None, 2, 0, 0.0, seed=c.seed, init_policy=1, flags=B.MOE_LAYER_SWAP)
+    xs = W.hidden_ar1(c.seed, 12, 1, c.hidden)
+    sim = O.ExpertCacheSim(1, c.n_experts, 2, 4, warm=True)
+    place = [O.SwapPlacement(c.n_experts, 2)]
+    _, sim, errs = run_teacher_forced(model, xs, c_ffn.expert_ffn, sim=sim, placement=place)
+    st = model.stack.stats()[0]
+    assert st["bytes_d2h_writeback"] == st["misses"] * model.stack.blob_bytes[0] > 0
+    say(f"  max abs {max(e[0] for e in errs):.2e} max rel-rms {max(e[1] for e in errs):.2e} write-backs {place[0].writebacks}")
     model.close()

@@ -102,6 +102,65 @@ def test_warm_start_reset_and_ablation_flags():
     st.close()
 
 
+@pytest.mark.parametrize("L,E,k,m,b,B_", [(3, 8, 2, 2, 4, 1), (2, 8, 4, 2, 4, 16), (2, 6, 3, 2, 1, 3), (2, 16, 4, 4, 4, 8)])
+def test_swap_mode_bookkeeping_and_placement_equal_the_oracle(L, E, k, m, b, B_):
+    """MOE_LAYER_SWAP (Sec. 3.3, hosts that cannot hold every expert): the decisions are those of the plain mode
+    with a warm start, and after every step each expert sits in the host buffer the oracle's placement says."""
+    rng = np.random.default_rng(7 * L + E + k + B_)
+    st = make_stack(L, E, k, m, b, flags=B.MOE_LAYER_SWAP, init_policy=1, max_batch=B_)
+    blob = B.moe_expert_blob_bytes(64, 64, 4, 64)
+    assert B.moe_layer_host_bytes(st.cfgs[0]) == (E - k + 1) * blob
+    codes = {}
+    for l in range(L):
+        for e in range(E):
+            for mtx in range(3):
+                q = rng.integers(0, 16, size=(64, 64)).astype(np.uint8)
+                sc = rng.integers(0, 1 << 16, size=(64, 1)).astype(np.uint16)
+                codes[(l, e, mtx)] = (q, sc)
+                B.moe_layer_load_expert(st.layers[l], e, mtx, q.ctypes.data, sc.ctypes.data, sc.ctypes.data)
+    sim = O.ExpertCacheSim(L, E, k, b, warm=True)
+    place = [O.SwapPlacement(E, k) for _ in range(L)]
+    for l in range(L):
+        assert B.moe_layer_placement(st.layers[l], E) == (place[l].host_buf_of, place[l].spare)
+    tr = B.StepTrace()
+    for _ in range(100):
+        for l in range(L):
+            sel = [[int(e) for e in rng.choice(E, size=2, replace=False)] for _ in range(B_)]
+            score = rng.dirichlet(np.ones(E)) * B_
+            nxt = st.layers[l + 1] if l + 1 < L else None
+            B.moe_layer_resolve(st.layers[l], nxt, [e for t in sel for e in t], B_, list(score) if nxt else None, tr)
+            acc, dec = sim.step(l, sel, O.prefetch_guess(score, m) if nxt else None)
+            assert tr.accesses() == [(a.expert, a.status, a.slot, a.victim) for a in acc]
+            assert tr.guesses() == [(e, i) for e, i in dec]
+            place[l].apply(acc)
+            assert B.moe_layer_placement(st.layers[l], E) == (place[l].host_buf_of, place[l].spare)
+    for l in range(L):
+        s, o = B.moe_layer_stats(st.layers[l]).as_dict(), sim.stats[l]
+        for name in ("needed", "hits", "prefetch_hits", "misses", "evictions", "spec_issued", "spec_wasted"):
+            assert s[name] == getattr(o, name), name
+        assert s["bytes_d2h_writeback"] == place[l].writebacks * blob == o.evictions * blob
+    # an expert on the device has no host copy to read; one on the host reads back what was loaded
+    lay = st.layers[0]
+    on_dev = place[0].on_device()[0]
+    expect(B.MOE_ESTATE, B.moe_layer_peek_weight, lay, on_dev, 0, 0, 0)
+    expect(B.MOE_ESTATE, B.moe_layer_reset, lay)
+    expect(B.MOE_EINVAL, B.moe_layer_set_flags, lay, B.MOE_LAYER_NO_CACHE)
+    st.close()
+
+
+def test_swap_mode_needs_the_warm_start():
+    cc = B.CtxConfig(4, 1, 64, 64, 2, B.MOE_CTX_HOST_ONLY, 1 << 16)
+    ctx = B.moe_ctx_create(cc, None, 0, None, None)
+    gw = np.zeros((8, 64), np.float32)
+    raw = np.zeros((1 << 20) + 64, np.uint8)
+    host = raw[(-raw.ctypes.data) % 64:][: 1 << 20]
+    bad = layer_config(64, 64, 8, 2, 4, 64, 2, 0, 0.0, 0, B.MOE_LAYER_SWAP)           # cold start
+    expect(B.MOE_EINVAL, B.moe_layer_create, ctx, bad, gw.ctypes.data, None, None, host.ctypes.data)
+    bad = layer_config(64, 64, 8, 2, 4, 64, 2, 0, 0.0, 1, B.MOE_LAYER_SWAP | B.MOE_LAYER_NO_CACHE)
+    expect(B.MOE_EINVAL, B.moe_layer_create, ctx, bad, gw.ctypes.data, None, None, host.ctypes.data)
+    B.moe_ctx_destroy(ctx)
+
+
 @pytest.mark.parametrize("bits,group", [(4, 32), (4, 64), (4, 128), (3, 64), (2, 16)])
 def test_packed_blob_reads_back_every_code(bits, group):
     rng = np.random.default_rng(group + bits)
