@@ -35,15 +35,17 @@ def log(msg: str) -> None:
     print(f"[bench] {msg}", file=sys.stderr, flush=True)
 
 
-def build_model(shape, formats, batch, device, keep_layers, n_staging=4):
+def build_model(shape, formats, batch, device, keep_layers, n_staging=4, swap=False):
     import torch
     import workload as W
     from paper_2312_17238_amd.engine import Stack, layer_config
 
     gates = [W.gate_weight(shape.seed, l, shape.n_experts, shape.hidden) for l in range(shape.layers)]
     gamma = [W.rms_gamma(shape.hidden) for _ in range(shape.layers)] if shape.rms_eps > 0 else None
+    from paper_2312_17238_amd import binding as B
     cfgs = [layer_config(shape.hidden, shape.ffn, shape.n_experts, shape.top_k, formats[l][0], formats[l][1],
-                         shape.cache_slots, shape.prefetch_m, shape.rms_eps) for l in range(shape.layers)]
+                         shape.cache_slots, shape.prefetch_m, shape.rms_eps, 1 if swap else 0,
+                         B.MOE_LAYER_SWAP if swap else 0) for l in range(shape.layers)]
     stack = Stack(cfgs, gates, gamma, n_staging=n_staging, max_batch=batch, device=device)
     kept = {}
     t0 = time.time()
@@ -111,6 +113,9 @@ def main() -> int:
     ap.add_argument("--fused", action="store_true", help="single-token steps run w1/w3 and w2 as one persistent launch")
     ap.add_argument("--no-token-path", action="store_true", help="single-token steps use the general kernels (atomics + residual kernel)")
     ap.add_argument("--no-probe", action="store_true", help="skip the plain streaming-read / copy calibration kernels")
+    ap.add_argument("--swap", action="store_true",
+                    help="hosts that cannot hold every expert (Sec. 3.3): experts split between host and device buffers, "
+                         "every load writes the evicted expert back (experts 0..k-1 start on the device)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (one process, no collectives); "
@@ -142,7 +147,7 @@ def main() -> int:
     keep_layers = set() if args.no_cpu_baseline else set(range(min(2, shape.layers)))
     log(f"workload {shape.name}: {shape.layers} layers, H={shape.hidden}, F={shape.ffn}, E={shape.n_experts}, "
         f"k={shape.cache_slots}, m={shape.prefetch_m}, batch={batch}, formats={sorted(set(formats))}")
-    stack, gates, gamma, kept = build_model(shape, formats, batch, device, keep_layers)
+    stack, gates, gamma, kept = build_model(shape, formats, batch, device, keep_layers, swap=args.swap)
     if args.no_cache:
         stack.set_flags(B.MOE_LAYER_NO_CACHE)
     B.moe_ctx_set_option(stack.ctx, "spec_head_mb", args.spec_head_mb)
@@ -219,7 +224,7 @@ def main() -> int:
                                f"{shape.n_experts} experts top-{shape.top_k}, formats {sorted(set(formats))}, "
                                f"LRU k={shape.cache_slots}, prefetch m={shape.prefetch_m}, b=4 staging buffers, "
                                f"batch {batch}, {shape.hidden_kind} hidden states, seed {shape.seed}",
-                   "no_cache": bool(args.no_cache), "spec_head_mb": args.spec_head_mb},
+                   "no_cache": bool(args.no_cache), "spec_head_mb": args.spec_head_mb, "swap": bool(args.swap)},
     }
     link_bytes = d["bytes_h2d_demand"] + d["bytes_h2d_spec"]
     result["cache"] = {"needed": d["needed"], "hits": d["hits"], "prefetch_hits": d["prefetch_hits"], "misses": d["misses"],
@@ -278,6 +283,13 @@ def main() -> int:
                               "measured_h2d_probe_gbs": probe.get("h2d_gbs") if probe else None,
                               "busy_frac_of_wall": cp["total_ms"] / (1e3 * dt),
                               "wall_gbs": link_bytes / dt / 1e9}
+        wb = prof["writeback"]
+        if wb["launches"]:
+            aw = wb["bytes"] / max(wb["total_ms"], 1e-9) / 1e6
+            result["link_writeback"] = {"bound": "host-link (device to host)", "achieved": aw, "peak": LINK_PEAK_GBS, "unit": "GB/s",
+                                        "frac": aw / LINK_PEAK_GBS, "copies": wb["launches"],
+                                        "busy_frac_of_wall": wb["total_ms"] / (1e3 * dt),
+                                        "bytes_per_token": d["bytes_d2h_writeback"] / tokens}
         result["gate_avg_us"] = 1e3 * gt["total_ms"] / max(1, gt["launches"])
     if probe:
         result["probe"] = probe
