@@ -16,6 +16,8 @@ def _load():
         _lib = ctypes.CDLL(_build.build())
         _lib.moe_oracle_expert_ffn.restype = ctypes.c_int
         _lib.moe_oracle_expert_ffn.argtypes = [ctypes.c_int] * 3 + [ctypes.c_void_p] * 11
+        _lib.moe_oracle_expert_ffn_f64meta.restype = ctypes.c_int
+        _lib.moe_oracle_expert_ffn_f64meta.argtypes = [ctypes.c_int] * 3 + [ctypes.c_void_p] * 11
         _lib.moe_oracle_threads.restype = ctypes.c_int
     return _lib
 
@@ -33,6 +35,8 @@ def _p(a: np.ndarray, dtype) -> np.ndarray:
 def expert_ffn(h_f16: np.ndarray, expert, group: int) -> np.ndarray:
     """Same contract as moe_oracle.expert_ffn, computed by the plain C loops."""
     lib = _load()
+    if len(expert[0]) == 4:
+        return _expert_ffn_meta8(lib, h_f16, expert, group)
     (q1, s1, z1), (q3, s3, z3), (q2, s2, z2) = expert
     F, H = q1.shape
     assert q3.shape == (F, H) and q2.shape == (H, F)
@@ -43,4 +47,20 @@ def expert_ffn(h_f16: np.ndarray, expert, group: int) -> np.ndarray:
     rc = lib.moe_oracle_expert_ffn(H, F, group, *[a.ctypes.data for a in keep], y.ctypes.data)
     if rc != 0:
         raise ValueError("moe_oracle_expert_ffn rejected its arguments")
+    return y
+
+
+def _expert_ffn_meta8(lib, h_f16: np.ndarray, expert, group: int) -> np.ndarray:
+    """Two-level experts [(codes, scale codes, zero codes, meta)]: the second level is evaluated by the numpy
+    oracle's definition (a few numbers per row), the loops over the weights run in C."""
+    from . import moe_oracle as O
+    F, H = expert[0][0].shape
+    keep = [_p(h_f16, np.float16)]
+    for q, qs, qz, meta in expert:
+        s, z = O.meta8_scale_zero(qs, qz, meta)
+        keep += [_p(q, np.uint8), _p(s, np.float64), _p(z, np.float64)]
+    y = np.empty(H, dtype=np.float64)
+    rc = lib.moe_oracle_expert_ffn_f64meta(H, F, group, *[a.ctypes.data for a in keep], y.ctypes.data)
+    if rc != 0:
+        raise ValueError("moe_oracle_expert_ffn_f64meta rejected its arguments")
     return y

@@ -86,6 +86,50 @@ int moe_oracle_expert_ffn(int H, int F, int g, const uint16_t *h_f16,
     return 0;
 }
 
+/* The same loops for experts whose per-group scale and zero are given as fp64 values (two-level formats:
+ * the caller evaluates the second level, a few numbers per row, by its own definition). */
+static void dequant_matvec_f64(int rows, int cols, int g, const uint8_t *q, const double *scale,
+                               const double *zero, const double *x, double *out)
+{
+    int groups = cols / g;
+#pragma omp parallel for schedule(static)
+    for (int r = 0; r < rows; ++r) {
+        const uint8_t *qr = q + (size_t)r * cols;
+        double acc = 0.0;
+        for (int c = 0; c < cols; ++c) {
+            size_t m = (size_t)r * groups + c / g;
+            acc += ((double)qr[c] - zero[m]) * scale[m] * x[c];
+        }
+        out[r] = acc;
+    }
+}
+
+int moe_oracle_expert_ffn_f64meta(int H, int F, int g, const uint16_t *h_f16,
+                                  const uint8_t *q1, const double *s1, const double *z1,
+                                  const uint8_t *q3, const double *s3, const double *z3,
+                                  const uint8_t *q2, const double *s2, const double *z2,
+                                  double *y_out)
+{
+    if (H <= 0 || F <= 0 || g <= 0 || H % g || F % g)
+        return -1;
+    double *h = malloc(sizeof(double) * H);
+    double *u = malloc(sizeof(double) * F);
+    double *v = malloc(sizeof(double) * F);
+    if (!h || !u || !v) {
+        free(h); free(u); free(v);
+        return -1;
+    }
+    for (int i = 0; i < H; ++i)
+        h[i] = half_bits_to_double(h_f16[i]);
+    dequant_matvec_f64(F, H, g, q1, s1, z1, h, u);
+    dequant_matvec_f64(F, H, g, q3, s3, z3, h, v);
+    for (int i = 0; i < F; ++i)
+        u[i] = u[i] / (1.0 + exp(-u[i])) * v[i];
+    dequant_matvec_f64(H, F, g, q2, s2, z2, u, y_out);
+    free(h); free(u); free(v);
+    return 0;
+}
+
 int moe_oracle_threads(void)
 {
 #ifdef _OPENMP

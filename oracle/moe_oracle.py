@@ -119,16 +119,48 @@ def dequantize(codes_u8: np.ndarray, scale_f16: np.ndarray, zero_f16: np.ndarray
     return (codes_u8.astype(np.float64) - z) * s
 
 
+def quantize_meta8(scale_f16: np.ndarray, zero_f16: np.ndarray, scale_group: int):
+    """Second level (Sec. 4.2, "scale group size"): per row, runs of `scale_group` consecutive groups (the
+    whole row if it has fewer) quantize their fp16 scales, and separately their fp16 zeros, to 8 bits with
+    the min/max rule of quantize_minmax.  Returns (scale codes u8, zero codes u8, meta f16 [out, runs, 4])
+    with meta[r, j] = (scale, zero) of the scale codes followed by (scale, zero) of the zero codes."""
+    r = min(scale_group, scale_f16.shape[1])
+    qs, ss, sz = quantize_minmax(scale_f16.astype(np.float32), 8, r)
+    qz, zs, zz = quantize_minmax(zero_f16.astype(np.float32), 8, r)
+    return qs, qz, np.stack([ss, sz, zs, zz], axis=2)
+
+
+def meta8_scale_zero(scale_u8: np.ndarray, zero_u8: np.ndarray, meta_f16: np.ndarray):
+    """The per-group scale and zero a two-level matrix stands for, fp64:
+    scale = (scale code - meta[..,1]) * meta[..,0], zero = (zero code - meta[..,3]) * meta[..,2]."""
+    r = scale_u8.shape[1] // meta_f16.shape[1]
+    m = np.repeat(meta_f16.astype(np.float64), r, axis=1)
+    return (scale_u8.astype(np.float64) - m[:, :, 1]) * m[:, :, 0], (zero_u8.astype(np.float64) - m[:, :, 3]) * m[:, :, 2]
+
+
+def dequantize_meta8(codes_u8: np.ndarray, scale_u8: np.ndarray, zero_u8: np.ndarray, meta_f16: np.ndarray,
+                     group: int) -> np.ndarray:
+    """W^[r,c] = (q[r,c] - zero[r, c//g]) * scale[r, c//g] with the two-level scale and zero, fp64."""
+    s, z = meta8_scale_zero(scale_u8, zero_u8, meta_f16)
+    return (codes_u8.astype(np.float64) - np.repeat(z, group, axis=1)) * np.repeat(s, group, axis=1)
+
+
+def dequantize_any(matrix, group: int) -> np.ndarray:
+    """(codes, scale f16, zero f16) or (codes, scale codes, zero codes, meta)."""
+    return dequantize(*matrix, group) if len(matrix) == 3 else dequantize_meta8(*matrix, group)
+
+
 def silu(u: np.ndarray) -> np.ndarray:
     return u / (1.0 + np.exp(-u))
 
 
 def expert_ffn(h_f16: np.ndarray, expert, group: int) -> np.ndarray:
-    """y_e = W2^ ( silu(W1^ h) * (W3^ h) ), fp64.  expert = [(codes, scale, zero)] for w1, w3, w2."""
+    """y_e = W2^ ( silu(W1^ h) * (W3^ h) ), fp64.  expert = [(codes, scale, zero)] for w1, w3, w2
+    (or the two-level form of dequantize_meta8)."""
     h = h_f16.astype(np.float64)
-    w1 = dequantize(*expert[0], group)
-    w3 = dequantize(*expert[1], group)
-    w2 = dequantize(*expert[2], group)
+    w1 = dequantize_any(expert[0], group)
+    w3 = dequantize_any(expert[1], group)
+    w2 = dequantize_any(expert[2], group)
     a = silu(w1 @ h) * (w3 @ h)
     return w2 @ a
 

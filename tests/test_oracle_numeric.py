@@ -213,6 +213,91 @@ def test_c_loops_equal_numpy_dense(bits, g, H, F):
         assert np.abs(a - b).max() <= 1e-12 * np.abs(a).max()
 
 
+# ------------------------------------------------------------------ second quantization level
+
+def test_two_level_quantizer_hand_worked_examples(golden_dir):
+    with open(os.path.join(golden_dir, "quantizer_two_level_worked_example.json")) as f:
+        cases = json.load(f)["cases"]
+    for c in cases:
+        s16, z16 = np.array(c["scale"], dtype=np.float16), np.array(c["zero"], dtype=np.float16)
+        qs, qz, meta = O.quantize_meta8(s16, z16, c["scale_group"])
+        assert qs.tolist() == c["scale_codes"] and qz.tolist() == c["zero_codes"]
+        assert meta.astype(np.float64).tolist() == c["meta"]
+        s, z = O.meta8_scale_zero(qs, qz, meta)
+        assert s.tolist() == c["scale_decoded"] and z.tolist() == c["zero_decoded"]
+
+
+def test_two_level_dequantize_against_exact_rational_definition():
+    """weight = (q - zero) * scale with scale = (scale code - m1) * m0 and zero = (zero code - m3) * m2, the four
+    m's shared by a run of consecutive groups of the row: exact rational arithmetic on a non-square matrix with
+    two runs per row and distinct metadata everywhere (a transposed or mis-indexed run shows)."""
+    rng = np.random.default_rng(14)
+    rows, g, groups, run = 3, 4, 6, 3
+    q = rng.integers(0, 16, size=(rows, groups * g)).astype(np.uint8)
+    qs = rng.integers(0, 256, size=(rows, groups)).astype(np.uint8)
+    qz = rng.integers(0, 256, size=(rows, groups)).astype(np.uint8)
+    meta = np.stack([rng.uniform(1e-5, 1e-4, (rows, 2)), rng.uniform(-40, 0, (rows, 2)),
+                     rng.uniform(0.01, 0.06, (rows, 2)), rng.uniform(-5, 5, (rows, 2))], axis=2).astype(np.float16)
+    w = O.dequantize_meta8(q, qs, qz, meta, g)
+    for r in range(rows):
+        for c in range(groups * g):
+            j, k = c // g, c // g // run
+            sc = (Fraction(int(qs[r, j])) - frac16(meta[r, k, 1])) * frac16(meta[r, k, 0])
+            ze = (Fraction(int(qz[r, j])) - frac16(meta[r, k, 3])) * frac16(meta[r, k, 2])
+            exact = (Fraction(int(q[r, c])) - ze) * sc
+            assert abs(Fraction(float(w[r, c])) - exact) <= abs(exact) * Fraction(1, 10**14) + Fraction(1, 10**30)
+
+
+def test_two_level_quantizer_codes_runs_and_roundtrip_bound():
+    """Codes use the whole 8-bit range per run (run minimum -> 0, maximum -> 255), rows shorter than the scale
+    group form one run, and a decoded scale is within half a step (plus the rounding of the run's fp16 pair)."""
+    rng = np.random.default_rng(15)
+    w = (rng.normal(size=(16, 8 * 64)) * 0.02).astype(np.float32)
+    q, s16, z16 = O.quantize_minmax(w, 4, 64)                       # 8 groups per row
+    for scale_group, runs in ((4, 2), (8, 1), (256, 1)):
+        qs, qz, meta = O.quantize_meta8(s16, z16, scale_group)
+        assert qs.dtype == np.uint8 and meta.shape == (16, runs, 4) and meta.dtype == np.float16
+        r = 8 // runs
+        for arr16, codes, j in ((s16, qs, 0), (z16, qz, 2)):
+            v = arr16.astype(np.float64).reshape(16, runs, r)
+            cg = codes.reshape(16, runs, r).astype(np.int64)
+            lo, hi = v.min(axis=2), v.max(axis=2)
+            step, zero = meta[:, :, j].astype(np.float64), meta[:, :, j + 1].astype(np.float64)
+            # run minimum -> code 0; the maximum reaches the top code up to the rounding of the run's fp16 pair
+            # (255 codes times a 2^-11 relative error of the step, plus the zero's own rounding)
+            assert (np.take_along_axis(cg, v.argmin(axis=2)[..., None], 2)[..., 0] <= 1).all()
+            assert (np.take_along_axis(cg, v.argmax(axis=2)[..., None], 2)[..., 0] >= 250).all()
+            # |v - v^| <= step/2 + 255 |step - step_exact| + step |zero - zero_exact|, as for the first level
+            step_exact = np.where(hi > lo, (hi - lo) / 255.0, 1.0)
+            bound = step / 2 + 255 * np.abs(step - step_exact) + step * np.abs(zero - (-lo / step)) + 1e-9
+            dec = (cg - zero[..., None]) * step[..., None]
+            assert (np.abs(dec - v) <= bound[..., None]).all()
+            assert np.abs(dec - v).mean() > 0.1 * (step / 2).mean()
+        s, z = O.meta8_scale_zero(qs, qz, meta)
+        assert np.array_equal(s.reshape(16, runs, r), (qs.reshape(16, runs, r) - meta[:, :, 1:2].astype(np.float64)) * meta[:, :, 0:1].astype(np.float64))
+    # the weights the two-level form stands for stay close to the one-level ones
+    qs, qz, meta = O.quantize_meta8(s16, z16, 256)
+    w1, w2 = O.dequantize(q, s16, z16, 64), O.dequantize_meta8(q, qs, qz, meta, 64)
+    assert np.abs(w1 - w2).max() < 0.02 * np.abs(w1).max()
+
+
+def test_two_level_c_loops_equal_numpy_dense():
+    rng = np.random.default_rng(16)
+    H, F, g = 256, 512, 64
+    ex = []
+    for r, c in ((F, H), (F, H), (H, F)):
+        w = (rng.normal(size=(r, c)) * 0.02).astype(np.float32)
+        q, s16, z16 = O.quantize_minmax(w, 4, g)
+        ex.append((q,) + O.quantize_meta8(s16, z16, 4))
+    for _ in range(3):
+        h = rng.normal(size=H).astype(np.float16)
+        a = O.expert_ffn(h, ex, g)
+        dense = O.dequantize_meta8(*ex[2], g) @ (O.silu(O.dequantize_meta8(*ex[0], g) @ h.astype(np.float64))
+                                                 * (O.dequantize_meta8(*ex[1], g) @ h.astype(np.float64)))
+        assert np.abs(a - dense).max() <= 1e-13 * np.abs(dense).max()
+        assert np.abs(a - c_ffn.expert_ffn(h, ex, g)).max() <= 1e-12 * np.abs(a).max()
+
+
 def test_c_oracle_rejects_ragged_groups():
     rng = np.random.default_rng(8)
     ex = rand_expert(rng, 8, 12, 4, 4)

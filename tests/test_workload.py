@@ -43,6 +43,18 @@ def test_generator_quantizer_matches_oracle_quantizer_bit_for_bit(bits, group):
     assert (z.numpy().view(np.uint16) == zo.view(np.uint16)).all()
 
 
+def test_generator_second_level_matches_oracle_bit_for_bit():
+    w = W.expert_matrix(0, 0, 2, W.generate.W2, 256, 512)           # w2: [256][512], 8 groups of 64 per row
+    q, s, z = W.quantize_minmax(w, 4, 64)
+    for scale_group in (4, 256):
+        qs, qz, meta = W.quantize_meta8(s, z, scale_group)
+        qso, qzo, metao = O.quantize_meta8(s.numpy(), z.numpy(), scale_group)
+        assert (qs.numpy() == qso).all() and (qz.numpy() == qzo).all()
+        assert (meta.numpy().view(np.uint16) == metao.view(np.uint16)).all()
+    ex = W.quantized_expert(0, 0, 1, 256, 512, 4, 64, scale_group=256)
+    assert len(ex) == 3 and all(len(m) == 4 for m in ex) and ex[0][3].shape == (512, 1, 4) and ex[2][3].shape == (256, 1, 4)
+
+
 def test_layer_formats():
     assert W.layer_formats(W.CONFIGS["mixtral_stack"]) == [(4, 64)] * 32
     f = W.layer_formats(W.CONFIGS["mixtral_stack_lowbit"])

@@ -15,6 +15,8 @@ from .generate import (  # noqa: F401
     expert_matrix_shape,
     expert_matrix,
     quantize_minmax,
+    quantize_meta8,
+    run_length,
     quantized_expert,
     hidden_iid,
     hidden_ar1,

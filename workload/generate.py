@@ -129,13 +129,36 @@ def quantize_minmax(w: torch.Tensor, bits: int, group: int):
     return q.to(torch.uint8).reshape(out_f, in_f), s16, z16
 
 
+def run_length(groups: int, scale_group: int) -> int:
+    """Groups per run of the second quantization level: scale_group, or the whole row if it has fewer groups."""
+    r = min(scale_group, groups)
+    assert groups % r == 0, (groups, scale_group)
+    return r
+
+
+def quantize_meta8(scale_f16: torch.Tensor, zero_f16: torch.Tensor, scale_group: int):
+    """Second quantization level (Sec. 4.2 "scale group size"): the fp16 scales, and separately the fp16 zeros,
+    of a row are themselves quantized to 8 bits with the same min/max rule, in runs of `scale_group`
+    consecutive groups of that row (the whole row if it has fewer), each run with an fp16 (scale, zero) of its own.
+
+    Returns (scale codes u8 [out, in/g], zero codes u8 [out, in/g], meta fp16 [out, runs, 4]) with
+    meta[r, j] = (scale of the scale codes, zero of the scale codes, scale of the zero codes, zero of the zero codes).
+    """
+    r = run_length(scale_f16.shape[1], scale_group)
+    qs, ss, sz = quantize_minmax(scale_f16.to(torch.float32), 8, r)
+    qz, zs, zz = quantize_minmax(zero_f16.to(torch.float32), 8, r)
+    return qs, qz, torch.stack([ss, sz, zs, zz], dim=2).contiguous()
+
+
 def quantized_expert(seed: int, layer: int, expert: int, hidden: int, ffn: int, bits: int, group: int,
-                     device="cpu"):
-    """[(codes, scale, zero)] for matrices w1, w3, w2 of one expert."""
+                     device="cpu", scale_group: int = 0):
+    """[(codes, scale, zero)] for matrices w1, w3, w2 of one expert; with scale_group > 0
+    [(codes, scale codes, zero codes, meta)] (see quantize_meta8)."""
     out = []
     for m in (W1, W3, W2):
         w = expert_matrix(seed, layer, expert, m, hidden, ffn, device)
-        out.append(quantize_minmax(w, bits, group))
+        q, s, z = quantize_minmax(w, bits, group)
+        out.append((q,) + quantize_meta8(s, z, scale_group) if scale_group else (q, s, z))
         del w
     return out
 
