@@ -100,6 +100,12 @@ typedef struct {
     float   rms_eps;          /* > 0: RMSNorm with this eps in front of the gate; 0: gate sees x */
     int32_t init_policy;      /* 0: cache starts empty; 1: experts 0..k-1 resident after loading */
     int32_t flags;            /* MOE_LAYER_*                                                     */
+    int32_t scale_group;      /* 0: one fp16 (scale, zero) pair per group.  R > 0 (a power of two, 4-bit codes
+                                 only): two-level metadata (Sec. 4.2 "scale group size") -- per group an 8-bit
+                                 scale code and an 8-bit zero code, per run of R consecutive groups of a row
+                                 (the whole row if it has fewer; else R must divide its group count) four fp16:
+                                 scale = (scale code - m[1]) * m[0], zero = (zero code - m[3]) * m[2]; the
+                                 weight is (code - zero) * scale as before.  4.25 bits per weight            */
 } moe_layer_config_t;
 
 typedef struct {
@@ -140,6 +146,8 @@ typedef struct {
 /* Bytes of one expert's contiguous blob (w1, w3, w2 codes and their fp16 scale/zero pairs) in the
  * library's private layout; 0 if the shape or format is unsupported.  Sec. 3.3: one buffer per expert. */
 uint64_t moe_expert_blob_bytes(int32_t hidden, int32_t ffn, int32_t bits, int32_t group);
+/* The same for two-level metadata (moe_layer_config_t.scale_group; 0 gives moe_expert_blob_bytes). */
+uint64_t moe_expert_blob_bytes_2level(int32_t hidden, int32_t ffn, int32_t bits, int32_t group, int32_t scale_group);
 /* Device arena bytes moe_ctx_create needs: b staging buffers plus activation scratch.  0 on bad config. */
 uint64_t moe_ctx_dev_bytes(const moe_ctx_config_t *cfg);
 /* Device bytes moe_layer_create needs: k buffers of the context's buffer size, the gate matrix, the gain. */
@@ -175,9 +183,19 @@ int32_t moe_layer_destroy(moe_layer_t *layer);
  * MOE_LAYER_SWAP they are packed in ordinary memory of the library's own and keep no host copy). */
 int32_t moe_layer_load_expert(moe_layer_t *layer, int32_t expert, int32_t matrix, const uint8_t *codes,
                               const uint16_t *scale_f16, const uint16_t *zero_f16);
-/* Read one weight back out of the packed host blob (checks the private layout without a GPU). */
+/* The same for a layer with two-level metadata (scale_group > 0).  scale_code, zero_code: one byte per group,
+ * [out][in/group]; run_meta: fp16 bits, [out][runs][4] with runs = max(1, (in/group) / scale_group), the four
+ * numbers of moe_layer_config_t.scale_group in that order.  All host memory, read during the call only. */
+int32_t moe_layer_load_expert_2level(moe_layer_t *layer, int32_t expert, int32_t matrix, const uint8_t *codes,
+                                     const uint8_t *scale_code, const uint8_t *zero_code, const uint16_t *run_meta_f16);
+/* Read one weight back out of the packed host blob (checks the private layout without a GPU).  With two-level
+ * metadata *scale_f16 and *zero_f16 receive the group's byte codes, and moe_layer_peek_run_meta the four fp16 of
+ * the run the column belongs to. */
 int32_t moe_layer_peek_weight(const moe_layer_t *layer, int32_t expert, int32_t matrix, int32_t row,
                               int32_t col, uint8_t *code, uint16_t *scale_f16, uint16_t *zero_f16);
+
+int32_t moe_layer_peek_run_meta(const moe_layer_t *layer, int32_t expert, int32_t matrix, int32_t row,
+                                int32_t col, uint16_t *run_meta_f16 /*[4]*/);
 
 /* ---- the decode step ------------------------------------------------------------------------ */
 

@@ -92,12 +92,16 @@ def route(w_gate_f32: np.ndarray, h_f16: np.ndarray, k: int = 2) -> Tuple[List[i
     return idx, w, z
 
 
-def quantize_minmax(w_f32: np.ndarray, bits: int, group: int):
+def quantize_minmax(w_f32: np.ndarray, bits: int, group: int, zero_limit: Optional[float] = None):
     """Reference asymmetric min/max quantizer (fp32 arithmetic, fp16 scale and zero).
 
     Per group along the last axis: scale = fp16((max-min)/(2^bits-1)), 1 if that is 0;
     zero = fp16(-min/scale) (real valued); code = clip(rint(w/scale + zero), 0, 2^bits-1)
-    with the rounded scale and zero.  Returns (codes u8 [out,in], scale f16 [out,in/g], zero f16)."""
+    with the rounded scale and zero.  Returns (codes u8 [out,in], scale f16 [out,in/g], zero f16).
+
+    zero_limit (second level only): a group whose values are so close together, relative to their size,
+    that |min/scale| would exceed it (and overflow fp16) is stored as a constant instead: scale = 1,
+    zero = fp16(-min), all codes 0."""
     out_f, in_f = w_f32.shape
     qmax = np.float32((1 << bits) - 1)
     wg = w_f32.astype(np.float32).reshape(out_f, in_f // group, group)
@@ -105,6 +109,8 @@ def quantize_minmax(w_f32: np.ndarray, bits: int, group: int):
     hi = wg.max(axis=2)
     s16 = ((hi - lo) / qmax).astype(np.float16)
     s16[s16 == 0] = np.float16(1.0)
+    if zero_limit is not None:
+        s16[np.abs(lo / s16.astype(np.float32)) > np.float32(zero_limit)] = np.float16(1.0)
     sf = s16.astype(np.float32)
     z16 = (-lo / sf).astype(np.float16)
     zf = z16.astype(np.float32)
@@ -119,14 +125,17 @@ def dequantize(codes_u8: np.ndarray, scale_f16: np.ndarray, zero_f16: np.ndarray
     return (codes_u8.astype(np.float64) - z) * s
 
 
+META8_ZERO_LIMIT = 60000.0   # largest |zero| a run's fp16 pair may carry (fp16 overflows at 65520)
+
+
 def quantize_meta8(scale_f16: np.ndarray, zero_f16: np.ndarray, scale_group: int):
     """Second level (Sec. 4.2, "scale group size"): per row, runs of `scale_group` consecutive groups (the
     whole row if it has fewer) quantize their fp16 scales, and separately their fp16 zeros, to 8 bits with
     the min/max rule of quantize_minmax.  Returns (scale codes u8, zero codes u8, meta f16 [out, runs, 4])
     with meta[r, j] = (scale, zero) of the scale codes followed by (scale, zero) of the zero codes."""
     r = min(scale_group, scale_f16.shape[1])
-    qs, ss, sz = quantize_minmax(scale_f16.astype(np.float32), 8, r)
-    qz, zs, zz = quantize_minmax(zero_f16.astype(np.float32), 8, r)
+    qs, ss, sz = quantize_minmax(scale_f16.astype(np.float32), 8, r, zero_limit=META8_ZERO_LIMIT)
+    qz, zs, zz = quantize_minmax(zero_f16.astype(np.float32), 8, r, zero_limit=META8_ZERO_LIMIT)
     return qs, qz, np.stack([ss, sz, zs, zz], axis=2)
 
 

@@ -21,9 +21,9 @@ MOE_LAYER_NO_CACHE = 1
 MOE_LAYER_SWAP = 2
 
 EXPORTS = [
-    "moe_expert_blob_bytes", "moe_ctx_dev_bytes", "moe_layer_dev_bytes", "moe_layer_host_bytes",
+    "moe_expert_blob_bytes", "moe_expert_blob_bytes_2level", "moe_ctx_dev_bytes", "moe_layer_dev_bytes", "moe_layer_host_bytes",
     "moe_ctx_create", "moe_ctx_destroy", "moe_layer_create", "moe_layer_destroy",
-    "moe_layer_load_expert", "moe_layer_peek_weight", "moe_layer_step", "moe_layer_prefetch",
+    "moe_layer_load_expert", "moe_layer_load_expert_2level", "moe_layer_peek_weight", "moe_layer_peek_run_meta", "moe_layer_step", "moe_layer_prefetch",
     "moe_stack_step", "moe_layer_resolve", "moe_layer_stats", "moe_layer_cache_state", "moe_layer_placement",
     "moe_layer_reset", "moe_ctx_read_y", "moe_ctx_profile_enable", "moe_ctx_profile_read", "moe_ctx_set_option", "moe_probe_bandwidth", "moe_layer_set_prefetch", "moe_layer_set_flags", "moe_last_error", "moe_last_hip_error",
 ]
@@ -38,7 +38,7 @@ class CtxConfig(C.Structure):
 class LayerConfig(C.Structure):
     _fields_ = [("hidden", C.c_int32), ("ffn", C.c_int32), ("n_experts", C.c_int32), ("top_k", C.c_int32),
                 ("bits", C.c_int32), ("group", C.c_int32), ("cache_slots", C.c_int32), ("prefetch_m", C.c_int32),
-                ("rms_eps", C.c_float), ("init_policy", C.c_int32), ("flags", C.c_int32)]
+                ("rms_eps", C.c_float), ("init_policy", C.c_int32), ("flags", C.c_int32), ("scale_group", C.c_int32)]
 
 
 class Access(C.Structure):
@@ -115,6 +115,10 @@ def lib() -> C.CDLL:
     vp, i32, u64 = C.c_void_p, C.c_int32, C.c_uint64
     L.moe_expert_blob_bytes.restype = u64
     L.moe_expert_blob_bytes.argtypes = [i32, i32, i32, i32]
+    L.moe_expert_blob_bytes_2level.restype = u64
+    L.moe_expert_blob_bytes_2level.argtypes = [i32, i32, i32, i32, i32]
+    L.moe_layer_load_expert_2level.argtypes = [vp, i32, i32, vp, vp, vp, vp]
+    L.moe_layer_peek_run_meta.argtypes = [vp, i32, i32, i32, i32, C.POINTER(C.c_uint16)]
     L.moe_ctx_dev_bytes.restype = u64
     L.moe_ctx_dev_bytes.argtypes = [C.POINTER(CtxConfig)]
     L.moe_layer_dev_bytes.restype = u64
@@ -162,7 +166,9 @@ def check(rc: int) -> None:
 # thin wrappers, same names as the C entry points
 # --------------------------------------------------------------------------------------------
 
-def moe_expert_blob_bytes(hidden: int, ffn: int, bits: int, group: int) -> int:
+def moe_expert_blob_bytes(hidden: int, ffn: int, bits: int, group: int, scale_group: int = 0) -> int:
+    if scale_group:
+        return int(lib().moe_expert_blob_bytes_2level(hidden, ffn, bits, group, scale_group))
     return int(lib().moe_expert_blob_bytes(hidden, ffn, bits, group))
 
 
@@ -201,6 +207,17 @@ def moe_layer_destroy(layer) -> None:
 
 def moe_layer_load_expert(layer, expert: int, matrix: int, codes: int, scale: int, zero: int) -> None:
     check(lib().moe_layer_load_expert(layer, expert, matrix, codes, scale, zero))
+
+
+def moe_layer_load_expert_2level(layer, expert: int, matrix: int, codes: int, scale_code: int, zero_code: int,
+                                 run_meta: int) -> None:
+    check(lib().moe_layer_load_expert_2level(layer, expert, matrix, codes, scale_code, zero_code, run_meta))
+
+
+def moe_layer_peek_run_meta(layer, expert: int, matrix: int, row: int, col: int):
+    m = (C.c_uint16 * 4)()
+    check(lib().moe_layer_peek_run_meta(layer, expert, matrix, row, col, m))
+    return tuple(m)
 
 
 def moe_layer_peek_weight(layer, expert: int, matrix: int, row: int, col: int):

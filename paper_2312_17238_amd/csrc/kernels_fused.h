@@ -33,7 +33,7 @@ struct FusedArgs {
     uint32_t *barrier;              // device flags, one per block: the epoch of the last launch the block arrived in
     uint32_t barrier_target;        // this launch's epoch (increases by one per launch)
     uint32_t *error_flag;           // host-visible: set if the barrier gave up
-    int32_t H, F, group;
+    int32_t H, F, group, scale_group;
     uint32_t stride13, meta13, stride2, meta2;
     uint64_t off_w2;
     int32_t rows_per_block;         // R
@@ -95,7 +95,7 @@ __device__ __forceinline__ void token_w2_phase(const FusedArgs &A, float *red, i
     const int c = cs * 64 + lane;
     const bool live2 = active && c < n_chunks2;
     const int cc = live2 ? c : 0;
-    const RowGeom geo2 = row_geom<BITS>(A.meta2, A.F, A.group);
+    const RowGeom geo2 = row_geom<BITS>(A.meta2, A.F, A.group, A.scale_group);
     const int R = A.rows_per_block;
     const int row0 = blockIdx.x * R;
     const int row_end = min(row0 + R, A.H);
@@ -152,7 +152,7 @@ __global__ __launch_bounds__(FUSED_WAVES *WAVE) void k_ffn_token(FusedArgs A)
     // ---------------- phase 1: a[e][r] = silu(W1_e h)[r] * (W3_e h)[r] ----------------
     {
         const int n_chunks = A.H / F::CODES;
-        const RowGeom geo = row_geom<BITS>(A.meta13, A.H, A.group);
+        const RowGeom geo = row_geom<BITS>(A.meta13, A.H, A.group, A.scale_group);
         int cidx[KCH];
         bool live[KCH];
 #pragma unroll

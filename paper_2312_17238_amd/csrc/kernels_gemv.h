@@ -30,6 +30,7 @@ struct FfnArgs {
     uint16_t *a;                    // [B*K][F] fp16 SwiGLU activations
     float *yacc;                    // [B][H] fp32 accumulators (cleared by the gate kernel)
     int32_t H, F, group;
+    int32_t scale_group;            // two-level metadata: groups per run of the second level (0: fp16 pairs)
     uint32_t stride13, meta13;      // w1/w3 row: stride and offset of the (scale, zero) pairs
     uint32_t stride2, meta2;        // w2 row
     uint64_t off_w2;
@@ -41,6 +42,8 @@ struct RowGeom {
     uint32_t meta_off;   // byte offset of the (scale, zero) pairs (4-bit, 3-bit)
     uint32_t b_off;      // byte offset of region B (3-bit)
     int32_t gshift;      // 4-bit: log2(group / 32)
+    uint32_t meta2_off;  // two-level metadata: byte offset of the per-run fp16 quads
+    int32_t run_shift;   // ... log2(groups per run); 31 when the row is one run
 };
 
 // sum over one 32-bit word of 4-bit fields (8 codes) times 8 activations, biases 1024 / 64 alternating
@@ -102,6 +105,35 @@ struct Fmt<4> {
         d = dot_word4(r.q.w, a.h + 12, d);
         const float s = live ? lo_half(r.m) : 0.f;
         return s * fmaf(-hi_half(r.m), a.hsum, d);
+    }
+};
+
+// 4-bit with two-level metadata (Sec. 4.2 "scale group size"): per group a (scale code, zero code) byte pair, per run
+// of groups an fp16 quad (scale step, scale zero, zero step, zero zero); scale = (code - zero) * step for both.
+// The codes and the activations are those of Fmt<4>; only where a chunk's scale and zero come from differs.
+template <>
+struct Fmt<48> {
+    static constexpr int CODES = 32;
+    struct Row { uint4 q; uint32_t m; uint2 quad; };
+    using Act = Fmt<4>::Act;
+    static __device__ __forceinline__ void load(Row &r, const uint8_t *row, const RowGeom &g, int c)
+    {
+        const int grp = c >> g.gshift;
+        r.q = ldw4(row, c);
+        r.m = *reinterpret_cast<const uint16_t *>(row + g.meta_off + 2 * grp);
+        r.quad = *reinterpret_cast<const uint2 *>(row + g.meta2_off + 8 * (grp >> g.run_shift));   // shared by the row's lanes: plain load
+    }
+    static __device__ __forceinline__ void load_act(Act &a, const uint16_t *vec, int c, bool live) { Fmt<4>::load_act(a, vec, c, live); }
+    static __device__ __forceinline__ float contrib(const Row &r, const Act &a, bool live)
+    {
+        float d = -a.bias_dot;
+        d = dot_word4(r.q.x, a.h + 0, d);
+        d = dot_word4(r.q.y, a.h + 4, d);
+        d = dot_word4(r.q.z, a.h + 8, d);
+        d = dot_word4(r.q.w, a.h + 12, d);
+        const float s = ((float)(r.m & 0xffu) - hi_half(r.quad.x)) * lo_half(r.quad.x);
+        const float z = ((float)(r.m >> 8) - hi_half(r.quad.y)) * lo_half(r.quad.y);
+        return (live ? s : 0.f) * fmaf(-z, a.hsum, d);
     }
 };
 
@@ -214,12 +246,15 @@ struct Fmt<3> {
 };
 
 template <int BITS>
-__device__ __forceinline__ RowGeom row_geom(uint32_t meta_off, int cols, int group)
+__device__ __forceinline__ RowGeom row_geom(uint32_t meta_off, int cols, int group, int scale_group)
 {
     RowGeom g;
     g.meta_off = meta_off;
     g.b_off = BITS == 3 ? (uint32_t)(cols / 64) * 16u : 0u;
     g.gshift = (group == 32) ? 0 : (group == 64 ? 1 : 2);
+    const int groups = cols / group;
+    g.meta2_off = (meta_off + 2u * groups + 7u) & ~7u;
+    g.run_shift = (scale_group <= 0 || groups <= scale_group) ? 31 : __builtin_ctz((unsigned)scale_group);
     return g;
 }
 
@@ -238,7 +273,7 @@ __global__ __launch_bounds__(W13_WAVES *WAVE) void k_w13(FfnArgs A)
     const int lane = threadIdx.x & 63;
     const int wave = uniform(blockIdx.x * W13_WAVES + (threadIdx.x >> 6)), n_waves = gridDim.x * W13_WAVES;
     const int n_chunks = A.H / F::CODES;
-    const RowGeom geo = row_geom<BITS>(A.meta13, A.H, A.group);
+    const RowGeom geo = row_geom<BITS>(A.meta13, A.H, A.group, A.scale_group);
     const uint8_t *base = en.blob;
 
     int cidx[KCH];
@@ -312,7 +347,7 @@ __global__ __launch_bounds__(512) void k_w2(FfnArgs A)
     const int c = cs * 64 + lane;
     const bool live = c < n_chunks;
     const int cc = live ? c : 0;
-    const RowGeom geo = row_geom<BITS>(A.meta2, A.F, A.group);
+    const RowGeom geo = row_geom<BITS>(A.meta2, A.F, A.group, A.scale_group);
     const int R = A.rows_per_block;
     const int row0 = blockIdx.x * R;
     const int row_end = min(row0 + R, A.H);

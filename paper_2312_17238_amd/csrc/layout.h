@@ -21,6 +21,11 @@
 // (3-bit value in each nibble), A_i = (T_2i & 0x33333333) | (T_2i+1 & 0x33333333) << 2 holds the low two
 // bits of two such words and B_i = sum_j ((T_4i+j >> 2) & 0x11111111) << j the third bits of four, so a
 // decoder rebuilds T_j with three bit operations and reuses the 4-bit arithmetic.  3.0 bits per weight.
+//
+// Two-level metadata (4-bit only, Sec. 4.2 "scale group size"): the row's codes are followed by one
+// (scale code, zero code) byte pair per group, then, 8-byte aligned, one fp16 quad per run of scale_group
+// consecutive groups (the whole row if it has fewer): (step of the scale codes, zero of the scale codes,
+// step of the zero codes, zero of the zero codes).  4.25 bits per weight plus 8 bytes per run.
 #pragma once
 #include <cstdint>
 #include <cstring>
@@ -32,10 +37,12 @@ struct MatLayout {
     uint32_t code_bytes = 0;   // packed codes per row
     uint32_t meta_off = 0;     // byte offset of the (scale, zero) pairs inside a row (4/3-bit)
     uint32_t row_stride = 0;   // bytes from one row of this matrix to the next row of the same matrix's stream
+    uint32_t meta2_off = 0;    // two-level metadata: byte offset of the per-run fp16 quads
+    uint32_t run_len = 0;      // ... groups per run (0: one-level metadata)
 };
 
 struct BlobLayout {
-    int32_t hidden = 0, ffn = 0, bits = 0, group = 0;
+    int32_t hidden = 0, ffn = 0, bits = 0, group = 0, scale_group = 0;
     MatLayout m13;             // w1 and w3 rows: [F][H]; interleaved, so consecutive rows of w1 are 2*row_stride apart
     MatLayout m2;              // w2 rows: [H][F]
     uint64_t off_w13 = 0, off_w2 = 0, total = 0;
@@ -44,13 +51,19 @@ struct BlobLayout {
 
 inline uint32_t align_up(uint32_t v, uint32_t a) { return (v + a - 1) / a * a; }
 
-inline MatLayout mat_layout(uint32_t rows, uint32_t cols, int bits, int group)
+inline MatLayout mat_layout(uint32_t rows, uint32_t cols, int bits, int group, int scale_group = 0)
 {
     MatLayout m;
     m.rows = rows;
     m.cols = cols;
     uint32_t groups = cols / group;
-    if (bits == 2) {                       // interleaved: 8 bytes per group of 16
+    if (scale_group > 0) {                 // 4-bit codes, byte pairs, per-run quads
+        m.code_bytes = cols / 2;
+        m.meta_off = m.code_bytes;
+        m.run_len = groups < (uint32_t)scale_group ? groups : (uint32_t)scale_group;
+        m.meta2_off = align_up(m.meta_off + groups * 2, 8);
+        m.row_stride = align_up(m.meta2_off + groups / m.run_len * 8, 16);
+    } else if (bits == 2) {                       // interleaved: 8 bytes per group of 16
         m.code_bytes = groups * 8;
         m.meta_off = 0;
         m.row_stride = align_up(m.code_bytes, 16);
@@ -74,14 +87,24 @@ inline bool format_supported(int bits, int group)
     return false;
 }
 
-inline BlobLayout blob_layout(int32_t hidden, int32_t ffn, int32_t bits, int32_t group)
+// scale_group: 0, or a power of two with 4-bit codes; a row's groups must then split into whole runs
+inline bool scale_group_supported(int bits, int group, int scale_group, int cols)
+{
+    if (scale_group == 0) return true;
+    if (bits != 4 || scale_group < 1 || (scale_group & (scale_group - 1))) return false;
+    const int groups = cols / group;
+    return groups <= scale_group || groups % scale_group == 0;
+}
+
+inline BlobLayout blob_layout(int32_t hidden, int32_t ffn, int32_t bits, int32_t group, int32_t scale_group = 0)
 {
     BlobLayout b;
-    b.hidden = hidden; b.ffn = ffn; b.bits = bits; b.group = group;
+    b.hidden = hidden; b.ffn = ffn; b.bits = bits; b.group = group; b.scale_group = scale_group;
     if (hidden <= 0 || ffn <= 0 || hidden % 64 || ffn % 64 || !format_supported(bits, group)) return b;
     if (hidden % group || ffn % group) return b;
-    b.m13 = mat_layout(ffn, hidden, bits, group);
-    b.m2 = mat_layout(hidden, ffn, bits, group);
+    if (!scale_group_supported(bits, group, scale_group, hidden) || !scale_group_supported(bits, group, scale_group, ffn)) return b;
+    b.m13 = mat_layout(ffn, hidden, bits, group, scale_group);
+    b.m2 = mat_layout(hidden, ffn, bits, group, scale_group);
     b.off_w13 = 0;
     b.off_w2 = (uint64_t)2 * ffn * b.m13.row_stride;
     b.total = b.off_w2 + (uint64_t)hidden * b.m2.row_stride;
@@ -145,6 +168,35 @@ inline void pack_row(const BlobLayout &b, const MatLayout &m, const uint8_t *cod
     }
     uint32_t *meta = reinterpret_cast<uint32_t *>(dst + m.meta_off);
     for (uint32_t g = 0; g < groups; ++g) meta[g] = (uint32_t)scale[g] | (uint32_t)zero[g] << 16;
+}
+
+// two-level metadata: codes as in the 4-bit layout, then the byte pairs, then the per-run quads
+inline void pack_row_meta8(const BlobLayout &b, const MatLayout &m, const uint8_t *codes, const uint8_t *scale_code,
+                           const uint8_t *zero_code, const uint16_t *run_meta, uint8_t *dst)
+{
+    const uint32_t cols = m.cols, groups = cols / b.group;
+    uint32_t *w = reinterpret_cast<uint32_t *>(dst);
+    for (uint32_t i = 0; i < cols / 8; ++i) {
+        const uint8_t *c = codes + 8 * i;
+        uint32_t v = 0;
+        for (int n = 0; n < 4; ++n)
+            v |= (uint32_t)(c[2 * n] & 15) << (4 * n) | (uint32_t)(c[2 * n + 1] & 15) << (16 + 4 * n);
+        w[i] = v;
+    }
+    uint8_t *pairs = dst + m.meta_off;
+    for (uint32_t g = 0; g < groups; ++g) { pairs[2 * g] = scale_code[g]; pairs[2 * g + 1] = zero_code[g]; }
+    memset(pairs + 2 * groups, 0, m.meta2_off - (m.meta_off + 2 * groups));
+    memcpy(dst + m.meta2_off, run_meta, (size_t)groups / m.run_len * 8);
+}
+
+inline void peek_row_meta8(const BlobLayout &b, const MatLayout &m, const uint8_t *src, uint32_t col, uint8_t *code,
+                           uint8_t *scale_code, uint8_t *zero_code, uint16_t run_meta[4])
+{
+    const uint32_t v = reinterpret_cast<const uint32_t *>(src)[col / 8], i = col % 8, g = col / b.group;
+    *code = (v >> (4 * (i / 2) + 16 * (i & 1))) & 15;
+    *scale_code = src[m.meta_off + 2 * g];
+    *zero_code = src[m.meta_off + 2 * g + 1];
+    memcpy(run_meta, src + m.meta2_off + (size_t)(g / m.run_len) * 8, 8);
 }
 
 inline void peek_row(const BlobLayout &b, const MatLayout &m, const uint8_t *src, uint32_t col, uint8_t *code,

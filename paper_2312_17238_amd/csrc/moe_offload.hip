@@ -159,7 +159,7 @@ static bool layer_cfg_ok(const moe_layer_config_t *c)
            c->prefetch_m >= 0 && c->prefetch_m <= MOE_MAX_GUESS && c->rms_eps >= 0.f &&
            (c->init_policy == 0 || c->init_policy == 1) && (c->flags & ~(MOE_LAYER_NO_CACHE | MOE_LAYER_SWAP)) == 0 &&
            (!(c->flags & MOE_LAYER_SWAP) || (c->init_policy == 1 && !(c->flags & MOE_LAYER_NO_CACHE))) &&
-           blob_layout(c->hidden, c->ffn, c->bits, c->group).ok;
+           c->scale_group >= 0 && blob_layout(c->hidden, c->ffn, c->bits, c->group, c->scale_group).ok;
 }
 
 struct ScratchPlan { uint64_t staging, h, a, yacc, x0, x1, barrier, gs_h, gs_a, total; };
@@ -192,6 +192,12 @@ extern "C" uint64_t moe_expert_blob_bytes(int32_t hidden, int32_t ffn, int32_t b
     return b.ok ? b.total : 0;
 }
 
+extern "C" uint64_t moe_expert_blob_bytes_2level(int32_t hidden, int32_t ffn, int32_t bits, int32_t group, int32_t scale_group)
+{
+    BlobLayout b = blob_layout(hidden, ffn, bits, group, scale_group < 0 ? -1 : scale_group);
+    return (scale_group >= 0 && b.ok) ? b.total : 0;
+}
+
 extern "C" uint64_t moe_ctx_dev_bytes(const moe_ctx_config_t *cfg)
 {
     if (!ctx_cfg_ok(cfg)) return 0;
@@ -208,7 +214,7 @@ extern "C" uint64_t moe_layer_dev_bytes(const moe_ctx_t *ctx, const moe_layer_co
 extern "C" uint64_t moe_layer_host_bytes(const moe_layer_config_t *cfg)
 {
     if (!layer_cfg_ok(cfg)) return 0;
-    return blob_layout(cfg->hidden, cfg->ffn, cfg->bits, cfg->group).total * (uint64_t)n_host_bufs(*cfg);
+    return blob_layout(cfg->hidden, cfg->ffn, cfg->bits, cfg->group, cfg->scale_group).total * (uint64_t)n_host_bufs(*cfg);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -337,7 +343,7 @@ extern "C" int32_t moe_layer_create(moe_ctx_t *ctx, const moe_layer_config_t *cf
     if (!ctx) return fail(MOE_EINVAL, "moe_layer_create: ctx is null");
     if (!layer_cfg_ok(cfg)) return fail(MOE_EINVAL, "moe_layer_create: bad or unsupported configuration");
     if (!gate_w_host || !pinned_host_mem) return fail(MOE_EINVAL, "moe_layer_create: null gate or host arena");
-    BlobLayout lay = blob_layout(cfg->hidden, cfg->ffn, cfg->bits, cfg->group);
+    BlobLayout lay = blob_layout(cfg->hidden, cfg->ffn, cfg->bits, cfg->group, cfg->scale_group);
     if (lay.total > ctx->buf_bytes) return fail(MOE_EINVAL, "moe_layer_create: expert blob (%llu B) exceeds the context's buffer size (%llu B)", (unsigned long long)lay.total, (unsigned long long)ctx->buf_bytes);
     if (cfg->hidden > ctx->cfg.max_hidden || cfg->ffn > ctx->cfg.max_ffn || cfg->top_k > ctx->cfg.max_top_k)
         return fail(MOE_EINVAL, "moe_layer_create: layer exceeds the context's maxima");
@@ -439,10 +445,10 @@ static int32_t warm_fill(moe_layer *l, int32_t e)
     return MOE_OK;
 }
 
-extern "C" int32_t moe_layer_load_expert(moe_layer_t *l, int32_t expert, int32_t matrix, const uint8_t *codes,
-                                         const uint16_t *scale, const uint16_t *zero)
+// Common part of the two load entry points: checks, threading over rows, bookkeeping.  pack(r, dst) packs row r.
+template <typename PackRow>
+static int32_t load_matrix(moe_layer *l, int32_t expert, int32_t matrix, const uint8_t *codes, PackRow pack)
 {
-    if (!l || !codes || !scale || !zero) return fail(MOE_EINVAL, "moe_layer_load_expert: null argument");
     if (expert < 0 || expert >= l->cfg.n_experts || matrix < 0 || matrix > 2)
         return fail(MOE_EINVAL, "moe_layer_load_expert: expert %d / matrix %d out of range", expert, matrix);
     const BlobLayout &b = l->lay;
@@ -454,7 +460,6 @@ extern "C" int32_t moe_layer_load_expert(moe_layer_t *l, int32_t expert, int32_t
         }
     }
     uint8_t *blob = host_blob(l, expert);
-    const uint32_t groups = m.cols / b.group;
     const uint32_t qmax = (1u << b.bits) - 1;
     const unsigned hw = std::max(1u, std::min(16u, std::thread::hardware_concurrency()));
     const unsigned nthreads = (uint64_t)m.rows * m.cols < (1u << 20) ? 1 : hw;
@@ -465,7 +470,7 @@ extern "C" int32_t moe_layer_load_expert(moe_layer_t *l, int32_t expert, int32_t
             uint32_t mx = 0;
             for (uint32_t i = 0; i < m.cols; ++i) mx |= cr[i];
             if (mx > qmax) { bad.store(1); return; }
-            pack_row(b, m, cr, scale + (uint64_t)r * groups, zero + (uint64_t)r * groups, blob + row_offset(b, matrix, r));
+            pack(r, blob + row_offset(b, matrix, r));
         }
     };
     if (nthreads == 1) {
@@ -485,6 +490,35 @@ extern "C" int32_t moe_layer_load_expert(moe_layer_t *l, int32_t expert, int32_t
     return MOE_OK;
 }
 
+extern "C" int32_t moe_layer_load_expert(moe_layer_t *l, int32_t expert, int32_t matrix, const uint8_t *codes,
+                                         const uint16_t *scale, const uint16_t *zero)
+{
+    if (!l || !codes || !scale || !zero) return fail(MOE_EINVAL, "moe_layer_load_expert: null argument");
+    if (l->lay.scale_group) return fail(MOE_ESTATE, "moe_layer_load_expert: the layer has two-level metadata; use moe_layer_load_expert_2level");
+    if (matrix < 0 || matrix > 2) return fail(MOE_EINVAL, "moe_layer_load_expert: matrix %d out of range", matrix);
+    const BlobLayout &b = l->lay;
+    const MatLayout &m = mat_of(b, matrix);
+    const uint32_t groups = m.cols / b.group;
+    return load_matrix(l, expert, matrix, codes, [&](uint32_t r, uint8_t *dst) {
+        pack_row(b, m, codes + (uint64_t)r * m.cols, scale + (uint64_t)r * groups, zero + (uint64_t)r * groups, dst);
+    });
+}
+
+extern "C" int32_t moe_layer_load_expert_2level(moe_layer_t *l, int32_t expert, int32_t matrix, const uint8_t *codes,
+                                                const uint8_t *scale_code, const uint8_t *zero_code, const uint16_t *run_meta)
+{
+    if (!l || !codes || !scale_code || !zero_code || !run_meta) return fail(MOE_EINVAL, "moe_layer_load_expert_2level: null argument");
+    if (!l->lay.scale_group) return fail(MOE_ESTATE, "moe_layer_load_expert_2level: the layer has one-level metadata; use moe_layer_load_expert");
+    if (matrix < 0 || matrix > 2) return fail(MOE_EINVAL, "moe_layer_load_expert_2level: matrix %d out of range", matrix);
+    const BlobLayout &b = l->lay;
+    const MatLayout &m = mat_of(b, matrix);
+    const uint32_t groups = m.cols / b.group, runs = groups / m.run_len;
+    return load_matrix(l, expert, matrix, codes, [&](uint32_t r, uint8_t *dst) {
+        pack_row_meta8(b, m, codes + (uint64_t)r * m.cols, scale_code + (uint64_t)r * groups, zero_code + (uint64_t)r * groups,
+                       run_meta + (uint64_t)r * runs * 4, dst);
+    });
+}
+
 extern "C" int32_t moe_layer_peek_weight(const moe_layer_t *l, int32_t expert, int32_t matrix, int32_t row, int32_t col,
                                          uint8_t *code, uint16_t *scale, uint16_t *zero)
 {
@@ -497,7 +531,32 @@ extern "C" int32_t moe_layer_peek_weight(const moe_layer_t *l, int32_t expert, i
     if (!(l->loaded[expert] & (1u << matrix))) return fail(MOE_ESTATE, "moe_layer_peek_weight: matrix not loaded");
     const uint8_t *blob = host_blob(const_cast<moe_layer *>(l), expert);
     if (!blob) return fail(MOE_ESTATE, "moe_layer_peek_weight: expert %d is on the device only (swap mode)", expert);
+    if (l->lay.scale_group) {               // two-level metadata: the byte codes, widened
+        uint8_t sc = 0, zc = 0;
+        uint16_t quad[4];
+        peek_row_meta8(l->lay, m, blob + row_offset(l->lay, matrix, row), col, code, &sc, &zc, quad);
+        *scale = sc; *zero = zc;
+        return MOE_OK;
+    }
     peek_row(l->lay, m, blob + row_offset(l->lay, matrix, row), col, code, scale, zero);
+    return MOE_OK;
+}
+
+extern "C" int32_t moe_layer_peek_run_meta(const moe_layer_t *l, int32_t expert, int32_t matrix, int32_t row, int32_t col,
+                                           uint16_t *run_meta)
+{
+    if (!l || !run_meta) return fail(MOE_EINVAL, "moe_layer_peek_run_meta: null argument");
+    if (!l->lay.scale_group) return fail(MOE_ESTATE, "moe_layer_peek_run_meta: the layer has one-level metadata");
+    if (expert < 0 || expert >= l->cfg.n_experts || matrix < 0 || matrix > 2)
+        return fail(MOE_EINVAL, "moe_layer_peek_run_meta: expert or matrix out of range");
+    const MatLayout &m = mat_of(l->lay, matrix);
+    if (row < 0 || (uint32_t)row >= m.rows || col < 0 || (uint32_t)col >= m.cols)
+        return fail(MOE_EINVAL, "moe_layer_peek_run_meta: row or column out of range");
+    if (!(l->loaded[expert] & (1u << matrix))) return fail(MOE_ESTATE, "moe_layer_peek_run_meta: matrix not loaded");
+    const uint8_t *blob = host_blob(const_cast<moe_layer *>(l), expert);
+    if (!blob) return fail(MOE_ESTATE, "moe_layer_peek_run_meta: expert %d is on the device only (swap mode)", expert);
+    uint8_t c, sc, zc;
+    peek_row_meta8(l->lay, m, blob + row_offset(l->lay, matrix, row), col, &c, &sc, &zc, run_meta);
     return MOE_OK;
 }
 
@@ -851,7 +910,7 @@ static int32_t launch_gate(moe_ctx *c, GateArgs ga, int32_t batch)
 #endif
 
 // Activation registers per (chunk, token) of each format: the budget that limits tokens per entry.
-template <int BITS> constexpr int act_regs() { return BITS == 3 ? 34 : (BITS == 2 ? 20 : 18); }
+template <int BITS> constexpr int act_regs() { return BITS == 3 ? 34 : (BITS == 2 ? 20 : 18); }   // (48: 4-bit codes, two-level metadata)
 constexpr int ACT_REG_BUDGET = 160;
 
 static int chunks_per_lane(int cols, int bits)      // 64-lane passes over one row (1, 2 or 4; 0 = too wide)
@@ -898,7 +957,7 @@ static int32_t launch_ffn_fmt(moe_layer *l, const std::vector<FfnEntry> &entries
         FfnArgs A{};
         for (int i = 0; i < n; ++i) A.e[i] = entries[first + i];
         A.h = c->h_buf; A.a = c->a_buf; A.yacc = c->yacc;
-        A.H = b.hidden; A.F = b.ffn; A.group = b.group;
+        A.H = b.hidden; A.F = b.ffn; A.group = b.group; A.scale_group = b.scale_group;
         A.stride13 = b.m13.row_stride; A.meta13 = b.m13.meta_off;
         A.stride2 = b.m2.row_stride; A.meta2 = b.m2.meta_off;
         A.off_w2 = b.off_w2;
@@ -967,6 +1026,7 @@ static int32_t launch_token_fmt(moe_layer *l, const FusedArgs &A0, bool one_laun
 
 static int32_t launch_token(moe_layer *l, const FusedArgs &A, bool one_launch, bool probe_only, bool *done)
 {
+    if (l->lay.scale_group) return launch_token_fmt<48>(l, A, one_launch, probe_only, done);
     switch (l->lay.bits) {
     case 4: return launch_token_fmt<4>(l, A, one_launch, probe_only, done);
     case 3: return launch_token_fmt<3>(l, A, one_launch, probe_only, done);
@@ -1105,6 +1165,7 @@ static int32_t launch_mfma(moe_layer *l, const std::vector<PassExpert> &experts,
 
 static int32_t launch_ffn(moe_layer *l, const std::vector<FfnEntry> &entries, int nt, bool w13_only = false)
 {
+    if (l->lay.scale_group) return launch_ffn_fmt<48>(l, entries, nt, w13_only);
     switch (l->lay.bits) {
     case 4: return launch_ffn_fmt<4>(l, entries, nt, w13_only);
     case 3: return launch_ffn_fmt<3>(l, entries, nt, w13_only);
@@ -1175,7 +1236,7 @@ extern "C" int32_t moe_layer_step(moe_layer_t *l, moe_layer_t *next, const uint1
     const bool try_fused = c->token_path && batch == 1 && passes.size() == 1 && plan.access.size() <= 2 &&
                            (int)plan.access.size() == cf.top_k && !plan.victim_needed;
     bool fused_done = false;
-    const bool use_mfma = batch >= c->mfma_min_batch && cf.bits == 4 && cf.group == 64 && cf.hidden % MF_KC == 0 &&
+    const bool use_mfma = batch >= c->mfma_min_batch && cf.bits == 4 && cf.group == 64 && cf.scale_group == 0 && cf.hidden % MF_KC == 0 &&
                           cf.ffn % MF_KC == 0 && batch * cf.top_k <= MF_MAX_PAIRS;
     for (size_t p = 0; p < passes.size(); ++p) {
         if (p > 0) {
@@ -1220,7 +1281,7 @@ extern "C" int32_t moe_layer_step(moe_layer_t *l, moe_layer_t *next, const uint1
             fa.n_exp = (int32_t)entries.size();
             for (int i = 0; i < fa.n_exp; ++i) { fa.blob[i] = entries[i].blob; fa.w[i] = entries[i].w[0]; fa.a_row[i] = entries[i].pair[0]; }
             fa.h = c->h_buf; fa.x = x_in; fa.x_out = x_out; fa.a = c->a_buf; fa.y = c->yacc;
-            fa.H = l->lay.hidden; fa.F = l->lay.ffn; fa.group = l->lay.group;
+            fa.H = l->lay.hidden; fa.F = l->lay.ffn; fa.group = l->lay.group; fa.scale_group = l->lay.scale_group;
             fa.stride13 = l->lay.m13.row_stride; fa.meta13 = l->lay.m13.meta_off;
             fa.stride2 = l->lay.m2.row_stride; fa.meta2 = l->lay.m2.meta_off; fa.off_w2 = l->lay.off_w2;
             if (c->fused) {

@@ -12,9 +12,9 @@ from . import binding as B
 
 
 def layer_config(hidden, ffn, n_experts=8, top_k=2, bits=4, group=64, cache_slots=2, prefetch_m=0,
-                 rms_eps=0.0, init_policy=0, flags=0) -> B.LayerConfig:
+                 rms_eps=0.0, init_policy=0, flags=0, scale_group=0) -> B.LayerConfig:
     return B.LayerConfig(hidden, ffn, n_experts, top_k, bits, group, cache_slots, prefetch_m, rms_eps,
-                         init_policy, flags)
+                         init_policy, flags, scale_group)
 
 
 class Stack:
@@ -28,7 +28,7 @@ class Stack:
         self.host_only = host_only
         self.device = torch.device(device) if not host_only else torch.device("cpu")
         self.max_batch = max_batch
-        blob = [B.moe_expert_blob_bytes(c.hidden, c.ffn, c.bits, c.group) for c in self.cfgs]
+        blob = [B.moe_expert_blob_bytes(c.hidden, c.ffn, c.bits, c.group, c.scale_group) for c in self.cfgs]
         if min(blob) == 0:
             raise B.MoeError(B.MOE_EINVAL, "unsupported shape or format")
         self.blob_bytes = blob
@@ -82,12 +82,20 @@ class Stack:
         return view
 
     def load_expert(self, layer: int, expert: int, matrix: int, codes: torch.Tensor, scale: torch.Tensor,
-                    zero: torch.Tensor) -> None:
+                    zero: torch.Tensor, run_meta: Optional[torch.Tensor] = None) -> None:
+        """One-level metadata: scale, zero fp16 per group.  Two-level (run_meta given): scale, zero are the byte
+        codes per group and run_meta the fp16 quads [out][runs][4]."""
         c = self._host(codes, "c")
         s = self._host(scale, "s")
         z = self._host(zero, "z")
-        assert c.dtype == torch.uint8 and s.dtype == torch.float16 and z.dtype == torch.float16
-        B.moe_layer_load_expert(self.layers[layer], expert, matrix, c.data_ptr(), s.data_ptr(), z.data_ptr())
+        if run_meta is None:
+            assert c.dtype == torch.uint8 and s.dtype == torch.float16 and z.dtype == torch.float16
+            B.moe_layer_load_expert(self.layers[layer], expert, matrix, c.data_ptr(), s.data_ptr(), z.data_ptr())
+        else:
+            m = self._host(run_meta, "m")
+            assert c.dtype == torch.uint8 and s.dtype == torch.uint8 and z.dtype == torch.uint8 and m.dtype == torch.float16
+            B.moe_layer_load_expert_2level(self.layers[layer], expert, matrix, c.data_ptr(), s.data_ptr(), z.data_ptr(),
+                                           m.data_ptr())
 
     # -- stepping ----------------------------------------------------------------------------
     def step_layer(self, layer: int, x_in: torch.Tensor, x_out: torch.Tensor, h_out: Optional[torch.Tensor] = None,

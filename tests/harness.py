@@ -17,7 +17,7 @@ TOL_REL_RMS = 1e-3
 
 
 def to_np_expert(mats):
-    return [(q.cpu().numpy(), s.cpu().numpy(), z.cpu().numpy()) for q, s, z in mats]
+    return [tuple(t.cpu().numpy() for t in m) for m in mats]
 
 
 class Model:
@@ -25,24 +25,25 @@ class Model:
 
     def __init__(self, L, H, F, E=8, K=2, formats: Optional[Sequence[Tuple[int, int]]] = None, k=2, m=0,
                  rms_eps=0.0, b=4, max_batch=1, seed=0, device="cuda:0", keep_layers: Optional[Sequence[int]] = None,
-                 init_policy=0, flags=0):
+                 init_policy=0, flags=0, scale_group=0):
         self.L, self.H, self.F, self.E, self.K, self.k, self.m, self.eps = L, H, F, E, K, k, m, rms_eps
         self.formats = list(formats) if formats else [(4, 64)] * L
+        self.scale_group = scale_group      # > 0: two-level metadata (8-bit scale and zero codes, fp16 quads per run)
         self.seed = seed
         self.device = device
         self.gate = [W.gate_weight(seed, l, E, H) for l in range(L)]
         self.gamma = [W.rms_gamma(H) for _ in range(L)] if rms_eps > 0 else None
-        cfgs = [layer_config(H, F, E, K, self.formats[l][0], self.formats[l][1], k, m, rms_eps, init_policy, flags)
-                for l in range(L)]
+        cfgs = [layer_config(H, F, E, K, self.formats[l][0], self.formats[l][1], k, m, rms_eps, init_policy, flags,
+                             scale_group) for l in range(L)]
         self.stack = Stack(cfgs, self.gate, self.gamma, n_staging=b, max_batch=max_batch, device=device)
         self.experts: Dict[Tuple[int, int], list] = {}
         keep = set(range(L)) if keep_layers is None else set(keep_layers)
         for l in range(L):
             bits, group = self.formats[l]
             for e in range(E):
-                mats = W.quantized_expert(seed, l, e, H, F, bits, group, device)
-                for mtx, (q, s, z) in enumerate(mats):
-                    self.stack.load_expert(l, e, mtx, q, s, z)
+                mats = W.quantized_expert(seed, l, e, H, F, bits, group, device, scale_group)
+                for mtx, m in enumerate(mats):
+                    self.stack.load_expert(l, e, mtx, *m)
                 if l in keep:
                     self.experts[(l, e)] = to_np_expert(mats)
                 del mats
@@ -51,7 +52,7 @@ class Model:
         """Unpacked (codes, scale, zero) of one expert; regenerated from its seed if not kept."""
         if (l, e) not in self.experts:
             bits, group = self.formats[l]
-            return to_np_expert(W.quantized_expert(self.seed, l, e, self.H, self.F, bits, group, self.device))
+            return to_np_expert(W.quantized_expert(self.seed, l, e, self.H, self.F, bits, group, self.device, self.scale_group))
         return self.experts[(l, e)]
 
     def gate_np(self, l):

@@ -498,3 +498,33 @@ def test_swap_eviction_mixtral_layer():
     assert st["bytes_d2h_writeback"] == st["misses"] * model.stack.blob_bytes[0] > 0
     say(f"  max abs {max(e[0] for e in errs):.2e} max rel-rms {max(e[1] for e in errs):.2e} write-backs {place[0].writebacks}")
     model.close()
+
+
+@pytest.mark.parametrize("R,Bn,k,m,variant", [(256, 1, 2, 2, "token"), (2, 1, 2, 2, "token"), (2, 1, 2, 1, "general"), (2, 1, 2, 2, "one_launch"),
+                                              (2, 4, 4, 2, "general"), (256, 16, 4, 2, "general"), (4, 3, 8, 0, "general")])
+def test_small_stack_two_level_metadata(R, Bn, k, m, variant):
+    """4-bit experts whose scales and zeros are themselves 8-bit codes (Sec. 4.2 "scale group size"): runs of R groups
+    per row (R=2 gives 2 and 4 runs per row here, R=256 one), through the single-token kernels, the general GEMV
+    kernels, the one-launch kernel and batches (which stay on the GEMV kernels: the matrix-core path takes fp16 pairs)."""
+    L, H, F = 3, 256, 512
+    say(f"two-level metadata R={R} B={Bn} k={k} m={m} {variant}")
+    model = Model(L, H, F, 8, 2, None, k, m, 1e-5, max_batch=Bn, seed=71, scale_group=R)
+    B.moe_ctx_set_option(model.stack.ctx, "token_path", 0 if variant == "general" else 1)
+    B.moe_ctx_set_option(model.stack.ctx, "fused", 1 if variant == "one_launch" else 0)
+    assert model.stack.blob_bytes[0] == B.moe_expert_blob_bytes(H, F, 4, 64, R)
+    xs = W.hidden_ar1(71, 10, Bn, H)
+    _, sim, errs = run_teacher_forced(model, xs, O.expert_ffn)
+    say(f"  max abs {max(e[0] for e in errs):.2e} max rel-rms {max(e[1] for e in errs):.2e}")
+    model.close()
+
+
+def test_mixtral_layer_two_level_metadata():
+    """One Mixtral-shaped layer with two-level metadata (scale group 256: one run per row), k=4, C oracle on every token."""
+    c = W.CONFIGS["mixtral_layer"]
+    say("mixtral layer, two-level metadata: build")
+    model = Model(1, c.hidden, c.ffn, c.n_experts, c.top_k, None, 4, 0, 0.0, seed=c.seed, scale_group=256)
+    assert model.stack.blob_bytes[0] == 94_109_696
+    xs = W.hidden_ar1(c.seed, 6, 1, c.hidden)
+    _, sim, errs = run_teacher_forced(model, xs, c_ffn.expert_ffn)
+    say(f"  max abs {max(e[0] for e in errs):.2e} max rel-rms {max(e[1] for e in errs):.2e}")
+    model.close()

@@ -188,6 +188,44 @@ def test_packed_blob_reads_back_every_code(bits, group):
     st.close()
 
 
+def test_two_level_blob_size_and_read_back():
+    """Two-level metadata (4-bit codes, one byte pair per group, one fp16 quad per run): 4.25 bits per weight plus the
+    quads; every code, byte pair and quad reads back from the packed blob, also with several runs per row."""
+    P = 3 * 4096 * 14336
+    rows_quads = (2 * 14336 + 4096) * 8                       # one run per row: 64 and 224 groups are below 256
+    w13_row, w2_row = 2048 + 128 + 8, 7168 + 448 + 8
+    assert B.moe_expert_blob_bytes(4096, 14336, 4, 64, 256) == 2 * 14336 * (-(-w13_row // 16) * 16) + 4096 * (-(-w2_row // 16) * 16) == 94_109_696
+    assert 94_109_696 - (P // 2 + P // 64 * 2 + rows_quads) == (2 * 14336 + 4096) * 8     # 16-byte row padding
+    assert B.moe_expert_blob_bytes(4096, 14336, 3, 64, 128) == 0 and B.moe_expert_blob_bytes(256, 512, 4, 64, 3) == 0
+    rng = np.random.default_rng(21)
+    H, F, E, R = 256, 512, 2, 2                               # 4 and 8 groups per row -> 2 and 4 runs
+    st = Stack([layer_config(H, F, E, 2, 4, 64, 2, scale_group=R)], [torch.zeros(E, H)], host_only=True)
+    lay = st.layers[0]
+    mats = {}
+    for e in range(E):
+        for mtx, (r, c) in enumerate(((F, H), (F, H), (H, F))):
+            q = rng.integers(0, 16, size=(r, c)).astype(np.uint8)
+            qs = rng.integers(0, 256, size=(r, c // 64)).astype(np.uint8)
+            qz = rng.integers(0, 256, size=(r, c // 64)).astype(np.uint8)
+            meta = rng.integers(0, 1 << 16, size=(r, c // 64 // R, 4)).astype(np.uint16)
+            mats[(e, mtx)] = (q, qs, qz, meta)
+            B.moe_layer_load_expert_2level(lay, e, mtx, q.ctypes.data, qs.ctypes.data, qz.ctypes.data, meta.ctypes.data)
+    for (e, mtx), (q, qs, qz, meta) in mats.items():
+        for r in [0, 1, q.shape[0] - 1] + [int(x) for x in rng.integers(0, q.shape[0], 3)]:
+            for c in range(q.shape[1]):
+                assert B.moe_layer_peek_weight(lay, e, mtx, r, c) == (q[r, c], qs[r, c // 64], qz[r, c // 64])
+                assert B.moe_layer_peek_run_meta(lay, e, mtx, r, c) == tuple(int(v) for v in meta[r, c // 64 // R])
+    assert B.moe_layer_host_bytes(st.cfgs[0]) == E * B.moe_expert_blob_bytes(H, F, 4, 64, R)
+    # the one-level entry point refuses a two-level layer and the other way round
+    q, qs, qz, meta = mats[(0, 0)]
+    h16 = np.zeros((F, H // 64), np.float16)
+    expect(B.MOE_ESTATE, B.moe_layer_load_expert, lay, 0, 0, q.ctypes.data, h16.ctypes.data, h16.ctypes.data)
+    st.close()
+    st = Stack([layer_config(H, F, E, 2, 4, 64, 2)], [torch.zeros(E, H)], host_only=True)
+    expect(B.MOE_ESTATE, B.moe_layer_load_expert_2level, st.layers[0], 0, 0, q.ctypes.data, qs.ctypes.data, qz.ctypes.data, meta.ctypes.data)
+    st.close()
+
+
 def expect(code, fn, *args):
     with pytest.raises(B.MoeError) as ei:
         fn(*args)

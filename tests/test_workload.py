@@ -46,11 +46,15 @@ def test_generator_quantizer_matches_oracle_quantizer_bit_for_bit(bits, group):
 def test_generator_second_level_matches_oracle_bit_for_bit():
     w = W.expert_matrix(0, 0, 2, W.generate.W2, 256, 512)           # w2: [256][512], 8 groups of 64 per row
     q, s, z = W.quantize_minmax(w, 4, 64)
-    for scale_group in (4, 256):
+    degenerate = 0
+    for scale_group in (1, 2, 4, 256):                              # short runs hit the "stored as a constant" rule
         qs, qz, meta = W.quantize_meta8(s, z, scale_group)
         qso, qzo, metao = O.quantize_meta8(s.numpy(), z.numpy(), scale_group)
         assert (qs.numpy() == qso).all() and (qz.numpy() == qzo).all()
         assert (meta.numpy().view(np.uint16) == metao.view(np.uint16)).all()
+        assert np.isfinite(metao.astype(np.float64)).all()
+        degenerate += int((metao[:, :, 0] == 1).sum())
+    assert degenerate > 0
     ex = W.quantized_expert(0, 0, 1, 256, 512, 4, 64, scale_group=256)
     assert len(ex) == 3 and all(len(m) == 4 for m in ex) and ex[0][3].shape == (512, 1, 4) and ex[2][3].shape == (256, 1, 4)
 

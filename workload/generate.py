@@ -103,7 +103,10 @@ def expert_matrix(seed: int, layer: int, expert: int, matrix: int, hidden: int, 
     return torch.randn(out_f, in_f, generator=g, dtype=torch.float32, device=device) * 0.02
 
 
-def quantize_minmax(w: torch.Tensor, bits: int, group: int):
+META8_ZERO_LIMIT = 60000.0   # largest |zero| a run's fp16 pair may carry (fp16 overflows at 65520)
+
+
+def quantize_minmax(w: torch.Tensor, bits: int, group: int, zero_limit=None):
     """Asymmetric min/max group quantization along the input (last) dimension.
 
     Per group of `group` consecutive elements of a row: lo = min, hi = max,
@@ -113,6 +116,10 @@ def quantize_minmax(w: torch.Tensor, bits: int, group: int):
     scale and zero, all arithmetic in fp32.
 
     Returns (codes uint8 [out, in], scale fp16 [out, in/group], zero fp16 [out, in/group]).
+
+    zero_limit (second level only): a group whose |lo / scale| would exceed it (values close together
+    relative to their size; the zero would overflow fp16) is stored as a constant: scale = 1,
+    zero = fp16(-lo), all codes 0.
     """
     out_f, in_f = w.shape
     assert in_f % group == 0
@@ -122,6 +129,8 @@ def quantize_minmax(w: torch.Tensor, bits: int, group: int):
     hi = wg.amax(dim=2)
     s16 = ((hi - lo) / qmax).to(torch.float16)
     s16 = torch.where(s16 == 0, torch.ones_like(s16), s16)
+    if zero_limit is not None:
+        s16 = torch.where((lo / s16.to(torch.float32)).abs() > zero_limit, torch.ones_like(s16), s16)
     sf = s16.to(torch.float32)
     z16 = (-lo / sf).to(torch.float16)
     zf = z16.to(torch.float32)
@@ -145,8 +154,8 @@ def quantize_meta8(scale_f16: torch.Tensor, zero_f16: torch.Tensor, scale_group:
     meta[r, j] = (scale of the scale codes, zero of the scale codes, scale of the zero codes, zero of the zero codes).
     """
     r = run_length(scale_f16.shape[1], scale_group)
-    qs, ss, sz = quantize_minmax(scale_f16.to(torch.float32), 8, r)
-    qz, zs, zz = quantize_minmax(zero_f16.to(torch.float32), 8, r)
+    qs, ss, sz = quantize_minmax(scale_f16.to(torch.float32), 8, r, META8_ZERO_LIMIT)
+    qz, zs, zz = quantize_minmax(zero_f16.to(torch.float32), 8, r, META8_ZERO_LIMIT)
     return qs, qz, torch.stack([ss, sz, zs, zz], dim=2).contiguous()
 
 
