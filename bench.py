@@ -35,7 +35,7 @@ def log(msg: str) -> None:
     print(f"[bench] {msg}", file=sys.stderr, flush=True)
 
 
-def build_model(shape, formats, batch, device, keep_layers, n_staging=4, swap=False):
+def build_model(shape, formats, batch, device, keep_layers, n_staging=4, swap=False, scale_group=0):
     import torch
     import workload as W
     from paper_2312_17238_amd.engine import Stack, layer_config
@@ -45,18 +45,18 @@ def build_model(shape, formats, batch, device, keep_layers, n_staging=4, swap=Fa
     from paper_2312_17238_amd import binding as B
     cfgs = [layer_config(shape.hidden, shape.ffn, shape.n_experts, shape.top_k, formats[l][0], formats[l][1],
                          shape.cache_slots, shape.prefetch_m, shape.rms_eps, 1 if swap else 0,
-                         B.MOE_LAYER_SWAP if swap else 0) for l in range(shape.layers)]
+                         B.MOE_LAYER_SWAP if swap else 0, scale_group) for l in range(shape.layers)]
     stack = Stack(cfgs, gates, gamma, n_staging=n_staging, max_batch=batch, device=device)
     kept = {}
     t0 = time.time()
     for l in range(shape.layers):
         bits, group = formats[l]
         for e in range(shape.n_experts):
-            mats = W.quantized_expert(shape.seed, l, e, shape.hidden, shape.ffn, bits, group, device)
-            for m, (q, s, z) in enumerate(mats):
-                stack.load_expert(l, e, m, q, s, z)
+            mats = W.quantized_expert(shape.seed, l, e, shape.hidden, shape.ffn, bits, group, device, scale_group)
+            for m, mat in enumerate(mats):
+                stack.load_expert(l, e, m, *mat)
             if l in keep_layers:
-                kept[(l, e)] = [(q.cpu().numpy(), s.cpu().numpy(), z.cpu().numpy()) for q, s, z in mats]
+                kept[(l, e)] = [tuple(t.cpu().numpy() for t in mat) for mat in mats]
             del mats
         if l % 4 == 3 or l + 1 == shape.layers:
             log(f"generated, quantized and loaded layers 0..{l} ({time.time() - t0:.1f} s)")
@@ -113,6 +113,9 @@ def main() -> int:
     ap.add_argument("--fused", action="store_true", help="single-token steps run w1/w3 and w2 as one persistent launch")
     ap.add_argument("--no-token-path", action="store_true", help="single-token steps use the general kernels (atomics + residual kernel)")
     ap.add_argument("--no-probe", action="store_true", help="skip the plain streaming-read / copy calibration kernels")
+    ap.add_argument("--scale-group", type=int, default=0,
+                    help="two-level metadata (Sec. 4.2): 8-bit scale and zero codes with an fp16 quad per run of this many "
+                         "groups (256 for the paper's 4-bit scheme); 4-bit formats only, 4.25 instead of 4.5 bits per weight")
     ap.add_argument("--swap", action="store_true",
                     help="hosts that cannot hold every expert (Sec. 3.3): experts split between host and device buffers, "
                          "every load writes the evicted expert back (experts 0..k-1 start on the device)")
@@ -147,7 +150,8 @@ def main() -> int:
     keep_layers = set() if args.no_cpu_baseline else set(range(min(2, shape.layers)))
     log(f"workload {shape.name}: {shape.layers} layers, H={shape.hidden}, F={shape.ffn}, E={shape.n_experts}, "
         f"k={shape.cache_slots}, m={shape.prefetch_m}, batch={batch}, formats={sorted(set(formats))}")
-    stack, gates, gamma, kept = build_model(shape, formats, batch, device, keep_layers, swap=args.swap)
+    stack, gates, gamma, kept = build_model(shape, formats, batch, device, keep_layers, swap=args.swap,
+                                            scale_group=args.scale_group)
     if args.no_cache:
         stack.set_flags(B.MOE_LAYER_NO_CACHE)
     B.moe_ctx_set_option(stack.ctx, "spec_head_mb", args.spec_head_mb)
@@ -224,7 +228,8 @@ def main() -> int:
                                f"{shape.n_experts} experts top-{shape.top_k}, formats {sorted(set(formats))}, "
                                f"LRU k={shape.cache_slots}, prefetch m={shape.prefetch_m}, b=4 staging buffers, "
                                f"batch {batch}, {shape.hidden_kind} hidden states, seed {shape.seed}",
-                   "no_cache": bool(args.no_cache), "spec_head_mb": args.spec_head_mb, "swap": bool(args.swap)},
+                   "no_cache": bool(args.no_cache), "spec_head_mb": args.spec_head_mb, "swap": bool(args.swap),
+                   "scale_group": args.scale_group, "expert_blob_bytes": max(stack.blob_bytes)},
     }
     link_bytes = d["bytes_h2d_demand"] + d["bytes_h2d_spec"]
     result["cache"] = {"needed": d["needed"], "hits": d["hits"], "prefetch_hits": d["prefetch_hits"], "misses": d["misses"],
@@ -257,11 +262,11 @@ def main() -> int:
     elif prof:
         w13, w2, cp, gt = prof["w13"], prof["w2"], prof["copy"], prof["gate"]
         ach = w13["bytes"] / max(w13["total_ms"], 1e-9) / 1e6      # GB/s
-        matrix_cores = batch >= 16 and set(formats) == {(4, 64)}
+        matrix_cores = batch >= 16 and set(formats) == {(4, 64)} and not args.scale_group
         result["roofline"] = {"bound": "hbm", "kernel": "k_mfma_stream_q4<true> (grouped dequant-GEMM w1,w3 -> SiLU*mul)" if matrix_cores
                               else "k_w13 (fused dequant-GEMV w1,w3 -> SiLU*mul)",
                               "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
-                              "traffic": PMC_TRAFFIC_W13_4BIT_B1 if (batch == 1 and set(formats) == {(4, 64)}
+                              "traffic": PMC_TRAFFIC_W13_4BIT_B1 if (batch == 1 and set(formats) == {(4, 64)} and not args.scale_group
                                                                      and shape.hidden == 4096 and shape.ffn == 14336) else None,
                               "launches": w13["launches"],
                               "bytes_per_launch": w13["bytes"] / max(1, w13["launches"]),
