@@ -528,3 +528,26 @@ def test_mixtral_layer_two_level_metadata():
     _, sim, errs = run_teacher_forced(model, xs, c_ffn.expert_ffn)
     say(f"  max abs {max(e[0] for e in errs):.2e} max rel-rms {max(e[1] for e in errs):.2e}")
     model.close()
+
+
+def test_recall_study_tool_against_closed_forms():
+    """paper_2312_17238_amd.recall_study (the Fig. 2 analogue): on a small stack its LRU hit ratio for k = top_k = 2
+    equals the closed form sum_t |S_t & S_{t-1}| / needed, for k = E only the first touches miss, and guessing all
+    E experts recalls everything."""
+    from paper_2312_17238_amd import recall_study as R
+    shape = W.MoEShape("study", 3, 256, 512, 8, 2, 4, 64, 2, 2, 1e-5, 24, 1, "ar1", 5)
+    routing, h_all, gates = R.record(shape, W.layer_formats(shape), shape.tokens, "cuda:0")
+    T, L = shape.tokens, shape.layers
+    assert len(routing) == T and all(len(r) == L and all(len(s) == 2 for s in r) for r in routing)
+    closed = sum(len(set(routing[t][l]) & set(routing[t - 1][l])) for t in range(1, T) for l in range(L)) / (2 * T * L)
+    assert abs(R.lru_hit_ratio(routing, L, 8, 2, 2) - closed) < 1e-12
+    touched = sum(len({e for t in range(T) for e in routing[t][l]}) for l in range(L))
+    assert abs(R.lru_hit_ratio(routing, L, 8, 2, 8) - (1 - touched / (2 * T * L))) < 1e-12
+    assert R.speculative_recall(routing, h_all, gates, 1, 8) == 1.0
+    r1, r2 = R.speculative_recall(routing, h_all, gates, 1, 1), R.speculative_recall(routing, h_all, gates, 1, 2)
+    assert 0.0 <= r1 <= 0.5 and r1 <= r2 <= 1.0
+    # the routing the tool recorded is the oracle's
+    for t in (0, T - 1):
+        for l in range(L):
+            idx, _, _ = O.route(gates[l].numpy(), h_all[t, l].numpy(), 2)
+            assert list(idx) == routing[t][l]
