@@ -39,7 +39,7 @@ extern "C" {
 
 #define MOE_MAX_EXPERTS 16   /* experts per layer                    */
 #define MOE_MAX_TOPK     4   /* active experts per token             */
-#define MOE_MAX_BATCH   64   /* tokens per decode step               */
+#define MOE_MAX_BATCH   1024 /* tokens per step: a decode batch, or a prompt (or a piece of one) encoded layer by layer */
 #define MOE_MAX_GUESS    4   /* speculatively loaded experts per step */
 
 typedef enum {

@@ -13,7 +13,7 @@ from typing import List, Optional, Sequence
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libmoe_offload.so")
 
-MOE_MAX_EXPERTS, MOE_MAX_TOPK, MOE_MAX_BATCH, MOE_MAX_GUESS = 16, 4, 64, 4
+MOE_MAX_EXPERTS, MOE_MAX_TOPK, MOE_MAX_BATCH, MOE_MAX_GUESS = 16, 4, 1024, 4
 MOE_OK, MOE_EINVAL, MOE_ESTATE, MOE_ENOMEM, MOE_EHIP = 0, -1, -2, -3, -4
 MOE_HIT, MOE_PREFETCH_HIT, MOE_MISS = 0, 1, 2
 MOE_CTX_HOST_ONLY = 1

@@ -9,12 +9,14 @@ namespace moe {
 // K1: RMSNorm + gate + top-k (+ next layer's gate for speculative loading)
 // ---------------------------------------------------------------------------------------------
 
+constexpr int GATE_MAX_TOKENS = 1024;   // tokens per launch (the interface's batch limit)
+
 struct GateHostOut {                // lives in host-mapped pinned memory; written by the kernel
-    int32_t idx[64 * 4];            // [b*K + j]
-    float w[64 * 4];
-    double logits[64 * 16];         // [b*E + e]
-    double spec_p[64 * 16];         // [b*E2 + e] next-layer gate probabilities per token
-    uint32_t done[64];              // [b] = sequence number of the launch, stored by block b after its results
+    int32_t idx[GATE_MAX_TOKENS * 4];            // [b*K + j]
+    float w[GATE_MAX_TOKENS * 4];
+    double logits[GATE_MAX_TOKENS * 16];         // [b*E + e]
+    double spec_p[GATE_MAX_TOKENS * 16];         // [b*E2 + e] next-layer gate probabilities per token
+    uint32_t done[GATE_MAX_TOKENS];              // [b] = sequence number of the launch, stored by block b after its results
                                     // (system-scope release; one word per block: posted writes, no round trips)
     uint32_t ffn_error;             // set by the fused FFN kernel if its grid barrier gave up
 };

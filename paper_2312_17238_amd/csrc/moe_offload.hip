@@ -28,6 +28,8 @@
 
 using namespace moe;
 
+static_assert(GATE_MAX_TOKENS == MOE_MAX_BATCH && MOE_MAX_TOPK == 4 && MOE_MAX_EXPERTS == 16, "the gate kernel's result arrays are sized for the interface limits");
+
 // ---------------------------------------------------------------------------------------------
 // errors
 // ---------------------------------------------------------------------------------------------
@@ -1041,29 +1043,11 @@ struct PassExpert { const uint8_t *blob; std::vector<int> pairs; };
 
 // Streaming matrix-core form: persistent blocks over (entry, 128-row block, K part) items.
 // An expert with more than 32 tokens becomes two entries (token tiles) that read the same weights.
-static int32_t launch_mfma_stream(moe_layer *l, const std::vector<PassExpert> &experts, const float *w)
+static int32_t launch_mfma_stream(moe_layer *l, const std::vector<PassExpert> &experts, const float *w, int batch)
 {
     moe_ctx *c = l->ctx;
     const BlobLayout &b = l->lay;
     const int K = l->cfg.top_k;
-    TileArgs A{};
-    int n = 0, first = 0;
-    for (const PassExpert &pe : experts)
-        for (size_t t0 = 0; t0 < pe.pairs.size(); t0 += 32) {
-            if (n >= 32) return fail(MOE_EINVAL, "more than 32 (expert, token tile) entries in one pass");
-            const size_t t1 = std::min(pe.pairs.size(), t0 + 32);
-            A.e[n].blob = pe.blob;
-            A.e[n].n_tok = (int32_t)(t1 - t0);
-            A.e[n].first = first;
-            for (size_t i = t0; i < t1; ++i) {
-                const int q = pe.pairs[i];
-                A.tok[first] = (uint8_t)(q / K);
-                A.pair[first] = (uint8_t)q;
-                A.w[first] = w[q];
-                ++first;
-            }
-            ++n;
-        }
     static bool lds_attr_set = false;      // staging buffers above the default dynamic LDS limit
     if (!lds_attr_set) {
         HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_stream_q4<true>), hipFuncAttributeMaxDynamicSharedMemorySize, TL_LDS_BYTES));
@@ -1071,27 +1055,63 @@ static int32_t launch_mfma_stream(moe_layer *l, const std::vector<PassExpert> &e
         lds_attr_set = true;
     }
     const int n_cu = c->n_cu > 0 ? c->n_cu : 256;
-    auto shape = [&](int rows, int Kdim, bool may_split) {
-        const int n_seg = (Kdim / 64 + TL_SG - 1) / TL_SG;
-        A.row_blocks = (rows + TL_ROWS - 1) / TL_ROWS;
-        int parts = 1;
-        if (may_split) parts = std::min(n_seg, std::max(1, (2 * n_cu + n * A.row_blocks - 1) / (n * A.row_blocks)));
-        A.seg_per_part = (n_seg + parts - 1) / parts;
-        A.k_parts = (n_seg + A.seg_per_part - 1) / A.seg_per_part;       // no empty part
-        A.n_items = n * A.row_blocks * A.k_parts;
-        return dim3(std::min(A.n_items, TL_BLOCKS_PER_CU * n_cu));
-    };
-    const uint64_t bytes13 = (uint64_t)n * 2 * b.ffn * b.m13.row_stride, bytes2 = (uint64_t)n * b.hidden * b.m2.row_stride;
-    A.a = c->a_buf; A.yacc = c->yacc;
-    A.act = c->h_buf;
-    A.K = b.hidden; A.N = b.ffn; A.stride = b.m13.row_stride; A.meta_off = b.m13.meta_off; A.mat_off = b.off_w13;
-    const dim3 g13 = shape(2 * b.ffn, b.hidden, false);
-    int32_t rc = launch_timed(c, PROF_W13, bytes13, k_mfma_stream_q4<true>, g13, dim3(TL_THREADS), TL_LDS_BYTES, A);
-    if (rc) return rc;
-    A.act = c->a_buf;
-    A.K = b.ffn; A.N = b.hidden; A.stride = b.m2.row_stride; A.meta_off = b.m2.meta_off; A.mat_off = b.off_w2;
-    const dim3 g2 = shape(b.hidden, b.ffn, true);
-    return launch_timed(c, PROF_W2, bytes2, k_mfma_stream_q4<false>, g2, dim3(TL_THREADS), TL_LDS_BYTES, A);
+    // The kernels address tokens and pairs with one byte, so a large batch (a prompt, Sec. 3) goes through in
+    // windows of 256 / top_k tokens: each window is a launch pair of its own over the same resident experts, with the
+    // activation, scratch and accumulator pointers moved to the window's first token.
+    const int window = MF_MAX_PAIRS / K;
+    for (int w0 = 0; w0 < batch; w0 += window) {
+        const int w1 = std::min(batch, w0 + window);
+        TileArgs A{};
+        int n = 0, first = 0, n_distinct = 0;
+        for (const PassExpert &pe : experts) {
+            std::vector<int> mine;
+            for (int q : pe.pairs)
+                if (q / K >= w0 && q / K < w1) mine.push_back(q);
+            if (mine.empty()) continue;
+            ++n_distinct;
+            for (size_t t0 = 0; t0 < mine.size(); t0 += 32) {
+                if (n >= 32) return fail(MOE_EINVAL, "more than 32 (expert, token tile) entries in one launch");
+                const size_t t1 = std::min(mine.size(), t0 + 32);
+                A.e[n].blob = pe.blob;
+                A.e[n].n_tok = (int32_t)(t1 - t0);
+                A.e[n].first = first;
+                for (size_t i = t0; i < t1; ++i) {
+                    const int q = mine[i];
+                    A.tok[first] = (uint8_t)(q / K - w0);
+                    A.pair[first] = (uint8_t)(q - w0 * K);
+                    A.w[first] = w[q];
+                    ++first;
+                }
+                ++n;
+            }
+        }
+        if (n == 0) continue;
+        auto shape = [&](int rows, int Kdim, bool may_split) {
+            const int n_seg = (Kdim / 64 + TL_SG - 1) / TL_SG;
+            A.row_blocks = (rows + TL_ROWS - 1) / TL_ROWS;
+            int parts = 1;
+            if (may_split) parts = std::min(n_seg, std::max(1, (2 * n_cu + n * A.row_blocks - 1) / (n * A.row_blocks)));
+            A.seg_per_part = (n_seg + parts - 1) / parts;
+            A.k_parts = (n_seg + A.seg_per_part - 1) / A.seg_per_part;       // no empty part
+            A.n_items = n * A.row_blocks * A.k_parts;
+            return dim3(std::min(A.n_items, TL_BLOCKS_PER_CU * n_cu));
+        };
+        // algorithmic bytes: every distinct expert of the launch once (a second token tile reads it again)
+        const uint64_t bytes13 = (uint64_t)n_distinct * 2 * b.ffn * b.m13.row_stride, bytes2 = (uint64_t)n_distinct * b.hidden * b.m2.row_stride;
+        uint16_t *a_win = c->a_buf + (size_t)w0 * K * b.ffn;
+        A.a = a_win; A.yacc = c->yacc + (size_t)w0 * b.hidden;
+        A.act = c->h_buf + (size_t)w0 * b.hidden;
+        A.K = b.hidden; A.N = b.ffn; A.stride = b.m13.row_stride; A.meta_off = b.m13.meta_off; A.mat_off = b.off_w13;
+        const dim3 g13 = shape(2 * b.ffn, b.hidden, false);
+        int32_t rc = launch_timed(c, PROF_W13, bytes13, k_mfma_stream_q4<true>, g13, dim3(TL_THREADS), TL_LDS_BYTES, A);
+        if (rc) return rc;
+        A.act = a_win;
+        A.K = b.ffn; A.N = b.hidden; A.stride = b.m2.row_stride; A.meta_off = b.m2.meta_off; A.mat_off = b.off_w2;
+        const dim3 g2 = shape(b.hidden, b.ffn, true);
+        rc = launch_timed(c, PROF_W2, bytes2, k_mfma_stream_q4<false>, g2, dim3(TL_THREADS), TL_LDS_BYTES, A);
+        if (rc) return rc;
+    }
+    return MOE_OK;
 }
 
 static int32_t launch_mfma(moe_layer *l, const std::vector<PassExpert> &experts, const float *w, int batch, bool first_pass)
@@ -1099,6 +1119,7 @@ static int32_t launch_mfma(moe_layer *l, const std::vector<PassExpert> &experts,
     moe_ctx *c = l->ctx;
     const BlobLayout &b = l->lay;
     const int K = l->cfg.top_k;
+    if (c->mfma_form == 2 || batch * K > MF_MAX_PAIRS) return launch_mfma_stream(l, experts, w, batch);   // the older forms index pairs with one byte
     MfmaArgs A{};
     int n = 0, first = 0, max_tok = 0;
     for (const PassExpert &pe : experts) {
@@ -1129,7 +1150,6 @@ static int32_t launch_mfma(moe_layer *l, const std::vector<PassExpert> &experts,
         return std::max<size_t>((size_t)32 * (sg * 32 + 16) + (size_t)32 * ((sg + 3) & ~3) * 4, (size_t)MF2_WAVES * mt * 16 * 64 * 4);
     };
     const int mt = max_tok > 32 ? 2 : 1;
-    if (c->mfma_form == 2) return launch_mfma_stream(l, experts, w);
     if (c->mfma_form == 1) {
         static bool lds_attr_set = false;  // these kernels stage 72 KB: above the default dynamic LDS limit
         if (!lds_attr_set) {
@@ -1237,7 +1257,7 @@ extern "C" int32_t moe_layer_step(moe_layer_t *l, moe_layer_t *next, const uint1
                            (int)plan.access.size() == cf.top_k && !plan.victim_needed;
     bool fused_done = false;
     const bool use_mfma = batch >= c->mfma_min_batch && cf.bits == 4 && cf.group == 64 && cf.scale_group == 0 && cf.hidden % MF_KC == 0 &&
-                          cf.ffn % MF_KC == 0 && batch * cf.top_k <= MF_MAX_PAIRS;
+                          cf.ffn % MF_KC == 0;
     for (size_t p = 0; p < passes.size(); ++p) {
         if (p > 0) {
             HIPCHK(hipEventRecord(c->ev_compute, c->compute));

@@ -551,3 +551,22 @@ def test_recall_study_tool_against_closed_forms():
         for l in range(L):
             idx, _, _ = O.route(gates[l].numpy(), h_all[t, l].numpy(), 2)
             assert list(idx) == routing[t][l]
+
+
+@pytest.mark.parametrize("Bn,k,T,form", [(200, 4, 2, 2), (130, 2, 2, 1), (1000, 8, 1, 2), (1024, 2, 1, 2)])
+def test_prompt_sized_batches(Bn, k, T, form):
+    """Prompt encoding (Sec. 3: prompt tokens go through a layer in parallel, every expert is loaded once for all of
+    them) is a step with a large batch: up to MOE_MAX_BATCH = 1024 tokens, through the matrix cores in windows of
+    128 tokens per launch over the same resident experts; with k=2 and all 8 experts needed the step runs in
+    several passes.  Every decision and every output row against the oracle."""
+    L, H, F = 2, 256, 512
+    say(f"prompt-sized batch B={Bn} k={k} form={form}")
+    model = Model(L, H, F, 8, 2, None, k, 2, 1e-5, max_batch=Bn, seed=81)
+    B.moe_ctx_set_option(model.stack.ctx, "mfma_form", form)
+    B.moe_ctx_profile_enable(model.stack.ctx, True)
+    xs = W.hidden_ar1(81, T, Bn, H)
+    _, sim, errs = run_teacher_forced(model, xs, O.expert_ffn)
+    prof = B.moe_ctx_profile_read(model.stack.ctx).as_dict()
+    assert prof["w13"]["launches"] >= T * L * -(-Bn // 128)
+    say(f"  max abs {max(e[0] for e in errs):.2e} max rel-rms {max(e[1] for e in errs):.2e} w1/w3 launches {prof['w13']['launches']}")
+    model.close()

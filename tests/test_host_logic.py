@@ -45,7 +45,7 @@ def make_stack(L, E, k, m, b, H=64, F=64, flags=0, init_policy=0, max_batch=1):
 
 
 @pytest.mark.parametrize("L,E,k,m,b,B_", [(4, 8, 2, 2, 4, 1), (3, 8, 4, 2, 4, 1), (5, 8, 2, 1, 2, 1), (2, 6, 3, 2, 1, 1),
-                                          (3, 8, 4, 2, 4, 16), (3, 8, 4, 2, 4, 4), (2, 8, 8, 2, 4, 1)])
+                                          (3, 8, 4, 2, 4, 16), (3, 8, 4, 2, 4, 4), (2, 8, 8, 2, 4, 1), (2, 8, 2, 2, 4, 300)])
 def test_bookkeeping_equals_oracle_simulator(L, E, k, m, b, B_):
     rng = np.random.default_rng(L * 100 + k * 10 + B_)
     st = make_stack(L, E, k, m, b, max_batch=B_)
