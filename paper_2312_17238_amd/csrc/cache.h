@@ -57,10 +57,12 @@ struct BufferPool {
 
 // Resolve the accesses of one step: `needed` ascending and distinct.  Resident experts are touched
 // first, then absent ones, each in ascending id.  Appends demand copies to `copies`.
-// swap: a miss that evicts takes a free staging buffer for the slot, when there is one, and frees the victim's.
+// redirect: a miss that evicts takes a free staging buffer for the slot, when there is one, and frees the victim's
+// (swap mode: the victim is still draining out of its buffer; a step that needs more experts than the layer has
+// slots: the victim's buffer is still being read by this step's earlier kernels).
 inline void resolve_accesses(LayerCache &c, BufferPool &pool, Counters &st, const std::vector<int32_t> &needed,
                              bool forget_first, std::vector<AccessRec> &out, std::vector<CopyOp> &copies,
-                             bool swap = false)
+                             bool redirect = false)
 {
     if (forget_first)
         for (int s = 0; s < c.k; ++s) c.slot_expert[s] = -1;
@@ -99,7 +101,7 @@ inline void resolve_accesses(LayerCache &c, BufferPool &pool, Counters &st, cons
             st.prefetch_hits++;
         } else {
             status = 2;                     // MISS
-            if (swap && victim >= 0 && !pool.free_staging.empty()) {
+            if (redirect && victim >= 0 && !pool.free_staging.empty()) {
                 auto it = std::min_element(pool.free_staging.begin(), pool.free_staging.end());
                 c.slot_buf[s] = *it;        // one buffer taken, one given back: the number of free buffers,
                 *it = old_buf;              // the only thing decisions depend on, does not change

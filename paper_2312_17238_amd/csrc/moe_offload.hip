@@ -677,7 +677,9 @@ static int32_t plan_step(moe_layer *l, moe_layer *next, const int32_t *idx, int3
     std::sort(needed.begin(), needed.end());
     needed.erase(std::unique(needed.begin(), needed.end()), needed.end());
     std::vector<CopyOp> misses;
-    resolve_accesses(l->cache, l->ctx->pool, l->st, needed, (cf.flags & MOE_LAYER_NO_CACHE) != 0, plan.access, misses, l->swap);
+    // loads go to a free staging buffer instead of the victim's own when that one cannot be overwritten yet
+    const bool redirect = l->swap || (int)needed.size() > cf.cache_slots;
+    resolve_accesses(l->cache, l->ctx->pool, l->st, needed, (cf.flags & MOE_LAYER_NO_CACHE) != 0, plan.access, misses, redirect);
     size_t next_miss = 0;
     for (const AccessRec &a : plan.access) {
         if (a.victim >= 0 && std::binary_search(needed.begin(), needed.end(), a.victim)) plan.victim_needed = true;
@@ -1258,6 +1260,7 @@ extern "C" int32_t moe_layer_step(moe_layer_t *l, moe_layer_t *next, const uint1
     bool fused_done = false;
     const bool use_mfma = batch >= c->mfma_min_batch && cf.bits == 4 && cf.group == 64 && cf.scale_group == 0 && cf.hidden % MF_KC == 0 &&
                           cf.ffn % MF_KC == 0;
+    bool sums_done = false;     // the direct-to-lane matrix-core form needs the group sums of h once per step
     for (size_t p = 0; p < passes.size(); ++p) {
         if (p > 0) {
             HIPCHK(hipEventRecord(c->ev_compute, c->compute));
@@ -1267,19 +1270,38 @@ extern "C" int32_t moe_layer_step(moe_layer_t *l, moe_layer_t *next, const uint1
         if (p + 1 == passes.size() && !plan.victim_needed && passes.size() == 1)
             for (const CopyOp &op : plan.spec) { rc = issue_copy(c, next, op); if (rc) return rc; }
         if (use_mfma) {
-            std::vector<PassExpert> pes;
-            for (int i : passes[p]) {
-                const AccessRec &a = plan.access[i];
-                PoolBuf &pb = c->bufs[a.buf];
-                if (pb.pending) { HIPCHK(hipStreamWaitEvent(c->compute, pb.ready, 0)); pb.pending = false; }
+            // Experts already on the device go first, in one launch pair per window.  For a prompt-sized batch the
+            // experts still in flight then follow one by one in the order their copies were issued, each waiting
+            // for its own copy only: the multiply of one expert runs under the transfer of the next.
+            const bool one_by_one = batch > 64;
+            auto pass_expert = [&](int i) {
                 PassExpert pe;
-                pe.blob = pb.ptr;
+                pe.blob = c->bufs[plan.access[i].buf].ptr;
                 for (int q = 0; q < batch * cf.top_k; ++q)
-                    if (idx[q] == a.expert) pe.pairs.push_back(q);
-                pes.push_back(pe);
+                    if (idx[q] == plan.access[i].expert) pe.pairs.push_back(q);
+                return pe;
+            };
+            std::vector<PassExpert> group;
+            std::vector<int> in_flight;
+            for (int i : passes[p]) {
+                PoolBuf &pb = c->bufs[plan.access[i].buf];
+                if (one_by_one && pb.pending) { in_flight.push_back(i); continue; }
+                if (pb.pending) { HIPCHK(hipStreamWaitEvent(c->compute, pb.ready, 0)); pb.pending = false; }
+                group.push_back(pass_expert(i));
             }
-            rc = launch_mfma(l, pes, w, batch, p == 0);
-            if (rc) return rc;
+            if (!group.empty()) {
+                rc = launch_mfma(l, group, w, batch, !sums_done);
+                if (rc) return rc;
+                sums_done = true;
+            }
+            for (int i : in_flight) {
+                PoolBuf &pb = c->bufs[plan.access[i].buf];
+                HIPCHK(hipStreamWaitEvent(c->compute, pb.ready, 0));
+                pb.pending = false;
+                rc = launch_mfma(l, std::vector<PassExpert>{pass_expert(i)}, w, batch, !sums_done);
+                if (rc) return rc;
+                sums_done = true;
+            }
             continue;
         }
         std::vector<FfnEntry> entries;
