@@ -570,3 +570,16 @@ def test_prompt_sized_batches(Bn, k, T, form):
     assert prof["w13"]["launches"] >= T * L * -(-Bn // 128)
     say(f"  max abs {max(e[0] for e in errs):.2e} max rel-rms {max(e[1] for e in errs):.2e} w1/w3 launches {prof['w13']['launches']}")
     model.close()
+
+
+@pytest.mark.parametrize("formats,scale_group,Bn", [([(2, 16), (3, 64)], 0, 300), ([(4, 64), (4, 64)], 256, 200)])
+def test_prompt_sized_batches_on_the_gemv_kernels(formats, scale_group, Bn):
+    """Formats the matrix-core kernels do not take (2-bit, 3-bit, two-level metadata) run a large batch through the
+    GEMV kernels, four tokens per entry and sixteen entries per launch."""
+    L, H, F = 2, 256, 512
+    say(f"prompt-sized batch on GEMV kernels B={Bn} formats={formats} scale_group={scale_group}")
+    model = Model(L, H, F, 8, 2, formats, 4, 2, 1e-5, max_batch=Bn, seed=83, scale_group=scale_group)
+    xs = W.hidden_ar1(83, 1, Bn, H)
+    _, sim, errs = run_teacher_forced(model, xs, O.expert_ffn)
+    say(f"  max abs {max(e[0] for e in errs):.2e} max rel-rms {max(e[1] for e in errs):.2e}")
+    model.close()
