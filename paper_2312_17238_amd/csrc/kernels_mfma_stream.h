@@ -62,6 +62,8 @@ struct TileArgs {
     float *yacc;                             // w2 output (accumulated)
     int32_t K, N;                            // contraction length, output rows of the matrix
     uint32_t stride, meta_off;
+    uint32_t meta2_off;                      // two-level metadata: byte offset of the per-run fp16 quads inside a row
+    int32_t run_shift;                       // ... log2(groups per run), 31 when a row is one run
     uint64_t mat_off;
     int32_t row_blocks, k_parts, seg_per_part, n_items;   // item = ((entry * row_blocks) + row block) * k_parts + part
 };
@@ -81,7 +83,10 @@ __device__ __forceinline__ h8_t codes_to_w8(uint32_t w, h2_t b1024, h2_t b64, h2
     return r;
 }
 
-template <bool W13>
+// META8: two-level metadata (Sec. 4.2 "scale group size").  A step then stages, per row, 16 bytes of (scale code, zero
+// code) byte pairs and the run's fp16 quad instead of 32 bytes of fp16 pairs, and a unit decodes scale and zero in fp32
+// before the same fp16 dequantisation.
+template <bool W13, bool META8>
 __global__ __launch_bounds__(TL_THREADS, TL_BLOCKS_PER_CU) void k_mfma_stream_q4(TileArgs A)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
@@ -136,7 +141,18 @@ __global__ __launch_bounds__(TL_THREADS, TL_BLOCKS_PER_CU) void k_mfma_stream_q4
             const int p = tid + i * TL_THREADS, r = p / TL_MPR, c = p % TL_MPR;
             // a step takes 32 B of a row's pairs, its neighbours in the cache line belong to the next steps: a
             // plain load, so that L2 keeps the line (the streaming hint would fetch it from HBM once per step)
-            st_m[i] = reinterpret_cast<const uint4 *>(mat + (size_t)min(row0 + r, n_rows - 1) * A.stride + A.meta_off)[g0 / 4 + (c < (sg + 3) / 4 ? c : 0)];
+            const uint8_t *rowp = mat + (size_t)min(row0 + r, n_rows - 1) * A.stride;
+            if constexpr (META8) {            // piece 0: the step's 8 byte pairs; piece 1: the fp16 quad of its run
+                static_assert(TL_SG == 8 && TL_MPR == 2, "two-level staging is laid out for steps of 8 groups");
+                if (c == 0) {
+                    st_m[i] = reinterpret_cast<const uint4 *>(rowp + A.meta_off)[g0 / 8];
+                } else {
+                    const uint2 quad = *reinterpret_cast<const uint2 *>(rowp + A.meta2_off + 8 * (g0 >> A.run_shift));
+                    st_m[i] = make_uint4(quad.x, quad.y, 0u, 0u);
+                }
+            } else {
+                st_m[i] = reinterpret_cast<const uint4 *>(rowp + A.meta_off)[g0 / 4 + (c < (sg + 3) / 4 ? c : 0)];
+            }
         }
     };
     auto commit = [&](int b) {                                       // pieces past a short segment hold copies nobody reads
@@ -177,18 +193,34 @@ __global__ __launch_bounds__(TL_THREADS, TL_BLOCKS_PER_CU) void k_mfma_stream_q4
         }
     };
     // One unit = one group of one 32-row tile; its codes and pair are read from LDS one unit ahead of their use.
-    auto unit_load = [&](int b, int gl, int rt, uint4 &q, uint32_t &m) {
+    struct UnitMeta { uint32_t m, quad0, quad1; };                   // one-level: m = (scale, zero) fp16; two-level: byte pair + the run's quad
+    auto unit_load = [&](int b, int gl, int rt, uint4 &q, UnitMeta &um) {
         const uint8_t *codes = lds + b * TL_BUF_BYTES;
         const uint32_t *meta = reinterpret_cast<const uint32_t *>(codes + TL_ROWS * TL_CODE_PITCH);
         const int r = rt * 32 + col;
         q = *reinterpret_cast<const uint4 *>(codes + r * TL_CODE_PITCH + gl * 32 + kh * 16);
-        m = meta[r * TL_META_PITCH + gl];
+        if constexpr (META8) {
+            um.m = (meta[r * TL_META_PITCH + (gl >> 1)] >> (16 * (gl & 1))) & 0xffffu;
+            um.quad0 = meta[r * TL_META_PITCH + 4];
+            um.quad1 = meta[r * TL_META_PITCH + 5];
+        } else {
+            um.m = meta[r * TL_META_PITCH + gl];
+        }
     };
-    auto unit_multiply = [&](const h8_t (&a)[4], const uint4 &q, uint32_t m, int rt) {
-        const _Float16 s16 = __builtin_bit_cast(_Float16, (uint16_t)(m & 0xffff));
-        const _Float16 z16 = __builtin_bit_cast(_Float16, (uint16_t)(m >> 16));
-        const _Float16 zi = __builtin_rintf16(z16);
-        const _Float16 c16 = (zi - z16) * s16, k1024 = (_Float16)-1024.f - zi, k64 = (_Float16)-64.f - zi;
+    auto unit_multiply = [&](const h8_t (&a)[4], const uint4 &q, const UnitMeta &um, int rt) {
+        _Float16 s16, zi, c16;
+        if constexpr (META8) {              // scale = (code - m1) m0, zero = (code - m3) m2, in fp32; then as below
+            const float sc = ((float)(um.m & 0xffu) - hi_half(um.quad0)) * lo_half(um.quad0);
+            const float ze = ((float)(um.m >> 8) - hi_half(um.quad1)) * lo_half(um.quad1);
+            const float zr = rintf(ze);
+            s16 = (_Float16)sc; zi = (_Float16)zr; c16 = (_Float16)((zr - ze) * sc);
+        } else {
+            s16 = __builtin_bit_cast(_Float16, (uint16_t)(um.m & 0xffff));
+            const _Float16 z16 = __builtin_bit_cast(_Float16, (uint16_t)(um.m >> 16));
+            zi = __builtin_rintf16(z16);
+            c16 = (zi - z16) * s16;
+        }
+        const _Float16 k1024 = (_Float16)-1024.f - zi, k64 = (_Float16)-64.f - zi;
         const h2_t s2 = {s16, s16}, c2 = {c16, c16}, b1024 = {k1024, k1024}, b64 = {k64, k64};
         h8_t b[4];
         b[0] = codes_to_w8(q.x, b1024, b64, s2, c2); b[1] = codes_to_w8(q.y, b1024, b64, s2, c2);
@@ -197,12 +229,12 @@ __global__ __launch_bounds__(TL_THREADS, TL_BLOCKS_PER_CU) void k_mfma_stream_q4
         for (int j = 0; j < 4; ++j) acc[rt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[j], b[j], acc[rt], 0, 0, 0);
     };
     uint4 q_next = make_uint4(0, 0, 0, 0);
-    uint32_t m_next = 0;
+    UnitMeta m_next = {0u, 0u, 0u};
     auto group_multiply = [&](const h8_t (&a)[4], int b, int gl, int sg) {   // q_next/m_next hold tile 0 of group gl
 #pragma unroll
         for (int rt = 0; rt < TL_RT; ++rt) {
             const uint4 q = q_next;
-            const uint32_t m = m_next;
+            const UnitMeta m = m_next;
             if (rt + 1 < TL_RT) unit_load(b, gl, rt + 1, q_next, m_next);
             else if (gl + TL_WAVES < sg) unit_load(b, gl + TL_WAVES, 0, q_next, m_next);
             unit_multiply(a, q, m, rt);

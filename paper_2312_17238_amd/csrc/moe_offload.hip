@@ -1052,8 +1052,10 @@ static int32_t launch_mfma_stream(moe_layer *l, const std::vector<PassExpert> &e
     const int K = l->cfg.top_k;
     static bool lds_attr_set = false;      // staging buffers above the default dynamic LDS limit
     if (!lds_attr_set) {
-        HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_stream_q4<true>), hipFuncAttributeMaxDynamicSharedMemorySize, TL_LDS_BYTES));
-        HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_stream_q4<false>), hipFuncAttributeMaxDynamicSharedMemorySize, TL_LDS_BYTES));
+        HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_stream_q4<true, false>), hipFuncAttributeMaxDynamicSharedMemorySize, TL_LDS_BYTES));
+        HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_stream_q4<false, false>), hipFuncAttributeMaxDynamicSharedMemorySize, TL_LDS_BYTES));
+        HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_stream_q4<true, true>), hipFuncAttributeMaxDynamicSharedMemorySize, TL_LDS_BYTES));
+        HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_stream_q4<false, true>), hipFuncAttributeMaxDynamicSharedMemorySize, TL_LDS_BYTES));
         lds_attr_set = true;
     }
     const int n_cu = c->n_cu > 0 ? c->n_cu : 256;
@@ -1103,14 +1105,20 @@ static int32_t launch_mfma_stream(moe_layer *l, const std::vector<PassExpert> &e
         uint16_t *a_win = c->a_buf + (size_t)w0 * K * b.ffn;
         A.a = a_win; A.yacc = c->yacc + (size_t)w0 * b.hidden;
         A.act = c->h_buf + (size_t)w0 * b.hidden;
+        const bool meta8 = b.scale_group > 0;
+        auto run_shift = [&](const MatLayout &m) { return (m.run_len == 0 || m.run_len >= m.cols / (uint32_t)b.group) ? 31 : __builtin_ctz(m.run_len); };
         A.K = b.hidden; A.N = b.ffn; A.stride = b.m13.row_stride; A.meta_off = b.m13.meta_off; A.mat_off = b.off_w13;
+        A.meta2_off = b.m13.meta2_off; A.run_shift = run_shift(b.m13);
         const dim3 g13 = shape(2 * b.ffn, b.hidden, false);
-        int32_t rc = launch_timed(c, PROF_W13, bytes13, k_mfma_stream_q4<true>, g13, dim3(TL_THREADS), TL_LDS_BYTES, A);
+        int32_t rc = meta8 ? launch_timed(c, PROF_W13, bytes13, k_mfma_stream_q4<true, true>, g13, dim3(TL_THREADS), TL_LDS_BYTES, A)
+                           : launch_timed(c, PROF_W13, bytes13, k_mfma_stream_q4<true, false>, g13, dim3(TL_THREADS), TL_LDS_BYTES, A);
         if (rc) return rc;
         A.act = a_win;
         A.K = b.ffn; A.N = b.hidden; A.stride = b.m2.row_stride; A.meta_off = b.m2.meta_off; A.mat_off = b.off_w2;
+        A.meta2_off = b.m2.meta2_off; A.run_shift = run_shift(b.m2);
         const dim3 g2 = shape(b.hidden, b.ffn, true);
-        rc = launch_timed(c, PROF_W2, bytes2, k_mfma_stream_q4<false>, g2, dim3(TL_THREADS), TL_LDS_BYTES, A);
+        rc = meta8 ? launch_timed(c, PROF_W2, bytes2, k_mfma_stream_q4<false, true>, g2, dim3(TL_THREADS), TL_LDS_BYTES, A)
+                   : launch_timed(c, PROF_W2, bytes2, k_mfma_stream_q4<false, false>, g2, dim3(TL_THREADS), TL_LDS_BYTES, A);
         if (rc) return rc;
     }
     return MOE_OK;
@@ -1121,7 +1129,7 @@ static int32_t launch_mfma(moe_layer *l, const std::vector<PassExpert> &experts,
     moe_ctx *c = l->ctx;
     const BlobLayout &b = l->lay;
     const int K = l->cfg.top_k;
-    if (c->mfma_form == 2 || batch * K > MF_MAX_PAIRS) return launch_mfma_stream(l, experts, w, batch);   // the older forms index pairs with one byte
+    if (c->mfma_form == 2 || batch * K > MF_MAX_PAIRS || b.scale_group > 0) return launch_mfma_stream(l, experts, w, batch);   // the older forms index pairs with one byte
     MfmaArgs A{};
     int n = 0, first = 0, max_tok = 0;
     for (const PassExpert &pe : experts) {
@@ -1258,8 +1266,10 @@ extern "C" int32_t moe_layer_step(moe_layer_t *l, moe_layer_t *next, const uint1
     const bool try_fused = c->token_path && batch == 1 && passes.size() == 1 && plan.access.size() <= 2 &&
                            (int)plan.access.size() == cf.top_k && !plan.victim_needed;
     bool fused_done = false;
-    const bool use_mfma = batch >= c->mfma_min_batch && cf.bits == 4 && cf.group == 64 && cf.scale_group == 0 && cf.hidden % MF_KC == 0 &&
-                          cf.ffn % MF_KC == 0;
+    // two-level metadata: a step of the streaming kernel stages one run's quad per row, so a run must cover the step
+    auto runs_ok = [&](const MatLayout &m) { return m.run_len == 0 || m.run_len == m.cols / (uint32_t)cf.group || m.run_len % TL_SG == 0; };
+    const bool use_mfma = batch >= c->mfma_min_batch && cf.bits == 4 && cf.group == 64 && cf.hidden % MF_KC == 0 &&
+                          cf.ffn % MF_KC == 0 && runs_ok(l->lay.m13) && runs_ok(l->lay.m2);
     bool sums_done = false;     // the direct-to-lane matrix-core form needs the group sums of h once per step
     for (size_t p = 0; p < passes.size(); ++p) {
         if (p > 0) {

@@ -500,19 +500,32 @@ def test_swap_eviction_mixtral_layer():
     model.close()
 
 
+def test_two_level_metadata_several_runs_on_the_matrix_cores():
+    """H=1024 and F=2048 give 16 and 32 groups per row; with runs of 8 groups a row has 2 and 4 runs, each of them one
+    step of the streaming matrix-core kernel."""
+    model = Model(2, 1024, 2048, 8, 2, None, 4, 2, 1e-5, max_batch=24, seed=73, scale_group=8)
+    B.moe_ctx_profile_enable(model.stack.ctx, True)
+    xs = W.hidden_ar1(73, 3, 24, 1024)
+    _, sim, errs = run_teacher_forced(model, xs, O.expert_ffn)
+    say(f"two-level, runs of 8, matrix cores: max abs {max(e[0] for e in errs):.2e} max rel-rms {max(e[1] for e in errs):.2e}")
+    model.close()
+
+
 @pytest.mark.parametrize("R,Bn,k,m,variant", [(256, 1, 2, 2, "token"), (2, 1, 2, 2, "token"), (2, 1, 2, 1, "general"), (2, 1, 2, 2, "one_launch"),
-                                              (2, 4, 4, 2, "general"), (256, 16, 4, 2, "general"), (4, 3, 8, 0, "general")])
+                                              (2, 4, 4, 2, "general"), (256, 16, 4, 2, "matrix"), (2, 40, 4, 2, "matrix"),
+                                              (4, 200, 2, 1, "matrix"), (4, 3, 8, 0, "general"), (2, 20, 4, 2, "gemv")])
 def test_small_stack_two_level_metadata(R, Bn, k, m, variant):
     """4-bit experts whose scales and zeros are themselves 8-bit codes (Sec. 4.2 "scale group size"): runs of R groups
     per row (R=2 gives 2 and 4 runs per row here, R=256 one), through the single-token kernels, the general GEMV
-    kernels, the one-launch kernel and batches (which stay on the GEMV kernels: the matrix-core path takes fp16 pairs)."""
+    kernels, the one-launch kernel, and batches on the matrix cores (and on the GEMV kernels, threshold raised)."""
     L, H, F = 3, 256, 512
     say(f"two-level metadata R={R} B={Bn} k={k} m={m} {variant}")
     model = Model(L, H, F, 8, 2, None, k, m, 1e-5, max_batch=Bn, seed=71, scale_group=R)
     B.moe_ctx_set_option(model.stack.ctx, "token_path", 0 if variant == "general" else 1)
     B.moe_ctx_set_option(model.stack.ctx, "fused", 1 if variant == "one_launch" else 0)
+    B.moe_ctx_set_option(model.stack.ctx, "mfma_min_batch", 1000 if variant == "gemv" else 16)
     assert model.stack.blob_bytes[0] == B.moe_expert_blob_bytes(H, F, 4, 64, R)
-    xs = W.hidden_ar1(71, 10, Bn, H)
+    xs = W.hidden_ar1(71, 10 if Bn < 100 else 2, Bn, H)
     _, sim, errs = run_teacher_forced(model, xs, O.expert_ffn)
     say(f"  max abs {max(e[0] for e in errs):.2e} max rel-rms {max(e[1] for e in errs):.2e}")
     model.close()
@@ -574,11 +587,12 @@ def test_prompt_sized_batches(Bn, k, T, form):
 
 @pytest.mark.parametrize("formats,scale_group,Bn", [([(2, 16), (3, 64)], 0, 300), ([(4, 64), (4, 64)], 256, 200)])
 def test_prompt_sized_batches_on_the_gemv_kernels(formats, scale_group, Bn):
-    """Formats the matrix-core kernels do not take (2-bit, 3-bit, two-level metadata) run a large batch through the
-    GEMV kernels, four tokens per entry and sixteen entries per launch."""
+    """Formats the matrix-core kernels do not take (2-bit, 3-bit; and 4-bit with the threshold raised) run a large
+    batch through the GEMV kernels, four tokens per entry and sixteen entries per launch."""
     L, H, F = 2, 256, 512
     say(f"prompt-sized batch on GEMV kernels B={Bn} formats={formats} scale_group={scale_group}")
     model = Model(L, H, F, 8, 2, formats, 4, 2, 1e-5, max_batch=Bn, seed=83, scale_group=scale_group)
+    B.moe_ctx_set_option(model.stack.ctx, "mfma_min_batch", 100000)
     xs = W.hidden_ar1(83, 1, Bn, H)
     _, sim, errs = run_teacher_forced(model, xs, O.expert_ffn)
     say(f"  max abs {max(e[0] for e in errs):.2e} max rel-rms {max(e[1] for e in errs):.2e}")
