@@ -273,8 +273,8 @@ int32_t moe_ctx_profile_read(moe_ctx_t *ctx, moe_profile_t *out);
  *                (grouped dequantize+GEMM); smaller batches, and other formats, use the GEMV kernels;
  *   "mfma_form"  which matrix-core kernels: 2 (default) persistent streaming kernels that round each dequantised
  *                weight once to fp16 before the multiply, as Sec. 4.2's fp16 experts do; 1 row-staging kernels that
- *                keep the codes exact and scale every group's product in fp32; 0 the direct-to-lane kernels.  All
- *                three meet the same output tolerance; they differ in speed;
+ *                keep the codes exact and scale every group's product in fp32 (batches of at most 64 tokens,
+ *                fp16 metadata; otherwise form 2 runs).  Both meet the output tolerance;
  *   "spec_head_mb" 0 (default): a speculative load copies the whole expert at once, as the paper describes;
  *                N > 0: it copies only the first N MiB, and the rest is fetched (like a demand load) when the next
  *                layer confirms the guess.  Decisions, traces and results are identical; only how many bytes a wrong

@@ -2,13 +2,9 @@
 // expert the step is a real contraction, U[t][r] = sum_k h[t][k] W^[r][k] over the tokens t of that expert.
 // 4-bit codes with group 64 (the batched configuration); other formats stay on the GEMV kernels.
 //
-// v_mfma_f32_32x32x16_f16 with M = tokens (A operand = activations, staged through LDS and shared by the
-// block's waves), N = 32 output rows per wave (B operand = weights, loaded straight from HBM into the
-// lane that feeds them: lane l supplies row l%32, codes 32*(l/32)..+31 of the current group, i.e. one uint4).
-// A lane's accumulators all belong to ONE output row (its column of D), so the group's scale and zero are two
-// per-lane scalars and the factorisation  sum (q - z) s h = s (sum q h - z sum h)  costs two FMAs per
-// accumulator and group; sum q h is exact in the MFMA (codes 0..15 as fp16, fp32 accumulation) and the
-// per-(token, group) sums of h come from a small table computed once per step.
+// This file: the shared argument types, the exact integer conversion of the codes, and the row-staging kernel
+// that scales every group's product in fp32 (GEMV-path accuracy).  The default, faster kernel is in
+// kernels_mfma_stream.h.
 //
 // D layout of the 32x32 MFMA: lane l, register i  ->  row (token) m = 8*(i/4) + 4*(l/32) + i%4, column l%32.
 #pragma once
@@ -19,8 +15,6 @@ namespace moe {
 typedef _Float16 h8_t __attribute__((ext_vector_type(8)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
 
-constexpr int MF_KC = 256;                   // codes per K chunk (4 groups)
-constexpr int MF_PITCH = MF_KC + 8;          // LDS row pitch in halves (16 B pad against bank conflicts)
 constexpr int MF_MAX_PAIRS = 256;            // (token, expert) pairs per step: batch * top_k
 
 struct MfmaEntry {
@@ -35,30 +29,12 @@ struct MfmaArgs {
     uint8_t pair[MF_MAX_PAIRS];              // row of a[.][F] of each pair (= b*K + j)
     float w[MF_MAX_PAIRS];                   // combine weight of each pair
     const uint16_t *act;                     // w1/w3: h [B][H];   w2: a [B*K][F]
-    const float *gsum;                       // per-(row of act, group of 64) sums of act
     uint16_t *a;                             // w1/w3 output
     float *yacc;                             // w2 output (accumulated)
     int32_t K, N;                            // contraction length, output rows of the matrix
     uint32_t stride, meta_off;               // row stride and offset of the (scale, zero) pairs
     uint64_t mat_off;                        // byte offset of the matrix inside the blob
 };
-
-// sums of groups of 64 consecutive fp16 values: out[v][g] = sum_i vec[v][64 g + i], one thread per (v, g)
-__global__ void k_group_sums(const uint16_t *vec, float *out, int n_vec, int K)
-{
-    const int i = blockIdx.x * blockDim.x + threadIdx.x, groups = K / 64;
-    if (i >= n_vec * groups) return;
-    const uint4 *p = reinterpret_cast<const uint4 *>(vec + (size_t)(i / groups) * K + (size_t)(i % groups) * 64);
-    float s = 0.f;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        const uint4 v = p[j];
-        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-        for (int q = 0; q < 4; ++q) s += (float)as_h2(w[q]).x + (float)as_h2(w[q]).y;
-    }
-    out[i] = s;
-}
 
 // 8 codes of one word as 8 exact fp16 integers, in the order of the contraction index
 __device__ __forceinline__ h8_t codes_to_h8(uint32_t w)
@@ -72,155 +48,6 @@ __device__ __forceinline__ h8_t codes_to_h8(uint32_t w)
     h8_t r;
     r[0] = t0.x; r[1] = t0.y; r[2] = t1.x; r[3] = t1.y; r[4] = t2.x; r[5] = t2.y; r[6] = t3.x; r[7] = t3.y;
     return r;
-}
-
-// W13 = true : a[pair][r] = silu(W1^ h)[r] * (W3^ h)[r] for the rows of this block and all tokens of the entry.
-// W13 = false: yacc[tok][r] += w * (W2^ a[pair])[r].
-// grid = (ceil(N / (32 WAVES)), entries); MT = 32-token tiles (1 or 2).
-// Software pipeline over K chunks: while chunk kc is multiplied, the weights of chunk kc+1 are already on
-// their way to registers and its activation tile to a second LDS buffer; one barrier per chunk.
-template <bool W13, int MT, int WAVES>
-__global__ __launch_bounds__(WAVES *WAVE) void k_mfma_q4(MfmaArgs A)
-{
-    constexpr int NS = W13 ? 2 : 1;                                   // weight streams
-    constexpr int THREADS = WAVES * WAVE;
-    constexpr int TILE_PIECES = MT * 32 * (MF_KC / 8);                // 16-byte pieces of one activation tile
-    constexpr int PPT = (TILE_PIECES + THREADS - 1) / THREADS;        // pieces per thread
-    constexpr int GS_ITEMS = MT * 32 * 4;
-    constexpr int GPT = (GS_ITEMS + THREADS - 1) / THREADS;
-    __shared__ __attribute__((aligned(16))) uint16_t tile[2][MT * 32 * MF_PITCH];
-    __shared__ __attribute__((aligned(16))) float gs[2][4][2][MT][16];   // [buffer][group][lane half][tile][register]
-    const MfmaEntry &en = A.e[blockIdx.y];
-    const int tid = threadIdx.x, lane = tid & 63, wv = uniform(tid >> 6);
-    const int col = lane & 31, kh = lane >> 5;
-    const int r = blockIdx.x * (WAVES * 32) + wv * 32 + col;          // this lane's output row
-    const int rc = min(r, A.N - 1);
-    const uint8_t *row[NS];
-#pragma unroll
-    for (int s = 0; s < NS; ++s) row[s] = en.blob + A.mat_off + (size_t)(W13 ? 2 * rc + s : rc) * A.stride;
-    const int n_chunks = A.K / MF_KC;
-
-    struct Wregs { uint4 q[NS][4]; uint32_t m[NS][4]; };
-    auto load_w = [&](Wregs &w, int kc) {
-#pragma unroll
-        for (int s = 0; s < NS; ++s)
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                // plain (temporal) loads: a wave instruction uses only 32 bytes of each 128-byte line here, the
-                // other three quarters are requested by the next three instructions and must still be found in cache
-                w.q[s][g] = reinterpret_cast<const uint4 *>(row[s])[(kc * 4 + g) * 2 + kh];
-                w.m[s][g] = reinterpret_cast<const uint32_t *>(row[s] + A.meta_off)[kc * 4 + g];
-            }
-    };
-    struct Tregs { uint4 v[PPT]; float g[GPT]; };
-    auto load_t = [&](Tregs &t, int kc) {
-#pragma unroll
-        for (int j = 0; j < PPT; ++j) {
-            const int i = tid + j * THREADS, tk = i / (MF_KC / 8), p = i % (MF_KC / 8);
-            t.v[j] = make_uint4(0, 0, 0, 0);
-            if (i < TILE_PIECES && tk < en.n_tok) {
-                const int src = W13 ? A.tok[en.first + tk] : A.pair[en.first + tk];
-                t.v[j] = *reinterpret_cast<const uint4 *>(A.act + (size_t)src * A.K + (size_t)kc * MF_KC + p * 8);
-            }
-        }
-#pragma unroll
-        for (int j = 0; j < GPT; ++j) {
-            const int i = tid + j * THREADS, tk = i / 4, g = i % 4;
-            t.g[j] = 0.f;
-            if (i < GS_ITEMS && tk < en.n_tok) {
-                const int src = W13 ? A.tok[en.first + tk] : A.pair[en.first + tk];
-                t.g[j] = A.gsum[(size_t)src * (A.K / 64) + kc * 4 + g];
-            }
-        }
-    };
-    auto store_t = [&](const Tregs &t, int buf) {
-#pragma unroll
-        for (int j = 0; j < PPT; ++j) {
-            const int i = tid + j * THREADS, tk = i / (MF_KC / 8), p = i % (MF_KC / 8);
-            if (i < TILE_PIECES) *reinterpret_cast<uint4 *>(&tile[buf][tk * MF_PITCH + p * 8]) = t.v[j];
-        }
-#pragma unroll
-        for (int j = 0; j < GPT; ++j) {
-            const int i = tid + j * THREADS, tk = i / 4, g = i % 4, tt = tk & 31;
-            // token tt of tile tk/32 is register (tt/8)*4 + tt%4 of lane half (tt/4)%2
-            if (i < GS_ITEMS) gs[buf][g][(tt >> 2) & 1][tk >> 5][(tt >> 3) * 4 + (tt & 3)] = t.g[j];
-        }
-    };
-
-    f32x16_t acc[NS][MT];
-#pragma unroll
-    for (int s = 0; s < NS; ++s)
-#pragma unroll
-        for (int t = 0; t < MT; ++t)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acc[s][t][i] = 0.f;
-
-    Wregs wc, wn;
-    Tregs tr;
-    load_w(wc, 0);
-    load_t(tr, 0);
-    store_t(tr, 0);
-    __syncthreads();
-    for (int kc = 0; kc < n_chunks; ++kc) {
-        const int buf = kc & 1, nk = min(kc + 1, n_chunks - 1);       // the last iteration re-requests its own chunk
-        load_w(wn, nk);
-        load_t(tr, nk);
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            h8_t b[NS][4];
-#pragma unroll
-            for (int s = 0; s < NS; ++s) {
-                b[s][0] = codes_to_h8(wc.q[s][g].x);
-                b[s][1] = codes_to_h8(wc.q[s][g].y);
-                b[s][2] = codes_to_h8(wc.q[s][g].z);
-                b[s][3] = codes_to_h8(wc.q[s][g].w);
-            }
-#pragma unroll
-            for (int t = 0; t < MT; ++t) {
-                f32x16_t cg[NS];
-#pragma unroll
-                for (int s = 0; s < NS; ++s)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) cg[s][i] = 0.f;
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const h8_t av = *reinterpret_cast<const h8_t *>(&tile[buf][(t * 32 + col) * MF_PITCH + g * 64 + kh * 32 + j * 8]);
-#pragma unroll
-                    for (int s = 0; s < NS; ++s) cg[s] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av, b[s][j], cg[s], 0, 0, 0);
-                }
-                float hs[16];
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const float4 v = *reinterpret_cast<const float4 *>(&gs[buf][g][kh][t][4 * i]);
-                    hs[4 * i] = v.x; hs[4 * i + 1] = v.y; hs[4 * i + 2] = v.z; hs[4 * i + 3] = v.w;
-                }
-#pragma unroll
-                for (int s = 0; s < NS; ++s) {
-                    const float sc = lo_half(wc.m[s][g]), nz = -hi_half(wc.m[s][g]);
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) acc[s][t][i] = fmaf(sc, fmaf(nz, hs[i], cg[s][i]), acc[s][t][i]);
-                }
-            }
-        }
-        store_t(tr, buf ^ 1);                                         // nobody reads that buffer during this chunk
-        __syncthreads();
-        wc = wn;
-    }
-    if (r >= A.N) return;
-#pragma unroll
-    for (int t = 0; t < MT; ++t)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int tok = t * 32 + 8 * (i / 4) + 4 * kh + (i % 4);
-            if (tok < en.n_tok) {
-                if (W13) {
-                    const _Float16 av = (_Float16)silu_mul(acc[0][t][i], acc[NS - 1][t][i]);
-                    A.a[(size_t)A.pair[en.first + tok] * A.N + r] = __builtin_bit_cast(uint16_t, av);
-                } else {
-                    atomicAdd(&A.yacc[(size_t)A.tok[en.first + tok] * A.N + r], A.w[en.first + tok] * acc[0][t][i]);
-                }
-            }
-        }
 }
 
 // ---------------------------------------------------------------------------------------------

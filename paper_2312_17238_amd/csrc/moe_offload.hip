@@ -105,8 +105,7 @@ struct moe_ctx {
     int32_t n_layers = 0;
     int32_t w13_blocks = 256, w2_rows = 32;
     uint32_t gate_seq = 0;              // sequence number of the last gate launch
-    float *gs_h = nullptr, *gs_a = nullptr;   // group sums of h and of a for the matrix-core path
-    int32_t mfma_form = 2;              // matrix-core kernels: 0 direct-to-lane, 1 row-streaming with fp32 group scaling, 2 persistent streaming form with fp16 weights
+    int32_t mfma_form = 2;              // matrix-core kernels: 2 persistent streaming form with fp16 weights, 1 row-staging form with fp32 group scaling
     int32_t mfma_min_batch = 16;        // batches at least this large use the matrix-core kernels (4-bit g64)
     uint64_t spec_head_bytes = 0;       // 0: a speculative load moves the whole expert at once (as the paper describes);
                                         // > 0: only this many leading bytes, the rest when the guess is confirmed
@@ -164,7 +163,7 @@ static bool layer_cfg_ok(const moe_layer_config_t *c)
            c->scale_group >= 0 && blob_layout(c->hidden, c->ffn, c->bits, c->group, c->scale_group).ok;
 }
 
-struct ScratchPlan { uint64_t staging, h, a, yacc, x0, x1, barrier, gs_h, gs_a, total; };
+struct ScratchPlan { uint64_t staging, h, a, yacc, x0, x1, barrier, total; };
 
 static ScratchPlan plan_scratch(const moe_ctx_config_t *c)
 {
@@ -177,8 +176,6 @@ static ScratchPlan plan_scratch(const moe_ctx_config_t *c)
     p.yacc = off; off += align_u64((uint64_t)c->max_batch * c->max_hidden * 4, 256);
     p.x0 = off;   off += align_u64((uint64_t)c->max_batch * c->max_hidden * 2, 256);
     p.x1 = off;   off += align_u64((uint64_t)c->max_batch * c->max_hidden * 2, 256);
-    p.gs_h = off; off += align_u64((uint64_t)c->max_batch * (c->max_hidden / 64) * 4, 256);
-    p.gs_a = off; off += align_u64((uint64_t)c->max_batch * c->max_top_k * (c->max_ffn / 64) * 4, 256);
     p.barrier = off; off += 4096;     // one flag per block of the persistent kernel (at most 1024 compute units)
     p.total = off;
     return p;
@@ -265,8 +262,6 @@ extern "C" int32_t moe_ctx_create(const moe_ctx_config_t *cfg, void *dev_arena, 
     c->xbuf[0] = reinterpret_cast<uint16_t *>(base + p.x0);
     c->xbuf[1] = reinterpret_cast<uint16_t *>(base + p.x1);
     c->barrier = reinterpret_cast<uint32_t *>(base + p.barrier);
-    c->gs_h = reinterpret_cast<float *>(base + p.gs_h);
-    c->gs_a = reinterpret_cast<float *>(base + p.gs_a);
     c->mfma_min_batch = env_int("MOE_MFMA_MIN_BATCH", 16);
     c->fused = env_int("MOE_FUSED", 0) != 0;
     hipError_t e = hipMemset(c->barrier, 0, 4096);
@@ -903,12 +898,6 @@ static int32_t launch_gate(moe_ctx *c, GateArgs ga, int32_t batch)
 #ifndef MOE_W2_G
 #define MOE_W2_G 4
 #endif
-#ifndef MOE_MFMA_W13_WAVES
-#define MOE_MFMA_W13_WAVES 4      // waves (32 output rows each) per block of the matrix-core w1/w3 kernel
-#endif
-#ifndef MOE_MFMA_W2_WAVES
-#define MOE_MFMA_W2_WAVES 2       // ... of the w2 kernel (fewer rows in total, so smaller blocks fill the chip)
-#endif
 #ifndef MOE_FUSED_G2
 #define MOE_FUSED_G2 8
 #endif
@@ -1124,12 +1113,13 @@ static int32_t launch_mfma_stream(moe_layer *l, const std::vector<PassExpert> &e
     return MOE_OK;
 }
 
-static int32_t launch_mfma(moe_layer *l, const std::vector<PassExpert> &experts, const float *w, int batch, bool first_pass)
+static int32_t launch_mfma(moe_layer *l, const std::vector<PassExpert> &experts, const float *w, int batch)
 {
     moe_ctx *c = l->ctx;
     const BlobLayout &b = l->lay;
     const int K = l->cfg.top_k;
-    if (c->mfma_form == 2 || batch * K > MF_MAX_PAIRS || b.scale_group > 0) return launch_mfma_stream(l, experts, w, batch);   // the older forms index pairs with one byte
+    // the row-staging form takes up to 64 tokens per expert, indexes pairs with one byte and reads fp16 pairs only
+    if (c->mfma_form == 2 || batch > 64 || batch * K > MF_MAX_PAIRS || b.scale_group > 0) return launch_mfma_stream(l, experts, w, batch);
     MfmaArgs A{};
     int n = 0, first = 0, max_tok = 0;
     for (const PassExpert &pe : experts) {
@@ -1146,51 +1136,31 @@ static int32_t launch_mfma(moe_layer *l, const std::vector<PassExpert> &experts,
         ++n;
     }
     const uint64_t bytes13 = (uint64_t)n * 2 * b.ffn * b.m13.row_stride, bytes2 = (uint64_t)n * b.hidden * b.m2.row_stride;
-    constexpr int W13W = MOE_MFMA_W13_WAVES, W2W = MOE_MFMA_W2_WAVES;
-    if (first_pass && c->mfma_form == 0) {
-        const int items = batch * (b.hidden / 64);
-        hipLaunchKernelGGL(k_group_sums, dim3((items + 255) / 256), dim3(256), 0, c->compute, c->h_buf, c->gs_h, batch, b.hidden);
-        HIPCHK(hipGetLastError());
-    }
-    A.act = c->h_buf; A.gsum = c->gs_h; A.a = c->a_buf; A.yacc = c->yacc;
+    A.act = c->h_buf; A.a = c->a_buf; A.yacc = c->yacc;
     A.K = b.hidden; A.N = b.ffn; A.stride = b.m13.row_stride; A.meta_off = b.m13.meta_off; A.mat_off = b.off_w13;
-    // LDS of the row-streaming form: 32 staged rows (codes + pairs) or the final reduction buffer
-    auto rows_lds = [&](int K, int mt) {
-        const int sg = std::min(K / 64, MF2_SEG);
+    // LDS: 32 staged rows (codes + pairs) or the final reduction buffer
+    auto rows_lds = [&](int Kdim, int mt) {
+        const int sg = std::min(Kdim / 64, MF2_SEG);
         return std::max<size_t>((size_t)32 * (sg * 32 + 16) + (size_t)32 * ((sg + 3) & ~3) * 4, (size_t)MF2_WAVES * mt * 16 * 64 * 4);
     };
-    const int mt = max_tok > 32 ? 2 : 1;
-    if (c->mfma_form == 1) {
-        static bool lds_attr_set = false;  // these kernels stage 72 KB: above the default dynamic LDS limit
-        if (!lds_attr_set) {
-            const int lim = 96 * 1024;
-            HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_rows_q4<true, 1>), hipFuncAttributeMaxDynamicSharedMemorySize, lim));
-            HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_rows_q4<true, 2>), hipFuncAttributeMaxDynamicSharedMemorySize, lim));
-            HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_rows_q4<false, 1>), hipFuncAttributeMaxDynamicSharedMemorySize, lim));
-            HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_rows_q4<false, 2>), hipFuncAttributeMaxDynamicSharedMemorySize, lim));
-            lds_attr_set = true;
-        }
-        const dim3 blkr(MF2_WAVES * WAVE), gr13((2 * b.ffn + 31) / 32, n), gr2((b.hidden + 31) / 32, n);
-        int32_t rr = mt == 2 ? launch_timed(c, PROF_W13, bytes13, k_mfma_rows_q4<true, 2>, gr13, blkr, rows_lds(b.hidden, 2), A)
-                             : launch_timed(c, PROF_W13, bytes13, k_mfma_rows_q4<true, 1>, gr13, blkr, rows_lds(b.hidden, 1), A);
-        if (rr) return rr;
-        A.act = c->a_buf; A.gsum = c->gs_a;
-        A.K = b.ffn; A.N = b.hidden; A.stride = b.m2.row_stride; A.meta_off = b.m2.meta_off; A.mat_off = b.off_w2;
-        return mt == 2 ? launch_timed(c, PROF_W2, bytes2, k_mfma_rows_q4<false, 2>, gr2, blkr, rows_lds(b.ffn, 2), A)
-                       : launch_timed(c, PROF_W2, bytes2, k_mfma_rows_q4<false, 1>, gr2, blkr, rows_lds(b.ffn, 1), A);
+    static bool lds_attr_set = false;  // these kernels stage 72 KB: above the default dynamic LDS limit
+    if (!lds_attr_set) {
+        const int lim = 96 * 1024;
+        HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_rows_q4<true, 1>), hipFuncAttributeMaxDynamicSharedMemorySize, lim));
+        HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_rows_q4<true, 2>), hipFuncAttributeMaxDynamicSharedMemorySize, lim));
+        HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_rows_q4<false, 1>), hipFuncAttributeMaxDynamicSharedMemorySize, lim));
+        HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_rows_q4<false, 2>), hipFuncAttributeMaxDynamicSharedMemorySize, lim));
+        lds_attr_set = true;
     }
-    const dim3 g13((b.ffn + W13W * 32 - 1) / (W13W * 32), n), blk13(W13W * WAVE);
-    int32_t rc = max_tok > 32 ? launch_timed(c, PROF_W13, bytes13, k_mfma_q4<true, 2, W13W>, g13, blk13, 0, A)
-                              : launch_timed(c, PROF_W13, bytes13, k_mfma_q4<true, 1, W13W>, g13, blk13, 0, A);
-    if (rc) return rc;
-    const int items = batch * K * (b.ffn / 64);
-    hipLaunchKernelGGL(k_group_sums, dim3((items + 255) / 256), dim3(256), 0, c->compute, c->a_buf, c->gs_a, batch * K, b.ffn);
-    HIPCHK(hipGetLastError());
-    A.act = c->a_buf; A.gsum = c->gs_a;
+    const int mt = max_tok > 32 ? 2 : 1;
+    const dim3 blkr(MF2_WAVES * WAVE), gr13((2 * b.ffn + 31) / 32, n), gr2((b.hidden + 31) / 32, n);
+    int32_t rr = mt == 2 ? launch_timed(c, PROF_W13, bytes13, k_mfma_rows_q4<true, 2>, gr13, blkr, rows_lds(b.hidden, 2), A)
+                         : launch_timed(c, PROF_W13, bytes13, k_mfma_rows_q4<true, 1>, gr13, blkr, rows_lds(b.hidden, 1), A);
+    if (rr) return rr;
+    A.act = c->a_buf;
     A.K = b.ffn; A.N = b.hidden; A.stride = b.m2.row_stride; A.meta_off = b.m2.meta_off; A.mat_off = b.off_w2;
-    const dim3 g2((b.hidden + W2W * 32 - 1) / (W2W * 32), n), blk2(W2W * WAVE);
-    return max_tok > 32 ? launch_timed(c, PROF_W2, bytes2, k_mfma_q4<false, 2, W2W>, g2, blk2, 0, A)
-                        : launch_timed(c, PROF_W2, bytes2, k_mfma_q4<false, 1, W2W>, g2, blk2, 0, A);
+    return mt == 2 ? launch_timed(c, PROF_W2, bytes2, k_mfma_rows_q4<false, 2>, gr2, blkr, rows_lds(b.ffn, 2), A)
+                   : launch_timed(c, PROF_W2, bytes2, k_mfma_rows_q4<false, 1>, gr2, blkr, rows_lds(b.ffn, 1), A);
 }
 
 static int32_t launch_ffn(moe_layer *l, const std::vector<FfnEntry> &entries, int nt, bool w13_only = false)
@@ -1268,9 +1238,7 @@ extern "C" int32_t moe_layer_step(moe_layer_t *l, moe_layer_t *next, const uint1
     bool fused_done = false;
     // two-level metadata: a step of the streaming kernel stages one run's quad per row, so a run must cover the step
     auto runs_ok = [&](const MatLayout &m) { return m.run_len == 0 || m.run_len == m.cols / (uint32_t)cf.group || m.run_len % TL_SG == 0; };
-    const bool use_mfma = batch >= c->mfma_min_batch && cf.bits == 4 && cf.group == 64 && cf.hidden % MF_KC == 0 &&
-                          cf.ffn % MF_KC == 0 && runs_ok(l->lay.m13) && runs_ok(l->lay.m2);
-    bool sums_done = false;     // the direct-to-lane matrix-core form needs the group sums of h once per step
+    const bool use_mfma = batch >= c->mfma_min_batch && cf.bits == 4 && cf.group == 64 && runs_ok(l->lay.m13) && runs_ok(l->lay.m2);
     for (size_t p = 0; p < passes.size(); ++p) {
         if (p > 0) {
             HIPCHK(hipEventRecord(c->ev_compute, c->compute));
@@ -1300,17 +1268,15 @@ extern "C" int32_t moe_layer_step(moe_layer_t *l, moe_layer_t *next, const uint1
                 group.push_back(pass_expert(i));
             }
             if (!group.empty()) {
-                rc = launch_mfma(l, group, w, batch, !sums_done);
+                rc = launch_mfma(l, group, w, batch);
                 if (rc) return rc;
-                sums_done = true;
             }
             for (int i : in_flight) {
                 PoolBuf &pb = c->bufs[plan.access[i].buf];
                 HIPCHK(hipStreamWaitEvent(c->compute, pb.ready, 0));
                 pb.pending = false;
-                rc = launch_mfma(l, std::vector<PassExpert>{pass_expert(i)}, w, batch, !sums_done);
+                rc = launch_mfma(l, std::vector<PassExpert>{pass_expert(i)}, w, batch);
                 if (rc) return rc;
-                sums_done = true;
             }
             continue;
         }
@@ -1498,7 +1464,7 @@ extern "C" int32_t moe_ctx_set_option(moe_ctx_t *c, const char *name, int32_t va
     else if (n == "token_path") c->token_path = value != 0;
     else if (n == "spec_head_mb" && value >= 0) c->spec_head_bytes = (uint64_t)value << 20;
     else if (n == "mfma_min_batch" && value >= 1) c->mfma_min_batch = value;
-    else if (n == "mfma_form" && value >= 0 && value <= 2) c->mfma_form = value;
+    else if (n == "mfma_form" && (value == 1 || value == 2)) c->mfma_form = value;
     else return fail(MOE_EINVAL, "moe_ctx_set_option: unknown option or bad value: %s = %d", name, value);
     return MOE_OK;
 }

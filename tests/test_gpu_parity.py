@@ -302,13 +302,12 @@ def test_single_token_kernel_variants_agree(formats):
         assert outs["general"][1] == outs[other][1]
 
 
-@pytest.mark.parametrize("form", [2, 1, 0])
+@pytest.mark.parametrize("form", [2, 1])
 @pytest.mark.parametrize("Bn,k", [(16, 4), (64, 4), (33, 8), (64, 2)])
 def test_small_stack_matrix_core_path(Bn, k, form):
     """Batches of 16 and more run 4-bit g64 experts as grouped dequantize+GEMM on the matrix cores
     (more than 32 tokens on one expert needs two token tiles; k=2 with 8 needed experts needs several passes).
-    All three kernel forms (2: fp16 weights, the default; 1: fp32 group scaling; 0: direct-to-lane) meet the
-    same bound against the oracle."""
+    Both kernel forms (2: fp16 weights, the default; 1: fp32 group scaling) meet the same bound against the oracle."""
     L, H, F = 3, 256, 512
     say(f"matrix-core stack B={Bn} k={k} form={form}")
     model = Model(L, H, F, 8, 2, None, k, 2, 1e-5, max_batch=Bn, seed=41)
@@ -320,10 +319,10 @@ def test_small_stack_matrix_core_path(Bn, k, form):
     model.close()
 
 
-@pytest.mark.parametrize("form,rel", [(0, 1e-4), (1, 1e-4), (2, 2e-3)])
+@pytest.mark.parametrize("form,rel", [(1, 1e-4), (2, 2e-3)])
 def test_matrix_core_path_agrees_with_gemv_path(form, rel):
     """The same batched steps through the GEMV kernels (threshold raised) and the matrix cores: identical
-    traces; outputs equal to within the summation-order noise of fp32 for the forms that scale groups in fp32,
+    traces; outputs equal to within the summation-order noise of fp32 for the form that scales groups in fp32,
     and to within the rounding of the weights to fp16 for the form that dequantises before the multiply."""
     L, H, F, Bn = 2, 256, 512, 24
     xs = W.hidden_ar1(43, 4, Bn, H)
