@@ -273,3 +273,11 @@ def test_error_codes():
     B.moe_layer_destroy(lay)
     B.moe_ctx_destroy(ctx)
     B.moe_ctx_destroy(big)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU; any other --gpus exits with a message instead of launching anything."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 2 and "one GPU" in r.stderr and r.stdout.strip() == ""
