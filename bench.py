@@ -26,7 +26,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 # HBM bytes per launch (read + written) of the dominant kernel from hardware counters, valid for the default
 # workload and launch shape only (4-bit g64 Mixtral experts, batch 1): FETCH_SIZE and WRITE_SIZE of two
 # rocprofv3 --pmc runs, scaled by the copy probe; see profiles/hbm_traffic_gemv_kernels_4bit.md
-PMC_TRAFFIC_W13_4BIT_B1 = 132_577_126
+PMC_TRAFFIC_W13_4BIT_B1 = 132_465_708
 PMC_TRAFFIC_FFN_4BIT_B1 = None   # filled from profiles/ once the counters of the fused kernel are collected
 LINK_PEAK_GBS = 64.0           # PCIe Gen5 x16, one direction, nominal
 

@@ -259,7 +259,7 @@ __device__ __forceinline__ RowGeom row_geom(uint32_t meta_off, int cols, int gro
 }
 
 #ifndef MOE_W13_WAVES
-#define MOE_W13_WAVES 4
+#define MOE_W13_WAVES 8
 #endif
 constexpr int W13_WAVES = MOE_W13_WAVES;
 
