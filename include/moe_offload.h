@@ -265,6 +265,8 @@ int32_t moe_ctx_profile_read(moe_ctx_t *ctx, moe_profile_t *out);
 /* Launch-shape tuning knobs (defaults are the measured best for Mixtral shapes on MI355X):
  *   "w13_blocks" total thread blocks of the w1/w3 kernel (default 256: one per compute unit);
  *   "w2_rows"    output rows per block of the w2 kernel (default 32);
+ *   "w2_token_rows" output rows per block of the single-token w2 kernel, at most 64 (default 0: hidden size /
+ *                compute units, 16 for Mixtral's width);
  *   "sync_wait"  1: wait for the gate result with hipStreamSynchronize instead of polling host-mapped memory;
  *   "token_path" 1 (default): a single-token step runs w2 with the combine and the residual add inside the
  *                kernel (one block sees both experts' rows; no atomics, no separate residual kernel);

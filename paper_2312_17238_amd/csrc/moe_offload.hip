@@ -104,6 +104,7 @@ struct moe_ctx {
     hipEvent_t ev_gate = nullptr, ev_compute = nullptr;
     int32_t n_layers = 0;
     int32_t w13_blocks = 256, w2_rows = 32;
+    int32_t w2_token_rows = 0;          // rows per block of the single-token w2 kernel; 0: hidden / compute units
     uint32_t gate_seq = 0;              // sequence number of the last gate launch
     int32_t mfma_form = 2;              // matrix-core kernels: 2 persistent streaming form with fp16 weights, 1 row-staging form with fp32 group scaling
     int32_t mfma_min_batch = 16;        // batches at least this large use the matrix-core kernels (4-bit g64)
@@ -241,6 +242,7 @@ extern "C" int32_t moe_ctx_create(const moe_ctx_config_t *cfg, void *dev_arena, 
     for (int i = 0; i < cfg->n_staging; ++i) c->pool.free_staging.push_back(i);
     c->w13_blocks = std::max(1, env_int("MOE_W13_BLOCKS", c->w13_blocks));
     c->w2_rows = std::max(4, env_int("MOE_W2_ROWS", c->w2_rows));
+    c->w2_token_rows = std::min(64, std::max(0, env_int("MOE_W2T_ROWS", c->w2_token_rows)));
     c->sync_wait = env_int("MOE_SYNC_WAIT", 0) != 0;
     if (c->host_only) {
         c->gate_out = static_cast<GateHostOut *>(calloc(1, sizeof(GateHostOut)));
@@ -901,6 +903,9 @@ static int32_t launch_gate(moe_ctx *c, GateArgs ga, int32_t batch)
 #ifndef MOE_FUSED_G2
 #define MOE_FUSED_G2 8
 #endif
+#ifndef MOE_W2T_G
+#define MOE_W2T_G 4
+#endif
 
 // Activation registers per (chunk, token) of each format: the budget that limits tokens per entry.
 template <int BITS> constexpr int act_regs() { return BITS == 3 ? 34 : (BITS == 2 ? 20 : 18); }   // (48: 4-bit codes, two-level metadata)
@@ -991,7 +996,7 @@ static int32_t launch_token_fmt(moe_layer *l, const FusedArgs &A0, bool one_laun
     const int kch = chunks_per_lane(b.hidden, BITS);
     const int cs = (b.ffn / Fmt<BITS>::CODES + 63) / 64;
     const int grid = c->n_cu;
-    const int rows = (b.hidden + grid - 1) / grid;
+    const int rows = (one_launch || c->w2_token_rows <= 0) ? (b.hidden + grid - 1) / grid : c->w2_token_rows;
     *done = false;
     const int items_per_wave = (A0.n_exp * b.ffn + grid * FUSED_WAVES - 1) / (grid * FUSED_WAVES);
     if (kch == 0 || kch > 2 || (BITS == 3 && kch > 1) || cs > 8 || cs * A0.n_exp > FUSED_WAVES || rows > 64 || grid < 1 || grid > 1024 ||
@@ -1004,7 +1009,7 @@ static int32_t launch_token_fmt(moe_layer *l, const FusedArgs &A0, bool one_laun
     if (!one_launch) {
         // w2 half only (k_w13 ran before): blocks of n_exp * CS waves, no barrier
         const uint64_t bytes2 = (uint64_t)A.n_exp * b.hidden * b.m2.row_stride;
-        return launch_timed(c, PROF_W2, bytes2, k_w2_token<BITS, 4>, dim3((b.hidden + rows - 1) / rows),
+        return launch_timed(c, PROF_W2, bytes2, k_w2_token<BITS, MOE_W2T_G>, dim3((b.hidden + rows - 1) / rows),
                             dim3(A.n_exp * cs * WAVE), 0, A);
     }
     A.barrier = c->barrier;
@@ -1459,6 +1464,7 @@ extern "C" int32_t moe_ctx_set_option(moe_ctx_t *c, const char *name, int32_t va
     const std::string n(name);
     if (n == "w13_blocks" && value >= 1) c->w13_blocks = value;
     else if (n == "w2_rows" && value >= 1 && value <= 256) c->w2_rows = value;
+    else if (n == "w2_token_rows" && value >= 0 && value <= 64) c->w2_token_rows = value;
     else if (n == "sync_wait") c->sync_wait = value != 0;
     else if (n == "fused") c->fused = value != 0;
     else if (n == "token_path") c->token_path = value != 0;
