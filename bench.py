@@ -95,7 +95,7 @@ def cpu_baseline(shape, formats, gates, gamma, kept, xs, budget_s=20.0):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=256)
+    ap.add_argument("--steps", type=int, default=512)
     ap.add_argument("--warmup", type=int, default=16)
     ap.add_argument("--workload", default="mixtral_stack",
                     choices=["tiny", "mixtral_layer", "mixtral_stack", "mixtral_stack_lowbit", "mixtral_stack_batched"])

@@ -84,8 +84,8 @@ struct ProfKind {
 struct Profiler {
     bool on = false;
     ProfKind kind[PROF_KINDS];
-    static constexpr size_t RING = 20000;      // pairs per kind before a drain (which synchronises) is needed
-    static constexpr size_t PREALLOC = 8192;   // pairs per kind created when profiling is switched on
+    static constexpr size_t RING = 65536;      // pairs per kind before a drain (which synchronises) is needed
+    static constexpr size_t PREALLOC = 16384;  // pairs per kind created when profiling is switched on
 };
 
 struct moe_ctx {
