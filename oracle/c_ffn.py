@@ -35,7 +35,7 @@ def _p(a: np.ndarray, dtype) -> np.ndarray:
 def expert_ffn(h_f16: np.ndarray, expert, group: int) -> np.ndarray:
     """Same contract as moe_oracle.expert_ffn, computed by the plain C loops."""
     lib = _load()
-    if len(expert[0]) == 4:
+    if len(expert[0]) == 5:
         return _expert_ffn_meta8(lib, h_f16, expert, group)
     (q1, s1, z1), (q3, s3, z3), (q2, s2, z2) = expert
     F, H = q1.shape
@@ -51,13 +51,13 @@ def expert_ffn(h_f16: np.ndarray, expert, group: int) -> np.ndarray:
 
 
 def _expert_ffn_meta8(lib, h_f16: np.ndarray, expert, group: int) -> np.ndarray:
-    """Two-level experts [(codes, scale codes, zero codes, meta)]: the second level is evaluated by the numpy
+    """Two-level experts [(codes, scale codes, zero codes, meta, groups per run)]: the second level is evaluated by the numpy
     oracle's definition (a few numbers per row), the loops over the weights run in C."""
     from . import moe_oracle as O
     F, H = expert[0][0].shape
     keep = [_p(h_f16, np.float16)]
-    for q, qs, qz, meta in expert:
-        s, z = O.meta8_scale_zero(qs, qz, meta)
+    for q, qs, qz, meta, run_len in expert:
+        s, z = O.meta8_scale_zero(qs, qz, meta, run_len)
         keep += [_p(q, np.uint8), _p(s, np.float64), _p(z, np.float64)]
     y = np.empty(H, dtype=np.float64)
     rc = lib.moe_oracle_expert_ffn_f64meta(H, F, group, *[a.ctypes.data for a in keep], y.ctypes.data)

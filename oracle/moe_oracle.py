@@ -130,32 +130,44 @@ META8_ZERO_LIMIT = 60000.0   # largest |zero| a run's fp16 pair may carry (fp16 
 
 def quantize_meta8(scale_f16: np.ndarray, zero_f16: np.ndarray, scale_group: int):
     """Second level (Sec. 4.2, "scale group size"): per row, runs of `scale_group` consecutive groups (the
-    whole row if it has fewer) quantize their fp16 scales, and separately their fp16 zeros, to 8 bits with
-    the min/max rule of quantize_minmax.  Returns (scale codes u8, zero codes u8, meta f16 [out, runs, 4])
-    with meta[r, j] = (scale, zero) of the scale codes followed by (scale, zero) of the zero codes."""
-    r = min(scale_group, scale_f16.shape[1])
-    qs, ss, sz = quantize_minmax(scale_f16.astype(np.float32), 8, r, zero_limit=META8_ZERO_LIMIT)
-    qz, zs, zz = quantize_minmax(zero_f16.astype(np.float32), 8, r, zero_limit=META8_ZERO_LIMIT)
-    return qs, qz, np.stack([ss, sz, zs, zz], axis=2)
+    whole row if it has fewer; a last run of a row may be shorter) quantize their fp16 scales, and separately
+    their fp16 zeros, to 8 bits with the min/max rule of quantize_minmax.  Returns (scale codes u8, zero codes u8,
+    meta f16 [out, runs, 4], groups per run) with meta[r, j] = (scale, zero) of the scale codes followed by
+    (scale, zero) of the zero codes."""
+    groups = scale_f16.shape[1]
+    r = min(scale_group, groups)
+    runs = -(-groups // r)
+
+    def level2(v16):
+        # a short last run is filled up with copies of its last value: its minimum and maximum stay what they are
+        v = np.pad(v16.astype(np.float32), ((0, 0), (0, runs * r - groups)), mode="edge")
+        q, s, z = quantize_minmax(v, 8, r, zero_limit=META8_ZERO_LIMIT)
+        return q[:, :groups], s, z
+
+    qs, ss, sz = level2(scale_f16)
+    qz, zs, zz = level2(zero_f16)
+    return qs, qz, np.stack([ss, sz, zs, zz], axis=2), r
 
 
-def meta8_scale_zero(scale_u8: np.ndarray, zero_u8: np.ndarray, meta_f16: np.ndarray):
+def meta8_scale_zero(scale_u8: np.ndarray, zero_u8: np.ndarray, meta_f16: np.ndarray, run_len: int):
     """The per-group scale and zero a two-level matrix stands for, fp64:
-    scale = (scale code - meta[..,1]) * meta[..,0], zero = (zero code - meta[..,3]) * meta[..,2]."""
-    r = scale_u8.shape[1] // meta_f16.shape[1]
-    m = np.repeat(meta_f16.astype(np.float64), r, axis=1)
+    scale = (scale code - meta[..,1]) * meta[..,0], zero = (zero code - meta[..,3]) * meta[..,2],
+    meta[:, j] belonging to groups j run_len .. j run_len + run_len - 1 of the row."""
+    groups = scale_u8.shape[1]
+    assert (meta_f16.shape[1] - 1) * run_len < groups <= meta_f16.shape[1] * run_len
+    m = np.repeat(meta_f16.astype(np.float64), run_len, axis=1)[:, :groups]
     return (scale_u8.astype(np.float64) - m[:, :, 1]) * m[:, :, 0], (zero_u8.astype(np.float64) - m[:, :, 3]) * m[:, :, 2]
 
 
 def dequantize_meta8(codes_u8: np.ndarray, scale_u8: np.ndarray, zero_u8: np.ndarray, meta_f16: np.ndarray,
-                     group: int) -> np.ndarray:
+                     run_len: int, group: int) -> np.ndarray:
     """W^[r,c] = (q[r,c] - zero[r, c//g]) * scale[r, c//g] with the two-level scale and zero, fp64."""
-    s, z = meta8_scale_zero(scale_u8, zero_u8, meta_f16)
+    s, z = meta8_scale_zero(scale_u8, zero_u8, meta_f16, run_len)
     return (codes_u8.astype(np.float64) - np.repeat(z, group, axis=1)) * np.repeat(s, group, axis=1)
 
 
 def dequantize_any(matrix, group: int) -> np.ndarray:
-    """(codes, scale f16, zero f16) or (codes, scale codes, zero codes, meta)."""
+    """(codes, scale f16, zero f16) or (codes, scale codes, zero codes, meta, groups per run)."""
     return dequantize(*matrix, group) if len(matrix) == 3 else dequantize_meta8(*matrix, group)
 
 

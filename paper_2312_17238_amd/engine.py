@@ -82,9 +82,10 @@ class Stack:
         return view
 
     def load_expert(self, layer: int, expert: int, matrix: int, codes: torch.Tensor, scale: torch.Tensor,
-                    zero: torch.Tensor, run_meta: Optional[torch.Tensor] = None) -> None:
+                    zero: torch.Tensor, run_meta: Optional[torch.Tensor] = None, run_len: Optional[int] = None) -> None:
         """One-level metadata: scale, zero fp16 per group.  Two-level (run_meta given): scale, zero are the byte
-        codes per group and run_meta the fp16 quads [out][runs][4]."""
+        codes per group and run_meta the fp16 quads [out][runs][4]; run_len, if given, is checked against the
+        groups per run the layer was configured with."""
         c = self._host(codes, "c")
         s = self._host(scale, "s")
         z = self._host(zero, "z")
@@ -93,6 +94,8 @@ class Stack:
             B.moe_layer_load_expert(self.layers[layer], expert, matrix, c.data_ptr(), s.data_ptr(), z.data_ptr())
         else:
             m = self._host(run_meta, "m")
+            if run_len is not None and run_len != min(self.cfgs[layer].scale_group, s.shape[1]):
+                raise ValueError(f"expert quantized with runs of {run_len} groups, layer configured for {self.cfgs[layer].scale_group}")
             assert c.dtype == torch.uint8 and s.dtype == torch.uint8 and z.dtype == torch.uint8 and m.dtype == torch.float16
             B.moe_layer_load_expert_2level(self.layers[layer], expert, matrix, c.data_ptr(), s.data_ptr(), z.data_ptr(),
                                            m.data_ptr())

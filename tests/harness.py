@@ -17,7 +17,7 @@ TOL_REL_RMS = 1e-3
 
 
 def to_np_expert(mats):
-    return [tuple(t.cpu().numpy() for t in m) for m in mats]
+    return [tuple(t.cpu().numpy() if hasattr(t, "cpu") else t for t in m) for m in mats]
 
 
 class Model:

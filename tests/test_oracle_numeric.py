@@ -220,25 +220,31 @@ def test_two_level_quantizer_hand_worked_examples(golden_dir):
         cases = json.load(f)["cases"]
     for c in cases:
         s16, z16 = np.array(c["scale"], dtype=np.float16), np.array(c["zero"], dtype=np.float16)
-        qs, qz, meta = O.quantize_meta8(s16, z16, c["scale_group"])
+        qs, qz, meta, run = O.quantize_meta8(s16, z16, c["scale_group"])
         assert qs.tolist() == c["scale_codes"] and qz.tolist() == c["zero_codes"]
-        assert meta.astype(np.float64).tolist() == c["meta"]
-        s, z = O.meta8_scale_zero(qs, qz, meta)
+        assert meta.astype(np.float64).tolist() == c["meta"] and run == min(c["scale_group"], s16.shape[1])
+        s, z = O.meta8_scale_zero(qs, qz, meta, run)
         assert s.tolist() == c["scale_decoded"] and z.tolist() == c["zero_decoded"]
 
 
 def test_two_level_dequantize_against_exact_rational_definition():
     """weight = (q - zero) * scale with scale = (scale code - m1) * m0 and zero = (zero code - m3) * m2, the four
-    m's shared by a run of consecutive groups of the row: exact rational arithmetic on a non-square matrix with
-    two runs per row and distinct metadata everywhere (a transposed or mis-indexed run shows)."""
+    m's shared by a run of consecutive groups of the row: exact rational arithmetic on non-square matrices with
+    several runs per row, the last one whole or shorter, and distinct metadata everywhere (a transposed or
+    mis-indexed run shows)."""
+    for groups, run in ((6, 3), (7, 4), (5, 2)):
+        check_two_level_exact(groups, run)
+
+
+def check_two_level_exact(groups, run):
     rng = np.random.default_rng(14)
-    rows, g, groups, run = 3, 4, 6, 3
+    rows, g, runs = 3, 4, -(-groups // run)
     q = rng.integers(0, 16, size=(rows, groups * g)).astype(np.uint8)
     qs = rng.integers(0, 256, size=(rows, groups)).astype(np.uint8)
     qz = rng.integers(0, 256, size=(rows, groups)).astype(np.uint8)
-    meta = np.stack([rng.uniform(1e-5, 1e-4, (rows, 2)), rng.uniform(-40, 0, (rows, 2)),
-                     rng.uniform(0.01, 0.06, (rows, 2)), rng.uniform(-5, 5, (rows, 2))], axis=2).astype(np.float16)
-    w = O.dequantize_meta8(q, qs, qz, meta, g)
+    meta = np.stack([rng.uniform(1e-5, 1e-4, (rows, runs)), rng.uniform(-40, 0, (rows, runs)),
+                     rng.uniform(0.01, 0.06, (rows, runs)), rng.uniform(-5, 5, (rows, runs))], axis=2).astype(np.float16)
+    w = O.dequantize_meta8(q, qs, qz, meta, run, g)
     for r in range(rows):
         for c in range(groups * g):
             j, k = c // g, c // g // run
@@ -255,9 +261,9 @@ def test_two_level_quantizer_codes_runs_and_roundtrip_bound():
     w = (rng.normal(size=(16, 8 * 64)) * 0.02).astype(np.float32)
     q, s16, z16 = O.quantize_minmax(w, 4, 64)                       # 8 groups per row
     for scale_group, runs in ((4, 2), (8, 1), (256, 1)):
-        qs, qz, meta = O.quantize_meta8(s16, z16, scale_group)
+        qs, qz, meta, r = O.quantize_meta8(s16, z16, scale_group)
         assert qs.dtype == np.uint8 and meta.shape == (16, runs, 4) and meta.dtype == np.float16
-        r = 8 // runs
+        assert r == 8 // runs
         for arr16, codes, j in ((s16, qs, 0), (z16, qz, 2)):
             v = arr16.astype(np.float64).reshape(16, runs, r)
             cg = codes.reshape(16, runs, r).astype(np.int64)
@@ -273,22 +279,47 @@ def test_two_level_quantizer_codes_runs_and_roundtrip_bound():
             dec = (cg - zero[..., None]) * step[..., None]
             assert (np.abs(dec - v) <= bound[..., None]).all()
             assert np.abs(dec - v).mean() > 0.1 * (step / 2).mean()
-        s, z = O.meta8_scale_zero(qs, qz, meta)
+        s, z = O.meta8_scale_zero(qs, qz, meta, r)
         assert np.array_equal(s.reshape(16, runs, r), (qs.reshape(16, runs, r) - meta[:, :, 1:2].astype(np.float64)) * meta[:, :, 0:1].astype(np.float64))
     # the weights the two-level form stands for stay close to the one-level ones
-    qs, qz, meta = O.quantize_meta8(s16, z16, 256)
-    w1, w2 = O.dequantize(q, s16, z16, 64), O.dequantize_meta8(q, qs, qz, meta, 64)
+    qs, qz, meta, r = O.quantize_meta8(s16, z16, 256)
+    w1, w2 = O.dequantize(q, s16, z16, 64), O.dequantize_meta8(q, qs, qz, meta, r, 64)
     assert np.abs(w1 - w2).max() < 0.02 * np.abs(w1).max()
 
 
-def test_two_level_c_loops_equal_numpy_dense():
+def test_two_level_quantizer_short_last_run_equals_runs_quantized_one_by_one():
+    """A row whose groups do not divide into whole runs (Sec. 4.2's 3-bit scheme: 224 groups of 64 along Mixtral's
+    14336-wide rows, scale group 128) ends in a shorter run, quantized from its own minimum and maximum: the
+    result equals quantizing every run of every row separately with the (pinned) first-level routine."""
+    rng = np.random.default_rng(17)
+    for bits, g, groups, scale_group in ((3, 64, 7, 4), (2, 16, 11, 4), (4, 64, 5, 2), (3, 64, 224, 128)):
+        rows = 5 if groups < 100 else 2
+        w = (rng.normal(size=(rows, groups * g)) * 0.02).astype(np.float32)
+        q, s16, z16 = O.quantize_minmax(w, bits, g)
+        qs, qz, meta, r = O.quantize_meta8(s16, z16, scale_group)
+        runs = -(-groups // scale_group)
+        assert r == scale_group and qs.shape == (rows, groups) and meta.shape == (rows, runs, 4)
+        for j in range(runs):
+            lo, hi = j * r, min(groups, (j + 1) * r)
+            for arr16, codes, k in ((s16, qs, 0), (z16, qz, 2)):
+                c1, s1, z1 = O.quantize_minmax(arr16[:, lo:hi].astype(np.float32), 8, hi - lo, zero_limit=O.META8_ZERO_LIMIT)
+                assert np.array_equal(codes[:, lo:hi], c1)
+                assert np.array_equal(meta[:, j, k].view(np.uint16), s1[:, 0].view(np.uint16))
+                assert np.array_equal(meta[:, j, k + 1].view(np.uint16), z1[:, 0].view(np.uint16))
+        s, z = O.meta8_scale_zero(qs, qz, meta, r)
+        for gi in range(groups):
+            m = meta[:, gi // r].astype(np.float64)
+            assert np.array_equal(s[:, gi], (qs[:, gi] - m[:, 1]) * m[:, 0]) and np.array_equal(z[:, gi], (qz[:, gi] - m[:, 3]) * m[:, 2])
+
+
+@pytest.mark.parametrize("bits,g,H,F,R", [(4, 64, 256, 512, 4), (3, 64, 320, 448, 4), (2, 16, 96, 160, 4)])
+def test_two_level_c_loops_equal_numpy_dense(bits, g, H, F, R):
     rng = np.random.default_rng(16)
-    H, F, g = 256, 512, 64
     ex = []
     for r, c in ((F, H), (F, H), (H, F)):
         w = (rng.normal(size=(r, c)) * 0.02).astype(np.float32)
-        q, s16, z16 = O.quantize_minmax(w, 4, g)
-        ex.append((q,) + O.quantize_meta8(s16, z16, 4))
+        q, s16, z16 = O.quantize_minmax(w, bits, g)
+        ex.append((q,) + O.quantize_meta8(s16, z16, R))
     for _ in range(3):
         h = rng.normal(size=H).astype(np.float16)
         a = O.expert_ffn(h, ex, g)

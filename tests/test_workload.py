@@ -48,15 +48,26 @@ def test_generator_second_level_matches_oracle_bit_for_bit():
     q, s, z = W.quantize_minmax(w, 4, 64)
     degenerate = 0
     for scale_group in (1, 2, 4, 256):                              # short runs hit the "stored as a constant" rule
-        qs, qz, meta = W.quantize_meta8(s, z, scale_group)
-        qso, qzo, metao = O.quantize_meta8(s.numpy(), z.numpy(), scale_group)
+        qs, qz, meta, r = W.quantize_meta8(s, z, scale_group)
+        qso, qzo, metao, ro = O.quantize_meta8(s.numpy(), z.numpy(), scale_group)
+        assert r == ro == min(scale_group, 8)
         assert (qs.numpy() == qso).all() and (qz.numpy() == qzo).all()
         assert (meta.numpy().view(np.uint16) == metao.view(np.uint16)).all()
         assert np.isfinite(metao.astype(np.float64)).all()
         degenerate += int((metao[:, :, 0] == 1).sum())
     assert degenerate > 0
     ex = W.quantized_expert(0, 0, 1, 256, 512, 4, 64, scale_group=256)
-    assert len(ex) == 3 and all(len(m) == 4 for m in ex) and ex[0][3].shape == (512, 1, 4) and ex[2][3].shape == (256, 1, 4)
+    assert len(ex) == 3 and all(len(m) == 5 for m in ex) and ex[0][3].shape == (512, 1, 4) and ex[2][3].shape == (256, 1, 4)
+    assert ex[0][4] == 4 and ex[2][4] == 8
+    # rows that end in a shorter run (3-bit and 2-bit schemes), against the oracle's quantizer
+    for bits, g, cols, scale_group in ((3, 64, 448, 4), (2, 16, 176, 8)):
+        w = W.expert_matrix(0, 1, 3, W.generate.W2, 64, cols)
+        q, s, z = W.quantize_minmax(w, bits, g)
+        qs, qz, meta, r = W.quantize_meta8(s, z, scale_group)
+        qso, qzo, metao, ro = O.quantize_meta8(s.numpy(), z.numpy(), scale_group)
+        assert r == ro == scale_group and meta.shape[1] == -(-(cols // g) // scale_group) and (cols // g) % scale_group != 0
+        assert (qs.numpy() == qso).all() and (qz.numpy() == qzo).all()
+        assert (meta.numpy().view(np.uint16) == metao.view(np.uint16)).all()
 
 
 def test_layer_formats():

@@ -139,10 +139,9 @@ def quantize_minmax(w: torch.Tensor, bits: int, group: int, zero_limit=None):
 
 
 def run_length(groups: int, scale_group: int) -> int:
-    """Groups per run of the second quantization level: scale_group, or the whole row if it has fewer groups."""
-    r = min(scale_group, groups)
-    assert groups % r == 0, (groups, scale_group)
-    return r
+    """Groups per run of the second quantization level: scale_group, or the whole row if it has fewer groups.
+    A row whose groups do not divide into whole runs ends in a shorter one."""
+    return min(scale_group, groups)
 
 
 def quantize_meta8(scale_f16: torch.Tensor, zero_f16: torch.Tensor, scale_group: int):
@@ -150,19 +149,29 @@ def quantize_meta8(scale_f16: torch.Tensor, zero_f16: torch.Tensor, scale_group:
     of a row are themselves quantized to 8 bits with the same min/max rule, in runs of `scale_group`
     consecutive groups of that row (the whole row if it has fewer), each run with an fp16 (scale, zero) of its own.
 
-    Returns (scale codes u8 [out, in/g], zero codes u8 [out, in/g], meta fp16 [out, runs, 4]) with
+    Returns (scale codes u8 [out, in/g], zero codes u8 [out, in/g], meta fp16 [out, runs, 4], groups per run) with
     meta[r, j] = (scale of the scale codes, zero of the scale codes, scale of the zero codes, zero of the zero codes).
     """
-    r = run_length(scale_f16.shape[1], scale_group)
-    qs, ss, sz = quantize_minmax(scale_f16.to(torch.float32), 8, r, META8_ZERO_LIMIT)
-    qz, zs, zz = quantize_minmax(zero_f16.to(torch.float32), 8, r, META8_ZERO_LIMIT)
-    return qs, qz, torch.stack([ss, sz, zs, zz], dim=2).contiguous()
+    groups = scale_f16.shape[1]
+    r = run_length(groups, scale_group)
+    runs = (groups + r - 1) // r
+
+    def level2(v16):
+        v = v16.to(torch.float32)
+        if runs * r > groups:      # short last run: repeat its last value, which leaves its minimum and maximum alone
+            v = torch.cat([v, v[:, -1:].expand(-1, runs * r - groups)], dim=1)
+        q, s, z = quantize_minmax(v, 8, r, META8_ZERO_LIMIT)
+        return q[:, :groups].contiguous(), s, z
+
+    qs, ss, sz = level2(scale_f16)
+    qz, zs, zz = level2(zero_f16)
+    return qs, qz, torch.stack([ss, sz, zs, zz], dim=2).contiguous(), r
 
 
 def quantized_expert(seed: int, layer: int, expert: int, hidden: int, ffn: int, bits: int, group: int,
                      device="cpu", scale_group: int = 0):
     """[(codes, scale, zero)] for matrices w1, w3, w2 of one expert; with scale_group > 0
-    [(codes, scale codes, zero codes, meta)] (see quantize_meta8)."""
+    [(codes, scale codes, zero codes, meta, groups per run)] (see quantize_meta8)."""
     out = []
     for m in (W1, W3, W2):
         w = expert_matrix(seed, layer, expert, m, hidden, ffn, device)
