@@ -100,12 +100,14 @@ typedef struct {
     float   rms_eps;          /* > 0: RMSNorm with this eps in front of the gate; 0: gate sees x */
     int32_t init_policy;      /* 0: cache starts empty; 1: experts 0..k-1 resident after loading */
     int32_t flags;            /* MOE_LAYER_*                                                     */
-    int32_t scale_group;      /* 0: one fp16 (scale, zero) pair per group.  R > 0 (a power of two, 4-bit codes
-                                 only): two-level metadata (Sec. 4.2 "scale group size") -- per group an 8-bit
-                                 scale code and an 8-bit zero code, per run of R consecutive groups of a row
-                                 (the whole row if it has fewer; else R must divide its group count) four fp16:
+    int32_t scale_group;      /* 0: one fp16 (scale, zero) pair per group.  R > 0 (a power of two; with 2-bit
+                                 codes at least 4 unless a row has no more than R groups): two-level metadata
+                                 (Sec. 4.2 "scale group size") -- per group an 8-bit scale code and an 8-bit
+                                 zero code, per run of R consecutive groups of a row (the whole row if it has
+                                 fewer; the last run of a row may be shorter) four fp16:
                                  scale = (scale code - m[1]) * m[0], zero = (zero code - m[3]) * m[2]; the
-                                 weight is (code - zero) * scale as before.  4.25 bits per weight            */
+                                 weight is (code - zero) * scale as before.  4.25 / 3.25 / 3.0 bits per weight
+                                 for 4-bit g64, 3-bit g64, 2-bit g16, plus 8 bytes per run                   */
 } moe_layer_config_t;
 
 typedef struct {
@@ -184,7 +186,7 @@ int32_t moe_layer_destroy(moe_layer_t *layer);
 int32_t moe_layer_load_expert(moe_layer_t *layer, int32_t expert, int32_t matrix, const uint8_t *codes,
                               const uint16_t *scale_f16, const uint16_t *zero_f16);
 /* The same for a layer with two-level metadata (scale_group > 0).  scale_code, zero_code: one byte per group,
- * [out][in/group]; run_meta: fp16 bits, [out][runs][4] with runs = max(1, (in/group) / scale_group), the four
+ * [out][in/group]; run_meta: fp16 bits, [out][runs][4] with runs = ceil((in/group) / scale_group), the four
  * numbers of moe_layer_config_t.scale_group in that order.  All host memory, read during the call only. */
 int32_t moe_layer_load_expert_2level(moe_layer_t *layer, int32_t expert, int32_t matrix, const uint8_t *codes,
                                      const uint8_t *scale_code, const uint8_t *zero_code, const uint16_t *run_meta_f16);

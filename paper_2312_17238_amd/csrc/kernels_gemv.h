@@ -1,5 +1,6 @@
 // Fused dequantize+GEMV kernels of the expert FFN for 4-bit, 3-bit and 2-bit group-quantized weights
-// (formats of Sec. 4.2 with fp16 scale and zero per group).
+// (formats of Sec. 4.2 with fp16 scale and zero per group: Fmt<4>, Fmt<3>, Fmt<2>; or with 8-bit scale and zero
+// codes per group and an fp16 quad per run of groups, its "scale group size": Fmt<48>, Fmt<38>, Fmt<28>).
 //
 // Dequantization is never materialised.  With W^ = (q - z) s per group,
 //     sum_i W^_i h_i = s * (sum_i q_i h_i - z * sum_i h_i),
@@ -227,10 +228,11 @@ struct Fmt<3> {
         a.bias_dot = bd;
         a.hsum = hs;
     }
-    static __device__ __forceinline__ float contrib(const Row &r, const Act &a, bool live)
+    // sum of code * activation over the group, the field biases already taken off
+    static __device__ __forceinline__ float code_dot(const uint4 &ra, const uint2 &rb, const Act &a)
     {
-        const uint32_t A[4] = {r.a.x, r.a.y, r.a.z, r.a.w};
-        const uint32_t B[2] = {r.b.x, r.b.y};
+        const uint32_t A[4] = {ra.x, ra.y, ra.z, ra.w};
+        const uint32_t B[2] = {rb.x, rb.y};
         float d = -a.bias_dot;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
@@ -240,8 +242,95 @@ struct Fmt<3> {
             const uint32_t t = and_or(lo, 0x33333333u, hb & 0x44444444u);
             d = dot_word4(t, a.h + 4 * j, d);
         }
+        return d;
+    }
+    static __device__ __forceinline__ float contrib(const Row &r, const Act &a, bool live)
+    {
+        const float d = code_dot(r.a, r.b, a);
         const float s = live ? lo_half(r.m) : 0.f;
         return s * fmaf(-hi_half(r.m), a.hsum, d);
+    }
+};
+
+// Scale and zero of one group from its byte pair (scale code in the low byte) and its run's quad.
+__device__ __forceinline__ void decode_meta8(uint32_t pair, const uint2 &quad, float &s, float &z)
+{
+    s = ((float)(pair & 0xffu) - hi_half(quad.x)) * lo_half(quad.x);
+    z = ((float)((pair >> 8) & 0xffu) - hi_half(quad.y)) * lo_half(quad.y);
+}
+
+// 3-bit with two-level metadata: the codes and activations of Fmt<3>, scale and zero as in Fmt<48>.
+template <>
+struct Fmt<38> {
+    static constexpr int CODES = 64;
+    struct Row { uint4 a; uint2 b; uint32_t m; uint2 quad; };
+    using Act = Fmt<3>::Act;
+    static __device__ __forceinline__ void load(Row &r, const uint8_t *row, const RowGeom &g, int c)
+    {
+        r.a = ldw4(row, c);
+        r.b = ldw2(row + g.b_off, c);
+        r.m = *reinterpret_cast<const uint16_t *>(row + g.meta_off + 2 * c);
+        r.quad = *reinterpret_cast<const uint2 *>(row + g.meta2_off + 8 * (c >> g.run_shift));
+    }
+    static __device__ __forceinline__ void load_act(Act &a, const uint16_t *vec, int c, bool live) { Fmt<3>::load_act(a, vec, c, live); }
+    static __device__ __forceinline__ float contrib(const Row &r, const Act &a, bool live)
+    {
+        const float d = Fmt<3>::code_dot(r.a, r.b, a);
+        float s, z;
+        decode_meta8(r.m, r.quad, s, z);
+        return (live ? s : 0.f) * fmaf(-z, a.hsum, d);
+    }
+};
+
+// 2-bit with two-level metadata: chunk = 64 codes = four groups = one uint4 of code words (no longer interleaved
+// with metadata), four byte pairs (one uint2) and the quad of the run the four groups lie in.
+template <>
+struct Fmt<28> {
+    static constexpr int CODES = 64;
+    struct Row { uint4 q; uint2 m; uint2 quad; };
+    struct Act { h2_t h[32]; float bias_dot[4], hsum[4]; };
+    static __device__ __forceinline__ void load(Row &r, const uint8_t *row, const RowGeom &g, int c)
+    {
+        r.q = ldw4(row, c);
+        r.m = ldw2(row + g.meta_off, c);
+        r.quad = *reinterpret_cast<const uint2 *>(row + g.meta2_off + 8 * ((4 * c) >> g.run_shift));
+    }
+    static __device__ __forceinline__ void load_act(Act &a, const uint16_t *vec, int c, bool live)
+    {
+        const uint4 *p = reinterpret_cast<const uint4 *>(vec + (size_t)c * CODES);
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            float bd = 0.f, hs = 0.f;
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const uint4 v = live ? p[2 * g + i] : make_uint4(0, 0, 0, 0);
+                const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int n = 4 * i + j;
+                    a.h[8 * g + n] = as_h2(w[j]);
+                    const float s = (float)a.h[8 * g + n].x + (float)a.h[8 * g + n].y;
+                    hs += s;
+                    bd += Fmt<2>::bias_of(n) * s;
+                }
+            }
+            a.bias_dot[g] = bd;
+            a.hsum[g] = hs;
+        }
+    }
+    static __device__ __forceinline__ float contrib(const Row &r, const Act &a, bool live)
+    {
+        const uint32_t w[4] = {r.q.x, r.q.y, r.q.z, r.q.w};
+        const uint32_t pr[4] = {r.m.x, r.m.x >> 16, r.m.y, r.m.y >> 16};
+        float acc = 0.f;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const float d = Fmt<2>::dot_word2(w[g], a.h + 8 * g, -a.bias_dot[g]);
+            float s, z;
+            decode_meta8(pr[g], r.quad, s, z);
+            acc = fmaf(s, fmaf(-z, a.hsum[g], d), acc);
+        }
+        return live ? acc : 0.f;
     }
 };
 
@@ -250,7 +339,7 @@ __device__ __forceinline__ RowGeom row_geom(uint32_t meta_off, int cols, int gro
 {
     RowGeom g;
     g.meta_off = meta_off;
-    g.b_off = BITS == 3 ? (uint32_t)(cols / 64) * 16u : 0u;
+    g.b_off = (BITS == 3 || BITS == 38) ? (uint32_t)(cols / 64) * 16u : 0u;
     g.gshift = (group == 32) ? 0 : (group == 64 ? 1 : 2);
     const int groups = cols / group;
     g.meta2_off = (meta_off + 2u * groups + 7u) & ~7u;
@@ -258,20 +347,15 @@ __device__ __forceinline__ RowGeom row_geom(uint32_t meta_off, int cols, int gro
     return g;
 }
 
-#ifndef MOE_W13_WAVES
-#define MOE_W13_WAVES 8
-#endif
-constexpr int W13_WAVES = MOE_W13_WAVES;
-
-// K2: a[pair][r] = silu(W1^ h)[r] * (W3^ h)[r].  grid = (row blocks, entries); a wave walks rows
-// r = wave_id, wave_id + n_waves, ... with G of them in flight; KCH = chunks per lane per row.
-template <int BITS, int KCH, int NT, int G>
-__global__ __launch_bounds__(W13_WAVES *WAVE) void k_w13(FfnArgs A)
+// K2: a[pair][r] = silu(W1^ h)[r] * (W3^ h)[r].  grid = (row blocks, entries), WAVES waves per block; a wave
+// walks rows r = wave_id, wave_id + n_waves, ... with G of them in flight; KCH = chunks per lane per row.
+template <int BITS, int KCH, int NT, int G, int WAVES>
+__global__ __launch_bounds__(WAVES *WAVE) void k_w13(FfnArgs A)
 {
     using F = Fmt<BITS>;
     const FfnEntry &en = A.e[blockIdx.y];
     const int lane = threadIdx.x & 63;
-    const int wave = uniform(blockIdx.x * W13_WAVES + (threadIdx.x >> 6)), n_waves = gridDim.x * W13_WAVES;
+    const int wave = uniform(blockIdx.x * WAVES + (threadIdx.x >> 6)), n_waves = gridDim.x * WAVES;
     const int n_chunks = A.H / F::CODES;
     const RowGeom geo = row_geom<BITS>(A.meta13, A.H, A.group, A.scale_group);
     const uint8_t *base = en.blob;

@@ -22,10 +22,12 @@
 // bits of two such words and B_i = sum_j ((T_4i+j >> 2) & 0x11111111) << j the third bits of four, so a
 // decoder rebuilds T_j with three bit operations and reuses the 4-bit arithmetic.  3.0 bits per weight.
 //
-// Two-level metadata (4-bit only, Sec. 4.2 "scale group size"): the row's codes are followed by one
-// (scale code, zero code) byte pair per group, then, 8-byte aligned, one fp16 quad per run of scale_group
-// consecutive groups (the whole row if it has fewer): (step of the scale codes, zero of the scale codes,
-// step of the zero codes, zero of the zero codes).  4.25 bits per weight plus 8 bytes per run.
+// Two-level metadata (Sec. 4.2 "scale group size"): the row's codes are followed by one (scale code, zero code)
+// byte pair per group, then, 8-byte aligned, one fp16 quad per run of scale_group consecutive groups (the whole
+// row if it has fewer; the last run of a row may be shorter): (step of the scale codes, zero of the scale codes,
+// step of the zero codes, zero of the zero codes).  4.25 / 3.25 / 3.0 bits per weight for the 4-bit g64, 3-bit g64
+// and 2-bit g16 codes, plus 8 bytes per run.  The codes are laid out as above, except that the 2-bit words are
+// no longer interleaved with metadata: word g holds group g.
 #pragma once
 #include <cstdint>
 #include <cstring>
@@ -57,12 +59,12 @@ inline MatLayout mat_layout(uint32_t rows, uint32_t cols, int bits, int group, i
     m.rows = rows;
     m.cols = cols;
     uint32_t groups = cols / group;
-    if (scale_group > 0) {                 // 4-bit codes, byte pairs, per-run quads
-        m.code_bytes = cols / 2;
+    if (scale_group > 0) {                 // codes, byte pairs, per-run quads
+        m.code_bytes = bits == 4 ? cols / 2 : (bits == 3 ? groups * 24 : groups * 4);
         m.meta_off = m.code_bytes;
         m.run_len = groups < (uint32_t)scale_group ? groups : (uint32_t)scale_group;
         m.meta2_off = align_up(m.meta_off + groups * 2, 8);
-        m.row_stride = align_up(m.meta2_off + groups / m.run_len * 8, 16);
+        m.row_stride = align_up(m.meta2_off + (groups + m.run_len - 1) / m.run_len * 8, 16);
     } else if (bits == 2) {                       // interleaved: 8 bytes per group of 16
         m.code_bytes = groups * 8;
         m.meta_off = 0;
@@ -87,13 +89,14 @@ inline bool format_supported(int bits, int group)
     return false;
 }
 
-// scale_group: 0, or a power of two with 4-bit codes; a row's groups must then split into whole runs
+// scale_group: 0, or a power of two.  The 2-bit kernels read four groups (64 codes) per lane, which must not
+// straddle runs: there a run is at least four groups, or the whole row.
 inline bool scale_group_supported(int bits, int group, int scale_group, int cols)
 {
     if (scale_group == 0) return true;
-    if (bits != 4 || scale_group < 1 || (scale_group & (scale_group - 1))) return false;
+    if (scale_group < 1 || (scale_group & (scale_group - 1))) return false;
     const int groups = cols / group;
-    return groups <= scale_group || groups % scale_group == 0;
+    return bits != 2 || groups <= scale_group || scale_group >= 4;
 }
 
 inline BlobLayout blob_layout(int32_t hidden, int32_t ffn, int32_t bits, int32_t group, int32_t scale_group = 0)
@@ -124,76 +127,104 @@ inline const MatLayout &mat_of(const BlobLayout &b, int matrix) { return matrix 
 
 // ---- packing one row ------------------------------------------------------------------------
 
+// 8 consecutive 4-bit (or 3-bit, `mask` 7) codes as one word of the 4-bit layout
+inline uint32_t word_of_8(const uint8_t *c, uint32_t mask)
+{
+    uint32_t v = 0;
+    for (int n = 0; n < 4; ++n)
+        v |= (uint32_t)(c[2 * n] & mask) << (4 * n) | (uint32_t)(c[2 * n + 1] & mask) << (16 + 4 * n);
+    return v;
+}
+
+// 16 consecutive 2-bit codes as one word
+inline uint32_t word_of_16(const uint8_t *c)
+{
+    uint32_t v = 0;
+    for (int n = 0; n < 8; ++n)
+        v |= (uint32_t)(c[2 * n] & 3) << (2 * n) | (uint32_t)(c[2 * n + 1] & 3) << (16 + 2 * n);
+    return v;
+}
+
+// the 4-bit code words of a row, or the regions A and B of a 3-bit row
+inline void pack_codes_43(int bits, uint32_t cols, const uint8_t *codes, uint32_t *w)
+{
+    if (bits == 4) {
+        for (uint32_t i = 0; i < cols / 8; ++i) w[i] = word_of_8(codes + 8 * i, 15);
+        return;
+    }
+    const uint32_t groups = cols / 64;
+    uint32_t *ra = w, *rb = w + groups * 4;
+    for (uint32_t g = 0; g < groups; ++g) {
+        uint32_t t[8];
+        for (int j = 0; j < 8; ++j) t[j] = word_of_8(codes + 64 * g + 8 * j, 7);
+        for (int i = 0; i < 4; ++i) ra[4 * g + i] = (t[2 * i] & 0x33333333u) | (t[2 * i + 1] & 0x33333333u) << 2;
+        for (int i = 0; i < 2; ++i) {
+            uint32_t v = 0;
+            for (int j = 0; j < 4; ++j) v |= ((t[4 * i + j] >> 2) & 0x11111111u) << j;
+            rb[2 * g + i] = v;
+        }
+    }
+}
+
 inline void pack_row(const BlobLayout &b, const MatLayout &m, const uint8_t *codes, const uint16_t *scale,
                      const uint16_t *zero, uint8_t *dst)
 {
     const uint32_t cols = m.cols, groups = cols / b.group;
     uint32_t *w = reinterpret_cast<uint32_t *>(dst);
-    if (b.bits == 4) {
-        for (uint32_t i = 0; i < cols / 8; ++i) {
-            const uint8_t *c = codes + 8 * i;
-            uint32_t v = 0;
-            for (int n = 0; n < 4; ++n)
-                v |= (uint32_t)(c[2 * n] & 15) << (4 * n) | (uint32_t)(c[2 * n + 1] & 15) << (16 + 4 * n);
-            w[i] = v;
-        }
-    } else if (b.bits == 2) {
+    if (b.bits == 2) {
         for (uint32_t g = 0; g < groups; ++g) {
-            const uint8_t *c = codes + 16 * g;
-            uint32_t v = 0;
-            for (int n = 0; n < 8; ++n)
-                v |= (uint32_t)(c[2 * n] & 3) << (2 * n) | (uint32_t)(c[2 * n + 1] & 3) << (16 + 2 * n);
-            w[2 * g] = v;
+            w[2 * g] = word_of_16(codes + 16 * g);
             w[2 * g + 1] = (uint32_t)scale[g] | (uint32_t)zero[g] << 16;
         }
         return;
-    } else {  // 3-bit: regions A and B per group of 64
-        uint32_t *ra = w, *rb = w + groups * 4;
-        for (uint32_t g = 0; g < groups; ++g) {
-            const uint8_t *c = codes + 64 * g;
-            uint32_t t[8];
-            for (int j = 0; j < 8; ++j) {
-                uint32_t v = 0;
-                for (int n = 0; n < 4; ++n)
-                    v |= (uint32_t)(c[8 * j + 2 * n] & 7) << (4 * n) | (uint32_t)(c[8 * j + 2 * n + 1] & 7) << (16 + 4 * n);
-                t[j] = v;
-            }
-            for (int i = 0; i < 4; ++i) ra[4 * g + i] = (t[2 * i] & 0x33333333u) | (t[2 * i + 1] & 0x33333333u) << 2;
-            for (int i = 0; i < 2; ++i) {
-                uint32_t v = 0;
-                for (int j = 0; j < 4; ++j) v |= ((t[4 * i + j] >> 2) & 0x11111111u) << j;
-                rb[2 * g + i] = v;
-            }
-        }
     }
+    pack_codes_43(b.bits, cols, codes, w);
     uint32_t *meta = reinterpret_cast<uint32_t *>(dst + m.meta_off);
     for (uint32_t g = 0; g < groups; ++g) meta[g] = (uint32_t)scale[g] | (uint32_t)zero[g] << 16;
 }
 
-// two-level metadata: codes as in the 4-bit layout, then the byte pairs, then the per-run quads
+// two-level metadata: the codes, then the byte pairs, then the per-run quads
 inline void pack_row_meta8(const BlobLayout &b, const MatLayout &m, const uint8_t *codes, const uint8_t *scale_code,
                            const uint8_t *zero_code, const uint16_t *run_meta, uint8_t *dst)
 {
     const uint32_t cols = m.cols, groups = cols / b.group;
     uint32_t *w = reinterpret_cast<uint32_t *>(dst);
-    for (uint32_t i = 0; i < cols / 8; ++i) {
-        const uint8_t *c = codes + 8 * i;
-        uint32_t v = 0;
-        for (int n = 0; n < 4; ++n)
-            v |= (uint32_t)(c[2 * n] & 15) << (4 * n) | (uint32_t)(c[2 * n + 1] & 15) << (16 + 4 * n);
-        w[i] = v;
-    }
+    if (b.bits == 2)
+        for (uint32_t g = 0; g < groups; ++g) w[g] = word_of_16(codes + 16 * g);
+    else
+        pack_codes_43(b.bits, cols, codes, w);
     uint8_t *pairs = dst + m.meta_off;
     for (uint32_t g = 0; g < groups; ++g) { pairs[2 * g] = scale_code[g]; pairs[2 * g + 1] = zero_code[g]; }
     memset(pairs + 2 * groups, 0, m.meta2_off - (m.meta_off + 2 * groups));
-    memcpy(dst + m.meta2_off, run_meta, (size_t)groups / m.run_len * 8);
+    memcpy(dst + m.meta2_off, run_meta, (size_t)((groups + m.run_len - 1) / m.run_len) * 8);
+}
+
+// code at column col of a 4-bit or 3-bit row
+inline uint8_t peek_code_43(int bits, uint32_t cols, const uint32_t *w, uint32_t col)
+{
+    if (bits == 4) {
+        const uint32_t v = w[col / 8], i = col % 8;
+        return (v >> (4 * (i / 2) + 16 * (i & 1))) & 15;
+    }
+    const uint32_t groups = cols / 64, g = col / 64, e = col % 64, j = e / 8, pos = e % 8;
+    const uint32_t p = 4 * (pos / 2) + 16 * (pos & 1);
+    const uint32_t low = (w[4 * g + j / 2] >> (p + 2 * (j & 1))) & 3;
+    const uint32_t high = (w[groups * 4 + 2 * g + j / 4] >> (p + (j % 4))) & 1;
+    return (uint8_t)(low | high << 2);
+}
+
+inline uint8_t peek_code_2(uint32_t word, uint32_t col)
+{
+    const uint32_t i = col % 16;
+    return (word >> (2 * (i / 2) + 16 * (i & 1))) & 3;
 }
 
 inline void peek_row_meta8(const BlobLayout &b, const MatLayout &m, const uint8_t *src, uint32_t col, uint8_t *code,
                            uint8_t *scale_code, uint8_t *zero_code, uint16_t run_meta[4])
 {
-    const uint32_t v = reinterpret_cast<const uint32_t *>(src)[col / 8], i = col % 8, g = col / b.group;
-    *code = (v >> (4 * (i / 2) + 16 * (i & 1))) & 15;
+    const uint32_t *w = reinterpret_cast<const uint32_t *>(src);
+    const uint32_t g = col / b.group;
+    *code = b.bits == 2 ? peek_code_2(w[g], col) : peek_code_43(b.bits, m.cols, w, col);
     *scale_code = src[m.meta_off + 2 * g];
     *zero_code = src[m.meta_off + 2 * g + 1];
     memcpy(run_meta, src + m.meta2_off + (size_t)(g / m.run_len) * 8, 8);
@@ -204,20 +235,11 @@ inline void peek_row(const BlobLayout &b, const MatLayout &m, const uint8_t *src
 {
     const uint32_t *w = reinterpret_cast<const uint32_t *>(src);
     uint32_t g = col / b.group, meta;
-    if (b.bits == 4) {
-        uint32_t v = w[col / 8], i = col % 8;
-        *code = (v >> (4 * (i / 2) + 16 * (i & 1))) & 15;
-        meta = reinterpret_cast<const uint32_t *>(src + m.meta_off)[g];
-    } else if (b.bits == 2) {
-        uint32_t v = w[2 * g], i = col % 16;
-        *code = (v >> (2 * (i / 2) + 16 * (i & 1))) & 3;
+    if (b.bits == 2) {
+        *code = peek_code_2(w[2 * g], col);
         meta = w[2 * g + 1];
     } else {
-        const uint32_t groups = m.cols / b.group, e = col % 64, j = e / 8, pos = e % 8;
-        const uint32_t p = 4 * (pos / 2) + 16 * (pos & 1);
-        const uint32_t low = (w[4 * g + j / 2] >> (p + 2 * (j & 1))) & 3;
-        const uint32_t high = (w[groups * 4 + 2 * g + j / 4] >> (p + (j % 4))) & 1;
-        *code = (uint8_t)(low | high << 2);
+        *code = peek_code_43(b.bits, m.cols, w, col);
         meta = reinterpret_cast<const uint32_t *>(src + m.meta_off)[g];
     }
     *scale = (uint16_t)(meta & 0xffff);

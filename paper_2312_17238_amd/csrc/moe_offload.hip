@@ -511,7 +511,7 @@ extern "C" int32_t moe_layer_load_expert_2level(moe_layer_t *l, int32_t expert, 
     if (matrix < 0 || matrix > 2) return fail(MOE_EINVAL, "moe_layer_load_expert_2level: matrix %d out of range", matrix);
     const BlobLayout &b = l->lay;
     const MatLayout &m = mat_of(b, matrix);
-    const uint32_t groups = m.cols / b.group, runs = groups / m.run_len;
+    const uint32_t groups = m.cols / b.group, runs = (groups + m.run_len - 1) / m.run_len;
     return load_matrix(l, expert, matrix, codes, [&](uint32_t r, uint8_t *dst) {
         pack_row_meta8(b, m, codes + (uint64_t)r * m.cols, scale_code + (uint64_t)r * groups, zero_code + (uint64_t)r * groups,
                        run_meta + (uint64_t)r * runs * 4, dst);
@@ -907,39 +907,54 @@ static int32_t launch_gate(moe_ctx *c, GateArgs ga, int32_t batch)
 #define MOE_W2T_G 4
 #endif
 
+// Format policy of a layer's blobs: the bit width, or bits * 10 + 8 with two-level metadata (48, 38, 28).
+static int fmt_of(const BlobLayout &b) { return b.scale_group ? b.bits * 10 + 8 : b.bits; }
+
 // Activation registers per (chunk, token) of each format: the budget that limits tokens per entry.
-template <int BITS> constexpr int act_regs() { return BITS == 3 ? 34 : (BITS == 2 ? 20 : 18); }   // (48: 4-bit codes, two-level metadata)
+constexpr int act_regs_of(int fmt) { return (fmt == 3 || fmt == 38) ? 34 : (fmt == 2 ? 20 : (fmt == 28 ? 40 : 18)); }
+template <int BITS> constexpr int act_regs() { return act_regs_of(BITS); }
+constexpr int codes_per_chunk(int fmt) { return (fmt == 3 || fmt == 38 || fmt == 28) ? 64 : 32; }
 constexpr int ACT_REG_BUDGET = 160;
 
-static int chunks_per_lane(int cols, int bits)      // 64-lane passes over one row (1, 2 or 4; 0 = too wide)
+static int chunks_per_lane(int cols, int fmt)       // 64-lane passes over one row (1, 2 or 4; 0 = too wide)
 {
-    const int n = (cols / (bits == 3 ? 64 : 32) + 63) / 64;
+    const int n = (cols / codes_per_chunk(fmt) + 63) / 64;
     return n <= 1 ? 1 : (n <= 2 ? 2 : (n <= 4 ? 4 : 0));
 }
 
-static int max_tokens_per_entry(int hidden, int bits)
+static int max_tokens_per_entry(int hidden, int fmt)
 {
-    const int kch = std::max(1, chunks_per_lane(hidden, bits));
-    const int regs = bits == 3 ? 34 : (bits == 2 ? 20 : 18);
-    const int n = ACT_REG_BUDGET / (kch * regs);
+    const int kch = std::max(1, chunks_per_lane(hidden, fmt));
+    const int n = ACT_REG_BUDGET / (kch * act_regs_of(fmt));
     return n >= 4 ? 4 : (n >= 2 ? 2 : 1);
 }
 
+// Waves per block of the w1/w3 kernel.  8 (two per SIMD, measured best for the single-token kernels) while the
+// activations leave room under the 256 registers a lane may then use; 4 (512 registers) for the variants that
+// keep more activations, which would otherwise spill.
+#ifndef MOE_W13_WAVES
+#define MOE_W13_WAVES 8
+#endif
+template <int BITS, int KCH, int NT> constexpr int w13_waves() { return KCH * NT * act_regs<BITS>() <= 80 ? MOE_W13_WAVES : 4; }
+
 template <int BITS, int KCH, int NT>
-static int32_t launch_w13_t(moe_ctx *c, uint64_t bytes, dim3 grid, const FfnArgs &A)
+static int32_t launch_w13_t(moe_ctx *c, uint64_t bytes, int n_entries, const FfnArgs &A)
 {
-    if constexpr (KCH * NT * act_regs<BITS>() <= ACT_REG_BUDGET)
-        return launch_timed(c, PROF_W13, bytes, k_w13<BITS, KCH, NT, MOE_W13_G>, grid, dim3(W13_WAVES * WAVE), 0, A);
-    else
+    if constexpr (KCH * NT * act_regs<BITS>() <= ACT_REG_BUDGET) {
+        constexpr int WAVES = w13_waves<BITS, KCH, NT>();
+        const dim3 grid(std::max(1, std::min((A.F + WAVES - 1) / WAVES, c->w13_blocks / n_entries)), n_entries);
+        return launch_timed(c, PROF_W13, bytes, k_w13<BITS, KCH, NT, MOE_W13_G, WAVES>, grid, dim3(WAVES * WAVE), 0, A);
+    } else {
         return fail(MOE_EINVAL, "no w1/w3 kernel for %d chunks per lane and %d tokens per entry", KCH, NT);
+    }
 }
 
 template <int BITS, int KCH>
-static int32_t launch_w13_k(moe_ctx *c, int nt, uint64_t bytes, dim3 grid, const FfnArgs &A)
+static int32_t launch_w13_k(moe_ctx *c, int nt, uint64_t bytes, int n_entries, const FfnArgs &A)
 {
-    if (nt == 1) return launch_w13_t<BITS, KCH, 1>(c, bytes, grid, A);
-    if (nt == 2) return launch_w13_t<BITS, KCH, 2>(c, bytes, grid, A);
-    return launch_w13_t<BITS, KCH, 4>(c, bytes, grid, A);
+    if (nt == 1) return launch_w13_t<BITS, KCH, 1>(c, bytes, n_entries, A);
+    if (nt == 2) return launch_w13_t<BITS, KCH, 2>(c, bytes, n_entries, A);
+    return launch_w13_t<BITS, KCH, 4>(c, bytes, n_entries, A);
 }
 
 template <int BITS>
@@ -969,12 +984,10 @@ static int32_t launch_ffn_fmt(moe_layer *l, const std::vector<FfnEntry> &entries
         }
         const uint64_t bytes13 = n_distinct * 2 * (uint64_t)b.ffn * b.m13.row_stride;
         const uint64_t bytes2 = n_distinct * (uint64_t)b.hidden * b.m2.row_stride;
-        const int bx = std::max(1, std::min((b.ffn + W13_WAVES - 1) / W13_WAVES, c->w13_blocks / n));
-        const dim3 g13(bx, n);
         int32_t rc;
-        if (kch == 1) rc = launch_w13_k<BITS, 1>(c, nt, bytes13, g13, A);
-        else if (kch == 2) rc = launch_w13_k<BITS, 2>(c, nt, bytes13, g13, A);
-        else rc = launch_w13_k<BITS, 4>(c, nt, bytes13, g13, A);
+        if (kch == 1) rc = launch_w13_k<BITS, 1>(c, nt, bytes13, n, A);
+        else if (kch == 2) rc = launch_w13_k<BITS, 2>(c, nt, bytes13, n, A);
+        else rc = launch_w13_k<BITS, 4>(c, nt, bytes13, n, A);
         if (rc) return rc;
         if (w13_only) continue;
         const dim3 g2((b.hidden + A.rows_per_block - 1) / A.rows_per_block, n), blk(cs * WAVE);
@@ -999,8 +1012,9 @@ static int32_t launch_token_fmt(moe_layer *l, const FusedArgs &A0, bool one_laun
     const int rows = (one_launch || c->w2_token_rows <= 0) ? (b.hidden + grid - 1) / grid : c->w2_token_rows;
     *done = false;
     const int items_per_wave = (A0.n_exp * b.ffn + grid * FUSED_WAVES - 1) / (grid * FUSED_WAVES);
-    if (kch == 0 || kch > 2 || (BITS == 3 && kch > 1) || cs > 8 || cs * A0.n_exp > FUSED_WAVES || rows > 64 || grid < 1 || grid > 1024 ||
-        items_per_wave + 2 > FUSED_MAX_ITEMS)
+    constexpr bool has_one_launch = BITS != 38 && BITS != 28;      // no persistent one-launch kernel for these
+    if (kch == 0 || kch > 2 || (codes_per_chunk(BITS) == 64 && kch > 1) || cs > 8 || cs * A0.n_exp > FUSED_WAVES || rows > 64 ||
+        grid < 1 || grid > 1024 || items_per_wave + 2 > FUSED_MAX_ITEMS || (one_launch && !has_one_launch))
         return MOE_OK;
     *done = true;
     if (probe_only) return MOE_OK;
@@ -1012,23 +1026,27 @@ static int32_t launch_token_fmt(moe_layer *l, const FusedArgs &A0, bool one_laun
         return launch_timed(c, PROF_W2, bytes2, k_w2_token<BITS, MOE_W2T_G>, dim3((b.hidden + rows - 1) / rows),
                             dim3(A.n_exp * cs * WAVE), 0, A);
     }
-    A.barrier = c->barrier;
-    A.barrier_target = ++c->barrier_count;
-    A.error_flag = &c->gate_out_dev->ffn_error;
-    const uint64_t bytes = (uint64_t)A.n_exp * (2 * (uint64_t)b.ffn * b.m13.row_stride + (uint64_t)b.hidden * b.m2.row_stride);
-    const dim3 g(grid), blk(FUSED_WAVES * WAVE);
-    if (kch == 1) return launch_timed(c, PROF_FFN, bytes, k_ffn_token<BITS, 1, 2, MOE_FUSED_G2>, g, blk, 0, A);
-    if constexpr (BITS != 3) return launch_timed(c, PROF_FFN, bytes, k_ffn_token<BITS, 2, 2, MOE_FUSED_G2>, g, blk, 0, A);
+    if constexpr (has_one_launch) {
+        A.barrier = c->barrier;
+        A.barrier_target = ++c->barrier_count;
+        A.error_flag = &c->gate_out_dev->ffn_error;
+        const uint64_t bytes = (uint64_t)A.n_exp * (2 * (uint64_t)b.ffn * b.m13.row_stride + (uint64_t)b.hidden * b.m2.row_stride);
+        const dim3 g(grid), blk(FUSED_WAVES * WAVE);
+        if (kch == 1) return launch_timed(c, PROF_FFN, bytes, k_ffn_token<BITS, 1, 2, MOE_FUSED_G2>, g, blk, 0, A);
+        if constexpr (BITS != 3) return launch_timed(c, PROF_FFN, bytes, k_ffn_token<BITS, 2, 2, MOE_FUSED_G2>, g, blk, 0, A);
+    }
     return fail(MOE_EINVAL, "no fused kernel for this shape");
 }
 
 static int32_t launch_token(moe_layer *l, const FusedArgs &A, bool one_launch, bool probe_only, bool *done)
 {
-    if (l->lay.scale_group) return launch_token_fmt<48>(l, A, one_launch, probe_only, done);
-    switch (l->lay.bits) {
+    switch (fmt_of(l->lay)) {
     case 4: return launch_token_fmt<4>(l, A, one_launch, probe_only, done);
     case 3: return launch_token_fmt<3>(l, A, one_launch, probe_only, done);
     case 2: return launch_token_fmt<2>(l, A, one_launch, probe_only, done);
+    case 48: return launch_token_fmt<48>(l, A, one_launch, probe_only, done);
+    case 38: return launch_token_fmt<38>(l, A, one_launch, probe_only, done);
+    case 28: return launch_token_fmt<28>(l, A, one_launch, probe_only, done);
     default: *done = false; return MOE_OK;
     }
 }
@@ -1170,11 +1188,13 @@ static int32_t launch_mfma(moe_layer *l, const std::vector<PassExpert> &experts,
 
 static int32_t launch_ffn(moe_layer *l, const std::vector<FfnEntry> &entries, int nt, bool w13_only = false)
 {
-    if (l->lay.scale_group) return launch_ffn_fmt<48>(l, entries, nt, w13_only);
-    switch (l->lay.bits) {
+    switch (fmt_of(l->lay)) {
     case 4: return launch_ffn_fmt<4>(l, entries, nt, w13_only);
     case 3: return launch_ffn_fmt<3>(l, entries, nt, w13_only);
     case 2: return launch_ffn_fmt<2>(l, entries, nt, w13_only);
+    case 48: return launch_ffn_fmt<48>(l, entries, nt, w13_only);
+    case 38: return launch_ffn_fmt<38>(l, entries, nt, w13_only);
+    case 28: return launch_ffn_fmt<28>(l, entries, nt, w13_only);
     default: return fail(MOE_EINVAL, "unsupported bit width %d", l->lay.bits);
     }
 }
@@ -1235,7 +1255,7 @@ extern "C" int32_t moe_layer_step(moe_layer_t *l, moe_layer_t *next, const uint1
         for (int i = 0; i < batch * cf.top_k; ++i) n += (idx[i] == a.expert);
         max_tok = std::max(max_tok, n);
     }
-    const int nt = std::min(max_tok == 1 ? 1 : (max_tok == 2 ? 2 : 4), max_tokens_per_entry(cf.hidden, cf.bits));
+    const int nt = std::min(max_tok == 1 ? 1 : (max_tok == 2 ? 2 : 4), max_tokens_per_entry(cf.hidden, fmt_of(l->lay)));
 
     if (c->gate_out->ffn_error) return fail(MOE_ESTATE, "an earlier fused FFN kernel gave up waiting at its grid barrier");
     const bool try_fused = c->token_path && batch == 1 && passes.size() == 1 && plan.access.size() <= 2 &&

@@ -530,6 +530,43 @@ def test_small_stack_two_level_metadata(R, Bn, k, m, variant):
     model.close()
 
 
+@pytest.mark.parametrize("formats,R,F,Bn,k,m,variant", [
+    ([(3, 64)] * 3, 2, 448, 1, 2, 2, "token"), ([(3, 64)] * 3, 4, 448, 1, 2, 1, "general"), ([(3, 64)] * 3, 128, 448, 1, 4, 2, "token"),
+    ([(2, 16)] * 3, 4, 320, 1, 2, 2, "token"), ([(2, 16)] * 3, 8, 320, 1, 2, 1, "general"), ([(2, 16)] * 3, 128, 320, 1, 4, 2, "token"),
+    ([(2, 16), (3, 64), (2, 16)], 8, 448, 4, 4, 2, "general"), ([(3, 64), (2, 16), (3, 64)], 4, 320, 20, 4, 2, "general"),
+    ([(2, 16), (3, 64), (4, 64)], 8, 448, 2, 8, 0, "general")])
+def test_small_stack_two_level_metadata_low_bit(formats, R, F, Bn, k, m, variant):
+    """The 3-bit g64 and 2-bit g16 schemes with 8-bit scale and zero codes (Sec. 4.2 pairs both with scale group size
+    128).  H=256 gives 4 (16 for 2-bit) groups per w1/w3 row; F=448 gives 7 groups of 64 (runs of 2: 2+2+2+1, of 4: 4+3)
+    and 28 of 16 (runs of 8: 8+8+8+4); F=320 gives 5 and 20 (runs of 8: 8+8+4): rows that end in a shorter run, several
+    runs per row, whole rows as one run, through the single-token and the general kernels with 1, 2 and 4 tokens
+    per entry."""
+    L, H = 3, 256
+    say(f"two-level metadata low-bit formats={formats} R={R} F={F} B={Bn} k={k} m={m} {variant}")
+    model = Model(L, H, F, 8, 2, formats, k, m, 1e-5, max_batch=Bn, seed=79, scale_group=R)
+    B.moe_ctx_set_option(model.stack.ctx, "token_path", 0 if variant == "general" else 1)
+    for l, (bits, g) in enumerate(formats):
+        assert model.stack.blob_bytes[l] == B.moe_expert_blob_bytes(H, F, bits, g, R)
+    xs = W.hidden_ar1(79, 10 if Bn < 10 else 4, Bn, H)
+    _, sim, errs = run_teacher_forced(model, xs, O.expert_ffn)
+    say(f"  max abs {max(e[0] for e in errs):.2e} max rel-rms {max(e[1] for e in errs):.2e}")
+    model.close()
+
+
+@pytest.mark.parametrize("bits,g,blob", [(3, 64, 72_089_600), (2, 16, 66_781_184)])
+def test_mixtral_layer_two_level_metadata_low_bit(bits, g, blob):
+    """One Mixtral-shaped layer in the paper's 3-bit and 2-bit schemes with scale group 128 (w2 rows of the 3-bit
+    scheme: 224 groups = one run of 128 and one of 96), k=4, C oracle on every token."""
+    c = W.CONFIGS["mixtral_layer"]
+    say(f"mixtral layer, {bits}-bit g{g}, scale group 128: build")
+    model = Model(1, c.hidden, c.ffn, c.n_experts, c.top_k, [(bits, g)], 4, 0, 0.0, seed=c.seed, scale_group=128)
+    assert model.stack.blob_bytes[0] == blob
+    xs = W.hidden_ar1(c.seed, 5, 1, c.hidden)
+    _, sim, errs = run_teacher_forced(model, xs, c_ffn.expert_ffn)
+    say(f"  max abs {max(e[0] for e in errs):.2e} max rel-rms {max(e[1] for e in errs):.2e}")
+    model.close()
+
+
 def test_mixtral_layer_two_level_metadata():
     """One Mixtral-shaped layer with two-level metadata (scale group 256: one run per row), k=4, C oracle on every token."""
     c = W.CONFIGS["mixtral_layer"]

@@ -188,40 +188,57 @@ def test_packed_blob_reads_back_every_code(bits, group):
     st.close()
 
 
-def test_two_level_blob_size_and_read_back():
-    """Two-level metadata (4-bit codes, one byte pair per group, one fp16 quad per run): 4.25 bits per weight plus the
-    quads; every code, byte pair and quad reads back from the packed blob, also with several runs per row."""
+def test_two_level_blob_sizes():
+    """Two-level metadata (one byte pair per group, one fp16 quad per run): 4.25, 3.25 and 3.0 bits per weight plus
+    the quads and the padding of a row to 16 bytes."""
     P = 3 * 4096 * 14336
     rows_quads = (2 * 14336 + 4096) * 8                       # one run per row: 64 and 224 groups are below 256
     w13_row, w2_row = 2048 + 128 + 8, 7168 + 448 + 8
-    assert B.moe_expert_blob_bytes(4096, 14336, 4, 64, 256) == 2 * 14336 * (-(-w13_row // 16) * 16) + 4096 * (-(-w2_row // 16) * 16) == 94_109_696
+    pad16 = lambda n: -(-n // 16) * 16
+    assert B.moe_expert_blob_bytes(4096, 14336, 4, 64, 256) == 2 * 14336 * pad16(w13_row) + 4096 * pad16(w2_row) == 94_109_696
     assert 94_109_696 - (P // 2 + P // 64 * 2 + rows_quads) == (2 * 14336 + 4096) * 8     # 16-byte row padding
-    assert B.moe_expert_blob_bytes(4096, 14336, 3, 64, 128) == 0 and B.moe_expert_blob_bytes(256, 512, 4, 64, 3) == 0
+    # 3-bit g64, scale group 128 (Sec. 4.2): 64 groups = one run along w1/w3 rows, 224 groups = 128 + 96 along w2 rows
+    assert B.moe_expert_blob_bytes(4096, 14336, 3, 64, 128) == 2 * 14336 * pad16(64 * 26 + 8) + 4096 * pad16(224 * 26 + 16) == 72_089_600
+    # 2-bit g16, scale group 128: 256 groups = 2 runs, 896 groups = 7 runs
+    assert B.moe_expert_blob_bytes(4096, 14336, 2, 16, 128) == 2 * 14336 * pad16(256 * 6 + 16) + 4096 * pad16(896 * 6 + 56) == 66_781_184
+    assert B.moe_expert_blob_bytes(4096, 14336, 3, 64) == 77_070_336 and B.moe_expert_blob_bytes(4096, 14336, 2, 16) == 88_080_384
+    # not a power of two; 2-bit runs shorter than the four groups a lane reads
+    assert B.moe_expert_blob_bytes(256, 512, 4, 64, 3) == 0 and B.moe_expert_blob_bytes(256, 512, 2, 16, 2) == 0
+    assert B.moe_expert_blob_bytes(64, 64, 2, 16, 2) == 0 and B.moe_expert_blob_bytes(64, 64, 2, 16, 4) > 0
+
+
+@pytest.mark.parametrize("bits,g,H,F,R", [(4, 64, 256, 512, 2), (3, 64, 192, 448, 2), (3, 64, 192, 448, 4), (2, 16, 64, 320, 4), (2, 16, 64, 320, 8), (2, 16, 64, 320, 16)])
+def test_two_level_read_back(bits, g, H, F, R):
+    """Every code, byte pair and quad reads back from the packed blob, with several runs per row and rows that
+    end in a shorter run (448/64 = 7 groups in runs of 2 or 4; 320/16 = 20 groups in runs of 8 or 16)."""
     rng = np.random.default_rng(21)
-    H, F, E, R = 256, 512, 2, 2                               # 4 and 8 groups per row -> 2 and 4 runs
-    st = Stack([layer_config(H, F, E, 2, 4, 64, 2, scale_group=R)], [torch.zeros(E, H)], host_only=True)
+    E = 2
+    st = Stack([layer_config(H, F, E, 2, bits, g, 2, scale_group=R)], [torch.zeros(E, H)], host_only=True)
     lay = st.layers[0]
     mats = {}
     for e in range(E):
         for mtx, (r, c) in enumerate(((F, H), (F, H), (H, F))):
-            q = rng.integers(0, 16, size=(r, c)).astype(np.uint8)
-            qs = rng.integers(0, 256, size=(r, c // 64)).astype(np.uint8)
-            qz = rng.integers(0, 256, size=(r, c // 64)).astype(np.uint8)
-            meta = rng.integers(0, 1 << 16, size=(r, c // 64 // R, 4)).astype(np.uint16)
+            runs = -(-(c // g) // R)
+            q = rng.integers(0, 1 << bits, size=(r, c)).astype(np.uint8)
+            qs = rng.integers(0, 256, size=(r, c // g)).astype(np.uint8)
+            qz = rng.integers(0, 256, size=(r, c // g)).astype(np.uint8)
+            meta = rng.integers(0, 1 << 16, size=(r, runs, 4)).astype(np.uint16)
             mats[(e, mtx)] = (q, qs, qz, meta)
             B.moe_layer_load_expert_2level(lay, e, mtx, q.ctypes.data, qs.ctypes.data, qz.ctypes.data, meta.ctypes.data)
     for (e, mtx), (q, qs, qz, meta) in mats.items():
         for r in [0, 1, q.shape[0] - 1] + [int(x) for x in rng.integers(0, q.shape[0], 3)]:
             for c in range(q.shape[1]):
-                assert B.moe_layer_peek_weight(lay, e, mtx, r, c) == (q[r, c], qs[r, c // 64], qz[r, c // 64])
-                assert B.moe_layer_peek_run_meta(lay, e, mtx, r, c) == tuple(int(v) for v in meta[r, c // 64 // R])
-    assert B.moe_layer_host_bytes(st.cfgs[0]) == E * B.moe_expert_blob_bytes(H, F, 4, 64, R)
+                assert B.moe_layer_peek_weight(lay, e, mtx, r, c) == (q[r, c], qs[r, c // g], qz[r, c // g])
+                assert B.moe_layer_peek_run_meta(lay, e, mtx, r, c) == tuple(int(v) for v in meta[r, c // g // R])
+    assert B.moe_layer_host_bytes(st.cfgs[0]) == E * B.moe_expert_blob_bytes(H, F, bits, g, R)
     # the one-level entry point refuses a two-level layer and the other way round
     q, qs, qz, meta = mats[(0, 0)]
-    h16 = np.zeros((F, H // 64), np.float16)
+    h16 = np.zeros((F, H // g), np.float16)
     expect(B.MOE_ESTATE, B.moe_layer_load_expert, lay, 0, 0, q.ctypes.data, h16.ctypes.data, h16.ctypes.data)
+    bad = q.copy(); bad[3, 5] = 1 << bits
+    expect(B.MOE_EINVAL, B.moe_layer_load_expert_2level, lay, 0, 0, bad.ctypes.data, qs.ctypes.data, qz.ctypes.data, meta.ctypes.data)
     st.close()
-    st = Stack([layer_config(H, F, E, 2, 4, 64, 2)], [torch.zeros(E, H)], host_only=True)
+    st = Stack([layer_config(H, F, E, 2, bits, g, 2)], [torch.zeros(E, H)], host_only=True)
     expect(B.MOE_ESTATE, B.moe_layer_load_expert_2level, st.layers[0], 0, 0, q.ctypes.data, qs.ctypes.data, qz.ctypes.data, meta.ctypes.data)
     st.close()
 
