@@ -1495,16 +1495,10 @@ extern "C" int32_t moe_ctx_set_option(moe_ctx_t *c, const char *name, int32_t va
     return MOE_OK;
 }
 
-extern "C" int32_t moe_probe_bandwidth(const void *src_dev, void *dst_dev, uint64_t bytes, int32_t blocks, int32_t iters,
-                                       void *stream, double *avg_ms)
+// The timed part of moe_probe_bandwidth; the caller owns (and always releases) the events and the sink.
+static int32_t probe_run(const void *src_dev, void *dst_dev, uint64_t bytes, int32_t blocks, int32_t iters, hipStream_t s,
+                         hipEvent_t e0, hipEvent_t e1, uint32_t *sink, double *avg_ms)
 {
-    if (!src_dev || !avg_ms || bytes < 16 || blocks < 1 || iters < 1) return fail(MOE_EINVAL, "moe_probe_bandwidth: bad argument");
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    hipEvent_t e0, e1;
-    HIPCHK(hipEventCreate(&e0));
-    HIPCHK(hipEventCreate(&e1));
-    uint32_t *sink = nullptr;
-    if (!dst_dev) HIPCHK(hipMalloc(reinterpret_cast<void **>(&sink), (size_t)blocks * 4));
     const size_t n16 = bytes / 16;
     for (int it = -1; it < iters; ++it) {      // one untimed warm-up launch
         if (it == 0) HIPCHK(hipEventRecord(e0, s));
@@ -1517,10 +1511,29 @@ extern "C" int32_t moe_probe_bandwidth(const void *src_dev, void *dst_dev, uint6
     float ms = 0.f;
     HIPCHK(hipEventElapsedTime(&ms, e0, e1));
     *avg_ms = (double)ms / iters;
-    if (sink) (void)hipFree(sink);
-    (void)hipEventDestroy(e0);
-    (void)hipEventDestroy(e1);
     return MOE_OK;
+}
+
+extern "C" int32_t moe_probe_bandwidth(const void *src_dev, void *dst_dev, uint64_t bytes, int32_t blocks, int32_t iters,
+                                       void *stream, double *avg_ms)
+{
+    if (!src_dev || !avg_ms || bytes < 16 || blocks < 1 || iters < 1) return fail(MOE_EINVAL, "moe_probe_bandwidth: bad argument");
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    uint32_t *sink = nullptr;
+    hipError_t e = hipEventCreate(&e0);
+    if (e == hipSuccess) e = hipEventCreate(&e1);
+    if (e == hipSuccess && !dst_dev) e = hipMalloc(reinterpret_cast<void **>(&sink), (size_t)blocks * 4);
+    int32_t rc;
+    if (e != hipSuccess) {
+        g_hip_err = (int32_t)e;
+        rc = fail(MOE_EHIP, "moe_probe_bandwidth: HIP set-up failed: %s", hipGetErrorString(e));
+    } else {
+        rc = probe_run(src_dev, dst_dev, bytes, blocks, iters, static_cast<hipStream_t>(stream), e0, e1, sink, avg_ms);
+    }
+    if (sink) (void)hipFree(sink);
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    return rc;
 }
 
 extern "C" int32_t moe_layer_set_prefetch(moe_layer_t *l, int32_t m)
