@@ -248,6 +248,21 @@ def test_mixtral_stack_full_size_sampled():
         model.stack.synchronize()
         assert (x_out.cpu().numpy().view(np.uint16) == outs[t].view(np.uint16)).all(), f"async stack differs at token {t}"
     assert model.stack.total_stats() == tot
+    # ... and with bench.py's default of speculative loads as a 4 MiB head plus a confirmed tail: the same outputs and
+    # decisions, fewer bytes for the wrong guesses
+    model.stack.reset()
+    B.moe_ctx_set_option(model.stack.ctx, "spec_head_mb", 4)
+    for t in range(T):
+        x_in.copy_(xs[t])
+        torch.cuda.synchronize()
+        model.stack.step(x_in, x_out, None)
+        model.stack.synchronize()
+        assert (x_out.cpu().numpy().view(np.uint16) == outs[t].view(np.uint16)).all(), f"head-then-tail stack differs at token {t}"
+    tot4 = model.stack.total_stats()
+    for key in ("needed", "hits", "prefetch_hits", "misses", "evictions", "spec_issued", "spec_wasted", "bytes_h2d_demand"):
+        assert tot4[key] == tot[key], key
+    blob = model.stack.blob_bytes[0]
+    assert tot4["bytes_h2d_spec"] == tot["bytes_h2d_spec"] - tot["spec_wasted"] * (blob - (4 << 20))
     model.close()
 
 
