@@ -141,6 +141,8 @@ typedef struct {
     uint64_t bytes_h2d_demand;
     uint64_t bytes_h2d_spec;
     uint64_t bytes_d2h_writeback; /* MOE_LAYER_SWAP: evicted experts written back to host buffers    */
+    uint64_t steps_device_routed; /* ... of `steps`, those enqueued without waiting for the gate (every
+                                     expert resident, one token; option "device_routing")            */
 } moe_stats_t;                /* "expert recall" (Sec. 4.1) = (hits + prefetch_hits) / needed    */
 
 /* ---- sizes ---------------------------------------------------------------------------------- */
@@ -284,7 +286,16 @@ int32_t moe_ctx_profile_read(moe_ctx_t *ctx, moe_profile_t *out);
  *                layer confirms the guess.  Decisions, traces and results are identical; only how many bytes a wrong
  *                guess costs changes (N MiB instead of a whole expert).  Meant for links that are already saturated;
  *   "fused"      1: such a step runs w1/w3 and w2 as ONE persistent launch with a grid barrier (measured
- *                slower than two launches on MI355X, hence default 0). */
+ *                slower than two launches on MI355X, hence default 0);
+ *   "device_routing" 1 (default): a single-token step of a layer whose experts are ALL on the device (cache_slots ==
+ *                n_experts, every slot filled) and whose caller asks for no trace is enqueued without waiting for
+ *                its gate kernel: no cache decision depends on the routing then, so the FFN kernels read the selection
+ *                and the combine weights the gate kernel left in device memory, and moe_layer_step returns at once.
+ *                Outputs are bit-identical to a waiting step's.  The recency stamps and counters such steps owe are
+ *                caught up from a host-visible log of the selections (which waits for the compute stream) before any
+ *                call reads or changes them: moe_layer_stats, moe_layer_cache_state, moe_layer_reset, a waiting step,
+ *                moe_layer_resolve, moe_layer_prefetch, moe_layer_destroy, or when 8192 such steps are pending.
+ *                0: every step waits for its gate. */
 int32_t moe_ctx_set_option(moe_ctx_t *ctx, const char *name, int32_t value);
 
 /* Calibration probe, independent of any context: `iters` launches of a plain streaming-read kernel over

@@ -75,7 +75,7 @@ class StepTrace(C.Structure):
 class Stats(C.Structure):
     _fields_ = [(n, C.c_uint64) for n in ("steps", "needed", "hits", "prefetch_hits", "misses", "evictions",
                                           "spec_issued", "spec_wasted", "bytes_h2d_demand", "bytes_h2d_spec",
-                                          "bytes_d2h_writeback")]
+                                          "bytes_d2h_writeback", "steps_device_routed")]
 
     def as_dict(self):
         return {n: int(getattr(self, n)) for n, _ in self._fields_}

@@ -37,6 +37,11 @@ struct FusedArgs {
     uint32_t stride13, meta13, stride2, meta2;
     uint64_t off_w2;
     int32_t rows_per_block;         // R
+    // Device-side routing (k_w2_token only): expert e of the step is route_idx[e], its combine weight route_w[e], its
+    // weights table[route_idx[e]], as the gate kernel of the same step left them.  Null: blob[] and w[] above.
+    const int32_t *route_idx;
+    const float *route_w;
+    const uint8_t *table[16];
 };
 
 // All blocks of the grid meet here.  Bounded: a block that waits too long raises the error flag and goes
@@ -100,7 +105,8 @@ __device__ __forceinline__ void token_w2_phase(const FusedArgs &A, float *red, i
     const int row0 = blockIdx.x * R;
     const int row_end = min(row0 + R, A.H);
     const int last2 = max(row_end - 1, 0);
-    const uint8_t *base2 = A.blob[active ? e2 : 0] + A.off_w2;
+    const uint8_t *blob2 = A.route_idx ? A.table[uniform(A.route_idx[active ? e2 : 0]) & 15] : A.blob[active ? e2 : 0];
+    const uint8_t *base2 = blob2 + A.off_w2;
     typename F::Row ring2[G2];
 #pragma unroll
     for (int s = 0; s < G2; ++s) F::load(ring2[s], base2 + (size_t)min(row0 + s, last2) * A.stride2, geo2, cc);
@@ -126,11 +132,15 @@ __device__ __forceinline__ void token_w2_phase(const FusedArgs &A, float *red, i
     __syncthreads();
     const int rr = threadIdx.x;
     if (rr < row_end - row0) {
+        // The experts are added in ascending id, the order the host puts them in: with device-side routing the
+        // entries are in selection order, so two of them may have to swap.
+        const bool swap = A.route_idx && A.n_exp == 2 && A.route_idx[0] > A.route_idx[1];
         float y = 0.f;
-        for (int e = 0; e < A.n_exp; ++e) {
+        for (int i = 0; i < A.n_exp; ++i) {
+            const int e = swap ? 1 - i : i;
             float s = 0.f;
             for (int k = 0; k < CS; ++k) s += red[(e * 8 + k) * 64 + rr];
-            y += A.w[e] * s;
+            y += (A.route_idx ? A.route_w[e] : A.w[e]) * s;
         }
         const int row = row0 + rr;
         A.y[row] = y;

@@ -33,6 +33,12 @@ struct GateArgs {
     double eps;                     // 0: no norm
     int32_t H, E, E2, K;
     uint32_t seq;                   // value to publish in out->done[b]
+    // Device-side routing (one token, every expert of the layer resident): the selection and the combine weights go
+    // to device memory for the FFN kernels of the same step, the selection also to a host-visible log the host reads
+    // later for its bookkeeping; nothing is published in `out` and nobody waits for this launch.
+    int32_t *route_idx;             // [K] device, or null
+    float *route_w;                 // [K] device
+    int32_t *route_log;             // [K] host-mapped
 };
 
 constexpr int GATE_THREADS = 1024;
@@ -139,6 +145,14 @@ __global__ __launch_bounds__(GATE_THREADS) void k_gate(GateArgs a)
             const double zmax = tot[chosen[0]];
             double p[4], ps = 0.0;
             for (int j = 0; j < a.K; ++j) { p[j] = exp(tot[chosen[j]] - zmax); ps += p[j]; }
+            if (a.route_idx) {
+                for (int j = 0; j < a.K; ++j) {
+                    a.route_idx[j] = chosen[j];
+                    a.route_w[j] = (float)(p[j] / ps);
+                    a.route_log[j] = chosen[j];
+                }
+                return;
+            }
             for (int j = 0; j < a.K; ++j) {
                 o->idx[b * a.K + j] = chosen[j];
                 o->w[b * a.K + j] = (float)(p[j] / ps);

@@ -36,6 +36,10 @@ struct FfnArgs {
     uint32_t stride2, meta2;        // w2 row
     uint64_t off_w2;
     int32_t rows_per_block;         // w2 kernel
+    // Device-side routing: entry j serves the j-th selected expert, whose id the gate kernel of the same step left in
+    // route_idx[j]; its weights are in table[id].  Null: the entries carry their blob pointers themselves.
+    const int32_t *route_idx;
+    const uint8_t *table[16];       // device buffer of every expert of the layer (all resident)
 };
 
 // Geometry of one matrix row as the format policies see it.
@@ -358,7 +362,7 @@ __global__ __launch_bounds__(WAVES *WAVE) void k_w13(FfnArgs A)
     const int wave = uniform(blockIdx.x * WAVES + (threadIdx.x >> 6)), n_waves = gridDim.x * WAVES;
     const int n_chunks = A.H / F::CODES;
     const RowGeom geo = row_geom<BITS>(A.meta13, A.H, A.group, A.scale_group);
-    const uint8_t *base = en.blob;
+    const uint8_t *base = A.route_idx ? A.table[uniform(A.route_idx[blockIdx.y]) & 15] : en.blob;
 
     int cidx[KCH];
     bool live[KCH];

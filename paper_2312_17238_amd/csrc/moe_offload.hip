@@ -116,6 +116,17 @@ struct moe_ctx {
     uint32_t *barrier = nullptr;        // device counter of its grid barrier
     uint32_t barrier_count = 0;         // value it reaches after all launches enqueued so far
     bool sync_wait = false;
+    // Device-side routing: steps of one token through a layer whose experts are all resident need no decision of the
+    // host, so they are enqueued without waiting for the gate; the cache bookkeeping (recency stamps, counters) is
+    // caught up from a host-visible log of the selections before anything reads or changes it.
+    bool device_routing = true;
+    int32_t *route_idx = nullptr;       // device: the current step's selection, written by its gate kernel
+    float *route_w = nullptr;           // device: ... and combine weights
+    int32_t *route_log = nullptr;       // host-mapped ring of ROUTE_LOG entries of MOE_MAX_TOPK selections
+    int32_t *route_log_dev = nullptr;   // the same memory as the device sees it
+    struct PendingStep { moe_layer *layer; uint32_t slot; };
+    std::vector<PendingStep> pending;   // steps enqueued that way whose bookkeeping is still to be done, oldest first
+    static constexpr uint32_t ROUTE_LOG = 8192;
 };
 
 struct moe_layer {
@@ -137,7 +148,10 @@ struct moe_layer {
     std::vector<int32_t> host_reader;   // per host buffer: pool buffer whose `ready` event covers its last read, or -1
     std::vector<int32_t> host_writer;   // per host buffer: pool buffer whose `drained` event covers its last write, or -1
     std::vector<std::vector<uint8_t>> pack_tmp;   // swap mode: experts 0..k-1 are packed here until they move to the device
+    uint64_t steps_device_routed = 0;   // steps enqueued without waiting for their gate
 };
+
+static int32_t fold_pending(moe_ctx *c);   // bookkeeping of device-routed steps; every reader of cache state calls it first
 
 static int32_t n_host_bufs(const moe_layer_config_t &c)
 {
@@ -164,7 +178,7 @@ static bool layer_cfg_ok(const moe_layer_config_t *c)
            c->scale_group >= 0 && blob_layout(c->hidden, c->ffn, c->bits, c->group, c->scale_group).ok;
 }
 
-struct ScratchPlan { uint64_t staging, h, a, yacc, x0, x1, barrier, total; };
+struct ScratchPlan { uint64_t staging, h, a, yacc, x0, x1, barrier, route, total; };
 
 static ScratchPlan plan_scratch(const moe_ctx_config_t *c)
 {
@@ -178,6 +192,7 @@ static ScratchPlan plan_scratch(const moe_ctx_config_t *c)
     p.x0 = off;   off += align_u64((uint64_t)c->max_batch * c->max_hidden * 2, 256);
     p.x1 = off;   off += align_u64((uint64_t)c->max_batch * c->max_hidden * 2, 256);
     p.barrier = off; off += 4096;     // one flag per block of the persistent kernel (at most 1024 compute units)
+    p.route = off; off += 256;        // device-side routing: MOE_MAX_TOPK selections and as many combine weights
     p.total = off;
     return p;
 }
@@ -264,6 +279,9 @@ extern "C" int32_t moe_ctx_create(const moe_ctx_config_t *cfg, void *dev_arena, 
     c->xbuf[0] = reinterpret_cast<uint16_t *>(base + p.x0);
     c->xbuf[1] = reinterpret_cast<uint16_t *>(base + p.x1);
     c->barrier = reinterpret_cast<uint32_t *>(base + p.barrier);
+    c->route_idx = reinterpret_cast<int32_t *>(base + p.route);
+    c->route_w = reinterpret_cast<float *>(base + p.route + 128);
+    c->device_routing = env_int("MOE_DEVICE_ROUTING", 1) != 0;
     c->mfma_min_batch = env_int("MOE_MFMA_MIN_BATCH", 16);
     c->fused = env_int("MOE_FUSED", 0) != 0;
     hipError_t e = hipMemset(c->barrier, 0, 4096);
@@ -276,6 +294,8 @@ extern "C" int32_t moe_ctx_create(const moe_ctx_config_t *cfg, void *dev_arena, 
     }
     if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void **>(&c->gate_out), sizeof(GateHostOut), hipHostMallocMapped);
     if (e == hipSuccess) e = hipHostGetDevicePointer(reinterpret_cast<void **>(&c->gate_out_dev), c->gate_out, 0);
+    if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void **>(&c->route_log), (size_t)moe_ctx::ROUTE_LOG * MOE_MAX_TOPK * sizeof(int32_t), hipHostMallocMapped);
+    if (e == hipSuccess) e = hipHostGetDevicePointer(reinterpret_cast<void **>(&c->route_log_dev), c->route_log, 0);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_gate, hipEventDisableTiming);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_compute, hipEventDisableTiming);
     for (int i = 0; i < cfg->n_staging && e == hipSuccess; ++i) {
@@ -312,6 +332,7 @@ extern "C" int32_t moe_ctx_destroy(moe_ctx_t *c)
         if (c->ev_gate) (void)hipEventDestroy(c->ev_gate);
         if (c->ev_compute) (void)hipEventDestroy(c->ev_compute);
         if (c->gate_out) (void)hipHostFree(c->gate_out);
+        if (c->route_log) (void)hipHostFree(c->route_log);
     }
     delete c;
     return MOE_OK;
@@ -331,6 +352,7 @@ static void cache_init(moe_layer *l)
     c.slot_buf = l->own_bufs;
     c.staged.clear();
     l->st = Counters();
+    l->steps_device_routed = 0;
 }
 
 extern "C" int32_t moe_layer_create(moe_ctx_t *ctx, const moe_layer_config_t *cfg, const float *gate_w_host,
@@ -404,6 +426,7 @@ extern "C" int32_t moe_layer_create(moe_ctx_t *ctx, const moe_layer_config_t *cf
 extern "C" int32_t moe_layer_destroy(moe_layer_t *l)
 {
     if (!l) return MOE_OK;
+    (void)fold_pending(l->ctx);
     if (!l->ctx->host_only) {
         (void)hipStreamSynchronize(l->ctx->compute);
         (void)hipStreamSynchronize(l->ctx->copy);
@@ -816,6 +839,8 @@ extern "C" int32_t moe_layer_resolve(moe_layer_t *l, moe_layer_t *next, const in
     if (rc) return rc;
     if (!expert_idx) return fail(MOE_EINVAL, "moe_layer_resolve: expert_idx is null");
     if (!l->ctx->host_only && !all_loaded(l)) return fail(MOE_ESTATE, "moe_layer_resolve: not every expert of the layer is loaded");
+    rc = fold_pending(l->ctx);
+    if (rc) return rc;
     StepPlan plan;
     rc = plan_step(l, next, expert_idx, batch, guess_score, trace, plan);
     if (rc) return rc;
@@ -957,8 +982,9 @@ static int32_t launch_w13_k(moe_ctx *c, int nt, uint64_t bytes, int n_entries, c
     return launch_w13_t<BITS, KCH, 4>(c, bytes, n_entries, A);
 }
 
+// table (device-side routing): the layer's expert -> device buffer map; entry j then serves the j-th selected expert
 template <int BITS>
-static int32_t launch_ffn_fmt(moe_layer *l, const std::vector<FfnEntry> &entries, int nt, bool w13_only)
+static int32_t launch_ffn_fmt(moe_layer *l, const std::vector<FfnEntry> &entries, int nt, bool w13_only, const uint8_t *const *table)
 {
     moe_ctx *c = l->ctx;
     const BlobLayout &b = l->lay;
@@ -975,11 +1001,15 @@ static int32_t launch_ffn_fmt(moe_layer *l, const std::vector<FfnEntry> &entries
         A.stride2 = b.m2.row_stride; A.meta2 = b.m2.meta_off;
         A.off_w2 = b.off_w2;
         A.rows_per_block = c->w2_rows;
+        if (table) {
+            A.route_idx = c->route_idx;
+            for (int e = 0; e < 16; ++e) A.table[e] = table[e];
+        }
         // algorithmic bytes: every distinct expert of the launch is read once
         uint64_t n_distinct = 0;
         for (int i = 0; i < n; ++i) {
             bool seen = false;
-            for (int j = 0; j < i; ++j) seen |= (A.e[j].blob == A.e[i].blob);
+            for (int j = 0; j < i && !table; ++j) seen |= (A.e[j].blob == A.e[i].blob);
             n_distinct += !seen;
         }
         const uint64_t bytes13 = n_distinct * 2 * (uint64_t)b.ffn * b.m13.row_stride;
@@ -1186,17 +1216,115 @@ static int32_t launch_mfma(moe_layer *l, const std::vector<PassExpert> &experts,
                    : launch_timed(c, PROF_W2, bytes2, k_mfma_rows_q4<false, 1>, gr2, blkr, rows_lds(b.ffn, 1), A);
 }
 
-static int32_t launch_ffn(moe_layer *l, const std::vector<FfnEntry> &entries, int nt, bool w13_only = false)
+static int32_t launch_ffn(moe_layer *l, const std::vector<FfnEntry> &entries, int nt, bool w13_only = false,
+                          const uint8_t *const *table = nullptr)
 {
     switch (fmt_of(l->lay)) {
-    case 4: return launch_ffn_fmt<4>(l, entries, nt, w13_only);
-    case 3: return launch_ffn_fmt<3>(l, entries, nt, w13_only);
-    case 2: return launch_ffn_fmt<2>(l, entries, nt, w13_only);
-    case 48: return launch_ffn_fmt<48>(l, entries, nt, w13_only);
-    case 38: return launch_ffn_fmt<38>(l, entries, nt, w13_only);
-    case 28: return launch_ffn_fmt<28>(l, entries, nt, w13_only);
+    case 4: return launch_ffn_fmt<4>(l, entries, nt, w13_only, table);
+    case 3: return launch_ffn_fmt<3>(l, entries, nt, w13_only, table);
+    case 2: return launch_ffn_fmt<2>(l, entries, nt, w13_only, table);
+    case 48: return launch_ffn_fmt<48>(l, entries, nt, w13_only, table);
+    case 38: return launch_ffn_fmt<38>(l, entries, nt, w13_only, table);
+    case 28: return launch_ffn_fmt<28>(l, entries, nt, w13_only, table);
     default: return fail(MOE_EINVAL, "unsupported bit width %d", l->lay.bits);
     }
+}
+
+// ---------------------------------------------------------------------------------------------
+// device-side routing
+// ---------------------------------------------------------------------------------------------
+
+// Catch up the bookkeeping of the steps that were enqueued without waiting for their gate: wait for them, then
+// replay their selections, oldest first, through the same cache logic a waiting step runs.
+static int32_t fold_pending(moe_ctx *c)
+{
+    if (c->pending.empty()) return MOE_OK;
+    HIPCHK(hipStreamSynchronize(c->compute));
+    std::vector<AccessRec> access;
+    std::vector<CopyOp> misses;
+    std::vector<int32_t> needed;
+    for (const moe_ctx::PendingStep &p : c->pending) {
+        moe_layer *l = p.layer;
+        const int32_t *idx = c->route_log + (size_t)p.slot * MOE_MAX_TOPK;
+        needed.assign(idx, idx + l->cfg.top_k);
+        std::sort(needed.begin(), needed.end());
+        needed.erase(std::unique(needed.begin(), needed.end()), needed.end());
+        if (needed.front() < 0 || needed.back() >= l->cfg.n_experts) { c->pending.clear(); return fail(MOE_ESTATE, "device-routed step logged expert %d", needed.front() < 0 ? needed.front() : needed.back()); }
+        access.clear();
+        misses.clear();
+        resolve_accesses(l->cache, c->pool, l->st, needed, false, access, misses);
+        if (!misses.empty()) { c->pending.clear(); return fail(MOE_ESTATE, "device-routed step met an expert that is not resident"); }
+    }
+    c->pending.clear();
+    return MOE_OK;
+}
+
+static bool all_resident(const moe_layer *l)
+{
+    if (l->swap || (l->cfg.flags & MOE_LAYER_NO_CACHE) || l->cfg.cache_slots != l->cfg.n_experts || !l->cache.staged.empty()) return false;
+    for (int s = 0; s < l->cache.k; ++s)
+        if (l->cache.slot_expert[s] < 0 || l->ctx->bufs[l->cache.slot_buf[s]].pending) return false;
+    return true;
+}
+
+static FusedArgs token_args(moe_layer *l, const uint16_t *x_in, uint16_t *x_out)
+{
+    moe_ctx *c = l->ctx;
+    FusedArgs fa{};
+    fa.h = c->h_buf; fa.x = x_in; fa.x_out = x_out; fa.a = c->a_buf; fa.y = c->yacc;
+    fa.H = l->lay.hidden; fa.F = l->lay.ffn; fa.group = l->lay.group; fa.scale_group = l->lay.scale_group;
+    fa.stride13 = l->lay.m13.row_stride; fa.meta13 = l->lay.m13.meta_off;
+    fa.stride2 = l->lay.m2.row_stride; fa.meta2 = l->lay.m2.meta_off; fa.off_w2 = l->lay.off_w2;
+    return fa;
+}
+
+// One token through a layer whose experts are all on the device: no cache decision depends on the routing, so the
+// gate, w1/w3 and w2 kernels are enqueued back to back and the call returns without waiting for any of them.
+static bool device_routed_step_fits(moe_layer *l, const moe_layer *next, int32_t batch, const moe_step_trace_t *trace, bool spec)
+{
+    moe_ctx *c = l->ctx;
+    if (!c->device_routing || batch != 1 || trace || !c->token_path || c->fused || l->cfg.top_k > 2 || c->gate_out->ffn_error) return false;
+    if (!all_resident(l) || (spec && !all_resident(next))) return false;
+    FusedArgs fa = token_args(l, nullptr, nullptr);
+    fa.n_exp = l->cfg.top_k;
+    bool fits = false;
+    return launch_token(l, fa, false, true, &fits) == MOE_OK && fits;
+}
+
+static int32_t device_routed_step(moe_layer *l, const uint16_t *x_in, uint16_t *x_out, uint16_t *h_out)
+{
+    moe_ctx *c = l->ctx;
+    const moe_layer_config_t &cf = l->cfg;
+    if (c->pending.size() >= moe_ctx::ROUTE_LOG) { int32_t rc = fold_pending(c); if (rc) return rc; }
+    // a log slot is free once its step has been folded: with fewer than ROUTE_LOG steps pending the oldest slots are
+    uint32_t slot = c->pending.empty() ? 0 : (c->pending.back().slot + 1) % moe_ctx::ROUTE_LOG;
+    GateArgs ga{};
+    ga.x = x_in; ga.wg = l->gate_w_dev; ga.gamma = l->gamma_dev; ga.h_out = c->h_buf; ga.h_out2 = h_out; ga.yacc = c->yacc;
+    ga.out = c->gate_out_dev; ga.eps = (double)cf.rms_eps; ga.H = cf.hidden; ga.E = cf.n_experts; ga.K = cf.top_k;
+    ga.route_idx = c->route_idx; ga.route_w = c->route_w; ga.route_log = c->route_log_dev + (size_t)slot * MOE_MAX_TOPK;
+    int32_t rc = launch_timed(c, PROF_GATE, 0, k_gate, dim3(1), dim3(GATE_THREADS), 0, ga);
+    if (rc) return rc;
+    c->pending.push_back({l, slot});
+    l->steps_device_routed++;
+
+    const uint8_t *table[16];
+    for (int e = 0; e < 16; ++e) table[e] = c->bufs[l->cache.slot_buf[l->cache.find(e < cf.n_experts ? e : 0)]].ptr;
+    std::vector<FfnEntry> entries(cf.top_k);
+    for (int j = 0; j < cf.top_k; ++j) {
+        entries[j] = FfnEntry{};
+        entries[j].n_tok = 1; entries[j].tok[0] = 0; entries[j].pair[0] = j;
+    }
+    rc = launch_ffn(l, entries, 1, true, table);
+    if (rc) return rc;
+    FusedArgs fa = token_args(l, x_in, x_out);
+    fa.n_exp = cf.top_k;
+    for (int j = 0; j < cf.top_k; ++j) fa.a_row[j] = j;
+    fa.route_idx = c->route_idx; fa.route_w = c->route_w;
+    for (int e = 0; e < 16; ++e) fa.table[e] = table[e];
+    bool done = false;
+    rc = launch_token(l, fa, false, false, &done);
+    if (!rc && !done) rc = fail(MOE_ESTATE, "device-routed step: the single-token kernels do not fit this shape");
+    return rc;
 }
 
 extern "C" int32_t moe_layer_step(moe_layer_t *l, moe_layer_t *next, const uint16_t *x_in, int32_t batch,
@@ -1211,6 +1339,9 @@ extern "C" int32_t moe_layer_step(moe_layer_t *l, moe_layer_t *next, const uint1
     const moe_layer_config_t &cf = l->cfg;
     const bool spec = next && next->cfg.prefetch_m > 0 && c->cfg.n_staging > 0;
     if (spec && !all_loaded(next)) return fail(MOE_ESTATE, "moe_layer_step: next layer not fully loaded");
+    if (device_routed_step_fits(l, next, batch, trace, spec)) return device_routed_step(l, x_in, x_out, h_out);
+    rc = fold_pending(c);
+    if (rc) return rc;
 
     GateArgs ga{};
     ga.x = x_in; ga.wg = l->gate_w_dev; ga.wg2 = spec ? next->gate_w_dev : nullptr;
@@ -1320,13 +1451,9 @@ extern "C" int32_t moe_layer_step(moe_layer_t *l, moe_layer_t *next, const uint1
             if (en.n_tok) entries.push_back(en);
         }
         if (try_fused) {
-            FusedArgs fa{};
+            FusedArgs fa = token_args(l, x_in, x_out);
             fa.n_exp = (int32_t)entries.size();
             for (int i = 0; i < fa.n_exp; ++i) { fa.blob[i] = entries[i].blob; fa.w[i] = entries[i].w[0]; fa.a_row[i] = entries[i].pair[0]; }
-            fa.h = c->h_buf; fa.x = x_in; fa.x_out = x_out; fa.a = c->a_buf; fa.y = c->yacc;
-            fa.H = l->lay.hidden; fa.F = l->lay.ffn; fa.group = l->lay.group; fa.scale_group = l->lay.scale_group;
-            fa.stride13 = l->lay.m13.row_stride; fa.meta13 = l->lay.m13.meta_off;
-            fa.stride2 = l->lay.m2.row_stride; fa.meta2 = l->lay.m2.meta_off; fa.off_w2 = l->lay.off_w2;
             if (c->fused) {
                 rc = launch_token(l, fa, true, false, &fused_done);
             } else {
@@ -1365,6 +1492,8 @@ extern "C" int32_t moe_layer_prefetch(moe_layer_t *l, const uint16_t *h_dev, int
     if (!all_loaded(l)) return fail(MOE_ESTATE, "moe_layer_prefetch: not every expert of the layer is loaded");
     if (trace) trace->n_guess = 0;
     if (l->cfg.prefetch_m <= 0 || c->cfg.n_staging <= 0) return MOE_OK;
+    rc = fold_pending(c);
+    if (rc) return rc;
     GateArgs ga{};
     ga.x = h_dev; ga.wg2 = l->gate_w_dev; ga.out = c->gate_out_dev; ga.eps = 0.0; ga.H = l->cfg.hidden;
     ga.E2 = l->cfg.n_experts; ga.K = l->cfg.top_k;
@@ -1418,9 +1547,11 @@ extern "C" int32_t moe_stack_step(moe_layer_t *const *layers, int32_t n_layers, 
 extern "C" int32_t moe_layer_stats(const moe_layer_t *l, moe_stats_t *o)
 {
     if (!l || !o) return fail(MOE_EINVAL, "moe_layer_stats: null argument");
+    int32_t rc = fold_pending(l->ctx);
+    if (rc) return rc;
     const Counters &s = l->st;
     *o = {s.steps, s.needed, s.hits, s.prefetch_hits, s.misses, s.evictions, s.spec_issued, s.spec_wasted, s.bytes_demand, s.bytes_spec,
-          s.bytes_writeback};
+          s.bytes_writeback, l->steps_device_routed};
     return MOE_OK;
 }
 
@@ -1428,6 +1559,8 @@ extern "C" int32_t moe_layer_cache_state(const moe_layer_t *l, int32_t *slot_exp
                                          int32_t *n_staged)
 {
     if (!l) return fail(MOE_EINVAL, "moe_layer_cache_state: layer is null");
+    int32_t rc = fold_pending(l->ctx);
+    if (rc) return rc;
     for (int s = 0; s < l->cache.k; ++s) {
         if (slot_expert) slot_expert[s] = l->cache.slot_expert[s];
         if (slot_stamp) slot_stamp[s] = l->cache.slot_stamp[s];
@@ -1452,6 +1585,8 @@ extern "C" int32_t moe_layer_reset(moe_layer_t *l)
     if (!l) return fail(MOE_EINVAL, "moe_layer_reset: layer is null");
     if (l->swap) return fail(MOE_ESTATE, "moe_layer_reset: a layer in swap mode cannot return to its initial placement; create it again");
     moe_ctx *c = l->ctx;
+    int32_t rcf = fold_pending(c);
+    if (rcf) return rcf;
     if (!c->host_only) {
         HIPCHK(hipStreamSynchronize(c->compute));
         HIPCHK(hipStreamSynchronize(c->copy));
@@ -1491,6 +1626,7 @@ extern "C" int32_t moe_ctx_set_option(moe_ctx_t *c, const char *name, int32_t va
     else if (n == "spec_head_mb" && value >= 0) c->spec_head_bytes = (uint64_t)value << 20;
     else if (n == "mfma_min_batch" && value >= 1) c->mfma_min_batch = value;
     else if (n == "mfma_form" && (value == 1 || value == 2)) c->mfma_form = value;
+    else if (n == "device_routing") c->device_routing = value != 0;
     else return fail(MOE_EINVAL, "moe_ctx_set_option: unknown option or bad value: %s = %d", name, value);
     return MOE_OK;
 }
@@ -1539,6 +1675,8 @@ extern "C" int32_t moe_probe_bandwidth(const void *src_dev, void *dst_dev, uint6
 extern "C" int32_t moe_layer_set_prefetch(moe_layer_t *l, int32_t m)
 {
     if (!l || m < 0 || m > MOE_MAX_GUESS) return fail(MOE_EINVAL, "moe_layer_set_prefetch: bad argument");
+    int32_t rc = fold_pending(l->ctx);
+    if (rc) return rc;
     l->cfg.prefetch_m = m;
     return MOE_OK;
 }
@@ -1547,6 +1685,8 @@ extern "C" int32_t moe_layer_set_flags(moe_layer_t *l, int32_t flags)
 {
     if (!l || (flags & ~MOE_LAYER_NO_CACHE)) return fail(MOE_EINVAL, "moe_layer_set_flags: bad argument");
     if (l->swap && flags) return fail(MOE_EINVAL, "moe_layer_set_flags: a layer in swap mode cannot forget residency");
+    int32_t rc = fold_pending(l->ctx);
+    if (rc) return rc;
     l->cfg.flags = flags | (l->swap ? MOE_LAYER_SWAP : 0);
     return MOE_OK;
 }

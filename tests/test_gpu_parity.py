@@ -594,6 +594,76 @@ def test_mixtral_layer_two_level_metadata():
     model.close()
 
 
+@pytest.mark.parametrize("formats,scale_group,init_policy,m", [([(4, 64)] * 3, 0, 0, 2), ([(4, 64)] * 3, 0, 1, 0), ([(2, 16), (3, 64), (4, 64)], 0, 1, 2),
+                                                               ([(4, 64), (3, 64), (2, 16)], 8, 0, 1)])
+def test_device_routed_steps_against_oracle_and_waiting_steps(formats, scale_group, init_policy, m):
+    """A layer with every expert resident (k = E) takes single-token steps without the host waiting for the gate:
+    the FFN kernels read the selection the gate kernel left on the device, the cache bookkeeping is caught up later.
+    Checked against the oracle (gate input bit-exact, y within tolerance, the cache simulator's counters and
+    recency order at the end) and against the same run with the feature off (outputs bit-identical, counters and
+    stamps equal), from a cold start (the first steps still wait, until every slot is filled) and from a warm one,
+    with a waiting step (one that asks for a trace) thrown in every few tokens."""
+    L, H, F, E, K, T = 3, 256, 512, 8, 2, 40
+    say(f"device-routed steps formats={formats} scale_group={scale_group} init_policy={init_policy} m={m}")
+    fast = Model(L, H, F, E, K, formats, E, m, 1e-5, seed=91, init_policy=init_policy, scale_group=scale_group)
+    slow = Model(L, H, F, E, K, formats, E, m, 1e-5, seed=91, init_policy=init_policy, scale_group=scale_group, keep_layers=[])
+    B.moe_ctx_set_option(slow.stack.ctx, "device_routing", 0)
+    xs = W.hidden_ar1(91, T, 1, H)
+    dev = fast.stack.device
+    sim = O.ExpertCacheSim(L, E, E, 4, warm=(init_policy == 1))
+    xa = [torch.empty(1, H, dtype=torch.float16, device=dev) for _ in range(L + 1)]
+    xb = [torch.empty(1, H, dtype=torch.float16, device=dev) for _ in range(L + 1)]
+    hb = torch.empty(1, H, dtype=torch.float16, device=dev)
+    errs = []
+    for t in range(T):
+        xa[0].copy_(xs[t]); xb[0].copy_(xs[t])
+        torch.cuda.synchronize()
+        for l in range(L):
+            tr = B.StepTrace() if t % 7 == 3 else None
+            fast.stack.step_layer(l, xa[l], xa[l + 1], hb, tr)
+            slow.stack.step_layer(l, xb[l], xb[l + 1], None, None)
+            fast.stack.synchronize(); slow.stack.synchronize()
+            x_np = xa[l].cpu().numpy()
+            (h, idx, w, _), = oracle_routing(fast, l, x_np)
+            assert (hb.cpu().numpy()[0].view(np.uint16) == h.view(np.uint16)).all(), f"gate input differs t={t} l={l}"
+            guess = O.prefetch_guess(O.prefetch_scores(fast.gate_np(l + 1), h[None]), m) if (l + 1 < L and m > 0) else None
+            sim.step(l, [idx], guess)
+            y_ref = oracle_y(fast, l, h, idx, w, O.expert_ffn)
+            errs.append(check_y(fast.stack.read_y(1, H)[0], y_ref, f"y t={t} l={l}"))
+            assert (xa[l + 1].cpu().numpy().view(np.uint16) == xb[l + 1].cpu().numpy().view(np.uint16)).all(), f"x_out differs t={t} l={l}"
+    sa, sb = fast.stack.stats(), slow.stack.stats()
+    routed = [d.pop("steps_device_routed") for d in sa]
+    assert all(d.pop("steps_device_routed") == 0 for d in sb) and sa == sb
+    # every step without a trace is device-routed once the layer (and, with speculation, the next one) is full
+    traced = len([t for t in range(T) if t % 7 == 3])
+    say(f"  device-routed steps per layer: {routed} of {T} ({traced} asked for a trace)")
+    assert all(0 < r <= T - traced for r in routed) and (init_policy == 0 or all(r == T - traced for r in routed))
+    for l in range(L):
+        assert sa[l]["hits"] == sim.stats[l].hits and sa[l]["misses"] == sim.stats[l].misses and sa[l]["steps"] == T
+        ca, cb = B.moe_layer_cache_state(fast.stack.layers[l], E), B.moe_layer_cache_state(slow.stack.layers[l], E)
+        assert ca == cb
+        # recency order of the slots = the simulator's
+        order = [e for _, e in sorted(zip(ca[1], ca[0]))]
+        assert order == [e for _, e in sorted(zip(sim.slot_stamp[l], sim.slot_expert[l]))]
+    say(f"  max abs {max(e[0] for e in errs):.2e} max rel-rms {max(e[1] for e in errs):.2e}")
+    fast.close(); slow.close()
+
+
+def test_device_routed_steps_log_wraps():
+    """More device-routed steps than the selection log has entries, with no call in between that would catch the
+    bookkeeping up: the library does it by itself when the log is full, and the counters come out complete."""
+    H, F, E, T = 256, 512, 8, 9000
+    model = Model(1, H, F, E, 2, None, E, 0, 0.0, seed=93, init_policy=1, keep_layers=[])
+    xs = W.hidden_iid(93, 64, 1, H).to(model.stack.device)
+    x_out = torch.empty(1, H, dtype=torch.float16, device=model.stack.device)
+    for t in range(T):
+        model.stack.step(xs[t % 64], x_out, None)
+    model.stack.synchronize()
+    st = model.stack.stats()[0]
+    assert st["steps"] == T == st["steps_device_routed"] and st["needed"] == 2 * T == st["hits"] and st["misses"] == 0
+    model.close()
+
+
 def test_recall_study_tool_against_closed_forms():
     """paper_2312_17238_amd.recall_study (the Fig. 2 analogue): on a small stack its LRU hit ratio for k = top_k = 2
     equals the closed form sum_t |S_t & S_{t-1}| / needed, for k = E only the first touches miss, and guessing all
