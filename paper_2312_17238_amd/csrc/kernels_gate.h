@@ -51,6 +51,8 @@ __global__ __launch_bounds__(GATE_THREADS) void k_gate(GateArgs a)
 {
     __shared__ double red[GATE_WAVES][32];
     __shared__ double tot[33];
+    __shared__ double prob[16];          // thread 0's small tables live in LDS: indexed at run time, they would
+    __shared__ int chosen[4];            // otherwise be carved out of scratch memory for every lane of the launch
     const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const uint16_t *x = a.x + (size_t)b * a.H;
     const int n1 = a.wg ? a.E : 0, n2 = a.wg2 ? a.E2 : 0;
@@ -130,7 +132,6 @@ __global__ __launch_bounds__(GATE_THREADS) void k_gate(GateArgs a)
         GateHostOut *o = a.out;
         if (n1) {
             // top-K by (logit descending, index ascending)
-            int chosen[4];
             for (int j = 0; j < a.K; ++j) {
                 int best = -1;
                 for (int e = 0; e < n1; ++e) {
@@ -143,28 +144,28 @@ __global__ __launch_bounds__(GATE_THREADS) void k_gate(GateArgs a)
             }
             // softmax over all experts, renormalised over the chosen ones == softmax over the chosen logits
             const double zmax = tot[chosen[0]];
-            double p[4], ps = 0.0;
-            for (int j = 0; j < a.K; ++j) { p[j] = exp(tot[chosen[j]] - zmax); ps += p[j]; }
+            double ps = 0.0;
+            for (int j = 0; j < a.K; ++j) { prob[j] = exp(tot[chosen[j]] - zmax); ps += prob[j]; }
             if (a.route_idx) {
                 for (int j = 0; j < a.K; ++j) {
                     a.route_idx[j] = chosen[j];
-                    a.route_w[j] = (float)(p[j] / ps);
+                    a.route_w[j] = (float)(prob[j] / ps);
                     a.route_log[j] = chosen[j];
                 }
                 return;
             }
             for (int j = 0; j < a.K; ++j) {
                 o->idx[b * a.K + j] = chosen[j];
-                o->w[b * a.K + j] = (float)(p[j] / ps);
+                o->w[b * a.K + j] = (float)(prob[j] / ps);
             }
             for (int e = 0; e < n1; ++e) o->logits[b * n1 + e] = tot[e];
         }
         if (n2) {
             double zmax = tot[16];
             for (int e = 1; e < n2; ++e) zmax = tot[16 + e] > zmax ? tot[16 + e] : zmax;
-            double pe[16], ps = 0.0;
-            for (int e = 0; e < n2; ++e) { pe[e] = exp(tot[16 + e] - zmax); ps += pe[e]; }
-            for (int e = 0; e < n2; ++e) o->spec_p[b * n2 + e] = pe[e] / ps;
+            double ps = 0.0;
+            for (int e = 0; e < n2; ++e) { prob[e] = exp(tot[16 + e] - zmax); ps += prob[e]; }
+            for (int e = 0; e < n2; ++e) o->spec_p[b * n2 + e] = prob[e] / ps;
         }
         __hip_atomic_store(&o->done[b], a.seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
     }
