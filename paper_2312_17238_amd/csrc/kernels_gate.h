@@ -47,15 +47,28 @@ constexpr int GATE_WAVES = GATE_THREADS / WAVE;
 // One block per token, 4 consecutive elements per thread and pass.  All decisions are taken in fp64:
 // the products fp32 x fp16 are exact in fp64 and the sums differ from any other fp64 summation order
 // only at the 1e-16 level, so routing equals an fp64 reference except on ties closer than that.
+// SPEC: the launch also evaluates the next layer's gate (a.wg2).  Without it the accumulators of the second gate
+// are not needed and the registers go to this thread's first slice of W_g instead, requested before the norm's
+// reduction so that its memory latency overlaps the norm rather than following it.
+template <bool SPEC>
 __global__ __launch_bounds__(GATE_THREADS) void k_gate(GateArgs a)
 {
+    constexpr int NACC = SPEC ? 32 : 16;
+    constexpr int NPRE = SPEC ? 0 : 8;                   // experts whose first slice is requested up front
     __shared__ double red[GATE_WAVES][32];
     __shared__ double tot[33];
     __shared__ double prob[16];          // thread 0's small tables live in LDS: indexed at run time, they would
     __shared__ int chosen[4];            // otherwise be carved out of scratch memory for every lane of the launch
     const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const uint16_t *x = a.x + (size_t)b * a.H;
-    const int n1 = a.wg ? a.E : 0, n2 = a.wg2 ? a.E2 : 0;
+    const int n1 = a.wg ? a.E : 0, n2 = (SPEC && a.wg2) ? a.E2 : 0;
+
+    float4 wpre[NPRE > 0 ? NPRE : 1];
+    if constexpr (NPRE > 0) {
+#pragma unroll
+        for (int e = 0; e < NPRE; ++e)
+            wpre[e] = (e < n1 && tid * 4 < a.H) ? *reinterpret_cast<const float4 *>(a.wg + (size_t)e * a.H + tid * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
 
     double scale = 1.0;
     if (a.eps > 0.0) {
@@ -78,9 +91,9 @@ __global__ __launch_bounds__(GATE_THREADS) void k_gate(GateArgs a)
         scale = tot[32];
     }
 
-    double acc[32];
+    double acc[NACC];
 #pragma unroll
-    for (int e = 0; e < 32; ++e) acc[e] = 0.0;
+    for (int e = 0; e < NACC; ++e) acc[e] = 0.0;
     for (int i = tid * 4; i < a.H; i += GATE_THREADS * 4) {
         const uint2 p = *reinterpret_cast<const uint2 *>(x + i);
         uint16_t hv[4] = {(uint16_t)(p.x & 0xffff), (uint16_t)(p.x >> 16), (uint16_t)(p.y & 0xffff), (uint16_t)(p.y >> 16)};
@@ -100,18 +113,22 @@ __global__ __launch_bounds__(GATE_THREADS) void k_gate(GateArgs a)
 #pragma unroll
         for (int e = 0; e < 16; ++e)
             if (e < n1) {
-                const float4 w = *reinterpret_cast<const float4 *>(a.wg + (size_t)e * a.H + i);
+                float4 w;
+                if (e < NPRE && i == tid * 4) w = wpre[e < NPRE ? e : 0];
+                else w = *reinterpret_cast<const float4 *>(a.wg + (size_t)e * a.H + i);
                 acc[e] += (double)w.x * h0; acc[e] += (double)w.y * h1; acc[e] += (double)w.z * h2; acc[e] += (double)w.w * h3;
             }
+        if constexpr (SPEC) {
 #pragma unroll
-        for (int e = 0; e < 16; ++e)
-            if (e < n2) {
-                const float4 w = *reinterpret_cast<const float4 *>(a.wg2 + (size_t)e * a.H + i);
-                acc[16 + e] += (double)w.x * h0; acc[16 + e] += (double)w.y * h1; acc[16 + e] += (double)w.z * h2; acc[16 + e] += (double)w.w * h3;
-            }
+            for (int e = 0; e < 16; ++e)
+                if (e < n2) {
+                    const float4 w = *reinterpret_cast<const float4 *>(a.wg2 + (size_t)e * a.H + i);
+                    acc[16 + e] += (double)w.x * h0; acc[16 + e] += (double)w.y * h1; acc[16 + e] += (double)w.z * h2; acc[16 + e] += (double)w.w * h3;
+                }
+        }
     }
 #pragma unroll
-    for (int e = 0; e < 32; ++e) {
+    for (int e = 0; e < NACC; ++e) {
         const bool live = (e < 16) ? (e < n1) : (e - 16 < n2);
         if (live) {
             const double v = wave_sum_f64(acc[e]);
@@ -144,8 +161,10 @@ __global__ __launch_bounds__(GATE_THREADS) void k_gate(GateArgs a)
             }
             // softmax over all experts, renormalised over the chosen ones == softmax over the chosen logits
             const double zmax = tot[chosen[0]];
-            double ps = 0.0;
-            for (int j = 0; j < a.K; ++j) { prob[j] = exp(tot[chosen[j]] - zmax); ps += prob[j]; }
+            double ps;
+            prob[0] = 1.0;                   // exp(0): the first choice holds the largest logit
+            ps = 1.0;
+            for (int j = 1; j < a.K; ++j) { prob[j] = exp(tot[chosen[j]] - zmax); ps += prob[j]; }
             if (a.route_idx) {
                 for (int j = 0; j < a.K; ++j) {
                     a.route_idx[j] = chosen[j];

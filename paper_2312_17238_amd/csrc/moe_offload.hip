@@ -912,7 +912,8 @@ static int32_t launch_gate(moe_ctx *c, GateArgs ga, int32_t batch)
 {
     if (++c->gate_seq == 0) ++c->gate_seq;             // 0 is what a fresh context holds
     ga.seq = c->gate_seq;
-    int32_t rc = launch_timed(c, PROF_GATE, 0, k_gate, dim3(batch), dim3(GATE_THREADS), 0, ga);
+    int32_t rc = ga.wg2 ? launch_timed(c, PROF_GATE, 0, k_gate<true>, dim3(batch), dim3(GATE_THREADS), 0, ga)
+                        : launch_timed(c, PROF_GATE, 0, k_gate<false>, dim3(batch), dim3(GATE_THREADS), 0, ga);
     if (rc) return rc;
     if (!c->sync_wait) HIPCHK(hipEventRecord(c->ev_gate, c->compute));
     return wait_gate(c, batch, ga.seq);
@@ -1302,7 +1303,7 @@ static int32_t device_routed_step(moe_layer *l, const uint16_t *x_in, uint16_t *
     ga.x = x_in; ga.wg = l->gate_w_dev; ga.gamma = l->gamma_dev; ga.h_out = c->h_buf; ga.h_out2 = h_out; ga.yacc = c->yacc;
     ga.out = c->gate_out_dev; ga.eps = (double)cf.rms_eps; ga.H = cf.hidden; ga.E = cf.n_experts; ga.K = cf.top_k;
     ga.route_idx = c->route_idx; ga.route_w = c->route_w; ga.route_log = c->route_log_dev + (size_t)slot * MOE_MAX_TOPK;
-    int32_t rc = launch_timed(c, PROF_GATE, 0, k_gate, dim3(1), dim3(GATE_THREADS), 0, ga);
+    int32_t rc = launch_timed(c, PROF_GATE, 0, k_gate<false>, dim3(1), dim3(GATE_THREADS), 0, ga);
     if (rc) return rc;
     c->pending.push_back({l, slot});
     l->steps_device_routed++;
