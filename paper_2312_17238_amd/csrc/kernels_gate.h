@@ -148,23 +148,31 @@ __global__ __launch_bounds__(GATE_THREADS) void k_gate(GateArgs a)
     if (tid == 0) {
         GateHostOut *o = a.out;
         if (n1) {
-            // top-K by (logit descending, index ascending)
+            // top-K by (logit descending, index ascending).  The logits move to registers first (fixed indices): every
+            // comparison out of LDS would otherwise be a dependent round trip of this one thread.
+            double z[16];
+#pragma unroll
+            for (int e = 0; e < 16; ++e) z[e] = e < n1 ? tot[e] : 0.0;
+            uint32_t used = 0;
             for (int j = 0; j < a.K; ++j) {
                 int best = -1;
-                for (int e = 0; e < n1; ++e) {
-                    bool used = false;
-                    for (int q = 0; q < j; ++q) used |= (chosen[q] == e);
-                    if (used) continue;
-                    if (best < 0 || tot[e] > tot[best]) best = e;
+                double zb = 0.0;
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const bool take = e < n1 && !((used >> e) & 1u) && (best < 0 || z[e] > zb);
+                    best = take ? e : best;
+                    zb = take ? z[e] : zb;
                 }
                 chosen[j] = best;
+                used |= 1u << best;
+                prob[j] = zb;                // the chosen logit, until the softmax below replaces it
             }
             // softmax over all experts, renormalised over the chosen ones == softmax over the chosen logits
-            const double zmax = tot[chosen[0]];
+            const double zmax = prob[0];
             double ps;
             prob[0] = 1.0;                   // exp(0): the first choice holds the largest logit
             ps = 1.0;
-            for (int j = 1; j < a.K; ++j) { prob[j] = exp(tot[chosen[j]] - zmax); ps += prob[j]; }
+            for (int j = 1; j < a.K; ++j) { prob[j] = exp(prob[j] - zmax); ps += prob[j]; }
             if (a.route_idx) {
                 for (int j = 0; j < a.K; ++j) {
                     a.route_idx[j] = chosen[j];
@@ -177,7 +185,9 @@ __global__ __launch_bounds__(GATE_THREADS) void k_gate(GateArgs a)
                 o->idx[b * a.K + j] = chosen[j];
                 o->w[b * a.K + j] = (float)(prob[j] / ps);
             }
-            for (int e = 0; e < n1; ++e) o->logits[b * n1 + e] = tot[e];
+#pragma unroll
+            for (int e = 0; e < 16; ++e)
+                if (e < n1) o->logits[b * n1 + e] = z[e];
         }
         if (n2) {
             double zmax = tot[16];
