@@ -236,6 +236,8 @@ int32_t moe_layer_resolve(moe_layer_t *layer, moe_layer_t *next, const int32_t *
 
 /* ---- state ---------------------------------------------------------------------------------- */
 
+/* Both calls below first bring the bookkeeping of device-routed steps up to date (option "device_routing"), which
+ * waits for the compute stream when such steps are pending. */
 int32_t moe_layer_stats(const moe_layer_t *layer, moe_stats_t *out);
 /* Cache contents: slot_expert[k] (expert id or -1), slot_stamp[k] (recency, larger = more recent),
  * staged[MOE_MAX_EXPERTS] (n_staged ids speculatively loaded for this layer).  Any pointer may be NULL. */
