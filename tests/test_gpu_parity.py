@@ -317,6 +317,28 @@ def test_single_token_kernel_variants_agree(formats):
         assert outs["general"][1] == outs[other][1]
 
 
+@pytest.mark.parametrize("Bn,token_path", [(1, 1), (1, 0), (3, 1)])
+def test_launch_shape_knobs_do_not_change_results(Bn, token_path):
+    """The tuning knobs (blocks of the w1/w3 kernel, rows per block of the two w2 kernels, waiting for the gate with
+    a stream synchronisation instead of polling) only move work between blocks: outputs, traces and statistics
+    stay bit-identical, also for odd values that leave ragged last blocks."""
+    L, H, F = 2, 256, 512
+    xs = W.hidden_ar1(37, 12, Bn, H)
+    outs = []
+    for knobs in ({}, {"w13_blocks": 7, "w2_rows": 5, "w2_token_rows": 3, "sync_wait": 1}, {"w13_blocks": 1000, "w2_rows": 64, "w2_token_rows": 64}):
+        model = Model(L, H, F, 8, 2, [(4, 64), (3, 64)], 2, 2, 1e-5, max_batch=Bn, seed=37)
+        B.moe_ctx_set_option(model.stack.ctx, "token_path", token_path)
+        for name, value in knobs.items():
+            B.moe_ctx_set_option(model.stack.ctx, name, value)
+        o, sim, errs = run_teacher_forced(model, xs, O.expert_ffn)
+        outs.append((o, model.stack.total_stats()))
+        model.close()
+    for o, st in outs[1:]:
+        for a, b in zip(outs[0][0], o):
+            assert (a.view(np.uint16) == b.view(np.uint16)).all()
+        assert st == outs[0][1]
+
+
 @pytest.mark.parametrize("form", [2, 1])
 @pytest.mark.parametrize("Bn,k", [(16, 4), (64, 4), (33, 8), (64, 2)])
 def test_small_stack_matrix_core_path(Bn, k, form):
