@@ -267,6 +267,10 @@ typedef struct { uint64_t launches; uint64_t bytes; double total_ms; } moe_profi
 typedef struct { moe_profile_entry_t gate, w13, w2, copy, ffn, writeback; } moe_profile_t;
 int32_t moe_ctx_profile_enable(moe_ctx_t *ctx, int32_t on);
 int32_t moe_ctx_profile_read(moe_ctx_t *ctx, moe_profile_t *out);
+/* Diagnostic: when each launch of one kind (0 gate, 1 w1/w3, 2 w2, 3 copy, 4 ffn, 5 write-back) recorded since
+ * enable(1) -- and not yet consumed by moe_ctx_profile_read -- began and ended, in ms after the enable call.
+ * *n receives how many there are; at most cap are written.  Waits for the streams. */
+int32_t moe_ctx_profile_timeline(moe_ctx_t *ctx, int32_t kind, double *start_ms, double *stop_ms, int32_t cap, int32_t *n);
 
 /* Launch-shape tuning knobs (defaults are the measured best for Mixtral shapes on MI355X):
  *   "w13_blocks" total thread blocks of the w1/w3 kernel (default 256: one per compute unit);

@@ -25,7 +25,7 @@ EXPORTS = [
     "moe_ctx_create", "moe_ctx_destroy", "moe_layer_create", "moe_layer_destroy",
     "moe_layer_load_expert", "moe_layer_load_expert_2level", "moe_layer_peek_weight", "moe_layer_peek_run_meta", "moe_layer_step", "moe_layer_prefetch",
     "moe_stack_step", "moe_layer_resolve", "moe_layer_stats", "moe_layer_cache_state", "moe_layer_placement",
-    "moe_layer_reset", "moe_ctx_read_y", "moe_ctx_profile_enable", "moe_ctx_profile_read", "moe_ctx_set_option", "moe_probe_bandwidth", "moe_layer_set_prefetch", "moe_layer_set_flags", "moe_last_error", "moe_last_hip_error",
+    "moe_layer_reset", "moe_ctx_read_y", "moe_ctx_profile_enable", "moe_ctx_profile_read", "moe_ctx_profile_timeline", "moe_ctx_set_option", "moe_probe_bandwidth", "moe_layer_set_prefetch", "moe_layer_set_flags", "moe_last_error", "moe_last_hip_error",
 ]
 
 
@@ -143,6 +143,7 @@ def lib() -> C.CDLL:
     L.moe_ctx_read_y.argtypes = [vp, i32, i32, vp]
     L.moe_ctx_profile_enable.argtypes = [vp, i32]
     L.moe_ctx_profile_read.argtypes = [vp, C.POINTER(Profile)]
+    L.moe_ctx_profile_timeline.argtypes = [vp, i32, C.POINTER(C.c_double), C.POINTER(C.c_double), i32, C.POINTER(i32)]
     L.moe_ctx_set_option.argtypes = [vp, C.c_char_p, i32]
     L.moe_probe_bandwidth.argtypes = [vp, vp, u64, i32, i32, vp, C.POINTER(C.c_double)]
     L.moe_layer_set_prefetch.argtypes = [vp, i32]
@@ -278,6 +279,13 @@ def moe_ctx_read_y(ctx, batch: int, hidden: int, y_host: int) -> None:
 
 def moe_ctx_profile_enable(ctx, on: bool) -> None:
     check(lib().moe_ctx_profile_enable(ctx, 1 if on else 0))
+
+
+def moe_ctx_profile_timeline(ctx, kind: int, cap: int = 1 << 16):
+    """[(start ms, stop ms)] of the launches of one kind recorded since profiling was switched on."""
+    a, b, n = (C.c_double * cap)(), (C.c_double * cap)(), C.c_int32()
+    check(lib().moe_ctx_profile_timeline(ctx, kind, a, b, cap, C.byref(n)))
+    return [(a[i], b[i]) for i in range(min(cap, n.value))]
 
 
 def moe_ctx_profile_read(ctx) -> Profile:

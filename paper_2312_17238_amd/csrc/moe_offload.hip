@@ -83,6 +83,7 @@ struct ProfKind {
 
 struct Profiler {
     bool on = false;
+    hipEvent_t base = nullptr;                 // recorded on the compute stream when profiling is switched on: time zero of the timeline
     ProfKind kind[PROF_KINDS];
     static constexpr size_t RING = 65536;      // pairs per kind before a drain (which synchronises) is needed
     static constexpr size_t PREALLOC = 16384;  // pairs per kind created when profiling is switched on
@@ -329,6 +330,7 @@ extern "C" int32_t moe_ctx_destroy(moe_ctx_t *c)
             for (hipEvent_t e : c->prof.kind[k].start) (void)hipEventDestroy(e);
             for (hipEvent_t e : c->prof.kind[k].stop) (void)hipEventDestroy(e);
         }
+        if (c->prof.base) (void)hipEventDestroy(c->prof.base);
         if (c->ev_gate) (void)hipEventDestroy(c->ev_gate);
         if (c->ev_compute) (void)hipEventDestroy(c->ev_compute);
         if (c->gate_out) (void)hipHostFree(c->gate_out);
@@ -649,7 +651,32 @@ extern "C" int32_t moe_ctx_profile_enable(moe_ctx_t *c, int32_t on)
             p.stop.push_back(b);
         }
     }
+    if (on) {
+        if (!c->prof.base) HIPCHK(hipEventCreate(&c->prof.base));
+        HIPCHK(hipEventRecord(c->prof.base, c->compute));
+        HIPCHK(hipEventSynchronize(c->prof.base));
+    }
     c->prof.on = on != 0;
+    return MOE_OK;
+}
+
+extern "C" int32_t moe_ctx_profile_timeline(moe_ctx_t *c, int32_t kind, double *start_ms, double *stop_ms, int32_t cap, int32_t *n)
+{
+    if (!c || !n || kind < 0 || kind >= PROF_KINDS || cap < 0 || (cap > 0 && (!start_ms || !stop_ms)))
+        return fail(MOE_EINVAL, "moe_ctx_profile_timeline: bad argument");
+    if (c->host_only || !c->prof.base) return fail(MOE_ESTATE, "moe_ctx_profile_timeline: profiling was never switched on");
+    HIPCHK(hipStreamSynchronize(c->compute));
+    HIPCHK(hipStreamSynchronize(c->copy));
+    if (c->writeback) HIPCHK(hipStreamSynchronize(c->writeback));
+    const ProfKind &p = c->prof.kind[kind];
+    *n = (int32_t)std::min<size_t>(p.used, (size_t)INT32_MAX);
+    for (size_t i = 0; i < p.used && i < (size_t)cap; ++i) {
+        float a = 0.f, b = 0.f;
+        HIPCHK(hipEventElapsedTime(&a, c->prof.base, p.start[i]));
+        HIPCHK(hipEventElapsedTime(&b, c->prof.base, p.stop[i]));
+        start_ms[i] = a;
+        stop_ms[i] = b;
+    }
     return MOE_OK;
 }
 
@@ -683,6 +710,7 @@ struct StepPlan {
     std::vector<CopyOp> writeback;  // swap mode: evicted expert `expert` from pool buffer `buf` to host buffer `host_buf`
     std::vector<int> writeback_of;  // per access: index into `writeback`, or -1
     bool victim_needed = false;     // an expert needed in this step was evicted during it
+    bool victims_resident = true;   // ... and every such expert was on the device when the step began (its access is a HIT)
 };
 
 static int32_t plan_step(moe_layer *l, moe_layer *next, const int32_t *idx, int32_t batch, const double *guess_score,
@@ -702,7 +730,12 @@ static int32_t plan_step(moe_layer *l, moe_layer *next, const int32_t *idx, int3
     resolve_accesses(l->cache, l->ctx->pool, l->st, needed, (cf.flags & MOE_LAYER_NO_CACHE) != 0, plan.access, misses, redirect);
     size_t next_miss = 0;
     for (const AccessRec &a : plan.access) {
-        if (a.victim >= 0 && std::binary_search(needed.begin(), needed.end(), a.victim)) plan.victim_needed = true;
+        if (a.victim >= 0 && std::binary_search(needed.begin(), needed.end(), a.victim)) {
+            plan.victim_needed = true;
+            bool hit = false;
+            for (const AccessRec &v : plan.access) hit |= (v.expert == a.victim && v.status == MOE_HIT);
+            plan.victims_resident &= hit;
+        }
         PoolBuf &pb = l->ctx->bufs[a.buf];
         int di = -1;
         if (a.status == MOE_MISS) {
@@ -1393,10 +1426,71 @@ extern "C" int32_t moe_layer_step(moe_layer_t *l, moe_layer_t *next, const uint1
     const bool try_fused = c->token_path && batch == 1 && passes.size() == 1 && plan.access.size() <= 2 &&
                            (int)plan.access.size() == cf.top_k && !plan.victim_needed;
     bool fused_done = false;
+    bool spec_issued = false;          // the speculative copies went out early (prompt-sized batches, below)
     // two-level metadata: a step of the streaming kernel stages one run's quad per row, so a run must cover the step
     auto runs_ok = [&](const MatLayout &m) { return m.run_len == 0 || m.run_len == m.cols / (uint32_t)cf.group || m.run_len % TL_SG == 0; };
     const bool use_mfma = batch >= c->mfma_min_batch && cf.bits == 4 && cf.group == 64 && runs_ok(l->lay.m13) && runs_ok(l->lay.m2);
-    for (size_t p = 0; p < passes.size(); ++p) {
+    auto pass_expert = [&](int i) {
+        PassExpert pe;
+        pe.blob = c->bufs[plan.access[i].buf].ptr;
+        for (int q = 0; q < batch * cf.top_k; ++q)
+            if (idx[q] == plan.access[i].expert) pe.pairs.push_back(q);
+        return pe;
+    };
+    // Prompt-sized batch (Sec. 3: a prompt goes through a layer in one step and needs nearly every expert) in which
+    // every buffer that changes hands belonged to an expert resident when the step began.  Those experts are
+    // multiplied first, in one launch pair per window, before any transfer is issued; a transfer into one of their
+    // buffers -- a miss that found no free staging buffer, a speculative load for the next layer -- then waits for
+    // that launch only, not for the multiplies of the experts still arriving, which follow one by one as their
+    // copies land.  The link never waits for a multiply that itself waits for the link.
+    bool staged_step = false;
+    if (use_mfma && batch > 64 && plan.victims_resident) {
+        std::vector<PassExpert> group;
+        std::vector<int> arriving;
+        std::vector<int32_t> read_first;       // buffers the first launch reads
+        for (int i = 0; i < (int)plan.access.size(); ++i) {
+            const AccessRec &a = plan.access[i];
+            if (a.status != MOE_HIT) { arriving.push_back(i); continue; }
+            PoolBuf &pb = c->bufs[a.buf];
+            if (pb.pending) { HIPCHK(hipStreamWaitEvent(c->compute, pb.ready, 0)); pb.pending = false; }
+            group.push_back(pass_expert(i));
+            read_first.push_back(a.buf);
+        }
+        if (!group.empty()) {
+            rc = launch_mfma(l, group, w, batch);
+            if (rc) return rc;
+        }
+        bool guarded = false;
+        auto needs_guard = [&](int32_t buf) { return !guarded && std::find(read_first.begin(), read_first.end(), buf) != read_first.end(); };
+        for (int i : arriving) {
+            const int di = plan.demand_of[i];
+            if (di >= 0 && needs_guard(plan.demand[di].buf)) {
+                HIPCHK(hipEventRecord(c->ev_compute, c->compute));
+                HIPCHK(hipStreamWaitEvent(c->copy, c->ev_compute, 0));
+                guarded = true;
+            }
+            rc = issue_access_transfers(c, l, plan, i);
+            if (rc) return rc;
+        }
+        for (const CopyOp &op : plan.spec) {
+            if (needs_guard(op.buf)) {
+                HIPCHK(hipEventRecord(c->ev_compute, c->compute));
+                HIPCHK(hipStreamWaitEvent(c->copy, c->ev_compute, 0));
+                guarded = true;
+            }
+            rc = issue_copy(c, next, op);
+            if (rc) return rc;
+        }
+        for (int i : arriving) {
+            PoolBuf &pb = c->bufs[plan.access[i].buf];
+            if (pb.pending) { HIPCHK(hipStreamWaitEvent(c->compute, pb.ready, 0)); pb.pending = false; }
+            rc = launch_mfma(l, std::vector<PassExpert>{pass_expert(i)}, w, batch);
+            if (rc) return rc;
+        }
+        staged_step = true;
+        spec_issued = true;
+    }
+    for (size_t p = 0; p < passes.size() && !staged_step; ++p) {
         if (p > 0) {
             HIPCHK(hipEventRecord(c->ev_compute, c->compute));
             HIPCHK(hipStreamWaitEvent(c->copy, c->ev_compute, 0));
@@ -1409,13 +1503,6 @@ extern "C" int32_t moe_layer_step(moe_layer_t *l, moe_layer_t *next, const uint1
             // experts still in flight then follow one by one in the order their copies were issued, each waiting
             // for its own copy only: the multiply of one expert runs under the transfer of the next.
             const bool one_by_one = batch > 64;
-            auto pass_expert = [&](int i) {
-                PassExpert pe;
-                pe.blob = c->bufs[plan.access[i].buf].ptr;
-                for (int q = 0; q < batch * cf.top_k; ++q)
-                    if (idx[q] == plan.access[i].expert) pe.pairs.push_back(q);
-                return pe;
-            };
             std::vector<PassExpert> group;
             std::vector<int> in_flight;
             for (int i : passes[p]) {
@@ -1469,7 +1556,7 @@ extern "C" int32_t moe_layer_step(moe_layer_t *l, moe_layer_t *next, const uint1
             if (rc) return rc;
         }
     }
-    if (plan.victim_needed || passes.size() > 1) {
+    if ((plan.victim_needed || passes.size() > 1) && !spec_issued) {
         // a buffer freed during this step may still be read by its kernels: speculative copies wait for them
         HIPCHK(hipEventRecord(c->ev_compute, c->compute));
         HIPCHK(hipStreamWaitEvent(c->copy, c->ev_compute, 0));

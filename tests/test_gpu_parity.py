@@ -489,14 +489,15 @@ def test_largest_supported_matrices():
 
 
 @pytest.mark.parametrize("H,F,k,m,Bn,T,head_mb", [(256, 512, 2, 2, 1, 48, 0), (1024, 2048, 2, 2, 1, 20, 1), (256, 512, 4, 2, 4, 12, 0),
-                                                  (256, 512, 4, 2, 16, 6, 0), (256, 512, 2, 1, 8, 6, 0)])
+                                                  (256, 512, 4, 2, 16, 6, 0), (256, 512, 2, 1, 8, 6, 0), (256, 512, 4, 2, 100, 5, 0), (256, 512, 2, 2, 80, 4, 0)])
 def test_swap_eviction_keeps_every_expert_intact(H, F, k, m, Bn, T, head_mb):
     """Sec. 3.3, hosts that cannot hold every expert (MOE_LAYER_SWAP): every load writes the evicted expert back
     to the host.  Over many swaps every decision still equals the oracle's, every expert sits where the oracle's
     placement says, every output row is in tolerance (a blob damaged on its way out or back would show as soon as
     the expert is used again), and the outputs are bit-identical to the same stack without swapping.  The 3.5 MB
     blobs of the H=1024 case with a 1 MiB head also cover a confirmed guess whose tail is read from the host buffer
-    the expert is about to vacate."""
+    the expert is about to vacate.  Batches above 64 tokens take the prompt-sized schedule (resident experts first,
+    transfers into their buffers guarded by that launch)."""
     L, E = 4, 8
     xs = W.hidden_ar1(61, T, Bn, H)
     outs = {}
