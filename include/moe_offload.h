@@ -293,6 +293,12 @@ int32_t moe_ctx_profile_timeline(moe_ctx_t *ctx, int32_t kind, double *start_ms,
  *                guess costs changes (N MiB instead of a whole expert).  Meant for links that are already saturated;
  *   "fused"      1: such a step runs w1/w3 and w2 as ONE persistent launch with a grid barrier (measured
  *                slower than two launches on MI355X, hence default 0);
+ *   "staged_min_batch" matrix-core batches larger than this (default 0: all of them; GEMV batches of more than one
+ *                token always) run a step in three stages when every buffer that changes hands in it belonged to an
+ *                expert resident at its start: those experts are multiplied first, then the transfers are issued (one
+ *                into a buffer that launch reads waits for it alone), then the arriving experts are multiplied one by
+ *                one as their copies land.  Otherwise, and below the threshold, a step whose buffers are used twice
+ *                runs in passes, a pass's copies waiting for all kernels of the pass before;
  *   "device_routing" 1 (default): a single-token step of a layer whose experts are ALL on the device (cache_slots ==
  *                n_experts, every slot filled) and whose caller asks for no trace is enqueued without waiting for
  *                its gate kernel: no cache decision depends on the routing then, so the FFN kernels read the selection

@@ -109,6 +109,7 @@ struct moe_ctx {
     uint32_t gate_seq = 0;              // sequence number of the last gate launch
     int32_t mfma_form = 2;              // matrix-core kernels: 2 persistent streaming form with fp16 weights, 1 row-staging form with fp32 group scaling
     int32_t mfma_min_batch = 16;        // batches at least this large use the matrix-core kernels (4-bit g64)
+    int32_t staged_min_batch = 0;       // matrix-core batches larger than this: resident experts first, arriving ones one by one
     uint64_t spec_head_bytes = 0;       // 0: a speculative load moves the whole expert at once (as the paper describes);
                                         // > 0: only this many leading bytes, the rest when the guess is confirmed
     bool token_path = true;             // single-token steps: w2 kernel with in-kernel combine + residual (no atomics)
@@ -284,6 +285,7 @@ extern "C" int32_t moe_ctx_create(const moe_ctx_config_t *cfg, void *dev_arena, 
     c->route_w = reinterpret_cast<float *>(base + p.route + 128);
     c->device_routing = env_int("MOE_DEVICE_ROUTING", 1) != 0;
     c->mfma_min_batch = env_int("MOE_MFMA_MIN_BATCH", 16);
+    c->staged_min_batch = env_int("MOE_STAGED_MIN_BATCH", c->staged_min_batch);
     c->fused = env_int("MOE_FUSED", 0) != 0;
     hipError_t e = hipMemset(c->barrier, 0, 4096);
     if (e == hipSuccess) {
@@ -1437,29 +1439,48 @@ extern "C" int32_t moe_layer_step(moe_layer_t *l, moe_layer_t *next, const uint1
             if (idx[q] == plan.access[i].expert) pe.pairs.push_back(q);
         return pe;
     };
-    // Prompt-sized batch (Sec. 3: a prompt goes through a layer in one step and needs nearly every expert) in which
-    // every buffer that changes hands belonged to an expert resident when the step began.  Those experts are
-    // multiplied first, in one launch pair per window, before any transfer is issued; a transfer into one of their
-    // buffers -- a miss that found no free staging buffer, a speculative load for the next layer -- then waits for
-    // that launch only, not for the multiplies of the experts still arriving, which follow one by one as their
-    // copies land.  The link never waits for a multiply that itself waits for the link.
+    // The accesses `set` as one launch (pair): matrix cores, or GEMV entries of up to nt tokens each.
+    auto launch_set = [&](const std::vector<int> &set) -> int32_t {
+        if (set.empty()) return MOE_OK;
+        if (use_mfma) {
+            std::vector<PassExpert> g;
+            for (int i : set) g.push_back(pass_expert(i));
+            return launch_mfma(l, g, w, batch);
+        }
+        std::vector<FfnEntry> entries;
+        for (int i : set) {
+            FfnEntry en{};
+            en.blob = c->bufs[plan.access[i].buf].ptr;
+            for (int q = 0; q < batch * cf.top_k; ++q) {
+                if (idx[q] != plan.access[i].expert) continue;
+                en.tok[en.n_tok] = q / cf.top_k; en.pair[en.n_tok] = q; en.w[en.n_tok] = w[q];
+                if (++en.n_tok == nt) { entries.push_back(en); en.n_tok = 0; }
+            }
+            if (en.n_tok) entries.push_back(en);
+        }
+        return launch_ffn(l, entries, nt);
+    };
+    // A step of several tokens in which every buffer that changes hands belonged to an expert resident when the step
+    // began (a prompt, Sec. 3, needs nearly every expert of a layer, and so does a decode batch of a few dozen
+    // tokens).  Those experts are multiplied first, in one launch, before any transfer is issued; a transfer into one
+    // of their buffers -- a miss that found no free staging buffer, a speculative load for the next layer -- then
+    // waits for that launch only, not for the multiplies of the experts still arriving, which follow one by one as
+    // their copies land, each under the next one's transfer.  The link never waits for a multiply that itself waits
+    // for the link.
     bool staged_step = false;
-    if (use_mfma && batch > 64 && plan.victims_resident) {
-        std::vector<PassExpert> group;
-        std::vector<int> arriving;
+    if (batch > 1 && plan.victims_resident && (!use_mfma || batch > c->staged_min_batch)) {
+        std::vector<int> first, arriving;
         std::vector<int32_t> read_first;       // buffers the first launch reads
         for (int i = 0; i < (int)plan.access.size(); ++i) {
             const AccessRec &a = plan.access[i];
             if (a.status != MOE_HIT) { arriving.push_back(i); continue; }
             PoolBuf &pb = c->bufs[a.buf];
             if (pb.pending) { HIPCHK(hipStreamWaitEvent(c->compute, pb.ready, 0)); pb.pending = false; }
-            group.push_back(pass_expert(i));
+            first.push_back(i);
             read_first.push_back(a.buf);
         }
-        if (!group.empty()) {
-            rc = launch_mfma(l, group, w, batch);
-            if (rc) return rc;
-        }
+        rc = launch_set(first);
+        if (rc) return rc;
         bool guarded = false;
         auto needs_guard = [&](int32_t buf) { return !guarded && std::find(read_first.begin(), read_first.end(), buf) != read_first.end(); };
         for (int i : arriving) {
@@ -1484,7 +1505,7 @@ extern "C" int32_t moe_layer_step(moe_layer_t *l, moe_layer_t *next, const uint1
         for (int i : arriving) {
             PoolBuf &pb = c->bufs[plan.access[i].buf];
             if (pb.pending) { HIPCHK(hipStreamWaitEvent(c->compute, pb.ready, 0)); pb.pending = false; }
-            rc = launch_mfma(l, std::vector<PassExpert>{pass_expert(i)}, w, batch);
+            rc = launch_set(std::vector<int>{i});
             if (rc) return rc;
         }
         staged_step = true;
@@ -1715,6 +1736,7 @@ extern "C" int32_t moe_ctx_set_option(moe_ctx_t *c, const char *name, int32_t va
     else if (n == "mfma_min_batch" && value >= 1) c->mfma_min_batch = value;
     else if (n == "mfma_form" && (value == 1 || value == 2)) c->mfma_form = value;
     else if (n == "device_routing") c->device_routing = value != 0;
+    else if (n == "staged_min_batch" && value >= 0) c->staged_min_batch = value;
     else return fail(MOE_EINVAL, "moe_ctx_set_option: unknown option or bad value: %s = %d", name, value);
     return MOE_OK;
 }
