@@ -262,7 +262,10 @@ int32_t moe_ctx_read_y(moe_ctx_t *ctx, int32_t batch, int32_t hidden, float *y_h
  * enqueued on (gate, w1/w3 kernel, w2 kernel, one-launch single-token FFN kernel `ffn`: compute stream;
  * expert copies: copy stream; write-backs of evicted experts in swap mode: the library's write-back stream).
  * `bytes` are algorithmic: each distinct expert a launch touches counts its packed w1+w3 (or w2) once;
- * a copy counts the blob.  enable(1) clears the accumulators; read waits for both streams. */
+ * a copy counts the blob.  enable(1) clears the accumulators; read waits for both streams.
+ * Option "profile_copy_stride" = n > 1 times only every n-th transfer (copy and write-back entries then cover those
+ * transfers only; the byte totals of all transfers are in moe_stats_t): two event records around every copy take
+ * about 1 % off a saturated link. */
 typedef struct { uint64_t launches; uint64_t bytes; double total_ms; } moe_profile_entry_t;
 typedef struct { moe_profile_entry_t gate, w13, w2, copy, ffn, writeback; } moe_profile_t;
 int32_t moe_ctx_profile_enable(moe_ctx_t *ctx, int32_t on);

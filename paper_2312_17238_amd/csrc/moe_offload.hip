@@ -87,6 +87,8 @@ struct Profiler {
     ProfKind kind[PROF_KINDS];
     static constexpr size_t RING = 65536;      // pairs per kind before a drain (which synchronises) is needed
     static constexpr size_t PREALLOC = 16384;  // pairs per kind created when profiling is switched on
+    int32_t copy_stride = 1;                   // time every n-th transfer only: the two event records per copy cost the link ~1 %
+    uint64_t copy_seq = 0;
 };
 
 struct moe_ctx {
@@ -808,8 +810,9 @@ static int32_t issue_copy(moe_ctx *c, moe_layer *owner, const CopyOp &op)
         HIPCHK(hipStreamWaitEvent(c->copy, c->bufs[owner->host_writer[op.host_buf]].drained, 0));
         owner->host_writer[op.host_buf] = -1;
     }
-    int ps;
-    int32_t rc = prof_begin(c, PROF_COPY, c->copy, op.bytes, &ps);
+    int ps = -1;
+    int32_t rc = MOE_OK;
+    if (c->prof.on && c->prof.copy_seq++ % (uint64_t)c->prof.copy_stride == 0) rc = prof_begin(c, PROF_COPY, c->copy, op.bytes, &ps);
     if (rc) return rc;
     HIPCHK(hipMemcpyAsync(b.ptr + op.offset, owner->host_blobs + (uint64_t)op.host_buf * owner->lay.total + op.offset, op.bytes,
                           hipMemcpyHostToDevice, c->copy));
@@ -831,8 +834,9 @@ static int32_t issue_writeback(moe_ctx *c, moe_layer *owner, const CopyOp &op)
         owner->host_reader[op.host_buf] = -1;
     }
     HIPCHK(hipStreamWaitEvent(c->writeback, b.ready, 0));   // the victim's own load (it may have come in earlier in this very step)
-    int ps;
-    int32_t rc = prof_begin(c, PROF_WRITEBACK, c->writeback, op.bytes, &ps);
+    int ps = -1;
+    int32_t rc = MOE_OK;
+    if (c->prof.on && c->prof.copy_seq++ % (uint64_t)c->prof.copy_stride == 0) rc = prof_begin(c, PROF_WRITEBACK, c->writeback, op.bytes, &ps);
     if (rc) return rc;
     HIPCHK(hipMemcpyAsync(owner->host_blobs + (uint64_t)op.host_buf * owner->lay.total, b.ptr, op.bytes, hipMemcpyDeviceToHost, c->writeback));
     rc = prof_end(c, PROF_WRITEBACK, c->writeback, ps);
@@ -1737,6 +1741,7 @@ extern "C" int32_t moe_ctx_set_option(moe_ctx_t *c, const char *name, int32_t va
     else if (n == "mfma_form" && (value == 1 || value == 2)) c->mfma_form = value;
     else if (n == "device_routing") c->device_routing = value != 0;
     else if (n == "staged_min_batch" && value >= 0) c->staged_min_batch = value;
+    else if (n == "profile_copy_stride" && value >= 1) c->prof.copy_stride = value;
     else return fail(MOE_EINVAL, "moe_ctx_set_option: unknown option or bad value: %s = %d", name, value);
     return MOE_OK;
 }
