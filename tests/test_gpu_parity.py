@@ -687,6 +687,30 @@ def test_device_routed_steps_log_wraps():
     model.close()
 
 
+def test_profile_timeline_matches_profile_totals():
+    """The diagnostic timeline lists every timed launch of a kind with start <= stop, in issue order, and its
+    durations add up to what moe_ctx_profile_read reports; with a copy stride of 3 a third of the transfers is timed."""
+    model = Model(3, 256, 512, 8, 2, None, 2, 2, 1e-5, seed=97, keep_layers=[])
+    B.moe_ctx_set_option(model.stack.ctx, "profile_copy_stride", 3)
+    B.moe_ctx_profile_enable(model.stack.ctx, True)
+    xs = W.hidden_ar1(97, 12, 1, 256).to(model.stack.device)
+    x_out = torch.empty(1, 256, dtype=torch.float16, device=model.stack.device)
+    for t in range(12):
+        model.stack.step(xs[t], x_out, None)
+    model.stack.synchronize()
+    lines = {k: B.moe_ctx_profile_timeline(model.stack.ctx, k) for k in range(6)}
+    prof = B.moe_ctx_profile_read(model.stack.ctx).as_dict()
+    for k, name in enumerate(("gate", "w13", "w2", "copy", "ffn", "writeback")):
+        tl = lines[k]
+        assert len(tl) == prof[name]["launches"]
+        assert all(0.0 <= a <= b for a, b in tl) and all(tl[i][0] <= tl[i + 1][0] for i in range(len(tl) - 1))
+        assert abs(sum(b - a for a, b in tl) - prof[name]["total_ms"]) <= 1e-3 * max(1.0, prof[name]["total_ms"])
+    st = model.stack.total_stats()
+    n_copies = st["misses"] + st["spec_issued"]
+    assert len(lines[0]) == len(lines[1]) == len(lines[2]) == 36 and len(lines[3]) == -(-n_copies // 3) and not lines[4] and not lines[5]
+    model.close()
+
+
 def test_recall_study_tool_against_closed_forms():
     """paper_2312_17238_amd.recall_study (the Fig. 2 analogue): on a small stack its LRU hit ratio for k = top_k = 2
     equals the closed form sum_t |S_t & S_{t-1}| / needed, for k = E only the first touches miss, and guessing all
