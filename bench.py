@@ -56,7 +56,7 @@ def build_model(shape, formats, batch, device, keep_layers, n_staging=4, swap=Fa
             for m, mat in enumerate(mats):
                 stack.load_expert(l, e, m, *mat)
             if l in keep_layers:
-                kept[(l, e)] = [tuple(t.cpu().numpy() for t in mat) for mat in mats]
+                kept[(l, e)] = [tuple(t.cpu().numpy() if hasattr(t, "cpu") else t for t in mat) for mat in mats]
             del mats
         if l % 4 == 3 or l + 1 == shape.layers:
             log(f"generated, quantized and loaded layers 0..{l} ({time.time() - t0:.1f} s)")
