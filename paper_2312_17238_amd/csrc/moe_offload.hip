@@ -55,6 +55,21 @@ static int32_t fail(int32_t code, const char *fmt, ...)
         }                                                                                              \
     } while (0)
 
+// The boundary lets no C++ exception through (allocation failures of the containers, thread creation): every exported
+// function that can raise one is a function-try-block ending here.
+static int32_t on_exception(const char *what) noexcept
+{
+    try {
+        throw;
+    } catch (const std::bad_alloc &) {
+        return fail(MOE_ENOMEM, "%s: out of host memory", what);
+    } catch (const std::exception &e) {
+        return fail(MOE_ESTATE, "%s: %s", what, e.what());
+    } catch (...) {
+        return fail(MOE_ESTATE, "%s: unknown exception", what);
+    }
+}
+
 extern "C" const char *moe_last_error(void) { return g_err; }
 extern "C" int32_t moe_last_hip_error(void) { return g_hip_err; }
 
@@ -248,7 +263,7 @@ static int env_int(const char *name, int dflt)
 
 extern "C" int32_t moe_ctx_create(const moe_ctx_config_t *cfg, void *dev_arena, uint64_t dev_arena_bytes,
                                   void *compute_stream, void *copy_stream, moe_ctx_t **out)
-{
+try {
     if (!out) return fail(MOE_EINVAL, "moe_ctx_create: out is null");
     *out = nullptr;
     if (!ctx_cfg_ok(cfg)) return fail(MOE_EINVAL, "moe_ctx_create: bad configuration");
@@ -315,10 +330,12 @@ extern "C" int32_t moe_ctx_create(const moe_ctx_config_t *cfg, void *dev_arena, 
     memset(c->gate_out, 0, sizeof(GateHostOut));
     *out = c;
     return MOE_OK;
+} catch (...) {
+    return on_exception("moe_ctx_create");
 }
 
 extern "C" int32_t moe_ctx_destroy(moe_ctx_t *c)
-{
+try {
     if (!c) return MOE_OK;
     if (c->host_only) {
         free(c->gate_out);
@@ -342,6 +359,8 @@ extern "C" int32_t moe_ctx_destroy(moe_ctx_t *c)
     }
     delete c;
     return MOE_OK;
+} catch (...) {
+    return on_exception("moe_ctx_destroy");
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -364,7 +383,7 @@ static void cache_init(moe_layer *l)
 extern "C" int32_t moe_layer_create(moe_ctx_t *ctx, const moe_layer_config_t *cfg, const float *gate_w_host,
                                     const uint16_t *rms_gamma_host, void *dev_mem, void *pinned_host_mem,
                                     moe_layer_t **out)
-{
+try {
     if (!out) return fail(MOE_EINVAL, "moe_layer_create: out is null");
     *out = nullptr;
     if (!ctx) return fail(MOE_EINVAL, "moe_layer_create: ctx is null");
@@ -427,10 +446,12 @@ extern "C" int32_t moe_layer_create(moe_ctx_t *ctx, const moe_layer_config_t *cf
     ctx->n_layers++;
     *out = l;
     return MOE_OK;
+} catch (...) {
+    return on_exception("moe_layer_create");
 }
 
 extern "C" int32_t moe_layer_destroy(moe_layer_t *l)
-{
+try {
     if (!l) return MOE_OK;
     (void)fold_pending(l->ctx);
     if (!l->ctx->host_only) {
@@ -441,6 +462,8 @@ extern "C" int32_t moe_layer_destroy(moe_layer_t *l)
     l->ctx->n_layers--;
     delete l;   // pool buffers and their events stay with the context until it is destroyed
     return MOE_OK;
+} catch (...) {
+    return on_exception("moe_layer_destroy");
 }
 
 static bool all_loaded(const moe_layer *l)
@@ -505,10 +528,14 @@ static int32_t load_matrix(moe_layer *l, int32_t expert, int32_t matrix, const u
         work(0, m.rows);
     } else {
         std::vector<std::thread> th;
+        th.reserve(nthreads);
         const uint32_t per = (m.rows + nthreads - 1) / nthreads;
         for (unsigned t = 0; t < nthreads; ++t) {
             uint32_t r0 = t * per, r1 = std::min(m.rows, r0 + per);
-            if (r0 < r1) th.emplace_back(work, r0, r1);
+            if (r0 >= r1) continue;
+            // a thread that cannot be started (resource limits) leaves its share to this one: a joinable thread must
+            // never be destroyed by an exception on its way out
+            try { th.emplace_back(work, r0, r1); } catch (...) { work(r0, r1); }
         }
         for (std::thread &t : th) t.join();
     }
@@ -520,7 +547,7 @@ static int32_t load_matrix(moe_layer *l, int32_t expert, int32_t matrix, const u
 
 extern "C" int32_t moe_layer_load_expert(moe_layer_t *l, int32_t expert, int32_t matrix, const uint8_t *codes,
                                          const uint16_t *scale, const uint16_t *zero)
-{
+try {
     if (!l || !codes || !scale || !zero) return fail(MOE_EINVAL, "moe_layer_load_expert: null argument");
     if (l->lay.scale_group) return fail(MOE_ESTATE, "moe_layer_load_expert: the layer has two-level metadata; use moe_layer_load_expert_2level");
     if (matrix < 0 || matrix > 2) return fail(MOE_EINVAL, "moe_layer_load_expert: matrix %d out of range", matrix);
@@ -530,11 +557,13 @@ extern "C" int32_t moe_layer_load_expert(moe_layer_t *l, int32_t expert, int32_t
     return load_matrix(l, expert, matrix, codes, [&](uint32_t r, uint8_t *dst) {
         pack_row(b, m, codes + (uint64_t)r * m.cols, scale + (uint64_t)r * groups, zero + (uint64_t)r * groups, dst);
     });
+} catch (...) {
+    return on_exception("moe_layer_load_expert");
 }
 
 extern "C" int32_t moe_layer_load_expert_2level(moe_layer_t *l, int32_t expert, int32_t matrix, const uint8_t *codes,
                                                 const uint8_t *scale_code, const uint8_t *zero_code, const uint16_t *run_meta)
-{
+try {
     if (!l || !codes || !scale_code || !zero_code || !run_meta) return fail(MOE_EINVAL, "moe_layer_load_expert_2level: null argument");
     if (!l->lay.scale_group) return fail(MOE_ESTATE, "moe_layer_load_expert_2level: the layer has one-level metadata; use moe_layer_load_expert");
     if (matrix < 0 || matrix > 2) return fail(MOE_EINVAL, "moe_layer_load_expert_2level: matrix %d out of range", matrix);
@@ -545,11 +574,13 @@ extern "C" int32_t moe_layer_load_expert_2level(moe_layer_t *l, int32_t expert, 
         pack_row_meta8(b, m, codes + (uint64_t)r * m.cols, scale_code + (uint64_t)r * groups, zero_code + (uint64_t)r * groups,
                        run_meta + (uint64_t)r * runs * 4, dst);
     });
+} catch (...) {
+    return on_exception("moe_layer_load_expert_2level");
 }
 
 extern "C" int32_t moe_layer_peek_weight(const moe_layer_t *l, int32_t expert, int32_t matrix, int32_t row, int32_t col,
                                          uint8_t *code, uint16_t *scale, uint16_t *zero)
-{
+try {
     if (!l || !code || !scale || !zero) return fail(MOE_EINVAL, "moe_layer_peek_weight: null argument");
     if (expert < 0 || expert >= l->cfg.n_experts || matrix < 0 || matrix > 2)
         return fail(MOE_EINVAL, "moe_layer_peek_weight: expert or matrix out of range");
@@ -568,11 +599,13 @@ extern "C" int32_t moe_layer_peek_weight(const moe_layer_t *l, int32_t expert, i
     }
     peek_row(l->lay, m, blob + row_offset(l->lay, matrix, row), col, code, scale, zero);
     return MOE_OK;
+} catch (...) {
+    return on_exception("moe_layer_peek_weight");
 }
 
 extern "C" int32_t moe_layer_peek_run_meta(const moe_layer_t *l, int32_t expert, int32_t matrix, int32_t row, int32_t col,
                                            uint16_t *run_meta)
-{
+try {
     if (!l || !run_meta) return fail(MOE_EINVAL, "moe_layer_peek_run_meta: null argument");
     if (!l->lay.scale_group) return fail(MOE_ESTATE, "moe_layer_peek_run_meta: the layer has one-level metadata");
     if (expert < 0 || expert >= l->cfg.n_experts || matrix < 0 || matrix > 2)
@@ -586,6 +619,8 @@ extern "C" int32_t moe_layer_peek_run_meta(const moe_layer_t *l, int32_t expert,
     uint8_t c, sc, zc;
     peek_row_meta8(l->lay, m, blob + row_offset(l->lay, matrix, row), col, &c, &sc, &zc, run_meta);
     return MOE_OK;
+} catch (...) {
+    return on_exception("moe_layer_peek_run_meta");
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -637,7 +672,7 @@ static int32_t prof_end(moe_ctx *c, int k, hipStream_t s, int slot)
 }
 
 extern "C" int32_t moe_ctx_profile_enable(moe_ctx_t *c, int32_t on)
-{
+try {
     if (!c) return fail(MOE_EINVAL, "moe_ctx_profile_enable: ctx is null");
     if (c->host_only) return fail(MOE_ESTATE, "moe_ctx_profile_enable: host-only context");
     HIPCHK(hipStreamSynchronize(c->compute));
@@ -662,10 +697,12 @@ extern "C" int32_t moe_ctx_profile_enable(moe_ctx_t *c, int32_t on)
     }
     c->prof.on = on != 0;
     return MOE_OK;
+} catch (...) {
+    return on_exception("moe_ctx_profile_enable");
 }
 
 extern "C" int32_t moe_ctx_profile_timeline(moe_ctx_t *c, int32_t kind, double *start_ms, double *stop_ms, int32_t cap, int32_t *n)
-{
+try {
     if (!c || !n || kind < 0 || kind >= PROF_KINDS || cap < 0 || (cap > 0 && (!start_ms || !stop_ms)))
         return fail(MOE_EINVAL, "moe_ctx_profile_timeline: bad argument");
     if (c->host_only || !c->prof.base) return fail(MOE_ESTATE, "moe_ctx_profile_timeline: profiling was never switched on");
@@ -682,10 +719,12 @@ extern "C" int32_t moe_ctx_profile_timeline(moe_ctx_t *c, int32_t kind, double *
         stop_ms[i] = b;
     }
     return MOE_OK;
+} catch (...) {
+    return on_exception("moe_ctx_profile_timeline");
 }
 
 extern "C" int32_t moe_ctx_profile_read(moe_ctx_t *c, moe_profile_t *out)
-{
+try {
     if (!c || !out) return fail(MOE_EINVAL, "moe_ctx_profile_read: null argument");
     if (c->host_only) return fail(MOE_ESTATE, "moe_ctx_profile_read: host-only context");
     HIPCHK(hipStreamSynchronize(c->compute));
@@ -700,6 +739,8 @@ extern "C" int32_t moe_ctx_profile_read(moe_ctx_t *c, moe_profile_t *out)
         dst[k]->total_ms = c->prof.kind[k].ms;
     }
     return MOE_OK;
+} catch (...) {
+    return on_exception("moe_ctx_profile_read");
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -873,7 +914,7 @@ static int32_t check_step_args(const moe_layer *l, const moe_layer *next, int32_
 
 extern "C" int32_t moe_layer_resolve(moe_layer_t *l, moe_layer_t *next, const int32_t *expert_idx, int32_t batch,
                                      const double *guess_score, moe_step_trace_t *trace)
-{
+try {
     int32_t rc = check_step_args(l, next, batch);
     if (rc) return rc;
     if (!expert_idx) return fail(MOE_EINVAL, "moe_layer_resolve: expert_idx is null");
@@ -888,6 +929,8 @@ extern "C" int32_t moe_layer_resolve(moe_layer_t *l, moe_layer_t *next, const in
         for (const CopyOp &op : plan.spec) { rc = issue_copy(l->ctx, next, op); if (rc) return rc; }
     }
     return MOE_OK;
+} catch (...) {
+    return on_exception("moe_layer_resolve");
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1369,7 +1412,7 @@ static int32_t device_routed_step(moe_layer *l, const uint16_t *x_in, uint16_t *
 
 extern "C" int32_t moe_layer_step(moe_layer_t *l, moe_layer_t *next, const uint16_t *x_in, int32_t batch,
                                   uint16_t *x_out, uint16_t *h_out, moe_step_trace_t *trace)
-{
+try {
     int32_t rc = check_step_args(l, next, batch);
     if (rc) return rc;
     moe_ctx *c = l->ctx;
@@ -1593,10 +1636,12 @@ extern "C" int32_t moe_layer_step(moe_layer_t *l, moe_layer_t *next, const uint1
         HIPCHK(hipGetLastError());
     }
     return MOE_OK;
+} catch (...) {
+    return on_exception("moe_layer_step");
 }
 
 extern "C" int32_t moe_layer_prefetch(moe_layer_t *l, const uint16_t *h_dev, int32_t batch, moe_step_trace_t *trace)
-{
+try {
     int32_t rc = check_step_args(l, nullptr, batch);
     if (rc) return rc;
     moe_ctx *c = l->ctx;
@@ -1632,11 +1677,13 @@ extern "C" int32_t moe_layer_prefetch(moe_layer_t *l, const uint16_t *h_dev, int
         for (int e = 0; e < l->cfg.n_experts; ++e) trace->guess_score[e] = score[e];
     }
     return MOE_OK;
+} catch (...) {
+    return on_exception("moe_layer_prefetch");
 }
 
 extern "C" int32_t moe_stack_step(moe_layer_t *const *layers, int32_t n_layers, const uint16_t *x_in, int32_t batch,
                                   uint16_t *x_out, moe_step_trace_t *traces)
-{
+try {
     if (!layers || n_layers < 1) return fail(MOE_EINVAL, "moe_stack_step: no layers");
     for (int i = 0; i < n_layers; ++i)
         if (!layers[i] || layers[i]->ctx != layers[0]->ctx || layers[i]->cfg.hidden != layers[0]->cfg.hidden)
@@ -1651,6 +1698,8 @@ extern "C" int32_t moe_stack_step(moe_layer_t *const *layers, int32_t n_layers, 
         cur = dst;
     }
     return MOE_OK;
+} catch (...) {
+    return on_exception("moe_stack_step");
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1658,7 +1707,7 @@ extern "C" int32_t moe_stack_step(moe_layer_t *const *layers, int32_t n_layers, 
 // ---------------------------------------------------------------------------------------------
 
 extern "C" int32_t moe_layer_stats(const moe_layer_t *l, moe_stats_t *o)
-{
+try {
     if (!l || !o) return fail(MOE_EINVAL, "moe_layer_stats: null argument");
     int32_t rc = fold_pending(l->ctx);
     if (rc) return rc;
@@ -1666,11 +1715,13 @@ extern "C" int32_t moe_layer_stats(const moe_layer_t *l, moe_stats_t *o)
     *o = {s.steps, s.needed, s.hits, s.prefetch_hits, s.misses, s.evictions, s.spec_issued, s.spec_wasted, s.bytes_demand, s.bytes_spec,
           s.bytes_writeback, l->steps_device_routed};
     return MOE_OK;
+} catch (...) {
+    return on_exception("moe_layer_stats");
 }
 
 extern "C" int32_t moe_layer_cache_state(const moe_layer_t *l, int32_t *slot_expert, uint64_t *slot_stamp, int32_t *staged,
                                          int32_t *n_staged)
-{
+try {
     if (!l) return fail(MOE_EINVAL, "moe_layer_cache_state: layer is null");
     int32_t rc = fold_pending(l->ctx);
     if (rc) return rc;
@@ -1682,19 +1733,23 @@ extern "C" int32_t moe_layer_cache_state(const moe_layer_t *l, int32_t *slot_exp
         for (size_t i = 0; i < l->cache.staged.size() && i < MOE_MAX_EXPERTS; ++i) staged[i] = l->cache.staged[i].expert;
     if (n_staged) *n_staged = (int32_t)l->cache.staged.size();
     return MOE_OK;
+} catch (...) {
+    return on_exception("moe_layer_cache_state");
 }
 
 extern "C" int32_t moe_layer_placement(const moe_layer_t *l, int32_t *host_buf_of, int32_t *spare_host)
-{
+try {
     if (!l) return fail(MOE_EINVAL, "moe_layer_placement: layer is null");
     if (host_buf_of)
         for (int e = 0; e < l->cfg.n_experts; ++e) host_buf_of[e] = l->host_buf_of[e];
     if (spare_host) *spare_host = l->spare_host;
     return MOE_OK;
+} catch (...) {
+    return on_exception("moe_layer_placement");
 }
 
 extern "C" int32_t moe_layer_reset(moe_layer_t *l)
-{
+try {
     if (!l) return fail(MOE_EINVAL, "moe_layer_reset: layer is null");
     if (l->swap) return fail(MOE_ESTATE, "moe_layer_reset: a layer in swap mode cannot return to its initial placement; create it again");
     moe_ctx *c = l->ctx;
@@ -1713,10 +1768,12 @@ extern "C" int32_t moe_layer_reset(moe_layer_t *l)
         for (int e = 0; e < l->cfg.cache_slots; ++e)
             if (l->loaded[e] == 7u) { int32_t rc = warm_fill(l, e); if (rc) return rc; }
     return MOE_OK;
+} catch (...) {
+    return on_exception("moe_layer_reset");
 }
 
 extern "C" int32_t moe_ctx_read_y(moe_ctx_t *c, int32_t batch, int32_t hidden, float *y_host)
-{
+try {
     if (!c || !y_host) return fail(MOE_EINVAL, "moe_ctx_read_y: null argument");
     if (c->host_only) return fail(MOE_ESTATE, "moe_ctx_read_y: host-only context");
     if (batch < 1 || batch > c->cfg.max_batch || hidden < 1 || hidden > c->cfg.max_hidden)
@@ -1724,10 +1781,12 @@ extern "C" int32_t moe_ctx_read_y(moe_ctx_t *c, int32_t batch, int32_t hidden, f
     HIPCHK(hipStreamSynchronize(c->compute));
     HIPCHK(hipMemcpy(y_host, c->yacc, (size_t)batch * hidden * sizeof(float), hipMemcpyDeviceToHost));
     return MOE_OK;
+} catch (...) {
+    return on_exception("moe_ctx_read_y");
 }
 
 extern "C" int32_t moe_ctx_set_option(moe_ctx_t *c, const char *name, int32_t value)
-{
+try {
     if (!c || !name) return fail(MOE_EINVAL, "moe_ctx_set_option: null argument");
     const std::string n(name);
     if (n == "w13_blocks" && value >= 1) c->w13_blocks = value;
@@ -1744,6 +1803,8 @@ extern "C" int32_t moe_ctx_set_option(moe_ctx_t *c, const char *name, int32_t va
     else if (n == "profile_copy_stride" && value >= 1) c->prof.copy_stride = value;
     else return fail(MOE_EINVAL, "moe_ctx_set_option: unknown option or bad value: %s = %d", name, value);
     return MOE_OK;
+} catch (...) {
+    return on_exception("moe_ctx_set_option");
 }
 
 // The timed part of moe_probe_bandwidth; the caller owns (and always releases) the events and the sink.
@@ -1767,7 +1828,7 @@ static int32_t probe_run(const void *src_dev, void *dst_dev, uint64_t bytes, int
 
 extern "C" int32_t moe_probe_bandwidth(const void *src_dev, void *dst_dev, uint64_t bytes, int32_t blocks, int32_t iters,
                                        void *stream, double *avg_ms)
-{
+try {
     if (!src_dev || !avg_ms || bytes < 16 || blocks < 1 || iters < 1) return fail(MOE_EINVAL, "moe_probe_bandwidth: bad argument");
     hipEvent_t e0 = nullptr, e1 = nullptr;
     uint32_t *sink = nullptr;
@@ -1785,23 +1846,29 @@ extern "C" int32_t moe_probe_bandwidth(const void *src_dev, void *dst_dev, uint6
     if (e0) (void)hipEventDestroy(e0);
     if (e1) (void)hipEventDestroy(e1);
     return rc;
+} catch (...) {
+    return on_exception("moe_probe_bandwidth");
 }
 
 extern "C" int32_t moe_layer_set_prefetch(moe_layer_t *l, int32_t m)
-{
+try {
     if (!l || m < 0 || m > MOE_MAX_GUESS) return fail(MOE_EINVAL, "moe_layer_set_prefetch: bad argument");
     int32_t rc = fold_pending(l->ctx);
     if (rc) return rc;
     l->cfg.prefetch_m = m;
     return MOE_OK;
+} catch (...) {
+    return on_exception("moe_layer_set_prefetch");
 }
 
 extern "C" int32_t moe_layer_set_flags(moe_layer_t *l, int32_t flags)
-{
+try {
     if (!l || (flags & ~MOE_LAYER_NO_CACHE)) return fail(MOE_EINVAL, "moe_layer_set_flags: bad argument");
     if (l->swap && flags) return fail(MOE_EINVAL, "moe_layer_set_flags: a layer in swap mode cannot forget residency");
     int32_t rc = fold_pending(l->ctx);
     if (rc) return rc;
     l->cfg.flags = flags | (l->swap ? MOE_LAYER_SWAP : 0);
     return MOE_OK;
+} catch (...) {
+    return on_exception("moe_layer_set_flags");
 }
