@@ -16,6 +16,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <memory>
 #include <new>
 #include <string>
 #include <thread>
@@ -269,6 +270,7 @@ try {
     if (!ctx_cfg_ok(cfg)) return fail(MOE_EINVAL, "moe_ctx_create: bad configuration");
     moe_ctx *c = new (std::nothrow) moe_ctx();
     if (!c) return fail(MOE_ENOMEM, "moe_ctx_create: out of host memory");
+    std::unique_ptr<moe_ctx, int32_t (*)(moe_ctx *)> own(c, moe_ctx_destroy);   // released into *out on success
     c->cfg = *cfg;
     c->host_only = (cfg->flags & MOE_CTX_HOST_ONLY) != 0;
     c->buf_bytes = align_u64(cfg->max_expert_bytes, 4096);
@@ -280,14 +282,14 @@ try {
     c->sync_wait = env_int("MOE_SYNC_WAIT", 0) != 0;
     if (c->host_only) {
         c->gate_out = static_cast<GateHostOut *>(calloc(1, sizeof(GateHostOut)));
-        if (!c->gate_out) { delete c; return fail(MOE_ENOMEM, "moe_ctx_create: out of host memory"); }
-        *out = c;
+        if (!c->gate_out) return fail(MOE_ENOMEM, "moe_ctx_create: out of host memory");
+        *out = own.release();
         return MOE_OK;
     }
     const ScratchPlan p = plan_scratch(cfg);
-    if (!dev_arena || ((uintptr_t)dev_arena & 255)) { delete c; return fail(MOE_EINVAL, "moe_ctx_create: device arena null or not 256-byte aligned"); }
-    if (dev_arena_bytes < p.total) { delete c; return fail(MOE_ENOMEM, "moe_ctx_create: device arena has %llu bytes, %llu needed", (unsigned long long)dev_arena_bytes, (unsigned long long)p.total); }
-    if (compute_stream == copy_stream) { delete c; return fail(MOE_EINVAL, "moe_ctx_create: compute and copy stream must differ"); }
+    if (!dev_arena || ((uintptr_t)dev_arena & 255)) return fail(MOE_EINVAL, "moe_ctx_create: device arena null or not 256-byte aligned");
+    if (dev_arena_bytes < p.total) return fail(MOE_ENOMEM, "moe_ctx_create: device arena has %llu bytes, %llu needed", (unsigned long long)dev_arena_bytes, (unsigned long long)p.total);
+    if (compute_stream == copy_stream) return fail(MOE_EINVAL, "moe_ctx_create: compute and copy stream must differ");
     c->compute = static_cast<hipStream_t>(compute_stream);
     c->copy = static_cast<hipStream_t>(copy_stream);
     uint8_t *base = static_cast<uint8_t *>(dev_arena);
@@ -324,11 +326,10 @@ try {
     }
     if (e != hipSuccess) {
         g_hip_err = (int32_t)e;
-        moe_ctx_destroy(c);
         return fail(MOE_EHIP, "moe_ctx_create: HIP set-up failed: %s", hipGetErrorString(e));
     }
     memset(c->gate_out, 0, sizeof(GateHostOut));
-    *out = c;
+    *out = own.release();
     return MOE_OK;
 } catch (...) {
     return on_exception("moe_ctx_create");
@@ -396,6 +397,7 @@ try {
     if ((uintptr_t)pinned_host_mem & 63) return fail(MOE_EINVAL, "moe_layer_create: host arena not 64-byte aligned");
     moe_layer *l = new (std::nothrow) moe_layer();
     if (!l) return fail(MOE_ENOMEM, "moe_layer_create: out of host memory");
+    std::unique_ptr<moe_layer> own(l);      // released into *out on success
     l->ctx = ctx;
     l->cfg = *cfg;
     l->lay = lay;
@@ -411,7 +413,7 @@ try {
     l->pack_tmp.resize(l->swap ? cfg->cache_slots : 0);
     const int first = (int)ctx->bufs.size();
     if (!ctx->host_only) {
-        if (!dev_mem || ((uintptr_t)dev_mem & 255)) { delete l; return fail(MOE_EINVAL, "moe_layer_create: device memory null or not 256-byte aligned"); }
+        if (!dev_mem || ((uintptr_t)dev_mem & 255)) return fail(MOE_EINVAL, "moe_layer_create: device memory null or not 256-byte aligned");
         uint8_t *base = static_cast<uint8_t *>(dev_mem);
         const uint64_t gate_bytes = (uint64_t)cfg->n_experts * cfg->hidden * 4;
         l->gate_w_dev = reinterpret_cast<float *>(base + ctx->buf_bytes * cfg->cache_slots);
@@ -434,7 +436,6 @@ try {
         if (e != hipSuccess) {
             for (PoolBuf &b : fresh) { if (b.ready) (void)hipEventDestroy(b.ready); if (b.drained) (void)hipEventDestroy(b.drained); }
             g_hip_err = (int32_t)e;
-            delete l;
             return fail(MOE_EHIP, "moe_layer_create: HIP set-up failed: %s", hipGetErrorString(e));
         }
         for (PoolBuf &b : fresh) ctx->bufs.push_back(b);
@@ -444,7 +445,7 @@ try {
     for (int s = 0; s < cfg->cache_slots; ++s) l->own_bufs.push_back(first + s);
     cache_init(l);
     ctx->n_layers++;
-    *out = l;
+    *out = own.release();
     return MOE_OK;
 } catch (...) {
     return on_exception("moe_layer_create");
