@@ -145,6 +145,16 @@ __global__ __launch_bounds__(GATE_THREADS) void k_gate(GateArgs a)
         }
     }
     __syncthreads();
+    // speculative gate: one thread per expert takes its exponential (thread 0 alone would take them one after another)
+    __shared__ double spec_e[16];
+    if constexpr (SPEC) {
+        if (tid < n2) {
+            double zmax = tot[16];
+            for (int e = 1; e < n2; ++e) zmax = tot[16 + e] > zmax ? tot[16 + e] : zmax;
+            spec_e[tid] = exp(tot[16 + tid] - zmax);
+        }
+        __syncthreads();
+    }
     if (tid == 0) {
         GateHostOut *o = a.out;
         if (n1) {
@@ -190,11 +200,9 @@ __global__ __launch_bounds__(GATE_THREADS) void k_gate(GateArgs a)
                 if (e < n1) o->logits[b * n1 + e] = z[e];
         }
         if (n2) {
-            double zmax = tot[16];
-            for (int e = 1; e < n2; ++e) zmax = tot[16 + e] > zmax ? tot[16 + e] : zmax;
             double ps = 0.0;
-            for (int e = 0; e < n2; ++e) { prob[e] = exp(tot[16 + e] - zmax); ps += prob[e]; }
-            for (int e = 0; e < n2; ++e) o->spec_p[b * n2 + e] = prob[e] / ps;
+            for (int e = 0; e < n2; ++e) ps += spec_e[e];
+            for (int e = 0; e < n2; ++e) o->spec_p[b * n2 + e] = spec_e[e] / ps;
         }
         __hip_atomic_store(&o->done[b], a.seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
     }
