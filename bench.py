@@ -112,6 +112,7 @@ def main() -> int:
                     help="time only every n-th expert transfer with HIP events (1: all; the event pairs slow a saturated link by ~1 %%)")
     ap.add_argument("--spec-head-mb", type=int, default=4,
                     help="speculative loads copy only the first N MiB until the guess is confirmed (0: whole expert, as in the paper)")
+    ap.add_argument("--mfma-form", type=int, default=0, help="matrix-core kernel form 1..3 (0: the library's default)")
     ap.add_argument("--fused", action="store_true", help="single-token steps run w1/w3 and w2 as one persistent launch")
     ap.add_argument("--no-token-path", action="store_true", help="single-token steps use the general kernels (atomics + residual kernel)")
     ap.add_argument("--no-probe", action="store_true", help="skip the plain streaming-read / copy calibration kernels")
@@ -157,6 +158,8 @@ def main() -> int:
     if args.no_cache:
         stack.set_flags(B.MOE_LAYER_NO_CACHE)
     B.moe_ctx_set_option(stack.ctx, "spec_head_mb", args.spec_head_mb)
+    if args.mfma_form:
+        B.moe_ctx_set_option(stack.ctx, "mfma_form", args.mfma_form)
     if args.fused:
         B.moe_ctx_set_option(stack.ctx, "fused", 1)
     if args.no_token_path:

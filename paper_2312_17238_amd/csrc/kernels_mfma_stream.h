@@ -20,6 +20,17 @@
 //              weights; the GEMV kernels keep more).  At the end of an item the waves add their partial
 //              sums through the LDS buffer just consumed, two tiles at a time, in a fixed order.
 //
+// R1 (default when the second level of metadata is absent): the exact subtraction above is left out.  The codes
+//              enter as 1024+q or 64+q (the and_or patterns) and ONE fused multiply-add per pair of weights gives
+//              (bias+q) s - e with e = fp16((bias+z) s): the bias cancels inside the fma, the result is rounded once,
+//              as before.  What the rounding of e leaves, d = e - (bias+z) s (one number per row, group and bias, at
+//              most half an ulp of e), multiplies every activation that meets a code of that bias; the sums of
+//              those activations per (token, group, half of the group, bias) are taken from the A operands the lane already holds
+//              (sixteen two-way dot products with ones per group, shared by the four tiles), and one more MFMA
+//              per (tile, wave, step) adds sum d * (partial sum) back: 16 K-slots = 2 halves x 2 groups x 2 biases
+//              (the rest zero).  The term is ~8 % of the result, so fp16 factors suffice.  A third fewer vector
+//              instructions in the dequantisation.
+//
 // MFMA layouts (v_mfma_f32_32x32x16_f16): A lane l = row (token) l%32, k-slot l/32; B lane l = column (memory
 // row) l%32, k-slot l/32; D lane l, register i = row 8*(i/4) + 4*(l/32) + i%4, column l%32.
 #pragma once
@@ -83,12 +94,44 @@ __device__ __forceinline__ h8_t codes_to_w8(uint32_t w, h2_t b1024, h2_t b64, h2
     return r;
 }
 
+// R1: eight codes -> eight fp16 weights with one fused multiply-add per pair: (bias + q) s - e
+__device__ __forceinline__ h8_t codes_to_w8_r1(uint32_t w, h2_t s2, h2_t ne1024, h2_t ne64)
+{
+    const uint32_t hi = w >> 8;
+    const h2_t t0 = __builtin_elementwise_fma(as_h2(and_or(w, 0x000F000Fu, 0x64006400u)), s2, ne1024);
+    const h2_t t1 = __builtin_elementwise_fma(as_h2(and_or(w, 0x00F000F0u, 0x54005400u)), s2, ne64);
+    const h2_t t2 = __builtin_elementwise_fma(as_h2(and_or(hi, 0x000F000Fu, 0x64006400u)), s2, ne1024);
+    const h2_t t3 = __builtin_elementwise_fma(as_h2(and_or(hi, 0x00F000F0u, 0x54005400u)), s2, ne64);
+    h8_t r;
+    r[0] = t0.x; r[1] = t0.y; r[2] = t1.x; r[3] = t1.y; r[4] = t2.x; r[5] = t2.y; r[6] = t3.x; r[7] = t3.y;
+    return r;
+}
+
+// R1: the lane's 32 activations of one group half (A operand layout) -> fp16 pair (sum of those at positions 0,1,4,5
+// mod 8: they meet the codes that decode with bias 1024; sum of those at 2,3,6,7 mod 8: bias 64), summed in fp32
+__device__ __forceinline__ uint32_t half_sums(const h8_t (&a)[4])
+{
+    const h2_t ones = {(_Float16)1.f, (_Float16)1.f};
+    float s1024 = 0.f, s64 = 0.f;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const u32x4_t u = __builtin_bit_cast(u32x4_t, a[q]);
+        s1024 = __builtin_amdgcn_fdot2(as_h2(u[0]), ones, s1024, false);
+        s64 = __builtin_amdgcn_fdot2(as_h2(u[1]), ones, s64, false);
+        s1024 = __builtin_amdgcn_fdot2(as_h2(u[2]), ones, s1024, false);
+        s64 = __builtin_amdgcn_fdot2(as_h2(u[3]), ones, s64, false);
+    }
+    const h2_t r = {(_Float16)s1024, (_Float16)s64};
+    return __builtin_bit_cast(uint32_t, r);
+}
+
 // META8: two-level metadata (Sec. 4.2 "scale group size").  A step then stages, per row, 16 bytes of (scale code, zero
 // code) byte pairs and the run's fp16 quad instead of 32 bytes of fp16 pairs, and a unit decodes scale and zero in fp32
 // before the same fp16 dequantisation.
-template <bool W13, bool META8>
+template <bool W13, bool META8, bool R1 = false>
 __global__ __launch_bounds__(TL_THREADS, TL_BLOCKS_PER_CU) void k_mfma_stream_q4(TileArgs A)
 {
+    static_assert(!(META8 && R1), "the rank-1 form reads fp16 (scale, zero) pairs");
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const int tid = threadIdx.x, lane = tid & 63, wv = uniform(tid >> 6);
     const int col = lane & 31, kh = lane >> 5;
@@ -177,13 +220,13 @@ __global__ __launch_bounds__(TL_THREADS, TL_BLOCKS_PER_CU) void k_mfma_stream_q4
     for (int rt = 0; rt < TL_RT; ++rt)
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[rt][i] = 0.f;
-    auto token_row = [&](const TileStep &s) -> const uint16_t * {    // lanes past the last token read the first again
+    auto token_index = [&](const TileStep &s) -> int {               // row of act; lanes past the last token read the first again
         const MfmaEntry &en = A.e[s.e];
         const int tk = col < en.n_tok ? col : 0;
-        return A.act + (size_t)(W13 ? l_tok[en.first + tk] : l_pair[en.first + tk]) * A.K;
+        return W13 ? l_tok[en.first + tk] : l_pair[en.first + tk];
     };
     auto load_a = [&](h8_t (&dst)[TL_GPW][4], const TileStep &s) {   // this wave's A operands of step s
-        const uint16_t *row = token_row(s);
+        const uint16_t *row = A.act + (size_t)token_index(s) * A.K;
 #pragma unroll
         for (int j = 0; j < TL_GPW; ++j) {
             const int g = s.seg * TL_SG + min(wv + TL_WAVES * j, seg_groups(s) - 1);
@@ -207,7 +250,26 @@ __global__ __launch_bounds__(TL_THREADS, TL_BLOCKS_PER_CU) void k_mfma_stream_q4
             um.m = meta[r * TL_META_PITCH + gl];
         }
     };
-    auto unit_multiply = [&](const h8_t (&a)[4], const uint4 &q, const UnitMeta &um, int rt) {
+    uint32_t rho[TL_RT][TL_GPW] = {};                               // R1: what the rounding of e left, per tile and group of the step
+    auto unit_multiply = [&](const h8_t (&a)[4], const uint4 &q, const UnitMeta &um, int rt, int j) {
+        if constexpr (R1) {
+            const h2_t m2 = as_h2(um.m);                                 // (scale, zero)
+            const h2_t s2 = __builtin_shufflevector(m2, m2, 0, 0), z2 = __builtin_shufflevector(m2, m2, 1, 1);
+            const h2_t bias = {(_Float16)1024.f, (_Float16)64.f};
+            const h2_t sb = s2 * bias;                                   // bias * s, exact
+            const h2_t e = __builtin_elementwise_fma(z2, s2, sb);        // fp16((bias + z) s), both biases
+            const h2_t t = e - sb;                                       // exact (the two are within 2 % of each other)
+            const h2_t d = __builtin_elementwise_fma(-z2, s2, t);        // e - (bias + z) s, the fma exact before its rounding
+            rho[rt][j] = __builtin_bit_cast(uint32_t, d);
+            const h2_t ne = -e;
+            const h2_t ne1024 = __builtin_shufflevector(ne, ne, 0, 0), ne64 = __builtin_shufflevector(ne, ne, 1, 1);
+            h8_t b[4];
+            b[0] = codes_to_w8_r1(q.x, s2, ne1024, ne64); b[1] = codes_to_w8_r1(q.y, s2, ne1024, ne64);
+            b[2] = codes_to_w8_r1(q.z, s2, ne1024, ne64); b[3] = codes_to_w8_r1(q.w, s2, ne1024, ne64);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) acc[rt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[k], b[k], acc[rt], 0, 0, 0);
+            return;
+        }
         _Float16 s16, zi, c16;
         if constexpr (META8) {              // scale = (code - m1) m0, zero = (code - m3) m2, in fp32; then as below
             const float sc = ((float)(um.m & 0xffu) - hi_half(um.quad0)) * lo_half(um.quad0);
@@ -230,14 +292,24 @@ __global__ __launch_bounds__(TL_THREADS, TL_BLOCKS_PER_CU) void k_mfma_stream_q4
     };
     uint4 q_next = make_uint4(0, 0, 0, 0);
     UnitMeta m_next = {0u, 0u, 0u};
-    auto group_multiply = [&](const h8_t (&a)[4], int b, int gl, int sg) {   // q_next/m_next hold tile 0 of group gl
+    auto group_multiply = [&](const h8_t (&a)[4], int b, int gl, int sg, int j) {   // q_next/m_next hold tile 0 of group gl
 #pragma unroll
         for (int rt = 0; rt < TL_RT; ++rt) {
             const uint4 q = q_next;
             const UnitMeta m = m_next;
             if (rt + 1 < TL_RT) unit_load(b, gl, rt + 1, q_next, m_next);
             else if (gl + TL_WAVES < sg) unit_load(b, gl + TL_WAVES, 0, q_next, m_next);
-            unit_multiply(a, q, m, rt);
+            unit_multiply(a, q, m, rt, j);
+        }
+    };
+    // R1: add sum over (group, bias, half) of d * (partial activation sum): slots 0..3 of each half of the K dimension
+    auto rank1_correct = [&](const h8_t (&a)[TL_GPW][4]) {
+        static_assert(TL_GPW == 2, "the correction packs two groups per wave and step");
+        const u32x4_t av = {half_sums(a[0]), half_sums(a[1]), 0u, 0u};
+#pragma unroll
+        for (int rt = 0; rt < TL_RT; ++rt) {
+            const u32x4_t bv = {rho[rt][0], rho[rt][1], 0u, 0u};
+            acc[rt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(h8_t, av), __builtin_bit_cast(h8_t, bv), acc[rt], 0, 0, 0);
         }
     };
 
@@ -290,14 +362,22 @@ __global__ __launch_bounds__(TL_THREADS, TL_BLOCKS_PER_CU) void k_mfma_stream_q4
     // ---------------- one step; true when it was the block's last ----------------
     auto step = [&](const h8_t (&a_use)[TL_GPW][4], h8_t (&a_load)[TL_GPW][4]) -> bool {
         const bool item_ends = !nxt.valid || nxt.it != cur.it;
-        load_a(a_load, nxt.valid ? nxt : cur);                       // past the last step: re-read, never used
+        load_a(a_load, nxt.valid ? nxt : cur);              // past the last step: re-read, never used
         if (nxt.valid) fetch(nxt);
         const int sg = seg_groups(cur);
         if (wv < sg) {
             unit_load(buf, wv, 0, q_next, m_next);
-            group_multiply(a_use[0], buf, wv, sg);
+            group_multiply(a_use[0], buf, wv, sg, 0);
         }
-        if (wv + TL_WAVES < sg) group_multiply(a_use[1], buf, wv + TL_WAVES, sg);
+        if (wv + TL_WAVES < sg) {
+            group_multiply(a_use[1], buf, wv + TL_WAVES, sg, 1);
+        } else if constexpr (R1) {
+#pragma unroll
+            for (int rt = 0; rt < TL_RT; ++rt) rho[rt][1] = 0u;      // no second group in a short step
+        }
+        if constexpr (R1) {
+            if (wv < sg) rank1_correct(a_use);
+        }
         if (item_ends) finish_item(cur, buf);
         // unconditional (after the last step it stores stale registers nobody reads): the wait for the loads above
         // then sits on every path, and the next step starts with nothing in flight as far as the compiler can tell

@@ -125,7 +125,8 @@ struct moe_ctx {
     int32_t w13_blocks = 256, w2_rows = 32;
     int32_t w2_token_rows = 0;          // rows per block of the single-token w2 kernel; 0: hidden / compute units
     uint32_t gate_seq = 0;              // sequence number of the last gate launch
-    int32_t mfma_form = 2;              // matrix-core kernels: 2 persistent streaming form with fp16 weights, 1 row-staging form with fp32 group scaling
+    int32_t mfma_form = 3;              // matrix-core kernels: 3 streaming form, one fma per pair of weights plus a rank-1 correction;
+                                        // 2 streaming form with an exact subtraction first; 1 row-staging form with fp32 group scaling
     int32_t mfma_min_batch = 16;        // batches at least this large use the matrix-core kernels (4-bit g64)
     int32_t staged_min_batch = 0;       // matrix-core batches larger than this: resident experts first, arriving ones one by one
     uint64_t spec_head_bytes = 0;       // 0: a speculative load moves the whole expert at once (as the paper describes);
@@ -213,6 +214,7 @@ static ScratchPlan plan_scratch(const moe_ctx_config_t *c)
     p.x1 = off;   off += align_u64((uint64_t)c->max_batch * c->max_hidden * 2, 256);
     p.barrier = off; off += 4096;     // one flag per block of the persistent kernel (at most 1024 compute units)
     p.route = off; off += 256;        // device-side routing: MOE_MAX_TOPK selections and as many combine weights
+    // matrix-core kernels, rank-1 form: partial activation sums per (row, half group), an fp16 pair each
     p.total = off;
     return p;
 }
@@ -304,6 +306,7 @@ try {
     c->route_w = reinterpret_cast<float *>(base + p.route + 128);
     c->device_routing = env_int("MOE_DEVICE_ROUTING", 1) != 0;
     c->mfma_min_batch = env_int("MOE_MFMA_MIN_BATCH", 16);
+    c->mfma_form = std::min(3, std::max(1, env_int("MOE_MFMA_FORM", c->mfma_form)));
     c->staged_min_batch = env_int("MOE_STAGED_MIN_BATCH", c->staged_min_batch);
     c->fused = env_int("MOE_FUSED", 0) != 0;
     hipError_t e = hipMemset(c->barrier, 0, 4096);
@@ -1182,6 +1185,8 @@ static int32_t launch_mfma_stream(moe_layer *l, const std::vector<PassExpert> &e
         HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_stream_q4<false, false>), hipFuncAttributeMaxDynamicSharedMemorySize, TL_LDS_BYTES));
         HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_stream_q4<true, true>), hipFuncAttributeMaxDynamicSharedMemorySize, TL_LDS_BYTES));
         HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_stream_q4<false, true>), hipFuncAttributeMaxDynamicSharedMemorySize, TL_LDS_BYTES));
+        HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_stream_q4<true, false, true>), hipFuncAttributeMaxDynamicSharedMemorySize, TL_LDS_BYTES));
+        HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_stream_q4<false, false, true>), hipFuncAttributeMaxDynamicSharedMemorySize, TL_LDS_BYTES));
         lds_attr_set = true;
     }
     const int n_cu = c->n_cu > 0 ? c->n_cu : 256;
@@ -1232,11 +1237,13 @@ static int32_t launch_mfma_stream(moe_layer *l, const std::vector<PassExpert> &e
         A.a = a_win; A.yacc = c->yacc + (size_t)w0 * b.hidden;
         A.act = c->h_buf + (size_t)w0 * b.hidden;
         const bool meta8 = b.scale_group > 0;
+        const bool r1 = c->mfma_form == 3 && !meta8;
         auto run_shift = [&](const MatLayout &m) { return (m.run_len == 0 || m.run_len >= m.cols / (uint32_t)b.group) ? 31 : __builtin_ctz(m.run_len); };
         A.K = b.hidden; A.N = b.ffn; A.stride = b.m13.row_stride; A.meta_off = b.m13.meta_off; A.mat_off = b.off_w13;
         A.meta2_off = b.m13.meta2_off; A.run_shift = run_shift(b.m13);
         const dim3 g13 = shape(2 * b.ffn, b.hidden, false);
         int32_t rc = meta8 ? launch_timed(c, PROF_W13, bytes13, k_mfma_stream_q4<true, true>, g13, dim3(TL_THREADS), TL_LDS_BYTES, A)
+                     : r1  ? launch_timed(c, PROF_W13, bytes13, k_mfma_stream_q4<true, false, true>, g13, dim3(TL_THREADS), TL_LDS_BYTES, A)
                            : launch_timed(c, PROF_W13, bytes13, k_mfma_stream_q4<true, false>, g13, dim3(TL_THREADS), TL_LDS_BYTES, A);
         if (rc) return rc;
         A.act = a_win;
@@ -1244,6 +1251,7 @@ static int32_t launch_mfma_stream(moe_layer *l, const std::vector<PassExpert> &e
         A.meta2_off = b.m2.meta2_off; A.run_shift = run_shift(b.m2);
         const dim3 g2 = shape(b.hidden, b.ffn, true);
         rc = meta8 ? launch_timed(c, PROF_W2, bytes2, k_mfma_stream_q4<false, true>, g2, dim3(TL_THREADS), TL_LDS_BYTES, A)
+             : r1  ? launch_timed(c, PROF_W2, bytes2, k_mfma_stream_q4<false, false, true>, g2, dim3(TL_THREADS), TL_LDS_BYTES, A)
                    : launch_timed(c, PROF_W2, bytes2, k_mfma_stream_q4<false, false>, g2, dim3(TL_THREADS), TL_LDS_BYTES, A);
         if (rc) return rc;
     }
@@ -1256,7 +1264,7 @@ static int32_t launch_mfma(moe_layer *l, const std::vector<PassExpert> &experts,
     const BlobLayout &b = l->lay;
     const int K = l->cfg.top_k;
     // the row-staging form takes up to 64 tokens per expert, indexes pairs with one byte and reads fp16 pairs only
-    if (c->mfma_form == 2 || batch > 64 || batch * K > MF_MAX_PAIRS || b.scale_group > 0) return launch_mfma_stream(l, experts, w, batch);
+    if (c->mfma_form != 1 || batch > 64 || batch * K > MF_MAX_PAIRS || b.scale_group > 0) return launch_mfma_stream(l, experts, w, batch);
     MfmaArgs A{};
     int n = 0, first = 0, max_tok = 0;
     for (const PassExpert &pe : experts) {
@@ -1798,7 +1806,7 @@ try {
     else if (n == "token_path") c->token_path = value != 0;
     else if (n == "spec_head_mb" && value >= 0) c->spec_head_bytes = (uint64_t)value << 20;
     else if (n == "mfma_min_batch" && value >= 1) c->mfma_min_batch = value;
-    else if (n == "mfma_form" && (value == 1 || value == 2)) c->mfma_form = value;
+    else if (n == "mfma_form" && value >= 1 && value <= 3) c->mfma_form = value;
     else if (n == "device_routing") c->device_routing = value != 0;
     else if (n == "staged_min_batch" && value >= 0) c->staged_min_batch = value;
     else if (n == "profile_copy_stride" && value >= 1) c->prof.copy_stride = value;

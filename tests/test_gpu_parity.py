@@ -339,12 +339,12 @@ def test_launch_shape_knobs_do_not_change_results(Bn, token_path):
         assert st == outs[0][1]
 
 
-@pytest.mark.parametrize("form", [2, 1])
+@pytest.mark.parametrize("form", [3, 2, 1])
 @pytest.mark.parametrize("Bn,k", [(16, 4), (64, 4), (33, 8), (64, 2)])
 def test_small_stack_matrix_core_path(Bn, k, form):
     """Batches of 16 and more run 4-bit g64 experts as grouped dequantize+GEMM on the matrix cores
     (more than 32 tokens on one expert needs two token tiles; k=2 with 8 needed experts needs several passes).
-    Both kernel forms (2: fp16 weights, the default; 1: fp32 group scaling) meet the same bound against the oracle."""
+    All kernel forms (3: fp16 weights from one fma plus a rank-1 correction, the default; 2: fp16 weights with the exact subtraction; 1: fp32 group scaling) meet the same bound against the oracle."""
     L, H, F = 3, 256, 512
     say(f"matrix-core stack B={Bn} k={k} form={form}")
     model = Model(L, H, F, 8, 2, None, k, 2, 1e-5, max_batch=Bn, seed=41)
@@ -356,7 +356,7 @@ def test_small_stack_matrix_core_path(Bn, k, form):
     model.close()
 
 
-@pytest.mark.parametrize("form,rel", [(1, 1e-4), (2, 2e-3)])
+@pytest.mark.parametrize("form,rel", [(1, 1e-4), (2, 2e-3), (3, 2e-3)])
 def test_matrix_core_path_agrees_with_gemv_path(form, rel):
     """The same batched steps through the GEMV kernels (threshold raised) and the matrix cores: identical
     traces; outputs equal to within the summation-order noise of fp32 for the form that scales groups in fp32,
@@ -734,7 +734,7 @@ def test_recall_study_tool_against_closed_forms():
             assert list(idx) == routing[t][l]
 
 
-@pytest.mark.parametrize("Bn,k,T,form", [(200, 4, 2, 2), (130, 2, 2, 1), (1000, 8, 1, 2), (1024, 2, 1, 2)])
+@pytest.mark.parametrize("Bn,k,T,form", [(200, 4, 2, 3), (130, 2, 2, 1), (1000, 8, 1, 2), (1024, 2, 1, 3), (300, 4, 1, 2)])
 def test_prompt_sized_batches(Bn, k, T, form):
     """Prompt encoding (Sec. 3: prompt tokens go through a layer in parallel, every expert is loaded once for all of
     them) is a step with a large batch: up to MOE_MAX_BATCH = 1024 tokens, through the matrix cores in windows of
