@@ -70,9 +70,10 @@ def softmax(z: np.ndarray) -> np.ndarray:
 
 
 def top_k(z: Sequence[float], k: int) -> List[int]:
-    """Indices of the k largest entries, largest first; equal values: lower index first."""
+    """Indices of the k largest entries, largest first; equal values: lower index first.
+    Asked for more than there are, it returns all of them in that order."""
     chosen: List[int] = []
-    for _ in range(k):
+    for _ in range(min(k, len(z))):
         best = -1
         for e in range(len(z)):
             if e in chosen:

@@ -765,3 +765,55 @@ def test_prompt_sized_batches_on_the_gemv_kernels(formats, scale_group, Bn):
     _, sim, errs = run_teacher_forced(model, xs, O.expert_ffn)
     say(f"  max abs {max(e[0] for e in errs):.2e} max rel-rms {max(e[1] for e in errs):.2e}")
     model.close()
+
+
+def draw_configuration(seed):
+    """A seeded draw over shapes, formats, cache sizes, modes and launch options that the interface accepts."""
+    r = np.random.RandomState(7000 + seed)
+    pick = lambda xs: xs[int(r.randint(len(xs)))]
+    c = {}
+    c["E"] = pick([3, 4, 8, 8, 16])
+    c["K"] = min(pick([1, 2, 2, 2, 3, 4]), c["E"])
+    c["k"] = int(r.randint(c["K"], c["E"] + 1))
+    c["m"] = pick([0, 1, 2, 2, 3, 4])
+    c["L"] = pick([2, 3])
+    c["H"] = pick([256, 512])
+    c["F"] = pick([320, 512, 1024])
+    c["Bn"] = pick([1, 1, 1, 2, 3, 5, 8, 16, 17, 40, 70])
+    c["T"] = 6 if c["Bn"] <= 8 else 3
+    c["formats"] = [pick([(4, 64), (4, 64), (3, 64), (2, 16)]) for _ in range(c["L"])]
+    c["scale_group"] = pick([0, 0, 4, 8])
+    c["swap"] = bool(r.rand() < 0.3)
+    c["warm"] = c["swap"] or bool(r.rand() < 0.3)
+    c["eps"] = pick([0.0, 1e-5])
+    c["options"] = {
+        "token_path": pick([1, 1, 0]), "fused": pick([0, 0, 0, 1]), "mfma_form": pick([1, 2, 3]),
+        "mfma_min_batch": pick([16, 16, 2, 1000]), "staged_min_batch": pick([0, 0, 1000]),
+        "spec_head_mb": pick([0, 0, 1]), "w13_blocks": pick([256, 64, 24]), "w2_rows": pick([32, 16, 8]),
+        "sync_wait": pick([0, 0, 1]),
+    }
+    return c
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_random_configurations(seed):
+    """Forty seeded combinations of shapes, per-layer formats, metadata levels, cache sizes, swap mode, warm start
+    and launch options, none of them chosen by hand: every decision bit-exact and every output row in tolerance
+    against the oracle, as in the hand-picked cases above."""
+    c = draw_configuration(seed)
+    say(f"random configuration {seed}: {c}")
+    model = Model(c["L"], c["H"], c["F"], c["E"], c["K"], c["formats"], c["k"], c["m"], c["eps"], max_batch=c["Bn"],
+                  seed=7000 + seed, init_policy=1 if c["warm"] else 0, flags=B.MOE_LAYER_SWAP if c["swap"] else 0,
+                  scale_group=c["scale_group"])
+    for name, value in c["options"].items():
+        B.moe_ctx_set_option(model.stack.ctx, name, value)
+    xs = W.hidden_ar1(7000 + seed, c["T"], c["Bn"], c["H"])
+    sim = O.ExpertCacheSim(c["L"], c["E"], c["k"], 4, warm=c["warm"])
+    place = [O.SwapPlacement(c["E"], c["k"]) for _ in range(c["L"])] if c["swap"] else None
+    _, sim, errs = run_teacher_forced(model, xs, O.expert_ffn, sim=sim, placement=place)
+    tot = model.stack.total_stats()
+    assert tot["needed"] == sum(s.needed for s in sim.stats)
+    assert tot["misses"] == sum(s.misses for s in sim.stats)
+    assert tot["prefetch_hits"] == sum(s.prefetch_hits for s in sim.stats)
+    say(f"  max abs {max(e[0] for e in errs):.2e} max rel-rms {max(e[1] for e in errs):.2e} misses {tot['misses']}")
+    model.close()

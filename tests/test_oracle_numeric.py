@@ -40,6 +40,8 @@ def test_top_k_ties_and_adversarial():
     assert O.top_k([0.0, 3.0, 3.0, 1.0], 2) == [1, 2]           # tie for first
     assert O.top_k([5.0, 1.0, 2.0, 2.0], 2) == [0, 2]           # tie for second: lower index
     assert O.top_k([-1.0, -2.0, -0.0, 0.0], 2) == [2, 3]        # -0.0 == 0.0 is a tie
+    assert O.top_k([0.5, 2.0, 1.0], 4) == [1, 2, 0]             # more asked for than there are: all, in order
+    assert O.prefetch_guess(np.array([0.2, 0.7, 0.1]), 4) == [1, 0, 2]
     for vals in itertools.product([0.0, 1.0, 2.0], repeat=5):   # exhaustive small alphabet
         for k in (1, 2, 3):
             assert O.top_k(list(vals), k) == full_sort_top(list(vals), k)
