@@ -792,28 +792,71 @@ def draw_configuration(seed):
         "spec_head_mb": pick([0, 0, 1]), "w13_blocks": pick([256, 64, 24]), "w2_rows": pick([32, 16, 8]),
         "sync_wait": pick([0, 0, 1]),
     }
+    if r.rand() < 0.2:      # decode with every expert resident: the steps that do not wait for their gate
+        c.update(Bn=1, T=6, k=c["E"], K=min(c["K"], 2))
+        c["options"].update(token_path=1, fused=0)
     return c
+
+
+def build_configuration(c, seed):
+    model = Model(c["L"], c["H"], c["F"], c["E"], c["K"], c["formats"], c["k"], c["m"], c["eps"], max_batch=c["Bn"],
+                  seed=7000 + seed, init_policy=1 if c["warm"] else 0, flags=B.MOE_LAYER_SWAP if c["swap"] else 0,
+                  scale_group=c["scale_group"])
+    for name, value in c["options"].items():
+        B.moe_ctx_set_option(model.stack.ctx, name, value)
+    return model
 
 
 @pytest.mark.parametrize("seed", range(40))
 def test_random_configurations(seed):
     """Forty seeded combinations of shapes, per-layer formats, metadata levels, cache sizes, swap mode, warm start
     and launch options, none of them chosen by hand: every decision bit-exact and every output row in tolerance
-    against the oracle, as in the hand-picked cases above."""
+    against the oracle, as in the hand-picked cases above.  Then the same tokens through the whole-stack entry point
+    without traces (after a reset, or on a stack built anew; statistics read at seeded moments, which makes
+    device-routed steps catch up their bookkeeping there): the same counters, and bit-identical outputs wherever the
+    order of the fp32 additions is fixed."""
     c = draw_configuration(seed)
     say(f"random configuration {seed}: {c}")
-    model = Model(c["L"], c["H"], c["F"], c["E"], c["K"], c["formats"], c["k"], c["m"], c["eps"], max_batch=c["Bn"],
-                  seed=7000 + seed, init_policy=1 if c["warm"] else 0, flags=B.MOE_LAYER_SWAP if c["swap"] else 0,
-                  scale_group=c["scale_group"])
-    for name, value in c["options"].items():
-        B.moe_ctx_set_option(model.stack.ctx, name, value)
+    model = build_configuration(c, seed)
     xs = W.hidden_ar1(7000 + seed, c["T"], c["Bn"], c["H"])
     sim = O.ExpertCacheSim(c["L"], c["E"], c["k"], 4, warm=c["warm"])
     place = [O.SwapPlacement(c["E"], c["k"]) for _ in range(c["L"])] if c["swap"] else None
-    _, sim, errs = run_teacher_forced(model, xs, O.expert_ffn, sim=sim, placement=place)
+    outs, sim, errs = run_teacher_forced(model, xs, O.expert_ffn, sim=sim, placement=place)
     tot = model.stack.total_stats()
     assert tot["needed"] == sum(s.needed for s in sim.stats)
     assert tot["misses"] == sum(s.misses for s in sim.stats)
     assert tot["prefetch_hits"] == sum(s.prefetch_hits for s in sim.stats)
     say(f"  max abs {max(e[0] for e in errs):.2e} max rel-rms {max(e[1] for e in errs):.2e} misses {tot['misses']}")
+    r = np.random.RandomState(9000 + seed)
+    if c["swap"] or r.rand() < 0.5:          # a layer in swap mode cannot be reset
+        model.close()
+        model = build_configuration(c, seed)
+    else:
+        model.stack.reset()
+    dev = model.stack.device
+    x_in = torch.empty(c["Bn"], c["H"], dtype=torch.float16, device=dev)
+    x_out = torch.empty(c["Bn"], c["H"], dtype=torch.float16, device=dev)
+    # an element of y with more than two fp32 addends (top-k above 2; K split over blocks on the matrix cores) takes
+    # them in the order of arrival: such outputs are reproducible to the last bit of fp32 only
+    matrix_cores = c["Bn"] >= c["options"]["mfma_min_batch"] and (4, 64) in c["formats"]
+    order_free = not matrix_cores and c["K"] <= 2
+    for t in range(c["T"]):
+        x_in.copy_(xs[t])
+        torch.cuda.synchronize()
+        model.stack.step(x_in, x_out, None)
+        if r.rand() < 0.4:
+            model.stack.total_stats()
+        model.stack.synchronize()
+        got = x_out.cpu().numpy()
+        differ = got.view(np.uint16) != outs[t].view(np.uint16)
+        gap = np.abs(got.astype(np.float64) - outs[t].astype(np.float64))
+        what = f"whole-stack step differs at token {t}: {int(differ.sum())} of {differ.size} elements, largest gap {gap.max():.3e}"
+        if order_free:
+            assert not differ.any(), what
+        else:       # a few elements one fp16 ulp apart, and what that does to the layers after
+            assert differ.mean() <= 2e-3 and (gap <= 2.0 ** -9 * np.maximum(np.abs(outs[t].astype(np.float64)), 1.0)).all(), what
+    again = model.stack.total_stats()
+    for name in ("needed", "hits", "misses", "prefetch_hits", "evictions", "spec_issued", "spec_wasted", "bytes_d2h_writeback"):
+        assert again[name] == tot[name], f"{name}: {again[name]} after the whole-stack pass, {tot[name]} before"
+    say(f"  whole-stack pass: device-routed steps {again['steps_device_routed']}")
     model.close()
