@@ -76,6 +76,43 @@ def test_bookkeeping_equals_oracle_simulator(L, E, k, m, b, B_):
     st.close()
 
 
+def test_bookkeeping_random_configurations():
+    """Sixty seeded draws over everything the bookkeeping depends on (experts, top-k, slots, guesses, staging buffers
+    including none, batch, per-layer shapes alike) against the oracle simulator, decision by decision."""
+    for seed in range(60):
+        rng = np.random.default_rng(4000 + seed)
+        E = int(rng.integers(1, 17))
+        K = int(rng.integers(1, min(4, E) + 1))
+        k = int(rng.integers(K, E + 1))
+        m = int(rng.integers(0, 5))
+        b = int(rng.integers(0, 7))
+        L = int(rng.integers(1, 5))
+        B_ = int(rng.choice([1, 1, 2, 3, 7, 16, 40]))
+        cfgs = [layer_config(64, 64, E, K, 4, 64, k, m, 0.0, 0, 0) for _ in range(L)]
+        st = Stack(cfgs, [torch.zeros(E, 64) for _ in range(L)], n_staging=b, max_batch=B_, host_only=True)
+        sim = O.ExpertCacheSim(L, E, k, b)
+        tr = B.StepTrace()
+        what = f"seed {seed}: E={E} K={K} k={k} m={m} b={b} L={L} B={B_}"
+        for _ in range(25):
+            for l in range(L):
+                sel = [[int(e) for e in rng.choice(E, size=K, replace=False)] for _ in range(B_)]
+                score = rng.dirichlet(np.ones(E)) * B_
+                if E > 1 and rng.random() < 0.2:
+                    score[rng.integers(E)] = score[rng.integers(E)]
+                nxt = st.layers[l + 1] if l + 1 < L else None
+                B.moe_layer_resolve(st.layers[l], nxt, [e for t in sel for e in t], B_, list(score) if nxt else None, tr)
+                acc, dec = sim.step(l, sel, O.prefetch_guess(score, m) if nxt else None)
+                assert tr.accesses() == [(a.expert, a.status, a.slot, a.victim) for a in acc], what
+                assert tr.guesses() == [(e, i) for e, i in dec], what
+        for l in range(L):
+            se, ss, staged = B.moe_layer_cache_state(st.layers[l], k)
+            assert se == sim.slot_expert[l] and ss == sim.slot_stamp[l] and staged == sim.staged[l], what
+            s_, o = B.moe_layer_stats(st.layers[l]).as_dict(), sim.stats[l]
+            for name in ("steps", "needed", "hits", "prefetch_hits", "misses", "evictions", "spec_issued", "spec_wasted"):
+                assert s_[name] == getattr(o, name), (what, name)
+        st.close()
+
+
 def test_warm_start_reset_and_ablation_flags():
     st = make_stack(2, 8, 3, 2, 4, init_policy=1)
     lay = st.layers[0]
