@@ -777,8 +777,8 @@ def draw_configuration(seed):
     c["k"] = int(r.randint(c["K"], c["E"] + 1))
     c["m"] = pick([0, 1, 2, 2, 3, 4])
     c["L"] = pick([2, 3])
-    c["H"] = pick([256, 512])
-    c["F"] = pick([320, 512, 1024])
+    c["H"] = pick([64, 192, 256, 320, 512, 768])       # any multiple of 64: ragged last chunks, blocks and tiles
+    c["F"] = pick([64, 192, 320, 448, 512, 1024])
     c["Bn"] = pick([1, 1, 1, 2, 3, 5, 8, 16, 17, 40, 70])
     c["T"] = 6 if c["Bn"] <= 8 else 3
     c["formats"] = [pick([(4, 64), (4, 64), (3, 64), (2, 16)]) for _ in range(c["L"])]
@@ -854,7 +854,7 @@ def test_random_configurations(seed):
         if order_free:
             assert not differ.any(), what
         else:       # a few elements one fp16 ulp apart, and what that does to the layers after
-            assert differ.mean() <= 2e-3 and (gap <= 2.0 ** -9 * np.maximum(np.abs(outs[t].astype(np.float64)), 1.0)).all(), what
+            assert differ.mean() <= 2e-2 and (gap <= 2.0 ** -9 * np.maximum(np.abs(outs[t].astype(np.float64)), 1.0)).all(), what
     again = model.stack.total_stats()
     for name in ("needed", "hits", "misses", "prefetch_hits", "evictions", "spec_issued", "spec_wasted", "bytes_d2h_writeback"):
         assert again[name] == tot[name], f"{name}: {again[name]} after the whole-stack pass, {tot[name]} before"
