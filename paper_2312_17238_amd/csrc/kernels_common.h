@@ -72,33 +72,88 @@ __device__ __forceinline__ double wave_sum_f64(double v)
     return (readlane_d(v, 0) + readlane_d(v, 16)) + (readlane_d(v, 32) + readlane_d(v, 48));
 }
 
-// Round-to-nearest-even conversion of a double straight to binary16 (no intermediate fp32 rounding,
-// which could double-round).  NaN maps to a quiet NaN.
+__device__ __forceinline__ double bpermute_d(double v, int src_lane)
+{
+    const long long b = __double_as_longlong(v);
+    const int lo = __builtin_amdgcn_ds_bpermute(src_lane * 4, (int)(b & 0xffffffffll));
+    const int hi = __builtin_amdgcn_ds_bpermute(src_lane * 4, (int)(b >> 32));
+    return __longlong_as_double(((long long)hi << 32) | (unsigned int)lo);
+}
+
+// fp64 sums of N values per lane over the 64 lanes, all at once.  A butterfly over one value costs the same six
+// exchanges whatever the lane holds; here, in each of the first log2(N) stages a lane GIVES half of what it still
+// holds to its partner and adds the partner's other half to the half it keeps, so the values in flight halve from
+// stage to stage (N-1 exchanges in all instead of 6 N); the remaining stages are plain butterflies on v[0].
+// Which half a lane keeps is decided by the lane bit that the stage's partner differs in: stage 0 pairs lane i with
+// 7-i of its group of eight (bit 2), then i^1 (bit 0), i^2 (bit 1), i+8 within the row of 16 (bit 3), i^16 (bit 4),
+// i^32 (bit 5).  Afterwards v[0] of every lane is the total of value wave_sum_index<N>(lane); lanes 0..N-1 cover
+// all N.  Fixed order, so deterministic.
+template <int N>
+__device__ __forceinline__ int wave_sum_index(int lane)
+{
+    constexpr int BIT[6] = {2, 0, 1, 3, 4, 5};
+    int idx = 0, n = N;
+#pragma unroll
+    for (int s = 0; s < 6; ++s)
+        if (n > 1) { n >>= 1; idx += ((lane >> BIT[s]) & 1) * n; }
+    return idx;
+}
+
+template <int STAGE>
+__device__ __forceinline__ double wave_sum_exchange(double give, int lane)
+{
+    if constexpr (STAGE == 0) return dpp_d<0x141>(give);                  // row_half_mirror
+    else if constexpr (STAGE == 1) return dpp_d<0xB1>(give);              // quad_perm [1,0,3,2]
+    else if constexpr (STAGE == 2) return dpp_d<0x4E>(give);              // quad_perm [2,3,0,1]
+    else if constexpr (STAGE == 3) return dpp_d<0x128>(give);             // row_ror:8
+    else if constexpr (STAGE == 4) return bpermute_d(give, lane ^ 16);
+    else return bpermute_d(give, lane ^ 32);
+}
+
+template <int STAGE, int HELD, int M>
+__device__ __forceinline__ void wave_sum_stage(double (&v)[M], int lane)
+{
+    if constexpr (STAGE < 6) {
+        constexpr int BIT[6] = {2, 0, 1, 3, 4, 5};
+        if constexpr (HELD > 1) {
+            constexpr int H = HELD / 2;
+            const bool up = (lane >> BIT[STAGE]) & 1;
+#pragma unroll
+            for (int j = 0; j < H; ++j) {
+                const double keep = up ? v[j + H] : v[j], give = up ? v[j] : v[j + H];
+                v[j] = keep + wave_sum_exchange<STAGE>(give, lane);
+            }
+            wave_sum_stage<STAGE + 1, H, M>(v, lane);
+        } else {
+            v[0] += wave_sum_exchange<STAGE>(v[0], lane);
+            wave_sum_stage<STAGE + 1, 1, M>(v, lane);
+        }
+    }
+}
+
+template <int N, int M>
+__device__ __forceinline__ void wave_sum_many_f64(double (&v)[M], int lane)
+{
+    static_assert((N == 8 || N == 16 || N == 32) && N <= M, "8, 16 or 32 of the array's values");
+    wave_sum_stage<0, N, M>(v, lane);
+}
+
+// Round-to-nearest-even conversion of a double to binary16 as if done in one step.  Two hardware conversions
+// (fp64 -> fp32 -> fp16) would round twice; rounding the first one TO ODD instead (truncate toward zero, then set the
+// last bit if anything was lost) keeps in fp32's 24 bits everything the second, nearest-even rounding to 11 bits or
+// fewer needs.  The truncation is recovered from the nearest-even conversion: where that one moved away from zero,
+// the neighbour toward zero is the fp32 pattern minus one.  NaN maps to a quiet NaN.
 __device__ __forceinline__ uint16_t f64_to_f16_rne(double d)
 {
-    const uint64_t b = (uint64_t)__double_as_longlong(d);
-    const uint16_t sign = (uint16_t)((b >> 48) & 0x8000u);
-    const int ex = (int)((b >> 52) & 0x7ff);
-    const uint64_t man = b & 0xFFFFFFFFFFFFFull;
-    if (ex == 0x7ff) return sign | (man ? 0x7e00u : 0x7c00u);
-    if (ex == 0) return sign;                        // zero or a double subnormal: far below half range
-    const int e = ex - 1023;
-    if (e > 15) return sign | 0x7c00u;
-    const uint64_t m = man | (1ull << 52);
-    int shift = 42;
-    uint32_t base = (uint32_t)(e + 15) << 10;
-    if (e < -14) {                                   // half subnormal
-        shift = 42 + (-14 - e);
-        base = 0;
-        if (shift > 63) return sign;
+    const float t = (float)d;
+    const double r = (double)t;
+    uint32_t tb = __builtin_bit_cast(uint32_t, t);
+    if (r != d) {
+        if (__builtin_fabs(r) > __builtin_fabs(d)) tb -= 1u;
+        tb |= 1u;
     }
-    uint64_t q = m >> shift;
-    const uint64_t rem = m & ((1ull << shift) - 1), halfway = 1ull << (shift - 1);
-    if (rem > halfway || (rem == halfway && (q & 1))) ++q;
-    // normal: q is in [1024, 2048]; adding q-1024 to the exponent field carries correctly on 2048.
-    // subnormal: q is in [0, 1024]; 1024 carries into the smallest normal.
-    const uint32_t r = (e < -14) ? (uint32_t)q : base + (uint32_t)(q - 1024);
-    return sign | (uint16_t)(r > 0x7c00u ? 0x7c00u : r);
+    const uint16_t h = __builtin_bit_cast(uint16_t, (_Float16)__builtin_bit_cast(float, tb));
+    return d != d ? (uint16_t)(((uint64_t)__double_as_longlong(d) >> 48) & 0x8000u) | 0x7e00u : h;
 }
 
 // Weight loads.  Every weight byte is used exactly once per step, so the loads carry the streaming

@@ -127,13 +127,16 @@ __global__ __launch_bounds__(GATE_THREADS) void k_gate(GateArgs a)
                 }
         }
     }
-#pragma unroll
-    for (int e = 0; e < NACC; ++e) {
-        const bool live = (e < 16) ? (e < n1) : (e - 16 < n2);
-        if (live) {
-            const double v = wave_sum_f64(acc[e]);
-            if (lane == 0) red[wv][e] = v;
-        }
+    // all logits' wave sums at once; accumulators of experts that do not exist hold zeros
+    if constexpr (SPEC) {
+        wave_sum_many_f64<32>(acc, lane);
+        if (lane < 32) red[wv][wave_sum_index<32>(lane)] = acc[0];
+    } else if (n1 <= 8) {
+        wave_sum_many_f64<8>(acc, lane);
+        if (lane < 8) red[wv][wave_sum_index<8>(lane)] = acc[0];
+    } else {
+        wave_sum_many_f64<16>(acc, lane);
+        if (lane < 16) red[wv][wave_sum_index<16>(lane)] = acc[0];
     }
     __syncthreads();
     if (tid < 32) {
