@@ -310,8 +310,8 @@ int32_t moe_ctx_profile_timeline(moe_ctx_t *ctx, int32_t kind, double *start_ms,
  *                its gate kernel: no cache decision depends on the routing then, so the FFN kernels read the selection
  *                and the combine weights the gate kernel left in device memory, and moe_layer_step returns at once.
  *                Outputs are bit-identical to a waiting step's.  The recency stamps and counters such steps owe are
- *                caught up from a host-visible log of the selections (which waits for the compute stream) before any
- *                call reads or changes them: moe_layer_stats, moe_layer_cache_state, moe_layer_reset, a waiting step,
+ *                caught up from a log of the selections in device memory (copied back after waiting for the compute
+ *                stream) before any call reads or changes them: moe_layer_stats, moe_layer_cache_state, moe_layer_reset, a waiting step,
  *                moe_layer_resolve, moe_layer_prefetch, moe_layer_destroy, or when 8192 such steps are pending.
  *                0: every step waits for its gate. */
 int32_t moe_ctx_set_option(moe_ctx_t *ctx, const char *name, int32_t value);

@@ -34,11 +34,11 @@ struct GateArgs {
     int32_t H, E, E2, K;
     uint32_t seq;                   // value to publish in out->done[b]
     // Device-side routing (one token, every expert of the layer resident): the selection and the combine weights go
-    // to device memory for the FFN kernels of the same step, the selection also to a host-visible log the host reads
+    // to device memory for the FFN kernels of the same step, the selection also to a log ring the host copies back
     // later for its bookkeeping; nothing is published in `out` and nobody waits for this launch.
     int32_t *route_idx;             // [K] device, or null
     float *route_w;                 // [K] device
-    int32_t *route_log;             // [K] host-mapped
+    int32_t *route_log;             // [K] device: this step's slot of the log ring
 };
 
 constexpr int GATE_THREADS = 1024;

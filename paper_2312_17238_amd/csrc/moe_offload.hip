@@ -107,6 +107,8 @@ struct Profiler {
     uint64_t copy_seq = 0;
 };
 
+constexpr uint32_t ROUTE_LOG_ENTRIES = 8192;      // device-routed steps whose bookkeeping may be pending at once
+
 struct moe_ctx {
     moe_ctx_config_t cfg{};
     Profiler prof;
@@ -139,15 +141,15 @@ struct moe_ctx {
     bool sync_wait = false;
     // Device-side routing: steps of one token through a layer whose experts are all resident need no decision of the
     // host, so they are enqueued without waiting for the gate; the cache bookkeeping (recency stamps, counters) is
-    // caught up from a host-visible log of the selections before anything reads or changes it.
+    // caught up from a log of the selections (a ring in device memory, copied back then) before anything reads or changes it.
     bool device_routing = true;
     int32_t *route_idx = nullptr;       // device: the current step's selection, written by its gate kernel
     float *route_w = nullptr;           // device: ... and combine weights
-    int32_t *route_log = nullptr;       // host-mapped ring of ROUTE_LOG entries of MOE_MAX_TOPK selections
-    int32_t *route_log_dev = nullptr;   // the same memory as the device sees it
+    int32_t *route_log = nullptr;       // pinned host copy of the ring below, refreshed when the bookkeeping catches up
+    int32_t *route_log_dev = nullptr;   // device ring of ROUTE_LOG entries of MOE_MAX_TOPK selections, written by the gate kernel
     struct PendingStep { moe_layer *layer; uint32_t slot; };
     std::vector<PendingStep> pending;   // steps enqueued that way whose bookkeeping is still to be done, oldest first
-    static constexpr uint32_t ROUTE_LOG = 8192;
+    static constexpr uint32_t ROUTE_LOG = ROUTE_LOG_ENTRIES;
 };
 
 struct moe_layer {
@@ -199,7 +201,7 @@ static bool layer_cfg_ok(const moe_layer_config_t *c)
            c->scale_group >= 0 && blob_layout(c->hidden, c->ffn, c->bits, c->group, c->scale_group).ok;
 }
 
-struct ScratchPlan { uint64_t staging, h, a, yacc, x0, x1, barrier, route, total; };
+struct ScratchPlan { uint64_t staging, h, a, yacc, x0, x1, barrier, route, route_log, total; };
 
 static ScratchPlan plan_scratch(const moe_ctx_config_t *c)
 {
@@ -214,7 +216,7 @@ static ScratchPlan plan_scratch(const moe_ctx_config_t *c)
     p.x1 = off;   off += align_u64((uint64_t)c->max_batch * c->max_hidden * 2, 256);
     p.barrier = off; off += 4096;     // one flag per block of the persistent kernel (at most 1024 compute units)
     p.route = off; off += 256;        // device-side routing: MOE_MAX_TOPK selections and as many combine weights
-    // matrix-core kernels, rank-1 form: partial activation sums per (row, half group), an fp16 pair each
+    p.route_log = off; off += align_u64((uint64_t)ROUTE_LOG_ENTRIES * MOE_MAX_TOPK * sizeof(int32_t), 256);
     p.total = off;
     return p;
 }
@@ -304,6 +306,7 @@ try {
     c->barrier = reinterpret_cast<uint32_t *>(base + p.barrier);
     c->route_idx = reinterpret_cast<int32_t *>(base + p.route);
     c->route_w = reinterpret_cast<float *>(base + p.route + 128);
+    c->route_log_dev = reinterpret_cast<int32_t *>(base + p.route_log);
     c->device_routing = env_int("MOE_DEVICE_ROUTING", 1) != 0;
     c->mfma_min_batch = env_int("MOE_MFMA_MIN_BATCH", 16);
     c->mfma_form = std::min(3, std::max(1, env_int("MOE_MFMA_FORM", c->mfma_form)));
@@ -319,8 +322,7 @@ try {
     }
     if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void **>(&c->gate_out), sizeof(GateHostOut), hipHostMallocMapped);
     if (e == hipSuccess) e = hipHostGetDevicePointer(reinterpret_cast<void **>(&c->gate_out_dev), c->gate_out, 0);
-    if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void **>(&c->route_log), (size_t)moe_ctx::ROUTE_LOG * MOE_MAX_TOPK * sizeof(int32_t), hipHostMallocMapped);
-    if (e == hipSuccess) e = hipHostGetDevicePointer(reinterpret_cast<void **>(&c->route_log_dev), c->route_log, 0);
+    if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void **>(&c->route_log), (size_t)moe_ctx::ROUTE_LOG * MOE_MAX_TOPK * sizeof(int32_t), hipHostMallocDefault);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_gate, hipEventDisableTiming);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_compute, hipEventDisableTiming);
     for (int i = 0; i < cfg->n_staging && e == hipSuccess; ++i) {
@@ -1332,6 +1334,13 @@ static int32_t fold_pending(moe_ctx *c)
 {
     if (c->pending.empty()) return MOE_OK;
     HIPCHK(hipStreamSynchronize(c->compute));
+    {   // the pending slots are consecutive in the ring (oldest first), possibly wrapping once
+        const size_t entry = MOE_MAX_TOPK * sizeof(int32_t);
+        const uint32_t first = c->pending.front().slot, n = (uint32_t)c->pending.size();
+        const uint32_t head = std::min(n, moe_ctx::ROUTE_LOG - first);
+        HIPCHK(hipMemcpy(c->route_log + (size_t)first * MOE_MAX_TOPK, c->route_log_dev + (size_t)first * MOE_MAX_TOPK, head * entry, hipMemcpyDeviceToHost));
+        if (n > head) HIPCHK(hipMemcpy(c->route_log, c->route_log_dev, (n - head) * entry, hipMemcpyDeviceToHost));
+    }
     std::vector<AccessRec> access;
     std::vector<CopyOp> misses;
     std::vector<int32_t> needed;
