@@ -49,32 +49,39 @@ constexpr int GATE_WAVES = GATE_THREADS / WAVE;
 // only at the 1e-16 level, so routing equals an fp64 reference except on ties closer than that.
 // SPEC: the launch also evaluates the next layer's gate (a.wg2).  Without it the accumulators of the second gate
 // are not needed and the registers go to this thread's first slice of W_g instead, requested before the norm's
-// reduction so that its memory latency overlaps the norm rather than following it.
+// reduction so that its memory latency overlaps the norm rather than following it (after the thread's slice of x:
+// loads return in order, and the norm waits for x).
+// After the one barrier that collects the waves' partial logits, wave 0 finishes alone: lane e holds logit e (lane
+// 16 + e the next layer's), the selection runs on values read from those lanes, and the exponentials, divisions and
+// stores of the K chosen experts (and of the next layer's probabilities) are one per lane.
 template <bool SPEC>
 __global__ __launch_bounds__(GATE_THREADS) void k_gate(GateArgs a)
 {
     constexpr int NACC = SPEC ? 32 : 16;
     constexpr int NPRE = SPEC ? 0 : 8;                   // experts whose first slice is requested up front
     __shared__ double red[GATE_WAVES][32];
-    __shared__ double tot[33];
-    __shared__ double prob[16];          // thread 0's small tables live in LDS: indexed at run time, they would
-    __shared__ int chosen[4];            // otherwise be carved out of scratch memory for every lane of the launch
+    __shared__ double inv_rms;
     const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const uint16_t *x = a.x + (size_t)b * a.H;
     const int n1 = a.wg ? a.E : 0, n2 = (SPEC && a.wg2) ? a.E2 : 0;
+    const bool normed = a.eps > 0.0;
 
+    const int i0 = tid * 4;                              // the thread's first slice
+    const uint2 ones = make_uint2(0x3c003c00u, 0x3c003c00u);
+    const uint2 x0 = i0 < a.H ? *reinterpret_cast<const uint2 *>(x + i0) : make_uint2(0u, 0u);
+    const uint2 g0 = (normed && a.gamma && i0 < a.H) ? *reinterpret_cast<const uint2 *>(a.gamma + i0) : ones;
     float4 wpre[NPRE > 0 ? NPRE : 1];
     if constexpr (NPRE > 0) {
 #pragma unroll
         for (int e = 0; e < NPRE; ++e)
-            wpre[e] = (e < n1 && tid * 4 < a.H) ? *reinterpret_cast<const float4 *>(a.wg + (size_t)e * a.H + tid * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
+            wpre[e] = (e < n1 && i0 < a.H) ? *reinterpret_cast<const float4 *>(a.wg + (size_t)e * a.H + i0) : make_float4(0.f, 0.f, 0.f, 0.f);
     }
 
     double scale = 1.0;
-    if (a.eps > 0.0) {
+    if (normed) {
         double ss = 0.0;
-        for (int i = tid * 4; i < a.H; i += GATE_THREADS * 4) {
-            const uint2 p = *reinterpret_cast<const uint2 *>(x + i);
+        for (int i = i0; i < a.H; i += GATE_THREADS * 4) {
+            const uint2 p = i == i0 ? x0 : *reinterpret_cast<const uint2 *>(x + i);
             const double v0 = half_bits_to_f64(p.x & 0xffff), v1 = half_bits_to_f64(p.x >> 16);
             const double v2 = half_bits_to_f64(p.y & 0xffff), v3 = half_bits_to_f64(p.y >> 16);
             ss += v0 * v0; ss += v1 * v1; ss += v2 * v2; ss += v3 * v3;
@@ -85,21 +92,21 @@ __global__ __launch_bounds__(GATE_THREADS) void k_gate(GateArgs a)
         if (tid == 0) {
             double t = 0.0;
             for (int w = 0; w < GATE_WAVES; ++w) t += red[w][0];
-            tot[32] = 1.0 / sqrt(t / (double)a.H + a.eps);
+            inv_rms = 1.0 / sqrt(t / (double)a.H + a.eps);
         }
         __syncthreads();
-        scale = tot[32];
+        scale = inv_rms;
     }
 
     double acc[NACC];
 #pragma unroll
     for (int e = 0; e < NACC; ++e) acc[e] = 0.0;
-    for (int i = tid * 4; i < a.H; i += GATE_THREADS * 4) {
-        const uint2 p = *reinterpret_cast<const uint2 *>(x + i);
+    for (int i = i0; i < a.H; i += GATE_THREADS * 4) {
+        const uint2 p = i == i0 ? x0 : *reinterpret_cast<const uint2 *>(x + i);
         uint16_t hv[4] = {(uint16_t)(p.x & 0xffff), (uint16_t)(p.x >> 16), (uint16_t)(p.y & 0xffff), (uint16_t)(p.y >> 16)};
-        if (a.eps > 0.0) {
-            uint2 g = make_uint2(0x3c003c00u, 0x3c003c00u);
-            if (a.gamma) g = *reinterpret_cast<const uint2 *>(a.gamma + i);
+        if (normed) {
+            uint2 g = ones;
+            if (a.gamma) g = i == i0 ? g0 : *reinterpret_cast<const uint2 *>(a.gamma + i);
             const uint16_t gv[4] = {(uint16_t)(g.x & 0xffff), (uint16_t)(g.x >> 16), (uint16_t)(g.y & 0xffff), (uint16_t)(g.y >> 16)};
 #pragma unroll
             for (int j = 0; j < 4; ++j) hv[j] = f64_to_f16_rne(half_bits_to_f64(hv[j]) * scale * half_bits_to_f64(gv[j]));
@@ -114,7 +121,7 @@ __global__ __launch_bounds__(GATE_THREADS) void k_gate(GateArgs a)
         for (int e = 0; e < 16; ++e)
             if (e < n1) {
                 float4 w;
-                if (e < NPRE && i == tid * 4) w = wpre[e < NPRE ? e : 0];
+                if (e < NPRE && i == i0) w = wpre[e < NPRE ? e : 0];
                 else w = *reinterpret_cast<const float4 *>(a.wg + (size_t)e * a.H + i);
                 acc[e] += (double)w.x * h0; acc[e] += (double)w.y * h1; acc[e] += (double)w.z * h2; acc[e] += (double)w.w * h3;
             }
@@ -139,35 +146,24 @@ __global__ __launch_bounds__(GATE_THREADS) void k_gate(GateArgs a)
         if (lane < 16) red[wv][wave_sum_index<16>(lane)] = acc[0];
     }
     __syncthreads();
-    if (tid < 32) {
-        const bool live = (tid < 16) ? (tid < n1) : (tid - 16 < n2);
-        if (live) {
-            double t = 0.0;
-            for (int w = 0; w < GATE_WAVES; ++w) t += red[w][tid];
-            tot[tid] = t;
-        }
-    }
-    __syncthreads();
-    // speculative gate: one thread per expert takes its exponential (thread 0 alone would take them one after another)
-    __shared__ double spec_e[16];
-    if constexpr (SPEC) {
-        if (tid < n2) {
-            double zmax = tot[16];
-            for (int e = 1; e < n2; ++e) zmax = tot[16 + e] > zmax ? tot[16 + e] : zmax;
-            spec_e[tid] = exp(tot[16 + tid] - zmax);
-        }
-        __syncthreads();
-    }
-    if (tid == 0) {
-        GateHostOut *o = a.out;
-        if (n1) {
-            // top-K by (logit descending, index ascending).  The logits move to registers first (fixed indices): every
-            // comparison out of LDS would otherwise be a dependent round trip of this one thread.
-            double z[16];
+    if (wv != 0) return;
+
+    const bool live = lane < 16 ? lane < n1 : (lane < 32 && lane - 16 < n2);
+    double t = 0.0;
+    if (live)
+        for (int w = 0; w < GATE_WAVES; ++w) t += red[w][lane];
+    GateHostOut *o = a.out;
+    if (n1) {
+        // top-K by (logit descending, index ascending), the same for every lane: on the 16 logits read from their lanes
+        double z[16];
 #pragma unroll
-            for (int e = 0; e < 16; ++e) z[e] = e < n1 ? tot[e] : 0.0;
-            uint32_t used = 0;
-            for (int j = 0; j < a.K; ++j) {
+        for (int e = 0; e < 16; ++e) z[e] = readlane_d(t, e);
+        int c[4] = {0, 0, 0, 0};
+        double zc[4] = {0.0, 0.0, 0.0, 0.0};
+        uint32_t used = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (j < a.K) {
                 int best = -1;
                 double zb = 0.0;
 #pragma unroll
@@ -176,39 +172,56 @@ __global__ __launch_bounds__(GATE_THREADS) void k_gate(GateArgs a)
                     best = take ? e : best;
                     zb = take ? z[e] : zb;
                 }
-                chosen[j] = best;
+                c[j] = best;
+                zc[j] = zb;
                 used |= 1u << best;
-                prob[j] = zb;                // the chosen logit, until the softmax below replaces it
             }
-            // softmax over all experts, renormalised over the chosen ones == softmax over the chosen logits
-            const double zmax = prob[0];
-            double ps;
-            prob[0] = 1.0;                   // exp(0): the first choice holds the largest logit
-            ps = 1.0;
-            for (int j = 1; j < a.K; ++j) { prob[j] = exp(prob[j] - zmax); ps += prob[j]; }
-            if (a.route_idx) {
-                for (int j = 0; j < a.K; ++j) {
-                    a.route_idx[j] = chosen[j];
-                    a.route_w[j] = (float)(prob[j] / ps);
-                    a.route_log[j] = chosen[j];
+        // softmax over all experts, renormalised over the chosen ones == softmax over the chosen logits; lane j < K
+        // takes choice j (the first holds the largest logit: exp(0) = 1)
+        int mine = 0;
+        double zmine = zc[0];
+#pragma unroll
+        for (int j = 1; j < 4; ++j)
+            if (lane == j && j < a.K) { mine = c[j]; zmine = zc[j]; }
+        if (lane == 0) mine = c[0];
+        const double pe = exp(zmine - zc[0]);
+        double ps = 0.0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (j < a.K) ps += readlane_d(pe, j);
+        const float wgt = (float)(pe / ps);
+        if (a.route_idx) {
+            if (lane < a.K) {
+                a.route_idx[lane] = mine;
+                a.route_w[lane] = wgt;
+                a.route_log[lane] = mine;
+            }
+            return;
+        }
+        if (lane < a.K) {
+            o->idx[b * a.K + lane] = mine;
+            o->w[b * a.K + lane] = wgt;
+        }
+        if (lane < n1) o->logits[b * n1 + lane] = t;
+    }
+    if constexpr (SPEC) {
+        if (n2) {
+            double zmax = readlane_d(t, 16);
+#pragma unroll
+            for (int e = 1; e < 16; ++e)
+                if (e < n2) {
+                    const double v = readlane_d(t, 16 + e);
+                    zmax = v > zmax ? v : zmax;
                 }
-                return;
-            }
-            for (int j = 0; j < a.K; ++j) {
-                o->idx[b * a.K + j] = chosen[j];
-                o->w[b * a.K + j] = (float)(prob[j] / ps);
-            }
+            const double se = exp(t - zmax);
+            double ps = 0.0;
 #pragma unroll
             for (int e = 0; e < 16; ++e)
-                if (e < n1) o->logits[b * n1 + e] = z[e];
+                if (e < n2) ps += readlane_d(se, 16 + e);
+            if (lane >= 16 && lane - 16 < n2) o->spec_p[b * n2 + lane - 16] = se / ps;
         }
-        if (n2) {
-            double ps = 0.0;
-            for (int e = 0; e < n2; ++e) ps += spec_e[e];
-            for (int e = 0; e < n2; ++e) o->spec_p[b * n2 + e] = spec_e[e] / ps;
-        }
-        __hip_atomic_store(&o->done[b], a.seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
     }
+    if (lane == 0) __hip_atomic_store(&o->done[b], a.seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
 }
 
 }  // namespace moe
