@@ -8,11 +8,14 @@
 // Step       = one segment of 8 groups (512 codes) of a work item: 128 rows x (256 B codes + 32 B pairs) = 36 KB.
 // Block      = 4 waves, two blocks per compute unit (their phases drift apart, so one block's loads overlap the
 //              other's arithmetic), each walking its items (blockIdx.x, +gridDim.x, ...) as one sequence of
-//              steps.  During step s every wave first requests what step s+1 needs -- its own A operands
+//              steps.  During step s every wave requests what step s+1 needs -- its own A operands
 //              (activations of up to 32 tokens, from L2) and its share of the 36 KB of weights (from HBM, into
-//              registers) -- then multiplies step s out of one of two LDS buffers, then stores the arrived weights
-//              to the other buffer; one barrier per step.  Memory loads return in order per wave, so nothing
-//              inside the multiply may wait for a load: that is why the A operands travel a full step ahead.
+//              registers) -- in eight pieces, one beside each (group, tile) unit it multiplies out of one of two LDS
+//              buffers (a wave that issues its whole share at once stalls on the full queues of the memory pipeline;
+//              what depends on the item alone -- expert, token rows -- is looked up once per item), then stores the
+//              arrived weights to the other buffer; one barrier per step.  Memory loads return in order per wave, so
+//              nothing inside the multiply may wait for a load of the same step: the A operands travel a full step
+//              ahead.
 // Wave w     = groups w and w+4 of the step for all four 32-row tiles: A operand once per group, reused by the four
 //              tiles; B operand from LDS as codes (read one tile ahead), dequantised to fp16 in registers,
 //              w = (q - z) s computed as (q - rint(z)) s + (rint(z) - z) s with one rounding, and the MFMA
@@ -169,22 +172,53 @@ __global__ __launch_bounds__(TL_THREADS, TL_BLOCKS_PER_CU) void k_mfma_stream_q4
     TileStep nxt = next(cur);
     int buf = 0;
 
+    // ---------------- addresses ----------------
+    // What depends on the item alone -- its expert's matrix, this lane's token row of the activations (a lookup in the
+    // LDS tables) -- is worked out when the sequence of loads enters the item; a step then adds only uniform terms
+    // (segment, 16-row slab), which stay in scalar registers, to per-thread offsets that never change.
+    int addr_it = -1;
+    const uint8_t *mat_base = nullptr;
+    uint32_t act_off = 0;                                            // bytes: token row of act + this lane's half of a group
+    auto token_index = [&](const TileStep &s) -> int {               // row of act; lanes past the last token read the first again
+        const MfmaEntry &en = A.e[s.e];
+        const int tk = col < en.n_tok ? col : 0;
+        return W13 ? l_tok[en.first + tk] : l_pair[en.first + tk];
+    };
+    auto enter_item = [&](const TileStep &s) {
+        if (s.it == addr_it) return;
+        addr_it = s.it;
+        mat_base = A.e[s.e].blob + A.mat_off;
+        act_off = (uint32_t)token_index(s) * (uint32_t)A.K * 2u + (uint32_t)kh * 64u;
+    };
+
     // ---------------- weights: HBM -> registers -> LDS ----------------
+    // The loads of a step go out in pieces, one between every two units of the multiply (below): a wave that issues
+    // its whole share at once finds the memory pipeline's queues full and stalls where it could be computing.
     uint4 st_c[TL_CP], st_m[TL_MP];
-    auto fetch = [&](const TileStep &s) {
-        const uint8_t *mat = A.e[s.e].blob + A.mat_off;
-        const int g0 = s.seg * TL_SG, sg = seg_groups(s), row0 = s.rb * TL_ROWS;
-#pragma unroll
-        for (int i = 0; i < TL_CP; ++i) {
-            const int p = tid + i * TL_THREADS, r = p / TL_CPR, c = p % TL_CPR;
-            st_c[i] = ldw4(mat + (size_t)min(row0 + r, n_rows - 1) * A.stride, g0 * 2 + (c < 2 * sg ? c : 0));
-        }
+    struct FetchCtx { const uint8_t *seg; uint32_t voff; int row0, g0, sg; };
+    constexpr int SLAB = TL_THREADS / TL_CPR;                        // rows that one piece index covers (16)
+    static_assert(TL_THREADS % TL_CPR == 0 && 64 % SLAB == 0, "a slab of rows lies wholly inside or outside a matrix of 64 k rows");
+    auto fetch_begin = [&](const TileStep &s) -> FetchCtx {
+        enter_item(s);
+        FetchCtx f;
+        f.g0 = s.seg * TL_SG; f.sg = seg_groups(s); f.row0 = s.rb * TL_ROWS;
+        const uint32_t c = tid % TL_CPR;
+        f.voff = (uint32_t)(tid / TL_CPR) * A.stride + ((int)c < 2 * f.sg ? c : 0u) * 16u;
+        f.seg = mat_base + (size_t)f.g0 * 32;
+        return f;
+    };
+    auto fetch_codes = [&](const FetchCtx &f, int i) {
+        // a slab past the end of the matrix reads the last one instead: a redundant, cached read nobody uses
+        st_c[i] = ldw4(f.seg + (size_t)min(f.row0 + i * SLAB, n_rows - SLAB) * A.stride + f.voff, 0);
+    };
+    auto fetch_meta = [&](const FetchCtx &f) {
+        const int g0 = f.g0, sg = f.sg, row0 = f.row0;
 #pragma unroll
         for (int i = 0; i < TL_MP; ++i) {
             const int p = tid + i * TL_THREADS, r = p / TL_MPR, c = p % TL_MPR;
             // a step takes 32 B of a row's pairs, its neighbours in the cache line belong to the next steps: a
             // plain load, so that L2 keeps the line (the streaming hint would fetch it from HBM once per step)
-            const uint8_t *rowp = mat + (size_t)min(row0 + r, n_rows - 1) * A.stride;
+            const uint8_t *rowp = mat_base + (size_t)min(row0 + r, n_rows - 1) * A.stride;
             if constexpr (META8) {            // piece 0: the step's 8 byte pairs; piece 1: the fp16 quad of its run
                 static_assert(TL_SG == 8 && TL_MPR == 2, "two-level staging is laid out for steps of 8 groups");
                 if (c == 0) {
@@ -220,20 +254,17 @@ __global__ __launch_bounds__(TL_THREADS, TL_BLOCKS_PER_CU) void k_mfma_stream_q4
     for (int rt = 0; rt < TL_RT; ++rt)
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[rt][i] = 0.f;
-    auto token_index = [&](const TileStep &s) -> int {               // row of act; lanes past the last token read the first again
-        const MfmaEntry &en = A.e[s.e];
-        const int tk = col < en.n_tok ? col : 0;
-        return W13 ? l_tok[en.first + tk] : l_pair[en.first + tk];
+    auto load_a_piece = [&](h8_t (&dst)[TL_GPW][4], const TileStep &s, int j, int q) {   // one MFMA's A operand of step s
+        const int g = s.seg * TL_SG + min(wv + TL_WAVES * j, seg_groups(s) - 1);
+        const uint8_t *grp = reinterpret_cast<const uint8_t *>(A.act) + (size_t)g * 128;
+        dst[j][q] = __builtin_bit_cast(h8_t, *reinterpret_cast<const uint4 *>(grp + act_off + q * 16));
     };
-    auto load_a = [&](h8_t (&dst)[TL_GPW][4], const TileStep &s) {   // this wave's A operands of step s
-        const uint16_t *row = A.act + (size_t)token_index(s) * A.K;
-#pragma unroll
-        for (int j = 0; j < TL_GPW; ++j) {
-            const int g = s.seg * TL_SG + min(wv + TL_WAVES * j, seg_groups(s) - 1);
-#pragma unroll
-            for (int q = 0; q < 4; ++q)
-                dst[j][q] = __builtin_bit_cast(h8_t, *reinterpret_cast<const uint4 *>(row + (size_t)g * 64 + kh * 32 + q * 8));
-        }
+    // piece u of the loads of step s: unit u = (group j, tile rt) of the multiply runs beside it
+    static_assert(TL_CP == TL_GPW * TL_RT && TL_RT == 4, "one piece of codes and one A operand per unit");
+    auto load_piece = [&](const FetchCtx &f, h8_t (&a_dst)[TL_GPW][4], const TileStep &s, int u) {
+        if (u == 0) fetch_meta(f);
+        fetch_codes(f, u);
+        load_a_piece(a_dst, s, u / TL_RT, u % TL_RT);
     };
     // One unit = one group of one 32-row tile; its codes and pair are read from LDS one unit ahead of their use.
     struct UnitMeta { uint32_t m, quad0, quad1; };                   // one-level: m = (scale, zero) fp16; two-level: byte pair + the run's quad
@@ -292,13 +323,14 @@ __global__ __launch_bounds__(TL_THREADS, TL_BLOCKS_PER_CU) void k_mfma_stream_q4
     };
     uint4 q_next = make_uint4(0, 0, 0, 0);
     UnitMeta m_next = {0u, 0u, 0u};
-    auto group_multiply = [&](const h8_t (&a)[4], int b, int gl, int sg, int j) {   // q_next/m_next hold tile 0 of group gl
+    auto group_multiply = [&](const h8_t (&a)[4], int b, int gl, int sg, int j, auto &&beside) {   // q_next/m_next hold tile 0 of group gl
 #pragma unroll
         for (int rt = 0; rt < TL_RT; ++rt) {
             const uint4 q = q_next;
             const UnitMeta m = m_next;
             if (rt + 1 < TL_RT) unit_load(b, gl, rt + 1, q_next, m_next);
             else if (gl + TL_WAVES < sg) unit_load(b, gl + TL_WAVES, 0, q_next, m_next);
+            beside(j * TL_RT + rt);
             unit_multiply(a, q, m, rt, j);
         }
     };
@@ -362,24 +394,32 @@ __global__ __launch_bounds__(TL_THREADS, TL_BLOCKS_PER_CU) void k_mfma_stream_q4
     // ---------------- one step; true when it was the block's last ----------------
     auto step = [&](const h8_t (&a_use)[TL_GPW][4], h8_t (&a_load)[TL_GPW][4]) -> bool {
         const bool item_ends = !nxt.valid || nxt.it != cur.it;
-        load_a(a_load, nxt.valid ? nxt : cur);              // past the last step: re-read, never used
-        if (nxt.valid) fetch(nxt);
+        const TileStep &ld = nxt.valid ? nxt : cur;                  // past the last step: re-read, never used
+        const FetchCtx f = fetch_begin(ld);
+        auto beside = [&](int u) { load_piece(f, a_load, ld, u); };
         const int sg = seg_groups(cur);
         if (wv < sg) {
             unit_load(buf, wv, 0, q_next, m_next);
-            group_multiply(a_use[0], buf, wv, sg, 0);
+            group_multiply(a_use[0], buf, wv, sg, 0, beside);
+        } else {
+#pragma unroll
+            for (int u = 0; u < TL_RT; ++u) beside(u);
         }
         if (wv + TL_WAVES < sg) {
-            group_multiply(a_use[1], buf, wv + TL_WAVES, sg, 1);
-        } else if constexpr (R1) {
+            group_multiply(a_use[1], buf, wv + TL_WAVES, sg, 1, beside);
+        } else {
 #pragma unroll
-            for (int rt = 0; rt < TL_RT; ++rt) rho[rt][1] = 0u;      // no second group in a short step
+            for (int u = TL_RT; u < 2 * TL_RT; ++u) beside(u);
+            if constexpr (R1) {
+#pragma unroll
+                for (int rt = 0; rt < TL_RT; ++rt) rho[rt][1] = 0u;  // no second group in a short step
+            }
         }
         if constexpr (R1) {
             if (wv < sg) rank1_correct(a_use);
         }
         if (item_ends) finish_item(cur, buf);
-        // unconditional (after the last step it stores stale registers nobody reads): the wait for the loads above
+        // unconditional (after the last step it stores a copy nobody reads): the wait for the loads above
         // then sits on every path, and the next step starts with nothing in flight as far as the compiler can tell
         commit(buf ^ 1);
         __syncthreads();                                             // next buffer filled, this one free again
@@ -391,8 +431,11 @@ __global__ __launch_bounds__(TL_THREADS, TL_BLOCKS_PER_CU) void k_mfma_stream_q4
     };
 
     h8_t a0[TL_GPW][4], a1[TL_GPW][4];
-    load_a(a0, cur);
-    fetch(cur);
+    {
+        const FetchCtx f = fetch_begin(cur);
+#pragma unroll
+        for (int u = 0; u < TL_CP; ++u) load_piece(f, a0, cur, u);
+    }
     commit(0);
     __builtin_amdgcn_s_waitcnt(0x0F70);                              // vmcnt(0): the loop starts with nothing in flight
     __syncthreads();
