@@ -261,10 +261,12 @@ __global__ __launch_bounds__(TL_THREADS, TL_BLOCKS_PER_CU) void k_mfma_stream_q4
     };
     // piece u of the loads of step s: unit u = (group j, tile rt) of the multiply runs beside it
     static_assert(TL_CP == TL_GPW * TL_RT && TL_RT == 4, "one piece of codes and one A operand per unit");
+    // the A operand goes first: the codes then are the last load of a step, and the wait for them before they are
+    // stored to LDS leaves nothing in flight for the next step's multiply to wait for
     auto load_piece = [&](const FetchCtx &f, h8_t (&a_dst)[TL_GPW][4], const TileStep &s, int u) {
+        load_a_piece(a_dst, s, u / TL_RT, u % TL_RT);
         if (u == 0) fetch_meta(f);
         fetch_codes(f, u);
-        load_a_piece(a_dst, s, u / TL_RT, u % TL_RT);
     };
     // One unit = one group of one 32-row tile; its codes and pair are read from LDS one unit ahead of their use.
     struct UnitMeta { uint32_t m, quad0, quad1; };                   // one-level: m = (scale, zero) fp16; two-level: byte pair + the run's quad
