@@ -195,27 +195,32 @@ __global__ __launch_bounds__(TL_THREADS, TL_BLOCKS_PER_CU) void k_mfma_stream_q4
     // The loads of a step go out in pieces, one between every two units of the multiply (below): a wave that issues
     // its whole share at once finds the memory pipeline's queues full and stalls where it could be computing.
     uint4 st_c[TL_CP], st_m[TL_MP];
-    struct FetchCtx { const uint8_t *seg; uint32_t voff; int row0, g0, sg; };
+    struct FetchCtx { const uint8_t *seg; uint32_t voff; int row0, slab, g0, sg; bool live; };
     constexpr int SLAB = TL_THREADS / TL_CPR;                        // rows that one piece index covers (16)
     static_assert(TL_THREADS % TL_CPR == 0 && 64 % SLAB == 0, "a slab of rows lies wholly inside or outside a matrix of 64 k rows");
-    auto fetch_begin = [&](const TileStep &s) -> FetchCtx {
+    // live = false (after a block's last step there is nothing to fetch): the loads stay in the instruction stream,
+    // so that no branch surrounds them, but every lane of every piece reads the same 16 bytes
+    auto fetch_begin = [&](const TileStep &s, bool live) -> FetchCtx {
         enter_item(s);
         FetchCtx f;
-        f.g0 = s.seg * TL_SG; f.sg = seg_groups(s); f.row0 = s.rb * TL_ROWS;
+        f.live = live;
+        f.g0 = s.seg * TL_SG; f.sg = seg_groups(s);
+        f.row0 = live ? s.rb * TL_ROWS : 0;
+        f.slab = live ? SLAB : 0;
         const uint32_t c = tid % TL_CPR;
-        f.voff = (uint32_t)(tid / TL_CPR) * A.stride + ((int)c < 2 * f.sg ? c : 0u) * 16u;
+        f.voff = live ? (uint32_t)(tid / TL_CPR) * A.stride + ((int)c < 2 * f.sg ? c : 0u) * 16u : 0u;
         f.seg = mat_base + (size_t)f.g0 * 32;
         return f;
     };
     auto fetch_codes = [&](const FetchCtx &f, int i) {
         // a slab past the end of the matrix reads the last one instead: a redundant, cached read nobody uses
-        st_c[i] = ldw4(f.seg + (size_t)min(f.row0 + i * SLAB, n_rows - SLAB) * A.stride + f.voff, 0);
+        st_c[i] = ldw4(f.seg + (size_t)min(f.row0 + i * f.slab, n_rows - SLAB) * A.stride + f.voff, 0);
     };
     auto fetch_meta = [&](const FetchCtx &f) {
         const int g0 = f.g0, sg = f.sg, row0 = f.row0;
 #pragma unroll
         for (int i = 0; i < TL_MP; ++i) {
-            const int p = tid + i * TL_THREADS, r = p / TL_MPR, c = p % TL_MPR;
+            const int p = tid + i * TL_THREADS, r = f.live ? p / TL_MPR : 0, c = p % TL_MPR;
             // a step takes 32 B of a row's pairs, its neighbours in the cache line belong to the next steps: a
             // plain load, so that L2 keeps the line (the streaming hint would fetch it from HBM once per step)
             const uint8_t *rowp = mat_base + (size_t)min(row0 + r, n_rows - 1) * A.stride;
@@ -396,8 +401,8 @@ __global__ __launch_bounds__(TL_THREADS, TL_BLOCKS_PER_CU) void k_mfma_stream_q4
     // ---------------- one step; true when it was the block's last ----------------
     auto step = [&](const h8_t (&a_use)[TL_GPW][4], h8_t (&a_load)[TL_GPW][4]) -> bool {
         const bool item_ends = !nxt.valid || nxt.it != cur.it;
-        const TileStep &ld = nxt.valid ? nxt : cur;                  // past the last step: re-read, never used
-        const FetchCtx f = fetch_begin(ld);
+        const TileStep &ld = nxt.valid ? nxt : cur;                  // past the last step: 16 bytes re-read, never used
+        const FetchCtx f = fetch_begin(ld, nxt.valid);
         auto beside = [&](int u) { load_piece(f, a_load, ld, u); };
         const int sg = seg_groups(cur);
         if (wv < sg) {
@@ -434,7 +439,7 @@ __global__ __launch_bounds__(TL_THREADS, TL_BLOCKS_PER_CU) void k_mfma_stream_q4
 
     h8_t a0[TL_GPW][4], a1[TL_GPW][4];
     {
-        const FetchCtx f = fetch_begin(cur);
+        const FetchCtx f = fetch_begin(cur, true);
 #pragma unroll
         for (int u = 0; u < TL_CP; ++u) load_piece(f, a0, cur, u);
     }
