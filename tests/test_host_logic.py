@@ -78,7 +78,8 @@ def test_bookkeeping_equals_oracle_simulator(L, E, k, m, b, B_):
 
 def test_bookkeeping_random_configurations():
     """Sixty seeded draws over everything the bookkeeping depends on (experts, top-k, slots, guesses, staging buffers
-    including none, batch, per-layer shapes alike) against the oracle simulator, decision by decision."""
+    including none, batch, cold or warm start, swap mode with its placement of experts in host buffers) against the
+    oracle simulator, decision by decision."""
     for seed in range(60):
         rng = np.random.default_rng(4000 + seed)
         E = int(rng.integers(1, 17))
@@ -88,11 +89,20 @@ def test_bookkeeping_random_configurations():
         b = int(rng.integers(0, 7))
         L = int(rng.integers(1, 5))
         B_ = int(rng.choice([1, 1, 2, 3, 7, 16, 40]))
-        cfgs = [layer_config(64, 64, E, K, 4, 64, k, m, 0.0, 0, 0) for _ in range(L)]
+        warm = bool(rng.random() < 0.4)                  # experts 0..k-1 resident from the start
+        swap = warm and bool(rng.random() < 0.5)         # ... and evicted experts written back (host holds E-k+1 buffers)
+        cfgs = [layer_config(64, 64, E, K, 4, 64, k, m, 0.0, 1 if warm else 0, B.MOE_LAYER_SWAP if swap else 0) for _ in range(L)]
         st = Stack(cfgs, [torch.zeros(E, 64) for _ in range(L)], n_staging=b, max_batch=B_, host_only=True)
-        sim = O.ExpertCacheSim(L, E, k, b)
+        if warm:
+            q = np.zeros((64, 64), np.uint8); sz = np.zeros((64, 1), np.uint16)
+            for l in range(L):
+                for e in range(E):
+                    for mtx in range(3):
+                        B.moe_layer_load_expert(st.layers[l], e, mtx, q.ctypes.data, sz.ctypes.data, sz.ctypes.data)
+        sim = O.ExpertCacheSim(L, E, k, b, warm=warm)
+        place = [O.SwapPlacement(E, k) for _ in range(L)] if swap else None
         tr = B.StepTrace()
-        what = f"seed {seed}: E={E} K={K} k={k} m={m} b={b} L={L} B={B_}"
+        what = f"seed {seed}: E={E} K={K} k={k} m={m} b={b} L={L} B={B_} warm={warm} swap={swap}"
         for _ in range(25):
             for l in range(L):
                 sel = [[int(e) for e in rng.choice(E, size=K, replace=False)] for _ in range(B_)]
@@ -104,6 +114,9 @@ def test_bookkeeping_random_configurations():
                 acc, dec = sim.step(l, sel, O.prefetch_guess(score, m) if nxt else None)
                 assert tr.accesses() == [(a.expert, a.status, a.slot, a.victim) for a in acc], what
                 assert tr.guesses() == [(e, i) for e, i in dec], what
+                if swap:
+                    place[l].apply(acc)
+                    assert B.moe_layer_placement(st.layers[l], E) == (place[l].host_buf_of, place[l].spare), what
         for l in range(L):
             se, ss, staged = B.moe_layer_cache_state(st.layers[l], k)
             assert se == sim.slot_expert[l] and ss == sim.slot_stamp[l] and staged == sim.staged[l], what
