@@ -289,8 +289,9 @@ int32_t moe_ctx_profile_timeline(moe_ctx_t *ctx, int32_t kind, double *start_ms,
  *   "mfma_form"  which matrix-core kernels: 2 persistent streaming kernels that round each dequantised weight once
  *                to fp16 before the multiply, as Sec. 4.2's fp16 experts do; 3 (default) the same kernels with one
  *                fused multiply-add per pair of weights and the part its rounded constant leaves added back as a
- *                rank-1 term by one more matrix instruction per tile (fp16 metadata; with two-level metadata form
- *                2 runs); 1 row-staging kernels that keep the codes exact and scale every group's product in fp32
+ *                rank-1 term by one more matrix instruction per tile (fp16 metadata; with two-level metadata, and
+ *                for a layer loaded with a pair whose (1024 + |zero|) * |scale| exceeds 16384 -- the form computes
+ *                that product in fp16 -- form 2 runs); 1 row-staging kernels that keep the codes exact and scale every group's product in fp32
  *                (batches of at most 64 tokens, fp16 metadata; otherwise form 2 runs).  All meet the output
  *                tolerance;
  *   "spec_head_mb" 0 (default): a speculative load copies the whole expert at once, as the paper describes;

@@ -162,6 +162,7 @@ struct moe_layer {
     uint16_t *gamma_dev = nullptr;
     uint8_t *host_blobs = nullptr;
     std::vector<uint32_t> loaded;       // bit m set: matrix m of the expert was loaded
+    std::atomic<bool> wide_meta{false}; // a loaded (scale, zero) pair is too large for the rank-1 matrix-core form (below)
     std::vector<int32_t> own_bufs;      // the k pool buffers created for this layer
     // Where each expert's blob lives on the host: buffer index into host_blobs, or -1 while it is on the device
     // (swap mode only; otherwise expert e stays in buffer e for good).
@@ -551,6 +552,33 @@ static int32_t load_matrix(moe_layer *l, int32_t expert, int32_t matrix, const u
     return MOE_OK;
 }
 
+// binary16 bit pattern -> float (host side)
+static float half_bits_to_float(uint16_t h)
+{
+    const uint32_t sign = (uint32_t)(h & 0x8000u) << 16, ex = (h >> 10) & 0x1fu, man = h & 0x3ffu;
+    uint32_t bits;
+    if (ex == 0x1fu) bits = sign | 0x7f800000u | (man << 13);
+    else if (ex) bits = sign | ((ex + 112u) << 23) | (man << 13);
+    else if (!man) bits = sign;
+    else {
+        int e = -1;
+        uint32_t m = man;
+        do { m <<= 1; ++e; } while (!(m & 0x400u));
+        bits = sign | ((uint32_t)(112 - e) << 23) | ((m & 0x3ffu) << 13);
+    }
+    float f;
+    memcpy(&f, &bits, sizeof f);
+    return f;
+}
+
+// The rank-1 matrix-core form computes (1024 + z) * s in fp16: pairs for which that product (or anything else about
+// them) leaves the comfortable part of the fp16 range make the layer fall back to the form that subtracts first.
+static bool pair_fits_rank1(uint16_t scale, uint16_t zero)
+{
+    const float s = half_bits_to_float(scale), z = half_bits_to_float(zero);
+    return std::isfinite(s) && std::isfinite(z) && (1024.f + std::fabs(z)) * std::fabs(s) <= 16384.f;
+}
+
 extern "C" int32_t moe_layer_load_expert(moe_layer_t *l, int32_t expert, int32_t matrix, const uint8_t *codes,
                                          const uint16_t *scale, const uint16_t *zero)
 try {
@@ -560,8 +588,13 @@ try {
     const BlobLayout &b = l->lay;
     const MatLayout &m = mat_of(b, matrix);
     const uint32_t groups = m.cols / b.group;
+    const bool watch = b.bits == 4 && b.group == 64;     // the formats the matrix cores take
     return load_matrix(l, expert, matrix, codes, [&](uint32_t r, uint8_t *dst) {
-        pack_row(b, m, codes + (uint64_t)r * m.cols, scale + (uint64_t)r * groups, zero + (uint64_t)r * groups, dst);
+        const uint16_t *sr = scale + (uint64_t)r * groups, *zr = zero + (uint64_t)r * groups;
+        if (watch && !l->wide_meta.load(std::memory_order_relaxed))
+            for (uint32_t g = 0; g < groups; ++g)
+                if (!pair_fits_rank1(sr[g], zr[g])) { l->wide_meta.store(true, std::memory_order_relaxed); break; }
+        pack_row(b, m, codes + (uint64_t)r * m.cols, sr, zr, dst);
     });
 } catch (...) {
     return on_exception("moe_layer_load_expert");
@@ -1239,7 +1272,7 @@ static int32_t launch_mfma_stream(moe_layer *l, const std::vector<PassExpert> &e
         A.a = a_win; A.yacc = c->yacc + (size_t)w0 * b.hidden;
         A.act = c->h_buf + (size_t)w0 * b.hidden;
         const bool meta8 = b.scale_group > 0;
-        const bool r1 = c->mfma_form == 3 && !meta8;
+        const bool r1 = c->mfma_form == 3 && !meta8 && !l->wide_meta.load(std::memory_order_relaxed);
         auto run_shift = [&](const MatLayout &m) { return (m.run_len == 0 || m.run_len >= m.cols / (uint32_t)b.group) ? 31 : __builtin_ctz(m.run_len); };
         A.K = b.hidden; A.N = b.ffn; A.stride = b.m13.row_stride; A.meta_off = b.m13.meta_off; A.mat_off = b.off_w13;
         A.meta2_off = b.m13.meta2_off; A.run_shift = run_shift(b.m13);

@@ -866,3 +866,30 @@ def test_random_configurations(seed):
         assert again[name] == tot[name], f"{name}: {again[name]} after the whole-stack pass, {tot[name]} before"
     say(f"  whole-stack pass: device-routed steps {again['steps_device_routed']}")
     model.close()
+
+
+@pytest.mark.parametrize("factor,falls_back", [(1, False), (8192, True)])
+def test_rank1_matrix_core_form_gives_way_to_large_scales(factor, falls_back):
+    """The default matrix-core form forms (1024 + zero) * scale in fp16.  A layer that was loaded with a (scale, zero)
+    pair for which that product leaves the comfortable part of the fp16 range runs the form that subtracts first
+    instead: asking for form 3 then gives bit for bit what asking for form 2 gives (two addends per element here, so
+    the sums do not depend on their order), while on ordinary weights the two forms differ in the last bits."""
+    H, F, Bn = 256, 512, 16
+    say(f"rank-1 form and scales x{factor}")
+    model = Model(1, H, F, 8, 2, None, 8, 0, 0.0, max_batch=Bn, seed=77, keep_layers=[])
+    for e in range(8):
+        for mtx, (codes, scale, zero) in enumerate(W.quantized_expert(77, 0, e, H, F, 4, 64, model.device, 0)):
+            model.stack.load_expert(0, e, mtx, codes, (scale.float() * factor).half(), zero)
+    dev = model.stack.device
+    x_in = (W.hidden_ar1(77, 1, Bn, H)[0].float() / factor).half().to(dev)      # keeps the outputs in range
+    x_out = torch.empty(Bn, H, dtype=torch.float16, device=dev)
+    ys = {}
+    for form in (3, 2):
+        B.moe_ctx_set_option(model.stack.ctx, "mfma_form", form)
+        model.stack.step_layer(0, x_in, x_out, None, None, prefetch=False)
+        model.stack.synchronize()
+        ys[form] = model.stack.read_y(Bn, H).copy()
+        assert np.isfinite(ys[form]).all() and np.abs(ys[form]).max() > 0
+    same = (ys[3].view(np.uint32) == ys[2].view(np.uint32)).all()
+    assert same == falls_back, f"forms 3 and 2 {'agree' if same else 'differ'} bit for bit"
+    model.close()
