@@ -217,6 +217,22 @@ int32_t moe_layer_peek_run_meta(const moe_layer_t *layer, int32_t expert, int32_
 int32_t moe_layer_step(moe_layer_t *layer, moe_layer_t *next, const uint16_t *x_in_dev, int32_t batch,
                        uint16_t *x_out_dev, uint16_t *h_out_dev, moe_step_trace_t *trace);
 
+/* moe_layer_step for callers that cannot allocate device memory: code that runs while a HIP graph is being captured
+ * elsewhere in the process, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same decisions,
+ * traces and results as moe_layer_step, computed by the same kernels; the difference is where those kernels keep
+ * their intermediate results (the gate input h, the SwiGLU activations a, the fp32 block output y): not in the
+ * context's arena but in a fixed array inside the library's own device image (about 0.7 MB, held by every GPU the
+ * library runs on until the process ends).  The call makes no device or pinned-host allocation, frees none and
+ * creates no stream or event; its host-side bookkeeping uses the ordinary C++ heap.  Limits, checked with MOE_EINVAL:
+ * batch <= 4, hidden <= 8192, ffn <= 16384, top_k <= 4.  MOE_ESTATE while launch timing (moe_ctx_profile_enable) is on,
+ * and in a host-only context.  The host always waits for the gate here (no device-routed steps) and option "fused" is
+ * ignored.  The array keeps the previous call's contents; what must start at zero is cleared by the step's own gate
+ * kernel.  All calls on one GPU, from any context, share the one array: two that overlap in time (different
+ * contexts on different streams) race; calls of one context are ordered by its compute stream.
+ * moe_ctx_read_y does not see the y of such a step. */
+int32_t moe_layer_step_noalloc(moe_layer_t *layer, moe_layer_t *next, const uint16_t *x_in_dev, int32_t batch,
+                               uint16_t *x_out_dev, uint16_t *h_out_dev, moe_step_trace_t *trace);
+
 /* Stand-alone speculative loading (Sec. 3.2): apply `layer`'s own gate to h_dev [batch][H] fp16 (the
  * previous layer's gate input) and stage up to prefetch_m guesses for `layer`.  Makes exactly the
  * decisions moe_layer_step(prev, next=layer) makes.  trace (nullable) gets n_guess, guess_*. */

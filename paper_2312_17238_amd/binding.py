@@ -23,7 +23,7 @@ MOE_LAYER_SWAP = 2
 EXPORTS = [
     "moe_expert_blob_bytes", "moe_expert_blob_bytes_2level", "moe_ctx_dev_bytes", "moe_layer_dev_bytes", "moe_layer_host_bytes",
     "moe_ctx_create", "moe_ctx_destroy", "moe_layer_create", "moe_layer_destroy",
-    "moe_layer_load_expert", "moe_layer_load_expert_2level", "moe_layer_peek_weight", "moe_layer_peek_run_meta", "moe_layer_step", "moe_layer_prefetch",
+    "moe_layer_load_expert", "moe_layer_load_expert_2level", "moe_layer_peek_weight", "moe_layer_peek_run_meta", "moe_layer_step", "moe_layer_step_noalloc", "moe_layer_prefetch",
     "moe_stack_step", "moe_layer_resolve", "moe_layer_stats", "moe_layer_cache_state", "moe_layer_placement",
     "moe_layer_reset", "moe_ctx_read_y", "moe_ctx_profile_enable", "moe_ctx_profile_read", "moe_ctx_profile_timeline", "moe_ctx_set_option", "moe_probe_bandwidth", "moe_layer_set_prefetch", "moe_layer_set_flags", "moe_last_error", "moe_last_hip_error",
 ]
@@ -133,6 +133,7 @@ def lib() -> C.CDLL:
     L.moe_layer_peek_weight.argtypes = [vp, i32, i32, i32, i32, C.POINTER(C.c_uint8), C.POINTER(C.c_uint16),
                                         C.POINTER(C.c_uint16)]
     L.moe_layer_step.argtypes = [vp, vp, vp, i32, vp, vp, C.POINTER(StepTrace)]
+    L.moe_layer_step_noalloc.argtypes = [vp, vp, vp, i32, vp, vp, C.POINTER(StepTrace)]
     L.moe_layer_prefetch.argtypes = [vp, vp, i32, C.POINTER(StepTrace)]
     L.moe_stack_step.argtypes = [C.POINTER(vp), i32, vp, i32, vp, C.POINTER(StepTrace)]
     L.moe_layer_resolve.argtypes = [vp, vp, C.POINTER(i32), i32, C.POINTER(C.c_double), C.POINTER(StepTrace)]
@@ -231,6 +232,12 @@ def moe_layer_step(layer, next_layer, x_in_dev: int, batch: int, x_out_dev: int,
                    trace: Optional[StepTrace] = None) -> None:
     check(lib().moe_layer_step(layer, next_layer, x_in_dev, batch, x_out_dev, h_out_dev,
                                C.byref(trace) if trace is not None else None))
+
+
+def moe_layer_step_noalloc(layer, next_layer, x_in_dev: int, batch: int, x_out_dev: int, h_out_dev: Optional[int] = None,
+                           trace: Optional[StepTrace] = None) -> None:
+    check(lib().moe_layer_step_noalloc(layer, next_layer, x_in_dev, batch, x_out_dev, h_out_dev,
+                                       C.byref(trace) if trace is not None else None))
 
 
 def moe_layer_prefetch(layer, h_dev: int, batch: int, trace: Optional[StepTrace] = None) -> None:

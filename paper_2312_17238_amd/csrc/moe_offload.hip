@@ -75,6 +75,26 @@ extern "C" const char *moe_last_error(void) { return g_err; }
 extern "C" int32_t moe_last_hip_error(void) { return g_hip_err; }
 
 // ---------------------------------------------------------------------------------------------
+// scratch of the entry point that allocates nothing
+// ---------------------------------------------------------------------------------------------
+
+// moe_layer_step_noalloc runs a step whose kernels keep their intermediate results (gate input h, SwiGLU
+// activations a, fp32 block output y) in this file-scope device array instead of the context's arena, for steps of
+// at most NOALLOC_MAX_BATCH tokens of layers no wider than the limits below.  Every GPU the library runs on holds its
+// own copy until the process ends; all calls on one GPU share it.
+constexpr int NOALLOC_MAX_BATCH = 4, NOALLOC_MAX_HIDDEN = 8192, NOALLOC_MAX_FFN = 16384, NOALLOC_MAX_TOPK = 4;
+constexpr size_t NOALLOC_H_BYTES = (size_t)NOALLOC_MAX_BATCH * NOALLOC_MAX_HIDDEN * 2;                    //  64 KB
+constexpr size_t NOALLOC_A_BYTES = (size_t)NOALLOC_MAX_BATCH * NOALLOC_MAX_TOPK * NOALLOC_MAX_FFN * 2;    // 512 KB
+constexpr size_t NOALLOC_Y_BYTES = (size_t)NOALLOC_MAX_BATCH * NOALLOC_MAX_HIDDEN * 4;                    // 128 KB
+constexpr size_t NOALLOC_BYTES = NOALLOC_H_BYTES + NOALLOC_A_BYTES + NOALLOC_Y_BYTES;
+static __device__ __align__(256) uint8_t scratch[NOALLOC_BYTES];
+
+// In host code the array's name is only a handle; its device address is asked for once per device, with that device
+// current, and kept here.  Host code uses this pointer, never the name.
+constexpr int NOALLOC_MAX_DEVICES = 64;
+static uint8_t *g_scratch_ptr[NOALLOC_MAX_DEVICES] = {};
+
+// ---------------------------------------------------------------------------------------------
 // objects
 // ---------------------------------------------------------------------------------------------
 
@@ -120,6 +140,7 @@ struct moe_ctx {
     BufferPool pool;
     uint16_t *h_buf = nullptr, *a_buf = nullptr, *xbuf[2] = {nullptr, nullptr};
     float *yacc = nullptr;
+    uint8_t *noalloc_scratch = nullptr; // this device's copy of the file-scope scratch array (moe_layer_step_noalloc)
     GateHostOut *gate_out = nullptr;    // host pointer
     GateHostOut *gate_out_dev = nullptr;// the same memory as the device sees it
     hipEvent_t ev_gate = nullptr, ev_compute = nullptr;
@@ -320,6 +341,15 @@ try {
         e = hipGetDevice(&dev);
         if (e == hipSuccess) e = hipGetDeviceProperties(&prop, dev);
         if (e == hipSuccess) c->n_cu = prop.multiProcessorCount;
+        // the device address of the file-scope scratch array, once per device, with that device current
+        if (e == hipSuccess && (dev < 0 || dev >= NOALLOC_MAX_DEVICES)) return fail(MOE_EINVAL, "moe_ctx_create: device ordinal %d out of range", dev);
+        if (e == hipSuccess && !g_scratch_ptr[dev]) {
+            void *p = nullptr;
+            e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+            if (e == hipSuccess && !p) return fail(MOE_EHIP, "moe_ctx_create: the scratch array has no device address");
+            if (e == hipSuccess) g_scratch_ptr[dev] = static_cast<uint8_t *>(p);
+        }
+        if (e == hipSuccess) c->noalloc_scratch = g_scratch_ptr[dev];
     }
     if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void **>(&c->gate_out), sizeof(GateHostOut), hipHostMallocMapped);
     if (e == hipSuccess) e = hipHostGetDevicePointer(reinterpret_cast<void **>(&c->gate_out_dev), c->gate_out, 0);
@@ -1461,9 +1491,11 @@ static int32_t device_routed_step(moe_layer *l, const uint16_t *x_in, uint16_t *
     return rc;
 }
 
-extern "C" int32_t moe_layer_step(moe_layer_t *l, moe_layer_t *next, const uint16_t *x_in, int32_t batch,
-                                  uint16_t *x_out, uint16_t *h_out, moe_step_trace_t *trace)
-try {
+// One decode step of one layer.  plain: the variant for callers that cannot allocate -- the host waits for the gate
+// (no selection log in the arena) and the one-launch kernel with its barrier flags in the arena is not used.
+static int32_t step_impl(moe_layer *l, moe_layer *next, const uint16_t *x_in, int32_t batch, uint16_t *x_out, uint16_t *h_out,
+                         moe_step_trace_t *trace, bool plain)
+{
     int32_t rc = check_step_args(l, next, batch);
     if (rc) return rc;
     moe_ctx *c = l->ctx;
@@ -1473,7 +1505,7 @@ try {
     const moe_layer_config_t &cf = l->cfg;
     const bool spec = next && next->cfg.prefetch_m > 0 && c->cfg.n_staging > 0;
     if (spec && !all_loaded(next)) return fail(MOE_ESTATE, "moe_layer_step: next layer not fully loaded");
-    if (device_routed_step_fits(l, next, batch, trace, spec)) return device_routed_step(l, x_in, x_out, h_out);
+    if (!plain && device_routed_step_fits(l, next, batch, trace, spec)) return device_routed_step(l, x_in, x_out, h_out);
     rc = fold_pending(c);
     if (rc) return rc;
 
@@ -1661,7 +1693,7 @@ try {
             FusedArgs fa = token_args(l, x_in, x_out);
             fa.n_exp = (int32_t)entries.size();
             for (int i = 0; i < fa.n_exp; ++i) { fa.blob[i] = entries[i].blob; fa.w[i] = entries[i].w[0]; fa.a_row[i] = entries[i].pair[0]; }
-            if (c->fused) {
+            if (c->fused && !plain) {
                 rc = launch_token(l, fa, true, false, &fused_done);
             } else {
                 rc = launch_token(l, fa, false, true, &fused_done);       // does the shape fit the token kernels?
@@ -1687,8 +1719,38 @@ try {
         HIPCHK(hipGetLastError());
     }
     return MOE_OK;
+}
+
+extern "C" int32_t moe_layer_step(moe_layer_t *l, moe_layer_t *next, const uint16_t *x_in, int32_t batch,
+                                  uint16_t *x_out, uint16_t *h_out, moe_step_trace_t *trace)
+try {
+    return step_impl(l, next, x_in, batch, x_out, h_out, trace, false);
 } catch (...) {
     return on_exception("moe_layer_step");
+}
+
+extern "C" int32_t moe_layer_step_noalloc(moe_layer_t *l, moe_layer_t *next, const uint16_t *x_in, int32_t batch,
+                                          uint16_t *x_out, uint16_t *h_out, moe_step_trace_t *trace)
+try {
+    int32_t rc = check_step_args(l, next, batch);
+    if (rc) return rc;
+    moe_ctx *c = l->ctx;
+    if (c->host_only || !c->noalloc_scratch) return fail(MOE_ESTATE, "moe_layer_step_noalloc: the context has no GPU");
+    if (batch > NOALLOC_MAX_BATCH || l->cfg.hidden > NOALLOC_MAX_HIDDEN || l->cfg.ffn > NOALLOC_MAX_FFN || l->cfg.top_k > NOALLOC_MAX_TOPK)
+        return fail(MOE_EINVAL, "moe_layer_step_noalloc: batch %d, hidden %d, ffn %d, top_k %d exceed the fixed scratch (at most %d, %d, %d, %d)",
+                    batch, l->cfg.hidden, l->cfg.ffn, l->cfg.top_k, NOALLOC_MAX_BATCH, NOALLOC_MAX_HIDDEN, NOALLOC_MAX_FFN, NOALLOC_MAX_TOPK);
+    if (c->prof.on) return fail(MOE_ESTATE, "moe_layer_step_noalloc: switch the launch timing off first (it may create events)");
+    // the kernels of this step take their scratch from the file-scope array: same kernels, other pointers
+    struct Swap {
+        moe_ctx *c; uint16_t *h, *a; float *y;
+        ~Swap() { c->h_buf = h; c->a_buf = a; c->yacc = y; }
+    } restore{c, c->h_buf, c->a_buf, c->yacc};
+    c->h_buf = reinterpret_cast<uint16_t *>(c->noalloc_scratch);
+    c->a_buf = reinterpret_cast<uint16_t *>(c->noalloc_scratch + NOALLOC_H_BYTES);
+    c->yacc = reinterpret_cast<float *>(c->noalloc_scratch + NOALLOC_H_BYTES + NOALLOC_A_BYTES);
+    return step_impl(l, next, x_in, batch, x_out, h_out, trace, true);
+} catch (...) {
+    return on_exception("moe_layer_step_noalloc");
 }
 
 extern "C" int32_t moe_layer_prefetch(moe_layer_t *l, const uint16_t *h_dev, int32_t batch, moe_step_trace_t *trace)
