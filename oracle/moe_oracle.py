@@ -19,7 +19,8 @@ What follows the paper, and where:
 * speculative loading: the next layer's gate applied to the hidden state the
   current layer's gate saw, fetching the 1-2 most likely experts into
   temporary buffers that replace nothing until used (Sec. 3.2, Sec. 3.3) --
-  `prefetch_scores`, `prefetch_guess`, `ExpertCacheSim.step`;
+  `prefetch_scores`, `prefetch_guess`, `ExpertCacheSim.step`; its recall measured in
+  isolation, 1, 2 and 10 layers ahead (Sec. 4.1) -- `speculative_recall`;
 * "expert recall" = fraction of needed experts already on the device (Sec. 4.1)
   -- `CacheStats.recall`.
 
@@ -230,6 +231,24 @@ def prefetch_scores(w_gate_next_f32: np.ndarray, h_f16: np.ndarray) -> np.ndarra
 def prefetch_guess(scores: np.ndarray, m: int) -> List[int]:
     """The m most likely next-layer experts, most likely first, ties to the lower index."""
     return top_k(list(scores), m)
+
+
+def speculative_recall(routing, h_f16: np.ndarray, gates: Sequence[np.ndarray], ahead: int, m: int) -> Tuple[int, int]:
+    """Speculative loading in isolation (Sec. 4.1, Fig. 2 right): for every token t and layer l, guess the experts
+    of layer l+ahead by applying THAT layer's gate to the hidden state layer l's gate saw, keep the m most likely,
+    and count how many of the experts layer l+ahead really selected were among them.
+
+    routing[t][l]: experts selected for token t at layer l; h_f16[t][l]: [H] gate input of layer l; gates[l]: [E,H].
+    Returns (guessed and needed, needed); the recall is their ratio, 1.0 when every active expert was guessed.
+    ahead = 0 guesses a layer from its own gate input, which finds min(m, K) of its K experts by construction."""
+    got = need = 0
+    for t in range(len(routing)):
+        for l in range(len(gates) - ahead):
+            guess = prefetch_guess(prefetch_scores(gates[l + ahead], h_f16[t][l]), m)
+            actual = routing[t][l + ahead]
+            got += len(set(guess) & set(actual))
+            need += len(actual)
+    return got, need
 
 
 # ----------------------------------------------------------------------------

@@ -268,3 +268,48 @@ def test_swap_placement_hand_worked_trace():
     assert (p.host_buf_of, p.spare) == ([-1, 0, 1, -1], 2)
     p.apply(sim.step(0, [[0, 3]])[0])          # both resident: nothing moves
     assert (p.host_buf_of, p.spare, p.writebacks) == ([-1, 0, 1, -1], 2, 3)
+
+
+# ------------------------------------------------------------------ speculative recall in isolation (Sec. 4.1)
+
+def test_speculative_recall_hand_worked_example():
+    """Three experts, width 2, three layers, two tokens, top-2; every logit worked out by hand (ties go to the
+    lower expert).  Guessing layer l+1 from layer l's input: the four guesses are, most likely first,
+    (2,1,0) (0,1,2) (0,2,1) (0,2,1) against the needed sets {1,2} {0,2} {0,2} {0,1}; two layers ahead:
+    (0,1,2) (2,1,0) against {0,2} {0,1}.  A routine that took the wrong layer's gate, the wrong layer's input
+    or the wrong layer's selection gives other counts."""
+    gates = [np.array(g, np.float32) for g in ([[1, 0], [0, 1], [-1, -1]], [[0, 1], [1, 0], [1, 1]], [[2, 0], [0, -1], [-1, 1]])]
+    h = np.array([[[1, 0.5], [0.5, -1], [-1, 2]], [[-2, 1], [1, 1], [0.5, 0.25]]], np.float16)
+    routing = [[O.route(gates[l], h[t][l], 2)[0] for l in range(3)] for t in range(2)]
+    assert routing == [[[0, 1], [1, 2], [2, 0]], [[1, 2], [2, 0], [0, 1]]]
+    assert O.speculative_recall(routing, h, gates, 1, 1) == (4, 8)
+    assert O.speculative_recall(routing, h, gates, 1, 2) == (6, 8)
+    assert O.speculative_recall(routing, h, gates, 1, 3) == (8, 8)
+    assert O.speculative_recall(routing, h, gates, 2, 1) == (1, 4)
+    assert O.speculative_recall(routing, h, gates, 2, 2) == (2, 4)
+    assert O.speculative_recall(routing, h, gates, 3, 2) == (0, 0)       # no layer that far ahead
+
+
+def test_speculative_recall_closed_forms():
+    """(i) zero layers ahead a layer is guessed from its own input: min(m, K) of its K experts are found;
+    (ii) guessing all E experts recalls everything at any distance; (iii) experts that output zero leave the
+    residual stream unchanged, so with one gate matrix shared by all layers (and no norm) every layer selects the
+    same experts and guessing K of them any number of layers ahead recalls everything."""
+    rng = np.random.default_rng(17)
+    T, L, E, H, K = 9, 5, 8, 32, 2
+    gates = [rng.normal(size=(E, H)).astype(np.float32) for _ in range(L)]
+    h = rng.normal(size=(T, L, H)).astype(np.float16)
+    routing = [[O.route(gates[l], h[t][l], K)[0] for l in range(L)] for t in range(T)]
+    for m in (1, 2, 3):
+        assert O.speculative_recall(routing, h, gates, 0, m) == (min(m, K) * T * L, K * T * L)
+    for a in (1, 2, 4):
+        assert O.speculative_recall(routing, h, gates, a, E) == (K * T * (L - a), K * T * (L - a))
+        got, need = O.speculative_recall(routing, h, gates, a, 2)
+        assert need == K * T * (L - a) and 0 <= got < need          # unrelated random gates: far from perfect
+        assert O.speculative_recall(routing, h, gates, a, 1)[0] <= got <= O.speculative_recall(routing, h, gates, a, 4)[0]
+    shared = [gates[0]] * L
+    x = rng.normal(size=(T, H)).astype(np.float16)
+    h_same = np.repeat(x[:, None, :], L, axis=1)                      # x_{l+1} = x_l + 0
+    routing_same = [[O.route(shared[l], h_same[t][l], K)[0] for l in range(L)] for t in range(T)]
+    for a in (1, 2, 4):
+        assert O.speculative_recall(routing_same, h_same, shared, a, K) == (K * T * (L - a), K * T * (L - a))
