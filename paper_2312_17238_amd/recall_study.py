@@ -9,6 +9,8 @@ size, Sec. 3.2), recording for every (token, layer) the routing decision and the
     replayed through the library's own cache bookkeeping in a context without a GPU;
   * recall of speculative loading (Sec. 3.2, Fig. 2 right): the gate of layer l+a applied to the gate input of
     layer l, a = 1, 2 and 10 layers ahead, guessing m = 1, 2 or 4 experts; recall = guessed and needed / needed.
+    The guesses are the library's own: moe_layer_prefetch(layer l+a, h_l) runs the gate kernel and the top-m
+    selection of the decode path and reports them most likely first, so the first m of four are the guess for m.
 
 Prints one JSON object.  Needs a GPU and the built library; imports nothing of the test infrastructure.
 """
@@ -31,7 +33,8 @@ from paper_2312_17238_amd.engine import Stack, layer_config  # noqa: E402
 
 
 def record(shape, formats, tokens: int, device: str):
-    """Routing [T][L][K] and gate inputs [T][L][H] (fp16, CPU) of a batch-1 run with all experts resident."""
+    """Routing [T][L][K] and gate inputs [T][L][H] (fp16, CPU) of a batch-1 run with all experts resident, and the
+    stack itself (for speculative_guesses; the caller closes it)."""
     gates = [W.gate_weight(shape.seed, l, shape.n_experts, shape.hidden) for l in range(shape.layers)]
     gamma = [W.rms_gamma(shape.hidden) for _ in range(shape.layers)] if shape.rms_eps > 0 else None
     cfgs = [layer_config(shape.hidden, shape.ffn, shape.n_experts, shape.top_k, formats[l][0], formats[l][1],
@@ -58,8 +61,26 @@ def record(shape, formats, tokens: int, device: str):
             row.append(tr.routing()[0])
             h_all[t, l] = hb[0].cpu()
         routing.append(row)
-    stack.close()
-    return routing, h_all, gates
+    return routing, h_all, gates, stack
+
+
+def speculative_guesses(stack: Stack, h_all: torch.Tensor, ahead: int, m_max: int = B.MOE_MAX_GUESS):
+    """guess[t][l] = the m_max most likely experts of layer l+ahead given the gate input of layer l, most likely
+    first, as moe_layer_prefetch decides them (every expert of the recording stack is resident, so nothing is
+    copied; the decision is reported all the same)."""
+    T, L = h_all.shape[0], h_all.shape[1]
+    for layer in stack.layers:
+        B.moe_layer_set_prefetch(layer, m_max)
+    h_dev = h_all.to(stack.device)
+    tr = B.StepTrace()
+    out = []
+    for t in range(T):
+        row = []
+        for l in range(L - ahead):
+            B.moe_layer_prefetch(stack.layers[l + ahead], h_dev[t, l].data_ptr(), 1, tr)
+            row.append([tr.guess_expert[i] for i in range(tr.n_guess)])
+        out.append(row)
+    return out
 
 
 def lru_hit_ratio(routing, n_layers: int, n_experts: int, top_k: int, k: int) -> float:
@@ -74,17 +95,15 @@ def lru_hit_ratio(routing, n_layers: int, n_experts: int, top_k: int, k: int) ->
     return tot["hits"] / max(1, tot["needed"])
 
 
-def speculative_recall(routing, h_all, gates, ahead: int, m: int) -> float:
-    T, L = h_all.shape[0], h_all.shape[1]
+def speculative_recall_counts(routing, guesses, ahead: int, m: int):
+    """(guessed and needed, needed) over all tokens and layers, for the first m of each guess list."""
     got = need = 0
-    for l in range(L - ahead):
-        scores = h_all[:, l].to(torch.float64) @ gates[l + ahead].to(torch.float64).T        # [T][E]; softmax keeps the order
-        guess = torch.topk(scores, m, dim=1).indices.tolist()
-        for t in range(T):
+    for t, row in enumerate(guesses):
+        for l, g in enumerate(row):
             s = set(routing[t][l + ahead])
-            got += len(s.intersection(guess[t]))
+            got += len(s.intersection(g[:m]))
             need += len(s)
-    return got / max(1, need)
+    return got, need
 
 
 def main() -> int:
@@ -97,13 +116,21 @@ def main() -> int:
         return 2
     shape = W.CONFIGS[args.workload]
     formats = W.layer_formats(shape)
-    routing, h_all, gates = record(shape, formats, args.tokens, "cuda:0")
+    routing, h_all, gates, stack = record(shape, formats, args.tokens, "cuda:0")
+    spec = {}
+    for a in (1, 2, 10):
+        if a >= shape.layers:
+            continue
+        guesses = speculative_guesses(stack, h_all, a)
+        spec[f"{a} ahead"] = {}
+        for m in (1, 2, 4):
+            got, need = speculative_recall_counts(routing, guesses, a, m)
+            spec[f"{a} ahead"][str(m)] = round(got / max(1, need), 4)
+    stack.close()
     out = {"workload": shape.name, "tokens": args.tokens, "layers": shape.layers, "experts": shape.n_experts, "top_k": shape.top_k,
            "lru_hit_ratio": {str(k): round(lru_hit_ratio(routing, shape.layers, shape.n_experts, shape.top_k, k), 4)
                              for k in range(shape.top_k, shape.n_experts + 1)},
-           "speculative_recall": {f"{a} ahead": {str(m): round(speculative_recall(routing, h_all, gates, a, m), 4)
-                                                 for m in (1, 2, 4)}
-                                  for a in (1, 2, 10) if a < shape.layers}}
+           "speculative_recall": spec}
     print(json.dumps(out), flush=True)
     return 0
 

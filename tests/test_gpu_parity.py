@@ -711,27 +711,45 @@ def test_profile_timeline_matches_profile_totals():
     model.close()
 
 
-def test_recall_study_tool_against_closed_forms():
+def test_recall_study_tool_against_closed_forms_and_oracle():
     """paper_2312_17238_amd.recall_study (the Fig. 2 analogue): on a small stack its LRU hit ratio for k = top_k = 2
-    equals the closed form sum_t |S_t & S_{t-1}| / needed, for k = E only the first touches miss, and guessing all
-    E experts recalls everything."""
+    equals the closed form sum_t |S_t & S_{t-1}| / needed, for k = E only the first touches miss; its speculative
+    guesses -- taken by the library's gate kernel and top-m selection through moe_layer_prefetch -- give, for every
+    (layers ahead, m) cell, exactly the integer counts of the oracle's definition (Sec. 4.1), and guessing all E
+    experts recalls everything."""
     from paper_2312_17238_amd import recall_study as R
-    shape = W.MoEShape("study", 3, 256, 512, 8, 2, 4, 64, 2, 2, 1e-5, 24, 1, "ar1", 5)
-    routing, h_all, gates = R.record(shape, W.layer_formats(shape), shape.tokens, "cuda:0")
+    shape = W.MoEShape("study", 5, 256, 512, 8, 2, 4, 64, 2, 2, 1e-5, 24, 1, "ar1", 5)
+    routing, h_all, gates, stack = R.record(shape, W.layer_formats(shape), shape.tokens, "cuda:0")
     T, L = shape.tokens, shape.layers
     assert len(routing) == T and all(len(r) == L and all(len(s) == 2 for s in r) for r in routing)
     closed = sum(len(set(routing[t][l]) & set(routing[t - 1][l])) for t in range(1, T) for l in range(L)) / (2 * T * L)
     assert abs(R.lru_hit_ratio(routing, L, 8, 2, 2) - closed) < 1e-12
     touched = sum(len({e for t in range(T) for e in routing[t][l]}) for l in range(L))
     assert abs(R.lru_hit_ratio(routing, L, 8, 2, 8) - (1 - touched / (2 * T * L))) < 1e-12
-    assert R.speculative_recall(routing, h_all, gates, 1, 8) == 1.0
-    r1, r2 = R.speculative_recall(routing, h_all, gates, 1, 1), R.speculative_recall(routing, h_all, gates, 1, 2)
-    assert 0.0 <= r1 <= 0.5 and r1 <= r2 <= 1.0
-    # the routing the tool recorded is the oracle's
-    for t in (0, T - 1):
+    # the routing and the gate inputs the tool recorded are the oracle's
+    gates_np, h_np = [g.numpy() for g in gates], h_all.numpy()
+    for t in range(T):
         for l in range(L):
-            idx, _, _ = O.route(gates[l].numpy(), h_all[t, l].numpy(), 2)
+            idx, _, _ = O.route(gates_np[l], h_np[t, l], 2)
             assert list(idx) == routing[t][l]
+    cells = {}
+    for ahead in (1, 2, 4):
+        guesses = R.speculative_guesses(stack, h_all, ahead)
+        assert all(len(g) == 4 for row in guesses for g in row)
+        for m in (1, 2, 4):
+            got = R.speculative_recall_counts(routing, guesses, ahead, m)
+            want = O.speculative_recall(routing, h_np, gates_np, ahead, m)
+            assert got == want, f"{ahead} layers ahead, m={m}: library {got}, oracle {want}"
+            cells[(ahead, m)] = got[0] / got[1]
+        assert cells[(ahead, 1)] <= 0.5 and cells[(ahead, 1)] <= cells[(ahead, 2)] <= cells[(ahead, 4)] <= 1.0
+    # all E experts guessed (the interface takes four guesses, so on a stack of four experts)
+    stack.close()
+    say(f"recall study: {cells}")
+    small = W.MoEShape("study4", 3, 256, 512, 4, 2, 4, 64, 2, 2, 1e-5, 8, 1, "ar1", 6)
+    routing, h_all, gates, stack = R.record(small, W.layer_formats(small), small.tokens, "cuda:0")
+    got = R.speculative_recall_counts(routing, R.speculative_guesses(stack, h_all, 1), 1, 4)
+    assert got == (2 * 8 * 2, 2 * 8 * 2) == O.speculative_recall(routing, h_all.numpy(), [g.numpy() for g in gates], 1, 4)
+    stack.close()
 
 
 @pytest.mark.parametrize("Bn,k,T,form", [(200, 4, 2, 3), (130, 2, 2, 1), (1000, 8, 1, 2), (1024, 2, 1, 3), (300, 4, 1, 2)])
