@@ -184,7 +184,11 @@ int32_t moe_layer_destroy(moe_layer_t *layer);
  * [out][in/group], groups along `in`; the stored weight is (code - zero) * scale (Sec. 4.2).
  * All host memory, read during the call only.  The library repacks into the expert's blob in the
  * pinned arena; with init_policy 1, experts 0..k-1 are also copied to their slots once complete (with
- * MOE_LAYER_SWAP they are packed in ordinary memory of the library's own and keep no host copy). */
+ * MOE_LAYER_SWAP they are packed in ordinary memory of the library's own and keep no host copy).
+ * Experts are loaded before the layer's first step: once the layer has taken part in moe_layer_step,
+ * moe_stack_step, moe_layer_resolve or moe_layer_prefetch (as the layer itself or as `next`), both load calls
+ * return MOE_ESTATE -- copies of the blob may be in flight and resident copies would go stale -- until
+ * moe_layer_reset, after which matrices may be loaded again (a matrix may be loaded more than once before that). */
 int32_t moe_layer_load_expert(moe_layer_t *layer, int32_t expert, int32_t matrix, const uint8_t *codes,
                               const uint16_t *scale_f16, const uint16_t *zero_f16);
 /* The same for a layer with two-level metadata (scale_group > 0).  scale_code, zero_code: one byte per group,

@@ -29,7 +29,8 @@ struct FfnArgs {
     FfnEntry e[MAX_ENTRIES];
     const uint16_t *h;              // [B][H] fp16 gate input
     uint16_t *a;                    // [B*K][F] fp16 SwiGLU activations
-    float *yacc;                    // [B][H] fp32 accumulators (cleared by the gate kernel)
+    float *ypart;                   // [B*K][H] fp32: row `pair` receives w * (W2^ a[pair]); k_combine adds a token's rows
+    uint32_t *ytab;                 // [B*K]: where k_combine finds the rows of each pair (y_rows below)
     int32_t H, F, group;
     int32_t scale_group;            // two-level metadata: groups per run of the second level (0: fp16 pairs)
     uint32_t stride13, meta13;      // w1/w3 row: stride and offset of the (scale, zero) pairs
@@ -422,8 +423,13 @@ __global__ __launch_bounds__(WAVES *WAVE) void k_w13(FfnArgs A)
     }
 }
 
-// K3: yacc[tok][r] += w * (W2^ a[pair])[r].  grid = (row blocks, entries); block = CS waves, wave cs owns
-// column chunk cs*64 + lane of every row of the block (G rows in flight); partial sums meet in LDS.
+// Entry of the table that tells k_combine where the contribution of one (token, expert) pair lies: `parts`
+// consecutive rows of the partial-output buffer starting at `row` (several when the contraction was split over blocks).
+__host__ __device__ __forceinline__ uint32_t y_rows(uint32_t row, uint32_t parts) { return row | (parts << 24); }
+
+// K3: ypart[pair][r] = w * (W2^ a[pair])[r].  grid = (row blocks, entries); block = CS waves, wave cs owns
+// column chunk cs*64 + lane of every row of the block (G rows in flight); partial sums meet in LDS.  No atomics:
+// every element of ypart has one writer, and k_combine adds the rows of a token in a fixed order.
 template <int BITS, int NT, int G>
 __global__ __launch_bounds__(512) void k_w2(FfnArgs A)
 {
@@ -471,19 +477,40 @@ __global__ __launch_bounds__(512) void k_w2(FfnArgs A)
         if (t < en.n_tok) {
             float s = 0.f;
             for (int k = 0; k < CS; ++k) s += red[i * CS + k];
-            atomicAdd(&A.yacc[(size_t)en.tok[t] * A.H + row0 + rr], en.w[t] * s);
+            A.ypart[(size_t)en.pair[t] * A.H + row0 + rr] = en.w[t] * s;
         }
     }
+    if (blockIdx.x == 0 && (int)threadIdx.x < en.n_tok) A.ytab[en.pair[threadIdx.x]] = y_rows((uint32_t)en.pair[threadIdx.x], 1u);
 }
 
-// x_out = fp16(x + yacc)
-__global__ void k_residual(const uint16_t *x, const float *yacc, uint16_t *x_out, int n)
+// S7 for steps that do not finish inside a w2 kernel: y[b] = sum over the token's K pairs, in selection order, of the
+// pair's rows of ypart (parts of a split contraction in ascending order); x_out = fp16(x + y); y is kept (fp32) for
+// diagnostics.  One thread per four elements; the order of the additions is fixed, so the result is reproducible
+// bit for bit whatever order the w2 blocks finished in.
+__global__ __launch_bounds__(256) void k_combine(const uint16_t *x, const float *ypart, const uint32_t *ytab, float *y, uint16_t *x_out,
+                                                 int H, int K, uint32_t cap_rows)
 {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) {
-        const float v = (float)__builtin_bit_cast(_Float16, x[i]) + yacc[i];
-        x_out[i] = __builtin_bit_cast(uint16_t, (_Float16)v);
+    const int b = blockIdx.y, i = (blockIdx.x * blockDim.x + threadIdx.x) * 4;
+    if (i >= H) return;
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int j = 0; j < K; ++j) {
+        const uint32_t t = ytab[b * K + j];
+        const uint32_t row = t & 0xffffffu, parts = t >> 24;
+        if (parts == 0 || row + parts > cap_rows) continue;      // an entry no kernel of this step wrote: never read outside the buffer
+        float4 s = *reinterpret_cast<const float4 *>(ypart + (size_t)row * H + i);
+        for (uint32_t p = 1; p < parts; ++p) {
+            const float4 v = *reinterpret_cast<const float4 *>(ypart + (size_t)(row + p) * H + i);
+            s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+        }
+        acc.x += s.x; acc.y += s.y; acc.z += s.z; acc.w += s.w;
     }
+    *reinterpret_cast<float4 *>(y + (size_t)b * H + i) = acc;
+    const uint2 xv = *reinterpret_cast<const uint2 *>(x + (size_t)b * H + i);
+    const _Float16 o0 = (_Float16)(lo_half(xv.x) + acc.x), o1 = (_Float16)(hi_half(xv.x) + acc.y);
+    const _Float16 o2 = (_Float16)(lo_half(xv.y) + acc.z), o3 = (_Float16)(hi_half(xv.y) + acc.w);
+    const uint2 ov = make_uint2((uint32_t)__builtin_bit_cast(uint16_t, o0) | (uint32_t)__builtin_bit_cast(uint16_t, o1) << 16,
+                                (uint32_t)__builtin_bit_cast(uint16_t, o2) | (uint32_t)__builtin_bit_cast(uint16_t, o3) << 16);
+    *reinterpret_cast<uint2 *>(x_out + (size_t)b * H + i) = ov;
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -8,7 +8,7 @@
 //
 // D layout of the 32x32 MFMA: lane l, register i  ->  row (token) m = 8*(i/4) + 4*(l/32) + i%4, column l%32.
 #pragma once
-#include "kernels_common.h"
+#include "kernels_gemv.h"
 
 namespace moe {
 
@@ -30,7 +30,8 @@ struct MfmaArgs {
     float w[MF_MAX_PAIRS];                   // combine weight of each pair
     const uint16_t *act;                     // w1/w3: h [B][H];   w2: a [B*K][F]
     uint16_t *a;                             // w1/w3 output
-    float *yacc;                             // w2 output (accumulated)
+    float *ypart;                            // w2 output: row `pair` of [B*K][H] fp32 (k_combine adds a token's rows)
+    uint32_t *ytab;                          // [B*K]: y_rows(pair, 1) for every pair of the launch
     int32_t K, N;                            // contraction length, output rows of the matrix
     uint32_t stride, meta_off;               // row stride and offset of the (scale, zero) pairs
     uint64_t mat_off;                        // byte offset of the matrix inside the blob
@@ -203,9 +204,10 @@ __global__ __launch_bounds__(MF2_WAVES *WAVE) void k_mfma_rows_q4(MfmaArgs A)
                     A.a[(size_t)A.pair[en.first + tok] * A.N + (mrow >> 1)] = __builtin_bit_cast(uint16_t, av);
                 }
             } else if (tok < en.n_tok && mrow < n_rows) {
-                atomicAdd(&A.yacc[(size_t)A.tok[en.first + tok] * A.N + mrow], A.w[en.first + tok] * v);
+                A.ypart[(size_t)A.pair[en.first + tok] * A.N + mrow] = A.w[en.first + tok] * v;
             }
         }
+    if (!W13 && blockIdx.x == 0 && tid < en.n_tok) A.ytab[A.pair[en.first + tid]] = y_rows(A.pair[en.first + tid], 1u);
 }
 
 }  // namespace moe

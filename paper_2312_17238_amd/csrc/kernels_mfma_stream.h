@@ -4,7 +4,8 @@
 //
 // Work item  = 128 consecutive MEMORY rows of one matrix of one (expert, token tile) entry, over one part of K
 //              (w1/w3, whose rows are interleaved in the blob, always take all of K: their epilogue needs the
-//              complete sums; w2 may split K, its result is accumulated with atomics anyway).
+//              complete sums; w2 may split K: every part writes a row of partial sums of its own, and k_combine adds
+//              the parts in ascending order, so no atomics and a result that does not depend on timing).
 // Step       = one segment of 8 groups (512 codes) of a work item: 128 rows x (256 B codes + 32 B pairs) = 36 KB.
 // Block      = 4 waves, two blocks per compute unit (their phases drift apart, so one block's loads overlap the
 //              other's arithmetic), each walking its items (blockIdx.x, +gridDim.x, ...) as one sequence of
@@ -73,7 +74,10 @@ struct TileArgs {
     float w[MF_MAX_PAIRS];
     const uint16_t *act;                     // w1/w3: h [B][H];   w2: a [B*K][F]
     uint16_t *a;                             // w1/w3 output
-    float *yacc;                             // w2 output (accumulated)
+    float *ypart;                            // w2 output: fp32 rows of H, one per pair (and per part of a split contraction)
+    uint32_t *ytab;                          // [pairs of the window]: where k_combine finds each pair's rows
+    int32_t part_base;                       // k_parts > 1: pair i of the launch (its index in tok[]/pair[]) owns rows part_base + i * k_parts + part
+    int32_t row_bias;                        // added to a row before it goes into ytab (ypart and ytab point at the window's first pair)
     int32_t K, N;                            // contraction length, output rows of the matrix
     uint32_t stride, meta_off;
     uint32_t meta2_off;                      // two-level metadata: byte offset of the per-run fp16 quads inside a row
@@ -361,12 +365,19 @@ __global__ __launch_bounds__(TL_THREADS, TL_BLOCKS_PER_CU) void k_mfma_stream_q4
         const int t = wv / (TL_WAVES / 2), i0 = (wv % (TL_WAVES / 2)) * TL_NI;   // tile of the round, first register
         int dst[TL_NI];
         float wgt[TL_NI];
+        const int part = s.it % A.k_parts;
 #pragma unroll
         for (int ii = 0; ii < TL_NI; ++ii) {
             const int i = i0 + ii;
             const int tk = en.first + min(8 * (i / 4) + 4 * kh + (i % 4), en.n_tok - 1);
-            dst[ii] = W13 ? l_pair[tk] : l_tok[tk];
+            // w1/w3: row of a; w2: row of ypart -- the pair's own, or its part's row when the contraction is split
+            dst[ii] = W13 ? l_pair[tk] : (A.k_parts == 1 ? (int)l_pair[tk] : A.part_base + tk * A.k_parts + part);
             wgt[ii] = W13 ? 0.f : l_w[tk];
+        }
+        if (!W13 && s.rb == 0 && part == 0 && tid < en.n_tok) {      // one block per entry tells k_combine where the rows are
+            const int tk = en.first + tid;
+            const int row = A.k_parts == 1 ? (int)l_pair[tk] : A.part_base + tk * A.k_parts;
+            A.ytab[l_pair[tk]] = y_rows((uint32_t)(row + A.row_bias), (uint32_t)A.k_parts);
         }
 #pragma unroll
         for (int round = 0; round < TL_RT / 2; ++round) {
@@ -392,7 +403,7 @@ __global__ __launch_bounds__(TL_THREADS, TL_BLOCKS_PER_CU) void k_mfma_stream_q4
                     if ((lane & 1) == 0 && tok < en.n_tok && mrow < n_rows)
                         A.a[(size_t)dst[ii] * A.N + (mrow >> 1)] = __builtin_bit_cast(uint16_t, (_Float16)silu_mul(v, other));
                 } else if (tok < en.n_tok && mrow < n_rows) {
-                    atomicAdd(&A.yacc[(size_t)dst[ii] * A.N + mrow], wgt[ii] * v);
+                    A.ypart[(size_t)dst[ii] * A.N + mrow] = wgt[ii] * v;
                 }
             }
         }

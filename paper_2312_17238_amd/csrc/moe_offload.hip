@@ -79,14 +79,16 @@ extern "C" int32_t moe_last_hip_error(void) { return g_hip_err; }
 // ---------------------------------------------------------------------------------------------
 
 // moe_layer_step_noalloc runs a step whose kernels keep their intermediate results (gate input h, SwiGLU
-// activations a, fp32 block output y) in this file-scope device array instead of the context's arena, for steps of
+// activations a, the pairs' fp32 partial outputs and the block output y) in this file-scope device array instead of the context's arena, for steps of
 // at most NOALLOC_MAX_BATCH tokens of layers no wider than the limits below.  Every GPU the library runs on holds its
 // own copy until the process ends; all calls on one GPU share it.
 constexpr int NOALLOC_MAX_BATCH = 4, NOALLOC_MAX_HIDDEN = 8192, NOALLOC_MAX_FFN = 16384, NOALLOC_MAX_TOPK = 4;
 constexpr size_t NOALLOC_H_BYTES = (size_t)NOALLOC_MAX_BATCH * NOALLOC_MAX_HIDDEN * 2;                    //  64 KB
 constexpr size_t NOALLOC_A_BYTES = (size_t)NOALLOC_MAX_BATCH * NOALLOC_MAX_TOPK * NOALLOC_MAX_FFN * 2;    // 512 KB
 constexpr size_t NOALLOC_Y_BYTES = (size_t)NOALLOC_MAX_BATCH * NOALLOC_MAX_HIDDEN * 4;                    // 128 KB
-constexpr size_t NOALLOC_BYTES = NOALLOC_H_BYTES + NOALLOC_A_BYTES + NOALLOC_Y_BYTES;
+constexpr size_t NOALLOC_YPART_BYTES = (size_t)NOALLOC_MAX_BATCH * NOALLOC_MAX_TOPK * NOALLOC_MAX_HIDDEN * 4;   // 512 KB: one row per (token, expert) pair
+constexpr size_t NOALLOC_YTAB_BYTES = 256;
+constexpr size_t NOALLOC_BYTES = NOALLOC_H_BYTES + NOALLOC_A_BYTES + NOALLOC_Y_BYTES + NOALLOC_YPART_BYTES + NOALLOC_YTAB_BYTES;
 static __device__ __align__(256) uint8_t scratch[NOALLOC_BYTES];
 
 // In host code the array's name is only a handle; its device address is asked for once per device, with that device
@@ -139,7 +141,15 @@ struct moe_ctx {
     std::vector<PoolBuf> bufs;          // [0, n_staging): staging; layers append their slots
     BufferPool pool;
     uint16_t *h_buf = nullptr, *a_buf = nullptr, *xbuf[2] = {nullptr, nullptr};
-    float *yacc = nullptr;
+    float *yacc = nullptr;              // [B][H] fp32 block output of the last step (before the residual add)
+    // Steps that do not finish inside a w2 kernel: every (token, expert) pair's weighted output goes to a row of its
+    // own in ypart (rows [0, B*K): row = pair), k_combine adds a token's rows in selection order.  A matrix-core w2
+    // launch that splits its contraction over blocks takes one row per (pair, part) from the rows behind those, as
+    // long as they last; ytab[pair] tells k_combine where a pair's rows are.
+    float *ypart = nullptr;
+    uint32_t *ytab = nullptr;
+    uint64_t ypart_extra_floats = 0;    // capacity behind the first B*K rows
+    uint64_t ypart_extra_used = 0;      // floats of it taken by the launches of the current step
     uint8_t *noalloc_scratch = nullptr; // this device's copy of the file-scope scratch array (moe_layer_step_noalloc)
     GateHostOut *gate_out = nullptr;    // host pointer
     GateHostOut *gate_out_dev = nullptr;// the same memory as the device sees it
@@ -194,6 +204,7 @@ struct moe_layer {
     std::vector<int32_t> host_writer;   // per host buffer: pool buffer whose `drained` event covers its last write, or -1
     std::vector<std::vector<uint8_t>> pack_tmp;   // swap mode: experts 0..k-1 are packed here until they move to the device
     uint64_t steps_device_routed = 0;   // steps enqueued without waiting for their gate
+    bool stepped = false;               // the layer has taken part in a step since it was created or reset: its blobs may be in flight
 };
 
 static int32_t fold_pending(moe_ctx *c);   // bookkeeping of device-routed steps; every reader of cache state calls it first
@@ -223,7 +234,7 @@ static bool layer_cfg_ok(const moe_layer_config_t *c)
            c->scale_group >= 0 && blob_layout(c->hidden, c->ffn, c->bits, c->group, c->scale_group).ok;
 }
 
-struct ScratchPlan { uint64_t staging, h, a, yacc, x0, x1, barrier, route, route_log, total; };
+struct ScratchPlan { uint64_t staging, h, a, yacc, ypart, ytab, ypart_extra_floats, x0, x1, barrier, route, route_log, total; };
 
 static ScratchPlan plan_scratch(const moe_ctx_config_t *c)
 {
@@ -234,6 +245,10 @@ static ScratchPlan plan_scratch(const moe_ctx_config_t *c)
     p.h = off;    off += align_u64((uint64_t)c->max_batch * c->max_hidden * 2, 256);
     p.a = off;    off += align_u64((uint64_t)c->max_batch * c->max_top_k * c->max_ffn * 2, 256);
     p.yacc = off; off += align_u64((uint64_t)c->max_batch * c->max_hidden * 4, 256);
+    const uint64_t pairs = (uint64_t)c->max_batch * c->max_top_k;
+    p.ypart_extra_floats = std::min<uint64_t>(2048, 16 * pairs) * c->max_hidden;
+    p.ypart = off; off += align_u64((pairs * c->max_hidden + p.ypart_extra_floats) * 4, 256);
+    p.ytab = off; off += align_u64(pairs * 4, 256);
     p.x0 = off;   off += align_u64((uint64_t)c->max_batch * c->max_hidden * 2, 256);
     p.x1 = off;   off += align_u64((uint64_t)c->max_batch * c->max_hidden * 2, 256);
     p.barrier = off; off += 4096;     // one flag per block of the persistent kernel (at most 1024 compute units)
@@ -323,6 +338,9 @@ try {
     c->h_buf = reinterpret_cast<uint16_t *>(base + p.h);
     c->a_buf = reinterpret_cast<uint16_t *>(base + p.a);
     c->yacc = reinterpret_cast<float *>(base + p.yacc);
+    c->ypart = reinterpret_cast<float *>(base + p.ypart);
+    c->ytab = reinterpret_cast<uint32_t *>(base + p.ytab);
+    c->ypart_extra_floats = p.ypart_extra_floats;
     c->xbuf[0] = reinterpret_cast<uint16_t *>(base + p.x0);
     c->xbuf[1] = reinterpret_cast<uint16_t *>(base + p.x1);
     c->barrier = reinterpret_cast<uint32_t *>(base + p.barrier);
@@ -539,6 +557,9 @@ static int32_t load_matrix(moe_layer *l, int32_t expert, int32_t matrix, const u
 {
     if (expert < 0 || expert >= l->cfg.n_experts || matrix < 0 || matrix > 2)
         return fail(MOE_EINVAL, "moe_layer_load_expert: expert %d / matrix %d out of range", expert, matrix);
+    // Once a layer has stepped, copies of its blobs may be in flight, resident copies would go stale, and in swap
+    // mode an expert on the device has no host buffer to pack into: loading ends with the first step.
+    if (l->stepped) return fail(MOE_ESTATE, "moe_layer_load_expert: the layer has already taken part in a step; experts are loaded before the first step (or after moe_layer_reset)");
     const BlobLayout &b = l->lay;
     const MatLayout &m = mat_of(b, matrix);
     if (l->swap && expert < l->cfg.cache_slots) {
@@ -548,6 +569,7 @@ static int32_t load_matrix(moe_layer *l, int32_t expert, int32_t matrix, const u
         }
     }
     uint8_t *blob = host_blob(l, expert);
+    if (!blob) return fail(MOE_ESTATE, "moe_layer_load_expert: expert %d has no host buffer to be packed into", expert);
     const uint32_t qmax = (1u << b.bits) - 1;
     const unsigned hw = std::max(1u, std::min(16u, std::thread::hardware_concurrency()));
     const unsigned nthreads = (uint64_t)m.rows * m.cols < (1u << 20) ? 1 : hw;
@@ -993,6 +1015,8 @@ try {
     StepPlan plan;
     rc = plan_step(l, next, expert_idx, batch, guess_score, trace, plan);
     if (rc) return rc;
+    l->stepped = true;
+    if (next) next->stepped = true;
     if (!l->ctx->host_only) {
         for (int i = 0; i < (int)plan.access.size(); ++i) { rc = issue_access_transfers(l->ctx, l, plan, i); if (rc) return rc; }
         for (const CopyOp &op : plan.spec) { rc = issue_copy(l->ctx, next, op); if (rc) return rc; }
@@ -1147,7 +1171,7 @@ static int32_t launch_ffn_fmt(moe_layer *l, const std::vector<FfnEntry> &entries
         const int n = (int)std::min<size_t>(MAX_ENTRIES, entries.size() - first);
         FfnArgs A{};
         for (int i = 0; i < n; ++i) A.e[i] = entries[first + i];
-        A.h = c->h_buf; A.a = c->a_buf; A.yacc = c->yacc;
+        A.h = c->h_buf; A.a = c->a_buf; A.ypart = c->ypart; A.ytab = c->ytab;
         A.H = b.hidden; A.F = b.ffn; A.group = b.group; A.scale_group = b.scale_group;
         A.stride13 = b.m13.row_stride; A.meta13 = b.m13.meta_off;
         A.stride2 = b.m2.row_stride; A.meta2 = b.m2.meta_off;
@@ -1290,7 +1314,12 @@ static int32_t launch_mfma_stream(moe_layer *l, const std::vector<PassExpert> &e
             const int n_seg = (Kdim / 64 + TL_SG - 1) / TL_SG;
             A.row_blocks = (rows + TL_ROWS - 1) / TL_ROWS;
             int parts = 1;
-            if (may_split) parts = std::min(n_seg, std::max(1, (2 * n_cu + n * A.row_blocks - 1) / (n * A.row_blocks)));
+            if (may_split) {
+                // a part per block that would otherwise idle, as far as the rows for the parts' partial sums last
+                parts = std::min(n_seg, std::max(1, (2 * n_cu + n * A.row_blocks - 1) / (n * A.row_blocks)));
+                const uint64_t left = (c->ypart_extra_floats - c->ypart_extra_used) / ((uint64_t)first * b.hidden);
+                parts = (int)std::max<uint64_t>(1, std::min<uint64_t>((uint64_t)std::min(parts, 255), left));
+            }
             A.seg_per_part = (n_seg + parts - 1) / parts;
             A.k_parts = (n_seg + A.seg_per_part - 1) / A.seg_per_part;       // no empty part
             A.n_items = n * A.row_blocks * A.k_parts;
@@ -1299,7 +1328,8 @@ static int32_t launch_mfma_stream(moe_layer *l, const std::vector<PassExpert> &e
         // algorithmic bytes: every distinct expert of the launch once (a second token tile reads it again)
         const uint64_t bytes13 = (uint64_t)n_distinct * 2 * b.ffn * b.m13.row_stride, bytes2 = (uint64_t)n_distinct * b.hidden * b.m2.row_stride;
         uint16_t *a_win = c->a_buf + (size_t)w0 * K * b.ffn;
-        A.a = a_win; A.yacc = c->yacc + (size_t)w0 * b.hidden;
+        A.a = a_win;
+        A.ypart = c->ypart + (size_t)w0 * K * b.hidden; A.ytab = c->ytab + (size_t)w0 * K; A.row_bias = w0 * K;
         A.act = c->h_buf + (size_t)w0 * b.hidden;
         const bool meta8 = b.scale_group > 0;
         const bool r1 = c->mfma_form == 3 && !meta8 && !l->wide_meta.load(std::memory_order_relaxed);
@@ -1315,6 +1345,10 @@ static int32_t launch_mfma_stream(moe_layer *l, const std::vector<PassExpert> &e
         A.K = b.ffn; A.N = b.hidden; A.stride = b.m2.row_stride; A.meta_off = b.m2.meta_off; A.mat_off = b.off_w2;
         A.meta2_off = b.m2.meta2_off; A.run_shift = run_shift(b.m2);
         const dim3 g2 = shape(b.hidden, b.ffn, true);
+        if (A.k_parts > 1) {        // rows behind the pairs' own, counted from the window's first pair
+            A.part_base = (int32_t)((uint64_t)batch * K + c->ypart_extra_used / b.hidden) - w0 * K;
+            c->ypart_extra_used += (uint64_t)first * A.k_parts * b.hidden;
+        }
         rc = meta8 ? launch_timed(c, PROF_W2, bytes2, k_mfma_stream_q4<false, true>, g2, dim3(TL_THREADS), TL_LDS_BYTES, A)
              : r1  ? launch_timed(c, PROF_W2, bytes2, k_mfma_stream_q4<false, false, true>, g2, dim3(TL_THREADS), TL_LDS_BYTES, A)
                    : launch_timed(c, PROF_W2, bytes2, k_mfma_stream_q4<false, false>, g2, dim3(TL_THREADS), TL_LDS_BYTES, A);
@@ -1346,7 +1380,7 @@ static int32_t launch_mfma(moe_layer *l, const std::vector<PassExpert> &experts,
         ++n;
     }
     const uint64_t bytes13 = (uint64_t)n * 2 * b.ffn * b.m13.row_stride, bytes2 = (uint64_t)n * b.hidden * b.m2.row_stride;
-    A.act = c->h_buf; A.a = c->a_buf; A.yacc = c->yacc;
+    A.act = c->h_buf; A.a = c->a_buf; A.ypart = c->ypart; A.ytab = c->ytab;
     A.K = b.hidden; A.N = b.ffn; A.stride = b.m13.row_stride; A.meta_off = b.m13.meta_off; A.mat_off = b.off_w13;
     // LDS: 32 staged rows (codes + pairs) or the final reduction buffer
     auto rows_lds = [&](int Kdim, int mt) {
@@ -1463,7 +1497,7 @@ static int32_t device_routed_step(moe_layer *l, const uint16_t *x_in, uint16_t *
     // a log slot is free once its step has been folded: with fewer than ROUTE_LOG steps pending the oldest slots are
     uint32_t slot = c->pending.empty() ? 0 : (c->pending.back().slot + 1) % moe_ctx::ROUTE_LOG;
     GateArgs ga{};
-    ga.x = x_in; ga.wg = l->gate_w_dev; ga.gamma = l->gamma_dev; ga.h_out = c->h_buf; ga.h_out2 = h_out; ga.yacc = c->yacc;
+    ga.x = x_in; ga.wg = l->gate_w_dev; ga.gamma = l->gamma_dev; ga.h_out = c->h_buf; ga.h_out2 = h_out;
     ga.out = c->gate_out_dev; ga.eps = (double)cf.rms_eps; ga.H = cf.hidden; ga.E = cf.n_experts; ga.K = cf.top_k;
     ga.route_idx = c->route_idx; ga.route_w = c->route_w; ga.route_log = c->route_log_dev + (size_t)slot * MOE_MAX_TOPK;
     int32_t rc = launch_timed(c, PROF_GATE, 0, k_gate<false>, dim3(1), dim3(GATE_THREADS), 0, ga);
@@ -1505,13 +1539,15 @@ static int32_t step_impl(moe_layer *l, moe_layer *next, const uint16_t *x_in, in
     const moe_layer_config_t &cf = l->cfg;
     const bool spec = next && next->cfg.prefetch_m > 0 && c->cfg.n_staging > 0;
     if (spec && !all_loaded(next)) return fail(MOE_ESTATE, "moe_layer_step: next layer not fully loaded");
+    l->stepped = true;
+    if (spec) next->stepped = true;
     if (!plain && device_routed_step_fits(l, next, batch, trace, spec)) return device_routed_step(l, x_in, x_out, h_out);
     rc = fold_pending(c);
     if (rc) return rc;
 
     GateArgs ga{};
     ga.x = x_in; ga.wg = l->gate_w_dev; ga.wg2 = spec ? next->gate_w_dev : nullptr;
-    ga.gamma = l->gamma_dev; ga.h_out = c->h_buf; ga.h_out2 = h_out; ga.yacc = c->yacc; ga.out = c->gate_out_dev;
+    ga.gamma = l->gamma_dev; ga.h_out = c->h_buf; ga.h_out2 = h_out; ga.out = c->gate_out_dev;
     ga.eps = (double)cf.rms_eps; ga.H = cf.hidden; ga.E = cf.n_experts; ga.E2 = spec ? next->cfg.n_experts : 0; ga.K = cf.top_k;
     rc = launch_gate(c, ga, batch);
     if (rc) return rc;
@@ -1528,6 +1564,7 @@ static int32_t step_impl(moe_layer *l, moe_layer *next, const uint16_t *x_in, in
     StepPlan plan;
     rc = plan_step(l, next, idx, batch, spec ? score : nullptr, trace, plan);
     if (rc) return rc;
+    c->ypart_extra_used = 0;
     if (trace) {
         for (int i = 0; i < batch * cf.top_k; ++i) trace->expert_w[i] = w[i];
         for (int i = 0; i < batch * cf.n_experts; ++i) trace->logits[i] = go->logits[i];
@@ -1713,9 +1750,10 @@ static int32_t step_impl(moe_layer *l, moe_layer *next, const uint16_t *x_in, in
         HIPCHK(hipStreamWaitEvent(c->copy, c->ev_compute, 0));
         for (const CopyOp &op : plan.spec) { rc = issue_copy(c, next, op); if (rc) return rc; }
     }
-    if (!fused_done) {
-        const int n = batch * cf.hidden;
-        hipLaunchKernelGGL(k_residual, dim3((n + 255) / 256), dim3(256), 0, c->compute, x_in, c->yacc, x_out, n);
+    if (!fused_done) {      // S7: the pairs' rows added per token in a fixed order, then the residual
+        const uint64_t cap_rows = ((uint64_t)batch * cf.top_k * cf.hidden + c->ypart_extra_floats) / cf.hidden;
+        hipLaunchKernelGGL(k_combine, dim3((cf.hidden / 4 + 255) / 256, batch), dim3(256), 0, c->compute, x_in, c->ypart, c->ytab, c->yacc,
+                           x_out, cf.hidden, cf.top_k, (uint32_t)cap_rows);
         HIPCHK(hipGetLastError());
     }
     return MOE_OK;
@@ -1742,12 +1780,16 @@ try {
     if (c->prof.on) return fail(MOE_ESTATE, "moe_layer_step_noalloc: switch the launch timing off first (it may create events)");
     // the kernels of this step take their scratch from the file-scope array: same kernels, other pointers
     struct Swap {
-        moe_ctx *c; uint16_t *h, *a; float *y;
-        ~Swap() { c->h_buf = h; c->a_buf = a; c->yacc = y; }
-    } restore{c, c->h_buf, c->a_buf, c->yacc};
-    c->h_buf = reinterpret_cast<uint16_t *>(c->noalloc_scratch);
-    c->a_buf = reinterpret_cast<uint16_t *>(c->noalloc_scratch + NOALLOC_H_BYTES);
-    c->yacc = reinterpret_cast<float *>(c->noalloc_scratch + NOALLOC_H_BYTES + NOALLOC_A_BYTES);
+        moe_ctx *c; uint16_t *h, *a; float *y, *yp; uint32_t *yt; uint64_t extra;
+        ~Swap() { c->h_buf = h; c->a_buf = a; c->yacc = y; c->ypart = yp; c->ytab = yt; c->ypart_extra_floats = extra; }
+    } restore{c, c->h_buf, c->a_buf, c->yacc, c->ypart, c->ytab, c->ypart_extra_floats};
+    uint8_t *s = c->noalloc_scratch;
+    c->h_buf = reinterpret_cast<uint16_t *>(s); s += NOALLOC_H_BYTES;
+    c->a_buf = reinterpret_cast<uint16_t *>(s); s += NOALLOC_A_BYTES;
+    c->yacc = reinterpret_cast<float *>(s); s += NOALLOC_Y_BYTES;
+    c->ypart = reinterpret_cast<float *>(s); s += NOALLOC_YPART_BYTES;
+    c->ytab = reinterpret_cast<uint32_t *>(s);
+    c->ypart_extra_floats = 0;          // a matrix-core w2 launch of such a step does not split its contraction
     return step_impl(l, next, x_in, batch, x_out, h_out, trace, true);
 } catch (...) {
     return on_exception("moe_layer_step_noalloc");
@@ -1765,6 +1807,7 @@ try {
     if (l->cfg.prefetch_m <= 0 || c->cfg.n_staging <= 0) return MOE_OK;
     rc = fold_pending(c);
     if (rc) return rc;
+    l->stepped = true;
     GateArgs ga{};
     ga.x = h_dev; ga.wg2 = l->gate_w_dev; ga.out = c->gate_out_dev; ga.eps = 0.0; ga.H = l->cfg.hidden;
     ga.E2 = l->cfg.n_experts; ga.K = l->cfg.top_k;
@@ -1877,6 +1920,7 @@ try {
     l->own_bufs = l->cache.slot_buf;
     for (int32_t b : l->own_bufs) c->bufs[b].pending = false;
     cache_init(l);
+    l->stepped = false;                 // both streams are idle and nothing is resident: experts may be loaded again
     if (l->cfg.init_policy == 1)
         for (int e = 0; e < l->cfg.cache_slots; ++e)
             if (l->loaded[e] == 7u) { int32_t rc = warm_fill(l, e); if (rc) return rc; }

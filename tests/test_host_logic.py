@@ -299,6 +299,36 @@ def expect(code, fn, *args):
     assert ei.value.code == code, ei.value
 
 
+@pytest.mark.parametrize("swap", [False, True])
+def test_experts_cannot_be_loaded_once_the_layer_has_stepped(swap):
+    """After the first step copies of a blob may be in flight and, in swap mode, an expert that sits on the device
+    has no host buffer to be packed into (this used to write through a null pointer): both load calls answer
+    MOE_ESTATE from then on, for the stepping layer and for the layer it guessed for; a reset opens loading again."""
+    H, F, E, k = 64, 64, 4, 2
+    flags = B.MOE_LAYER_SWAP if swap else 0
+    st = Stack([layer_config(H, F, E, 2, 4, 64, k, 2, 0.0, 1 if swap else 0, flags)] * 2, [torch.zeros(E, H)] * 2, host_only=True)
+    q = np.zeros((64, 64), np.uint8); s = np.ones((64, 1), np.float16); z = np.zeros((64, 1), np.float16)
+    load = lambda l, e, m: B.moe_layer_load_expert(st.layers[l], e, m, q.ctypes.data, s.ctypes.data, z.ctypes.data)
+    for l in range(2):
+        for e in range(E):
+            for m in range(3):
+                load(l, e, m)
+    if not swap:
+        load(0, 1, 2)                                   # a second time before any step: allowed
+    else:
+        expect(B.MOE_ESTATE, load, 0, 0, 0)             # swap mode: expert 0 has moved to the device for good
+    B.moe_layer_resolve(st.layers[0], st.layers[1], [2, 3], 1, [0.1, 0.2, 0.3, 0.4])
+    for l in range(2):                                  # layer 1 was only guessed for: its blobs may be in flight too
+        for e in (0, 3):
+            expect(B.MOE_ESTATE, load, l, e, 1)
+    assert "step" in B.lib().moe_last_error().decode()
+    if not swap:
+        B.moe_layer_reset(st.layers[0])
+        load(0, 3, 1)
+        expect(B.MOE_ESTATE, load, 1, 3, 1)
+    st.close()
+
+
 def test_error_codes():
     cc = B.CtxConfig(4, 1, 64, 64, 2, B.MOE_CTX_HOST_ONLY, 1 << 16)
     expect(B.MOE_EINVAL, B.moe_ctx_create, B.CtxConfig(4, 0, 64, 64, 2, 1, 1 << 16), None, 0, None, None)

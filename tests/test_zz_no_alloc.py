@@ -43,7 +43,7 @@ def step_both(ref: Model, sut: Model, l: int, x: torch.Tensor, tag: str):
     return outs[1]
 
 
-@pytest.mark.parametrize("formats,K,k", [([(4, 64), (4, 64)], 2, 2), ([(3, 64), (2, 16)], 2, 4)])
+@pytest.mark.parametrize("formats,K,k", [([(4, 64), (4, 64)], 2, 2), ([(3, 64), (2, 16)], 2, 4), ([(4, 64), (4, 64)], 4, 4)])
 def test_noalloc_step_matches_step_on_two_calls_in_a_row(formats, K, k):
     L, H, F, E = 2, 512, 1024, 8
     ref = Model(L, H, F, E, K, formats, k, 2, 1e-5, max_batch=4, seed=101)
