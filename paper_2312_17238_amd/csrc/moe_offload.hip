@@ -150,6 +150,7 @@ struct moe_ctx {
     uint32_t *ytab = nullptr;
     uint64_t ypart_extra_floats = 0;    // capacity behind the first B*K rows
     uint64_t ypart_extra_used = 0;      // floats of it taken by the launches of the current step
+    std::vector<int32_t> w2_parts;      // per window of the current step: parts the matrix-core w2 launches split their contraction into
     uint8_t *noalloc_scratch = nullptr; // this device's copy of the file-scope scratch array (moe_layer_step_noalloc)
     GateHostOut *gate_out = nullptr;    // host pointer
     GateHostOut *gate_out_dev = nullptr;// the same memory as the device sees it
@@ -1315,10 +1316,11 @@ static int32_t launch_mfma_stream(moe_layer *l, const std::vector<PassExpert> &e
             A.row_blocks = (rows + TL_ROWS - 1) / TL_ROWS;
             int parts = 1;
             if (may_split) {
-                // a part per block that would otherwise idle, as far as the rows for the parts' partial sums last
-                parts = std::min(n_seg, std::max(1, (2 * n_cu + n * A.row_blocks - 1) / (n * A.row_blocks)));
+                // the step fixed the number of parts per window from its routing alone; the rows for the parts'
+                // partial sums were budgeted there, the check below only guards the buffer
+                parts = std::min(n_seg, std::max<int>(1, c->w2_parts.at(w0 / window)));
                 const uint64_t left = (c->ypart_extra_floats - c->ypart_extra_used) / ((uint64_t)first * b.hidden);
-                parts = (int)std::max<uint64_t>(1, std::min<uint64_t>((uint64_t)std::min(parts, 255), left));
+                if (parts > 1 && (uint64_t)parts > left) parts = 1;
             }
             A.seg_per_part = (n_seg + parts - 1) / parts;
             A.k_parts = (n_seg + A.seg_per_part - 1) / A.seg_per_part;       // no empty part
@@ -1599,6 +1601,26 @@ static int32_t step_impl(moe_layer *l, moe_layer *next, const uint16_t *x_in, in
     // two-level metadata: a step of the streaming kernel stages one run's quad per row, so a run must cover the step
     auto runs_ok = [&](const MatLayout &m) { return m.run_len == 0 || m.run_len == m.cols / (uint32_t)cf.group || m.run_len % TL_SG == 0; };
     const bool use_mfma = batch >= c->mfma_min_batch && cf.bits == 4 && cf.group == 64 && runs_ok(l->lay.m13) && runs_ok(l->lay.m2);
+    if (use_mfma) {
+        // How many parts the w2 launches of a window split their contraction into decides the order in which a
+        // pair's partial sums are added, so it must not depend on how the step's experts happen to be grouped into
+        // launches (which follows from what is cached, in which buffers): it is fixed here from the routing alone,
+        // as if all needed experts of the window ran in one launch -- one part per block that would idle then --
+        // within the rows the partial sums have.  A step's result is then the same whatever the cache held.
+        const int window = MF_MAX_PAIRS / cf.top_k, n_cu = c->n_cu > 0 ? c->n_cu : 256;
+        const int row_blocks = (cf.hidden + TL_ROWS - 1) / TL_ROWS;
+        const uint64_t extra_rows = c->ypart_extra_floats / cf.hidden, pairs = (uint64_t)batch * cf.top_k;
+        const int max_parts = (int)std::min<uint64_t>(255, std::max<uint64_t>(1, extra_rows / pairs));
+        c->w2_parts.clear();
+        for (int w0 = 0; w0 < batch; w0 += window) {
+            const int w1 = std::min(batch, w0 + window);
+            int count[MOE_MAX_EXPERTS] = {0}, entries = 0;
+            for (int q = w0 * cf.top_k; q < w1 * cf.top_k; ++q) count[idx[q]]++;
+            for (int e = 0; e < cf.n_experts; ++e) entries += (count[e] + 31) / 32;
+            const int want = std::max(1, (2 * n_cu + entries * row_blocks - 1) / std::max(1, entries * row_blocks));
+            c->w2_parts.push_back(std::min(want, max_parts));
+        }
+    }
     auto pass_expert = [&](int i) {
         PassExpert pe;
         pe.blob = c->bufs[plan.access[i].buf].ptr;

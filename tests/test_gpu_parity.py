@@ -880,3 +880,43 @@ def test_block_output_is_reproducible_bit_for_bit(E, K, k, Bn, path):
             assert (ya.view(np.uint32) == yb.view(np.uint32)).all() and (xa.view(np.uint16) == xb.view(np.uint16)).all()
     for model in models:
         model.close()
+
+
+@pytest.mark.parametrize("H,F,k,Bn,path", [(256, 1024, 4, 16, "matrix"), (256, 1024, 8, 48, "matrix"), (1024, 2048, 4, 16, "matrix"),
+                                           (256, 1024, 4, 6, "gemv"), (256, 1024, 2, 1, "gemv")])
+def test_block_output_does_not_depend_on_what_the_cache_held(H, F, k, Bn, path):
+    """Sec. 3.2: caching and speculative loading change no prediction.  Here that holds to the last bit: the same
+    tokens give the same fp32 y from a cold cache (every expert arrives during the step, one launch per arrival or
+    several passes), from a warm one (resident experts first, in one launch), after a reset (the experts land in
+    other buffers, which groups the launches differently) and with speculative loading on or off."""
+    L, E, K = 2, 8, 2
+    xs = W.hidden_ar1(137, 2, Bn, H)
+    model = Model(L, H, F, E, K, None, k, 2, 1e-5, max_batch=Bn, seed=137, keep_layers=[])
+    B.moe_ctx_set_option(model.stack.ctx, "mfma_min_batch", 16 if path == "matrix" else 1000)
+    dev = model.stack.device
+    x_in = [xs[t].to(dev) for t in range(2)]
+    def run():
+        ys = []
+        for t in (0, 1, 0, 1):                      # the second visit of a token finds the cache warm
+            xa, xb2 = torch.empty(Bn, H, dtype=torch.float16, device=dev), torch.empty(Bn, H, dtype=torch.float16, device=dev)
+            model.stack.step_layer(0, x_in[t], xa, None, B.StepTrace())
+            model.stack.synchronize()
+            y0 = model.stack.read_y(Bn, H).copy()
+            model.stack.step_layer(1, xa, xb2, None, None)
+            model.stack.synchronize()
+            ys.append((y0, model.stack.read_y(Bn, H).copy()))
+        return ys
+    first = run()
+    for a, b in ((0, 2), (1, 3)):
+        for l in range(2):
+            assert (first[a][l].view(np.uint32) == first[b][l].view(np.uint32)).all(), f"cold and warm differ, token {a} layer {l}"
+    model.stack.reset()
+    again = run()
+    model.stack.reset()
+    model.stack.set_prefetch(0)
+    without = run()
+    for other, what in ((again, "after a reset"), (without, "without speculative loading")):
+        for i in range(4):
+            for l in range(2):
+                assert (first[i][l].view(np.uint32) == other[i][l].view(np.uint32)).all(), f"{what}: visit {i} layer {l} differs"
+    model.close()
