@@ -6,8 +6,12 @@ RMSNorm + gate + top-2, LRU cache resolve, demand copies of missed experts from 
 speculative prefetch for the next layer, fused dequant-GEMV expert FFN, combine + residual.
 
 Prints ONE JSON line: metric = decode tokens/s of the whole job, plus
-  roofline      -- the dominant kernel (the w1/w3 fused dequant-GEMV) against MI355X's 8 TB/s HBM peak:
-                   algorithmic bytes per launch / average launch duration (HIP events on the compute stream);
+  roofline      -- the fused dequant-GEMV as a whole (w1,w3 -> SiLU*mul -> w2 -> combine: both of its kernels, the
+                   bytes of both over the sum of their durations) against MI355X's 8 TB/s HBM peak; algorithmic bytes
+                   per launch / average launch duration (HIP events on the compute stream); roofline_w13 and
+                   roofline_w2 give the two kernels one by one;
+  ablations     -- the same workload, fewer steps, with whole-expert speculative loads (the paper's literal
+                   algorithm; the headline run moves a 4 MiB head first) and without speculative loading;
   cpu_baseline  -- the CPU oracle timed on the host cores on a bounded sample of the same workload.
 All inputs are synthetic and seeded (see workload/); hidden states are resident in HBM before timing.
 """
@@ -27,7 +31,8 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 # workload and launch shape only (4-bit g64 Mixtral experts, batch 1): FETCH_SIZE and WRITE_SIZE of two
 # rocprofv3 --pmc runs, scaled by the copy probe; see profiles/hbm_traffic_gemv_kernels_4bit.md
 PMC_TRAFFIC_W13_4BIT_B1 = 132_465_708
-PMC_TRAFFIC_FFN_4BIT_B1 = None   # filled from profiles/ once the counters of the fused kernel are collected
+PMC_TRAFFIC_W2_4BIT_B1 = 67_301_016     # k_w2_token: 67,276,440 B read + 24,576 B written
+PMC_TRAFFIC_FFN_4BIT_B1 = None   # the one-launch kernels are not the default; their counters were not collected
 LINK_PEAK_GBS = 64.0           # PCIe Gen5 x16, one direction, nominal
 
 
@@ -113,9 +118,12 @@ def main() -> int:
     ap.add_argument("--spec-head-mb", type=int, default=4,
                     help="speculative loads copy only the first N MiB until the guess is confirmed (0: whole expert, as in the paper)")
     ap.add_argument("--mfma-form", type=int, default=0, help="matrix-core kernel form 1..3 (0: the library's default)")
-    ap.add_argument("--fused", action="store_true", help="single-token steps run w1/w3 and w2 as one persistent launch")
+    ap.add_argument("--fused", type=int, default=-1,
+                    help="single-token steps run w1/w3 and w2 as one persistent launch: 1 with a grid barrier, 2 expert after expert; 0 two launches (-1: the library's default)")
     ap.add_argument("--no-token-path", action="store_true", help="single-token steps use the general kernels (atomics + residual kernel)")
     ap.add_argument("--no-probe", action="store_true", help="skip the plain streaming-read / copy calibration kernels")
+    ap.add_argument("--ablation-steps", type=int, default=64,
+                    help="steps of each ablation run after the timed one (whole-expert speculative loads; no speculative loading); 0: none")
     ap.add_argument("--scale-group", type=int, default=0,
                     help="two-level metadata (Sec. 4.2): 8-bit scale and zero codes with an fp16 quad per run of this many "
                          "groups (256 for the paper's 4-bit scheme); 4-bit formats only, 4.25 instead of 4.5 bits per weight")
@@ -160,8 +168,8 @@ def main() -> int:
     B.moe_ctx_set_option(stack.ctx, "spec_head_mb", args.spec_head_mb)
     if args.mfma_form:
         B.moe_ctx_set_option(stack.ctx, "mfma_form", args.mfma_form)
-    if args.fused:
-        B.moe_ctx_set_option(stack.ctx, "fused", 1)
+    if args.fused >= 0:
+        B.moe_ctx_set_option(stack.ctx, "fused", args.fused)
     if args.no_token_path:
         B.moe_ctx_set_option(stack.ctx, "token_path", 0)
     xs = (W.hidden_iid if shape.hidden_kind == "iid" else W.hidden_ar1)(shape.seed, n_tok, batch, shape.hidden)
@@ -238,12 +246,23 @@ def main() -> int:
                    "scale_group": args.scale_group, "expert_blob_bytes": max(stack.blob_bytes)},
     }
     link_bytes = d["bytes_h2d_demand"] + d["bytes_h2d_spec"]
+    per_layer = [{k: a[k] - b[k] for k in ("needed", "hits", "prefetch_hits")} for a, b in zip(layers_after, layers_before)]
+    # Sec. 4.1's recall counts an expert as "already available on GPU".  With head-then-tail speculative loads a
+    # confirmed guess has only its head there (requested, in flight or landed) when the gate decides; the rest
+    # crosses the link after the decision.  resident_byte_frac weighs every needed expert by the bytes that were
+    # on the device (or on their way) at decision time.
+    head = args.spec_head_mb << 20
+    on_dev = sum(x["hits"] * bb + x["prefetch_hits"] * (min(head, bb) if head else bb) for x, bb in zip(per_layer, stack.blob_bytes))
+    all_needed = sum(x["needed"] * bb for x, bb in zip(per_layer, stack.blob_bytes))
     result["cache"] = {"needed": d["needed"], "hits": d["hits"], "prefetch_hits": d["prefetch_hits"], "misses": d["misses"],
+                       "prefetch_hits_fully_staged": 0 if head else d["prefetch_hits"],
+                       "prefetch_hits_head_only": d["prefetch_hits"] if head else 0,
                        "spec_issued": d["spec_issued"], "spec_wasted": d["spec_wasted"],
                        "recall": (d["hits"] + d["prefetch_hits"]) / max(1, d["needed"]),
+                       "lru_hit_ratio": d["hits"] / max(1, d["needed"]),
+                       "resident_byte_frac": on_dev / max(1, all_needed),
                        "link_bytes_per_token": link_bytes / tokens}
     # per layer: LRU hit ratio and recall (hits + prefetch hits) over the timed steps
-    per_layer = [{k: a[k] - b[k] for k in ("needed", "hits", "prefetch_hits")} for a, b in zip(layers_after, layers_before)]
     result["cache"]["per_layer_hit_ratio"] = [round(x["hits"] / max(1, x["needed"]), 3) for x in per_layer]
     result["cache"]["per_layer_recall"] = [round((x["hits"] + x["prefetch_hits"]) / max(1, x["needed"]), 3) for x in per_layer]
     # the step can be no faster than its bytes over the slower of the two pipes (nominal peaks)
@@ -257,7 +276,8 @@ def main() -> int:
         # single-token steps run the expert FFN as one persistent launch: that kernel is the dominant one
         ff, cp, gt = prof["ffn"], prof["copy"], prof["gate"]
         ach = ff["bytes"] / max(ff["total_ms"], 1e-9) / 1e6
-        result["roofline"] = {"bound": "hbm", "kernel": "k_ffn_token (w1,w3 -> SiLU*mul -> grid barrier -> w2 -> combine -> residual)",
+        result["roofline"] = {"bound": "hbm", "kernel": "k_ffn_seq (w1,w3 -> SiLU*mul -> w2 -> combine -> residual in one launch, expert after expert)" if args.fused == 2
+                              else "k_ffn_token (w1,w3 -> SiLU*mul -> grid barrier -> w2 -> combine -> residual)",
                               "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
                               "traffic": PMC_TRAFFIC_FFN_4BIT_B1 if (batch == 1 and set(formats) == {(4, 64)}
                                                                      and shape.hidden == 4096 and shape.ffn == 14336) else None,
@@ -266,24 +286,32 @@ def main() -> int:
                               "measured_read_probe_gbs": probe["read_gbs"] if probe else None}
         result["gemv_hbm_gbs"] = ach
     elif prof:
-        w13, w2, cp, gt = prof["w13"], prof["w2"], prof["copy"], prof["gate"]
-        ach = w13["bytes"] / max(w13["total_ms"], 1e-9) / 1e6      # GB/s
-        matrix_cores = batch >= 16 and set(formats) == {(4, 64)} and not args.scale_group
-        result["roofline"] = {"bound": "hbm", "kernel": "k_mfma_stream_q4<true> (grouped dequant-GEMM w1,w3 -> SiLU*mul)" if matrix_cores
-                              else "k_w13 (fused dequant-GEMV w1,w3 -> SiLU*mul)",
-                              "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
-                              "traffic": PMC_TRAFFIC_W13_4BIT_B1 if (batch == 1 and set(formats) == {(4, 64)} and not args.scale_group
-                                                                     and shape.hidden == 4096 and shape.ffn == 14336) else None,
-                              "launches": w13["launches"],
-                              "bytes_per_launch": w13["bytes"] / max(1, w13["launches"]),
-                              "avg_us": 1e3 * w13["total_ms"] / max(1, w13["launches"]),
-                              "measured_read_probe_gbs": probe["read_gbs"] if probe else None}
-        a2 = w2["bytes"] / max(w2["total_ms"], 1e-9) / 1e6
-        result["roofline_w2"] = {"bound": "hbm", "kernel": "k_mfma_stream_q4<false> (grouped dequant-GEMM w2 -> combine)" if matrix_cores
-                                 else "k_w2 / k_w2_token (fused dequant-GEMV w2 -> combine -> residual)",
-                                 "achieved": a2, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": a2 / HBM_PEAK_GBS,
-                                 "launches": w2["launches"], "avg_us": 1e3 * w2["total_ms"] / max(1, w2["launches"])}
+        w13, w2 = prof["w13"], prof["w2"]
+        matrix_cores = batch >= 16 and set(formats) == {(4, 64)}
+        default_shape = (batch == 1 and set(formats) == {(4, 64)} and not args.scale_group and shape.hidden == 4096
+                         and shape.ffn == 14336 and not args.no_token_path)
+
+        def kernel_line(pr, name, traffic):
+            ach = pr["bytes"] / max(pr["total_ms"], 1e-9) / 1e6      # GB/s
+            return {"bound": "hbm", "kernel": name, "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
+                    "traffic": traffic if default_shape else None, "launches": pr["launches"],
+                    "bytes_per_launch": pr["bytes"] / max(1, pr["launches"]), "avg_us": 1e3 * pr["total_ms"] / max(1, pr["launches"])}
+
+        n13 = "k_mfma_stream_q4<W13> (grouped dequant-GEMM w1,w3 -> SiLU*mul)" if matrix_cores else "k_w13 (fused dequant-GEMV w1,w3 -> SiLU*mul)"
+        n2 = ("k_mfma_stream_q4<W2> (grouped dequant-GEMM w2; k_combine adds and applies the residual)" if matrix_cores
+              else "k_w2_token / k_w2 (fused dequant-GEMV w2 -> combine -> residual)")
+        result["roofline_w13"] = kernel_line(w13, n13, PMC_TRAFFIC_W13_4BIT_B1)
+        result["roofline_w2"] = kernel_line(w2, n2, PMC_TRAFFIC_W2_4BIT_B1)
+        # the fused dequant-GEMV as the metric names it: both kernels, bytes of both over the sum of their durations,
+        # per layer-step (one launch of each)
         both = (w13["bytes"] + w2["bytes"]) / max(w13["total_ms"] + w2["total_ms"], 1e-9) / 1e6
+        steps_l = max(1, min(w13["launches"], w2["launches"]))
+        result["roofline"] = {"bound": "hbm", "kernel": f"{n13} + {n2}", "achieved": both, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                              "frac": both / HBM_PEAK_GBS,
+                              "traffic": (PMC_TRAFFIC_W13_4BIT_B1 + PMC_TRAFFIC_W2_4BIT_B1) if default_shape else None,
+                              "launches": steps_l, "bytes_per_launch": (w13["bytes"] + w2["bytes"]) / steps_l,
+                              "avg_us": 1e3 * (w13["total_ms"] + w2["total_ms"]) / steps_l,
+                              "measured_read_probe_gbs": probe["read_gbs"] if probe else None}
         result["gemv_hbm_gbs"] = both
     if prof:
         cp, gt = prof["copy"], prof["gate"]
@@ -306,6 +334,32 @@ def main() -> int:
         result["gate_avg_us"] = 1e3 * gt["total_ms"] / max(1, gt["launches"])
     if probe:
         result["probe"] = probe
+    if args.ablation_steps > 0 and shape.prefetch_m > 0 and not args.swap and not args.no_cache:
+        # Table 2's rows on the same inputs: the literal algorithm of Sec. 3.2/3.3 (a guessed expert is loaded whole)
+        # and no speculative loading at all, each from a cold cache over the first tokens of the stream
+        def short_run(head_mb, m):
+            n = min(args.ablation_steps, n_tok - 8)
+            stack.reset()
+            B.moe_ctx_set_option(stack.ctx, "spec_head_mb", head_mb)
+            stack.set_prefetch(m)
+            for t in range(8):
+                stack.step(x_dev[t], x_out)
+            stack.synchronize()
+            b0 = stack.total_stats()
+            t1 = time.perf_counter()
+            for t in range(8, 8 + n):
+                stack.step(x_dev[t], x_out)
+            stack.synchronize()
+            torch.cuda.synchronize()
+            el = time.perf_counter() - t1
+            dd = {k: v - b0[k] for k, v in stack.total_stats().items()}
+            return {"tokens_per_s": n * batch / el, "steps": n, "spec_head_mb": head_mb, "prefetch_m": m,
+                    "recall": (dd["hits"] + dd["prefetch_hits"]) / max(1, dd["needed"]),
+                    "link_bytes_per_token": (dd["bytes_h2d_demand"] + dd["bytes_h2d_spec"]) / (n * batch)}
+        log("ablations: whole-expert speculative loads, no speculative loads, and the headline setting over the same steps")
+        result["ablations"] = {"literal_whole_expert_speculation": short_run(0, shape.prefetch_m),
+                               "without_speculative_loading": short_run(args.spec_head_mb, 0),
+                               "as_timed_above": short_run(args.spec_head_mb, shape.prefetch_m)}
     if not args.no_cpu_baseline:
         log("timing the CPU oracle on a bounded sample")
         result["cpu_baseline"] = cpu_baseline(shape, formats, gates, gamma, kept, xs)

@@ -9,8 +9,11 @@
 // Phase 2: block b owns output rows [b*R, (b+1)*R); waves [e*CS, (e+1)*CS) own the column chunks of expert e.
 #pragma once
 #include "kernels_gemv.h"
+// 1 (default): after the grid barrier the activations a are read back with agent-scope loads, which no stale line in
+// a die's L2 can serve -- correct by the memory model.  0: plain loads (a timing variant only: a block may then hit
+// a line of a that its own die cached before the other dies' stores arrived).
 #ifndef MOE_FUSED_COHERENT_A
-#define MOE_FUSED_COHERENT_A 0
+#define MOE_FUSED_COHERENT_A 1
 #endif
 
 
@@ -105,26 +108,25 @@ __device__ __forceinline__ void token_w2_phase(const FusedArgs &A, float *red, i
     const int row0 = blockIdx.x * R;
     const int row_end = min(row0 + R, A.H);
     const int last2 = max(row_end - 1, 0);
+    auto row_of = [&](int j) { return min(j, last2); };
     const uint8_t *blob2 = A.route_idx ? A.table[uniform(A.route_idx[active ? e2 : 0]) & 15] : A.blob[active ? e2 : 0];
     const uint8_t *base2 = blob2 + A.off_w2;
     typename F::Row ring2[G2];
 #pragma unroll
-    for (int s = 0; s < G2; ++s) F::load(ring2[s], base2 + (size_t)min(row0 + s, last2) * A.stride2, geo2, cc);
+    for (int s = 0; s < G2; ++s) F::load(ring2[s], base2 + (size_t)row_of(row0 + s) * A.stride2, geo2, cc);
 
     if (BARRIER) grid_barrier(A.barrier, A.barrier_target, A.error_flag);
 
     typename F::Act ac;
-#if MOE_FUSED_COHERENT_A
-    load_act_coherent<BITS>(ac, A.a + (size_t)A.a_row[active ? e2 : 0] * A.F, cc, live2);
-#else
-    F::load_act(ac, A.a + (size_t)A.a_row[active ? e2 : 0] * A.F, cc, live2);
-#endif
+    // a written by an earlier launch is visible to plain loads; a written inside this launch by other dies is not
+    if constexpr (BARRIER && MOE_FUSED_COHERENT_A) load_act_coherent<BITS>(ac, A.a + (size_t)A.a_row[active ? e2 : 0] * A.F, cc, live2);
+    else F::load_act(ac, A.a + (size_t)A.a_row[active ? e2 : 0] * A.F, cc, live2);
     for (int rbase = row0; rbase < row_end; rbase += G2) {
 #pragma unroll
         for (int s = 0; s < G2; ++s) {
             const int row = rbase + s;
             const float part = F::contrib(ring2[s], ac, live2);
-            F::load(ring2[s], base2 + (size_t)min(row + G2, last2) * A.stride2, geo2, cc);
+            F::load(ring2[s], base2 + (size_t)row_of(row + G2) * A.stride2, geo2, cc);
             const float p = wave_sum_l63(part);
             if (lane == 63 && active && row < row_end) red[(e2 * 8 + cs) * 64 + (row - row0)] = p;
         }
@@ -215,6 +217,183 @@ __global__ __launch_bounds__(FUSED_WAVES *WAVE) void k_ffn_token(FusedArgs A)
     }
 
     token_w2_phase<BITS, G2, true>(A, red, wv, lane);
+}
+
+// ---------------------------------------------------------------------------------------------
+// One launch, expert after expert: w1/w3 of expert 0, w1/w3 of expert 1, w2 of expert 0, w2 of expert 1.
+//
+// k_ffn_token above meets at ONE barrier between all of w1/w3 and all of w2, and every block waits there for the
+// slowest wave of the chip (waves of one launch finish their equal shares several microseconds apart).  Here the
+// dependencies are per expert -- w2 of expert e needs the activations a of expert e only -- and the phases are
+// ordered so that a whole phase of other work lies between producing an a and consuming it: by the time a wave asks
+// whether expert 0's a is complete it has streamed expert 1's w1/w3 rows, and before it asks for expert 1's it has
+// done expert 0's w2 rows.  The waits therefore find the flags already set (or nearly), the weight stream never
+// stops at a phase boundary (the first rows of the next phase are requested before the wait), and the launch pays
+// one ramp and one tail instead of two.  Blocks have 8 waves (two per SIMD, 256 registers per lane, the shape
+// k_w13 runs best in), one block per compute unit, all resident at once.
+//
+// Visibility across the dies' L2s as in k_ffn_token: a is written with agent-scope stores, the block waits for their
+// acknowledgement, then publishes flags[e][block] = epoch with an agent-scope store; a consumer polls the flags of
+// all blocks with agent-scope loads and then reads a with agent-scope loads.  Every wait is bounded.
+// ---------------------------------------------------------------------------------------------
+
+constexpr int SEQ_WAVES = 8;
+constexpr int SEQ_MAX_ROWS = 64;                   // rows of one expert's w1/w3 per wave
+constexpr int SEQ_FLAG_STRIDE = 1024;              // flags[e * SEQ_FLAG_STRIDE + block]
+
+// true when every block has published `epoch` (or a later one) for this expert; polled by one wave for itself
+__device__ __forceinline__ bool seq_arrived(const uint32_t *flags, uint32_t epoch, int lane)
+{
+    int ok = 1;
+    for (uint32_t i = lane; i < gridDim.x; i += 64)
+        ok &= (int32_t)(__hip_atomic_load(flags + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - epoch) >= 0;
+    return __builtin_amdgcn_ballot_w64(!ok) == 0;
+}
+
+template <int BITS, int KCH, int G1, int G2>
+__global__ __launch_bounds__(SEQ_WAVES *WAVE) void k_ffn_seq(FusedArgs A)
+{
+    using F = Fmt<BITS>;
+    __shared__ float red[2 * 8 * 64];                     // [expert][cs][row]
+    __shared__ uint16_t a_stage[SEQ_WAVES][SEQ_MAX_ROWS]; // a wave's outputs of the expert it is working on
+    const int lane = threadIdx.x & 63;
+    const int wv = uniform(threadIdx.x >> 6);
+    const int gw = uniform(blockIdx.x * SEQ_WAVES + wv), n_waves = gridDim.x * SEQ_WAVES;
+    auto blob_of = [&](int e) { return A.route_idx ? A.table[uniform(A.route_idx[e]) & 15] : A.blob[e]; };
+
+    // ---------------- w1/w3: a[e][r] = silu(W1_e h)[r] * (W3_e h)[r], expert after expert ----------------
+    {
+        const int n_chunks = A.H / F::CODES;
+        const RowGeom geo = row_geom<BITS>(A.meta13, A.H, A.group, A.scale_group);
+        int cidx[KCH];
+        bool live[KCH];
+#pragma unroll
+        for (int k = 0; k < KCH; ++k) {
+            live[k] = k * 64 + lane < n_chunks;
+            cidx[k] = live[k] ? k * 64 + lane : 0;
+        }
+        struct RowPair { typename F::Row w1[KCH], w3[KCH]; };
+        const int rpw = (A.F + n_waves - 1) / n_waves;      // this wave's rows of every expert: [r0, r0 + rpw)
+        const int r0 = gw * rpw;
+        const int last_row = A.F - 1;
+        // the ring runs over (expert, row) in order; past the end it re-reads the last row (cached, unused)
+        auto load_at = [&](RowPair &rb, int e, int j) {
+            const int ee = min(e, A.n_exp - 1);
+            const uint8_t *r1 = blob_of(ee) + (size_t)(2 * min(r0 + j, last_row)) * A.stride13, *r3 = r1 + A.stride13;
+#pragma unroll
+            for (int k = 0; k < KCH; ++k) {
+                F::load(rb.w1[k], r1, geo, cidx[k]);
+                F::load(rb.w3[k], r3, geo, cidx[k]);
+            }
+        };
+        RowPair ring[G1];
+        int le = 0, lj = 0;                                  // the next (expert, row) to request
+        auto advance = [&](int &e, int &j) { if (++j == rpw) { j = 0; ++e; } };
+#pragma unroll
+        for (int s = 0; s < G1; ++s) { load_at(ring[s], le, lj); advance(le, lj); }
+        typename F::Act hc[KCH];
+#pragma unroll
+        for (int k = 0; k < KCH; ++k) F::load_act(hc[k], A.h, cidx[k], live[k]);
+        const int total = A.n_exp * rpw, trips = (total + G1 - 1) / G1;
+        int ce = 0, cj = 0;                                  // the (expert, row) being computed
+        for (int it = 0; it < trips; ++it) {
+#pragma unroll
+            for (int s = 0; s < G1; ++s) {
+                float u = 0.f, v = 0.f;
+#pragma unroll
+                for (int k = 0; k < KCH; ++k) {
+                    u += F::contrib(ring[s].w1[k], hc[k], live[k]);
+                    v += F::contrib(ring[s].w3[k], hc[k], live[k]);
+                }
+                load_at(ring[s], le, lj);
+                advance(le, lj);
+                const float us = wave_sum_l63(u), vs = wave_sum_l63(v);
+                if (lane == 63 && ce < A.n_exp) a_stage[wv][cj] = __builtin_bit_cast(uint16_t, (_Float16)silu_mul(us, vs));
+                const bool expert_done = ce < A.n_exp && cj == rpw - 1;
+                advance(ce, cj);
+                if (expert_done) {
+                    // this wave's rows of expert ce-1 are complete: store them, wait for the stores (and, with them,
+                    // for the ring's loads, which the next trips need anyway), and let the block publish
+                    const int e = ce - 1;
+                    if (lane < rpw && r0 + lane < A.F)
+                        __hip_atomic_store(A.a + (size_t)A.a_row[e] * A.F + r0 + lane, a_stage[wv][lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+                    __syncthreads();
+                    if (threadIdx.x == 0)
+                        __hip_atomic_store(A.barrier + e * SEQ_FLAG_STRIDE + blockIdx.x, A.barrier_target, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+            }
+        }
+    }
+
+    // ---------------- w2: rows [b*R, (b+1)*R) of this block, expert after expert; combine; residual ----------------
+    {
+        const int n_chunks2 = A.F / F::CODES;
+        const int CS = (n_chunks2 + 63) / 64;               // waves that own a column chunk; the others only wait
+        const int cs = wv;
+        const bool owner = cs < CS;
+        const int c = cs * 64 + lane;
+        const bool live2 = owner && c < n_chunks2;
+        const int cc = live2 ? c : 0;
+        const RowGeom geo2 = row_geom<BITS>(A.meta2, A.F, A.group, A.scale_group);
+        const int R = A.rows_per_block;                      // a multiple of G2
+        const int row0 = blockIdx.x * R;
+        const int row_end = min(row0 + R, A.H);
+        const int last2 = max(row_end - 1, 0);
+        const bool has_rows = row0 < A.H;
+        typename F::Row ring2[G2];
+        auto load2 = [&](typename F::Row &rw, int e, int j) {
+            const int ee = min(e, A.n_exp - 1);
+            F::load(rw, blob_of(ee) + A.off_w2 + (size_t)min(row0 + j, last2) * A.stride2, geo2, cc);
+        };
+        int le = 0, lj = 0;
+        auto advance2 = [&](int &e, int &j) { if (++j == R) { j = 0; ++e; } };
+        if (owner && has_rows) {                             // the other waves have no column chunk (or no rows) and go straight to the end
+#pragma unroll
+        for (int s = 0; s < G2; ++s) { load2(ring2[s], le, lj); advance2(le, lj); }
+        typename F::Act ac;
+        for (int e = 0; e < A.n_exp; ++e) {
+            // expert e's activations must be complete on every block before any of them is read
+            const uint32_t *flags = A.barrier + e * SEQ_FLAG_STRIDE;
+            uint32_t spins = 0;
+            while (!seq_arrived(flags, A.barrier_target, lane)) {
+                if (++spins > BARRIER_SPIN_LIMIT) {
+                    if (lane == 0) __hip_atomic_store(A.error_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+                    break;
+                }
+                __builtin_amdgcn_s_sleep(2);
+            }
+            load_act_coherent<BITS>(ac, A.a + (size_t)A.a_row[e] * A.F, cc, live2);
+            for (int jb = 0; jb < R; jb += G2) {
+#pragma unroll
+                for (int s = 0; s < G2; ++s) {
+                    const int j = jb + s;
+                    const float part = F::contrib(ring2[s], ac, live2);
+                    load2(ring2[s], le, lj);
+                    advance2(le, lj);
+                    const float p = wave_sum_l63(part);
+                    if (lane == 63 && row0 + j < row_end) red[(e * 8 + cs) * 64 + j] = p;
+                }
+            }
+        }
+        }
+        __syncthreads();
+        const int rr = threadIdx.x;
+        if (has_rows && rr < row_end - row0) {
+            const bool swap = A.route_idx && A.n_exp == 2 && A.route_idx[0] > A.route_idx[1];   // ascending expert id, as the host orders them
+            float y = 0.f;
+            for (int i = 0; i < A.n_exp; ++i) {
+                const int e = swap ? 1 - i : i;
+                float s = 0.f;
+                for (int k = 0; k < CS; ++k) s += red[(e * 8 + k) * 64 + rr];
+                y += (A.route_idx ? A.route_w[e] : A.w[e]) * s;
+            }
+            const int row = row0 + rr;
+            A.y[row] = y;
+            const float v = (float)__builtin_bit_cast(_Float16, A.x[row]) + y;
+            A.x_out[row] = __builtin_bit_cast(uint16_t, (_Float16)v);
+        }
+    }
 }
 
 // The w2 half on its own (after k_w13): same combine and residual without atomics or a further kernel.

@@ -166,7 +166,8 @@ struct moe_ctx {
     uint64_t spec_head_bytes = 0;       // 0: a speculative load moves the whole expert at once (as the paper describes);
                                         // > 0: only this many leading bytes, the rest when the guess is confirmed
     bool token_path = true;             // single-token steps: w2 kernel with in-kernel combine + residual (no atomics)
-    bool fused = false;                 // ... and w1/w3 + w2 as one persistent launch with a grid barrier
+    int32_t fused = 0;                  // ... and w1/w3 + w2 as one persistent launch: 1 with a grid barrier between them, 2 expert after expert
+    uint32_t *seq_flags = nullptr;      // device flags of the expert-after-expert kernel: [expert][block] = epoch of the last arrival
     int32_t n_cu = 0;                   // compute units: grid size of the persistent kernel
     uint32_t *barrier = nullptr;        // device counter of its grid barrier
     uint32_t barrier_count = 0;         // value it reaches after all launches enqueued so far
@@ -247,12 +248,13 @@ static ScratchPlan plan_scratch(const moe_ctx_config_t *c)
     p.a = off;    off += align_u64((uint64_t)c->max_batch * c->max_top_k * c->max_ffn * 2, 256);
     p.yacc = off; off += align_u64((uint64_t)c->max_batch * c->max_hidden * 4, 256);
     const uint64_t pairs = (uint64_t)c->max_batch * c->max_top_k;
-    p.ypart_extra_floats = std::min<uint64_t>(2048, 16 * pairs) * c->max_hidden;
+    // rows for the partial sums of split contractions: sixteen parts for small batches, four for prompt-sized ones
+    p.ypart_extra_floats = std::max(std::min<uint64_t>(2048, 16 * pairs), std::min<uint64_t>(16384, 4 * pairs)) * c->max_hidden;
     p.ypart = off; off += align_u64((pairs * c->max_hidden + p.ypart_extra_floats) * 4, 256);
     p.ytab = off; off += align_u64(pairs * 4, 256);
     p.x0 = off;   off += align_u64((uint64_t)c->max_batch * c->max_hidden * 2, 256);
     p.x1 = off;   off += align_u64((uint64_t)c->max_batch * c->max_hidden * 2, 256);
-    p.barrier = off; off += 4096;     // one flag per block of the persistent kernel (at most 1024 compute units)
+    p.barrier = off; off += 4096 + 2 * SEQ_FLAG_STRIDE * 4;     // one flag per block of the persistent kernels (at most 1024 compute units); then [2 experts][blocks]
     p.route = off; off += 256;        // device-side routing: MOE_MAX_TOPK selections and as many combine weights
     p.route_log = off; off += align_u64((uint64_t)ROUTE_LOG_ENTRIES * MOE_MAX_TOPK * sizeof(int32_t), 256);
     p.total = off;
@@ -298,12 +300,6 @@ extern "C" uint64_t moe_layer_host_bytes(const moe_layer_config_t *cfg)
 // context
 // ---------------------------------------------------------------------------------------------
 
-static int env_int(const char *name, int dflt)
-{
-    const char *v = getenv(name);
-    return (v && *v) ? atoi(v) : dflt;
-}
-
 extern "C" int32_t moe_ctx_create(const moe_ctx_config_t *cfg, void *dev_arena, uint64_t dev_arena_bytes,
                                   void *compute_stream, void *copy_stream, moe_ctx_t **out)
 try {
@@ -318,10 +314,6 @@ try {
     c->buf_bytes = align_u64(cfg->max_expert_bytes, 4096);
     c->bufs.resize(cfg->n_staging);
     for (int i = 0; i < cfg->n_staging; ++i) c->pool.free_staging.push_back(i);
-    c->w13_blocks = std::max(1, env_int("MOE_W13_BLOCKS", c->w13_blocks));
-    c->w2_rows = std::max(4, env_int("MOE_W2_ROWS", c->w2_rows));
-    c->w2_token_rows = std::min(64, std::max(0, env_int("MOE_W2T_ROWS", c->w2_token_rows)));
-    c->sync_wait = env_int("MOE_SYNC_WAIT", 0) != 0;
     if (c->host_only) {
         c->gate_out = static_cast<GateHostOut *>(calloc(1, sizeof(GateHostOut)));
         if (!c->gate_out) return fail(MOE_ENOMEM, "moe_ctx_create: out of host memory");
@@ -345,15 +337,11 @@ try {
     c->xbuf[0] = reinterpret_cast<uint16_t *>(base + p.x0);
     c->xbuf[1] = reinterpret_cast<uint16_t *>(base + p.x1);
     c->barrier = reinterpret_cast<uint32_t *>(base + p.barrier);
+    c->seq_flags = c->barrier + 1024;
     c->route_idx = reinterpret_cast<int32_t *>(base + p.route);
     c->route_w = reinterpret_cast<float *>(base + p.route + 128);
     c->route_log_dev = reinterpret_cast<int32_t *>(base + p.route_log);
-    c->device_routing = env_int("MOE_DEVICE_ROUTING", 1) != 0;
-    c->mfma_min_batch = env_int("MOE_MFMA_MIN_BATCH", 16);
-    c->mfma_form = std::min(3, std::max(1, env_int("MOE_MFMA_FORM", c->mfma_form)));
-    c->staged_min_batch = env_int("MOE_STAGED_MIN_BATCH", c->staged_min_batch);
-    c->fused = env_int("MOE_FUSED", 0) != 0;
-    hipError_t e = hipMemset(c->barrier, 0, 4096);
+    hipError_t e = hipMemset(c->barrier, 0, 4096 + 2 * SEQ_FLAG_STRIDE * 4);
     if (e == hipSuccess) {
         int dev = 0;
         hipDeviceProp_t prop;
@@ -1207,6 +1195,58 @@ static int32_t launch_ffn_fmt(moe_layer *l, const std::vector<FfnEntry> &entries
     return MOE_OK;
 }
 
+// Ring depths of the expert-after-expert one-launch kernel.
+#ifndef MOE_SEQ_G1
+#define MOE_SEQ_G1 2
+#endif
+#ifndef MOE_SEQ_G2
+#define MOE_SEQ_G2 4
+#endif
+
+// The expert-after-expert one-launch kernel for a single token; *done = false when the shape does not fit it.
+template <int BITS>
+static int32_t launch_seq_fmt(moe_layer *l, const FusedArgs &A0, bool probe_only, bool *done)
+{
+    moe_ctx *c = l->ctx;
+    const BlobLayout &b = l->lay;
+    const int kch = chunks_per_lane(b.hidden, BITS);
+    const int cs = (b.ffn / Fmt<BITS>::CODES + 63) / 64;
+    const int grid = c->n_cu;
+    *done = false;
+    if (grid < 1 || grid > SEQ_FLAG_STRIDE) return MOE_OK;
+    const int rpw = (b.ffn + grid * SEQ_WAVES - 1) / (grid * SEQ_WAVES);
+    const int rows = ((b.hidden + grid - 1) / grid + MOE_SEQ_G2 - 1) / MOE_SEQ_G2 * MOE_SEQ_G2;
+    constexpr bool has_kernel = BITS == 4 || BITS == 48 || BITS == 2 || BITS == 3;
+    if (!has_kernel || kch == 0 || kch > 2 || (codes_per_chunk(BITS) == 64 && kch > 1) || cs > SEQ_WAVES || rpw > SEQ_MAX_ROWS || rows > 64 ||
+        A0.n_exp < 1 || A0.n_exp > 2)
+        return MOE_OK;
+    *done = true;
+    if (probe_only) return MOE_OK;
+    if constexpr (has_kernel) {
+        FusedArgs A = A0;
+        A.rows_per_block = rows;
+        A.barrier = c->seq_flags;
+        A.barrier_target = ++c->barrier_count;
+        A.error_flag = &c->gate_out_dev->ffn_error;
+        const uint64_t bytes = (uint64_t)A.n_exp * (2 * (uint64_t)b.ffn * b.m13.row_stride + (uint64_t)b.hidden * b.m2.row_stride);
+        const dim3 g(grid), blk(SEQ_WAVES * WAVE);
+        if (kch == 1) return launch_timed(c, PROF_FFN, bytes, k_ffn_seq<BITS, 1, MOE_SEQ_G1, MOE_SEQ_G2>, g, blk, 0, A);
+        if constexpr (BITS != 3) return launch_timed(c, PROF_FFN, bytes, k_ffn_seq<BITS, 2, MOE_SEQ_G1, MOE_SEQ_G2>, g, blk, 0, A);
+    }
+    return fail(MOE_EINVAL, "no one-launch kernel for this shape");
+}
+
+static int32_t launch_seq(moe_layer *l, const FusedArgs &A, bool probe_only, bool *done)
+{
+    switch (fmt_of(l->lay)) {
+    case 4: return launch_seq_fmt<4>(l, A, probe_only, done);
+    case 3: return launch_seq_fmt<3>(l, A, probe_only, done);
+    case 2: return launch_seq_fmt<2>(l, A, probe_only, done);
+    case 48: return launch_seq_fmt<48>(l, A, probe_only, done);
+    default: *done = false; return MOE_OK;
+    }
+}
+
 // The one-launch path for a single token; returns MOE_OK with *done = false when the shape does not fit it.
 template <int BITS>
 static int32_t launch_token_fmt(moe_layer *l, const FusedArgs &A0, bool one_launch, bool probe_only, bool *done)
@@ -1228,8 +1268,8 @@ static int32_t launch_token_fmt(moe_layer *l, const FusedArgs &A0, bool one_laun
     FusedArgs A = A0;
     A.rows_per_block = rows;
     if (!one_launch) {
-        // w2 half only (k_w13 ran before): blocks of n_exp * CS waves, no barrier
         const uint64_t bytes2 = (uint64_t)A.n_exp * b.hidden * b.m2.row_stride;
+        // w2 half only (k_w13 ran before): blocks of n_exp * CS waves, no barrier
         return launch_timed(c, PROF_W2, bytes2, k_w2_token<BITS, MOE_W2T_G>, dim3((b.hidden + rows - 1) / rows),
                             dim3(A.n_exp * cs * WAVE), 0, A);
     }
@@ -1617,7 +1657,9 @@ static int32_t step_impl(moe_layer *l, moe_layer *next, const uint16_t *x_in, in
             int count[MOE_MAX_EXPERTS] = {0}, entries = 0;
             for (int q = w0 * cf.top_k; q < w1 * cf.top_k; ++q) count[idx[q]]++;
             for (int e = 0; e < cf.n_experts; ++e) entries += (count[e] + 31) / 32;
-            const int want = std::max(1, (2 * n_cu + entries * row_blocks - 1) / std::max(1, entries * row_blocks));
+            // at least four: the experts that arrive during a step are multiplied one launch each, and with fewer
+            // parts such a launch leaves most of the chip idle on the step's critical path
+            const int want = std::max(4, (2 * n_cu + entries * row_blocks - 1) / std::max(1, entries * row_blocks));
             c->w2_parts.push_back(std::min(want, max_parts));
         }
     }
@@ -1752,7 +1794,11 @@ static int32_t step_impl(moe_layer *l, moe_layer *next, const uint16_t *x_in, in
             FusedArgs fa = token_args(l, x_in, x_out);
             fa.n_exp = (int32_t)entries.size();
             for (int i = 0; i < fa.n_exp; ++i) { fa.blob[i] = entries[i].blob; fa.w[i] = entries[i].w[0]; fa.a_row[i] = entries[i].pair[0]; }
-            if (c->fused && !plain) {
+            if (c->fused == 2 && !plain) rc = launch_seq(l, fa, false, &fused_done);
+            if (rc) return rc;
+            if (fused_done) {
+                // the expert-after-expert kernel did the whole FFN
+            } else if (c->fused == 1 && !plain) {
                 rc = launch_token(l, fa, true, false, &fused_done);
             } else {
                 rc = launch_token(l, fa, false, true, &fused_done);       // does the shape fit the token kernels?
@@ -1972,7 +2018,7 @@ try {
     else if (n == "w2_rows" && value >= 1 && value <= 256) c->w2_rows = value;
     else if (n == "w2_token_rows" && value >= 0 && value <= 64) c->w2_token_rows = value;
     else if (n == "sync_wait") c->sync_wait = value != 0;
-    else if (n == "fused") c->fused = value != 0;
+    else if (n == "fused" && value >= 0 && value <= 2) c->fused = value;
     else if (n == "token_path") c->token_path = value != 0;
     else if (n == "spec_head_mb" && value >= 0) c->spec_head_bytes = (uint64_t)value << 20;
     else if (n == "mfma_min_batch" && value >= 1) c->mfma_min_batch = value;
