@@ -188,6 +188,27 @@ def main() -> int:
         ms_c = B.moe_probe_bandwidth(src.data_ptr(), dst.data_ptr(), 1 << 30, 8192, 3, s0)
         probe = {"read_gbs": (4 << 30) / ms_r / 1e6, "read_bytes": 4 << 30,
                  "copy_gbs_each_way": (1 << 30) / ms_c / 1e6, "copy_bytes": 1 << 30}
+        # what a launch of the size of the two GEMV kernels can reach at all: the same plain read over exactly the
+        # algorithmic bytes of one launch of each (w1/w3 and w2 of top_k experts at batch 1), one launch at a time,
+        # each over another part of the 4 GiB buffer so that nothing comes from the memory-side cache; median of 9,
+        # best of three grid sizes.  A launch this short never reaches the steady-state rate above.
+        if batch == 1:
+            l0 = stack.cfgs[0]
+            # bytes of w2 and of w1+w3 of one expert, from the blob size: rows of w2 are ffn codes + metadata, of w1/w3 hidden codes + metadata
+            per_w = {4: 0.5, 3: 0.375, 2: 0.25}[l0.bits]
+            meta = (2 if l0.scale_group else 4) / l0.group
+            w2_bytes = int(shape.top_k * l0.hidden * l0.ffn * (per_w + meta)) // 256 * 256
+            w13_bytes = 2 * w2_bytes
+            def same_size(nbytes):
+                best = None
+                for blocks in (512, 2048, 4096):
+                    ts = sorted(B.moe_probe_bandwidth(src.data_ptr() + ((i * 409_600_000) % ((4 << 30) - nbytes)) // 256 * 256, None, nbytes, blocks, 1, s0)
+                                for i in range(9))
+                    best = ts[4] if best is None else min(best, ts[4])
+                return 1e3 * best
+            probe["read_us_at_w13_launch_bytes"] = same_size(w13_bytes)
+            probe["read_us_at_w2_launch_bytes"] = same_size(w2_bytes)
+            probe["w13_launch_bytes"], probe["w2_launch_bytes"] = w13_bytes, w2_bytes
         del src, dst
         torch.cuda.empty_cache()
         # the host link alone: pinned -> device copies of one expert blob, back to back on one stream
@@ -312,6 +333,11 @@ def main() -> int:
                               "launches": steps_l, "bytes_per_launch": (w13["bytes"] + w2["bytes"]) / steps_l,
                               "avg_us": 1e3 * (w13["total_ms"] + w2["total_ms"]) / steps_l,
                               "measured_read_probe_gbs": probe["read_gbs"] if probe else None}
+        if probe and "read_us_at_w13_launch_bytes" in probe and not matrix_cores:
+            # the two launches against two plain reads of their sizes on this machine
+            plain = probe["read_us_at_w13_launch_bytes"] + probe["read_us_at_w2_launch_bytes"]
+            result["roofline"]["plain_read_us_at_launch_sizes"] = plain
+            result["roofline"]["frac_of_plain_read_at_launch_sizes"] = plain / result["roofline"]["avg_us"]
         result["gemv_hbm_gbs"] = both
     if prof:
         cp, gt = prof["copy"], prof["gate"]

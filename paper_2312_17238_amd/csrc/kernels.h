@@ -6,3 +6,4 @@
 #include "kernels_fused.h"
 #include "kernels_mfma.h"
 #include "kernels_mfma_stream.h"
+#include "kernels_mfma16.h"

@@ -151,6 +151,7 @@ struct moe_ctx {
     uint64_t ypart_extra_floats = 0;    // capacity behind the first B*K rows
     uint64_t ypart_extra_used = 0;      // floats of it taken by the launches of the current step
     std::vector<int32_t> w2_parts;      // per window of the current step: parts the matrix-core w2 launches split their contraction into
+    std::vector<uint8_t> win_small;     // ... and whether no expert has more than 16 tokens of the window (the 16-token tile form fits)
     uint8_t *noalloc_scratch = nullptr; // this device's copy of the file-scope scratch array (moe_layer_step_noalloc)
     GateHostOut *gate_out = nullptr;    // host pointer
     GateHostOut *gate_out_dev = nullptr;// the same memory as the device sees it
@@ -159,7 +160,8 @@ struct moe_ctx {
     int32_t w13_blocks = 256, w2_rows = 32;
     int32_t w2_token_rows = 0;          // rows per block of the single-token w2 kernel; 0: hidden / compute units
     uint32_t gate_seq = 0;              // sequence number of the last gate launch
-    int32_t mfma_form = 3;              // matrix-core kernels: 3 streaming form, one fma per pair of weights plus a rank-1 correction;
+    int32_t mfma_form = 0;              // matrix-core kernels: 0 by the tokens per expert (4 up to sixteen, else 3); 4 streaming form with 16-token tiles;
+                                        // 3 streaming form, one fma per pair of weights plus a rank-1 correction;
                                         // 2 streaming form with an exact subtraction first; 1 row-staging form with fp32 group scaling
     int32_t mfma_min_batch = 16;        // batches at least this large use the matrix-core kernels (4-bit g64)
     int32_t staged_min_batch = 0;       // matrix-core batches larger than this: resident experts first, arriving ones one by one
@@ -1317,6 +1319,10 @@ static int32_t launch_mfma_stream(moe_layer *l, const std::vector<PassExpert> &e
         HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_stream_q4<false, true>), hipFuncAttributeMaxDynamicSharedMemorySize, TL_LDS_BYTES));
         HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_stream_q4<true, false, true>), hipFuncAttributeMaxDynamicSharedMemorySize, TL_LDS_BYTES));
         HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_stream_q4<false, false, true>), hipFuncAttributeMaxDynamicSharedMemorySize, TL_LDS_BYTES));
+        HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_stream16_q4<true, 1>), hipFuncAttributeMaxDynamicSharedMemorySize, TL_LDS_BYTES));
+        HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_stream16_q4<true, 2>), hipFuncAttributeMaxDynamicSharedMemorySize, TL_LDS_BYTES));
+        HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_stream16_q4<false, 1>), hipFuncAttributeMaxDynamicSharedMemorySize, TL_LDS_BYTES));
+        HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_stream16_q4<false, 2>), hipFuncAttributeMaxDynamicSharedMemorySize, TL_LDS_BYTES));
         lds_attr_set = true;
     }
     const int n_cu = c->n_cu > 0 ? c->n_cu : 256;
@@ -1374,12 +1380,19 @@ static int32_t launch_mfma_stream(moe_layer *l, const std::vector<PassExpert> &e
         A.ypart = c->ypart + (size_t)w0 * K * b.hidden; A.ytab = c->ytab + (size_t)w0 * K; A.row_bias = w0 * K;
         A.act = c->h_buf + (size_t)w0 * b.hidden;
         const bool meta8 = b.scale_group > 0;
-        const bool r1 = c->mfma_form == 3 && !meta8 && !l->wide_meta.load(std::memory_order_relaxed);
+        const bool r1 = (c->mfma_form == 3 || c->mfma_form == 0) && !meta8 && !l->wide_meta.load(std::memory_order_relaxed);
+        // Which kernels multiply a window is decided from the window's routing, never from the experts that happen to
+        // share a launch: the forms round differently, and a token's result must not depend on what the cache held.
+        const bool small = c->win_small.at(w0 / window) != 0;
+        const bool t16 = (c->mfma_form == 4 || (c->mfma_form == 0 && small)) && !meta8;
+        const int max_tok = small ? 16 : 32;
         auto run_shift = [&](const MatLayout &m) { return (m.run_len == 0 || m.run_len >= m.cols / (uint32_t)b.group) ? 31 : __builtin_ctz(m.run_len); };
         A.K = b.hidden; A.N = b.ffn; A.stride = b.m13.row_stride; A.meta_off = b.m13.meta_off; A.mat_off = b.off_w13;
         A.meta2_off = b.m13.meta2_off; A.run_shift = run_shift(b.m13);
         const dim3 g13 = shape(2 * b.ffn, b.hidden, false);
-        int32_t rc = meta8 ? launch_timed(c, PROF_W13, bytes13, k_mfma_stream_q4<true, true>, g13, dim3(TL_THREADS), TL_LDS_BYTES, A)
+        int32_t rc = t16 ? (max_tok <= 16 ? launch_timed(c, PROF_W13, bytes13, k_mfma_stream16_q4<true, 1>, g13, dim3(TL_THREADS), TL_LDS_BYTES, A)
+                                          : launch_timed(c, PROF_W13, bytes13, k_mfma_stream16_q4<true, 2>, g13, dim3(TL_THREADS), TL_LDS_BYTES, A))
+                     : meta8 ? launch_timed(c, PROF_W13, bytes13, k_mfma_stream_q4<true, true>, g13, dim3(TL_THREADS), TL_LDS_BYTES, A)
                      : r1  ? launch_timed(c, PROF_W13, bytes13, k_mfma_stream_q4<true, false, true>, g13, dim3(TL_THREADS), TL_LDS_BYTES, A)
                            : launch_timed(c, PROF_W13, bytes13, k_mfma_stream_q4<true, false>, g13, dim3(TL_THREADS), TL_LDS_BYTES, A);
         if (rc) return rc;
@@ -1391,7 +1404,9 @@ static int32_t launch_mfma_stream(moe_layer *l, const std::vector<PassExpert> &e
             A.part_base = (int32_t)((uint64_t)batch * K + c->ypart_extra_used / b.hidden) - w0 * K;
             c->ypart_extra_used += (uint64_t)first * A.k_parts * b.hidden;
         }
-        rc = meta8 ? launch_timed(c, PROF_W2, bytes2, k_mfma_stream_q4<false, true>, g2, dim3(TL_THREADS), TL_LDS_BYTES, A)
+        rc = t16 ? (max_tok <= 16 ? launch_timed(c, PROF_W2, bytes2, k_mfma_stream16_q4<false, 1>, g2, dim3(TL_THREADS), TL_LDS_BYTES, A)
+                                  : launch_timed(c, PROF_W2, bytes2, k_mfma_stream16_q4<false, 2>, g2, dim3(TL_THREADS), TL_LDS_BYTES, A))
+             : meta8 ? launch_timed(c, PROF_W2, bytes2, k_mfma_stream_q4<false, true>, g2, dim3(TL_THREADS), TL_LDS_BYTES, A)
              : r1  ? launch_timed(c, PROF_W2, bytes2, k_mfma_stream_q4<false, false, true>, g2, dim3(TL_THREADS), TL_LDS_BYTES, A)
                    : launch_timed(c, PROF_W2, bytes2, k_mfma_stream_q4<false, false>, g2, dim3(TL_THREADS), TL_LDS_BYTES, A);
         if (rc) return rc;
@@ -1652,11 +1667,14 @@ static int32_t step_impl(moe_layer *l, moe_layer *next, const uint16_t *x_in, in
         const uint64_t extra_rows = c->ypart_extra_floats / cf.hidden, pairs = (uint64_t)batch * cf.top_k;
         const int max_parts = (int)std::min<uint64_t>(255, std::max<uint64_t>(1, extra_rows / pairs));
         c->w2_parts.clear();
+        c->win_small.clear();
         for (int w0 = 0; w0 < batch; w0 += window) {
             const int w1 = std::min(batch, w0 + window);
             int count[MOE_MAX_EXPERTS] = {0}, entries = 0;
             for (int q = w0 * cf.top_k; q < w1 * cf.top_k; ++q) count[idx[q]]++;
-            for (int e = 0; e < cf.n_experts; ++e) entries += (count[e] + 31) / 32;
+            int most = 0;
+            for (int e = 0; e < cf.n_experts; ++e) { entries += (count[e] + 31) / 32; most = std::max(most, count[e]); }
+            c->win_small.push_back(most <= 16);
             // at least four: the experts that arrive during a step are multiplied one launch each, and with fewer
             // parts such a launch leaves most of the chip idle on the step's critical path
             const int want = std::max(4, (2 * n_cu + entries * row_blocks - 1) / std::max(1, entries * row_blocks));
@@ -2022,7 +2040,7 @@ try {
     else if (n == "token_path") c->token_path = value != 0;
     else if (n == "spec_head_mb" && value >= 0) c->spec_head_bytes = (uint64_t)value << 20;
     else if (n == "mfma_min_batch" && value >= 1) c->mfma_min_batch = value;
-    else if (n == "mfma_form" && value >= 1 && value <= 3) c->mfma_form = value;
+    else if (n == "mfma_form" && value >= 0 && value <= 4) c->mfma_form = value;
     else if (n == "device_routing") c->device_routing = value != 0;
     else if (n == "staged_min_batch" && value >= 0) c->staged_min_batch = value;
     else if (n == "profile_copy_stride" && value >= 1) c->prof.copy_stride = value;

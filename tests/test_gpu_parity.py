@@ -283,7 +283,7 @@ def test_launch_shape_knobs_do_not_change_results(Bn, token_path):
         assert st == outs[0][1]
 
 
-@pytest.mark.parametrize("form", [3, 2, 1])
+@pytest.mark.parametrize("form", [3, 2, 1, 4])
 @pytest.mark.parametrize("Bn,k", [(16, 4), (64, 4), (33, 8), (64, 2)])
 def test_small_stack_matrix_core_path(Bn, k, form):
     """Batches of 16 and more run 4-bit g64 experts as grouped dequantize+GEMM on the matrix cores
@@ -300,7 +300,7 @@ def test_small_stack_matrix_core_path(Bn, k, form):
     model.close()
 
 
-@pytest.mark.parametrize("form,rel", [(1, 1e-4), (2, 2e-3), (3, 2e-3)])
+@pytest.mark.parametrize("form,rel", [(1, 1e-4), (2, 2e-3), (3, 2e-3), (4, 2e-3)])
 def test_matrix_core_path_agrees_with_gemv_path(form, rel):
     """The same batched steps through the GEMV kernels (threshold raised) and the matrix cores: identical
     traces; outputs equal to within the summation-order noise of fp32 for the form that scales groups in fp32,
@@ -327,16 +327,18 @@ def test_matrix_core_path_agrees_with_gemv_path(form, rel):
     assert d < rel * max(1.0, np.abs(res["gemv"][0]).max()), d
 
 
+@pytest.mark.parametrize("form", [3, 4])
 @pytest.mark.parametrize("Bn,T,k", [(16, 2, 4), (64, 1, 8)])
-def test_mixtral_layer_batch16_matrix_cores(Bn, T, k):
+def test_mixtral_layer_batch16_matrix_cores(Bn, T, k, form):
     """Mixtral-shaped layer on the matrix cores, C oracle on every row: batch 16 with k=4 (8 needed experts over 4
     slots: several passes) and batch 64 with every expert resident (the launch shape bench.py times for the kernels)."""
     c = W.CONFIGS["mixtral_layer"]
     say(f"mixtral layer B={Bn} k={k} matrix cores: build")
     model = Model(1, c.hidden, c.ffn, c.n_experts, c.top_k, None, k, 0, 0.0, max_batch=Bn, seed=c.seed)
+    B.moe_ctx_set_option(model.stack.ctx, "mfma_form", form)
     xs = W.hidden_ar1(c.seed, T, Bn, c.hidden)
     _, sim, errs = run_teacher_forced(model, xs, c_ffn.expert_ffn)
-    say(f"  max abs {max(e[0] for e in errs):.2e} max rel-rms {max(e[1] for e in errs):.2e}")
+    say(f"  form {form}: max abs {max(e[0] for e in errs):.2e} max rel-rms {max(e[1] for e in errs):.2e}")
     model.close()
 
 
@@ -696,7 +698,7 @@ def test_recall_study_tool_against_closed_forms_and_oracle():
     stack.close()
 
 
-@pytest.mark.parametrize("Bn,k,T,form", [(200, 4, 2, 3), (130, 2, 2, 1), (1000, 8, 1, 2), (1024, 2, 1, 3), (300, 4, 1, 2)])
+@pytest.mark.parametrize("Bn,k,T,form", [(200, 4, 2, 3), (130, 2, 2, 1), (1000, 8, 1, 2), (1024, 2, 1, 3), (300, 4, 1, 2), (260, 4, 1, 4)])
 def test_prompt_sized_batches(Bn, k, T, form):
     """Prompt encoding (Sec. 3: prompt tokens go through a layer in parallel, every expert is loaded once for all of
     them) is a step with a large batch: up to MOE_MAX_BATCH = 1024 tokens, through the matrix cores in windows of
@@ -749,7 +751,7 @@ def draw_configuration(seed):
     c["warm"] = c["swap"] or bool(r.rand() < 0.3)
     c["eps"] = pick([0.0, 1e-5])
     c["options"] = {
-        "token_path": pick([1, 1, 0]), "fused": pick([0, 0, 0, 1, 2]), "mfma_form": pick([1, 2, 3]),
+        "token_path": pick([1, 1, 0]), "fused": pick([0, 0, 0, 1, 2]), "mfma_form": pick([1, 2, 3, 4]),
         "mfma_min_batch": pick([16, 16, 2, 1000]), "staged_min_batch": pick([0, 0, 1000]),
         "spec_head_mb": pick([0, 0, 1]), "w13_blocks": pick([256, 64, 24]), "w2_rows": pick([32, 16, 8]),
         "sync_wait": pick([0, 0, 1]),
