@@ -117,7 +117,8 @@ def main() -> int:
                     help="time only every n-th expert transfer with HIP events (1: all; the event pairs slow a saturated link by ~1 %%)")
     ap.add_argument("--spec-head-mb", type=int, default=4,
                     help="speculative loads copy only the first N MiB until the guess is confirmed (0: whole expert, as in the paper)")
-    ap.add_argument("--mfma-form", type=int, default=0, help="matrix-core kernel form 1..3 (0: the library's default)")
+    ap.add_argument("--mfma-form", type=int, default=0, help="matrix-core kernel form 1..4 (0: the library's default)")
+    ap.add_argument("--mfma16-waves", type=int, default=0, help="waves per block of the 16-token matrix-core kernels, 4 or 8 (0: the library's default)")
     ap.add_argument("--fused", type=int, default=-1,
                     help="single-token steps run w1/w3 and w2 as one persistent launch: 1 with a grid barrier, 2 expert after expert; 0 two launches (-1: the library's default)")
     ap.add_argument("--no-token-path", action="store_true", help="single-token steps use the general kernels (atomics + residual kernel)")
@@ -168,6 +169,8 @@ def main() -> int:
     B.moe_ctx_set_option(stack.ctx, "spec_head_mb", args.spec_head_mb)
     if args.mfma_form:
         B.moe_ctx_set_option(stack.ctx, "mfma_form", args.mfma_form)
+    if args.mfma16_waves:
+        B.moe_ctx_set_option(stack.ctx, "mfma16_waves", args.mfma16_waves)
     if args.fused >= 0:
         B.moe_ctx_set_option(stack.ctx, "fused", args.fused)
     if args.no_token_path:

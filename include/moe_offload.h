@@ -318,12 +318,15 @@ int32_t moe_ctx_profile_timeline(moe_ctx_t *ctx, int32_t kind, double *start_ms,
  *                -- the form computes that product in fp16 -- form 2 runs).  1: row-staging kernels that keep the codes
  *                exact and scale every group's product in fp32 (batches of at most 64 tokens, fp16 metadata; otherwise
  *                form 2 runs).  All meet the output tolerance;
+ *   "mfma16_waves" waves per block of form 4's kernels for up to 16 tokens per expert: 8 (default; 126 registers, four
+ *                waves per SIMD) or 4 (150 registers, two groups of a step per wave);
  *   "spec_head_mb" 0 (default): a speculative load copies the whole expert at once, as the paper describes;
  *                N > 0: it copies only the first N MiB, and the rest is fetched (like a demand load) when the next
  *                layer confirms the guess.  Decisions, traces and results are identical; only how many bytes a wrong
  *                guess costs changes (N MiB instead of a whole expert).  Meant for links that are already saturated;
- *   "fused"      1: such a step runs w1/w3 and w2 as ONE persistent launch with a grid barrier (measured
- *                slower than two launches on MI355X, hence default 0);
+ *   "fused"      such a step runs w1/w3 and w2 as ONE persistent launch: 1 with a grid barrier between them, 2 expert
+ *                after expert with one set of flags per expert (both measured slower than two launches on MI355X,
+ *                hence default 0);
  *   "staged_min_batch" matrix-core batches larger than this (default 0: all of them; GEMV batches of more than one
  *                token always) run a step in three stages when every buffer that changes hands in it belonged to an
  *                expert resident at its start: those experts are multiplied first, then the transfers are issued (one

@@ -23,10 +23,18 @@ typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
 constexpr int T16_ST = TL_ROWS / 16;                     // 16-row sub-tiles per item (8)
 
-template <bool W13, int MT>
-__global__ __launch_bounds__(TL_THREADS, TL_BLOCKS_PER_CU) void k_mfma_stream16_q4(TileArgs A)
+// WAVES: 4 (a wave multiplies two groups of a step) or 8 (one group; half the staging and A-operand registers per
+// lane, so that two blocks of 8 waves fit a compute unit: four waves per SIMD).
+template <bool W13, int MT, int WAVES>
+__global__ __launch_bounds__(WAVES *WAVE, TL_BLOCKS_PER_CU) void k_mfma_stream16_q4(TileArgs A)
 {
     static_assert(MT == 1 || MT == 2, "one or two token tiles of 16");
+    static_assert(WAVES == 4 || WAVES == 8, "four or eight waves per block");
+    constexpr int THREADS = WAVES * WAVE;
+    constexpr int GPW = TL_SG / WAVES;                               // groups per wave and step
+    constexpr int CP = TL_ROWS * TL_CPR / THREADS;                   // code pieces per thread and step
+    constexpr int MPIECES = TL_ROWS * TL_MPR;                        // pair pieces per step, at most one per thread
+    static_assert(GPW * WAVES == TL_SG && CP == GPW * TL_RT && MPIECES <= THREADS, "pieces and units must pair up");
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const int tid = threadIdx.x, lane = tid & 63, wv = uniform(tid >> 6);
     const int col = lane & 15, kb = lane >> 4;           // memory row (B) / token (A) of the tile; block of 8 k-slots
@@ -81,9 +89,10 @@ __global__ __launch_bounds__(TL_THREADS, TL_BLOCKS_PER_CU) void k_mfma_stream16_
     };
 
     // ---------------- weights: HBM -> registers -> LDS (as in the streaming kernel) ----------------
-    uint4 st_c[TL_CP], st_m[TL_MP];
+    uint4 st_c[CP], st_m;
     struct FetchCtx { const uint8_t *seg; uint32_t voff; int row0, slab, g0, sg; bool live; };
-    constexpr int SLAB = TL_THREADS / TL_CPR;
+    constexpr int SLAB = THREADS / TL_CPR;
+    static_assert(THREADS % TL_CPR == 0 && 64 % SLAB == 0, "a slab of rows lies wholly inside or outside a matrix of 64 k rows");
     auto fetch_begin = [&](const TileStep &s, bool live) -> FetchCtx {
         enter_item(s);
         FetchCtx f;
@@ -99,27 +108,23 @@ __global__ __launch_bounds__(TL_THREADS, TL_BLOCKS_PER_CU) void k_mfma_stream16_
     auto fetch_codes = [&](const FetchCtx &f, int i) {
         st_c[i] = ldw4(f.seg + (size_t)min(f.row0 + i * f.slab, n_rows - SLAB) * A.stride + f.voff, 0);
     };
-    auto fetch_meta = [&](const FetchCtx &f) {
-#pragma unroll
-        for (int i = 0; i < TL_MP; ++i) {
-            const int p = tid + i * TL_THREADS, r = f.live ? p / TL_MPR : 0, c = p % TL_MPR;
-            const uint8_t *rowp = mat_base + (size_t)min(f.row0 + r, n_rows - 1) * A.stride;
-            st_m[i] = reinterpret_cast<const uint4 *>(rowp + A.meta_off)[f.g0 / 4 + (c < (f.sg + 3) / 4 ? c : 0)];
-        }
+    auto fetch_meta = [&](const FetchCtx &f) {                       // threads past the last piece repeat the last row's
+        const int p = min(tid, MPIECES - 1), r = f.live ? p / TL_MPR : 0, c = p % TL_MPR;
+        const uint8_t *rowp = mat_base + (size_t)min(f.row0 + r, n_rows - 1) * A.stride;
+        st_m = reinterpret_cast<const uint4 *>(rowp + A.meta_off)[f.g0 / 4 + (c < (f.sg + 3) / 4 ? c : 0)];
     };
     auto commit = [&](int b) {
         uint8_t *codes = lds + b * TL_BUF_BYTES;
         uint32_t *meta = reinterpret_cast<uint32_t *>(codes + TL_ROWS * TL_CODE_PITCH);
 #pragma unroll
-        for (int i = 0; i < TL_CP; ++i) {
-            const int p = tid + i * TL_THREADS, r = p / TL_CPR, c = p % TL_CPR;
+        for (int i = 0; i < CP; ++i) {
+            const int p = tid + i * THREADS, r = p / TL_CPR, c = p % TL_CPR;
             *reinterpret_cast<uint4 *>(codes + r * TL_CODE_PITCH + c * 16) = st_c[i];
         }
-#pragma unroll
-        for (int i = 0; i < TL_MP; ++i) {
-            const int p = tid + i * TL_THREADS, r = p / TL_MPR, c = p % TL_MPR;
+        if (tid < MPIECES) {
+            const int r = tid / TL_MPR, c = tid % TL_MPR;
             uint32_t *d = meta + r * TL_META_PITCH + c * 4;
-            d[0] = st_m[i].x; d[1] = st_m[i].y; d[2] = st_m[i].z; d[3] = st_m[i].w;
+            d[0] = st_m.x; d[1] = st_m.y; d[2] = st_m.z; d[3] = st_m.w;
         }
     };
 
@@ -130,13 +135,13 @@ __global__ __launch_bounds__(TL_THREADS, TL_BLOCKS_PER_CU) void k_mfma_stream16_
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) acc[st][mt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
     // A operands of one group: [token tile][k-step]; piece q = mt * 2 + kk
-    auto load_a_piece = [&](h8_t (&dst)[TL_GPW][2 * MT], const TileStep &s, int j, int q) {
-        const int g = s.seg * TL_SG + min(wv + TL_WAVES * j, seg_groups(s) - 1);
+    auto load_a_piece = [&](h8_t (&dst)[GPW][2 * MT], const TileStep &s, int j, int q) {
+        const int g = s.seg * TL_SG + min(wv + WAVES * j, seg_groups(s) - 1);
         const uint8_t *grp = reinterpret_cast<const uint8_t *>(A.act) + (size_t)g * 128 + (q & 1) * 64;
         dst[j][q] = __builtin_bit_cast(h8_t, *reinterpret_cast<const uint4 *>(grp + act_off[q >> 1]));
     };
-    static_assert(TL_CP == TL_GPW * TL_RT && TL_RT == 4, "one piece of codes per unit");
-    auto load_piece = [&](const FetchCtx &f, h8_t (&a_dst)[TL_GPW][2 * MT], const TileStep &s, int u) {
+    static_assert(TL_RT == 4, "four 32-row tiles per item");
+    auto load_piece = [&](const FetchCtx &f, h8_t (&a_dst)[GPW][2 * MT], const TileStep &s, int u) {
         if (u % TL_RT < 2 * MT) load_a_piece(a_dst, s, u / TL_RT, u % TL_RT);
         if (u == 0) fetch_meta(f);
         fetch_codes(f, u);
@@ -179,19 +184,21 @@ __global__ __launch_bounds__(TL_THREADS, TL_BLOCKS_PER_CU) void k_mfma_stream16_
         for (int rt = 0; rt < TL_RT; ++rt) {
             const UnitRegs u = u_next;
             if (rt + 1 < TL_RT) unit_load(b, gl, rt + 1, u_next);
-            else if (gl + TL_WAVES < sg) unit_load(b, gl + TL_WAVES, 0, u_next);
+            else if (j + 1 < GPW && gl + WAVES < sg) unit_load(b, gl + WAVES, 0, u_next);
             beside(j * TL_RT + rt);
             unit_multiply(a, u, rt);
         }
     };
 
     // ---------------- end of an item: add the four waves' partial sums, finish, store ----------------
-    // One round per token tile through LDS buffer b (free: every wave is past its last read of it): every wave
-    // writes its 8 sub-tiles x 4 registers, then wave v adds the four waves' values of sub-tiles 2v and 2v+1.
-    static_assert(TL_WAVES * T16_ST * 4 * 64 * 4 <= TL_BUF_BYTES && T16_ST % TL_WAVES == 0, "one reduction round must fit a staging buffer");
-    constexpr int ST_PER_WAVE = T16_ST / TL_WAVES;
+    // Rounds through LDS buffer b (free: every wave is past its last read of it).  A round takes RS sub-tiles of one
+    // token tile: every wave writes its RS x 4 registers of them, then the RS x 4 registers are shared evenly among
+    // the waves, wave v adding all waves' values of NI consecutive ones, always in the order of the waves.
+    constexpr int RS = WAVES == 4 ? T16_ST : T16_ST / 2;             // sub-tiles per round
+    constexpr int NI = RS * 4 / WAVES;                               // registers a wave finishes per round (8 or 2)
+    static_assert(WAVES * RS * 4 * 64 * 4 <= TL_BUF_BYTES && NI * WAVES == RS * 4 && 4 % (NI < 4 ? NI : 4) == 0, "one reduction round must fit a staging buffer");
     auto finish_item = [&](const TileStep &s, int b) {
-        float *red = reinterpret_cast<float *>(lds + b * TL_BUF_BYTES);   // [wave][sub-tile][4][64]
+        float *red = reinterpret_cast<float *>(lds + b * TL_BUF_BYTES);   // [wave][sub-tile of the round][4][64]
         const MfmaEntry &en = A.e[s.e];
         const int part = s.it % A.k_parts;
         if (!W13 && s.rb == 0 && part == 0 && tid < en.n_tok) {      // one block per entry tells k_combine where the rows are
@@ -200,25 +207,25 @@ __global__ __launch_bounds__(TL_THREADS, TL_BLOCKS_PER_CU) void k_mfma_stream16_
             A.ytab[l_pair[tk]] = y_rows((uint32_t)(row + A.row_bias), (uint32_t)A.k_parts);
         }
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-            __syncthreads();                                         // buffer free (first round) / previous round read
+        for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-            for (int st = 0; st < T16_ST; ++st)
+            for (int r0 = 0; r0 < T16_ST; r0 += RS) {
+                __syncthreads();                                     // buffer free (first round) / previous round read
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    red[((wv * T16_ST + st) * 4 + i) * 64 + lane] = acc[st][mt][i];
-                    acc[st][mt][i] = 0.f;
-                }
-            __syncthreads();
+                for (int sl = 0; sl < RS; ++sl)
 #pragma unroll
-            for (int ss = 0; ss < ST_PER_WAVE; ++ss) {
-                const int st = wv * ST_PER_WAVE + ss;
-                const int mrow = s.rb * TL_ROWS + st * 16 + col;
+                    for (int i = 0; i < 4; ++i) {
+                        red[((wv * RS + sl) * 4 + i) * 64 + lane] = acc[r0 + sl][mt][i];
+                        acc[r0 + sl][mt][i] = 0.f;
+                    }
+                __syncthreads();
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
+                for (int ii = 0; ii < NI; ++ii) {
+                    const int flat = wv * NI + ii, sl = flat / 4, i = flat % 4;
+                    const int mrow = s.rb * TL_ROWS + (r0 + sl) * 16 + col;
                     float v = 0.f;
 #pragma unroll
-                    for (int w = 0; w < TL_WAVES; ++w) v += red[((w * T16_ST + st) * 4 + i) * 64 + lane];
+                    for (int w = 0; w < WAVES; ++w) v += red[((w * RS + sl) * 4 + i) * 64 + lane];
                     const int tok = mt * 16 + 4 * kb + i;            // token of the entry this register belongs to
                     const int tk = en.first + min(tok, en.n_tok - 1);
                     if (W13) {
@@ -231,28 +238,24 @@ __global__ __launch_bounds__(TL_THREADS, TL_BLOCKS_PER_CU) void k_mfma_stream16_
                     }
                 }
             }
-        }
     };
 
     // ---------------- one step; true when it was the block's last ----------------
-    auto step = [&](const h8_t (&a_use)[TL_GPW][2 * MT], h8_t (&a_load)[TL_GPW][2 * MT]) -> bool {
+    auto step = [&](const h8_t (&a_use)[GPW][2 * MT], h8_t (&a_load)[GPW][2 * MT]) -> bool {
         const bool item_ends = !nxt.valid || nxt.it != cur.it;
         const TileStep &ld = nxt.valid ? nxt : cur;                  // past the last step: 16 bytes re-read, never used
         const FetchCtx f = fetch_begin(ld, nxt.valid);
         auto beside = [&](int u) { load_piece(f, a_load, ld, u); };
         const int sg = seg_groups(cur);
-        if (wv < sg) {
-            unit_load(buf, wv, 0, u_next);
-            group_multiply(a_use[0], buf, wv, sg, 0, beside);
-        } else {
+        if (wv < sg) unit_load(buf, wv, 0, u_next);
 #pragma unroll
-            for (int u = 0; u < TL_RT; ++u) beside(u);
-        }
-        if (wv + TL_WAVES < sg) {
-            group_multiply(a_use[1], buf, wv + TL_WAVES, sg, 1, beside);
-        } else {
+        for (int j = 0; j < GPW; ++j) {
+            if (wv + WAVES * j < sg) {
+                group_multiply(a_use[j], buf, wv + WAVES * j, sg, j, beside);
+            } else {
 #pragma unroll
-            for (int u = TL_RT; u < 2 * TL_RT; ++u) beside(u);
+                for (int u = j * TL_RT; u < (j + 1) * TL_RT; ++u) beside(u);
+            }
         }
         if (item_ends) finish_item(cur, buf);
         commit(buf ^ 1);
@@ -264,11 +267,11 @@ __global__ __launch_bounds__(TL_THREADS, TL_BLOCKS_PER_CU) void k_mfma_stream16_
         return false;
     };
 
-    h8_t a0[TL_GPW][2 * MT], a1[TL_GPW][2 * MT];
+    h8_t a0[GPW][2 * MT], a1[GPW][2 * MT];
     {
         const FetchCtx f = fetch_begin(cur, true);
 #pragma unroll
-        for (int u = 0; u < TL_CP; ++u) load_piece(f, a0, cur, u);
+        for (int u = 0; u < CP; ++u) load_piece(f, a0, cur, u);
     }
     commit(0);
     __builtin_amdgcn_s_waitcnt(0x0F70);                              // vmcnt(0): the loop starts with nothing in flight

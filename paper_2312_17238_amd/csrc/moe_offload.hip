@@ -163,6 +163,8 @@ struct moe_ctx {
     int32_t mfma_form = 0;              // matrix-core kernels: 0 by the tokens per expert (4 up to sixteen, else 3); 4 streaming form with 16-token tiles;
                                         // 3 streaming form, one fma per pair of weights plus a rank-1 correction;
                                         // 2 streaming form with an exact subtraction first; 1 row-staging form with fp32 group scaling
+    int32_t mfma16_waves = 8;           // waves per block of the 16-token form's single-tile kernels: 4 or 8 (two blocks per compute unit either
+                                        // way; with two token tiles 8 waves need 170 registers, one block per unit, and measured 20 % slower)
     int32_t mfma_min_batch = 16;        // batches at least this large use the matrix-core kernels (4-bit g64)
     int32_t staged_min_batch = 0;       // matrix-core batches larger than this: resident experts first, arriving ones one by one
     uint64_t spec_head_bytes = 0;       // 0: a speculative load moves the whole expert at once (as the paper describes);
@@ -1319,10 +1321,12 @@ static int32_t launch_mfma_stream(moe_layer *l, const std::vector<PassExpert> &e
         HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_stream_q4<false, true>), hipFuncAttributeMaxDynamicSharedMemorySize, TL_LDS_BYTES));
         HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_stream_q4<true, false, true>), hipFuncAttributeMaxDynamicSharedMemorySize, TL_LDS_BYTES));
         HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_stream_q4<false, false, true>), hipFuncAttributeMaxDynamicSharedMemorySize, TL_LDS_BYTES));
-        HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_stream16_q4<true, 1>), hipFuncAttributeMaxDynamicSharedMemorySize, TL_LDS_BYTES));
-        HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_stream16_q4<true, 2>), hipFuncAttributeMaxDynamicSharedMemorySize, TL_LDS_BYTES));
-        HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_stream16_q4<false, 1>), hipFuncAttributeMaxDynamicSharedMemorySize, TL_LDS_BYTES));
-        HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_stream16_q4<false, 2>), hipFuncAttributeMaxDynamicSharedMemorySize, TL_LDS_BYTES));
+        HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_stream16_q4<true, 1, 4>), hipFuncAttributeMaxDynamicSharedMemorySize, TL_LDS_BYTES));
+        HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_stream16_q4<true, 2, 4>), hipFuncAttributeMaxDynamicSharedMemorySize, TL_LDS_BYTES));
+        HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_stream16_q4<false, 1, 4>), hipFuncAttributeMaxDynamicSharedMemorySize, TL_LDS_BYTES));
+        HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_stream16_q4<false, 2, 4>), hipFuncAttributeMaxDynamicSharedMemorySize, TL_LDS_BYTES));
+        HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_stream16_q4<true, 1, 8>), hipFuncAttributeMaxDynamicSharedMemorySize, TL_LDS_BYTES));
+        HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_stream16_q4<false, 1, 8>), hipFuncAttributeMaxDynamicSharedMemorySize, TL_LDS_BYTES));
         lds_attr_set = true;
     }
     const int n_cu = c->n_cu > 0 ? c->n_cu : 256;
@@ -1390,8 +1394,10 @@ static int32_t launch_mfma_stream(moe_layer *l, const std::vector<PassExpert> &e
         A.K = b.hidden; A.N = b.ffn; A.stride = b.m13.row_stride; A.meta_off = b.m13.meta_off; A.mat_off = b.off_w13;
         A.meta2_off = b.m13.meta2_off; A.run_shift = run_shift(b.m13);
         const dim3 g13 = shape(2 * b.ffn, b.hidden, false);
-        int32_t rc = t16 ? (max_tok <= 16 ? launch_timed(c, PROF_W13, bytes13, k_mfma_stream16_q4<true, 1>, g13, dim3(TL_THREADS), TL_LDS_BYTES, A)
-                                          : launch_timed(c, PROF_W13, bytes13, k_mfma_stream16_q4<true, 2>, g13, dim3(TL_THREADS), TL_LDS_BYTES, A))
+        const bool w8 = c->mfma16_waves == 8;
+        int32_t rc = t16 ? (max_tok <= 16 ? (w8 ? launch_timed(c, PROF_W13, bytes13, k_mfma_stream16_q4<true, 1, 8>, g13, dim3(512), TL_LDS_BYTES, A)
+                                                : launch_timed(c, PROF_W13, bytes13, k_mfma_stream16_q4<true, 1, 4>, g13, dim3(TL_THREADS), TL_LDS_BYTES, A))
+                                          : launch_timed(c, PROF_W13, bytes13, k_mfma_stream16_q4<true, 2, 4>, g13, dim3(TL_THREADS), TL_LDS_BYTES, A))
                      : meta8 ? launch_timed(c, PROF_W13, bytes13, k_mfma_stream_q4<true, true>, g13, dim3(TL_THREADS), TL_LDS_BYTES, A)
                      : r1  ? launch_timed(c, PROF_W13, bytes13, k_mfma_stream_q4<true, false, true>, g13, dim3(TL_THREADS), TL_LDS_BYTES, A)
                            : launch_timed(c, PROF_W13, bytes13, k_mfma_stream_q4<true, false>, g13, dim3(TL_THREADS), TL_LDS_BYTES, A);
@@ -1404,8 +1410,9 @@ static int32_t launch_mfma_stream(moe_layer *l, const std::vector<PassExpert> &e
             A.part_base = (int32_t)((uint64_t)batch * K + c->ypart_extra_used / b.hidden) - w0 * K;
             c->ypart_extra_used += (uint64_t)first * A.k_parts * b.hidden;
         }
-        rc = t16 ? (max_tok <= 16 ? launch_timed(c, PROF_W2, bytes2, k_mfma_stream16_q4<false, 1>, g2, dim3(TL_THREADS), TL_LDS_BYTES, A)
-                                  : launch_timed(c, PROF_W2, bytes2, k_mfma_stream16_q4<false, 2>, g2, dim3(TL_THREADS), TL_LDS_BYTES, A))
+        rc = t16 ? (max_tok <= 16 ? (w8 ? launch_timed(c, PROF_W2, bytes2, k_mfma_stream16_q4<false, 1, 8>, g2, dim3(512), TL_LDS_BYTES, A)
+                                        : launch_timed(c, PROF_W2, bytes2, k_mfma_stream16_q4<false, 1, 4>, g2, dim3(TL_THREADS), TL_LDS_BYTES, A))
+                                  : launch_timed(c, PROF_W2, bytes2, k_mfma_stream16_q4<false, 2, 4>, g2, dim3(TL_THREADS), TL_LDS_BYTES, A))
              : meta8 ? launch_timed(c, PROF_W2, bytes2, k_mfma_stream_q4<false, true>, g2, dim3(TL_THREADS), TL_LDS_BYTES, A)
              : r1  ? launch_timed(c, PROF_W2, bytes2, k_mfma_stream_q4<false, false, true>, g2, dim3(TL_THREADS), TL_LDS_BYTES, A)
                    : launch_timed(c, PROF_W2, bytes2, k_mfma_stream_q4<false, false>, g2, dim3(TL_THREADS), TL_LDS_BYTES, A);
@@ -2041,6 +2048,7 @@ try {
     else if (n == "spec_head_mb" && value >= 0) c->spec_head_bytes = (uint64_t)value << 20;
     else if (n == "mfma_min_batch" && value >= 1) c->mfma_min_batch = value;
     else if (n == "mfma_form" && value >= 0 && value <= 4) c->mfma_form = value;
+    else if (n == "mfma16_waves" && (value == 4 || value == 8)) c->mfma16_waves = value;
     else if (n == "device_routing") c->device_routing = value != 0;
     else if (n == "staged_min_batch" && value >= 0) c->staged_min_batch = value;
     else if (n == "profile_copy_stride" && value >= 1) c->prof.copy_stride = value;

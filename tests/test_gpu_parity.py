@@ -293,6 +293,7 @@ def test_small_stack_matrix_core_path(Bn, k, form):
     say(f"matrix-core stack B={Bn} k={k} form={form}")
     model = Model(L, H, F, 8, 2, None, k, 2, 1e-5, max_batch=Bn, seed=41)
     B.moe_ctx_set_option(model.stack.ctx, "mfma_form", form)
+    B.moe_ctx_set_option(model.stack.ctx, "mfma16_waves", 8 if k == 4 else 4)
     B.moe_ctx_profile_enable(model.stack.ctx, True)
     xs = W.hidden_ar1(41, 5, Bn, H)
     _, sim, errs = run_teacher_forced(model, xs, O.expert_ffn)
@@ -336,6 +337,7 @@ def test_mixtral_layer_batch16_matrix_cores(Bn, T, k, form):
     say(f"mixtral layer B={Bn} k={k} matrix cores: build")
     model = Model(1, c.hidden, c.ffn, c.n_experts, c.top_k, None, k, 0, 0.0, max_batch=Bn, seed=c.seed)
     B.moe_ctx_set_option(model.stack.ctx, "mfma_form", form)
+    B.moe_ctx_set_option(model.stack.ctx, "mfma16_waves", 8)
     xs = W.hidden_ar1(c.seed, T, Bn, c.hidden)
     _, sim, errs = run_teacher_forced(model, xs, c_ffn.expert_ffn)
     say(f"  form {form}: max abs {max(e[0] for e in errs):.2e} max rel-rms {max(e[1] for e in errs):.2e}")
@@ -751,7 +753,7 @@ def draw_configuration(seed):
     c["warm"] = c["swap"] or bool(r.rand() < 0.3)
     c["eps"] = pick([0.0, 1e-5])
     c["options"] = {
-        "token_path": pick([1, 1, 0]), "fused": pick([0, 0, 0, 1, 2]), "mfma_form": pick([1, 2, 3, 4]),
+        "token_path": pick([1, 1, 0]), "fused": pick([0, 0, 0, 1, 2]), "mfma_form": pick([1, 2, 3, 4, 0]), "mfma16_waves": pick([4, 8]),
         "mfma_min_batch": pick([16, 16, 2, 1000]), "staged_min_batch": pick([0, 0, 1000]),
         "spec_head_mb": pick([0, 0, 1]), "w13_blocks": pick([256, 64, 24]), "w2_rows": pick([32, 16, 8]),
         "sync_wait": pick([0, 0, 1]),
