@@ -224,9 +224,9 @@ int32_t moe_layer_step(moe_layer_t *layer, moe_layer_t *next, const uint16_t *x_
 /* moe_layer_step for callers that cannot allocate device memory: code that runs while a HIP graph is being captured
  * elsewhere in the process, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same decisions,
  * traces and results as moe_layer_step, computed by the same kernels; the difference is where those kernels keep
- * their intermediate results (the gate input h, the SwiGLU activations a, the fp32 block output y): not in the
- * context's arena but in a fixed array inside the library's own device image (about 0.7 MB, held by every GPU the
- * library runs on until the process ends).  The call makes no device or pinned-host allocation, frees none and
+ * their intermediate results (the gate input h, the SwiGLU activations a, the pairs' fp32 partial outputs, the block
+ * output y): not in the context's arena but in a fixed array inside the library's own device image (1.2 MB, held by
+ * every GPU the library runs on until the process ends).  The call makes no device or pinned-host allocation, frees none and
  * creates no stream or event; its host-side bookkeeping uses the ordinary C++ heap.  Limits, checked with MOE_EINVAL:
  * batch <= 4, hidden <= 8192, ffn <= 16384, top_k <= 4.  MOE_ESTATE while launch timing (moe_ctx_profile_enable) is on,
  * and in a host-only context.  The host always waits for the gate here (no device-routed steps) and option "fused" is
