@@ -117,7 +117,7 @@ def main() -> int:
                     help="time only every n-th expert transfer with HIP events (1: all; the event pairs slow a saturated link by ~1 %%)")
     ap.add_argument("--spec-head-mb", type=int, default=4,
                     help="speculative loads copy only the first N MiB until the guess is confirmed (0: whole expert, as in the paper)")
-    ap.add_argument("--mfma-form", type=int, default=0, help="matrix-core kernel form 1..4 (0: the library's default)")
+    ap.add_argument("--mfma-form", type=int, default=0, help="matrix-core kernel form 1..5 (0: the library's default)")
     ap.add_argument("--mfma16-waves", type=int, default=0, help="waves per block of the 16-token matrix-core kernels, 4 or 8 (0: the library's default)")
     ap.add_argument("--fused", type=int, default=-1,
                     help="single-token steps run w1/w3 and w2 as one persistent launch: 1 with a grid barrier, 2 expert after expert; 0 two launches (-1: the library's default)")

@@ -7,10 +7,27 @@
 // 8 x MT x 4 accumulator registers for the same 128 memory rows of an item, one A operand of 16 bytes per lane,
 // k-step and token tile (lanes of one token read 64 consecutive bytes), and half the matrix instructions' work.
 //
-// Everything around the multiply is the streaming kernel's: items, steps of 8 groups, HBM -> registers -> LDS copies in
-// eight pieces beside the units of the multiply, one barrier per step, partial sums of the four waves added through
-// the LDS buffer just consumed in a fixed order, the same epilogues.  The weights are dequantised as in its form 2
-// (exact q - rint(z), one fused multiply-add, one rounding to fp16; fp16 (scale, zero) pairs).
+// Items, steps of 8 groups, the two LDS buffers, the fixed-order reduction of the waves' partial sums through the
+// buffer just consumed and the epilogues are the streaming kernel's.  The weights are dequantised as in its form 2
+// (exact q - rint(z), one fused multiply-add, one rounding to fp16; fp16 (scale, zero) pairs) unless GS is set.
+//
+// Loads: two steps of weights are on their way at any time.  While step n is multiplied out of one LDS buffer, step
+// n + 1 sits in (or is still arriving in) the staging registers; at the END of step n it is written to the other
+// buffer, piece by piece, and each register takes a piece of step n + 2 as soon as it is free.  A step's loads so have
+// a whole step to arrive and a block never has less than a step's bytes in flight.  The loop has ONE body, the A
+// operands of the next step handed over by register copies at its end: with two alternating copies of the body the
+// compiler's placement of the waits for loads merges the paths through both and makes every second step wait for
+// everything in flight.
+//
+// GS ("group-scaled"): the weights are not dequantised at all.  The codes enter the matrix cores as the fp16 numbers
+// 1024 + q and 64 + q that the bit patterns 0x6400 | q and 0x5400 | q << 4 spell (one v_and_or_b32 per pair, nothing
+// else per weight).  Per group and token tile, four matrix instructions against constant B operands give, in fp32 and
+// already in the accumulators' layout, X = the sum of the group's activations per token (B all ones) and
+// -P = -(1024 X_a + 64 X_b), X_a and X_b the sums over the k-slots that meet a code with bias 1024 and 64 (B = -1024
+// and -64 in those slots).  A (sub-tile, group) product then starts from -P instead of zero, which takes the biases out
+// again, and two fp32 multiply-adds per accumulator register finish it: total += s (product - z X).  No weight is
+// rounded to fp16, nothing depends on the size of the activations (every sum is an fp32 one), 18 vector instructions
+// per (sub-tile, group) instead of 42.
 //
 // MFMA layouts (v_mfma_f32_16x16x32_f16): A lane l = row (token) l%16, k-slots 8*(l/16)..+7; B lane l = column (memory
 // row) l%16, k-slots 8*(l/16)..+7; D lane l, register i = row 4*(l/16) + i, column l%16.
@@ -23,10 +40,30 @@ typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
 constexpr int T16_ST = TL_ROWS / 16;                     // 16-row sub-tiles per item (8)
 
+// The masks and exponent patterns of the code -> fp16 trick as values the compiler cannot see through: with the mask
+// in a scalar and the pattern in a vector register it then selects one v_and_or_b32 per pair by itself.  The inline
+// assembly of and_or() must not feed a matrix instruction directly: the compiler does not know that it writes a
+// vector register and leaves out the two wait states that such a write needs before a matrix instruction reads it.
+struct BiasPatterns { uint32_t m_lo, m_hi, k1024, k64; };
+__device__ __forceinline__ BiasPatterns bias_patterns()
+{
+    BiasPatterns p = {0x000F000Fu, 0x00F000F0u, 0x64006400u, 0x54005400u};
+    asm("" : "+s"(p.m_lo), "+s"(p.m_hi), "+v"(p.k1024), "+v"(p.k64));
+    return p;
+}
+
+// eight codes as the fp16 numbers bias + q: slots 0, 1, 4, 5 with bias 1024, slots 2, 3, 6, 7 with bias 64
+__device__ __forceinline__ h8_t codes_biased(uint32_t w, const BiasPatterns &p)
+{
+    const uint32_t hi = w >> 8;
+    const u32x4_t r = {(w & p.m_lo) | p.k1024, (w & p.m_hi) | p.k64, (hi & p.m_lo) | p.k1024, (hi & p.m_hi) | p.k64};
+    return __builtin_bit_cast(h8_t, r);
+}
+
 // WAVES: 4 (a wave multiplies two groups of a step) or 8 (one group; half the staging and A-operand registers per
-// lane, so that two blocks of 8 waves fit a compute unit: four waves per SIMD).
-template <bool W13, int MT, int WAVES>
-__global__ __launch_bounds__(WAVES *WAVE, TL_BLOCKS_PER_CU) void k_mfma_stream16_q4(TileArgs A)
+// lane, so that two blocks of 8 waves fit a compute unit: four waves per SIMD, which is the second launch bound).
+template <bool W13, int MT, int WAVES, bool GS = false>
+__global__ __launch_bounds__(WAVES *WAVE, (WAVES == 8 && MT == 1 ? 4 : 2)) void k_mfma_stream16_q4(TileArgs A)
 {
     static_assert(MT == 1 || MT == 2, "one or two token tiles of 16");
     static_assert(WAVES == 4 || WAVES == 8, "four or eight waves per block");
@@ -108,19 +145,18 @@ __global__ __launch_bounds__(WAVES *WAVE, TL_BLOCKS_PER_CU) void k_mfma_stream16
     auto fetch_codes = [&](const FetchCtx &f, int i) {
         st_c[i] = ldw4(f.seg + (size_t)min(f.row0 + i * f.slab, n_rows - SLAB) * A.stride + f.voff, 0);
     };
+    auto commit_codes = [&](int b, int i) {
+        uint8_t *codes = lds + b * TL_BUF_BYTES;
+        const int p = tid + i * THREADS, r = p / TL_CPR, c = p % TL_CPR;
+        *reinterpret_cast<uint4 *>(codes + r * TL_CODE_PITCH + c * 16) = st_c[i];
+    };
     auto fetch_meta = [&](const FetchCtx &f) {                       // threads past the last piece repeat the last row's
         const int p = min(tid, MPIECES - 1), r = f.live ? p / TL_MPR : 0, c = p % TL_MPR;
         const uint8_t *rowp = mat_base + (size_t)min(f.row0 + r, n_rows - 1) * A.stride;
         st_m = reinterpret_cast<const uint4 *>(rowp + A.meta_off)[f.g0 / 4 + (c < (f.sg + 3) / 4 ? c : 0)];
     };
-    auto commit = [&](int b) {
-        uint8_t *codes = lds + b * TL_BUF_BYTES;
-        uint32_t *meta = reinterpret_cast<uint32_t *>(codes + TL_ROWS * TL_CODE_PITCH);
-#pragma unroll
-        for (int i = 0; i < CP; ++i) {
-            const int p = tid + i * THREADS, r = p / TL_CPR, c = p % TL_CPR;
-            *reinterpret_cast<uint4 *>(codes + r * TL_CODE_PITCH + c * 16) = st_c[i];
-        }
+    auto commit_meta = [&](int b) {
+        uint32_t *meta = reinterpret_cast<uint32_t *>(lds + b * TL_BUF_BYTES + TL_ROWS * TL_CODE_PITCH);
         if (tid < MPIECES) {
             const int r = tid / TL_MPR, c = tid % TL_MPR;
             uint32_t *d = meta + r * TL_META_PITCH + c * 4;
@@ -141,11 +177,6 @@ __global__ __launch_bounds__(WAVES *WAVE, TL_BLOCKS_PER_CU) void k_mfma_stream16
         dst[j][q] = __builtin_bit_cast(h8_t, *reinterpret_cast<const uint4 *>(grp + act_off[q >> 1]));
     };
     static_assert(TL_RT == 4, "four 32-row tiles per item");
-    auto load_piece = [&](const FetchCtx &f, h8_t (&a_dst)[GPW][2 * MT], const TileStep &s, int u) {
-        if (u % TL_RT < 2 * MT) load_a_piece(a_dst, s, u / TL_RT, u % TL_RT);
-        if (u == 0) fetch_meta(f);
-        fetch_codes(f, u);
-    };
     // One unit = one group of one 32-row tile = two 16-row sub-tiles; its code words (two per sub-tile: this lane's
     // block of 8 k-slots in each half of the group) and pairs are read from LDS one unit ahead of their use.
     struct UnitRegs { uint32_t q[2][2], m[2]; };
@@ -161,9 +192,38 @@ __global__ __launch_bounds__(WAVES *WAVE, TL_BLOCKS_PER_CU) void k_mfma_stream16
             u.m[h] = meta[r * TL_META_PITCH + gl];
         }
     };
+    // GS: per token of the lane's accumulator rows, the group's activation sum and minus the biases' share
+    f32x4_t g_x[MT], g_negp[MT];
+    const BiasPatterns bp = bias_patterns();
+    auto group_sums = [&](const h8_t (&a)[2 * MT]) {
+        const u32x4_t ones = {0x3C003C00u, 0x3C003C00u, 0x3C003C00u, 0x3C003C00u};       // 1, 1, ...
+        const u32x4_t negb = {0xE400E400u, 0xD400D400u, 0xE400E400u, 0xD400D400u};       // -1024, -1024, -64, -64, ...
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            const f32x4_t zero = {0.f, 0.f, 0.f, 0.f};
+            g_x[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[mt * 2], __builtin_bit_cast(h8_t, ones), zero, 0, 0, 0);
+            g_x[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[mt * 2 + 1], __builtin_bit_cast(h8_t, ones), g_x[mt], 0, 0, 0);
+            g_negp[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[mt * 2], __builtin_bit_cast(h8_t, negb), zero, 0, 0, 0);
+            g_negp[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[mt * 2 + 1], __builtin_bit_cast(h8_t, negb), g_negp[mt], 0, 0, 0);
+        }
+    };
     auto unit_multiply = [&](const h8_t (&a)[2 * MT], const UnitRegs &u, int rt) {
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
+            if constexpr (GS) {
+                const float s32 = (float)__builtin_bit_cast(_Float16, (uint16_t)(u.m[h] & 0xffff));
+                const float nz32 = -(float)__builtin_bit_cast(_Float16, (uint16_t)(u.m[h] >> 16));
+                const h8_t b0 = codes_biased(u.q[h][0], bp), b1 = codes_biased(u.q[h][1], bp);
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) {
+                    f32x4_t g = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[mt * 2], b0, g_negp[mt], 0, 0, 0);
+                    g = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[mt * 2 + 1], b1, g, 0, 0, 0);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        acc[rt * 2 + h][mt][i] = __builtin_fmaf(s32, __builtin_fmaf(nz32, g_x[mt][i], g[i]), acc[rt * 2 + h][mt][i]);
+                }
+                continue;
+            }
             const _Float16 s16 = __builtin_bit_cast(_Float16, (uint16_t)(u.m[h] & 0xffff));
             const _Float16 z16 = __builtin_bit_cast(_Float16, (uint16_t)(u.m[h] >> 16));
             const _Float16 zi = __builtin_rintf16(z16);
@@ -179,13 +239,13 @@ __global__ __launch_bounds__(WAVES *WAVE, TL_BLOCKS_PER_CU) void k_mfma_stream16
         }
     };
     UnitRegs u_next = {};
-    auto group_multiply = [&](const h8_t (&a)[2 * MT], int b, int gl, int sg, int j, auto &&beside) {   // u_next holds tile 0 of group gl
+    auto group_multiply = [&](const h8_t (&a)[2 * MT], int b, int gl, int sg, int j) {   // u_next holds tile 0 of group gl
+        if constexpr (GS) group_sums(a);
 #pragma unroll
         for (int rt = 0; rt < TL_RT; ++rt) {
             const UnitRegs u = u_next;
             if (rt + 1 < TL_RT) unit_load(b, gl, rt + 1, u_next);
             else if (j + 1 < GPW && gl + WAVES < sg) unit_load(b, gl + WAVES, 0, u_next);
-            beside(j * TL_RT + rt);
             unit_multiply(a, u, rt);
         }
     };
@@ -240,45 +300,71 @@ __global__ __launch_bounds__(WAVES *WAVE, TL_BLOCKS_PER_CU) void k_mfma_stream16
             }
     };
 
-    // ---------------- one step; true when it was the block's last ----------------
-    auto step = [&](const h8_t (&a_use)[GPW][2 * MT], h8_t (&a_load)[GPW][2 * MT]) -> bool {
-        const bool item_ends = !nxt.valid || nxt.it != cur.it;
+    // ---------------- the steps ----------------
+    h8_t a0[GPW][2 * MT], a1[GPW][2 * MT];                           // this step's A operands, the next step's
+    auto load_a = [&](h8_t (&dst)[GPW][2 * MT], const TileStep &s) {
+#pragma unroll
+        for (int j = 0; j < GPW; ++j)
+#pragma unroll
+            for (int q = 0; q < 2 * MT; ++q) load_a_piece(dst, s, j, q);
+    };
+    TileStep nxt2 = next(nxt);
+    {
+        const FetchCtx f = fetch_begin(cur, true);
+        fetch_meta(f);
+#pragma unroll
+        for (int i = 0; i < CP; ++i) fetch_codes(f, i);
+        load_a(a0, cur);
+    }
+#pragma unroll
+    for (int i = 0; i < CP; ++i) commit_codes(0, i);
+    commit_meta(0);
+    // Everything of step 0 has arrived before step 1 is requested: the compiler places the waits inside the loop from
+    // the order in which loads can be outstanding on ANY path into it.
+    __builtin_amdgcn_s_waitcnt(0x0F70);                              // vmcnt(0)
+    {
         const TileStep &ld = nxt.valid ? nxt : cur;                  // past the last step: 16 bytes re-read, never used
         const FetchCtx f = fetch_begin(ld, nxt.valid);
-        auto beside = [&](int u) { load_piece(f, a_load, ld, u); };
+        fetch_meta(f);
+#pragma unroll
+        for (int i = 0; i < CP; ++i) fetch_codes(f, i);
+        load_a(a1, ld);
+    }
+    __syncthreads();
+    while (true) {
+        const bool item_ends = !nxt.valid || nxt.it != cur.it;
         const int sg = seg_groups(cur);
         if (wv < sg) unit_load(buf, wv, 0, u_next);
 #pragma unroll
-        for (int j = 0; j < GPW; ++j) {
-            if (wv + WAVES * j < sg) {
-                group_multiply(a_use[j], buf, wv + WAVES * j, sg, j, beside);
-            } else {
-#pragma unroll
-                for (int u = j * TL_RT; u < (j + 1) * TL_RT; ++u) beside(u);
-            }
-        }
+        for (int j = 0; j < GPW; ++j)
+            if (wv + WAVES * j < sg) group_multiply(a0[j], buf, wv + WAVES * j, sg, j);
         if (item_ends) finish_item(cur, buf);
-        commit(buf ^ 1);
-        __syncthreads();                                             // next buffer filled, this one free again
-        if (!nxt.valid) return true;
-        cur = nxt;
-        nxt = next(cur);
-        buf ^= 1;
-        return false;
-    };
-
-    h8_t a0[GPW][2 * MT], a1[GPW][2 * MT];
-    {
-        const FetchCtx f = fetch_begin(cur, true);
+        // step n + 1 from the registers into the other buffer, step n + 2 into the registers
+        const TileStep &ld = nxt2.valid ? nxt2 : cur;                // past the last step: 16 bytes re-read, never used
+        const FetchCtx f = fetch_begin(ld, nxt2.valid);
+        commit_meta(buf ^ 1);
+        fetch_meta(f);
 #pragma unroll
-        for (int u = 0; u < CP; ++u) load_piece(f, a0, cur, u);
-    }
-    commit(0);
-    __builtin_amdgcn_s_waitcnt(0x0F70);                              // vmcnt(0): the loop starts with nothing in flight
-    __syncthreads();
-    while (true) {
-        if (step(a0, a1)) break;
-        if (step(a1, a0)) break;
+        for (int i = 0; i < CP; ++i) {
+            commit_codes(buf ^ 1, i);
+            fetch_codes(f, i);
+        }
+#pragma unroll
+        for (int j = 0; j < GPW; ++j)
+#pragma unroll
+            for (int q = 0; q < 2 * MT; ++q) {
+                a0[j][q] = a1[j][q];
+                // the copy is made HERE, before its source takes a new load: left to itself the compiler loads into
+                // fresh registers and copies at the top of the next step, behind a wait for the newest load
+                asm volatile("" : "+v"(a0[j][q]));
+            }
+        load_a(a1, ld);
+        __syncthreads();                                             // next buffer filled, this one free again
+        if (!nxt.valid) break;
+        cur = nxt;
+        nxt = nxt2;
+        nxt2 = next(nxt2);
+        buf ^= 1;
     }
 }
 

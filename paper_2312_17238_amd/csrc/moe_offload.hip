@@ -160,7 +160,8 @@ struct moe_ctx {
     int32_t w13_blocks = 256, w2_rows = 32;
     int32_t w2_token_rows = 0;          // rows per block of the single-token w2 kernel; 0: hidden / compute units
     uint32_t gate_seq = 0;              // sequence number of the last gate launch
-    int32_t mfma_form = 0;              // matrix-core kernels: 0 by the tokens per expert (4 up to sixteen, else 3); 4 streaming form with 16-token tiles;
+    int32_t mfma_form = 0;              // matrix-core kernels: 0 by the tokens per expert (5 up to sixteen, else 3); 5 streaming form with 16-token tiles,
+                                        // codes multiplied as they are and groups scaled in fp32; 4 the same with weights dequantised to fp16;
                                         // 3 streaming form, one fma per pair of weights plus a rank-1 correction;
                                         // 2 streaming form with an exact subtraction first; 1 row-staging form with fp32 group scaling
     int32_t mfma16_waves = 8;           // waves per block of the 16-token form's single-tile kernels: 4 or 8 (two blocks per compute unit either
@@ -1327,6 +1328,10 @@ static int32_t launch_mfma_stream(moe_layer *l, const std::vector<PassExpert> &e
         HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_stream16_q4<false, 2, 4>), hipFuncAttributeMaxDynamicSharedMemorySize, TL_LDS_BYTES));
         HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_stream16_q4<true, 1, 8>), hipFuncAttributeMaxDynamicSharedMemorySize, TL_LDS_BYTES));
         HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_stream16_q4<false, 1, 8>), hipFuncAttributeMaxDynamicSharedMemorySize, TL_LDS_BYTES));
+        HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_stream16_q4<true, 1, 8, true>), hipFuncAttributeMaxDynamicSharedMemorySize, TL_LDS_BYTES));
+        HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_stream16_q4<false, 1, 8, true>), hipFuncAttributeMaxDynamicSharedMemorySize, TL_LDS_BYTES));
+        HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_stream16_q4<true, 2, 8, true>), hipFuncAttributeMaxDynamicSharedMemorySize, TL_LDS_BYTES));
+        HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_stream16_q4<false, 2, 8, true>), hipFuncAttributeMaxDynamicSharedMemorySize, TL_LDS_BYTES));
         lds_attr_set = true;
     }
     const int n_cu = c->n_cu > 0 ? c->n_cu : 256;
@@ -1388,14 +1393,17 @@ static int32_t launch_mfma_stream(moe_layer *l, const std::vector<PassExpert> &e
         // Which kernels multiply a window is decided from the window's routing, never from the experts that happen to
         // share a launch: the forms round differently, and a token's result must not depend on what the cache held.
         const bool small = c->win_small.at(w0 / window) != 0;
-        const bool t16 = (c->mfma_form == 4 || (c->mfma_form == 0 && small)) && !meta8;
+        const bool t16 = (c->mfma_form == 4 || c->mfma_form == 5 || (c->mfma_form == 0 && small)) && !meta8;
+        const bool gs = c->mfma_form == 5 || c->mfma_form == 0;         // group-scaled arithmetic: any finite (scale, zero) pair
+        const bool w8 = c->mfma16_waves == 8;
         const int max_tok = small ? 16 : 32;
         auto run_shift = [&](const MatLayout &m) { return (m.run_len == 0 || m.run_len >= m.cols / (uint32_t)b.group) ? 31 : __builtin_ctz(m.run_len); };
         A.K = b.hidden; A.N = b.ffn; A.stride = b.m13.row_stride; A.meta_off = b.m13.meta_off; A.mat_off = b.off_w13;
         A.meta2_off = b.m13.meta2_off; A.run_shift = run_shift(b.m13);
         const dim3 g13 = shape(2 * b.ffn, b.hidden, false);
-        const bool w8 = c->mfma16_waves == 8;
-        int32_t rc = t16 ? (max_tok <= 16 ? (w8 ? launch_timed(c, PROF_W13, bytes13, k_mfma_stream16_q4<true, 1, 8>, g13, dim3(512), TL_LDS_BYTES, A)
+        int32_t rc = t16 && gs ? (max_tok <= 16 ? launch_timed(c, PROF_W13, bytes13, k_mfma_stream16_q4<true, 1, 8, true>, g13, dim3(512), TL_LDS_BYTES, A)
+                                                : launch_timed(c, PROF_W13, bytes13, k_mfma_stream16_q4<true, 2, 8, true>, g13, dim3(512), TL_LDS_BYTES, A))
+                   : t16 ? (max_tok <= 16 ? (w8 ? launch_timed(c, PROF_W13, bytes13, k_mfma_stream16_q4<true, 1, 8>, g13, dim3(512), TL_LDS_BYTES, A)
                                                 : launch_timed(c, PROF_W13, bytes13, k_mfma_stream16_q4<true, 1, 4>, g13, dim3(TL_THREADS), TL_LDS_BYTES, A))
                                           : launch_timed(c, PROF_W13, bytes13, k_mfma_stream16_q4<true, 2, 4>, g13, dim3(TL_THREADS), TL_LDS_BYTES, A))
                      : meta8 ? launch_timed(c, PROF_W13, bytes13, k_mfma_stream_q4<true, true>, g13, dim3(TL_THREADS), TL_LDS_BYTES, A)
@@ -1410,7 +1418,9 @@ static int32_t launch_mfma_stream(moe_layer *l, const std::vector<PassExpert> &e
             A.part_base = (int32_t)((uint64_t)batch * K + c->ypart_extra_used / b.hidden) - w0 * K;
             c->ypart_extra_used += (uint64_t)first * A.k_parts * b.hidden;
         }
-        rc = t16 ? (max_tok <= 16 ? (w8 ? launch_timed(c, PROF_W2, bytes2, k_mfma_stream16_q4<false, 1, 8>, g2, dim3(512), TL_LDS_BYTES, A)
+        rc = t16 && gs ? (max_tok <= 16 ? launch_timed(c, PROF_W2, bytes2, k_mfma_stream16_q4<false, 1, 8, true>, g2, dim3(512), TL_LDS_BYTES, A)
+                                        : launch_timed(c, PROF_W2, bytes2, k_mfma_stream16_q4<false, 2, 8, true>, g2, dim3(512), TL_LDS_BYTES, A))
+           : t16 ? (max_tok <= 16 ? (w8 ? launch_timed(c, PROF_W2, bytes2, k_mfma_stream16_q4<false, 1, 8>, g2, dim3(512), TL_LDS_BYTES, A)
                                         : launch_timed(c, PROF_W2, bytes2, k_mfma_stream16_q4<false, 1, 4>, g2, dim3(TL_THREADS), TL_LDS_BYTES, A))
                                   : launch_timed(c, PROF_W2, bytes2, k_mfma_stream16_q4<false, 2, 4>, g2, dim3(TL_THREADS), TL_LDS_BYTES, A))
              : meta8 ? launch_timed(c, PROF_W2, bytes2, k_mfma_stream_q4<false, true>, g2, dim3(TL_THREADS), TL_LDS_BYTES, A)
@@ -2047,7 +2057,7 @@ try {
     else if (n == "token_path") c->token_path = value != 0;
     else if (n == "spec_head_mb" && value >= 0) c->spec_head_bytes = (uint64_t)value << 20;
     else if (n == "mfma_min_batch" && value >= 1) c->mfma_min_batch = value;
-    else if (n == "mfma_form" && value >= 0 && value <= 4) c->mfma_form = value;
+    else if (n == "mfma_form" && value >= 0 && value <= 5) c->mfma_form = value;
     else if (n == "mfma16_waves" && (value == 4 || value == 8)) c->mfma16_waves = value;
     else if (n == "device_routing") c->device_routing = value != 0;
     else if (n == "staged_min_batch" && value >= 0) c->staged_min_batch = value;

@@ -283,7 +283,7 @@ def test_launch_shape_knobs_do_not_change_results(Bn, token_path):
         assert st == outs[0][1]
 
 
-@pytest.mark.parametrize("form", [3, 2, 1, 4])
+@pytest.mark.parametrize("form", [3, 2, 1, 4, 5])
 @pytest.mark.parametrize("Bn,k", [(16, 4), (64, 4), (33, 8), (64, 2)])
 def test_small_stack_matrix_core_path(Bn, k, form):
     """Batches of 16 and more run 4-bit g64 experts as grouped dequantize+GEMM on the matrix cores
@@ -301,7 +301,7 @@ def test_small_stack_matrix_core_path(Bn, k, form):
     model.close()
 
 
-@pytest.mark.parametrize("form,rel", [(1, 1e-4), (2, 2e-3), (3, 2e-3), (4, 2e-3)])
+@pytest.mark.parametrize("form,rel", [(1, 1e-4), (2, 2e-3), (3, 2e-3), (4, 2e-3), (5, 1e-4)])
 def test_matrix_core_path_agrees_with_gemv_path(form, rel):
     """The same batched steps through the GEMV kernels (threshold raised) and the matrix cores: identical
     traces; outputs equal to within the summation-order noise of fp32 for the form that scales groups in fp32,
@@ -328,7 +328,7 @@ def test_matrix_core_path_agrees_with_gemv_path(form, rel):
     assert d < rel * max(1.0, np.abs(res["gemv"][0]).max()), d
 
 
-@pytest.mark.parametrize("form", [3, 4])
+@pytest.mark.parametrize("form", [3, 4, 5])
 @pytest.mark.parametrize("Bn,T,k", [(16, 2, 4), (64, 1, 8)])
 def test_mixtral_layer_batch16_matrix_cores(Bn, T, k, form):
     """Mixtral-shaped layer on the matrix cores, C oracle on every row: batch 16 with k=4 (8 needed experts over 4
@@ -700,7 +700,7 @@ def test_recall_study_tool_against_closed_forms_and_oracle():
     stack.close()
 
 
-@pytest.mark.parametrize("Bn,k,T,form", [(200, 4, 2, 3), (130, 2, 2, 1), (1000, 8, 1, 2), (1024, 2, 1, 3), (300, 4, 1, 2), (260, 4, 1, 4)])
+@pytest.mark.parametrize("Bn,k,T,form", [(200, 4, 2, 3), (130, 2, 2, 1), (1000, 8, 1, 2), (1024, 2, 1, 3), (300, 4, 1, 2), (260, 4, 1, 4), (260, 4, 1, 5), (90, 2, 2, 5)])
 def test_prompt_sized_batches(Bn, k, T, form):
     """Prompt encoding (Sec. 3: prompt tokens go through a layer in parallel, every expert is loaded once for all of
     them) is a step with a large batch: up to MOE_MAX_BATCH = 1024 tokens, through the matrix cores in windows of
@@ -753,7 +753,7 @@ def draw_configuration(seed):
     c["warm"] = c["swap"] or bool(r.rand() < 0.3)
     c["eps"] = pick([0.0, 1e-5])
     c["options"] = {
-        "token_path": pick([1, 1, 0]), "fused": pick([0, 0, 0, 1, 2]), "mfma_form": pick([1, 2, 3, 4, 0]), "mfma16_waves": pick([4, 8]),
+        "token_path": pick([1, 1, 0]), "fused": pick([0, 0, 0, 1, 2]), "mfma_form": pick([1, 2, 3, 4, 5, 0]), "mfma16_waves": pick([4, 8]),
         "mfma_min_batch": pick([16, 16, 2, 1000]), "staged_min_batch": pick([0, 0, 1000]),
         "spec_head_mb": pick([0, 0, 1]), "w13_blocks": pick([256, 64, 24]), "w2_rows": pick([32, 16, 8]),
         "sync_wait": pick([0, 0, 1]),
@@ -827,7 +827,8 @@ def test_rank1_matrix_core_form_gives_way_to_large_scales(factor, falls_back):
     """The default matrix-core form forms (1024 + zero) * scale in fp16.  A layer that was loaded with a (scale, zero)
     pair for which that product leaves the comfortable part of the fp16 range runs the form that subtracts first
     instead: asking for form 3 then gives bit for bit what asking for form 2 gives (two addends per element here, so
-    the sums do not depend on their order), while on ordinary weights the two forms differ in the last bits."""
+    the sums do not depend on their order), while on ordinary weights the two forms differ in the last bits.  The
+    group-scaled form 5 works in fp32 and takes any pair: it stays in tolerance of form 2 either way."""
     H, F, Bn = 256, 512, 16
     say(f"rank-1 form and scales x{factor}")
     model = Model(1, H, F, 8, 2, None, 8, 0, 0.0, max_batch=Bn, seed=77, keep_layers=[])
@@ -838,7 +839,7 @@ def test_rank1_matrix_core_form_gives_way_to_large_scales(factor, falls_back):
     x_in = (W.hidden_ar1(77, 1, Bn, H)[0].float() / factor).half().to(dev)      # keeps the outputs in range
     x_out = torch.empty(Bn, H, dtype=torch.float16, device=dev)
     ys = {}
-    for form in (3, 2):
+    for form in (3, 2, 5):
         B.moe_ctx_set_option(model.stack.ctx, "mfma_form", form)
         model.stack.step_layer(0, x_in, x_out, None, None, prefetch=False)
         model.stack.synchronize()
@@ -846,6 +847,8 @@ def test_rank1_matrix_core_form_gives_way_to_large_scales(factor, falls_back):
         assert np.isfinite(ys[form]).all() and np.abs(ys[form]).max() > 0
     same = (ys[3].view(np.uint32) == ys[2].view(np.uint32)).all()
     assert same == falls_back, f"forms 3 and 2 {'agree' if same else 'differ'} bit for bit"
+    d = np.abs(ys[5] - ys[2]).max()
+    assert d <= 2e-3 * np.abs(ys[2]).max(), f"form 5 against form 2: {d:.3e} of {np.abs(ys[2]).max():.3e}"
     model.close()
 
 
