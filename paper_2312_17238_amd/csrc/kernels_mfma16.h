@@ -70,8 +70,7 @@ __global__ __launch_bounds__(WAVES *WAVE, (WAVES == 8 && MT == 1 ? 4 : 2)) void 
     constexpr int THREADS = WAVES * WAVE;
     constexpr int GPW = TL_SG / WAVES;                               // groups per wave and step
     constexpr int CP = TL_ROWS * TL_CPR / THREADS;                   // code pieces per thread and step
-    constexpr int MPIECES = TL_ROWS * TL_MPR;                        // pair pieces per step, at most one per thread
-    static_assert(GPW * WAVES == TL_SG && CP == GPW * TL_RT && MPIECES <= THREADS, "pieces and units must pair up");
+    static_assert(GPW * WAVES == TL_SG && CP == GPW * TL_RT, "pieces and units must pair up");
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const int tid = threadIdx.x, lane = tid & 63, wv = uniform(tid >> 6);
     const int col = lane & 15, kb = lane >> 4;           // memory row (B) / token (A) of the tile; block of 8 k-slots
@@ -110,13 +109,15 @@ __global__ __launch_bounds__(WAVES *WAVE, (WAVES == 8 && MT == 1 ? 4 : 2)) void 
 
     // ---------------- addresses ----------------
     int addr_it = -1;
-    const uint8_t *mat_base = nullptr;
+    // the item's matrix as a buffer: a load's address is this scalar descriptor, a scalar offset and ONE 32-bit vector
+    // register, instead of 64-bit arithmetic in vector registers per load (a matrix is far below 4 GB)
+    __amdgpu_buffer_rsrc_t mat_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(A.e[0].blob), 0, 0, 0x00020000);
     uint32_t act_off[MT];                                            // bytes: token row of act + this lane's block of 8 k-slots
     auto enter_item = [&](const TileStep &s) {
         if (s.it == addr_it) return;
         addr_it = s.it;
         const MfmaEntry &en = A.e[s.e];
-        mat_base = en.blob + A.mat_off;
+        mat_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(en.blob + A.mat_off), 0, n_rows * (int)A.stride, 0x00020000);
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {                            // lanes past the last token read the first again
             const int tk = mt * 16 + col < en.n_tok ? mt * 16 + col : 0;
@@ -127,7 +128,7 @@ __global__ __launch_bounds__(WAVES *WAVE, (WAVES == 8 && MT == 1 ? 4 : 2)) void 
 
     // ---------------- weights: HBM -> registers -> LDS (as in the streaming kernel) ----------------
     uint4 st_c[CP], st_m;
-    struct FetchCtx { const uint8_t *seg; uint32_t voff; int row0, slab, g0, sg; bool live; };
+    struct FetchCtx { uint32_t voff; int row0, slab, g0, sg; bool live; };
     constexpr int SLAB = THREADS / TL_CPR;
     static_assert(THREADS % TL_CPR == 0 && 64 % SLAB == 0, "a slab of rows lies wholly inside or outside a matrix of 64 k rows");
     auto fetch_begin = [&](const TileStep &s, bool live) -> FetchCtx {
@@ -139,29 +140,38 @@ __global__ __launch_bounds__(WAVES *WAVE, (WAVES == 8 && MT == 1 ? 4 : 2)) void 
         f.slab = live ? SLAB : 0;
         const uint32_t c = tid % TL_CPR;
         f.voff = live ? (uint32_t)(tid / TL_CPR) * A.stride + ((int)c < 2 * f.sg ? c : 0u) * 16u : 0u;
-        f.seg = mat_base + (size_t)f.g0 * 32;
         return f;
     };
     auto fetch_codes = [&](const FetchCtx &f, int i) {
-        st_c[i] = ldw4(f.seg + (size_t)min(f.row0 + i * f.slab, n_rows - SLAB) * A.stride + f.voff, 0);
+        const int soff = f.g0 * 32 + min(f.row0 + i * f.slab, n_rows - SLAB) * (int)A.stride;
+        const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(mat_rsrc, (int)f.voff, soff, 2);     // 2: non-temporal
+        st_c[i] = make_uint4(v.x, v.y, v.z, v.w);
     };
     auto commit_codes = [&](int b, int i) {
         uint8_t *codes = lds + b * TL_BUF_BYTES;
         const int p = tid + i * THREADS, r = p / TL_CPR, c = p % TL_CPR;
         *reinterpret_cast<uint4 *>(codes + r * TL_CODE_PITCH + c * 16) = st_c[i];
     };
-    auto fetch_meta = [&](const FetchCtx &f) {                       // threads past the last piece repeat the last row's
-        const int p = min(tid, MPIECES - 1), r = f.live ? p / TL_MPR : 0, c = p % TL_MPR;
-        const uint8_t *rowp = mat_base + (size_t)min(f.row0 + r, n_rows - 1) * A.stride;
-        st_m = reinterpret_cast<const uint4 *>(rowp + A.meta_off)[f.g0 / 4 + (c < (f.sg + 3) / 4 ? c : 0)];
+    // pairs: 32 bytes per row and step, shared evenly by the block's threads (8 bytes each with 8 waves, 16 with 4);
+    // pieces past the row's last group repeat the step's first
+    constexpr int MW = TL_ROWS * TL_SG / THREADS;                    // words per thread: 2 or 4
+    static_assert(MW == 2 || MW == 4, "a thread holds 8 or 16 bytes of pairs");
+    auto fetch_meta = [&](const FetchCtx &f) {
+        const int r = f.live ? tid / (TL_SG / MW) : 0, c = tid % (TL_SG / MW);
+        const int voff = min(f.row0 + r, n_rows - 1) * (int)A.stride + (c * MW < f.sg ? c : 0) * (MW * 4);
+        if constexpr (MW == 2) {
+            const u32x2_t v = __builtin_amdgcn_raw_buffer_load_b64(mat_rsrc, voff, (int)A.meta_off + f.g0 * 4, 0);
+            st_m.x = v.x; st_m.y = v.y;
+        } else {
+            const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(mat_rsrc, voff, (int)A.meta_off + f.g0 * 4, 0);
+            st_m = make_uint4(v.x, v.y, v.z, v.w);
+        }
     };
     auto commit_meta = [&](int b) {
         uint32_t *meta = reinterpret_cast<uint32_t *>(lds + b * TL_BUF_BYTES + TL_ROWS * TL_CODE_PITCH);
-        if (tid < MPIECES) {
-            const int r = tid / TL_MPR, c = tid % TL_MPR;
-            uint32_t *d = meta + r * TL_META_PITCH + c * 4;
-            d[0] = st_m.x; d[1] = st_m.y; d[2] = st_m.z; d[3] = st_m.w;
-        }
+        uint32_t *d = meta + (tid / (TL_SG / MW)) * TL_META_PITCH + (tid % (TL_SG / MW)) * MW;
+        d[0] = st_m.x; d[1] = st_m.y;
+        if constexpr (MW == 4) { d[2] = st_m.z; d[3] = st_m.w; }
     };
 
     // ---------------- multiply ----------------
@@ -238,14 +248,13 @@ __global__ __launch_bounds__(WAVES *WAVE, (WAVES == 8 && MT == 1 ? 4 : 2)) void 
             }
         }
     };
-    UnitRegs u_next = {};
-    auto group_multiply = [&](const h8_t (&a)[2 * MT], int b, int gl, int sg, int j) {   // u_next holds tile 0 of group gl
+    auto group_multiply = [&](const h8_t (&a)[2 * MT], int b, int gl, int j, auto &&beside) {
         if constexpr (GS) group_sums(a);
 #pragma unroll
         for (int rt = 0; rt < TL_RT; ++rt) {
-            const UnitRegs u = u_next;
-            if (rt + 1 < TL_RT) unit_load(b, gl, rt + 1, u_next);
-            else if (j + 1 < GPW && gl + WAVES < sg) unit_load(b, gl + WAVES, 0, u_next);
+            UnitRegs u;
+            unit_load(b, gl, rt, u);
+            beside(j * TL_RT + rt);
             unit_multiply(a, u, rt);
         }
     };
@@ -334,21 +343,27 @@ __global__ __launch_bounds__(WAVES *WAVE, (WAVES == 8 && MT == 1 ? 4 : 2)) void 
     while (true) {
         const bool item_ends = !nxt.valid || nxt.it != cur.it;
         const int sg = seg_groups(cur);
-        if (wv < sg) unit_load(buf, wv, 0, u_next);
-#pragma unroll
-        for (int j = 0; j < GPW; ++j)
-            if (wv + WAVES * j < sg) group_multiply(a0[j], buf, wv + WAVES * j, sg, j);
-        if (item_ends) finish_item(cur, buf);
         // step n + 1 from the registers into the other buffer, step n + 2 into the registers
         const TileStep &ld = nxt2.valid ? nxt2 : cur;                // past the last step: 16 bytes re-read, never used
         const FetchCtx f = fetch_begin(ld, nxt2.valid);
-        commit_meta(buf ^ 1);
-        fetch_meta(f);
+        auto beside = [&](int u) {                                   // one piece beside each (group, tile) unit of the multiply
+            if (u == 0) {
+                commit_meta(buf ^ 1);
+                fetch_meta(f);
+            }
+            commit_codes(buf ^ 1, u);
+            fetch_codes(f, u);
+        };
 #pragma unroll
-        for (int i = 0; i < CP; ++i) {
-            commit_codes(buf ^ 1, i);
-            fetch_codes(f, i);
+        for (int j = 0; j < GPW; ++j) {
+            if (wv + WAVES * j < sg) {
+                group_multiply(a0[j], buf, wv + WAVES * j, j, beside);
+            } else {
+#pragma unroll
+                for (int u = j * TL_RT; u < (j + 1) * TL_RT; ++u) beside(u);
+            }
         }
+        if (item_ends) finish_item(cur, buf);
 #pragma unroll
         for (int j = 0; j < GPW; ++j)
 #pragma unroll

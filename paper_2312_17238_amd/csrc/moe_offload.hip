@@ -160,12 +160,13 @@ struct moe_ctx {
     int32_t w13_blocks = 256, w2_rows = 32;
     int32_t w2_token_rows = 0;          // rows per block of the single-token w2 kernel; 0: hidden / compute units
     uint32_t gate_seq = 0;              // sequence number of the last gate launch
-    int32_t mfma_form = 0;              // matrix-core kernels: 0 by the tokens per expert (5 up to sixteen, else 3); 5 streaming form with 16-token tiles,
-                                        // codes multiplied as they are and groups scaled in fp32; 4 the same with weights dequantised to fp16;
+    int32_t mfma_form = 0;              // matrix-core kernels: 0 the default (5; 2 for two-level metadata); 5 streaming form with 16-token tiles (one per
+                                        // expert while no expert of the window has more than 16 tokens, else two), codes multiplied as they are and
+                                        // groups scaled in fp32; 4 the same with weights dequantised to fp16;
                                         // 3 streaming form, one fma per pair of weights plus a rank-1 correction;
                                         // 2 streaming form with an exact subtraction first; 1 row-staging form with fp32 group scaling
-    int32_t mfma16_waves = 8;           // waves per block of the 16-token form's single-tile kernels: 4 or 8 (two blocks per compute unit either
-                                        // way; with two token tiles 8 waves need 170 registers, one block per unit, and measured 20 % slower)
+    int32_t mfma16_waves = 8;           // waves per block of the 16-token forms' single-tile kernels: 4 or 8 (two blocks per compute unit either
+                                        // way; with two token tiles 8 waves need 194 registers, one block per unit, and measured 12 % slower)
     int32_t mfma_min_batch = 16;        // batches at least this large use the matrix-core kernels (4-bit g64)
     int32_t staged_min_batch = 0;       // matrix-core batches larger than this: resident experts first, arriving ones one by one
     uint64_t spec_head_bytes = 0;       // 0: a speculative load moves the whole expert at once (as the paper describes);
@@ -1330,8 +1331,8 @@ static int32_t launch_mfma_stream(moe_layer *l, const std::vector<PassExpert> &e
         HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_stream16_q4<false, 1, 8>), hipFuncAttributeMaxDynamicSharedMemorySize, TL_LDS_BYTES));
         HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_stream16_q4<true, 1, 8, true>), hipFuncAttributeMaxDynamicSharedMemorySize, TL_LDS_BYTES));
         HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_stream16_q4<false, 1, 8, true>), hipFuncAttributeMaxDynamicSharedMemorySize, TL_LDS_BYTES));
-        HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_stream16_q4<true, 2, 8, true>), hipFuncAttributeMaxDynamicSharedMemorySize, TL_LDS_BYTES));
-        HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_stream16_q4<false, 2, 8, true>), hipFuncAttributeMaxDynamicSharedMemorySize, TL_LDS_BYTES));
+        HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_stream16_q4<true, 2, 4, true>), hipFuncAttributeMaxDynamicSharedMemorySize, TL_LDS_BYTES));
+        HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_stream16_q4<false, 2, 4, true>), hipFuncAttributeMaxDynamicSharedMemorySize, TL_LDS_BYTES));
         lds_attr_set = true;
     }
     const int n_cu = c->n_cu > 0 ? c->n_cu : 256;
@@ -1390,10 +1391,13 @@ static int32_t launch_mfma_stream(moe_layer *l, const std::vector<PassExpert> &e
         A.act = c->h_buf + (size_t)w0 * b.hidden;
         const bool meta8 = b.scale_group > 0;
         const bool r1 = (c->mfma_form == 3 || c->mfma_form == 0) && !meta8 && !l->wide_meta.load(std::memory_order_relaxed);
-        // Which kernels multiply a window is decided from the window's routing, never from the experts that happen to
-        // share a launch: the forms round differently, and a token's result must not depend on what the cache held.
+        // Which kernels multiply a window (one or two token tiles of 16) is decided from the window's routing, never from
+        // the experts that happen to share a launch: they add in different orders, and a token's result must not depend
+        // on what the cache held.
         const bool small = c->win_small.at(w0 / window) != 0;
-        const bool t16 = (c->mfma_form == 4 || c->mfma_form == 5 || (c->mfma_form == 0 && small)) && !meta8;
+        // (the 16-token kernels address a matrix with 32-bit offsets)
+        const bool fits32 = 2ull * b.ffn * b.m13.row_stride < (1ull << 31) && (uint64_t)b.hidden * b.m2.row_stride < (1ull << 31);
+        const bool t16 = (c->mfma_form == 4 || c->mfma_form == 5 || c->mfma_form == 0) && !meta8 && fits32;
         const bool gs = c->mfma_form == 5 || c->mfma_form == 0;         // group-scaled arithmetic: any finite (scale, zero) pair
         const bool w8 = c->mfma16_waves == 8;
         const int max_tok = small ? 16 : 32;
@@ -1402,7 +1406,7 @@ static int32_t launch_mfma_stream(moe_layer *l, const std::vector<PassExpert> &e
         A.meta2_off = b.m13.meta2_off; A.run_shift = run_shift(b.m13);
         const dim3 g13 = shape(2 * b.ffn, b.hidden, false);
         int32_t rc = t16 && gs ? (max_tok <= 16 ? launch_timed(c, PROF_W13, bytes13, k_mfma_stream16_q4<true, 1, 8, true>, g13, dim3(512), TL_LDS_BYTES, A)
-                                                : launch_timed(c, PROF_W13, bytes13, k_mfma_stream16_q4<true, 2, 8, true>, g13, dim3(512), TL_LDS_BYTES, A))
+                                                : launch_timed(c, PROF_W13, bytes13, k_mfma_stream16_q4<true, 2, 4, true>, g13, dim3(TL_THREADS), TL_LDS_BYTES, A))
                    : t16 ? (max_tok <= 16 ? (w8 ? launch_timed(c, PROF_W13, bytes13, k_mfma_stream16_q4<true, 1, 8>, g13, dim3(512), TL_LDS_BYTES, A)
                                                 : launch_timed(c, PROF_W13, bytes13, k_mfma_stream16_q4<true, 1, 4>, g13, dim3(TL_THREADS), TL_LDS_BYTES, A))
                                           : launch_timed(c, PROF_W13, bytes13, k_mfma_stream16_q4<true, 2, 4>, g13, dim3(TL_THREADS), TL_LDS_BYTES, A))
@@ -1419,7 +1423,7 @@ static int32_t launch_mfma_stream(moe_layer *l, const std::vector<PassExpert> &e
             c->ypart_extra_used += (uint64_t)first * A.k_parts * b.hidden;
         }
         rc = t16 && gs ? (max_tok <= 16 ? launch_timed(c, PROF_W2, bytes2, k_mfma_stream16_q4<false, 1, 8, true>, g2, dim3(512), TL_LDS_BYTES, A)
-                                        : launch_timed(c, PROF_W2, bytes2, k_mfma_stream16_q4<false, 2, 8, true>, g2, dim3(512), TL_LDS_BYTES, A))
+                                        : launch_timed(c, PROF_W2, bytes2, k_mfma_stream16_q4<false, 2, 4, true>, g2, dim3(TL_THREADS), TL_LDS_BYTES, A))
            : t16 ? (max_tok <= 16 ? (w8 ? launch_timed(c, PROF_W2, bytes2, k_mfma_stream16_q4<false, 1, 8>, g2, dim3(512), TL_LDS_BYTES, A)
                                         : launch_timed(c, PROF_W2, bytes2, k_mfma_stream16_q4<false, 1, 4>, g2, dim3(TL_THREADS), TL_LDS_BYTES, A))
                                   : launch_timed(c, PROF_W2, bytes2, k_mfma_stream16_q4<false, 2, 4>, g2, dim3(TL_THREADS), TL_LDS_BYTES, A))
