@@ -112,6 +112,11 @@ __global__ __launch_bounds__(WAVES *WAVE, (WAVES == 8 && MT == 1 ? 4 : 2)) void 
     // the item's matrix as a buffer: a load's address is this scalar descriptor, a scalar offset and ONE 32-bit vector
     // register, instead of 64-bit arithmetic in vector registers per load (a matrix is far below 4 GB)
     __amdgpu_buffer_rsrc_t mat_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(A.e[0].blob), 0, 0, 0x00020000);
+    // The activations as a buffer too: a lane whose token does not exist carries an offset past the buffer's end, for
+    // which the hardware returns zeros without a request -- at four tokens per expert three quarters of the A operand's
+    // lanes, whose 16 bytes each would otherwise cross the compute unit's path to memory like any others.
+    constexpr uint32_t ACT_RANGE = 0x7fffff00u, ACT_NONE = 0x80000000u;       // no offset of a load wraps around
+    const __amdgpu_buffer_rsrc_t act_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(A.act), 0, (int)ACT_RANGE, 0x00020000);
     uint32_t act_off[MT];                                            // bytes: token row of act + this lane's block of 8 k-slots
     auto enter_item = [&](const TileStep &s) {
         if (s.it == addr_it) return;
@@ -119,10 +124,11 @@ __global__ __launch_bounds__(WAVES *WAVE, (WAVES == 8 && MT == 1 ? 4 : 2)) void 
         const MfmaEntry &en = A.e[s.e];
         mat_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(en.blob + A.mat_off), 0, n_rows * (int)A.stride, 0x00020000);
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {                            // lanes past the last token read the first again
-            const int tk = mt * 16 + col < en.n_tok ? mt * 16 + col : 0;
+        for (int mt = 0; mt < MT; ++mt) {
+            const bool live = mt * 16 + col < en.n_tok;
+            const int tk = live ? mt * 16 + col : 0;
             const int row = W13 ? l_tok[en.first + tk] : l_pair[en.first + tk];
-            act_off[mt] = (uint32_t)row * (uint32_t)A.K * 2u + (uint32_t)kb * 16u;
+            act_off[mt] = live ? (uint32_t)row * (uint32_t)A.K * 2u + (uint32_t)kb * 16u : ACT_NONE;
         }
     };
 
@@ -183,8 +189,7 @@ __global__ __launch_bounds__(WAVES *WAVE, (WAVES == 8 && MT == 1 ? 4 : 2)) void 
     // A operands of one group: [token tile][k-step]; piece q = mt * 2 + kk
     auto load_a_piece = [&](h8_t (&dst)[GPW][2 * MT], const TileStep &s, int j, int q) {
         const int g = s.seg * TL_SG + min(wv + WAVES * j, seg_groups(s) - 1);
-        const uint8_t *grp = reinterpret_cast<const uint8_t *>(A.act) + (size_t)g * 128 + (q & 1) * 64;
-        dst[j][q] = __builtin_bit_cast(h8_t, *reinterpret_cast<const uint4 *>(grp + act_off[q >> 1]));
+        dst[j][q] = __builtin_bit_cast(h8_t, __builtin_amdgcn_raw_buffer_load_b128(act_rsrc, (int)act_off[q >> 1], g * 128 + (q & 1) * 64, 0));
     };
     static_assert(TL_RT == 4, "four 32-row tiles per item");
     // One unit = one group of one 32-row tile = two 16-row sub-tiles; its code words (two per sub-tile: this lane's
