@@ -306,18 +306,18 @@ int32_t moe_ctx_profile_timeline(moe_ctx_t *ctx, int32_t kind, double *start_ms,
  *                0: the general kernels also for one token;
  *   "mfma_min_batch" batches at least this large (default 16) run 4-bit group-64 experts on the matrix cores
  *                (grouped dequantize+GEMM); smaller batches, and other formats, use the GEMV kernels;
- *   "mfma_form"  which matrix-core kernels.  0 (default): form 5 (form 2 with two-level metadata).  4: persistent
- *                streaming kernels with tiles of 16 tokens -- one tile per expert while no expert has more than 16 tokens
- *                of a window of up to 256 / top_k tokens of the step, else two, decided per window from its routing alone,
- *                so that a token's result does not depend on which experts share a launch -- each dequantised weight
- *                rounded once to fp16 before the multiply, as Sec. 4.2's fp16 experts do; fp16 metadata only (form 2 runs
- *                otherwise).  5: the kernels of form 4 with the
- *                weights not dequantised at all: the codes enter the matrix cores as they are and a group's product is
- *                corrected for the zero-point and scaled in fp32 (no rounding of a weight; any finite pair).  2: form
- *                4's arithmetic with tiles of 32 tokens.  3: as 2 with one fused multiply-add per pair of weights and the part its rounded constant
- *                leaves added back as a rank-1 term by one more matrix instruction per tile (fp16 metadata; with
- *                two-level metadata, and for a layer loaded with a pair whose (1024 + |zero|) * |scale| exceeds 16384
- *                -- the form computes that product in fp16 -- form 2 runs).  1: row-staging kernels that keep the codes
+ *   "mfma_form"  which matrix-core kernels.  0 (default): form 5.  4: persistent streaming kernels with
+ *                tiles of 16 tokens -- one tile per expert while no expert has more than 16 tokens of a window of up to
+ *                256 / top_k tokens of the step, else two, decided per window from its routing alone, so that a token's
+ *                result does not depend on which experts share a launch -- each dequantised weight rounded once to fp16
+ *                before the multiply, as Sec. 4.2's fp16 experts do; fp16 metadata only (form 2 runs otherwise).  5: the
+ *                kernels of form 4 with the weights not dequantised at all: the codes enter the matrix cores as they are
+ *                and a group's product is corrected for the zero-point and scaled in fp32 (no rounding of a weight; any
+ *                finite pair; fp16 and two-level metadata, the latter decoded in fp32).  2: form 4's arithmetic with
+ *                tiles of 32 tokens.  3: as 2 with one fused multiply-add per pair of weights and the part its rounded
+ *                constant leaves added back as a rank-1 term by one more matrix instruction per tile (fp16 metadata; with
+ *                two-level metadata, and for a layer loaded with a pair whose (1024 + |zero|) * |scale| exceeds 16384 --
+ *                the form computes that product in fp16 -- form 2 runs).  1: row-staging kernels that keep the codes
  *                exact and scale every group's product in fp32 (batches of at most 64 tokens, fp16 metadata; otherwise
  *                form 2 runs).  All meet the output tolerance;
  *   "mfma16_waves" waves per block of the kernels of forms 4 and 5 for up to 16 tokens per expert: 8 (default; 128

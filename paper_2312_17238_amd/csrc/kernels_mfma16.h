@@ -62,9 +62,13 @@ __device__ __forceinline__ h8_t codes_biased(uint32_t w, const BiasPatterns &p)
 
 // WAVES: 4 (a wave multiplies two groups of a step) or 8 (one group; half the staging and A-operand registers per
 // lane, so that two blocks of 8 waves fit a compute unit: four waves per SIMD, which is the second launch bound).
-template <bool W13, int MT, int WAVES, bool GS = false>
+// META8 (GS only): two-level metadata (Sec. 4.2 "scale group size").  A step then stages, per row, 16 bytes of (scale
+// code, zero code) byte pairs and the fp16 quad of the run the step lies in, and a unit decodes scale and zero in fp32
+// -- which is where the group-scaled arithmetic wants them anyway.
+template <bool W13, int MT, int WAVES, bool GS = false, bool META8 = false>
 __global__ __launch_bounds__(WAVES *WAVE, (WAVES == 8 && MT == 1 ? 4 : 2)) void k_mfma_stream16_q4(TileArgs A)
 {
+    static_assert(GS || !META8, "two-level metadata is decoded in fp32: group-scaled arithmetic only");
     static_assert(MT == 1 || MT == 2, "one or two token tiles of 16");
     static_assert(WAVES == 4 || WAVES == 8, "four or eight waves per block");
     constexpr int THREADS = WAVES * WAVE;
@@ -164,12 +168,23 @@ __global__ __launch_bounds__(WAVES *WAVE, (WAVES == 8 && MT == 1 ? 4 : 2)) void 
     static_assert(MW == 2 || MW == 4, "a thread holds 8 or 16 bytes of pairs");
     auto fetch_meta = [&](const FetchCtx &f) {
         const int r = f.live ? tid / (TL_SG / MW) : 0, c = tid % (TL_SG / MW);
-        const int voff = min(f.row0 + r, n_rows - 1) * (int)A.stride + (c * MW < f.sg ? c : 0) * (MW * 4);
+        int voff = min(f.row0 + r, n_rows - 1) * (int)A.stride, soff;
+        if constexpr (META8) {
+            // words 0..3 of the staged row: the step's 8 byte pairs; words 4, 5: the quad of its run; the rest is not read
+            static_assert(TL_SG == 8, "two-level staging is laid out for steps of 8 groups");
+            const int quad = (int)A.meta2_off + 8 * (f.g0 >> A.run_shift), pairs = (int)A.meta_off + f.g0 * 2;
+            if constexpr (MW == 2) voff = c == 3 ? (int)0x80000000u : voff + (c == 2 ? quad : pairs + c * 8);
+            else voff += c == 1 ? quad : pairs;
+            soff = 0;
+        } else {
+            voff += (c * MW < f.sg ? c : 0) * (MW * 4);
+            soff = (int)A.meta_off + f.g0 * 4;
+        }
         if constexpr (MW == 2) {
-            const u32x2_t v = __builtin_amdgcn_raw_buffer_load_b64(mat_rsrc, voff, (int)A.meta_off + f.g0 * 4, 0);
+            const u32x2_t v = __builtin_amdgcn_raw_buffer_load_b64(mat_rsrc, voff, soff, 0);
             st_m.x = v.x; st_m.y = v.y;
         } else {
-            const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(mat_rsrc, voff, (int)A.meta_off + f.g0 * 4, 0);
+            const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(mat_rsrc, voff, soff, 0);
             st_m = make_uint4(v.x, v.y, v.z, v.w);
         }
     };
@@ -194,7 +209,7 @@ __global__ __launch_bounds__(WAVES *WAVE, (WAVES == 8 && MT == 1 ? 4 : 2)) void 
     static_assert(TL_RT == 4, "four 32-row tiles per item");
     // One unit = one group of one 32-row tile = two 16-row sub-tiles; its code words (two per sub-tile: this lane's
     // block of 8 k-slots in each half of the group) and pairs are read from LDS one unit ahead of their use.
-    struct UnitRegs { uint32_t q[2][2], m[2]; };
+    struct UnitRegs { uint32_t q[2][2], m[2], quad[2][2]; };         // m: the (scale, zero) pair, fp16 or (META8) bytes; quad: META8 only
     auto unit_load = [&](int b, int gl, int rt, UnitRegs &u) {
         const uint8_t *codes = lds + b * TL_BUF_BYTES;
         const uint32_t *meta = reinterpret_cast<const uint32_t *>(codes + TL_ROWS * TL_CODE_PITCH);
@@ -204,7 +219,13 @@ __global__ __launch_bounds__(WAVES *WAVE, (WAVES == 8 && MT == 1 ? 4 : 2)) void 
             const uint32_t *w = reinterpret_cast<const uint32_t *>(codes + r * TL_CODE_PITCH + gl * 32);
             u.q[h][0] = w[kb];
             u.q[h][1] = w[4 + kb];
-            u.m[h] = meta[r * TL_META_PITCH + gl];
+            if constexpr (META8) {
+                u.m[h] = (meta[r * TL_META_PITCH + (gl >> 1)] >> (16 * (gl & 1))) & 0xffffu;
+                u.quad[h][0] = meta[r * TL_META_PITCH + 4];
+                u.quad[h][1] = meta[r * TL_META_PITCH + 5];
+            } else {
+                u.m[h] = meta[r * TL_META_PITCH + gl];
+            }
         }
     };
     // GS: per token of the lane's accumulator rows, the group's activation sum and minus the biases' share
@@ -226,8 +247,14 @@ __global__ __launch_bounds__(WAVES *WAVE, (WAVES == 8 && MT == 1 ? 4 : 2)) void 
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             if constexpr (GS) {
-                const float s32 = (float)__builtin_bit_cast(_Float16, (uint16_t)(u.m[h] & 0xffff));
-                const float nz32 = -(float)__builtin_bit_cast(_Float16, (uint16_t)(u.m[h] >> 16));
+                float s32, nz32;
+                if constexpr (META8) {          // scale = (code - m1) m0, zero = (code - m3) m2, in fp32
+                    s32 = ((float)(u.m[h] & 0xffu) - hi_half(u.quad[h][0])) * lo_half(u.quad[h][0]);
+                    nz32 = (hi_half(u.quad[h][1]) - (float)(u.m[h] >> 8)) * lo_half(u.quad[h][1]);
+                } else {
+                    s32 = (float)__builtin_bit_cast(_Float16, (uint16_t)(u.m[h] & 0xffff));
+                    nz32 = -(float)__builtin_bit_cast(_Float16, (uint16_t)(u.m[h] >> 16));
+                }
                 const h8_t b0 = codes_biased(u.q[h][0], bp), b1 = codes_biased(u.q[h][1], bp);
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt) {

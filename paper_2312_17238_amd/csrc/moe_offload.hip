@@ -160,7 +160,7 @@ struct moe_ctx {
     int32_t w13_blocks = 256, w2_rows = 32;
     int32_t w2_token_rows = 0;          // rows per block of the single-token w2 kernel; 0: hidden / compute units
     uint32_t gate_seq = 0;              // sequence number of the last gate launch
-    int32_t mfma_form = 0;              // matrix-core kernels: 0 the default (5; 2 for two-level metadata); 5 streaming form with 16-token tiles (one per
+    int32_t mfma_form = 0;              // matrix-core kernels: 0 the default (5); 5 streaming form with 16-token tiles (one per
                                         // expert while no expert of the window has more than 16 tokens, else two), codes multiplied as they are and
                                         // groups scaled in fp32; 4 the same with weights dequantised to fp16;
                                         // 3 streaming form, one fma per pair of weights plus a rank-1 correction;
@@ -1332,6 +1332,10 @@ static int32_t launch_mfma_stream(moe_layer *l, const std::vector<PassExpert> &e
         HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_stream16_q4<true, 1, 8, true>), hipFuncAttributeMaxDynamicSharedMemorySize, TL_LDS_BYTES));
         HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_stream16_q4<false, 1, 8, true>), hipFuncAttributeMaxDynamicSharedMemorySize, TL_LDS_BYTES));
         HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_stream16_q4<true, 2, 4, true>), hipFuncAttributeMaxDynamicSharedMemorySize, TL_LDS_BYTES));
+        HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_stream16_q4<true, 1, 8, true, true>), hipFuncAttributeMaxDynamicSharedMemorySize, TL_LDS_BYTES));
+        HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_stream16_q4<false, 1, 8, true, true>), hipFuncAttributeMaxDynamicSharedMemorySize, TL_LDS_BYTES));
+        HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_stream16_q4<true, 2, 4, true, true>), hipFuncAttributeMaxDynamicSharedMemorySize, TL_LDS_BYTES));
+        HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_stream16_q4<false, 2, 4, true, true>), hipFuncAttributeMaxDynamicSharedMemorySize, TL_LDS_BYTES));
         HIPCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_mfma_stream16_q4<false, 2, 4, true>), hipFuncAttributeMaxDynamicSharedMemorySize, TL_LDS_BYTES));
         lds_attr_set = true;
     }
@@ -1400,12 +1404,15 @@ static int32_t launch_mfma_stream(moe_layer *l, const std::vector<PassExpert> &e
         const bool t16 = (c->mfma_form == 4 || c->mfma_form == 5 || c->mfma_form == 0) && !meta8 && fits32;
         const bool gs = c->mfma_form == 5 || c->mfma_form == 0;         // group-scaled arithmetic: any finite (scale, zero) pair
         const bool w8 = c->mfma16_waves == 8;
+        const bool gs8 = meta8 && gs && fits32;                         // two-level metadata: the group-scaled kernels decode it in fp32
         const int max_tok = small ? 16 : 32;
         auto run_shift = [&](const MatLayout &m) { return (m.run_len == 0 || m.run_len >= m.cols / (uint32_t)b.group) ? 31 : __builtin_ctz(m.run_len); };
         A.K = b.hidden; A.N = b.ffn; A.stride = b.m13.row_stride; A.meta_off = b.m13.meta_off; A.mat_off = b.off_w13;
         A.meta2_off = b.m13.meta2_off; A.run_shift = run_shift(b.m13);
         const dim3 g13 = shape(2 * b.ffn, b.hidden, false);
-        int32_t rc = t16 && gs ? (max_tok <= 16 ? launch_timed(c, PROF_W13, bytes13, k_mfma_stream16_q4<true, 1, 8, true>, g13, dim3(512), TL_LDS_BYTES, A)
+        int32_t rc = gs8 ? (max_tok <= 16 ? launch_timed(c, PROF_W13, bytes13, k_mfma_stream16_q4<true, 1, 8, true, true>, g13, dim3(512), TL_LDS_BYTES, A)
+                                          : launch_timed(c, PROF_W13, bytes13, k_mfma_stream16_q4<true, 2, 4, true, true>, g13, dim3(TL_THREADS), TL_LDS_BYTES, A))
+                   : t16 && gs ? (max_tok <= 16 ? launch_timed(c, PROF_W13, bytes13, k_mfma_stream16_q4<true, 1, 8, true>, g13, dim3(512), TL_LDS_BYTES, A)
                                                 : launch_timed(c, PROF_W13, bytes13, k_mfma_stream16_q4<true, 2, 4, true>, g13, dim3(TL_THREADS), TL_LDS_BYTES, A))
                    : t16 ? (max_tok <= 16 ? (w8 ? launch_timed(c, PROF_W13, bytes13, k_mfma_stream16_q4<true, 1, 8>, g13, dim3(512), TL_LDS_BYTES, A)
                                                 : launch_timed(c, PROF_W13, bytes13, k_mfma_stream16_q4<true, 1, 4>, g13, dim3(TL_THREADS), TL_LDS_BYTES, A))
@@ -1422,7 +1429,9 @@ static int32_t launch_mfma_stream(moe_layer *l, const std::vector<PassExpert> &e
             A.part_base = (int32_t)((uint64_t)batch * K + c->ypart_extra_used / b.hidden) - w0 * K;
             c->ypart_extra_used += (uint64_t)first * A.k_parts * b.hidden;
         }
-        rc = t16 && gs ? (max_tok <= 16 ? launch_timed(c, PROF_W2, bytes2, k_mfma_stream16_q4<false, 1, 8, true>, g2, dim3(512), TL_LDS_BYTES, A)
+        rc = gs8 ? (max_tok <= 16 ? launch_timed(c, PROF_W2, bytes2, k_mfma_stream16_q4<false, 1, 8, true, true>, g2, dim3(512), TL_LDS_BYTES, A)
+                                  : launch_timed(c, PROF_W2, bytes2, k_mfma_stream16_q4<false, 2, 4, true, true>, g2, dim3(TL_THREADS), TL_LDS_BYTES, A))
+           : t16 && gs ? (max_tok <= 16 ? launch_timed(c, PROF_W2, bytes2, k_mfma_stream16_q4<false, 1, 8, true>, g2, dim3(512), TL_LDS_BYTES, A)
                                         : launch_timed(c, PROF_W2, bytes2, k_mfma_stream16_q4<false, 2, 4, true>, g2, dim3(TL_THREADS), TL_LDS_BYTES, A))
            : t16 ? (max_tok <= 16 ? (w8 ? launch_timed(c, PROF_W2, bytes2, k_mfma_stream16_q4<false, 1, 8>, g2, dim3(512), TL_LDS_BYTES, A)
                                         : launch_timed(c, PROF_W2, bytes2, k_mfma_stream16_q4<false, 1, 4>, g2, dim3(TL_THREADS), TL_LDS_BYTES, A))

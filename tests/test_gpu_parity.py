@@ -344,6 +344,22 @@ def test_mixtral_layer_batch16_matrix_cores(Bn, T, k, form):
     model.close()
 
 
+@pytest.mark.parametrize("form", [5, 2])
+@pytest.mark.parametrize("Bn,k", [(16, 8), (64, 8)])
+def test_mixtral_layer_two_level_metadata_matrix_cores(Bn, k, form):
+    """Mixtral-shaped layer with two-level metadata (scale group 128: one run per row of w1/w3, two per row of w2) on
+    the matrix cores, one and two token tiles, C oracle on every row: the group-scaled kernels decode scale and zero
+    in fp32 (default), form 2 dequantises to fp16 first."""
+    c = W.CONFIGS["mixtral_layer"]
+    say(f"mixtral layer, two-level metadata, B={Bn} form {form}: build")
+    model = Model(1, c.hidden, c.ffn, c.n_experts, c.top_k, None, k, 0, 0.0, max_batch=Bn, seed=c.seed, scale_group=128)
+    B.moe_ctx_set_option(model.stack.ctx, "mfma_form", form)
+    xs = W.hidden_ar1(c.seed, 1, Bn, c.hidden)
+    _, sim, errs = run_teacher_forced(model, xs, c_ffn.expert_ffn)
+    say(f"  form {form}: max abs {max(e[0] for e in errs):.2e} max rel-rms {max(e[1] for e in errs):.2e}")
+    model.close()
+
+
 def test_rmsnorm_small_and_large_inputs_bit_exact():
     """eps dominates for tiny inputs and the straight fp64->fp16 rounding matters for large ones: h must equal
     the oracle's bit for bit over magnitudes from fp16 subnormals to near overflow."""
