@@ -119,6 +119,7 @@ def main() -> int:
                     help="speculative loads copy only the first N MiB until the guess is confirmed (0: whole expert, as in the paper)")
     ap.add_argument("--mfma-form", type=int, default=0, help="matrix-core kernel form 1..5 (0: the library's default)")
     ap.add_argument("--mfma16-waves", type=int, default=0, help="waves per block of the 16-token matrix-core kernels, 4 or 8 (0: the library's default)")
+    ap.add_argument("--mfma-min-batch", type=int, default=0, help="batches at least this large run on the matrix cores (0: the library's default)")
     ap.add_argument("--fused", type=int, default=-1,
                     help="single-token steps run w1/w3 and w2 as one persistent launch: 1 with a grid barrier, 2 expert after expert; 0 two launches (-1: the library's default)")
     ap.add_argument("--no-token-path", action="store_true", help="single-token steps use the general kernels (atomics + residual kernel)")
@@ -171,6 +172,8 @@ def main() -> int:
         B.moe_ctx_set_option(stack.ctx, "mfma_form", args.mfma_form)
     if args.mfma16_waves:
         B.moe_ctx_set_option(stack.ctx, "mfma16_waves", args.mfma16_waves)
+    if args.mfma_min_batch:
+        B.moe_ctx_set_option(stack.ctx, "mfma_min_batch", args.mfma_min_batch)
     if args.fused >= 0:
         B.moe_ctx_set_option(stack.ctx, "fused", args.fused)
     if args.no_token_path:

@@ -223,7 +223,8 @@ int32_t moe_layer_step(moe_layer_t *layer, moe_layer_t *next, const uint16_t *x_
 
 /* moe_layer_step for callers that cannot allocate device memory: code that runs while a HIP graph is being captured
  * elsewhere in the process, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same decisions,
- * traces and results as moe_layer_step, computed by the same kernels; the difference is where those kernels keep
+ * traces and results as moe_layer_step with option "mfma_min_batch" above the batch (its four tokens at most always run
+ * on the GEMV kernels), computed by the same kernels; the difference is where those kernels keep
  * their intermediate results (the gate input h, the SwiGLU activations a, the pairs' fp32 partial outputs, the block
  * output y): not in the context's arena but in a fixed array inside the library's own device image (1.2 MB, held by
  * every GPU the library runs on until the process ends).  The call makes no device or pinned-host allocation, frees none and
@@ -304,8 +305,9 @@ int32_t moe_ctx_profile_timeline(moe_ctx_t *ctx, int32_t kind, double *start_ms,
  *   "token_path" 1 (default): a single-token step runs w2 with the combine and the residual add inside the
  *                kernel (one block sees both experts' rows; no atomics, no separate residual kernel);
  *                0: the general kernels also for one token;
- *   "mfma_min_batch" batches at least this large (default 16) run 4-bit group-64 experts on the matrix cores
- *                (grouped dequantize+GEMM); smaller batches, and other formats, use the GEMV kernels;
+ *   "mfma_min_batch" batches at least this large (default 3, from where on they are the faster ones on MI355X; 16
+ *                is the benchmark definition's threshold) run 4-bit group-64 experts on the matrix cores (grouped
+ *                dequantize+GEMM); smaller batches, and other formats, use the GEMV kernels;
  *   "mfma_form"  which matrix-core kernels.  0 (default): form 5.  4: persistent streaming kernels with
  *                tiles of 16 tokens -- one tile per expert while no expert has more than 16 tokens of a window of up to
  *                256 / top_k tokens of the step, else two, decided per window from its routing alone, so that a token's

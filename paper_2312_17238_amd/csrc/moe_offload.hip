@@ -167,7 +167,8 @@ struct moe_ctx {
                                         // 2 streaming form with an exact subtraction first; 1 row-staging form with fp32 group scaling
     int32_t mfma16_waves = 8;           // waves per block of the 16-token forms' single-tile kernels: 4 or 8 (two blocks per compute unit either
                                         // way; with two token tiles 8 waves need 194 registers, one block per unit, and measured 12 % slower)
-    int32_t mfma_min_batch = 16;        // batches at least this large use the matrix-core kernels (4-bit g64)
+    int32_t mfma_min_batch = 3;         // batches at least this large use the matrix-core kernels (4-bit g64): measured, all experts of a
+                                        // Mixtral-shaped layer resident, they are 9 % faster than the GEMV kernels at 3 tokens and 82 % at 12
     int32_t staged_min_batch = 0;       // matrix-core batches larger than this: resident experts first, arriving ones one by one
     uint64_t spec_head_bytes = 0;       // 0: a speculative load moves the whole expert at once (as the paper describes);
                                         // > 0: only this many leading bytes, the rest when the guess is confirmed
@@ -1896,16 +1897,17 @@ try {
     if (c->prof.on) return fail(MOE_ESTATE, "moe_layer_step_noalloc: switch the launch timing off first (it may create events)");
     // the kernels of this step take their scratch from the file-scope array: same kernels, other pointers
     struct Swap {
-        moe_ctx *c; uint16_t *h, *a; float *y, *yp; uint32_t *yt; uint64_t extra;
-        ~Swap() { c->h_buf = h; c->a_buf = a; c->yacc = y; c->ypart = yp; c->ytab = yt; c->ypart_extra_floats = extra; }
-    } restore{c, c->h_buf, c->a_buf, c->yacc, c->ypart, c->ytab, c->ypart_extra_floats};
+        moe_ctx *c; uint16_t *h, *a; float *y, *yp; uint32_t *yt; uint64_t extra; int32_t min_batch;
+        ~Swap() { c->h_buf = h; c->a_buf = a; c->yacc = y; c->ypart = yp; c->ytab = yt; c->ypart_extra_floats = extra; c->mfma_min_batch = min_batch; }
+    } restore{c, c->h_buf, c->a_buf, c->yacc, c->ypart, c->ytab, c->ypart_extra_floats, c->mfma_min_batch};
     uint8_t *s = c->noalloc_scratch;
     c->h_buf = reinterpret_cast<uint16_t *>(s); s += NOALLOC_H_BYTES;
     c->a_buf = reinterpret_cast<uint16_t *>(s); s += NOALLOC_A_BYTES;
     c->yacc = reinterpret_cast<float *>(s); s += NOALLOC_Y_BYTES;
     c->ypart = reinterpret_cast<float *>(s); s += NOALLOC_YPART_BYTES;
     c->ytab = reinterpret_cast<uint32_t *>(s);
-    c->ypart_extra_floats = 0;          // a matrix-core w2 launch of such a step does not split its contraction
+    c->ypart_extra_floats = 0;
+    c->mfma_min_batch = INT32_MAX;      // its four tokens at most run on the GEMV kernels, whose scratch is what the array is sized for
     return step_impl(l, next, x_in, batch, x_out, h_out, trace, true);
 } catch (...) {
     return on_exception("moe_layer_step_noalloc");

@@ -65,17 +65,19 @@ def test_mixtral_stack_lowbit_full_size():
     model.close()
 
 
-@pytest.mark.parametrize("Bn,T", [(16, 3), (64, 2), (4, 3)])
-def test_mixtral_stack_batched_full_size(Bn, T):
+@pytest.mark.parametrize("Bn,T,gemv", [(16, 3, False), (64, 2, False), (4, 3, False), (4, 3, True)])
+def test_mixtral_stack_batched_full_size(Bn, T, gemv):
     """32 layers, 4-bit, LRU k=4, prefetch 2, Bn independent streams per step: at 16 and 64 tokens nearly every expert of
     a layer is needed, so a step runs in stages (resident experts first, then the transfers, then the arrivals one by
-    one) on the matrix cores with four 99 MB copies in flight per layer; at 4 tokens the GEMV kernels take
-    the batch."""
+    one) on the matrix cores with four 99 MB copies in flight per layer; 4 tokens run on the matrix cores too (the
+    default from three tokens on) and, with `gemv`, on the GEMV kernels."""
     c = W.CONFIGS["mixtral_stack_batched"]
     say(f"batched stack B={Bn}: build (256 experts)")
     model = Model(c.layers, c.hidden, c.ffn, c.n_experts, c.top_k, None, c.cache_slots, c.prefetch_m, c.rms_eps,
                   max_batch=Bn, seed=c.seed, keep_layers=[])
     B.moe_ctx_profile_enable(model.stack.ctx, True)
+    if gemv:
+        B.moe_ctx_set_option(model.stack.ctx, "mfma_min_batch", 1000)
     xs = W.hidden_ar1(c.seed, T, Bn, c.hidden)
     # block outputs: three rows of the batch in four layers of the last step (warm cache: hits, misses and confirmed
     # guesses in one step) and two rows in the first layer of the first

@@ -46,13 +46,17 @@ def test_tiny_layer_all_resident_control():
     model.close()
 
 
-@pytest.mark.parametrize("k,m,Bn,T", [(2, 2, 1, 40), (4, 1, 1, 24), (4, 2, 4, 12), (4, 2, 16, 8), (2, 2, 3, 10)])
-def test_small_stack_with_prefetch(k, m, Bn, T):
+@pytest.mark.parametrize("k,m,Bn,T,gemv", [(2, 2, 1, 40, False), (4, 1, 1, 24, False), (4, 2, 4, 12, False), (4, 2, 4, 12, True),
+                                           (4, 2, 16, 8, False), (4, 2, 16, 8, True), (2, 2, 3, 10, False), (2, 2, 3, 10, True)])
+def test_small_stack_with_prefetch(k, m, Bn, T, gemv):
     """4 layers, RMSNorm, residual, LRU k, speculative prefetch of m, batch Bn (Bn=16 with k=4 needs
-    more experts than slots, so a step runs in several passes)."""
+    more experts than slots, so a step runs in several passes).  Batches of three and more tokens run on the matrix
+    cores by default; `gemv` keeps them on the GEMV kernels (up to four tokens per expert and launch entry)."""
     L, H, F = 4, 256, 512
-    say(f"small stack k={k} m={m} B={Bn}: build")
+    say(f"small stack k={k} m={m} B={Bn} gemv={gemv}: build")
     model = Model(L, H, F, 8, 2, None, k, m, 1e-5, max_batch=Bn, seed=3)
+    if gemv:
+        B.moe_ctx_set_option(model.stack.ctx, "mfma_min_batch", 1000)
     xs = W.hidden_ar1(3, T, Bn, H)
     say("run")
     outs, sim, errs = run_teacher_forced(model, xs, O.expert_ffn)
@@ -150,11 +154,14 @@ def test_mixtral_layer_all_resident():
     model.close()
 
 
-def test_mixtral_layer_small_cache_batch4():
-    """The same shape with k=2 (99 MB demand copies in flight while kernels wait on their events) and batch 4."""
+@pytest.mark.parametrize("path", ["matrix", "gemv"])
+def test_mixtral_layer_small_cache_batch4(path):
+    """The same shape with k=4 (99 MB demand copies in flight while kernels wait on their events) and batch 4: on the
+    matrix cores (the default from three tokens on) and on the GEMV kernels."""
     c = W.CONFIGS["mixtral_layer"]
-    say("mixtral layer k=2 B=4: build")
+    say(f"mixtral layer k=4 B=4 {path}: build")
     model = Model(1, c.hidden, c.ffn, c.n_experts, c.top_k, None, 4, 0, 0.0, max_batch=4, seed=c.seed)
+    B.moe_ctx_set_option(model.stack.ctx, "mfma_min_batch", 3 if path == "matrix" else 1000)
     xs = W.hidden_ar1(c.seed, 3, 4, c.hidden)
     say("run")
     _, sim, errs = run_teacher_forced(model, xs, c_ffn.expert_ffn, check_ffn=lambda t, l: True)
@@ -271,6 +278,7 @@ def test_launch_shape_knobs_do_not_change_results(Bn, token_path):
     outs = []
     for knobs in ({}, {"w13_blocks": 7, "w2_rows": 5, "w2_token_rows": 3, "sync_wait": 1}, {"w13_blocks": 1000, "w2_rows": 64, "w2_token_rows": 64}):
         model = Model(L, H, F, 8, 2, [(4, 64), (3, 64)], 2, 2, 1e-5, max_batch=Bn, seed=37)
+        B.moe_ctx_set_option(model.stack.ctx, "mfma_min_batch", 1000)      # the knobs are the GEMV kernels'
         B.moe_ctx_set_option(model.stack.ctx, "token_path", token_path)
         for name, value in knobs.items():
             B.moe_ctx_set_option(model.stack.ctx, name, value)
@@ -770,7 +778,7 @@ def draw_configuration(seed):
     c["eps"] = pick([0.0, 1e-5])
     c["options"] = {
         "token_path": pick([1, 1, 0]), "fused": pick([0, 0, 0, 1, 2]), "mfma_form": pick([1, 2, 3, 4, 5, 0]), "mfma16_waves": pick([4, 8]),
-        "mfma_min_batch": pick([16, 16, 2, 1000]), "staged_min_batch": pick([0, 0, 1000]),
+        "mfma_min_batch": pick([16, 3, 2, 1000]), "staged_min_batch": pick([0, 0, 1000]),
         "spec_head_mb": pick([0, 0, 1]), "w13_blocks": pick([256, 64, 24]), "w2_rows": pick([32, 16, 8]),
         "sync_wait": pick([0, 0, 1]),
     }

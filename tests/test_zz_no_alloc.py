@@ -48,6 +48,8 @@ def test_noalloc_step_matches_step_on_two_calls_in_a_row(formats, K, k):
     L, H, F, E = 2, 512, 1024, 8
     ref = Model(L, H, F, E, K, formats, k, 2, 1e-5, max_batch=4, seed=101)
     sut = Model(L, H, F, E, K, formats, k, 2, 1e-5, max_batch=4, seed=101, keep_layers=[])
+    # the entry point that allocates nothing runs the GEMV kernels whatever the batch; so does the reference here
+    B.moe_ctx_set_option(ref.stack.ctx, "mfma_min_batch", 1000)
     xs = W.hidden_ar1(101, 6, 4, H)
     # first call: four tokens (the general kernels, several tokens per expert); second call: one token (the
     # single-token kernels) -- a smaller input over the scratch the first call left behind; then on through layer 1
