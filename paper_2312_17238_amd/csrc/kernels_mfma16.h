@@ -12,12 +12,15 @@
 // (exact q - rint(z), one fused multiply-add, one rounding to fp16; fp16 (scale, zero) pairs) unless GS is set.
 //
 // Loads: two steps of weights are on their way at any time.  While step n is multiplied out of one LDS buffer, step
-// n + 1 sits in (or is still arriving in) the staging registers; at the END of step n it is written to the other
-// buffer, piece by piece, and each register takes a piece of step n + 2 as soon as it is free.  A step's loads so have
-// a whole step to arrive and a block never has less than a step's bytes in flight.  The loop has ONE body, the A
-// operands of the next step handed over by register copies at its end: with two alternating copies of the body the
-// compiler's placement of the waits for loads merges the paths through both and makes every second step wait for
-// everything in flight.
+// n + 1 sits in (or is still arriving in) the staging registers; beside the (group, tile) units of step n's multiply
+// it is written to the other buffer piece by piece, each register taking a piece of step n + 2 as soon as it is free
+// (staged all at once after the multiply, the waves of a compute unit queue for its one path to memory for as long as
+// the multiply took).  A step's loads so have a whole step to arrive and a block never has less than a step's bytes
+// in flight.  That fits 128 registers because an address is a buffer descriptor and an offset in scalar registers
+// plus ONE 32-bit vector register, and because nothing is read ahead from LDS.  The loop has ONE body, the A operands
+// of the next step handed over by register copies at its end: with two alternating copies of the body the compiler's
+// placement of the waits for loads merges the paths through both and makes every second step wait for everything in
+// flight; for the same reason no load sits behind a branch (an offset past the buffer's end makes one a no-op).
 //
 // GS ("group-scaled"): the weights are not dequantised at all.  The codes enter the matrix cores as the fp16 numbers
 // 1024 + q and 64 + q that the bit patterns 0x6400 | q and 0x5400 | q << 4 spell (one v_and_or_b32 per pair, nothing
@@ -27,7 +30,7 @@
 // and -64 in those slots).  A (sub-tile, group) product then starts from -P instead of zero, which takes the biases out
 // again, and two fp32 multiply-adds per accumulator register finish it: total += s (product - z X).  No weight is
 // rounded to fp16, nothing depends on the size of the activations (every sum is an fp32 one), 18 vector instructions
-// per (sub-tile, group) instead of 42.
+// per (sub-tile, group) instead of 42.  With two-level metadata (META8) scale and zero are decoded in fp32 right there.
 //
 // MFMA layouts (v_mfma_f32_16x16x32_f16): A lane l = row (token) l%16, k-slots 8*(l/16)..+7; B lane l = column (memory
 // row) l%16, k-slots 8*(l/16)..+7; D lane l, register i = row 4*(l/16) + i, column l%16.
